@@ -1,0 +1,171 @@
+/*
+ * cat.h -- C ABI of the MI355X (gfx950) hot path of CAT, the Cluster-based
+ * Affine Transformation of arXiv 2509.26277.
+ *
+ * Two phases (Sec. 3.1; Appendix B, Algorithms 1 and 2):
+ *   CAT Fitting      k-means over the low-bit-quantised (LQ) output vectors, then,
+ *                    per cluster and per channel, gamma = cov(LQ,FP) / var(LQ) and
+ *                    beta = mean(FP) - gamma * mean(LQ).
+ *   CAT Inferencing  nearest centroid, then  q + alpha * (gamma_k * q + beta_k - q).
+ * The paper reduces the LQ vectors with PCA before clustering; this library
+ * clusters in the full dimension D (the pca_dim = D case: a full-rank PCA is a
+ * rigid motion and leaves every distance unchanged).
+ *
+ * Conventions, valid for every entry point unless stated otherwise
+ *   - Every data pointer is a DEVICE pointer owned by the caller.  The library
+ *     allocates and frees nothing; scratch memory comes from `workspace`
+ *     (device, 256-byte aligned, at least the size the matching
+ *     *_workspace_bytes() returns; its contents on entry do not matter and are
+ *     garbage on return).
+ *   - Matrices are row-major and contiguous: lq, fp, corrected are N x D of
+ *     `dt` (CAT_F32: float, CAT_BF16: bfloat16 stored as uint16); centroids,
+ *     gamma, beta are K x D float.  Row starts must be 4-byte aligned (for
+ *     CAT_BF16 this means D even); the base pointers 16-byte aligned.
+ *   - 1 <= K <= N, 1 <= D, K <= CAT_MAX_K.  Element offsets are 64-bit.
+ *   - Work is enqueued on `hip_stream` (a hipStream_t; NULL = the default
+ *     stream); calls return without synchronising.  The status covers argument
+ *     checks and launch errors; an asynchronous fault shows at the caller's
+ *     next synchronisation.
+ *   - Inputs are never modified; outputs are fully overwritten.  Nullable
+ *     outputs are marked.  No exception crosses the ABI.
+ *   - Non-finite input values give unspecified results (no crash, no hang).
+ *   - Calls are re-entrant across distinct streams and workspaces.
+ *
+ * Distances are squared Euclidean.  A tie goes to the LOWEST cluster index.
+ * The assignment is exact up to rounding: a fast bf16-split MFMA pass ranks the
+ * centroids, and every row whose two best scores are closer than the pass's
+ * error bound is re-ranked with direct-form double-precision distances.
+ */
+#ifndef CAT_H
+#define CAT_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define CAT_MAX_K 1024
+
+typedef enum {
+    CAT_OK = 0,
+    CAT_ERR_INVALID_ARG = 1, /* null pointer, bad size, bad alignment, bad enum      */
+    CAT_ERR_UNSUPPORTED = 2, /* a valid request this build has no kernel for         */
+    CAT_ERR_WORKSPACE = 3,   /* workspace null, misaligned or too small              */
+    CAT_ERR_DEVICE = 4       /* a HIP call (launch, query) failed; see cat_last_error */
+} cat_status;
+
+typedef enum { CAT_F32 = 0, CAT_BF16 = 1 } cat_dtype;
+
+/* Kernel family used for the assignment-type steps.  CAT_PATH_AUTO picks the
+ * MFMA tile kernels whenever the shape fits them and the streaming kernels
+ * otherwise; the other two values force one family (tests use this to cover
+ * both on any shape).  Forcing CAT_PATH_TILE on a shape it cannot run makes the
+ * call return CAT_ERR_UNSUPPORTED.  Process-wide; default CAT_PATH_AUTO. */
+typedef enum { CAT_PATH_AUTO = 0, CAT_PATH_STREAM = 1, CAT_PATH_TILE = 2 } cat_path;
+cat_status cat_select_path(cat_path p);
+
+/* Bytes of device scratch cat_fit / cat_assign / cat_update / cat_stats need
+ * (one size covers all four) and cat_apply needs.  Returns 0 for invalid
+ * arguments. */
+size_t cat_fit_workspace_bytes(int64_t N, int64_t D, int32_t K, cat_dtype dt);
+size_t cat_apply_workspace_bytes(int64_t N, int64_t D, int32_t K, cat_dtype dt);
+
+/*
+ * CAT Fitting (Algorithm 1 with pca_dim = D; Sec. 3.1 for the statistics).
+ *
+ *   init      centroids <- init_centroids if given, else the K distinct rows of
+ *             lq picked by cat_init_indices(N, K, seed).
+ *   Lloyd     `iters` times: assign every row to its nearest centroid, then move
+ *             each centroid to the mean of its rows (a centroid with no rows
+ *             stays where it is).  No early stop.
+ *   final     one more assignment against the final centroids: this is what
+ *             `assignments`, `counts` and the last inertia entry describe, and
+ *             what cat_apply reproduces on the same rows.
+ *   affine    per cluster k and channel j, over the rows of cluster k:
+ *             var = mean((x - mean x)^2), cov = mean((x - mean x)(y - mean y)),
+ *             gamma = cov / max(var, 1e-8), beta = mean y - gamma * mean x
+ *             (x = lq, y = fp).  An empty cluster gets gamma = 1, beta = 0.
+ *
+ * lq, fp          in,  N x D of dt
+ * iters           >= 0 (0: centroids = init, then final + affine)
+ * init_centroids  in,  K x D float, or NULL
+ * centroids, gamma, beta   out, K x D float each
+ * assignments     out, N int32
+ * counts          out, K int32, nullable: rows per cluster of `assignments`
+ * inertia         out, iters + 1 doubles, nullable: k-means objective (sum of
+ *                 squared distances to the assigned centroid) of each of the
+ *                 iters + 1 assignment passes
+ */
+cat_status cat_fit(const void *lq, const void *fp, int64_t N, int64_t D, int32_t K,
+                   int32_t iters, uint64_t seed, cat_dtype dt,
+                   const float *init_centroids,
+                   float *centroids, float *gamma, float *beta,
+                   int32_t *assignments, int32_t *counts, double *inertia,
+                   void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
+ * CAT Inferencing (Algorithm 2; the alpha-blend at the end of Sec. 3.1), fused:
+ * corrected_i = x_i + alpha * (gamma_a * x_i + beta_a - x_i),  a = nearest centroid
+ * of x_i.  alpha is folded once into gamma' = 1 + alpha * (gamma - 1), beta' =
+ * alpha * beta (K x D, in the workspace), so alpha = 0 returns the input bit for
+ * bit and alpha = 1 is the pure affine map.  alpha must be finite.
+ *
+ * corrected     out, N x D of dt (may not alias lq)
+ * assignments   out, N int32, nullable
+ */
+cat_status cat_apply(const void *lq, int64_t N, int64_t D, int32_t K, cat_dtype dt,
+                     const float *centroids, const float *gamma, const float *beta,
+                     float alpha, void *corrected, int32_t *assignments,
+                     void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/* ---- step-level entry points (the pieces cat_fit is made of) ------------- */
+
+/* Assignment step (the Cluster-Model "predict" of Algorithms 1 and 2).
+ * assignments out N int32; counts out K int32, nullable; inertia out 1 double,
+ * nullable. */
+cat_status cat_assign(const void *lq, int64_t N, int64_t D, int32_t K, cat_dtype dt,
+                      const float *centroids, int32_t *assignments, int32_t *counts,
+                      double *inertia, void *workspace, size_t workspace_bytes,
+                      void *hip_stream);
+
+/* Centroid update step of Lloyd's iteration: centroids[k] = mean of the rows with
+ * assignments == k, or prev_centroids[k] if there is none.  assignments in, N
+ * int32, each in [0, K).  centroids out (may alias prev_centroids); counts out,
+ * nullable. */
+cat_status cat_update(const void *lq, const int32_t *assignments, int64_t N, int64_t D,
+                      int32_t K, cat_dtype dt, const float *prev_centroids,
+                      float *centroids, int32_t *counts,
+                      void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/* Per-cluster affine fit (Sec. 3.1 statistics, Eq. (gamma-beta), Algorithm 1's
+ * variance floor and empty-cluster rule) for a given partition.  `centroids` is
+ * an optional hint (K x D float, nullable): values near the cluster means of lq
+ * used as the shift of the one-pass moment accumulation; it never changes what
+ * is computed.  gamma, beta out; counts out, nullable. */
+cat_status cat_stats(const void *lq, const void *fp, const int32_t *assignments,
+                     int64_t N, int64_t D, int32_t K, cat_dtype dt, const float *centroids,
+                     float *gamma, float *beta, int32_t *counts,
+                     void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
+ * Seeded initial rows (the paper does not fix the k-means initialisation; this
+ * is the rule).  SplitMix64 (Steele, Lea, Flood 2014) as a counter-based
+ * generator: output t = mix(seed + (t + 1) * 0x9E3779B97F4A7C15) with
+ *   mix(z): z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9;
+ *           z = (z ^ (z >> 27)) * 0x94D049BB133111EB;  return z ^ (z >> 31);
+ * all in 64-bit unsigned arithmetic.  Walk t = 0, 1, 2, ...; the candidate is
+ * output mod N; a candidate already taken is skipped; stop at K indices.
+ * idx_out is a HOST array of K int64.  Pure host code, no GPU needed.
+ */
+cat_status cat_init_indices(int64_t N, int32_t K, uint64_t seed, int64_t *idx_out);
+
+/* Message of the last non-OK status on the calling thread ("" if none).  The
+ * pointer stays valid until the next failing call on the same thread. */
+const char *cat_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CAT_H */

@@ -1,0 +1,180 @@
+"""ctypes binding of the C oracle (``cat_oracle.c``).
+
+Test infrastructure only.  Arrays go in as contiguous numpy float32 (inputs) and
+float64 (centroids, gamma, beta); every result is float64 / int32 / int64.
+"""
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "cat_oracle.c")
+_SO = os.path.join(_HERE, "libcat_oracle.so")
+_lib = None
+
+
+def build(force=False):
+    """Compile the oracle with gcc (-O2, no fast-math).  Returns the .so path."""
+    if force or not os.path.exists(_SO) or os.path.getmtime(_SO) < os.path.getmtime(_SRC):
+        cmd = ["gcc", "-O2", "-std=c11", "-fPIC", "-shared", "-fopenmp", "-Wall", "-Wextra",
+               "-o", _SO, _SRC, "-lm"]
+        subprocess.run(cmd, check=True)
+    return _SO
+
+
+def _load():
+    global _lib
+    if _lib is not None:
+        return _lib
+    lib = ctypes.CDLL(build())
+    c = ctypes
+    f32p, f64p = c.POINTER(c.c_float), c.POINTER(c.c_double)
+    i32p, i64p = c.POINTER(c.c_int32), c.POINTER(c.c_int64)
+    lib.cat_oracle_threads.restype = c.c_int
+    lib.cat_oracle_splitmix64.restype = c.c_uint64
+    lib.cat_oracle_splitmix64.argtypes = [c.c_uint64, c.c_uint64]
+    lib.cat_oracle_init_indices.argtypes = [c.c_int64, c.c_int32, c.c_uint64, i64p]
+    lib.cat_oracle_assign.argtypes = [f32p, c.c_int64, c.c_int64, c.c_int32, f64p, i32p, f64p, f64p]
+    lib.cat_oracle_distances.argtypes = [f32p, c.c_int64, c.c_int64, c.c_int32, f64p, f64p]
+    lib.cat_oracle_update.argtypes = [f32p, i32p, c.c_int64, c.c_int64, c.c_int32, f64p, i64p]
+    lib.cat_oracle_affine.argtypes = [f32p, f32p, i32p, c.c_int64, c.c_int64, c.c_int32, f64p, f64p, i64p]
+    lib.cat_oracle_fit.argtypes = [f32p, f32p, c.c_int64, c.c_int64, c.c_int32, c.c_int32, c.c_uint64,
+                                   f64p, f64p, f64p, f64p, i32p, i64p, f64p]
+    lib.cat_oracle_apply.argtypes = [f32p, c.c_int64, c.c_int64, c.c_int32, f64p, f64p, f64p,
+                                     c.c_double, f64p, i32p]
+    for fn in ("cat_oracle_init_indices", "cat_oracle_assign", "cat_oracle_distances", "cat_oracle_update",
+               "cat_oracle_affine", "cat_oracle_fit", "cat_oracle_apply"):
+        getattr(lib, fn).restype = None
+    _lib = lib
+    return lib
+
+
+def _f32(a):
+    a = np.ascontiguousarray(a, dtype=np.float32)
+    return a, a.ctypes.data_as(ctypes.POINTER(ctypes.c_float))
+
+
+def _f64(a):
+    a = np.ascontiguousarray(a, dtype=np.float64)
+    return a, a.ctypes.data_as(ctypes.POINTER(ctypes.c_double))
+
+
+def _i32(a):
+    a = np.ascontiguousarray(a, dtype=np.int32)
+    return a, a.ctypes.data_as(ctypes.POINTER(ctypes.c_int32))
+
+
+def _p(a, ct):
+    return a.ctypes.data_as(ctypes.POINTER(ct))
+
+
+def threads():
+    return int(_load().cat_oracle_threads())
+
+
+def splitmix64(seed, t):
+    return int(_load().cat_oracle_splitmix64(seed & (2**64 - 1), t))
+
+
+def init_indices(N, K, seed):
+    idx = np.empty(K, dtype=np.int64)
+    _load().cat_oracle_init_indices(N, K, seed & (2**64 - 1), _p(idx, ctypes.c_int64))
+    return idx
+
+
+def assign(lq, centroids, want_distances=False):
+    """Nearest centroid per row (lowest index on ties).  Returns a, or (a, d1, d2)."""
+    lq, plq = _f32(lq)
+    cent, pc = _f64(centroids)
+    N, D = lq.shape
+    K = cent.shape[0]
+    assert cent.shape == (K, D)
+    a = np.empty(N, dtype=np.int32)
+    if want_distances:
+        d1 = np.empty(N, dtype=np.float64)
+        d2 = np.empty(N, dtype=np.float64)
+        _load().cat_oracle_assign(plq, N, D, K, pc, _p(a, ctypes.c_int32),
+                                  _p(d1, ctypes.c_double), _p(d2, ctypes.c_double))
+        return a, d1, d2
+    _load().cat_oracle_assign(plq, N, D, K, pc, _p(a, ctypes.c_int32), None, None)
+    return a
+
+
+def distances(lq, centroids):
+    lq, plq = _f32(lq)
+    cent, pc = _f64(centroids)
+    N, D = lq.shape
+    K = cent.shape[0]
+    out = np.empty((N, K), dtype=np.float64)
+    _load().cat_oracle_distances(plq, N, D, K, pc, _p(out, ctypes.c_double))
+    return out
+
+
+def update(lq, assignments, centroids):
+    """One centroid update; returns (new_centroids, counts)."""
+    lq, plq = _f32(lq)
+    a, pa = _i32(assignments)
+    cent = np.array(centroids, dtype=np.float64, order="C", copy=True)
+    N, D = lq.shape
+    K = cent.shape[0]
+    assert a.min() >= 0 and a.max() < K
+    counts = np.empty(K, dtype=np.int64)
+    _load().cat_oracle_update(plq, pa, N, D, K, _p(cent, ctypes.c_double), _p(counts, ctypes.c_int64))
+    return cent, counts
+
+
+def affine(lq, fp, assignments, K):
+    """Per-cluster per-channel gamma, beta; returns (gamma, beta, counts)."""
+    lq, plq = _f32(lq)
+    fp, pfp = _f32(fp)
+    a, pa = _i32(assignments)
+    N, D = lq.shape
+    assert fp.shape == (N, D)
+    assert a.min() >= 0 and a.max() < K
+    gamma = np.empty((K, D), dtype=np.float64)
+    beta = np.empty((K, D), dtype=np.float64)
+    counts = np.empty(K, dtype=np.int64)
+    _load().cat_oracle_affine(plq, pfp, pa, N, D, K, _p(gamma, ctypes.c_double),
+                              _p(beta, ctypes.c_double), _p(counts, ctypes.c_int64))
+    return gamma, beta, counts
+
+
+def fit(lq, fp, K, iters, seed=0, init_centroids=None):
+    """CAT Fitting.  Returns dict(centroids, gamma, beta, assignments, counts, inertia)."""
+    lq, plq = _f32(lq)
+    fp, pfp = _f32(fp)
+    N, D = lq.shape
+    assert fp.shape == (N, D) and 1 <= K <= N and iters >= 0
+    cent = np.empty((K, D), dtype=np.float64)
+    gamma = np.empty((K, D), dtype=np.float64)
+    beta = np.empty((K, D), dtype=np.float64)
+    a = np.empty(N, dtype=np.int32)
+    counts = np.empty(K, dtype=np.int64)
+    inertia = np.empty(iters + 1, dtype=np.float64)
+    if init_centroids is not None:
+        init, pinit = _f64(init_centroids)
+        assert init.shape == (K, D)
+    else:
+        pinit = None
+    _load().cat_oracle_fit(plq, pfp, N, D, K, iters, seed & (2**64 - 1), pinit,
+                           _p(cent, ctypes.c_double), _p(gamma, ctypes.c_double), _p(beta, ctypes.c_double),
+                           _p(a, ctypes.c_int32), _p(counts, ctypes.c_int64), _p(inertia, ctypes.c_double))
+    return dict(centroids=cent, gamma=gamma, beta=beta, assignments=a, counts=counts, inertia=inertia)
+
+
+def apply(lq, centroids, gamma, beta, alpha=1.0):
+    """CAT Inferencing.  Returns (corrected float64 N x D, assignments)."""
+    lq, plq = _f32(lq)
+    cent, pc = _f64(centroids)
+    g, pg = _f64(gamma)
+    b, pb = _f64(beta)
+    N, D = lq.shape
+    K = cent.shape[0]
+    assert cent.shape == (K, D) and g.shape == (K, D) and b.shape == (K, D)
+    out = np.empty((N, D), dtype=np.float64)
+    a = np.empty(N, dtype=np.int32)
+    _load().cat_oracle_apply(plq, N, D, K, pc, pg, pb, float(alpha), _p(out, ctypes.c_double),
+                             _p(a, ctypes.c_int32))
+    return out, a

@@ -1,0 +1,218 @@
+"""ctypes binding of ``libcat_hip.so`` (the C ABI declared in ``include/cat.h``).
+
+Argument marshalling only: every step of the path runs in the HIP kernels.
+PyTorch is used for device memory and the stream handle.  There is no CPU
+fallback: if the library is missing the first call raises.
+"""
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SO = os.path.join(_HERE, "libcat_hip.so")
+_lib = None
+
+CAT_F32, CAT_BF16 = 0, 1
+CAT_PATH_AUTO, CAT_PATH_STREAM, CAT_PATH_TILE = 0, 1, 2
+_STATUS = {0: "CAT_OK", 1: "CAT_ERR_INVALID_ARG", 2: "CAT_ERR_UNSUPPORTED", 3: "CAT_ERR_WORKSPACE",
+           4: "CAT_ERR_DEVICE"}
+
+EXPORTS = ("cat_select_path", "cat_fit_workspace_bytes", "cat_apply_workspace_bytes", "cat_fit", "cat_apply",
+           "cat_assign", "cat_update", "cat_stats", "cat_init_indices", "cat_last_error")
+
+
+class CatError(RuntimeError):
+    def __init__(self, status, message):
+        super().__init__(f"{_STATUS.get(status, status)}: {message}")
+        self.status = status
+
+
+def library_path():
+    return _SO
+
+
+def load_library():
+    """Load libcat_hip.so (built by ``python -m paper_2509_26277_amd.build``)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_SO):
+        raise RuntimeError(f"{_SO} is not built; run `python -m paper_2509_26277_amd.build` "
+                           "(there is no fallback path)")
+    lib = ctypes.CDLL(_SO)
+    c = ctypes
+    vp, i64, i32, u64, sz = c.c_void_p, c.c_int64, c.c_int32, c.c_uint64, c.c_size_t
+    lib.cat_select_path.argtypes = [c.c_int]
+    lib.cat_select_path.restype = c.c_int
+    lib.cat_fit_workspace_bytes.argtypes = [i64, i64, i32, c.c_int]
+    lib.cat_fit_workspace_bytes.restype = sz
+    lib.cat_apply_workspace_bytes.argtypes = [i64, i64, i32, c.c_int]
+    lib.cat_apply_workspace_bytes.restype = sz
+    lib.cat_fit.argtypes = [vp, vp, i64, i64, i32, i32, u64, c.c_int, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.cat_fit.restype = c.c_int
+    lib.cat_apply.argtypes = [vp, i64, i64, i32, c.c_int, vp, vp, vp, c.c_float, vp, vp, vp, sz, vp]
+    lib.cat_apply.restype = c.c_int
+    lib.cat_assign.argtypes = [vp, i64, i64, i32, c.c_int, vp, vp, vp, vp, vp, sz, vp]
+    lib.cat_assign.restype = c.c_int
+    lib.cat_update.argtypes = [vp, vp, i64, i64, i32, c.c_int, vp, vp, vp, vp, sz, vp]
+    lib.cat_update.restype = c.c_int
+    lib.cat_stats.argtypes = [vp, vp, vp, i64, i64, i32, c.c_int, vp, vp, vp, vp, vp, sz, vp]
+    lib.cat_stats.restype = c.c_int
+    lib.cat_init_indices.argtypes = [i64, i32, u64, c.POINTER(c.c_int64)]
+    lib.cat_init_indices.restype = c.c_int
+    lib.cat_last_error.argtypes = []
+    lib.cat_last_error.restype = c.c_char_p
+    _lib = lib
+    return lib
+
+
+def _check(status):
+    if status != 0:
+        raise CatError(status, load_library().cat_last_error().decode())
+
+
+def _dt(t):
+    if t.dtype == torch.float32:
+        return CAT_F32
+    if t.dtype == torch.bfloat16:
+        return CAT_BF16
+    raise TypeError(f"lq/fp must be float32 or bfloat16, got {t.dtype}")
+
+
+def _dev(t, dtype=None, shape=None, name="tensor"):
+    if t is None:
+        return None
+    if not t.is_cuda or not t.is_contiguous():
+        raise ValueError(f"{name} must be a contiguous device tensor")
+    if dtype is not None and t.dtype != dtype:
+        raise TypeError(f"{name} must be {dtype}, got {t.dtype}")
+    if shape is not None and tuple(t.shape) != tuple(shape):
+        raise ValueError(f"{name} must have shape {tuple(shape)}, got {tuple(t.shape)}")
+    return t.data_ptr()
+
+
+def _stream():
+    return torch.cuda.current_stream().cuda_stream
+
+
+def select_path(path):
+    _check(load_library().cat_select_path(int(path)))
+
+
+def cat_fit_workspace_bytes(N, D, K, dt=CAT_F32):
+    return int(load_library().cat_fit_workspace_bytes(N, D, K, dt))
+
+
+def cat_apply_workspace_bytes(N, D, K, dt=CAT_F32):
+    return int(load_library().cat_apply_workspace_bytes(N, D, K, dt))
+
+
+def _workspace(nbytes, device):
+    return torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device=device)
+
+
+def cat_init_indices(N, K, seed):
+    """Host-side seeded row indices (list of K ints)."""
+    buf = (ctypes.c_int64 * max(K, 1))()
+    _check(load_library().cat_init_indices(N, K, seed & (2**64 - 1), buf))
+    return list(buf)[:K]
+
+
+def cat_fit(lq, fp, K, iters, seed=0, init_centroids=None, want_inertia=True, workspace=None):
+    """CAT Fitting on device tensors.  Returns a dict of device tensors:
+    centroids, gamma, beta (K x D float32), assignments (N int32), counts (K int32),
+    inertia (iters+1 float64, or None)."""
+    lib = load_library()
+    N, D = lq.shape
+    dt = _dt(lq)
+    dev = lq.device
+    if workspace is None:
+        workspace = _workspace(lib.cat_fit_workspace_bytes(N, D, K, dt), dev)
+    cent = torch.empty((K, D), dtype=torch.float32, device=dev)
+    gamma = torch.empty((K, D), dtype=torch.float32, device=dev)
+    beta = torch.empty((K, D), dtype=torch.float32, device=dev)
+    a = torch.empty((N,), dtype=torch.int32, device=dev)
+    counts = torch.empty((K,), dtype=torch.int32, device=dev)
+    inertia = torch.empty((max(iters, 0) + 1,), dtype=torch.float64, device=dev) if want_inertia else None
+    _check(lib.cat_fit(_dev(lq, name="lq"), _dev(fp, lq.dtype, (N, D), "fp"), N, D, K, iters,
+                       seed & (2**64 - 1), dt, _dev(init_centroids, torch.float32, (K, D), "init_centroids"),
+                       cent.data_ptr(), gamma.data_ptr(), beta.data_ptr(), a.data_ptr(), counts.data_ptr(),
+                       None if inertia is None else inertia.data_ptr(),
+                       workspace.data_ptr(), workspace.numel(), _stream()))
+    return dict(centroids=cent, gamma=gamma, beta=beta, assignments=a, counts=counts, inertia=inertia)
+
+
+def cat_apply(lq, centroids, gamma, beta, alpha=1.0, want_assignments=True, out=None, workspace=None):
+    """CAT Inferencing.  Returns (corrected, assignments or None)."""
+    lib = load_library()
+    N, D = lq.shape
+    K = centroids.shape[0]
+    dt = _dt(lq)
+    dev = lq.device
+    if workspace is None:
+        workspace = _workspace(lib.cat_apply_workspace_bytes(N, D, K, dt), dev)
+    if out is None:
+        out = torch.empty_like(lq)
+    a = torch.empty((N,), dtype=torch.int32, device=dev) if want_assignments else None
+    _check(lib.cat_apply(_dev(lq, name="lq"), N, D, K, dt, _dev(centroids, torch.float32, (K, D), "centroids"),
+                         _dev(gamma, torch.float32, (K, D), "gamma"), _dev(beta, torch.float32, (K, D), "beta"),
+                         float(alpha), _dev(out, lq.dtype, (N, D), "out"),
+                         None if a is None else a.data_ptr(),
+                         workspace.data_ptr(), workspace.numel(), _stream()))
+    return out, a
+
+
+def cat_assign(lq, centroids, workspace=None):
+    """Assignment step.  Returns (assignments int32 N, counts int32 K, inertia float64 [1])."""
+    lib = load_library()
+    N, D = lq.shape
+    K = centroids.shape[0]
+    dt = _dt(lq)
+    dev = lq.device
+    if workspace is None:
+        workspace = _workspace(lib.cat_fit_workspace_bytes(N, D, K, dt), dev)
+    a = torch.empty((N,), dtype=torch.int32, device=dev)
+    counts = torch.empty((K,), dtype=torch.int32, device=dev)
+    inertia = torch.empty((1,), dtype=torch.float64, device=dev)
+    _check(lib.cat_assign(_dev(lq, name="lq"), N, D, K, dt, _dev(centroids, torch.float32, (K, D), "centroids"),
+                          a.data_ptr(), counts.data_ptr(), inertia.data_ptr(),
+                          workspace.data_ptr(), workspace.numel(), _stream()))
+    return a, counts, inertia
+
+
+def cat_update(lq, assignments, prev_centroids, workspace=None):
+    """Centroid update step.  Returns (centroids float32 K x D, counts int32 K)."""
+    lib = load_library()
+    N, D = lq.shape
+    K = prev_centroids.shape[0]
+    dt = _dt(lq)
+    dev = lq.device
+    if workspace is None:
+        workspace = _workspace(lib.cat_fit_workspace_bytes(N, D, K, dt), dev)
+    cent = torch.empty((K, D), dtype=torch.float32, device=dev)
+    counts = torch.empty((K,), dtype=torch.int32, device=dev)
+    _check(lib.cat_update(_dev(lq, name="lq"), _dev(assignments, torch.int32, (N,), "assignments"), N, D, K, dt,
+                          _dev(prev_centroids, torch.float32, (K, D), "prev_centroids"),
+                          cent.data_ptr(), counts.data_ptr(),
+                          workspace.data_ptr(), workspace.numel(), _stream()))
+    return cent, counts
+
+
+def cat_stats(lq, fp, assignments, K, centroids=None, workspace=None):
+    """Per-cluster affine fit for a given partition.  Returns (gamma, beta, counts)."""
+    lib = load_library()
+    N, D = lq.shape
+    dt = _dt(lq)
+    dev = lq.device
+    if workspace is None:
+        workspace = _workspace(lib.cat_fit_workspace_bytes(N, D, K, dt), dev)
+    gamma = torch.empty((K, D), dtype=torch.float32, device=dev)
+    beta = torch.empty((K, D), dtype=torch.float32, device=dev)
+    counts = torch.empty((K,), dtype=torch.int32, device=dev)
+    _check(lib.cat_stats(_dev(lq, name="lq"), _dev(fp, lq.dtype, (N, D), "fp"),
+                         _dev(assignments, torch.int32, (N,), "assignments"), N, D, K, dt,
+                         _dev(centroids, torch.float32, (K, D), "centroids"),
+                         gamma.data_ptr(), beta.data_ptr(), counts.data_ptr(),
+                         workspace.data_ptr(), workspace.numel(), _stream()))
+    return gamma, beta, counts
