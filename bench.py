@@ -1,0 +1,181 @@
+#!/usr/bin/env python3
+"""Benchmark of the CAT hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg2] [--no-cpu]
+
+One step = one pass of the whole hot path over one synthetic batch that is
+already resident in HBM: cat_fit (seeded init, `iters` Lloyd iterations, final
+assignment, per-cluster affine fit) followed by cat_apply on the same rows
+(inference-only workload cfg5: cat_apply alone).  Prints ONE JSON line.
+
+value        rows x Lloyd-iterations per second of whole-step time (cfg5: GB/s of
+             cat_apply, read + write)
+roofline     the dominant kernel launch (one Lloyd iteration; cfg5: the inference
+             kernel): algorithmic bytes (one read of lq per iteration; cfg5: one read
+             + one write) over its mean duration, measured with HIP events on the
+             launch stream, against the 8 TB/s HBM peak
+cpu_baseline the CPU oracle timed on a bounded sample of the same workload
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0
+
+
+def _events(fn, reps, torch):
+    """mean milliseconds of fn() over reps calls, HIP events on the current stream"""
+    e0 = torch.cuda.Event(enable_timing=True)
+    e1 = torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(reps):
+        fn()
+    e1.record()
+    e1.synchronize()
+    return e0.elapsed_time(e1) / reps
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--workload", default="cfg2", choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5"])
+    ap.add_argument("--rows", type=int, default=None, help="override N (debugging; the result is then not the named workload)")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build is single-GPU; run with --gpus 1 (rows shard trivially, see DESIGN.md)")
+
+    import numpy as np
+    import torch
+
+    from paper_2509_26277_amd import binding, cat_apply, cat_fit, workloads
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    binding.load_library()  # no fallback: fails here if the HIP library is missing
+
+    w = workloads.make(args.workload, n_rows=args.rows)
+    N, D, K, iters, dt = w["N"], w["D"], w["K"], w["iters"], w["dtype"]
+    esize = 4 if dt == "f32" else 2
+    fit_kind = w["kind"] == "fit"
+
+    def dev(x):
+        if dt == "f32":
+            return torch.from_numpy(x).cuda()
+        bits = workloads.f32_to_bf16_bits(x)
+        return torch.from_numpy(bits.view(np.int16)).cuda().view(torch.bfloat16)
+
+    lq = dev(w["lq"])
+    out = torch.empty_like(lq)
+    if fit_kind:
+        fp = dev(w["fp"])
+        ws_fit = torch.empty(binding.cat_fit_workspace_bytes(N, D, K, binding.CAT_F32 if dt == "f32" else binding.CAT_BF16),
+                             dtype=torch.uint8, device="cuda")
+    else:
+        cent, gamma, beta = (torch.from_numpy(w[k]).cuda() for k in ("centroids", "gamma", "beta"))
+    ws_apply = torch.empty(max(256, binding.cat_apply_workspace_bytes(N, D, K, binding.CAT_F32 if dt == "f32" else binding.CAT_BF16)),
+                           dtype=torch.uint8, device="cuda")
+    state = {}
+
+    def step():
+        if fit_kind:
+            r = cat_fit(lq, fp, K, iters, seed=w["seed"], workspace=ws_fit)
+            cat_apply(lq, r["centroids"], r["gamma"], r["beta"], out=out, workspace=ws_apply)
+            state["fit"] = r
+        else:
+            cat_apply(lq, cent, gamma, beta, out=out, workspace=ws_apply)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    ms_per_step = 1e3 * elapsed / args.steps
+
+    # ---- per-launch figures, HIP events on the launch stream (torch's current stream) ----
+    detail = {}
+    apply_bytes = N * D * esize * 2 + 4 * N
+    if fit_kind:
+        r = state["fit"]
+        reps = max(3, args.steps)
+        t_fit = _events(lambda: cat_fit(lq, fp, K, iters, seed=w["seed"], workspace=ws_fit), reps, torch)
+        t_fit0 = _events(lambda: cat_fit(lq, fp, K, 0, seed=w["seed"], workspace=ws_fit), reps, torch)
+        t_apply = _events(lambda: cat_apply(lq, r["centroids"], r["gamma"], r["beta"], out=out, workspace=ws_apply),
+                          reps, torch)
+        t_iter = (t_fit - t_fit0) / iters  # one Lloyd iteration
+        detail.update(fit_ms=t_fit, fit_iters0_ms=t_fit0, lloyd_iter_us=1e3 * t_iter,
+                      lloyd_iters_per_s=1e3 / t_iter, lloyd_rows_per_s=N * 1e3 / t_iter,
+                      apply_ms=t_apply, apply_GBps=apply_bytes / t_apply / 1e6,
+                      apply_frac_hbm=apply_bytes / t_apply / 1e6 / HBM_PEAK_GBPS)
+        alg_bytes = N * D * esize
+        achieved = alg_bytes / t_iter / 1e6
+        roof = dict(bound="hbm", kernel="lloyd_iteration", achieved=achieved, peak=HBM_PEAK_GBPS, unit="GB/s",
+                    frac=achieved / HBM_PEAK_GBPS, traffic=None, bytes_per_launch=alg_bytes,
+                    us_per_launch=1e3 * t_iter)
+        metric, unit = "cat_fit_lloyd_rows_per_s", "rows/s"
+        value = N * iters / (ms_per_step * 1e-3)
+    else:
+        reps = max(5, args.steps)
+        t_apply = _events(lambda: cat_apply(lq, cent, gamma, beta, out=out, workspace=ws_apply), reps, torch)
+        achieved = apply_bytes / t_apply / 1e6
+        detail.update(apply_ms=t_apply, apply_GBps=achieved, apply_rows_per_s=N * 1e3 / t_apply)
+        roof = dict(bound="hbm", kernel="cat_apply", achieved=achieved, peak=HBM_PEAK_GBPS, unit="GB/s",
+                    frac=achieved / HBM_PEAK_GBPS, traffic=None, bytes_per_launch=apply_bytes,
+                    us_per_launch=1e3 * t_apply)
+        metric, unit = "cat_apply_GBps", "GB/s"
+        value = apply_bytes / (ms_per_step * 1e-3) / 1e9
+
+    # context: plain device copy of the same matrix
+    t_copy = _events(lambda: out.copy_(lq), 5, torch)
+    detail["device_copy_GBps"] = 2 * N * D * esize / t_copy / 1e6
+
+    # ---- the oracle on the host cores, bounded sample ----
+    cpu = None
+    if not args.no_cpu:
+        import oracle
+        probe = min(N, max(K, 1024))
+        t = time.perf_counter()
+        if fit_kind:
+            oracle.fit(w["lq"][:probe], w["fp"][:probe], K, 1, seed=1)
+        else:
+            oracle.apply(w["lq"][:probe], w["centroids"], w["gamma"], w["beta"], 1.0)
+        per_row_pass = (time.perf_counter() - t) / (probe * (2 if fit_kind else 1))
+        it_s = 3 if fit_kind else 1
+        rows_s = int(min(N, max(K, 15.0 / max(per_row_pass, 1e-9) / (it_s + 1))))
+        t = time.perf_counter()
+        if fit_kind:
+            oracle.fit(w["lq"][:rows_s], w["fp"][:rows_s], K, it_s, seed=w["seed"])
+            sec = time.perf_counter() - t
+            cpu = dict(value=rows_s * it_s / sec, unit="rows/s", cores=oracle.threads(), kind="oracle",
+                       sample=f"oracle.fit on the first {rows_s} rows, {it_s} Lloyd iterations + final assign + "
+                              f"affine fit, {sec:.1f} s; rows x iterations / whole time")
+        else:
+            oracle.apply(w["lq"][:rows_s], w["centroids"], w["gamma"], w["beta"], 1.0)
+            sec = time.perf_counter() - t
+            cpu = dict(value=rows_s * D * esize * 2 / sec / 1e9, unit="GB/s", cores=oracle.threads(), kind="oracle",
+                       sample=f"oracle.apply on the first {rows_s} rows, {sec:.1f} s")
+
+    line = {
+        "metric": metric, "value": value, "unit": unit, "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32" if dt == "f32" else "bf16", "data": "synthetic",
+        "config": {"workload": f"{w['name']}: N={N} D={D} K={K} {dt} iters={iters}", "N": N, "D": D, "K": K,
+                   "iters": iters, "step": "cat_fit + cat_apply" if fit_kind else "cat_apply"},
+        "roofline": roof, "cpu_baseline": cpu, "detail": detail,
+    }
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

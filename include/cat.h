@@ -109,8 +109,8 @@ cat_status cat_fit(const void *lq, const void *fp, int64_t N, int64_t D, int32_t
  * CAT Inferencing (Algorithm 2; the alpha-blend at the end of Sec. 3.1), fused:
  * corrected_i = x_i + alpha * (gamma_a * x_i + beta_a - x_i),  a = nearest centroid
  * of x_i.  alpha is folded once into gamma' = 1 + alpha * (gamma - 1), beta' =
- * alpha * beta (K x D, in the workspace), so alpha = 0 returns the input bit for
- * bit and alpha = 1 is the pure affine map.  alpha must be finite.
+ * alpha * beta (K x D, in the workspace), so alpha = 0 returns the input values
+ * unchanged and alpha = 1 is the pure affine map.  alpha must be finite.
  *
  * corrected     out, N x D of dt (may not alias lq)
  * assignments   out, N int32, nullable

@@ -1,0 +1,355 @@
+// Host driver and C ABI of the CAT hot path (see include/cat.h for the contract).
+// Validates arguments, carves the caller's workspace, and enqueues the kernels of
+// each step on the caller's stream.  Nothing here synchronises or allocates.
+#include <atomic>
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+
+#include "cat_common.h"
+#include "cat_tile.h"
+
+namespace cat {
+
+static thread_local char g_err[512] = "";
+static std::atomic<int> g_path{CAT_PATH_AUTO};
+
+cat_status set_error(cat_status st, const char* fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+    return st;
+}
+
+// ---- workspace ------------------------------------------------------------------
+static inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+struct Carver {
+    char* base;
+    size_t off = 0;
+    explicit Carver(void* b) : base((char*)b) {}
+    template <typename T>
+    T* take(size_t count) {
+        T* p = base ? (T*)(base + off) : nullptr;
+        off += align256(count * sizeof(T));
+        return p;
+    }
+};
+
+struct FitWs {
+    double* acc;              // 4 x K x D   segmented-sum accumulators
+    float* cent[2];           // K x D each  centroid ping-pong
+    float* pivx;              // K x D       shifts of the statistics
+    float* pivy;              // K x D
+    int32_t* counts;          // K
+    unsigned long long* rep;  // K           smallest row index of each cluster
+    int64_t* idx;             // K           seeded initial rows
+    double* inertia;          // 1
+    TileWs tile;              // scratch of the MFMA tile kernels
+    size_t bytes;
+};
+
+static FitWs carve_fit(void* base, int64_t N, int64_t D, int32_t K, cat_dtype dt) {
+    (void)N;
+    Carver c(base);
+    FitWs w;
+    size_t KD = (size_t)K * (size_t)D;
+    w.acc = c.take<double>(4 * KD);
+    w.cent[0] = c.take<float>(KD);
+    w.cent[1] = c.take<float>(KD);
+    w.pivx = c.take<float>(KD);
+    w.pivy = c.take<float>(KD);
+    w.counts = c.take<int32_t>(K);
+    w.rep = c.take<unsigned long long>(K);
+    w.idx = c.take<int64_t>(K);
+    w.inertia = c.take<double>(1);
+    size_t tb = tile_workspace_bytes(D, K, dt);
+    w.tile = tile_carve(base ? (void*)(c.base + c.off) : nullptr, D, K, dt);
+    c.off += align256(tb);
+    w.bytes = c.off;
+    return w;
+}
+
+struct ApplyWs {
+    float* g_eff;
+    float* b_eff;
+    TileWs tile;
+    size_t bytes;
+};
+static ApplyWs carve_apply(void* base, int64_t D, int32_t K, cat_dtype dt) {
+    Carver c(base);
+    ApplyWs w;
+    size_t KD = (size_t)K * (size_t)D;
+    w.g_eff = c.take<float>(KD);
+    w.b_eff = c.take<float>(KD);
+    size_t tb = tile_workspace_bytes(D, K, dt);
+    w.tile = tile_carve(base ? (void*)(c.base + c.off) : nullptr, D, K, dt);
+    c.off += align256(tb);
+    w.bytes = c.off;
+    return w;
+}
+
+// ---- argument checks ----------------------------------------------------------------
+static bool shape_ok(int64_t N, int64_t D, int32_t K, cat_dtype dt) {
+    if (dt != CAT_F32 && dt != CAT_BF16) return false;
+    if (N < 1 || D < 1 || K < 1 || (int64_t)K > N || K > CAT_MAX_K) return false;
+    if (dt == CAT_BF16 && (D & 1)) return false;
+    if (D > (int64_t)1 << 24) return false;
+    if (N > ((int64_t)1 << 62) / D) return false;
+    return true;
+}
+static cat_status check_shape(const char* fn, int64_t N, int64_t D, int32_t K, cat_dtype dt) {
+    if (!shape_ok(N, D, K, dt))
+        return set_error(CAT_ERR_INVALID_ARG,
+                         "%s: need 1 <= K <= min(N, %d), D >= 1 (even for bf16), dt in {F32, BF16}; got N=%lld D=%lld "
+                         "K=%d dt=%d",
+                         fn, CAT_MAX_K, (long long)N, (long long)D, (int)K, (int)dt);
+    return CAT_OK;
+}
+static cat_status check_ptr(const char* fn, const char* name, const void* p, size_t align) {
+    if (!p) return set_error(CAT_ERR_INVALID_ARG, "%s: %s is NULL", fn, name);
+    if (((uintptr_t)p) % align) return set_error(CAT_ERR_INVALID_ARG, "%s: %s is not %zu-byte aligned", fn, name, align);
+    return CAT_OK;
+}
+static cat_status check_ws(const char* fn, const void* ws, size_t have, size_t need) {
+    if (!ws) return set_error(CAT_ERR_WORKSPACE, "%s: workspace is NULL (need %zu bytes)", fn, need);
+    if (((uintptr_t)ws) % 256) return set_error(CAT_ERR_WORKSPACE, "%s: workspace is not 256-byte aligned", fn);
+    if (have < need) return set_error(CAT_ERR_WORKSPACE, "%s: workspace has %zu bytes, need %zu", fn, have, need);
+    return CAT_OK;
+}
+#define CAT_TRY(expr)                      \
+    do {                                   \
+        cat_status _s = (expr);            \
+        if (_s != CAT_OK) return _s;       \
+    } while (0)
+
+// ---- steps ------------------------------------------------------------------------
+// One assignment pass on the selected kernel family.  counts / inertia / rep are optional
+// device outputs, initialised here.
+static cat_status step_assign(const void* lq, cat_dtype dt, int64_t N, int64_t D, int32_t K, const float* cent,
+                              int32_t* assign, int32_t* counts, double* inertia, unsigned long long* rep,
+                              const TileWs& tw, hipStream_t st) {
+    if (counts) CAT_TRY(launch_fill_zero(counts, (size_t)K * sizeof(int32_t), st));
+    if (inertia) CAT_TRY(launch_fill_zero(inertia, sizeof(double), st));
+    if (rep) CAT_TRY(launch_fill_u64(rep, K, ~0ull, st));
+    const int path = g_path.load();
+    const bool tile_ok = tile_supports(TILE_ASSIGN, D, K, dt);
+    if (path == CAT_PATH_TILE && !tile_ok)
+        return set_error(CAT_ERR_UNSUPPORTED, "tile path forced but D=%lld K=%d dt=%d does not fit it", (long long)D,
+                         (int)K, (int)dt);
+    if (tile_ok && path != CAT_PATH_STREAM)
+        return tile_assign(lq, dt, N, D, K, cent, assign, counts, inertia, rep, nullptr, nullptr, nullptr, tw, st);
+    return launch_assign_stream(lq, dt, N, D, K, cent, assign, counts, inertia, rep, nullptr, nullptr, nullptr, st);
+}
+
+static cat_status step_update(const void* lq, cat_dtype dt, const int32_t* assign, int64_t N, int64_t D, int32_t K,
+                              const int32_t* counts, const float* prev, float* cent, double* acc, hipStream_t st) {
+    CAT_TRY(launch_fill_zero(acc, (size_t)K * D * sizeof(double), st));
+    CAT_TRY(launch_segsum(1, lq, nullptr, dt, assign, N, D, K, nullptr, nullptr, acc, st));
+    return launch_finalize_centroids(acc, counts, prev, cent, D, K, st);
+}
+
+static cat_status step_stats(const void* lq, const void* fp, cat_dtype dt, const int32_t* assign, int64_t N, int64_t D,
+                             int32_t K, const int32_t* counts, const unsigned long long* rep, const float* hint,
+                             const FitWs& w, float* gamma, float* beta, hipStream_t st) {
+    CAT_TRY(launch_gather_pivots(lq, fp, dt, D, K, rep, hint, w.pivx, w.pivy, st));
+    CAT_TRY(launch_fill_zero(w.acc, (size_t)4 * K * D * sizeof(double), st));
+    CAT_TRY(launch_segsum(4, lq, fp, dt, assign, N, D, K, w.pivx, w.pivy, w.acc, st));
+    return launch_finalize_affine(w.acc, counts, w.pivx, w.pivy, gamma, beta, D, K, st);
+}
+
+}  // namespace cat
+
+using namespace cat;
+
+extern "C" {
+
+const char* cat_last_error(void) { return g_err; }
+
+cat_status cat_select_path(cat_path p) {
+    if (p != CAT_PATH_AUTO && p != CAT_PATH_STREAM && p != CAT_PATH_TILE)
+        return set_error(CAT_ERR_INVALID_ARG, "cat_select_path: unknown path %d", (int)p);
+    g_path.store((int)p);
+    return CAT_OK;
+}
+
+size_t cat_fit_workspace_bytes(int64_t N, int64_t D, int32_t K, cat_dtype dt) {
+    if (!shape_ok(N, D, K, dt)) return 0;
+    return carve_fit(nullptr, N, D, K, dt).bytes;
+}
+
+size_t cat_apply_workspace_bytes(int64_t N, int64_t D, int32_t K, cat_dtype dt) {
+    if (!shape_ok(N, D, K, dt)) return 0;
+    return carve_apply(nullptr, D, K, dt).bytes;
+}
+
+cat_status cat_init_indices(int64_t N, int32_t K, uint64_t seed, int64_t* idx_out) {
+    if (N < 1 || K < 1 || (int64_t)K > N || K > CAT_MAX_K || !idx_out)
+        return set_error(CAT_ERR_INVALID_ARG, "cat_init_indices: need 1 <= K <= min(N, %d) and idx_out != NULL",
+                         CAT_MAX_K);
+    const uint64_t cap = init_draw_cap(N);
+    int32_t have = 0;
+    uint64_t t = 0;
+    while (have < K && t < cap) {
+        int64_t cand = (int64_t)(splitmix64_at(seed, t) % (uint64_t)N);
+        t++;
+        bool dup = false;
+        for (int32_t q = 0; q < have && !dup; q++) dup = idx_out[q] == cand;
+        if (!dup) idx_out[have++] = cand;
+    }
+    for (int64_t c = 0; have < K && c < N; c++) {
+        bool dup = false;
+        for (int32_t q = 0; q < have && !dup; q++) dup = idx_out[q] == c;
+        if (!dup) idx_out[have++] = c;
+    }
+    return CAT_OK;
+}
+
+cat_status cat_assign(const void* lq, int64_t N, int64_t D, int32_t K, cat_dtype dt, const float* centroids,
+                      int32_t* assignments, int32_t* counts, double* inertia, void* workspace,
+                      size_t workspace_bytes, void* hip_stream) {
+    CAT_TRY(check_shape("cat_assign", N, D, K, dt));
+    CAT_TRY(check_ptr("cat_assign", "lq", lq, 16));
+    CAT_TRY(check_ptr("cat_assign", "centroids", centroids, 16));
+    CAT_TRY(check_ptr("cat_assign", "assignments", assignments, 4));
+    FitWs w = carve_fit(workspace, N, D, K, dt);
+    CAT_TRY(check_ws("cat_assign", workspace, workspace_bytes, w.bytes));
+    hipStream_t st = (hipStream_t)hip_stream;
+    return step_assign(lq, dt, N, D, K, centroids, assignments, counts, inertia, nullptr, w.tile, st);
+}
+
+cat_status cat_update(const void* lq, const int32_t* assignments, int64_t N, int64_t D, int32_t K, cat_dtype dt,
+                      const float* prev_centroids, float* centroids, int32_t* counts, void* workspace,
+                      size_t workspace_bytes, void* hip_stream) {
+    CAT_TRY(check_shape("cat_update", N, D, K, dt));
+    CAT_TRY(check_ptr("cat_update", "lq", lq, 16));
+    CAT_TRY(check_ptr("cat_update", "assignments", assignments, 4));
+    CAT_TRY(check_ptr("cat_update", "prev_centroids", prev_centroids, 16));
+    CAT_TRY(check_ptr("cat_update", "centroids", centroids, 16));
+    FitWs w = carve_fit(workspace, N, D, K, dt);
+    CAT_TRY(check_ws("cat_update", workspace, workspace_bytes, w.bytes));
+    hipStream_t st = (hipStream_t)hip_stream;
+    CAT_TRY(launch_fill_zero(w.counts, (size_t)K * sizeof(int32_t), st));
+    CAT_TRY(launch_fill_u64(w.rep, K, ~0ull, st));
+    CAT_TRY(launch_count_rep(assignments, N, K, w.counts, w.rep, st));
+    CAT_TRY(step_update(lq, dt, assignments, N, D, K, w.counts, prev_centroids, centroids, w.acc, st));
+    if (counts) CAT_TRY(launch_copy_words(w.counts, counts, K, st));
+    return CAT_OK;
+}
+
+cat_status cat_stats(const void* lq, const void* fp, const int32_t* assignments, int64_t N, int64_t D, int32_t K,
+                     cat_dtype dt, const float* centroids, float* gamma, float* beta, int32_t* counts,
+                     void* workspace, size_t workspace_bytes, void* hip_stream) {
+    CAT_TRY(check_shape("cat_stats", N, D, K, dt));
+    CAT_TRY(check_ptr("cat_stats", "lq", lq, 16));
+    CAT_TRY(check_ptr("cat_stats", "fp", fp, 16));
+    CAT_TRY(check_ptr("cat_stats", "assignments", assignments, 4));
+    CAT_TRY(check_ptr("cat_stats", "gamma", gamma, 16));
+    CAT_TRY(check_ptr("cat_stats", "beta", beta, 16));
+    if (centroids) CAT_TRY(check_ptr("cat_stats", "centroids", centroids, 16));
+    FitWs w = carve_fit(workspace, N, D, K, dt);
+    CAT_TRY(check_ws("cat_stats", workspace, workspace_bytes, w.bytes));
+    hipStream_t st = (hipStream_t)hip_stream;
+    CAT_TRY(launch_fill_zero(w.counts, (size_t)K * sizeof(int32_t), st));
+    CAT_TRY(launch_fill_u64(w.rep, K, ~0ull, st));
+    CAT_TRY(launch_count_rep(assignments, N, K, w.counts, w.rep, st));
+    CAT_TRY(step_stats(lq, fp, dt, assignments, N, D, K, w.counts, w.rep, centroids, w, gamma, beta, st));
+    if (counts) CAT_TRY(launch_copy_words(w.counts, counts, K, st));
+    return CAT_OK;
+}
+
+cat_status cat_fit(const void* lq, const void* fp, int64_t N, int64_t D, int32_t K, int32_t iters, uint64_t seed,
+                   cat_dtype dt, const float* init_centroids, float* centroids, float* gamma, float* beta,
+                   int32_t* assignments, int32_t* counts, double* inertia, void* workspace, size_t workspace_bytes,
+                   void* hip_stream) {
+    CAT_TRY(check_shape("cat_fit", N, D, K, dt));
+    if (iters < 0) return set_error(CAT_ERR_INVALID_ARG, "cat_fit: iters = %d is negative", (int)iters);
+    CAT_TRY(check_ptr("cat_fit", "lq", lq, 16));
+    CAT_TRY(check_ptr("cat_fit", "fp", fp, 16));
+    if (init_centroids) CAT_TRY(check_ptr("cat_fit", "init_centroids", init_centroids, 16));
+    CAT_TRY(check_ptr("cat_fit", "centroids", centroids, 16));
+    CAT_TRY(check_ptr("cat_fit", "gamma", gamma, 16));
+    CAT_TRY(check_ptr("cat_fit", "beta", beta, 16));
+    CAT_TRY(check_ptr("cat_fit", "assignments", assignments, 4));
+    if (inertia) CAT_TRY(check_ptr("cat_fit", "inertia", inertia, 8));
+    FitWs w = carve_fit(workspace, N, D, K, dt);
+    CAT_TRY(check_ws("cat_fit", workspace, workspace_bytes, w.bytes));
+    hipStream_t st = (hipStream_t)hip_stream;
+    const size_t KD = (size_t)K * (size_t)D;
+
+    // init
+    if (init_centroids) {
+        CAT_TRY(launch_copy_words(init_centroids, w.cent[0], (int64_t)KD, st));
+    } else {
+        CAT_TRY(launch_init_indices(N, K, seed, w.idx, st));
+        CAT_TRY(launch_gather_rows(lq, dt, D, K, w.idx, w.cent[0], st));
+    }
+
+    const int path = g_path.load();
+    int cur = 0;
+    const bool fused = tile_supports(TILE_LLOYD, D, K, dt) && path != CAT_PATH_STREAM;
+    if (path == CAT_PATH_TILE && !tile_supports(TILE_ASSIGN, D, K, dt))
+        return set_error(CAT_ERR_UNSUPPORTED, "tile path forced but D=%lld K=%d dt=%d does not fit it", (long long)D,
+                         (int)K, (int)dt);
+    if (fused) {
+        // one launch per Lloyd iteration: assignment with the centroid sums accumulated in the same pass
+        CAT_TRY(tile_lloyd(lq, dt, N, D, K, iters, w.cent[0], centroids, assignments, w.counts, inertia, w.rep, w.tile,
+                           st));
+    } else {
+        for (int32_t t = 0; t < iters; t++) {
+            CAT_TRY(step_assign(lq, dt, N, D, K, w.cent[cur], assignments, w.counts, inertia ? w.inertia : nullptr,
+                                nullptr, w.tile, st));
+            if (inertia)
+                CAT_TRY(launch_copy_words(w.inertia, inertia + t, 2, st));
+            CAT_TRY(step_update(lq, dt, assignments, N, D, K, w.counts, w.cent[cur], w.cent[cur ^ 1], w.acc, st));
+            cur ^= 1;
+        }
+        // final assignment against the final centroids
+        CAT_TRY(step_assign(lq, dt, N, D, K, w.cent[cur], assignments, w.counts, inertia ? w.inertia : nullptr, w.rep,
+                            w.tile, st));
+        if (inertia)
+            CAT_TRY(launch_copy_words(w.inertia, inertia + iters, 2, st));
+        CAT_TRY(launch_copy_words(w.cent[cur], centroids, (int64_t)KD, st));
+    }
+    // affine fit on that partition, shifted by the centroids
+    CAT_TRY(step_stats(lq, fp, dt, assignments, N, D, K, w.counts, w.rep, centroids, w, gamma, beta, st));
+    if (counts) CAT_TRY(launch_copy_words(w.counts, counts, K, st));
+    return CAT_OK;
+}
+
+cat_status cat_apply(const void* lq, int64_t N, int64_t D, int32_t K, cat_dtype dt, const float* centroids,
+                     const float* gamma, const float* beta, float alpha, void* corrected, int32_t* assignments,
+                     void* workspace, size_t workspace_bytes, void* hip_stream) {
+    CAT_TRY(check_shape("cat_apply", N, D, K, dt));
+    CAT_TRY(check_ptr("cat_apply", "lq", lq, 16));
+    CAT_TRY(check_ptr("cat_apply", "centroids", centroids, 16));
+    CAT_TRY(check_ptr("cat_apply", "gamma", gamma, 16));
+    CAT_TRY(check_ptr("cat_apply", "beta", beta, 16));
+    CAT_TRY(check_ptr("cat_apply", "corrected", corrected, 16));
+    if (corrected == lq) return set_error(CAT_ERR_INVALID_ARG, "cat_apply: corrected may not alias lq");
+    if (!std::isfinite(alpha)) return set_error(CAT_ERR_INVALID_ARG, "cat_apply: alpha is not finite");
+    ApplyWs w = carve_apply(workspace, D, K, dt);
+    CAT_TRY(check_ws("cat_apply", workspace, workspace_bytes, w.bytes));
+    hipStream_t st = (hipStream_t)hip_stream;
+    const float* g = gamma;
+    const float* b = beta;
+    if (alpha != 1.0f) {
+        CAT_TRY(launch_fold_alpha(gamma, beta, alpha, w.g_eff, w.b_eff, (int64_t)K * D, st));
+        g = w.g_eff;
+        b = w.b_eff;
+    }
+    const int path = g_path.load();
+    const bool tile_ok = tile_supports(TILE_APPLY, D, K, dt);
+    if (path == CAT_PATH_TILE && !tile_ok)
+        return set_error(CAT_ERR_UNSUPPORTED, "tile path forced but D=%lld K=%d dt=%d does not fit it", (long long)D,
+                         (int)K, (int)dt);
+    if (tile_ok && path != CAT_PATH_STREAM)
+        return tile_assign(lq, dt, N, D, K, centroids, assignments, nullptr, nullptr, nullptr, g, b, corrected, w.tile,
+                           st);
+    return launch_assign_stream(lq, dt, N, D, K, centroids, assignments, nullptr, nullptr, nullptr, g, b, corrected,
+                                st);
+}
+
+}  // extern "C"

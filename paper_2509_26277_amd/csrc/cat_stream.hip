@@ -1,0 +1,438 @@
+// Streaming (non-MFMA) kernels of the CAT hot path for gfx950: seeded init, the
+// direct-form assignment / inference kernel that serves every shape, the
+// segmented sums behind the centroid update and the affine statistics, and the
+// small K x D finalisers.
+#include "cat_common.h"
+
+namespace cat {
+
+// ---------------------------------------------------------------------------------
+// small utilities
+// ---------------------------------------------------------------------------------
+__global__ void k_fill_zero(uint32_t* p, size_t nwords) {
+    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    size_t step = (size_t)gridDim.x * blockDim.x;
+    for (; i < nwords; i += step) p[i] = 0u;
+}
+cat_status launch_fill_zero(void* p, size_t bytes, hipStream_t st) {
+    if (bytes == 0) return CAT_OK;
+    size_t nwords = bytes / 4;  // every workspace block is a multiple of 4 bytes
+    int blocks = (int)((nwords + 255) / 256 < 2048 ? (nwords + 255) / 256 : 2048);
+    hipLaunchKernelGGL(k_fill_zero, dim3(blocks), dim3(256), 0, st, (uint32_t*)p, nwords);
+    CAT_LAUNCH_CHECK("k_fill_zero");
+    return CAT_OK;
+}
+
+__global__ void k_fill_u64(unsigned long long* p, int64_t n, unsigned long long v) {
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = v;
+}
+cat_status launch_fill_u64(unsigned long long* p, int64_t n, unsigned long long v, hipStream_t st) {
+    hipLaunchKernelGGL(k_fill_u64, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, p, n, v);
+    CAT_LAUNCH_CHECK("k_fill_u64");
+    return CAT_OK;
+}
+
+__global__ void k_copy_words(const uint32_t* src, uint32_t* dst, int64_t n) {
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    int64_t step = (int64_t)gridDim.x * blockDim.x;
+    for (; i < n; i += step) dst[i] = src[i];
+}
+cat_status launch_copy_words(const void* src, void* dst, int64_t nwords, hipStream_t st) {
+    int64_t b = (nwords + 255) / 256;
+    hipLaunchKernelGGL(k_copy_words, dim3((unsigned)(b < 1024 ? b : 1024)), dim3(256), 0, st, (const uint32_t*)src,
+                       (uint32_t*)dst, nwords);
+    CAT_LAUNCH_CHECK("k_copy_words");
+    return CAT_OK;
+}
+
+// ---------------------------------------------------------------------------------
+// seeded initial rows: one wave walks the SplitMix64 counter; the 64 lanes share
+// the "already taken?" scan.  The walk has a hard draw cap, so the wave always exits.
+// ---------------------------------------------------------------------------------
+__global__ __launch_bounds__(64) void k_init_indices(int64_t N, int32_t K, uint64_t seed, int64_t* idx) {
+    __shared__ int64_t s_idx[CAT_MAX_K];
+    const int lane = threadIdx.x;
+    const uint64_t cap = init_draw_cap(N);
+    int32_t have = 0;
+    uint64_t t = 0;
+    while (have < K && t < cap) {
+        int64_t cand = (int64_t)(splitmix64_at(seed, t) % (uint64_t)N);
+        t++;
+        bool dup = false;
+        for (int q = lane; q < have; q += kWave) dup |= (s_idx[q] == cand);
+        if (__ballot(dup) == 0ull) {
+            if (lane == 0) s_idx[have] = cand;
+            have++;
+        }
+        __syncthreads();
+    }
+    // cap reached (not expected): complete with the smallest indices not yet taken
+    for (int64_t c = 0; have < K && c < N; c++) {
+        bool dup = false;
+        for (int q = lane; q < have; q += kWave) dup |= (s_idx[q] == c);
+        if (__ballot(dup) == 0ull) {
+            if (lane == 0) s_idx[have] = c;
+            have++;
+        }
+        __syncthreads();
+    }
+    for (int q = lane; q < K; q += kWave) idx[q] = s_idx[q];
+}
+cat_status launch_init_indices(int64_t N, int32_t K, uint64_t seed, int64_t* idx, hipStream_t st) {
+    hipLaunchKernelGGL(k_init_indices, dim3(1), dim3(64), 0, st, N, K, seed, idx);
+    CAT_LAUNCH_CHECK("k_init_indices");
+    return CAT_OK;
+}
+
+template <typename T>
+__global__ void k_gather_rows(const T* lq, int64_t D, const int64_t* idx, float* out) {
+    const int k = blockIdx.x;
+    const T* src = lq + idx[k] * D;
+    for (int64_t j = threadIdx.x; j < D; j += blockDim.x) out[(int64_t)k * D + j] = ld_elem(src + j);
+}
+cat_status launch_gather_rows(const void* lq, cat_dtype dt, int64_t D, int32_t K, const int64_t* idx,
+                              float* out, hipStream_t st) {
+    if (dt == CAT_F32)
+        hipLaunchKernelGGL(k_gather_rows<float>, dim3(K), dim3(256), 0, st, (const float*)lq, D, idx, out);
+    else
+        hipLaunchKernelGGL(k_gather_rows<bf16_t>, dim3(K), dim3(256), 0, st, (const bf16_t*)lq, D, idx, out);
+    CAT_LAUNCH_CHECK("k_gather_rows");
+    return CAT_OK;
+}
+
+// ---------------------------------------------------------------------------------
+// assignment / inference, any shape: one wave per row, direct-form squared
+// distances in double, strict "<" so the lowest index keeps a tie.
+// ---------------------------------------------------------------------------------
+constexpr int kAssignWaves = 4;
+
+template <typename T, bool APPLY>
+__global__ __launch_bounds__(kAssignWaves * kWave) void k_assign_stream(
+    const T* __restrict__ lq, int64_t N, int64_t D, int32_t K, const float* __restrict__ cent,
+    int32_t* __restrict__ assign, int32_t* counts, double* inertia, unsigned long long* rep,
+    const float* __restrict__ gamma, const float* __restrict__ beta, T* __restrict__ out) {
+    __shared__ int s_cnt[CAT_MAX_K];
+    __shared__ unsigned long long s_rep[CAT_MAX_K];
+    __shared__ double s_in[kAssignWaves];
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = threadIdx.x / kWave;
+    const bool hist = (counts != nullptr) || (rep != nullptr);
+    if (hist) {
+        for (int k = threadIdx.x; k < K; k += blockDim.x) {
+            s_cnt[k] = 0;
+            s_rep[k] = ~0ull;
+        }
+        __syncthreads();
+    }
+    double in_acc = 0.0;
+    const int64_t stride = (int64_t)gridDim.x * kAssignWaves;
+    for (int64_t row = (int64_t)blockIdx.x * kAssignWaves + wave; row < N; row += stride) {
+        const T* x = lq + row * D;
+        double best = __builtin_inf();
+        int arg = 0;
+        for (int k = 0; k < K; k++) {
+            const float* c = cent + (int64_t)k * D;
+            double s = 0.0;
+            for (int64_t j = lane; j < D; j += kWave) {
+                double d = (double)ld_elem(x + j) - (double)c[j];
+                s = fma(d, d, s);
+            }
+            s = wave_sum(s);
+            if (s < best) {
+                best = s;
+                arg = k;
+            }
+        }
+        if (lane == 0) {
+            if (assign) assign[row] = arg;
+            if (hist) {
+                atomicAdd(&s_cnt[arg], 1);
+                atomicMin(&s_rep[arg], (unsigned long long)row);
+            }
+            in_acc += best;
+        }
+        if (APPLY) {
+            const float* g = gamma + (int64_t)arg * D;
+            const float* b = beta + (int64_t)arg * D;
+            T* o = out + row * D;
+            for (int64_t j = lane; j < D; j += kWave) st_elem(o + j, fmaf(g[j], ld_elem(x + j), b[j]));
+        }
+    }
+    if (hist || inertia) {
+        if (lane == 0) s_in[wave] = in_acc;
+        __syncthreads();
+        if (hist)
+            for (int k = threadIdx.x; k < K; k += blockDim.x) {
+                if (counts && s_cnt[k]) atomicAdd(&counts[k], s_cnt[k]);
+                if (rep && s_rep[k] != ~0ull) atomicMin(&rep[k], s_rep[k]);
+            }
+        if (inertia && threadIdx.x == 0) {
+            double tot = 0.0;
+            for (int w = 0; w < kAssignWaves; w++) tot += s_in[w];
+            atomicAdd(inertia, tot);
+        }
+    }
+}
+
+cat_status launch_assign_stream(const void* lq, cat_dtype dt, int64_t N, int64_t D, int32_t K,
+                                const float* cent, int32_t* assign, int32_t* counts, double* inertia,
+                                unsigned long long* rep, const float* gamma, const float* beta,
+                                void* corrected, hipStream_t st) {
+    int64_t want = (N + kAssignWaves - 1) / kAssignWaves;
+    unsigned blocks = (unsigned)(want < 4096 ? want : 4096);
+    dim3 g(blocks), b(kAssignWaves * kWave);
+    const bool apply = gamma != nullptr;
+    if (dt == CAT_F32) {
+        if (apply)
+            hipLaunchKernelGGL((k_assign_stream<float, true>), g, b, 0, st, (const float*)lq, N, D, K, cent, assign,
+                               counts, inertia, rep, gamma, beta, (float*)corrected);
+        else
+            hipLaunchKernelGGL((k_assign_stream<float, false>), g, b, 0, st, (const float*)lq, N, D, K, cent, assign,
+                               counts, inertia, rep, gamma, beta, (float*)corrected);
+    } else {
+        if (apply)
+            hipLaunchKernelGGL((k_assign_stream<bf16_t, true>), g, b, 0, st, (const bf16_t*)lq, N, D, K, cent, assign,
+                               counts, inertia, rep, gamma, beta, (bf16_t*)corrected);
+        else
+            hipLaunchKernelGGL((k_assign_stream<bf16_t, false>), g, b, 0, st, (const bf16_t*)lq, N, D, K, cent,
+                               assign, counts, inertia, rep, gamma, beta, (bf16_t*)corrected);
+    }
+    CAT_LAUNCH_CHECK("k_assign_stream");
+    return CAT_OK;
+}
+
+// ---------------------------------------------------------------------------------
+// counts and representative rows from a given partition
+// ---------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void k_count_rep(const int32_t* __restrict__ assign, int64_t N, int32_t K,
+                                                   int32_t* counts, unsigned long long* rep) {
+    __shared__ int s_cnt[CAT_MAX_K];
+    __shared__ unsigned long long s_rep[CAT_MAX_K];
+    for (int k = threadIdx.x; k < K; k += blockDim.x) {
+        s_cnt[k] = 0;
+        s_rep[k] = ~0ull;
+    }
+    __syncthreads();
+    int64_t step = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < N; i += step) {
+        int a = assign[i];
+        if (a >= 0 && a < K) {
+            atomicAdd(&s_cnt[a], 1);
+            atomicMin(&s_rep[a], (unsigned long long)i);
+        }
+    }
+    __syncthreads();
+    for (int k = threadIdx.x; k < K; k += blockDim.x) {
+        if (s_cnt[k]) atomicAdd(&counts[k], s_cnt[k]);
+        if (s_rep[k] != ~0ull) atomicMin(&rep[k], s_rep[k]);
+    }
+}
+cat_status launch_count_rep(const int32_t* assign, int64_t N, int32_t K, int32_t* counts,
+                            unsigned long long* rep, hipStream_t st) {
+    int64_t b = (N + 255) / 256;
+    hipLaunchKernelGGL(k_count_rep, dim3((unsigned)(b < 1024 ? b : 1024)), dim3(256), 0, st, assign, N, K, counts,
+                       rep);
+    CAT_LAUNCH_CHECK("k_count_rep");
+    return CAT_OK;
+}
+
+// ---------------------------------------------------------------------------------
+// segmented sums.  grid = (row blocks, channel slices, cluster chunks).  A workgroup
+// owns a [rows x slice] panel; each wave walks whole rows of the panel, so a row's
+// cluster id is wave-uniform and the 64 lanes touch 64 different channels: the LDS
+// adds never collide inside a wave.  Short fp32 runs in LDS, merged into global
+// doubles with one atomic per (cluster, channel) per workgroup.
+// ---------------------------------------------------------------------------------
+constexpr int kSegWaves = 4;
+constexpr int kSegRows = 512;  // rows per workgroup panel
+
+template <typename T, int NQ>
+__global__ __launch_bounds__(kSegWaves * kWave) void k_segsum(
+    const T* __restrict__ lq, const T* __restrict__ fp, const int32_t* __restrict__ assign, int64_t N, int64_t D,
+    int32_t K, int32_t KC, int32_t SW, const float* __restrict__ pivx, const float* __restrict__ pivy,
+    double* __restrict__ acc) {
+    extern __shared__ float s_mem[];
+    float* s_acc = s_mem;                              // NQ x KC x SW
+    float* s_px = s_mem + (size_t)NQ * KC * SW;        // KC x SW (NQ == 4 only)
+    float* s_py = s_px + (size_t)KC * SW;
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = threadIdx.x / kWave;
+    const int64_t row0 = (int64_t)blockIdx.x * kSegRows;
+    const int64_t ch0 = (int64_t)blockIdx.y * SW;
+    const int k0 = blockIdx.z * KC;
+    const int kc = (K - k0) < KC ? (K - k0) : KC;
+    const int cells = KC * SW;
+
+    for (int i = threadIdx.x; i < NQ * cells; i += blockDim.x) s_acc[i] = 0.f;
+    if (NQ == 4) {
+        for (int i = threadIdx.x; i < cells; i += blockDim.x) {
+            int k = i / SW, c = i - k * SW;
+            bool ok = (k < kc) && (ch0 + c < D);
+            s_px[i] = ok ? pivx[(int64_t)(k0 + k) * D + ch0 + c] : 0.f;
+            s_py[i] = ok ? pivy[(int64_t)(k0 + k) * D + ch0 + c] : 0.f;
+        }
+    }
+    __syncthreads();
+
+    const int64_t rend = (row0 + kSegRows < N) ? row0 + kSegRows : N;
+    for (int64_t row = row0 + wave; row < rend; row += kSegWaves) {
+        int a = __builtin_amdgcn_readfirstlane(assign[row]) - k0;
+        if (a < 0 || a >= kc) continue;  // other chunk, or an out-of-range label
+        const T* x = lq + row * D + ch0;
+        const T* y = (NQ == 4) ? fp + row * D + ch0 : nullptr;
+        float* sa = s_acc + (size_t)a * SW;
+        for (int c = lane; c < SW; c += kWave) {
+            if (ch0 + c >= D) break;
+            float xv = ld_elem(x + c);
+            if (NQ == 1) {
+                atomicAdd(sa + c, xv);
+            } else {
+                float xs = xv - s_px[a * SW + c];
+                float ys = ld_elem(y + c) - s_py[a * SW + c];
+                atomicAdd(sa + c, xs);
+                atomicAdd(sa + cells + c, ys);
+                atomicAdd(sa + 2 * cells + c, xs * xs);
+                atomicAdd(sa + 3 * cells + c, xs * ys);
+            }
+        }
+    }
+    __syncthreads();
+    const int64_t KD = (int64_t)K * D;
+    for (int i = threadIdx.x; i < NQ * cells; i += blockDim.x) {
+        int q = i / cells;
+        int r = i - q * cells;
+        int k = r / SW, c = r - k * SW;
+        float v = s_acc[i];
+        if (k < kc && ch0 + c < D && v != 0.f) atomicAdd(acc + q * KD + (int64_t)(k0 + k) * D + ch0 + c, (double)v);
+    }
+}
+
+cat_status launch_segsum(int nq, const void* lq, const void* fp, cat_dtype dt, const int32_t* assign,
+                         int64_t N, int64_t D, int32_t K, const float* pivx, const float* pivy,
+                         double* acc, hipStream_t st) {
+    // LDS floats per (cluster, channel): the accumulators, plus two pivots for the statistics
+    const int per_cell = (nq == 4) ? 6 : 1;
+    const int budget = 96 * 1024 / 4;  // floats
+    int SW = 256;
+    while (SW > 64 && ((int64_t)SW / 2 >= D || (int64_t)K * SW * per_cell > budget)) SW /= 2;
+    int KC = budget / (SW * per_cell);
+    if (KC > K) KC = K;
+    if (KC < 1) return set_error(CAT_ERR_UNSUPPORTED, "segsum: no LDS tiling for K=%d", K);
+    dim3 grid((unsigned)((N + kSegRows - 1) / kSegRows), (unsigned)((D + SW - 1) / SW), (unsigned)((K + KC - 1) / KC));
+    dim3 block(kSegWaves * kWave);
+    size_t lds = (size_t)KC * SW * per_cell * sizeof(float);
+#define CAT_SEG(T, NQ_)                                                                                          \
+    do {                                                                                                         \
+        CAT_HIP_TRY(hipFuncSetAttribute((const void*)k_segsum<T, NQ_>, hipFuncAttributeMaxDynamicSharedMemorySize, \
+                                        (int)lds));                                                              \
+        hipLaunchKernelGGL((k_segsum<T, NQ_>), grid, block, lds, st, (const T*)lq, (const T*)fp, assign, N, D, K, KC, \
+                           SW, pivx, pivy, acc);                                                                 \
+    } while (0)
+    if (dt == CAT_F32) {
+        if (nq == 1) CAT_SEG(float, 1); else CAT_SEG(float, 4);
+    } else {
+        if (nq == 1) CAT_SEG(bf16_t, 1); else CAT_SEG(bf16_t, 4);
+    }
+#undef CAT_SEG
+    CAT_LAUNCH_CHECK("k_segsum");
+    return CAT_OK;
+}
+
+// ---------------------------------------------------------------------------------
+// K x D finalisers
+// ---------------------------------------------------------------------------------
+__global__ void k_finalize_centroids(const double* __restrict__ sums, const int32_t* __restrict__ counts,
+                                     const float* prev, float* cent, int64_t D, int64_t KD) {  // cent may alias prev
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= KD) return;
+    int n = counts[i / D];
+    cent[i] = n > 0 ? (float)(sums[i] / (double)n) : prev[i];
+}
+cat_status launch_finalize_centroids(const double* sums, const int32_t* counts, const float* prev,
+                                     float* cent, int64_t D, int32_t K, hipStream_t st) {
+    int64_t KD = (int64_t)K * D;
+    hipLaunchKernelGGL(k_finalize_centroids, dim3((unsigned)((KD + 255) / 256)), dim3(256), 0, st, sums, counts, prev,
+                       cent, D, KD);
+    CAT_LAUNCH_CHECK("k_finalize_centroids");
+    return CAT_OK;
+}
+
+template <typename T>
+__global__ void k_gather_pivots(const T* __restrict__ lq, const T* __restrict__ fp, int64_t D, int64_t KD,
+                                const unsigned long long* __restrict__ rep, const float* __restrict__ hint,
+                                float* __restrict__ pivx, float* __restrict__ pivy) {
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= KD) return;
+    int64_t k = i / D, j = i - k * D;
+    unsigned long long r = rep[k];
+    if (r == ~0ull) {
+        pivx[i] = 0.f;
+        pivy[i] = 0.f;
+    } else {
+        pivx[i] = hint ? hint[i] : ld_elem(lq + (int64_t)r * D + j);
+        pivy[i] = ld_elem(fp + (int64_t)r * D + j);
+    }
+}
+cat_status launch_gather_pivots(const void* lq, const void* fp, cat_dtype dt, int64_t D, int32_t K,
+                                const unsigned long long* rep, const float* hint, float* pivx, float* pivy,
+                                hipStream_t st) {
+    int64_t KD = (int64_t)K * D;
+    dim3 g((unsigned)((KD + 255) / 256)), b(256);
+    if (dt == CAT_F32)
+        hipLaunchKernelGGL(k_gather_pivots<float>, g, b, 0, st, (const float*)lq, (const float*)fp, D, KD, rep, hint,
+                           pivx, pivy);
+    else
+        hipLaunchKernelGGL(k_gather_pivots<bf16_t>, g, b, 0, st, (const bf16_t*)lq, (const bf16_t*)fp, D, KD, rep,
+                           hint, pivx, pivy);
+    CAT_LAUNCH_CHECK("k_gather_pivots");
+    return CAT_OK;
+}
+
+// gamma = cov / max(var, floor), beta = mean_y - gamma * mean_x, from the shifted raw moments
+__global__ void k_finalize_affine(const double* __restrict__ acc, const int32_t* __restrict__ counts,
+                                  const float* __restrict__ pivx, const float* __restrict__ pivy,
+                                  float* __restrict__ gamma, float* __restrict__ beta, int64_t D, int64_t KD) {
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= KD) return;
+    int n = counts[i / D];
+    if (n <= 0) {
+        gamma[i] = 1.f;
+        beta[i] = 0.f;
+        return;
+    }
+    double inv = 1.0 / (double)n;
+    double mx = acc[i] * inv, my = acc[KD + i] * inv;
+    double var = acc[2 * KD + i] * inv - mx * mx;
+    double cov = acc[3 * KD + i] * inv - mx * my;
+    if (var < kVarFloor) var = kVarFloor;
+    double g = cov / var;
+    gamma[i] = (float)g;
+    beta[i] = (float)(((double)pivy[i] + my) - g * ((double)pivx[i] + mx));
+}
+cat_status launch_finalize_affine(const double* acc, const int32_t* counts, const float* pivx,
+                                  const float* pivy, float* gamma, float* beta, int64_t D, int32_t K,
+                                  hipStream_t st) {
+    int64_t KD = (int64_t)K * D;
+    hipLaunchKernelGGL(k_finalize_affine, dim3((unsigned)((KD + 255) / 256)), dim3(256), 0, st, acc, counts, pivx,
+                       pivy, gamma, beta, D, KD);
+    CAT_LAUNCH_CHECK("k_finalize_affine");
+    return CAT_OK;
+}
+
+__global__ void k_fold_alpha(const float* __restrict__ gamma, const float* __restrict__ beta, float alpha,
+                             float* __restrict__ g_eff, float* __restrict__ b_eff, int64_t KD) {
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= KD) return;
+    g_eff[i] = 1.f + alpha * (gamma[i] - 1.f);
+    b_eff[i] = alpha * beta[i];
+}
+cat_status launch_fold_alpha(const float* gamma, const float* beta, float alpha, float* g_eff, float* b_eff,
+                             int64_t KD, hipStream_t st) {
+    hipLaunchKernelGGL(k_fold_alpha, dim3((unsigned)((KD + 255) / 256)), dim3(256), 0, st, gamma, beta, alpha, g_eff,
+                       b_eff, KD);
+    CAT_LAUNCH_CHECK("k_fold_alpha");
+    return CAT_OK;
+}
+
+}  // namespace cat

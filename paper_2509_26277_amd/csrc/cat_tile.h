@@ -1,0 +1,33 @@
+// MFMA tile kernels of the CAT hot path (cat_tile.hip): interface to the host driver.
+#pragma once
+#include "cat_common.h"
+
+namespace cat {
+
+enum TileMode { TILE_ASSIGN = 0, TILE_LLOYD = 1, TILE_APPLY = 2 };
+
+// Device scratch of the tile kernels, carved from the caller's workspace.
+struct TileWs {
+    void* base = nullptr;
+    size_t bytes = 0;
+};
+
+size_t tile_workspace_bytes(int64_t D, int32_t K, cat_dtype dt);
+TileWs tile_carve(void* base, int64_t D, int32_t K, cat_dtype dt);
+
+// Whether the tile kernels can run `mode` on this shape (LDS and register budgets).
+bool tile_supports(TileMode mode, int64_t D, int32_t K, cat_dtype dt);
+
+// Assignment pass (gamma == NULL) or fused inference (gamma, beta, corrected given).
+// counts / inertia / rep are optional and pre-initialised by the caller.
+cat_status tile_assign(const void* lq, cat_dtype dt, int64_t N, int64_t D, int32_t K, const float* cent,
+                       int32_t* assign, int32_t* counts, double* inertia, unsigned long long* rep,
+                       const float* gamma, const float* beta, void* corrected, const TileWs& ws, hipStream_t st);
+
+// `iters` fused Lloyd iterations from cent0 plus the final assignment: writes the final
+// centroids, assignments, counts (K), inertia (iters + 1, nullable) and rep (K).
+cat_status tile_lloyd(const void* lq, cat_dtype dt, int64_t N, int64_t D, int32_t K, int32_t iters,
+                      const float* cent0, float* cent_out, int32_t* assign, int32_t* counts, double* inertia,
+                      unsigned long long* rep, const TileWs& ws, hipStream_t st);
+
+}  // namespace cat

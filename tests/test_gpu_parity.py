@@ -1,0 +1,221 @@
+"""GPU-vs-oracle parity of the CAT hot path, through the C ABI.
+
+Step level ("teacher forced": the oracle's state is fed to one GPU step) and end
+to end, on structure-preserving small copies of the five workloads and on the
+method's edge cases.  Sizes span several 16-row tiles plus a ragged tail and the
+oracle finishes each in seconds.  Both kernel families are covered where a shape
+fits the tile kernels.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2509_26277_amd import binding, workloads
+from paper_2509_26277_amd import cat_apply, cat_assign, cat_fit, cat_stats, cat_update
+
+from parity_util import (RTOL, check_assignments, check_values, dev_matrix, f32_round, host_matrix)
+
+pytestmark = pytest.mark.gpu
+
+PATHS = [binding.CAT_PATH_STREAM, binding.CAT_PATH_AUTO]
+
+
+@pytest.fixture(autouse=True)
+def _auto_path_after():
+    yield
+    binding.select_path(binding.CAT_PATH_AUTO)
+
+
+def small(name, n_rows):
+    return workloads.make(name, n_rows=n_rows)
+
+
+SMALL_FIT = [("cfg1", 4096), ("cfg2", 1531), ("cfg3", 6007), ("cfg4", 1100)]
+
+
+# ---------------------------------------------------------------------------
+# seeded init
+# ---------------------------------------------------------------------------
+@pytest.mark.parametrize("name,n", [("cfg1", 4096), ("cfg4", 700)])
+def test_seeded_init_rows_are_copied_exactly(name, n):
+    w = small(name, n)
+    lq = dev_matrix(w["lq"], w["dtype"])
+    fp = dev_matrix(w["fp"], w["dtype"])
+    r = cat_fit(lq, fp, w["K"], iters=0, seed=4242)
+    idx = oracle.init_indices(n, w["K"], 4242)
+    assert (host_matrix(r["centroids"]) == w["lq"][idx].astype(np.float64)).all()
+
+
+# ---------------------------------------------------------------------------
+# teacher-forced steps
+# ---------------------------------------------------------------------------
+@pytest.mark.parametrize("path", PATHS)
+@pytest.mark.parametrize("name,n", SMALL_FIT)
+def test_assign_step(name, n, path):
+    binding.select_path(path)
+    w = small(name, n)
+    K = w["K"]
+    # the oracle's centroids after 2 iterations, rounded to the float the GPU is handed
+    o = oracle.fit(w["lq"], w["fp"], K, iters=2, seed=w["seed"])
+    cent = f32_round(o["centroids"])
+    a_o, d1, d2 = oracle.assign(w["lq"], cent, want_distances=True)
+    a_g, counts, inertia = cat_assign(dev_matrix(w["lq"], w["dtype"]), torch.from_numpy(cent.astype(np.float32)).cuda())
+    check_assignments(a_g.cpu().numpy(), a_o, d1, d2, f"{name} assign")
+    assert counts.cpu().numpy().tolist() == np.bincount(a_g.cpu().numpy(), minlength=K).tolist()
+    assert inertia.item() == pytest.approx(d1.sum(), rel=1e-5)
+
+
+@pytest.mark.parametrize("name,n", SMALL_FIT)
+def test_update_and_stats_steps(name, n):
+    w = small(name, n)
+    K, dt = w["K"], w["dtype"]
+    o = oracle.fit(w["lq"], w["fp"], K, iters=3, seed=w["seed"])
+    a = o["assignments"]
+    lq, fp = dev_matrix(w["lq"], dt), dev_matrix(w["fp"], dt)
+    a_dev = torch.from_numpy(a).cuda()
+    prev = f32_round(o["centroids"]) + 0.25
+    c_o, n_o = oracle.update(w["lq"], a, prev)
+    c_g, n_g = cat_update(lq, a_dev, torch.from_numpy(prev.astype(np.float32)).cuda())
+    assert n_g.cpu().numpy().tolist() == n_o.tolist()
+    check_values(host_matrix(c_g), c_o, RTOL[dt], f"{name} update")
+    g_o, b_o, _ = oracle.affine(w["lq"], w["fp"], a, K)
+    for hint in (None, c_g):
+        g_g, b_g, n2 = cat_stats(lq, fp, a_dev, K, centroids=hint)
+        assert n2.cpu().numpy().tolist() == n_o.tolist()
+        check_values(host_matrix(g_g), g_o, RTOL[dt], f"{name} gamma")
+        check_values(host_matrix(b_g), b_o, RTOL[dt], f"{name} beta")
+
+
+# ---------------------------------------------------------------------------
+# end to end
+# ---------------------------------------------------------------------------
+@pytest.mark.parametrize("path", PATHS)
+@pytest.mark.parametrize("name,n", SMALL_FIT)
+def test_fit_end_to_end(name, n, path):
+    binding.select_path(path)
+    w = small(name, n)
+    K, dt, iters = w["K"], w["dtype"], min(w["iters"], 8)
+    lq, fp = dev_matrix(w["lq"], dt), dev_matrix(w["fp"], dt)
+    r = cat_fit(lq, fp, K, iters, seed=w["seed"])
+    o = oracle.fit(w["lq"], w["fp"], K, iters, seed=w["seed"])
+    _, d1, d2 = oracle.assign(w["lq"], o["centroids"], want_distances=True)
+    a_g = r["assignments"].cpu().numpy()
+    check_assignments(a_g, o["assignments"], d1, d2, f"{name} fit")
+    assert r["counts"].cpu().numpy().tolist() == np.bincount(a_g, minlength=K).tolist()
+    check_values(host_matrix(r["centroids"]), o["centroids"], RTOL[dt], f"{name} centroids")
+    check_values(host_matrix(r["gamma"]), o["gamma"], RTOL[dt], f"{name} gamma")
+    check_values(host_matrix(r["beta"]), o["beta"], RTOL[dt], f"{name} beta")
+    np.testing.assert_allclose(r["inertia"].cpu().numpy(), o["inertia"], rtol=1e-5)
+    # fit <-> apply: inference on the fitting rows reproduces the partition
+    out, a2 = cat_apply(lq, r["centroids"], r["gamma"], r["beta"])
+    same = (a2.cpu().numpy() == a_g)
+    _, e1, e2 = oracle.assign(w["lq"], host_matrix(r["centroids"]), want_distances=True)
+    assert ((e2 - e1)[~same] <= 1e-5 * e2[~same]).all()
+
+
+@pytest.mark.parametrize("path", PATHS)
+@pytest.mark.parametrize("alpha", [1.0, 0.5, 0.0])
+def test_apply_end_to_end(alpha, path):
+    binding.select_path(path)
+    w = small("cfg5", 3001)
+    lq = dev_matrix(w["lq"], "f32")
+    args = [torch.from_numpy(w[k]).cuda() for k in ("centroids", "gamma", "beta")]
+    out, a = cat_apply(lq, *args, alpha=alpha)
+    o_out, o_a = oracle.apply(w["lq"], w["centroids"], w["gamma"], w["beta"], alpha=alpha)
+    _, d1, d2 = oracle.assign(w["lq"], w["centroids"].astype(np.float64), want_distances=True)
+    check_assignments(a.cpu().numpy(), o_a, d1, d2, "cfg5 apply")
+    ok = a.cpu().numpy() == o_a
+    check_values(host_matrix(out)[ok], o_out[ok], RTOL["f32"], f"cfg5 corrected alpha={alpha}")
+    if alpha == 0.0:
+        assert (out == lq).all()
+
+
+def test_apply_bf16_rows():
+    w = small("cfg4", 900)
+    K, D = w["K"], w["D"]
+    rng = np.random.default_rng(5)
+    cent = w["lq"][rng.choice(900, K, replace=False)]
+    gamma = rng.uniform(0.8, 1.2, (K, D)).astype(np.float32)
+    beta = rng.standard_normal((K, D)).astype(np.float32) * 0.3
+    out, a = cat_apply(dev_matrix(w["lq"], "bf16"), *[torch.from_numpy(v).cuda() for v in (cent, gamma, beta)])
+    o_out, o_a = oracle.apply(w["lq"], cent, gamma, beta)
+    _, d1, d2 = oracle.assign(w["lq"], cent.astype(np.float64), want_distances=True)
+    check_assignments(a.cpu().numpy(), o_a, d1, d2, "bf16 apply")
+    ok = a.cpu().numpy() == o_a
+    assert out.dtype == torch.bfloat16
+    check_values(host_matrix(out)[ok], o_out[ok], RTOL["bf16"], "bf16 corrected")
+
+
+# ---------------------------------------------------------------------------
+# edge cases of the method
+# ---------------------------------------------------------------------------
+@pytest.mark.parametrize("path", PATHS)
+def test_ties_duplicates_and_midpoints_go_to_the_lowest_index(path):
+    binding.select_path(path)
+    rng = np.random.default_rng(3)
+    D = 40
+    base = np.round(rng.standard_normal((3, D)) * 4) / 2            # half-integers: exact arithmetic
+    cent = np.stack([base[0], base[1], base[1], base[2], base[0]])  # duplicates 1==2, 0==4
+    rows = [base[1], base[0], (base[1] + base[2]) / 2, (base[0] + base[2]) / 2]
+    rows += [base[i % 3] + np.round(rng.standard_normal(D) * 2) / 4 for i in range(60)]
+    lq = np.stack(rows).astype(np.float32)
+    a_o, d1, d2 = oracle.assign(lq, cent, want_distances=True)
+    assert a_o[:4].tolist() == [1, 0, 1, 0]
+    a_g, _, _ = cat_assign(torch.from_numpy(lq).cuda(), torch.from_numpy(cent.astype(np.float32)).cuda())
+    assert a_g.cpu().numpy().tolist() == a_o.tolist()     # exact ties included: no exemption here
+
+
+@pytest.mark.parametrize("path", PATHS)
+def test_empty_cluster_constant_channel_single_row(path):
+    binding.select_path(path)
+    w = small("cfg1", 500)
+    lq_h = w["lq"].copy()
+    fp_h = w["fp"].copy()
+    lq_h[:, 3] = np.float32(0.1)          # a channel that is constant everywhere
+    lq_h[499] = 50.0                      # one far row: a single-member cluster
+    lq_h[499, 3] = np.float32(0.1)
+    init = np.stack([lq_h[0], lq_h[1], np.full(64, -300.0, np.float32), lq_h[499]])  # cluster 2 stays empty
+    r = cat_fit(torch.from_numpy(lq_h).cuda(), torch.from_numpy(fp_h).cuda(), 4, iters=4,
+                init_centroids=torch.from_numpy(init).cuda())
+    o = oracle.fit(lq_h, fp_h, 4, iters=4, init_centroids=init.astype(np.float64))
+    assert o["counts"][2] == 0 and o["counts"][3] == 1
+    assert (r["assignments"].cpu().numpy() == o["assignments"]).all()
+    assert r["counts"].cpu().numpy().tolist() == o["counts"].tolist()
+    g, b, c = host_matrix(r["gamma"]), host_matrix(r["beta"]), host_matrix(r["centroids"])
+    assert (g[2] == 1.0).all() and (b[2] == 0.0).all() and (c[2] == -300.0).all()
+    assert (g[3] == 0.0).all() and (b[3] == fp_h[499].astype(np.float64)).all()
+    check_values(g, o["gamma"], 1e-4, "gamma")
+    check_values(b, o["beta"], 1e-4, "beta")
+    assert np.abs(g[:2, 3]).max() < 1e-4  # constant channel: gamma 0, beta = mean FP
+    check_values(c, o["centroids"], 1e-4, "centroids")
+
+
+@pytest.mark.parametrize("path", PATHS)
+@pytest.mark.parametrize("N,D,K", [(1, 1, 1), (7, 1, 7), (65, 3, 2), (200, 130, 1), (333, 257, 19)])
+def test_degenerate_shapes(N, D, K, path):
+    binding.select_path(path)
+    rng = np.random.default_rng(N * 1000 + D)
+    lq = rng.standard_normal((N, D)).astype(np.float32)
+    fp = (lq * 0.9 + 0.1 * rng.standard_normal((N, D))).astype(np.float32)
+    r = cat_fit(torch.from_numpy(lq).cuda(), torch.from_numpy(fp).cuda(), K, iters=3, seed=11)
+    o = oracle.fit(lq, fp, K, iters=3, seed=11)
+    _, d1, d2 = oracle.assign(lq, o["centroids"], want_distances=True)
+    check_assignments(r["assignments"].cpu().numpy(), o["assignments"], d1, d2, "degenerate")
+    check_values(host_matrix(r["centroids"]), o["centroids"], 1e-4, "centroids")
+    check_values(host_matrix(r["gamma"]), o["gamma"], 1e-4, "gamma")
+    check_values(host_matrix(r["beta"]), o["beta"], 1e-4, "beta")
+    out, a = cat_apply(torch.from_numpy(lq).cuda(), r["centroids"], r["gamma"], r["beta"], alpha=0.7)
+    o_out, o_a = oracle.apply(lq, host_matrix(r["centroids"]), host_matrix(r["gamma"]), host_matrix(r["beta"]), 0.7)
+    ok = a.cpu().numpy() == o_a
+    assert ok.mean() > 0.99
+    check_values(host_matrix(out)[ok], o_out[ok], 1e-4, "corrected")
+
+
+def test_device_errors_are_statuses_not_crashes():
+    lq = torch.zeros((64, 8), device="cuda")
+    with pytest.raises(binding.CatError) as e:
+        cat_fit(lq, lq.clone(), 4, iters=1, workspace=torch.empty(256, dtype=torch.uint8, device="cuda"))
+    assert e.value.status == 3
+    with pytest.raises(binding.CatError):
+        cat_apply(lq, lq[:4].contiguous(), lq[:4].contiguous(), lq[:4].contiguous(), out=lq)
