@@ -279,38 +279,35 @@ cat_status cat_fit(const void* lq, const void* fp, int64_t N, int64_t D, int32_t
     hipStream_t st = (hipStream_t)hip_stream;
     const size_t KD = (size_t)K * (size_t)D;
 
-    // init
-    if (init_centroids) {
-        CAT_TRY(launch_copy_words(init_centroids, w.cent[0], (int64_t)KD, st));
-    } else {
-        CAT_TRY(launch_init_indices(N, K, seed, w.idx, st));
-        CAT_TRY(launch_gather_rows(lq, dt, D, K, w.idx, w.cent[0], st));
-    }
-
     const int path = g_path.load();
-    int cur = 0;
     const bool fused = tile_supports(TILE_LLOYD, D, K, dt) && path != CAT_PATH_STREAM;
-    if (path == CAT_PATH_TILE && !tile_supports(TILE_ASSIGN, D, K, dt))
+    if (path == CAT_PATH_TILE && !fused)
         return set_error(CAT_ERR_UNSUPPORTED, "tile path forced but D=%lld K=%d dt=%d does not fit it", (long long)D,
                          (int)K, (int)dt);
-    if (fused) {
-        // one launch per Lloyd iteration: assignment with the centroid sums accumulated in the same pass
-        CAT_TRY(tile_lloyd(lq, dt, N, D, K, iters, w.cent[0], centroids, assignments, w.counts, inertia, w.rep, w.tile,
-                           st));
+    // init: the fused path iterates in place in the caller's `centroids`
+    float* c0 = fused ? centroids : w.cent[0];
+    if (init_centroids) {
+        CAT_TRY(launch_copy_words(init_centroids, c0, (int64_t)KD, st));
     } else {
+        CAT_TRY(launch_init_indices(N, K, seed, w.idx, st));
+        CAT_TRY(launch_gather_rows(lq, dt, D, K, w.idx, c0, st));
+    }
+    if (fused) {
+        // one assignment launch per Lloyd iteration; only the rows that change cluster touch the sums
+        CAT_TRY(tile_lloyd(lq, dt, N, D, K, iters, centroids, w.acc, assignments, w.counts, inertia, w.rep, w.tile, st));
+    } else {
+        int cur = 0;
         for (int32_t t = 0; t < iters; t++) {
             CAT_TRY(step_assign(lq, dt, N, D, K, w.cent[cur], assignments, w.counts, inertia ? w.inertia : nullptr,
                                 nullptr, w.tile, st));
-            if (inertia)
-                CAT_TRY(launch_copy_words(w.inertia, inertia + t, 2, st));
+            if (inertia) CAT_TRY(launch_copy_words(w.inertia, inertia + t, 2, st));
             CAT_TRY(step_update(lq, dt, assignments, N, D, K, w.counts, w.cent[cur], w.cent[cur ^ 1], w.acc, st));
             cur ^= 1;
         }
         // final assignment against the final centroids
         CAT_TRY(step_assign(lq, dt, N, D, K, w.cent[cur], assignments, w.counts, inertia ? w.inertia : nullptr, w.rep,
                             w.tile, st));
-        if (inertia)
-            CAT_TRY(launch_copy_words(w.inertia, inertia + iters, 2, st));
+        if (inertia) CAT_TRY(launch_copy_words(w.inertia, inertia + iters, 2, st));
         CAT_TRY(launch_copy_words(w.cent[cur], centroids, (int64_t)KD, st));
     }
     // affine fit on that partition, shifted by the centroids

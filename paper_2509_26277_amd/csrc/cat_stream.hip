@@ -240,31 +240,32 @@ cat_status launch_count_rep(const int32_t* assign, int64_t N, int32_t K, int32_t
 // ---------------------------------------------------------------------------------
 // segmented sums.  grid = (row blocks, channel slices, cluster chunks).  A workgroup
 // owns a [rows x slice] panel; each wave walks whole rows of the panel, so a row's
-// cluster id is wave-uniform and the 64 lanes touch 64 different channels: the LDS
-// adds never collide inside a wave.  Short fp32 runs in LDS, merged into global
-// doubles with one atomic per (cluster, channel) per workgroup.
+// cluster id is wave-uniform and the 64 lanes touch 64 different channels.  The
+// panel accumulates in LDS doubles (on gfx950 the LDS f64 add runs ~20x faster than
+// the f32 one) and is merged into the global doubles with one atomic per touched
+// (cluster, channel) cell per workgroup.
 // ---------------------------------------------------------------------------------
-constexpr int kSegWaves = 4;
-constexpr int kSegRows = 512;  // rows per workgroup panel
+constexpr int kSegWaves = 8;
+constexpr int kSegRows = 1024;  // rows per workgroup panel
 
 template <typename T, int NQ>
 __global__ __launch_bounds__(kSegWaves * kWave) void k_segsum(
     const T* __restrict__ lq, const T* __restrict__ fp, const int32_t* __restrict__ assign, int64_t N, int64_t D,
     int32_t K, int32_t KC, int32_t SW, const float* __restrict__ pivx, const float* __restrict__ pivy,
     double* __restrict__ acc) {
-    extern __shared__ float s_mem[];
-    float* s_acc = s_mem;                              // NQ x KC x SW
-    float* s_px = s_mem + (size_t)NQ * KC * SW;        // KC x SW (NQ == 4 only)
+    extern __shared__ double s_mem[];
+    double* s_acc = s_mem;                                       // NQ x KC x SW
+    float* s_px = (float*)(s_mem + (size_t)NQ * KC * SW);         // KC x SW (NQ == 4 only)
     float* s_py = s_px + (size_t)KC * SW;
     const int lane = threadIdx.x & (kWave - 1);
-    const int wave = threadIdx.x / kWave;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
     const int64_t row0 = (int64_t)blockIdx.x * kSegRows;
     const int64_t ch0 = (int64_t)blockIdx.y * SW;
     const int k0 = blockIdx.z * KC;
     const int kc = (K - k0) < KC ? (K - k0) : KC;
     const int cells = KC * SW;
 
-    for (int i = threadIdx.x; i < NQ * cells; i += blockDim.x) s_acc[i] = 0.f;
+    for (int i = threadIdx.x; i < NQ * cells; i += blockDim.x) s_acc[i] = 0.0;
     if (NQ == 4) {
         for (int i = threadIdx.x; i < cells; i += blockDim.x) {
             int k = i / SW, c = i - k * SW;
@@ -281,19 +282,20 @@ __global__ __launch_bounds__(kSegWaves * kWave) void k_segsum(
         if (a < 0 || a >= kc) continue;  // other chunk, or an out-of-range label
         const T* x = lq + row * D + ch0;
         const T* y = (NQ == 4) ? fp + row * D + ch0 : nullptr;
-        float* sa = s_acc + (size_t)a * SW;
+        double* sa = s_acc + (size_t)a * SW;
         for (int c = lane; c < SW; c += kWave) {
             if (ch0 + c >= D) break;
             float xv = ld_elem(x + c);
             if (NQ == 1) {
-                atomicAdd(sa + c, xv);
+                atomicAdd(sa + c, (double)xv);
             } else {
+                // the shifts keep the raw second moments close to the centred ones
                 float xs = xv - s_px[a * SW + c];
                 float ys = ld_elem(y + c) - s_py[a * SW + c];
-                atomicAdd(sa + c, xs);
-                atomicAdd(sa + cells + c, ys);
-                atomicAdd(sa + 2 * cells + c, xs * xs);
-                atomicAdd(sa + 3 * cells + c, xs * ys);
+                atomicAdd(sa + c, (double)xs);
+                atomicAdd(sa + cells + c, (double)ys);
+                atomicAdd(sa + 2 * cells + c, (double)xs * (double)xs);
+                atomicAdd(sa + 3 * cells + c, (double)xs * (double)ys);
             }
         }
     }
@@ -303,17 +305,17 @@ __global__ __launch_bounds__(kSegWaves * kWave) void k_segsum(
         int q = i / cells;
         int r = i - q * cells;
         int k = r / SW, c = r - k * SW;
-        float v = s_acc[i];
-        if (k < kc && ch0 + c < D && v != 0.f) atomicAdd(acc + q * KD + (int64_t)(k0 + k) * D + ch0 + c, (double)v);
+        double v = s_acc[i];
+        if (k < kc && ch0 + c < D && v != 0.0) atomicAdd(acc + q * KD + (int64_t)(k0 + k) * D + ch0 + c, v);
     }
 }
 
 cat_status launch_segsum(int nq, const void* lq, const void* fp, cat_dtype dt, const int32_t* assign,
                          int64_t N, int64_t D, int32_t K, const float* pivx, const float* pivy,
                          double* acc, hipStream_t st) {
-    // LDS floats per (cluster, channel): the accumulators, plus two pivots for the statistics
-    const int per_cell = (nq == 4) ? 6 : 1;
-    const int budget = 96 * 1024 / 4;  // floats
+    // LDS bytes per (cluster, channel): the double accumulators, plus two float shifts for the statistics
+    const int per_cell = (nq == 4) ? 40 : 8;
+    const int budget = 128 * 1024;
     int SW = 256;
     while (SW > 64 && ((int64_t)SW / 2 >= D || (int64_t)K * SW * per_cell > budget)) SW /= 2;
     int KC = budget / (SW * per_cell);
@@ -321,7 +323,7 @@ cat_status launch_segsum(int nq, const void* lq, const void* fp, cat_dtype dt, c
     if (KC < 1) return set_error(CAT_ERR_UNSUPPORTED, "segsum: no LDS tiling for K=%d", K);
     dim3 grid((unsigned)((N + kSegRows - 1) / kSegRows), (unsigned)((D + SW - 1) / SW), (unsigned)((K + KC - 1) / KC));
     dim3 block(kSegWaves * kWave);
-    size_t lds = (size_t)KC * SW * per_cell * sizeof(float);
+    size_t lds = (size_t)KC * SW * per_cell;
 #define CAT_SEG(T, NQ_)                                                                                          \
     do {                                                                                                         \
         CAT_HIP_TRY(hipFuncSetAttribute((const void*)k_segsum<T, NQ_>, hipFuncAttributeMaxDynamicSharedMemorySize, \

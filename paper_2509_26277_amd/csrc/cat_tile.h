@@ -8,7 +8,9 @@ enum TileMode { TILE_ASSIGN = 0, TILE_LLOYD = 1, TILE_APPLY = 2 };
 
 // Device scratch of the tile kernels, carved from the caller's workspace.
 struct TileWs {
-    void* base = nullptr;
+    uint16_t* packA = nullptr;  // centroids as bf16 (hi, lo) in MFMA operand order
+    float* cnorm = nullptr;     // K16 squared centroid norms (padding clusters: huge)
+    float* cent = nullptr;      // K x D fp32 working centroids (cat_assign / cat_apply copy theirs here)
     size_t bytes = 0;
 };
 
@@ -24,10 +26,11 @@ cat_status tile_assign(const void* lq, cat_dtype dt, int64_t N, int64_t D, int32
                        int32_t* assign, int32_t* counts, double* inertia, unsigned long long* rep,
                        const float* gamma, const float* beta, void* corrected, const TileWs& ws, hipStream_t st);
 
-// `iters` fused Lloyd iterations from cent0 plus the final assignment: writes the final
-// centroids, assignments, counts (K), inertia (iters + 1, nullable) and rep (K).
+// `iters` Lloyd iterations from cent0 plus the final assignment.  cent_io holds the initial
+// centroids on entry and the final ones on return; sums is 2 x K x D doubles of scratch.
+// Writes assignments, counts (K), inertia (iters + 1, nullable) and rep (K).
 cat_status tile_lloyd(const void* lq, cat_dtype dt, int64_t N, int64_t D, int32_t K, int32_t iters,
-                      const float* cent0, float* cent_out, int32_t* assign, int32_t* counts, double* inertia,
+                      float* cent_io, double* sums, int32_t* assign, int32_t* counts, double* inertia,
                       unsigned long long* rep, const TileWs& ws, hipStream_t st);
 
 }  // namespace cat

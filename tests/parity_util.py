@@ -28,13 +28,31 @@ def f32_round(a):
     return np.asarray(a, dtype=np.float64).astype(np.float32).astype(np.float64)
 
 
-def check_values(got, want, rtol, what):
-    """|got - want| <= rtol * max(|want|, rms(want)) element-wise."""
+def beta_scale(lq, fp, assignments, K, gamma):
+    """Magnitude of the two terms beta is the difference of: |mean FP| + |gamma * mean LQ| per
+    (cluster, channel).  beta = mean FP - gamma * mean LQ cancels, so a gamma that is within its
+    own relative tolerance moves beta by rtol * |gamma * mean LQ|: that is beta's error scale."""
+    lq = np.asarray(lq, dtype=np.float64)
+    fp = np.asarray(fp, dtype=np.float64)
+    D = lq.shape[1]
+    out = np.zeros((K, D))
+    for k in range(K):
+        m = assignments == k
+        if m.any():
+            out[k] = np.abs(fp[m].mean(axis=0)) + np.abs(gamma[k] * lq[m].mean(axis=0))
+    return out
+
+
+def check_values(got, want, rtol, what, scale=None):
+    """|got - want| <= rtol * max(|want|, rms(want)[, scale]) element-wise."""
     got = np.asarray(got, dtype=np.float64)
     want = np.asarray(want, dtype=np.float64)
     assert got.shape == want.shape, (what, got.shape, want.shape)
     rms = float(np.sqrt(np.mean(want * want))) if want.size else 0.0
-    bound = rtol * np.maximum(np.abs(want), rms) + 1e-30
+    bound = np.maximum(np.abs(want), rms)
+    if scale is not None:
+        bound = np.maximum(bound, scale)
+    bound = rtol * bound + 1e-30
     err = np.abs(got - want)
     worst = np.unravel_index(np.argmax(err / bound), err.shape) if err.size else None
     assert (err <= bound).all(), (

@@ -14,7 +14,7 @@ import oracle
 from paper_2509_26277_amd import binding, workloads
 from paper_2509_26277_amd import cat_apply, cat_assign, cat_fit, cat_stats, cat_update
 
-from parity_util import (RTOL, check_assignments, check_values, dev_matrix, f32_round, host_matrix)
+from parity_util import (RTOL, beta_scale, check_assignments, check_values, dev_matrix, f32_round, host_matrix)
 
 pytestmark = pytest.mark.gpu
 
@@ -63,7 +63,7 @@ def test_assign_step(name, n, path):
     a_g, counts, inertia = cat_assign(dev_matrix(w["lq"], w["dtype"]), torch.from_numpy(cent.astype(np.float32)).cuda())
     check_assignments(a_g.cpu().numpy(), a_o, d1, d2, f"{name} assign")
     assert counts.cpu().numpy().tolist() == np.bincount(a_g.cpu().numpy(), minlength=K).tolist()
-    assert inertia.item() == pytest.approx(d1.sum(), rel=1e-5)
+    assert inertia.item() == pytest.approx(d1.sum(), rel=1e-4)
 
 
 @pytest.mark.parametrize("name,n", SMALL_FIT)
@@ -84,7 +84,7 @@ def test_update_and_stats_steps(name, n):
         g_g, b_g, n2 = cat_stats(lq, fp, a_dev, K, centroids=hint)
         assert n2.cpu().numpy().tolist() == n_o.tolist()
         check_values(host_matrix(g_g), g_o, RTOL[dt], f"{name} gamma")
-        check_values(host_matrix(b_g), b_o, RTOL[dt], f"{name} beta")
+        check_values(host_matrix(b_g), b_o, RTOL[dt], f"{name} beta", beta_scale(w["lq"], w["fp"], a, K, g_o))
 
 
 # ---------------------------------------------------------------------------
@@ -105,8 +105,9 @@ def test_fit_end_to_end(name, n, path):
     assert r["counts"].cpu().numpy().tolist() == np.bincount(a_g, minlength=K).tolist()
     check_values(host_matrix(r["centroids"]), o["centroids"], RTOL[dt], f"{name} centroids")
     check_values(host_matrix(r["gamma"]), o["gamma"], RTOL[dt], f"{name} gamma")
-    check_values(host_matrix(r["beta"]), o["beta"], RTOL[dt], f"{name} beta")
-    np.testing.assert_allclose(r["inertia"].cpu().numpy(), o["inertia"], rtol=1e-5)
+    check_values(host_matrix(r["beta"]), o["beta"], RTOL[dt], f"{name} beta",
+                 beta_scale(w["lq"], w["fp"], o["assignments"], K, o["gamma"]))
+    np.testing.assert_allclose(r["inertia"].cpu().numpy(), o["inertia"], rtol=1e-4)
     # fit <-> apply: inference on the fitting rows reproduces the partition
     out, a2 = cat_apply(lq, r["centroids"], r["gamma"], r["beta"])
     same = (a2.cpu().numpy() == a_g)
@@ -186,7 +187,7 @@ def test_empty_cluster_constant_channel_single_row(path):
     assert (g[2] == 1.0).all() and (b[2] == 0.0).all() and (c[2] == -300.0).all()
     assert (g[3] == 0.0).all() and (b[3] == fp_h[499].astype(np.float64)).all()
     check_values(g, o["gamma"], 1e-4, "gamma")
-    check_values(b, o["beta"], 1e-4, "beta")
+    check_values(b, o["beta"], 1e-4, "beta", beta_scale(lq_h, fp_h, o["assignments"], 4, o["gamma"]))
     assert np.abs(g[:2, 3]).max() < 1e-4  # constant channel: gamma 0, beta = mean FP
     check_values(c, o["centroids"], 1e-4, "centroids")
 
@@ -204,7 +205,7 @@ def test_degenerate_shapes(N, D, K, path):
     check_assignments(r["assignments"].cpu().numpy(), o["assignments"], d1, d2, "degenerate")
     check_values(host_matrix(r["centroids"]), o["centroids"], 1e-4, "centroids")
     check_values(host_matrix(r["gamma"]), o["gamma"], 1e-4, "gamma")
-    check_values(host_matrix(r["beta"]), o["beta"], 1e-4, "beta")
+    check_values(host_matrix(r["beta"]), o["beta"], 1e-4, "beta", beta_scale(lq, fp, o["assignments"], K, o["gamma"]))
     out, a = cat_apply(torch.from_numpy(lq).cuda(), r["centroids"], r["gamma"], r["beta"], alpha=0.7)
     o_out, o_a = oracle.apply(lq, host_matrix(r["centroids"]), host_matrix(r["gamma"]), host_matrix(r["beta"]), 0.7)
     ok = a.cpu().numpy() == o_a
