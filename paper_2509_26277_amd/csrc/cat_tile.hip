@@ -129,27 +129,32 @@ struct ChunkRegs {
     uint32_t w[kRows][BF16 ? 1 : 2];
 };
 
+// Rows beyond N repeat the last valid row and channels beyond D read channel 0 (both valid
+// addresses), so every load is unconditional; the consumer masks the padding channels to zero
+// (masking here would make the loads wait where they are issued).  `tile` is wave-uniform:
+// the 16 row pointers live in scalar registers and each load is pointer + 32-bit lane offset.
 template <bool BF16>
-__device__ __forceinline__ void load_chunk(ChunkRegs<BF16>& r, const TileParams& p, int64_t tile, int chunk, int lane) {
-    const int64_t row0 = tile * kRows;  // wave-uniform: the row base stays in scalar registers
+__device__ __forceinline__ void load_chunk(ChunkRegs<BF16>& r, const TileParams& p, int tile, int chunk, int lane) {
+    const int64_t row0 = (int64_t)tile * kRows;
+    const int nv = (p.N - row0) < kRows ? (int)(p.N - row0) : kRows;
     if (BF16) {
+        const bf16_t* x = (const bf16_t*)p.lq + row0 * p.D;
         const int ch = chunk * kChunk + 2 * lane;
-        const bool ok = ch < p.D;
+        const int o = ch < p.D ? ch : 0;
 #pragma unroll
         for (int i = 0; i < kRows; i++) {
-            const int64_t row = row0 + i < p.N ? row0 + i : p.N - 1;
-            const bf16_t* x = (const bf16_t*)p.lq + row * p.D;
-            r.w[i][0] = ok ? *(const uint32_t*)(x + ch) : 0u;
+            r.w[i][0] = *(const uint32_t*)(x + o);
+            if (i + 1 < nv) x += p.D;
         }
     } else {
+        const float* x = (const float*)p.lq + row0 * p.D;
         const int ch0 = chunk * kChunk + lane, ch1 = ch0 + 64;
-        const bool ok0 = ch0 < p.D, ok1 = ch1 < p.D;
+        const int o0 = ch0 < p.D ? ch0 : 0, o1 = ch1 < p.D ? ch1 : 0;
 #pragma unroll
         for (int i = 0; i < kRows; i++) {
-            const int64_t row = row0 + i < p.N ? row0 + i : p.N - 1;
-            const float* x = (const float*)p.lq + row * p.D;
-            r.w[i][0] = ok0 ? __float_as_uint(x[ch0]) : 0u;
-            r.w[i][1] = ok1 ? __float_as_uint(x[ch1]) : 0u;
+            r.w[i][0] = __float_as_uint(x[o0]);
+            r.w[i][1] = __float_as_uint(x[o1]);
+            if (i + 1 < nv) x += p.D;
         }
     }
 }
@@ -157,18 +162,22 @@ __device__ __forceinline__ void load_chunk(ChunkRegs<BF16>& r, const TileParams&
 // Stage one chunk and run its 4 MFMA steps against the resident centroids.
 template <int KT, int PASSES, bool BF16>
 __device__ __forceinline__ void contract_chunk(const ChunkRegs<BF16>& r, f32x4 (&acc)[KT], float (&nrm)[kRows],
-                                               const unsigned char* ldsA_chunk, uint32_t* stage, int lane) {
+                                               const unsigned char* ldsA_chunk, uint32_t* stage, int lane,
+                                               int chunk, int64_t D) {
     constexpr int P = PASSES == 1 ? 1 : 2;
     uint32_t* stage_lo = stage + kStagePlane;
+    // padding channels (>= D) were loaded from channel 0: mask them to zero
+    const int chb = chunk * kChunk + (BF16 ? 2 * lane : lane);
+    const uint32_t m0 = chb < D ? 0xFFFFFFFFu : 0u, m1 = chb + 64 < D ? 0xFFFFFFFFu : 0u;
 #pragma unroll
     for (int i = 0; i < kRows; i++) {
         if (BF16) {
-            uint32_t w = r.w[i][0];
+            uint32_t w = r.w[i][0] & m0;
             float x0 = lo_half(w), x1 = hi_half(w);
             nrm[i] = fmaf(x0, x0, fmaf(x1, x1, nrm[i]));
             stage[i * kStageStride + lane] = w;
         } else {
-            float x0 = __uint_as_float(r.w[i][0]), x1 = __uint_as_float(r.w[i][1]);
+            float x0 = __uint_as_float(r.w[i][0] & m0), x1 = __uint_as_float(r.w[i][BF16 ? 0 : 1] & m1);
             nrm[i] = fmaf(x0, x0, fmaf(x1, x1, nrm[i]));
             uint32_t h = pack_bf16(x0, x1);
             stage[i * kStageStride + lane] = h;
@@ -269,6 +278,109 @@ __device__ __forceinline__ void rank_rows(const TileParams& p, const f32x4 (&acc
     idx = i1;
 }
 
+// Per-tile finishing work of the streaming modes: rank, write, book-keep; resets acc / nrm.
+template <int KT, bool BF16, int MODE>
+__device__ __forceinline__ void finish_tile(const TileParams& p, unsigned char* smem, f32x4 (&acc)[KT],
+                                            float (&nrm)[kRows], int tile, int lane, float cmax, double& in_acc) {
+    const int n = lane & 15, q = lane >> 4;
+    const int64_t row0 = (int64_t)tile * kRows;
+    const float* s_cnorm = (const float*)(smem + p.off_cnorm);
+    const float xn2 = rowsum16(nrm, lane);
+    int idx;
+    float dmin;
+    rank_rows<KT, BF16>(p, acc, s_cnorm, xn2, cmax, row0, lane, idx, dmin);
+#pragma unroll
+    for (int t = 0; t < KT; t++) acc[t] = (f32x4){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int i = 0; i < kRows; i++) nrm[i] = 0.f;
+    const bool owner = q == 0 && row0 + n < p.N;
+
+    if (MODE == MODE_APPLY_REREAD) {
+        if (p.assign && owner) p.assign[row0 + n] = idx;
+        const int nv = (p.N - row0) < kRows ? (int)(p.N - row0) : kRows;
+        // 8 rows at a time: 24 independent loads per lane in flight
+#pragma unroll 1
+        for (int i0 = 0; i0 < kRows; i0 += 8) {
+            int a[8];
+#pragma unroll
+            for (int u = 0; u < 8; u++) a[u] = __builtin_amdgcn_readfirstlane(__shfl(idx, i0 + u, kWave));
+            if (BF16) {
+                for (int c2 = lane; 2 * c2 < p.D; c2 += kWave) {
+                    uint32_t w[8];
+                    f32x2 g[8], b[8];
+#pragma unroll
+                    for (int u = 0; u < 8; u++)
+                        if (i0 + u < nv) {
+                            w[u] = *((const uint32_t*)((const bf16_t*)p.lq + (row0 + i0 + u) * p.D) + c2);
+                            g[u] = *((const f32x2*)(p.gamma + (int64_t)a[u] * p.D) + c2);
+                            b[u] = *((const f32x2*)(p.beta + (int64_t)a[u] * p.D) + c2);
+                        }
+#pragma unroll
+                    for (int u = 0; u < 8; u++)
+                        if (i0 + u < nv)
+                            *((uint32_t*)((bf16_t*)p.out + (row0 + i0 + u) * p.D) + c2) =
+                                pack_bf16(fmaf(g[u].x, lo_half(w[u]), b[u].x), fmaf(g[u].y, hi_half(w[u]), b[u].y));
+                }
+            } else {
+                for (int ch = lane; ch < p.D; ch += kWave) {
+                    float x[8], g[8], b[8];
+#pragma unroll
+                    for (int u = 0; u < 8; u++)
+                        if (i0 + u < nv) {
+                            x[u] = ((const float*)p.lq + (row0 + i0 + u) * p.D)[ch];
+                            g[u] = (p.gamma + (int64_t)a[u] * p.D)[ch];
+                            b[u] = (p.beta + (int64_t)a[u] * p.D)[ch];
+                        }
+#pragma unroll
+                    for (int u = 0; u < 8; u++)
+                        if (i0 + u < nv)
+                            __builtin_nontemporal_store(fmaf(g[u], x[u], b[u]), (float*)p.out + (row0 + i0 + u) * p.D + ch);
+                }
+            }
+        }
+        return;
+    }
+
+    // assign / lloyd bookkeeping (lanes 0..15 own one row each)
+    int* s_hist = (int*)(smem + p.off_hist);
+    unsigned long long* s_rep = (unsigned long long*)(smem + p.off_rep);
+    int* s_misc = (int*)(smem + p.off_misc);
+    int prev = -1;
+    if (owner) {
+        if (p.delta_mode) prev = p.assign[row0 + n];
+        p.assign[row0 + n] = idx;
+        if (p.counts) atomicAdd(&s_hist[idx], 1);
+        if (p.rep) atomicMin(&s_rep[idx], (unsigned long long)(row0 + n));
+        in_acc += (double)dmin;
+    }
+    if (p.delta) {
+        const bool changed = owner && prev != idx;
+        bool ovf = false;
+        if (changed) {
+            int pos = atomicAdd(&s_misc[0], 1);
+            if (pos < kListCap) {
+                ((int64_t*)(smem + p.off_list))[pos] = row0 + n;
+                ((uint32_t*)(smem + p.off_list + (size_t)kListCap * 8))[pos] = ((uint32_t)(prev + 1) << 16) | (uint32_t)idx;
+            } else {
+                ovf = true;
+            }
+        }
+        unsigned long long om = __ballot(ovf);
+        while (om) {  // list full: this row goes straight to the global sums
+            const int r = __builtin_amdgcn_readfirstlane(__builtin_ctzll(om));
+            om &= om - 1;
+            const int nw = __builtin_amdgcn_readlane(idx, r), od = __builtin_amdgcn_readlane(prev, r);
+            const int64_t row = row0 + r;
+            for (int64_t ch = lane; ch < p.D; ch += kWave) {
+                double x = BF16 ? (double)bf16_to_f32(((const bf16_t*)p.lq)[row * p.D + ch])
+                                : (double)((const float*)p.lq)[row * p.D + ch];
+                atomicAdd(p.delta + (int64_t)nw * p.D + ch, x);
+                if (od >= 0) atomicAdd(p.delta + (int64_t)od * p.D + ch, -x);
+            }
+        }
+    }
+}
+
 // ---- the kernel ----------------------------------------------------------------------
 template <int KT, int PASSES, bool BF16, int MODE>
 __global__ __launch_bounds__(kMaxWaves * kWave) void k_tile(const TileParams p) {
@@ -301,13 +413,14 @@ __global__ __launch_bounds__(kMaxWaves * kWave) void k_tile(const TileParams p) 
     const float cmax = sqrtf(cmax2);
 
     double in_acc = 0.0;
-    const int64_t tstride = (int64_t)gridDim.x * p.waves;
-    int64_t tile = (int64_t)blockIdx.x * p.waves + wave;
+    const int ntiles = (int)p.ntiles;
+    const int tstride = (int)gridDim.x * p.waves;
+    const int tile0 = __builtin_amdgcn_readfirstlane((int)blockIdx.x * p.waves + wave);
 
     if (MODE == MODE_APPLY_RETAIN) {
         // the 16 rows stay in registers between ranking and the affine map
-        for (; tile < p.ntiles; tile += tstride) {
-            const int64_t row0 = tile * kRows;
+        for (int tile = tile0; tile < ntiles; tile += tstride) {
+            const int64_t row0 = (int64_t)tile * kRows;
             ChunkRegs<false> xr[kRetainCols / 2];
 #pragma unroll
             for (int c = 0; c < kRetainCols / 2; c++)
@@ -321,25 +434,26 @@ __global__ __launch_bounds__(kMaxWaves * kWave) void k_tile(const TileParams p) 
 #pragma unroll
             for (int c = 0; c < kRetainCols / 2; c++)
                 if (c < p.nchunks)
-                    contract_chunk<KT, PASSES, false>(xr[c], acc, nrm, smem + (size_t)c * 4 * KT * P * 1024, stage, lane);
+                    contract_chunk<KT, PASSES, false>(xr[c], acc, nrm, smem + (size_t)c * 4 * KT * P * 1024, stage, lane, c,
+                                                      p.D);
             const float xn2 = rowsum16(nrm, lane);
             int idx;
             float dmin;
             rank_rows<KT, false>(p, acc, s_cnorm, xn2, cmax, row0, lane, idx, dmin);
             if (p.assign && q == 0 && row0 + n < p.N) p.assign[row0 + n] = idx;
-            float* out = (float*)p.out;
+            float* out = (float*)p.out + row0 * p.D;
 #pragma unroll
             for (int i = 0; i < kRows; i++) {
                 const int a = __builtin_amdgcn_readlane(idx, i);
                 if (row0 + i < p.N) {
                     const float* g = p.gamma + (int64_t)a * p.D;
                     const float* b = p.beta + (int64_t)a * p.D;
-                    float* o = out + (row0 + i) * p.D;
+                    float* o = out + (int64_t)i * p.D;
 #pragma unroll
                     for (int c = 0; c < kRetainCols / 2; c++)
 #pragma unroll
                         for (int h = 0; h < 2; h++) {
-                            const int64_t ch = (int64_t)c * kChunk + 64 * h + lane;
+                            const int ch = c * kChunk + 64 * h + lane;
                             if (c < p.nchunks && ch < p.D)
                                 __builtin_nontemporal_store(fmaf(g[ch], __uint_as_float(xr[c].w[i][h]), b[ch]), o + ch);
                         }
@@ -349,93 +463,46 @@ __global__ __launch_bounds__(kMaxWaves * kWave) void k_tile(const TileParams p) 
         return;
     }
 
-    // streaming modes: chunks are prefetched one ahead, across tile boundaries
-    ChunkRegs<BF16> cur, nxt;
-    if (tile < p.ntiles) load_chunk<BF16>(cur, p, tile, 0, lane);
-    for (; tile < p.ntiles; tile += tstride) {
-        const int64_t row0 = tile * kRows;
-        f32x4 acc[KT];
-        float nrm[kRows];
+    // streaming modes: a three-buffer register pipeline keeps two chunks of loads in flight
+    // while a third is contracted; the (tile, chunk) cursors run across tile boundaries
+    f32x4 acc[KT];
+    float nrm[kRows];
 #pragma unroll
-        for (int t = 0; t < KT; t++) acc[t] = (f32x4){0.f, 0.f, 0.f, 0.f};
+    for (int t = 0; t < KT; t++) acc[t] = (f32x4){0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-        for (int i = 0; i < kRows; i++) nrm[i] = 0.f;
-        for (int c = 0; c < p.nchunks; c++) {
-            if (c + 1 < p.nchunks)
-                load_chunk<BF16>(nxt, p, tile, c + 1, lane);
-            else if (tile + tstride < p.ntiles)
-                load_chunk<BF16>(nxt, p, tile + tstride, 0, lane);
-            contract_chunk<KT, PASSES, BF16>(cur, acc, nrm, smem + (size_t)c * 4 * KT * P * 1024, stage, lane);
-            cur = nxt;
-        }
-        const float xn2 = rowsum16(nrm, lane);
-        int idx;
-        float dmin;
-        rank_rows<KT, BF16>(p, acc, s_cnorm, xn2, cmax, row0, lane, idx, dmin);
-        const bool owner = q == 0 && row0 + n < p.N;
-
-        if (MODE == MODE_APPLY_REREAD) {
-            if (p.assign && owner) p.assign[row0 + n] = idx;
-#pragma unroll 1
-            for (int i = 0; i < kRows; i++) {
-                const int a = __builtin_amdgcn_readfirstlane(__shfl(idx, i, kWave));
-                if (row0 + i >= p.N) break;
-                const float* g = p.gamma + (int64_t)a * p.D;
-                const float* b = p.beta + (int64_t)a * p.D;
-                if (BF16) {
-                    const uint32_t* x = (const uint32_t*)((const bf16_t*)p.lq + (row0 + i) * p.D);
-                    uint32_t* o = (uint32_t*)((bf16_t*)p.out + (row0 + i) * p.D);
-                    for (int64_t c2 = lane; 2 * c2 < p.D; c2 += kWave) {
-                        uint32_t w = x[c2];
-                        float v0 = fmaf(g[2 * c2], lo_half(w), b[2 * c2]);
-                        float v1 = fmaf(g[2 * c2 + 1], hi_half(w), b[2 * c2 + 1]);
-                        o[c2] = pack_bf16(v0, v1);
-                    }
-                } else {
-                    const float* x = (const float*)p.lq + (row0 + i) * p.D;
-                    float* o = (float*)p.out + (row0 + i) * p.D;
-                    for (int64_t ch = lane; ch < p.D; ch += kWave) o[ch] = fmaf(g[ch], x[ch], b[ch]);
-                }
-            }
-            continue;
-        }
-
-        // assign / lloyd bookkeeping (lanes 0..15 own one row each)
-        int prev = -1;
-        if (owner) {
-            if (p.delta_mode) prev = p.assign[row0 + n];
-            p.assign[row0 + n] = idx;
-            if (p.counts) atomicAdd(&s_hist[idx], 1);
-            if (p.rep) atomicMin(&s_rep[idx], (unsigned long long)(row0 + n));
-            in_acc += (double)dmin;
-        }
-        if (p.delta) {
-            const bool changed = owner && prev != idx;
-            bool ovf = false;
-            if (changed) {
-                int pos = atomicAdd(&s_misc[0], 1);
-                if (pos < kListCap) {
-                    ((int64_t*)(smem + p.off_list))[pos] = row0 + n;
-                    ((uint32_t*)(smem + p.off_list + (size_t)kListCap * 8))[pos] = ((uint32_t)(prev + 1) << 16) | (uint32_t)idx;
-                } else {
-                    ovf = true;
-                }
-            }
-            unsigned long long om = __ballot(ovf);
-            while (om) {  // list full: this row goes straight to the global sums
-                const int r = __builtin_amdgcn_readfirstlane(__builtin_ctzll(om));
-                om &= om - 1;
-                const int nw = __builtin_amdgcn_readlane(idx, r), od = __builtin_amdgcn_readlane(prev, r);
-                const int64_t row = row0 + r;
-                for (int64_t ch = lane; ch < p.D; ch += kWave) {
-                    double x = BF16 ? (double)bf16_to_f32(((const bf16_t*)p.lq)[row * p.D + ch])
-                                    : (double)((const float*)p.lq)[row * p.D + ch];
-                    atomicAdd(p.delta + (int64_t)nw * p.D + ch, x);
-                    if (od >= 0) atomicAdd(p.delta + (int64_t)od * p.D + ch, -x);
-                }
-            }
-        }
+    for (int i = 0; i < kRows; i++) nrm[i] = 0.f;
+    int tl = tile0, cl = 0;  // load cursor
+    int tc = tile0, cc = 0;  // compute cursor
+    ChunkRegs<BF16> b0, b1, b2;
+#define CAT_ISSUE(buf)                            \
+    if (tl < ntiles) {                            \
+        load_chunk<BF16>(buf, p, tl, cl, lane);   \
+        if (++cl == p.nchunks) {                  \
+            cl = 0;                               \
+            tl += tstride;                        \
+        }                                         \
     }
+#define CAT_STEP(buf)                                                                                              \
+    contract_chunk<KT, PASSES, BF16>(buf, acc, nrm, smem + (size_t)cc * 4 * KT * P * 1024, stage, lane, cc, p.D); \
+    if (++cc == p.nchunks) {                                                                                       \
+        finish_tile<KT, BF16, MODE>(p, smem, acc, nrm, tc, lane, cmax, in_acc);                                    \
+        cc = 0;                                                                                                    \
+        tc += tstride;                                                                                             \
+    }
+    CAT_ISSUE(b0)
+    CAT_ISSUE(b1)
+    while (tc < ntiles) {
+        CAT_ISSUE(b2)
+        CAT_STEP(b0)
+        if (tc >= ntiles) break;
+        CAT_ISSUE(b0)
+        CAT_STEP(b1)
+        if (tc >= ntiles) break;
+        CAT_ISSUE(b1)
+        CAT_STEP(b2)
+    }
+#undef CAT_ISSUE
+#undef CAT_STEP
 
     if (MODE != MODE_ASSIGN) return;
 
@@ -506,11 +573,14 @@ __global__ __launch_bounds__(kMaxWaves * kWave) void k_tile(const TileParams p) 
 // ---- centroid preparation: (sums -> centroids), split to bf16 (hi, lo), operand order ----
 // One workgroup per cluster slot k in [0, K16).  With `base` given: S = base + delta is
 // folded back into base, delta is cleared, centroid = S / count (kept if the cluster is
-// empty).  Then the row is split and scattered into packA, and its squared norm stored.
+// empty).  Then the row is split and scattered into packA, and its squared norm stored.  Last,
+// the outputs of the following pass are reset: counts (after its value was used), the objective
+// slot and the first-row table.
 template <bool BF16IN>
-__global__ __launch_bounds__(256) void k_tile_prep(float* cent, double* base, double* delta, const int32_t* counts,
+__global__ __launch_bounds__(256) void k_tile_prep(float* cent, double* base, double* delta, int32_t* counts,
                                                    int64_t D, int32_t K, int32_t KT, int32_t P, int32_t nchunks,
-                                                   uint16_t* packA, float* cnorm) {
+                                                   uint16_t* packA, float* cnorm, double* inertia_slot,
+                                                   unsigned long long* rep) {
     __shared__ double s_red[256];
     const int k = blockIdx.x;
     const int t = k >> 4, m = k & 15;
@@ -557,7 +627,15 @@ __global__ __launch_bounds__(256) void k_tile_prep(float* cent, double* base, do
         if ((int)threadIdx.x < o) s_red[threadIdx.x] += s_red[threadIdx.x + o];
         __syncthreads();
     }
-    if (threadIdx.x == 0) cnorm[k] = k < K ? (float)s_red[0] : kPadNorm;
+    if (threadIdx.x == 0) {
+        cnorm[k] = k < K ? (float)s_red[0] : kPadNorm;
+        // outputs the following pass accumulates into (the count was read above, before the barriers)
+        if (k < K) {
+            if (counts) counts[k] = 0;
+            if (rep) rep[k] = ~0ull;
+        }
+        if (k == 0 && inertia_slot) *inertia_slot = 0.0;
+    }
 }
 
 // ---- host side ----------------------------------------------------------------------------
@@ -576,7 +654,7 @@ static TileCfg tile_config(TileMode mode, int64_t D, int32_t K, cat_dtype dt) {
     int KT = 1;
     while (KT * 16 < K16) KT *= 2;
     if (KT > 16) return c;
-    if (D > 65536) return c;
+    if (D > 65536) return c;  // also bounds the fp32 accumulation term of the re-rank threshold
     const int nchunks = (int)((D + kChunk - 1) / kChunk);
     const bool bf16 = dt == CAT_BF16;
     const bool lists = mode == TILE_LLOYD;
@@ -607,7 +685,7 @@ static TileCfg tile_config(TileMode mode, int64_t D, int32_t K, cat_dtype dt) {
             t.planes = planes;
             t.ldsA = (uint32_t)ldsA;
             t.lds_total = off;
-            if (mode == TILE_APPLY) t.mode = (!bf16 && D <= 64 * kRetainCols) ? MODE_APPLY_RETAIN : MODE_APPLY_REREAD;
+            if (mode == TILE_APPLY) t.mode = (!bf16 && D <= 64 * kRetainCols && KT <= 8) ? MODE_APPLY_RETAIN : MODE_APPLY_REREAD;
             return t;
         }
     }
@@ -642,15 +720,16 @@ TileWs tile_carve(void* base, int64_t D, int32_t K, cat_dtype dt) {
     return w;
 }
 
-static cat_status launch_prep(cat_dtype dt, float* cent, double* base, double* delta, const int32_t* counts, int64_t D,
-                              int32_t K, const TileCfg& c, const TileWs& ws, hipStream_t st) {
+static cat_status launch_prep(cat_dtype dt, float* cent, double* base, double* delta, int32_t* counts, int64_t D,
+                              int32_t K, const TileCfg& c, const TileWs& ws, double* inertia_slot,
+                              unsigned long long* rep, hipStream_t st) {
     dim3 grid(c.KT * 16), block(256);
     if (dt == CAT_BF16)
         hipLaunchKernelGGL(k_tile_prep<true>, grid, block, 0, st, cent, base, delta, counts, D, K, c.KT, c.P, c.nchunks,
-                           ws.packA, ws.cnorm);
+                           ws.packA, ws.cnorm, inertia_slot, rep);
     else
         hipLaunchKernelGGL(k_tile_prep<false>, grid, block, 0, st, cent, base, delta, counts, D, K, c.KT, c.P,
-                           c.nchunks, ws.packA, ws.cnorm);
+                           c.nchunks, ws.packA, ws.cnorm, inertia_slot, rep);
     CAT_LAUNCH_CHECK("k_tile_prep");
     return CAT_OK;
 }
@@ -740,7 +819,7 @@ cat_status tile_assign(const void* lq, cat_dtype dt, int64_t N, int64_t D, int32
     if (!c.ok) return set_error(CAT_ERR_UNSUPPORTED, "tile kernels do not fit D=%lld K=%d", (long long)D, (int)K);
     cat_status s = launch_copy_words(cent, ws.cent, (int64_t)K * D, st);
     if (s != CAT_OK) return s;
-    s = launch_prep(dt, ws.cent, nullptr, nullptr, nullptr, D, K, c, ws, st);
+    s = launch_prep(dt, ws.cent, nullptr, nullptr, nullptr, D, K, c, ws, nullptr, nullptr, st);
     if (s != CAT_OK) return s;
     TileParams p = base_params(lq, N, D, K, c, ws, dt);
     p.cent = ws.cent;
@@ -773,24 +852,15 @@ cat_status tile_lloyd(const void* lq, cat_dtype dt, int64_t N, int64_t D, int32_
     p.assign = assign;
     p.counts = counts;
     for (int32_t t = 0; t <= iters; t++) {
-        // centroids of this pass: the initial ones, or the running sums over the counts of the last pass
-        if (t == 0)
-            CAT_T(launch_prep(dt, cent_io, nullptr, nullptr, nullptr, D, K, c, ws, st));
-        else
-            CAT_T(launch_prep(dt, cent_io, base, delta, counts, D, K, c, ws, st));
-        CAT_T(launch_fill_zero(counts, (size_t)K * sizeof(int32_t), st));
-        if (inertia) CAT_T(launch_fill_zero(inertia + t, sizeof(double), st));
+        const bool last = t == iters;
+        // centroids of this pass: the initial ones, or the running sums over the counts of the last pass;
+        // the same launch resets what this pass accumulates into
+        CAT_T(launch_prep(dt, cent_io, t ? base : nullptr, t ? delta : nullptr, counts, D, K, c, ws,
+                          inertia ? inertia + t : nullptr, last ? rep : nullptr, st));
         p.inertia = inertia ? inertia + t : nullptr;
-        p.rep = nullptr;
-        p.delta = nullptr;
-        p.delta_mode = 0;
-        if (t == iters) {  // final pass: the partition that is returned
-            CAT_T(launch_fill_u64(rep, K, ~0ull, st));
-            p.rep = rep;
-        } else if (t > 0) {
-            p.delta = delta;
-            p.delta_mode = 1;
-        }
+        p.rep = last ? rep : nullptr;  // the final pass describes the partition that is returned
+        p.delta = (t > 0 && !last) ? delta : nullptr;
+        p.delta_mode = p.delta ? 1 : 0;
         CAT_T(launch_tile(p, c, dt, st));
         if (t == 0 && iters > 0) {  // first full sums: one segmented pass; later passes only move the changed rows
             CAT_T(launch_fill_zero(sums, 2 * KD * sizeof(double), st));
