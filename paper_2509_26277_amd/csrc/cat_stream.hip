@@ -246,20 +246,19 @@ cat_status launch_count_rep(const int32_t* assign, int64_t N, int32_t K, int32_t
 // (cluster, channel) cell per workgroup.
 // ---------------------------------------------------------------------------------
 constexpr int kSegWaves = 8;
-constexpr int kSegRows = 1024;  // rows per workgroup panel
 
 template <typename T, int NQ>
 __global__ __launch_bounds__(kSegWaves * kWave) void k_segsum(
     const T* __restrict__ lq, const T* __restrict__ fp, const int32_t* __restrict__ assign, int64_t N, int64_t D,
-    int32_t K, int32_t KC, int32_t SW, const float* __restrict__ pivx, const float* __restrict__ pivy,
-    double* __restrict__ acc) {
+    int32_t K, int32_t KC, int32_t SW, int32_t panel_rows, const float* __restrict__ pivx,
+    const float* __restrict__ pivy, double* __restrict__ acc) {
     extern __shared__ double s_mem[];
     double* s_acc = s_mem;                                       // NQ x KC x SW
     float* s_px = (float*)(s_mem + (size_t)NQ * KC * SW);         // KC x SW (NQ == 4 only)
     float* s_py = s_px + (size_t)KC * SW;
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
-    const int64_t row0 = (int64_t)blockIdx.x * kSegRows;
+    const int64_t row0 = (int64_t)blockIdx.x * panel_rows;
     const int64_t ch0 = (int64_t)blockIdx.y * SW;
     const int k0 = blockIdx.z * KC;
     const int kc = (K - k0) < KC ? (K - k0) : KC;
@@ -276,27 +275,39 @@ __global__ __launch_bounds__(kSegWaves * kWave) void k_segsum(
     }
     __syncthreads();
 
-    const int64_t rend = (row0 + kSegRows < N) ? row0 + kSegRows : N;
-    for (int64_t row = row0 + wave; row < rend; row += kSegWaves) {
-        int a = __builtin_amdgcn_readfirstlane(assign[row]) - k0;
-        if (a < 0 || a >= kc) continue;  // other chunk, or an out-of-range label
-        const T* x = lq + row * D + ch0;
-        const T* y = (NQ == 4) ? fp + row * D + ch0 : nullptr;
-        double* sa = s_acc + (size_t)a * SW;
-        for (int c = lane; c < SW; c += kWave) {
-            if (ch0 + c >= D) break;
-            float xv = ld_elem(x + c);
-            if (NQ == 1) {
-                atomicAdd(sa + c, (double)xv);
-            } else {
-                // the shifts keep the raw second moments close to the centred ones
-                float xs = xv - s_px[a * SW + c];
-                float ys = ld_elem(y + c) - s_py[a * SW + c];
-                atomicAdd(sa + c, (double)xs);
-                atomicAdd(sa + cells + c, (double)ys);
-                atomicAdd(sa + 2 * cells + c, (double)xs * (double)xs);
-                atomicAdd(sa + 3 * cells + c, (double)xs * (double)ys);
-            }
+    const int64_t rend = (row0 + panel_rows < N) ? row0 + panel_rows : N;
+    constexpr int RB = 4;  // rows in flight per wave: all their loads are issued before the first add
+    for (int64_t rb = row0 + (int64_t)wave * RB; rb < rend; rb += (int64_t)kSegWaves * RB) {
+        int a[RB];
+#pragma unroll
+        for (int u = 0; u < RB; u++) {
+            int v = rb + u < rend ? __builtin_amdgcn_readfirstlane(assign[rb + u]) - k0 : -1;
+            a[u] = (v >= 0 && v < kc) ? v : -1;  // other chunk, past the end, or an out-of-range label
+        }
+        for (int c = lane; c < SW && ch0 + c < D; c += kWave) {
+            float xv[RB], yv[RB];
+#pragma unroll
+            for (int u = 0; u < RB; u++)
+                if (a[u] >= 0) {
+                    xv[u] = ld_elem(lq + (rb + u) * D + ch0 + c);
+                    if (NQ == 4) yv[u] = ld_elem(fp + (rb + u) * D + ch0 + c);
+                }
+#pragma unroll
+            for (int u = 0; u < RB; u++)
+                if (a[u] >= 0) {
+                    double* sa = s_acc + (size_t)a[u] * SW + c;
+                    if (NQ == 1) {
+                        atomicAdd(sa, (double)xv[u]);
+                    } else {
+                        // the shifts keep the raw second moments close to the centred ones
+                        float xs = xv[u] - s_px[a[u] * SW + c];
+                        float ys = yv[u] - s_py[a[u] * SW + c];
+                        atomicAdd(sa, (double)xs);
+                        atomicAdd(sa + cells, (double)ys);
+                        atomicAdd(sa + 2 * cells, (double)xs * (double)xs);
+                        atomicAdd(sa + 3 * cells, (double)xs * (double)ys);
+                    }
+                }
         }
     }
     __syncthreads();
@@ -313,15 +324,20 @@ __global__ __launch_bounds__(kSegWaves * kWave) void k_segsum(
 cat_status launch_segsum(int nq, const void* lq, const void* fp, cat_dtype dt, const int32_t* assign,
                          int64_t N, int64_t D, int32_t K, const float* pivx, const float* pivy,
                          double* acc, hipStream_t st) {
-    // LDS bytes per (cluster, channel): the double accumulators, plus two float shifts for the statistics
+    // LDS bytes per (cluster, channel): the double accumulators, plus two float shifts for the statistics.
+    // Narrow channel slices keep the merge traffic low: the global atomics of a launch total
+    // (row panels) x K x D x NQ, and the number of row panels shrinks with the slice width.
     const int per_cell = (nq == 4) ? 40 : 8;
-    const int budget = 128 * 1024;
-    int SW = 256;
-    while (SW > 64 && ((int64_t)SW / 2 >= D || (int64_t)K * SW * per_cell > budget)) SW /= 2;
+    const int budget = 64 * 1024;
+    const int SW = 64;
     int KC = budget / (SW * per_cell);
     if (KC > K) KC = K;
-    if (KC < 1) return set_error(CAT_ERR_UNSUPPORTED, "segsum: no LDS tiling for K=%d", K);
-    dim3 grid((unsigned)((N + kSegRows - 1) / kSegRows), (unsigned)((D + SW - 1) / SW), (unsigned)((K + KC - 1) / KC));
+    const int64_t slices = (D + SW - 1) / SW, kchunks = (K + KC - 1) / KC;
+    // about 1024 workgroups in all
+    int64_t panel_rows = (N * slices * kchunks + 1023) / 1024;
+    panel_rows = (panel_rows + 31) & ~(int64_t)31;
+    if (panel_rows < 256) panel_rows = 256;
+    dim3 grid((unsigned)((N + panel_rows - 1) / panel_rows), (unsigned)slices, (unsigned)kchunks);
     dim3 block(kSegWaves * kWave);
     size_t lds = (size_t)KC * SW * per_cell;
 #define CAT_SEG(T, NQ_)                                                                                          \
@@ -329,7 +345,7 @@ cat_status launch_segsum(int nq, const void* lq, const void* fp, cat_dtype dt, c
         CAT_HIP_TRY(hipFuncSetAttribute((const void*)k_segsum<T, NQ_>, hipFuncAttributeMaxDynamicSharedMemorySize, \
                                         (int)lds));                                                              \
         hipLaunchKernelGGL((k_segsum<T, NQ_>), grid, block, lds, st, (const T*)lq, (const T*)fp, assign, N, D, K, KC, \
-                           SW, pivx, pivy, acc);                                                                 \
+                           SW, (int32_t)panel_rows, pivx, pivy, acc);                                                                 \
     } while (0)
     if (dt == CAT_F32) {
         if (nq == 1) CAT_SEG(float, 1); else CAT_SEG(float, 4);

@@ -30,6 +30,7 @@ constexpr int kStageStride = 68;   // dwords per staged row: 64 + 4 pad, keeps d
 constexpr int kStagePlane = kRows * kStageStride;  // dwords
 constexpr int kMaxWaves = 8;
 constexpr int kListCap = 1024;     // changed rows a workgroup can defer per launch
+constexpr int kDirectRows = 8;     // up to this many deferred rows skip the LDS panel
 constexpr size_t kLdsLimit = 160 * 1024;
 constexpr float kPadNorm = 3.0e38f;
 
@@ -50,6 +51,7 @@ struct TileParams {
     unsigned long long* rep; // nullable
     double* delta;           // K x D, lloyd delta mode only
     int32_t delta_mode;      // 0: off, 1: rows carry a previous assignment
+    int32_t reverse;         // walk the tiles from the last to the first (see tile_lloyd)
     const float* gamma;      // apply
     const float* beta;
     void* out;
@@ -122,8 +124,8 @@ __device__ __forceinline__ double exact_dist(const void* lq, int64_t row, int64_
     return wave_sum(s);
 }
 
-// One chunk of 128 channels of the 16 rows, as loaded: f32 input: 2 dwords per row (channels
-// lane and lane + 64 of the chunk); bf16 input: 1 dword per row (channels 2 lane, 2 lane + 1).
+// One chunk of 128 channels of the 16 rows, as loaded: lane l holds channels 2 l and 2 l + 1 of the
+// chunk (f32 input: one 8-byte load per row, bf16 input: one 4-byte load per row).
 template <bool BF16>
 struct ChunkRegs {
     uint32_t w[kRows][BF16 ? 1 : 2];
@@ -135,7 +137,7 @@ struct ChunkRegs {
 // the 16 row pointers live in scalar registers and each load is pointer + 32-bit lane offset.
 template <bool BF16>
 __device__ __forceinline__ void load_chunk(ChunkRegs<BF16>& r, const TileParams& p, int tile, int chunk, int lane) {
-    const int64_t row0 = (int64_t)tile * kRows;
+    const int64_t row0 = (int64_t)(p.reverse ? (int)p.ntiles - 1 - tile : tile) * kRows;
     const int nv = (p.N - row0) < kRows ? (int)(p.N - row0) : kRows;
     if (BF16) {
         const bf16_t* x = (const bf16_t*)p.lq + row0 * p.D;
@@ -148,12 +150,13 @@ __device__ __forceinline__ void load_chunk(ChunkRegs<BF16>& r, const TileParams&
         }
     } else {
         const float* x = (const float*)p.lq + row0 * p.D;
-        const int ch0 = chunk * kChunk + lane, ch1 = ch0 + 64;
-        const int o0 = ch0 < p.D ? ch0 : 0, o1 = ch1 < p.D ? ch1 : 0;
+        const int ch = chunk * kChunk + 2 * lane;
+        const int o = ch < p.D ? ch : 0;  // D is even: a pair is valid or padding as a whole
 #pragma unroll
         for (int i = 0; i < kRows; i++) {
-            r.w[i][0] = __float_as_uint(x[o0]);
-            r.w[i][1] = __float_as_uint(x[o1]);
+            const f32x2 v = *(const f32x2*)(x + o);
+            r.w[i][0] = __float_as_uint(v.x);
+            r.w[i][1] = __float_as_uint(v.y);
             if (i + 1 < nv) x += p.D;
         }
     }
@@ -167,8 +170,7 @@ __device__ __forceinline__ void contract_chunk(const ChunkRegs<BF16>& r, f32x4 (
     constexpr int P = PASSES == 1 ? 1 : 2;
     uint32_t* stage_lo = stage + kStagePlane;
     // padding channels (>= D) were loaded from channel 0: mask them to zero
-    const int chb = chunk * kChunk + (BF16 ? 2 * lane : lane);
-    const uint32_t m0 = chb < D ? 0xFFFFFFFFu : 0u, m1 = chb + 64 < D ? 0xFFFFFFFFu : 0u;
+    const uint32_t m0 = chunk * kChunk + 2 * lane < D ? 0xFFFFFFFFu : 0u;
 #pragma unroll
     for (int i = 0; i < kRows; i++) {
         if (BF16) {
@@ -177,7 +179,7 @@ __device__ __forceinline__ void contract_chunk(const ChunkRegs<BF16>& r, f32x4 (
             nrm[i] = fmaf(x0, x0, fmaf(x1, x1, nrm[i]));
             stage[i * kStageStride + lane] = w;
         } else {
-            float x0 = __uint_as_float(r.w[i][0] & m0), x1 = __uint_as_float(r.w[i][BF16 ? 0 : 1] & m1);
+            float x0 = __uint_as_float(r.w[i][0] & m0), x1 = __uint_as_float(r.w[i][BF16 ? 0 : 1] & m0);
             nrm[i] = fmaf(x0, x0, fmaf(x1, x1, nrm[i]));
             uint32_t h = pack_bf16(x0, x1);
             stage[i * kStageStride + lane] = h;
@@ -283,7 +285,7 @@ template <int KT, bool BF16, int MODE>
 __device__ __forceinline__ void finish_tile(const TileParams& p, unsigned char* smem, f32x4 (&acc)[KT],
                                             float (&nrm)[kRows], int tile, int lane, float cmax, double& in_acc) {
     const int n = lane & 15, q = lane >> 4;
-    const int64_t row0 = (int64_t)tile * kRows;
+    const int64_t row0 = (int64_t)(p.reverse ? (int)p.ntiles - 1 - tile : tile) * kRows;
     const float* s_cnorm = (const float*)(smem + p.off_cnorm);
     const float xn2 = rowsum16(nrm, lane);
     int idx;
@@ -395,6 +397,25 @@ __global__ __launch_bounds__(kMaxWaves * kWave) void k_tile(const TileParams p) 
     int* s_misc = (int*)(smem + p.off_misc);  // [0] list count, [2..] doubles for the objective
     uint32_t* stage = (uint32_t*)(smem + p.off_stage) + (size_t)wave * p.stage_planes * kStagePlane;
 
+    const int ntiles = (int)p.ntiles;
+    const int tstride = (int)gridDim.x * p.waves;
+    const int tile0 = __builtin_amdgcn_readfirstlane((int)blockIdx.x * p.waves + wave);
+    // streaming modes: the first two chunks are requested before the prologue touches LDS
+    int tl = tile0, cl = 0;  // load cursor
+    ChunkRegs<BF16> b0, b1, b2;
+#define CAT_ISSUE(buf)                            \
+    if (tl < ntiles) {                            \
+        load_chunk<BF16>(buf, p, tl, cl, lane);   \
+        if (++cl == p.nchunks) {                  \
+            cl = 0;                               \
+            tl += tstride;                        \
+        }                                         \
+    }
+    if (MODE != MODE_APPLY_RETAIN) {
+        CAT_ISSUE(b0)
+        CAT_ISSUE(b1)
+    }
+
     // prologue: centroids (operand order) and their norms into LDS
     {
         const u32x4* src = (const u32x4*)p.packA;
@@ -413,14 +434,11 @@ __global__ __launch_bounds__(kMaxWaves * kWave) void k_tile(const TileParams p) 
     const float cmax = sqrtf(cmax2);
 
     double in_acc = 0.0;
-    const int ntiles = (int)p.ntiles;
-    const int tstride = (int)gridDim.x * p.waves;
-    const int tile0 = __builtin_amdgcn_readfirstlane((int)blockIdx.x * p.waves + wave);
 
     if (MODE == MODE_APPLY_RETAIN) {
         // the 16 rows stay in registers between ranking and the affine map
         for (int tile = tile0; tile < ntiles; tile += tstride) {
-            const int64_t row0 = (int64_t)tile * kRows;
+            const int64_t row0 = (int64_t)(p.reverse ? ntiles - 1 - tile : tile) * kRows;
             ChunkRegs<false> xr[kRetainCols / 2];
 #pragma unroll
             for (int c = 0; c < kRetainCols / 2; c++)
@@ -450,13 +468,16 @@ __global__ __launch_bounds__(kMaxWaves * kWave) void k_tile(const TileParams p) 
                     const float* b = p.beta + (int64_t)a * p.D;
                     float* o = out + (int64_t)i * p.D;
 #pragma unroll
-                    for (int c = 0; c < kRetainCols / 2; c++)
-#pragma unroll
-                        for (int h = 0; h < 2; h++) {
-                            const int ch = c * kChunk + 64 * h + lane;
-                            if (c < p.nchunks && ch < p.D)
-                                __builtin_nontemporal_store(fmaf(g[ch], __uint_as_float(xr[c].w[i][h]), b[ch]), o + ch);
+                    for (int c = 0; c < kRetainCols / 2; c++) {
+                        const int ch = c * kChunk + 2 * lane;
+                        if (c < p.nchunks && ch < p.D) {
+                            const f32x2 gv = *(const f32x2*)(g + ch), bv = *(const f32x2*)(b + ch);
+                            f32x2 ov;
+                            ov.x = fmaf(gv.x, __uint_as_float(xr[c].w[i][0]), bv.x);
+                            ov.y = fmaf(gv.y, __uint_as_float(xr[c].w[i][1]), bv.y);
+                            __builtin_nontemporal_store(ov, (f32x2*)(o + ch));
                         }
+                    }
                 }
             }
         }
@@ -471,17 +492,7 @@ __global__ __launch_bounds__(kMaxWaves * kWave) void k_tile(const TileParams p) 
     for (int t = 0; t < KT; t++) acc[t] = (f32x4){0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int i = 0; i < kRows; i++) nrm[i] = 0.f;
-    int tl = tile0, cl = 0;  // load cursor
     int tc = tile0, cc = 0;  // compute cursor
-    ChunkRegs<BF16> b0, b1, b2;
-#define CAT_ISSUE(buf)                            \
-    if (tl < ntiles) {                            \
-        load_chunk<BF16>(buf, p, tl, cl, lane);   \
-        if (++cl == p.nchunks) {                  \
-            cl = 0;                               \
-            tl += tstride;                        \
-        }                                         \
-    }
 #define CAT_STEP(buf)                                                                                              \
     contract_chunk<KT, PASSES, BF16>(buf, acc, nrm, smem + (size_t)cc * 4 * KT * P * 1024, stage, lane, cc, p.D); \
     if (++cc == p.nchunks) {                                                                                       \
@@ -489,8 +500,6 @@ __global__ __launch_bounds__(kMaxWaves * kWave) void k_tile(const TileParams p) 
         cc = 0;                                                                                                    \
         tc += tstride;                                                                                             \
     }
-    CAT_ISSUE(b0)
-    CAT_ISSUE(b1)
     while (tc < ntiles) {
         CAT_ISSUE(b2)
         CAT_STEP(b0)
@@ -533,15 +542,29 @@ __global__ __launch_bounds__(kMaxWaves * kWave) void k_tile(const TileParams p) 
     // panel width: everything below the norm table (operand + staging) is free now
     int CW = (int)((p.off_cnorm / 8 / p.K) & ~63u);
     if (CW > 1024) CW = 1024;
-    if (CW == 0) {  // no room for even a 64-channel panel: straight to the global sums
+    if (cnt <= kDirectRows || CW == 0) {
+        // a handful of rows (the usual case once Lloyd has nearly converged), or no room for a
+        // panel: one wave per row, all loads first, then straight to the global sums
         for (int e = wave; e < cnt; e += p.waves) {
             const int64_t row = l_row[e];
             const int nw = (int)(l_on[e] & 0xFFFFu), od = (int)(l_on[e] >> 16) - 1;
-            for (int64_t ch = lane; ch < p.D; ch += kWave) {
-                double x = BF16 ? (double)bf16_to_f32(((const bf16_t*)p.lq)[row * p.D + ch])
-                                : (double)((const float*)p.lq)[row * p.D + ch];
-                atomicAdd(p.delta + (int64_t)nw * p.D + ch, x);
-                if (od >= 0) atomicAdd(p.delta + (int64_t)od * p.D + ch, -x);
+            for (int64_t c0 = 0; c0 < p.D; c0 += 16 * kWave) {
+                float x[16];
+#pragma unroll
+                for (int u = 0; u < 16; u++) {
+                    const int64_t ch = c0 + u * kWave + lane;
+                    x[u] = ch < p.D ? (BF16 ? bf16_to_f32(((const bf16_t*)p.lq)[row * p.D + ch])
+                                            : ((const float*)p.lq)[row * p.D + ch])
+                                    : 0.f;
+                }
+#pragma unroll
+                for (int u = 0; u < 16; u++) {
+                    const int64_t ch = c0 + u * kWave + lane;
+                    if (ch < p.D) {
+                        atomicAdd(p.delta + (int64_t)nw * p.D + ch, (double)x[u]);
+                        if (od >= 0) atomicAdd(p.delta + (int64_t)od * p.D + ch, -(double)x[u]);
+                    }
+                }
             }
         }
         return;
@@ -576,7 +599,6 @@ __global__ __launch_bounds__(kMaxWaves * kWave) void k_tile(const TileParams p) 
 // empty).  Then the row is split and scattered into packA, and its squared norm stored.  Last,
 // the outputs of the following pass are reset: counts (after its value was used), the objective
 // slot and the first-row table.
-template <bool BF16IN>
 __global__ __launch_bounds__(256) void k_tile_prep(float* cent, double* base, double* delta, int32_t* counts,
                                                    int64_t D, int32_t K, int32_t KT, int32_t P, int32_t nchunks,
                                                    uint16_t* packA, float* cnorm, double* inertia_slot,
@@ -600,17 +622,10 @@ __global__ __launch_bounds__(256) void k_tile_prep(float* cent, double* base, do
             c = cent[i];
         }
         nn += (double)c * (double)c;
-        // position of channel ch in the operand: chunk, then (f32 input) half h, step s, lane group g,
-        // dword i, with value index 2 i + h; (bf16 input) dword d = (ch % 128) / 2, h = ch & 1
+        // position of channel ch in the operand: chunk, MFMA step s, lane group g, then the 8
+        // consecutive channels a lane feeds to one MFMA
         const int cc = (int)(ch / kChunk), r = (int)(ch % kChunk);
-        int h, d;
-        if (BF16IN) {
-            h = r & 1;
-            d = r >> 1;
-        } else {
-            h = r >> 6;
-            d = r & 63;
-        }
+        const int h = r & 1, d = r >> 1;
         const int s = d >> 4, g = (d >> 2) & 3, ii = d & 3;
         const int lane = g * 16 + m;
         const uint32_t hw = pack_bf16(c, 0.f) & 0xFFFFu;
@@ -654,6 +669,7 @@ static TileCfg tile_config(TileMode mode, int64_t D, int32_t K, cat_dtype dt) {
     int KT = 1;
     while (KT * 16 < K16) KT *= 2;
     if (KT > 16) return c;
+    if (D & 1) return c;      // rows must keep the 8-byte alignment of the paired loads
     if (D > 65536) return c;  // also bounds the fp32 accumulation term of the re-rank threshold
     const int nchunks = (int)((D + kChunk - 1) / kChunk);
     const bool bf16 = dt == CAT_BF16;
@@ -724,12 +740,9 @@ static cat_status launch_prep(cat_dtype dt, float* cent, double* base, double* d
                               int32_t K, const TileCfg& c, const TileWs& ws, double* inertia_slot,
                               unsigned long long* rep, hipStream_t st) {
     dim3 grid(c.KT * 16), block(256);
-    if (dt == CAT_BF16)
-        hipLaunchKernelGGL(k_tile_prep<true>, grid, block, 0, st, cent, base, delta, counts, D, K, c.KT, c.P, c.nchunks,
-                           ws.packA, ws.cnorm, inertia_slot, rep);
-    else
-        hipLaunchKernelGGL(k_tile_prep<false>, grid, block, 0, st, cent, base, delta, counts, D, K, c.KT, c.P,
-                           c.nchunks, ws.packA, ws.cnorm, inertia_slot, rep);
+    (void)dt;
+    hipLaunchKernelGGL(k_tile_prep, grid, block, 0, st, cent, base, delta, counts, D, K, c.KT, c.P, c.nchunks, ws.packA,
+                       ws.cnorm, inertia_slot, rep);
     CAT_LAUNCH_CHECK("k_tile_prep");
     return CAT_OK;
 }
@@ -861,6 +874,9 @@ cat_status tile_lloyd(const void* lq, cat_dtype dt, int64_t N, int64_t D, int32_
         p.rep = last ? rep : nullptr;  // the final pass describes the partition that is returned
         p.delta = (t > 0 && !last) ? delta : nullptr;
         p.delta_mode = p.delta ? 1 : 0;
+        // alternate the scan direction: the rows a pass reads last are the ones most likely still in
+        // the memory-side cache when the next pass starts
+        p.reverse = t & 1;
         CAT_T(launch_tile(p, c, dt, st));
         if (t == 0 && iters > 0) {  // first full sums: one segmented pass; later passes only move the changed rows
             CAT_T(launch_fill_zero(sums, 2 * KD * sizeof(double), st));
