@@ -144,27 +144,31 @@ def main():
     cpu = None
     if not args.no_cpu:
         import oracle
-        probe = min(N, max(K, 1024))
+        probe = min(N, max(K, 4096))
         t = time.perf_counter()
         if fit_kind:
             oracle.fit(w["lq"][:probe], w["fp"][:probe], K, 1, seed=1)
         else:
             oracle.apply(w["lq"][:probe], w["centroids"], w["gamma"], w["beta"], 1.0)
-        per_row_pass = (time.perf_counter() - t) / (probe * (2 if fit_kind else 1))
-        it_s = 3 if fit_kind else 1
-        rows_s = int(min(N, max(K, 15.0 / max(per_row_pass, 1e-9) / (it_s + 1))))
-        t = time.perf_counter()
+        per_row_pass = (time.perf_counter() - t) / (probe * (3 if fit_kind else 1))
+        budget = 20.0  # seconds of oracle time
         if fit_kind:
+            # passes of a fit: iters + 1 assignments, iters updates (cheap), 2 for the affine fit
+            it_s = iters if per_row_pass * N * (iters + 3) <= budget else max(1, int(budget / (per_row_pass * N)) - 3)
+            rows_s = N if per_row_pass * N * (it_s + 3) <= 1.5 * budget else max(K, int(budget / (per_row_pass * (it_s + 3))))
+            t = time.perf_counter()
             oracle.fit(w["lq"][:rows_s], w["fp"][:rows_s], K, it_s, seed=w["seed"])
             sec = time.perf_counter() - t
             cpu = dict(value=rows_s * it_s / sec, unit="rows/s", cores=oracle.threads(), kind="oracle",
-                       sample=f"oracle.fit on the first {rows_s} rows, {it_s} Lloyd iterations + final assign + "
-                              f"affine fit, {sec:.1f} s; rows x iterations / whole time")
+                       sample=f"oracle.fit on {'all' if rows_s == N else 'the first'} {rows_s} rows, {it_s} Lloyd "
+                              f"iterations + final assign + affine fit, {sec:.1f} s; rows x iterations / whole time")
         else:
+            rows_s = int(min(N, max(K, budget / max(per_row_pass, 1e-12))))
+            t = time.perf_counter()
             oracle.apply(w["lq"][:rows_s], w["centroids"], w["gamma"], w["beta"], 1.0)
             sec = time.perf_counter() - t
             cpu = dict(value=rows_s * D * esize * 2 / sec / 1e9, unit="GB/s", cores=oracle.threads(), kind="oracle",
-                       sample=f"oracle.apply on the first {rows_s} rows, {sec:.1f} s")
+                       sample=f"oracle.apply on the first {rows_s} rows, {sec:.1f} s; bytes read + written / time")
 
     line = {
         "metric": metric, "value": value, "unit": unit, "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
