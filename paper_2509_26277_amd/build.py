@@ -9,12 +9,14 @@ LDS / L2 add instructions.
 import os
 import subprocess
 import sys
+import time
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _ROOT = os.path.dirname(_HERE)
 CSRC = os.path.join(_HERE, "csrc")
-SOURCES = ["cat_api.hip", "cat_stream.hip", "cat_tile.hip"]
-HEADERS = ["cat_common.h", "cat_tile.h"]
+SOURCES = ["cat_api.hip", "cat_stream.hip", "cat_tile.hip"] + [
+    f"cat_tile_k{kt}_{dt}.hip" for kt in (16, 8, 4, 2, 1) for dt in ("f32", "bf16")]
+HEADERS = ["cat_common.h", "cat_tile.h", "cat_tile_kernel.h"]
 OUT = os.path.join(_HERE, "libcat_hip.so")
 OBJ_DIR = os.path.join(_HERE, "_build")
 
@@ -42,6 +44,8 @@ def build(force=False, verbose=True):
             cmd = ["hipcc", "-c", *FLAGS, "-o", o, s]
             if verbose:
                 print(" ".join(cmd), flush=True)
+            while sum(p.poll() is None for _, p in procs) >= max(2, (os.cpu_count() or 4)):
+                time.sleep(0.2)
             procs.append((src, subprocess.Popen(cmd)))
     for src, p in procs:
         if p.wait() != 0:
