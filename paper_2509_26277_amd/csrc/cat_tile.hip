@@ -33,18 +33,17 @@ __global__ __launch_bounds__(256) void k_tile_prep(float* cent, double* base, do
             c = cent[i];
         }
         nn += (double)c * (double)c;
-        // position of channel ch in the operand: chunk, MFMA step s, lane group g, then the 8
-        // consecutive channels a lane feeds to one MFMA
+        // position of channel ch in the operand: chunk, MFMA step s (32 channels), lane group g, then
+        // the 8 consecutive channels j that lane (m, g) feeds to one MFMA
         const int cc = (int)(ch / kChunk), r = (int)(ch % kChunk);
-        const int h = r & 1, d = r >> 1;
-        const int s = d >> 4, g = (d >> 2) & 3, ii = d & 3;
+        const int s = r >> 5, g = (r >> 3) & 3, j = r & 7;
         const int lane = g * 16 + m;
         const uint32_t hw = pack_bf16(c, 0.f) & 0xFFFFu;
         const size_t blk = ((size_t)(cc * 4 + s) * KT + t) * P;
-        packA[(blk * 64 + lane) * 8 + 2 * ii + h] = (uint16_t)hw;
+        packA[(blk * 64 + lane) * 8 + j] = (uint16_t)hw;
         if (P == 2) {
             const uint32_t lw = pack_bf16(c - lo_half(hw), 0.f) & 0xFFFFu;
-            packA[((blk + 1) * 64 + lane) * 8 + 2 * ii + h] = (uint16_t)lw;
+            packA[((blk + 1) * 64 + lane) * 8 + j] = (uint16_t)lw;
         }
     }
     s_red[threadIdx.x] = nn;
@@ -74,23 +73,19 @@ static TileCfg tile_config(TileMode mode, int64_t D, int32_t K, cat_dtype dt) {
     int KT = 1;
     while (KT * 16 < K16) KT *= 2;
     if (KT > 16) return c;
-    if (D & 1) return c;      // rows must keep the 8-byte alignment of the paired loads
+    if (D % (dt == CAT_BF16 ? 8 : 4)) return c;  // rows must keep the 16-byte alignment of the operand loads
     if (D > 65536) return c;  // also bounds the fp32 accumulation term of the re-rank threshold
     const int nchunks = (int)((D + kChunk - 1) / kChunk);
-    const bool bf16 = dt == CAT_BF16;
     const bool lists = mode == TILE_LLOYD;
     // first choice: the whole operand resident in LDS (hi + lo parts, else hi only); otherwise
     // the chunked operand (two chunk buffers, 8 waves)
     for (int pass = 0; pass < 4; pass++) {
         const bool chunked = pass >= 2;
         const int P = (pass & 1) ? 1 : 2;
-        const int planes = (P == 2 && !bf16) ? 2 : 1;
         const size_t ldsA = chunked ? (size_t)2 * 4 * KT * P * 1024 : (size_t)nchunks * 4 * KT * P * 1024;
-        for (int waves = kMaxWaves; waves >= (chunked ? kMaxWaves : 4); waves -= 2) {
+        for (int waves = kMaxWaves; waves >= kMaxWaves; waves -= 2) {
             size_t off = ldsA;
             TileCfg t;
-            t.off_stage = up16(off);
-            off = t.off_stage + (size_t)waves * planes * kStagePlane * 4;
             t.off_cnorm = up16(off);
             off = t.off_cnorm + (size_t)KT * 16 * 4;
             t.off_hist = up16(off);
@@ -107,12 +102,11 @@ static TileCfg tile_config(TileMode mode, int64_t D, int32_t K, cat_dtype dt) {
             t.P = P;
             t.waves = waves;
             t.nchunks = nchunks;
-            t.planes = planes;
             t.chunked = chunked;
             t.ldsA = (uint32_t)ldsA;
             t.lds_total = off;
             if (mode == TILE_APPLY)
-                t.mode = (!bf16 && !chunked && D <= 64 * kRetainCols && KT <= 8) ? MODE_APPLY_RETAIN : MODE_APPLY_REREAD;
+                t.mode = MODE_APPLY;
             return t;
         }
     }
@@ -193,13 +187,11 @@ static TileParams base_params(const void* lq, int64_t N, int64_t D, int32_t K, c
     p.tau = split + 4.f * n_acc * 5.96e-8f;
     p.tau2 = 4.0e-7f;
     p.ldsA_bytes = c.ldsA;
-    p.off_stage = c.off_stage;
     p.off_cnorm = c.off_cnorm;
     p.off_hist = c.off_hist;
     p.off_rep = c.off_rep;
     p.off_list = c.off_list;
     p.off_misc = c.off_misc;
-    p.stage_planes = c.planes;
     return p;
 }
 

@@ -1,21 +1,26 @@
 // MFMA tile kernel of the CAT hot path for gfx950: device code, kernel template and its launcher.
-// Included by cat_tile.hip (host logic) and by the per-KT instantiation units cat_tile_kN.hip.
+// Included by cat_tile.hip (host logic) and by the instantiation units cat_tile_k<KT>_<dtype>.hip.
 //
-// One wavefront owns a tile of 16 rows.  The rows stream in with fully coalesced
-// dword loads (lane = channel), are split into bf16 (hi, lo) pairs and staged through
-// a small wave-private LDS buffer into the operand layout of
-// v_mfma_f32_16x16x32_bf16, and are contracted against the centroids, which sit in
-// LDS for the whole kernel, already split and packed in operand order.  The scores
+// One wavefront owns a tile of 16 rows.  Lane (n, g) = (lane & 15, lane >> 4) loads, with
+// 16-byte loads, 8 consecutive channels of row n per MFMA step -- which is exactly the
+// B-operand layout of v_mfma_f32_16x16x32_bf16, so nothing is staged or transposed: fp32
+// data is split in registers into bf16 (hi, lo) pairs, bf16 data is used as loaded.  The
+// A operand is the centroids, split and packed in operand order by k_tile_prep and held
+// in LDS (whole, or streamed through two buffers when it does not fit).  Clusters are
+// the M dimension and rows the N dimension, so a lane ends up with 4 KT cluster scores
+// of ONE row: the argmin is in-register plus two cross-lane steps.  The scores
 // -2 x.c + |c|^2 rank the centroids; a row whose two best scores are closer than the
 // error bound of the split arithmetic is re-ranked with direct-form double-precision
-// distances over the candidates inside that bound, so the result is the exact
-// nearest centroid (lowest index on ties).
+// distances over the candidates inside that bound, so the result is the exact nearest
+// centroid (lowest index on ties).
 //
 //   assign      writes assignments (+ counts, objective, first row of each cluster)
 //   lloyd       assign + the rows that changed cluster since the previous pass are
 //               added to / subtracted from the running per-cluster sums
 //   apply       assign + corrected = gamma[a] * x + beta[a] in the same pass
 #pragma once
+#include <type_traits>
+
 #include "cat_tile.h"
 
 namespace cat {
@@ -27,17 +32,14 @@ typedef __attribute__((ext_vector_type(4))) float f32x4;
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 
 constexpr int kRows = 16;          // rows per wave tile (the N of the 16x16x32 MFMA)
-constexpr int kChunk = 128;        // channels staged at a time (4 MFMA steps)
-constexpr int kStageStride = 68;   // dwords per staged row: 64 + 4 pad, keeps ds_read_b128 conflict-free
-constexpr int kStagePlane = kRows * kStageStride;  // dwords
+constexpr int kChunk = 128;        // channels per pipeline stage (4 MFMA steps of 32)
 constexpr int kMaxWaves = 8;
 constexpr int kListCap = 1024;     // changed rows a workgroup can defer per launch
 constexpr int kDirectRows = 8;     // up to this many deferred rows skip the LDS panel
 constexpr size_t kLdsLimit = 160 * 1024;
 constexpr float kPadNorm = 3.0e38f;
 
-enum { MODE_ASSIGN = 0, MODE_APPLY_RETAIN = 1, MODE_APPLY_REREAD = 2 };
-constexpr int kRetainCols = 8;     // retained inference: D <= 64 * kRetainCols
+enum { MODE_ASSIGN = 0, MODE_APPLY = 2 };
 
 struct TileParams {
     const void* lq;
@@ -58,7 +60,7 @@ struct TileParams {
     const float* beta;
     void* out;
     float tau, tau2;         // re-rank threshold T = tau |x| cmax + tau2 cmax^2
-    uint32_t ldsA_bytes, off_stage, off_cnorm, off_hist, off_rep, off_list, off_misc, stage_planes;
+    uint32_t ldsA_bytes, off_cnorm, off_hist, off_rep, off_list, off_misc;
 };
 
 // ---- small device helpers ---------------------------------------------------------
@@ -70,41 +72,6 @@ __device__ __forceinline__ float lo_half(uint32_t w) { return __uint_as_float(w 
 __device__ __forceinline__ float hi_half(uint32_t w) { return __uint_as_float(w & 0xFFFF0000u); }
 __device__ __forceinline__ float readlane_f(float v, int l) {
     return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), l));
-}
-
-// Row totals of 16 per-lane partials: lane l returns the sum over all 64 lanes of p[l & 15].
-__device__ __forceinline__ float rowsum16(const float (&p)[16], int lane) {
-    float a8[8], a4[4], a2[2];
-    {
-        const bool up = lane & 8;
-#pragma unroll
-        for (int j = 0; j < 8; j++) {
-            float keep = up ? p[j + 8] : p[j], send = up ? p[j] : p[j + 8];
-            a8[j] = keep + __shfl_xor(send, 8, kWave);
-        }
-    }
-    {
-        const bool up = lane & 4;
-#pragma unroll
-        for (int j = 0; j < 4; j++) {
-            float keep = up ? a8[j + 4] : a8[j], send = up ? a8[j] : a8[j + 4];
-            a4[j] = keep + __shfl_xor(send, 4, kWave);
-        }
-    }
-    {
-        const bool up = lane & 2;
-#pragma unroll
-        for (int j = 0; j < 2; j++) {
-            float keep = up ? a4[j + 2] : a4[j], send = up ? a4[j] : a4[j + 2];
-            a2[j] = keep + __shfl_xor(send, 2, kWave);
-        }
-    }
-    const bool up = lane & 1;
-    float keep = up ? a2[1] : a2[0], send = up ? a2[0] : a2[1];
-    float v = keep + __shfl_xor(send, 1, kWave);
-    v += __shfl_xor(v, 16, kWave);
-    v += __shfl_xor(v, 32, kWave);
-    return v;
 }
 
 template <bool BF16>
@@ -126,76 +93,81 @@ __device__ __forceinline__ double exact_dist(const void* lq, int64_t row, int64_
     return wave_sum(s);
 }
 
-// One chunk of 128 channels of the 16 rows, as loaded: lane l holds channels 2 l and 2 l + 1 of the
-// chunk (f32 input: one 8-byte load per row, bf16 input: one 4-byte load per row).
+// One chunk (128 channels) of the tile as loaded: per MFMA step s, lane (n, g) holds channels
+// 128 c + 32 s + 8 g .. + 7 of row n: two 16-byte loads (fp32) or one (bf16).
 template <bool BF16>
 struct ChunkRegs {
-    uint32_t w[kRows][BF16 ? 1 : 2];
+    u32x4 v[BF16 ? 4 : 8];
 };
 
-// Rows beyond N repeat the last valid row and channels beyond D read channel 0 (both valid
-// addresses), so every load is unconditional; the consumer masks the padding channels to zero
-// (masking here would make the loads wait where they are issued).  `tile` is wave-uniform:
-// the 16 row pointers live in scalar registers and each load is pointer + 32-bit lane offset.
+// Rows past N repeat the last row and channel groups past D read the start of the row (valid
+// addresses either way), so no load is conditional; the consumer masks the padding channels
+// (masking here would make the loads wait where they are issued).  D is a multiple of 4 (fp32)
+// or 8 (bf16): rows are 16-byte aligned and a 16-byte group is valid or padding as a whole.
 template <bool BF16>
 __device__ __forceinline__ void load_chunk(ChunkRegs<BF16>& r, const TileParams& p, int tile, int chunk, int lane) {
     const int64_t row0 = (int64_t)(p.reverse ? (int)p.ntiles - 1 - tile : tile) * kRows;
     const int nv = (p.N - row0) < kRows ? (int)(p.N - row0) : kRows;
+    const int n = lane & 15, g = lane >> 4;
+    const int rn = n < nv ? n : nv - 1;
+    const int ch = chunk * kChunk + 8 * g;
     if (BF16) {
-        const bf16_t* x = (const bf16_t*)p.lq + row0 * p.D;
-        const int ch = chunk * kChunk + 2 * lane;
-        const int o = ch < p.D ? ch : 0;
+        const bf16_t* x = (const bf16_t*)p.lq + (row0 + rn) * p.D;
 #pragma unroll
-        for (int i = 0; i < kRows; i++) {
-            r.w[i][0] = *(const uint32_t*)(x + o);
-            if (i + 1 < nv) x += p.D;
+        for (int s = 0; s < 4; s++) {
+            const int c = ch + 32 * s;
+            r.v[s] = *(const u32x4*)(x + (c < p.D ? c : 0));
         }
     } else {
-        const float* x = (const float*)p.lq + row0 * p.D;
-        const int ch = chunk * kChunk + 2 * lane;
-        const int o = ch < p.D ? ch : 0;  // D is even: a pair is valid or padding as a whole
+        const float* x = (const float*)p.lq + (row0 + rn) * p.D;
 #pragma unroll
-        for (int i = 0; i < kRows; i++) {
-            const f32x2 v = *(const f32x2*)(x + o);
-            r.w[i][0] = __float_as_uint(v.x);
-            r.w[i][1] = __float_as_uint(v.y);
-            if (i + 1 < nv) x += p.D;
+        for (int s = 0; s < 4; s++) {
+            const int c = ch + 32 * s;
+            r.v[2 * s] = *(const u32x4*)(x + (c < p.D ? c : 0));
+            r.v[2 * s + 1] = *(const u32x4*)(x + (c + 4 < p.D ? c + 4 : 0));
         }
     }
 }
 
-// Stage one chunk and run its 4 MFMA steps against the resident centroids.
+// The 4 MFMA steps of one chunk against the centroid operand in LDS.  nrm accumulates the
+// lane's share of |x|^2 of row n.
 template <int KT, int PASSES, bool BF16>
-__device__ __forceinline__ void contract_chunk(const ChunkRegs<BF16>& r, f32x4 (&acc)[KT], float (&nrm)[kRows],
-                                               const unsigned char* ldsA_chunk, uint32_t* stage, int lane,
-                                               int chunk, int64_t D) {
+__device__ __forceinline__ void contract_chunk(const ChunkRegs<BF16>& r, f32x4 (&acc)[KT], float& nrm,
+                                               const unsigned char* ldsA_chunk, int lane, int chunk, int64_t D) {
     constexpr int P = PASSES == 1 ? 1 : 2;
-    uint32_t* stage_lo = stage + kStagePlane;
-    // padding channels (>= D) were loaded from channel 0: mask them to zero
-    const uint32_t m0 = chunk * kChunk + 2 * lane < D ? 0xFFFFFFFFu : 0u;
-#pragma unroll
-    for (int i = 0; i < kRows; i++) {
-        if (BF16) {
-            uint32_t w = r.w[i][0] & m0;
-            float x0 = lo_half(w), x1 = hi_half(w);
-            nrm[i] = fmaf(x0, x0, fmaf(x1, x1, nrm[i]));
-            stage[i * kStageStride + lane] = w;
-        } else {
-            float x0 = __uint_as_float(r.w[i][0] & m0), x1 = __uint_as_float(r.w[i][BF16 ? 0 : 1] & m0);
-            nrm[i] = fmaf(x0, x0, fmaf(x1, x1, nrm[i]));
-            uint32_t h = pack_bf16(x0, x1);
-            stage[i * kStageStride + lane] = h;
-            if (PASSES == 3) stage_lo[i * kStageStride + lane] = pack_bf16(x0 - lo_half(h), x1 - hi_half(h));
-        }
-    }
-    __builtin_amdgcn_wave_barrier();
-    const int n = lane & 15, g = lane >> 4;
+    const int ch = chunk * kChunk + 8 * (lane >> 4);
 #pragma unroll
     for (int s = 0; s < 4; s++) {
-        const uint32_t* bp = stage + n * kStageStride + 16 * s + 4 * g;
-        bf16x8 bh = __builtin_bit_cast(bf16x8, *(const u32x4*)bp);
-        bf16x8 bl;
-        if (PASSES == 3 && !BF16) bl = __builtin_bit_cast(bf16x8, *(const u32x4*)(bp + kStagePlane));
+        const int c = ch + 32 * s;
+        bf16x8 bh, bl;
+        if (BF16) {
+            u32x4 w = r.v[s];
+            const uint32_t m = c < D ? 0xFFFFFFFFu : 0u;
+            w.x &= m; w.y &= m; w.z &= m; w.w &= m;
+#pragma unroll
+            for (int j = 0; j < 4; j++) {
+                const float x0 = lo_half(w[j]), x1 = hi_half(w[j]);
+                nrm = fmaf(x0, x0, fmaf(x1, x1, nrm));
+            }
+            bh = __builtin_bit_cast(bf16x8, w);
+        } else {
+            const uint32_t m0 = c < D ? 0xFFFFFFFFu : 0u, m1 = c + 4 < D ? 0xFFFFFFFFu : 0u;
+            float x[8];
+#pragma unroll
+            for (int j = 0; j < 4; j++) {
+                x[j] = __uint_as_float(r.v[2 * s][j] & m0);
+                x[4 + j] = __uint_as_float(r.v[2 * s + 1][j] & m1);
+            }
+            u32x4 h, l;
+#pragma unroll
+            for (int j = 0; j < 4; j++) {
+                nrm = fmaf(x[2 * j], x[2 * j], fmaf(x[2 * j + 1], x[2 * j + 1], nrm));
+                h[j] = pack_bf16(x[2 * j], x[2 * j + 1]);
+                if (PASSES == 3) l[j] = pack_bf16(x[2 * j] - lo_half(h[j]), x[2 * j + 1] - hi_half(h[j]));
+            }
+            bh = __builtin_bit_cast(bf16x8, h);
+            if (PASSES == 3) bl = __builtin_bit_cast(bf16x8, l);
+        }
 #pragma unroll
         for (int t = 0; t < KT; t++) {
             const unsigned char* ap = ldsA_chunk + (size_t)((s * KT + t) * P) * 1024 + lane * 16;
@@ -206,9 +178,10 @@ __device__ __forceinline__ void contract_chunk(const ChunkRegs<BF16>& r, f32x4 (
                 acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(al, bh, acc[t], 0, 0, 0);
                 if (!BF16) acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ah, bl, acc[t], 0, 0, 0);
             }
+            // keep at most four cluster tiles of operand reads in registers at a time
+            if (KT > 4 && (t & 3) == 3) __builtin_amdgcn_sched_barrier(0);
         }
     }
-    __builtin_amdgcn_wave_barrier();
 }
 
 // Rank the centroids of the 16 rows from the accumulated dot products; exact re-rank of
@@ -284,62 +257,94 @@ __device__ __forceinline__ void rank_rows(const TileParams& p, const f32x4 (&acc
 
 // Per-tile finishing work of the streaming modes: rank, write, book-keep; resets acc / nrm.
 template <int KT, bool BF16, int MODE>
-__device__ __forceinline__ void finish_tile(const TileParams& p, unsigned char* smem, f32x4 (&acc)[KT],
-                                            float (&nrm)[kRows], int tile, int lane, float cmax, double& in_acc) {
+__device__ __forceinline__ void finish_tile(const TileParams& p, unsigned char* smem, f32x4 (&acc)[KT], float& nrm,
+                                            int tile, int lane, float cmax, double& in_acc) {
     const int n = lane & 15, q = lane >> 4;
     const int64_t row0 = (int64_t)(p.reverse ? (int)p.ntiles - 1 - tile : tile) * kRows;
     const float* s_cnorm = (const float*)(smem + p.off_cnorm);
-    const float xn2 = rowsum16(nrm, lane);
+    float xn2 = nrm;
+    xn2 += __shfl_xor(xn2, 16, kWave);
+    xn2 += __shfl_xor(xn2, 32, kWave);
     int idx;
     float dmin;
     rank_rows<KT, BF16>(p, acc, s_cnorm, xn2, cmax, row0, lane, idx, dmin);
 #pragma unroll
     for (int t = 0; t < KT; t++) acc[t] = (f32x4){0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-    for (int i = 0; i < kRows; i++) nrm[i] = 0.f;
-    const bool owner = q == 0 && row0 + n < p.N;
+    nrm = 0.f;
+    const bool valid = row0 + n < p.N;
+    const bool owner = q == 0 && valid;
 
-    if (MODE == MODE_APPLY_REREAD) {
+    if (MODE == MODE_APPLY) {
+        // The affine map walks the 16 rows again, this time one row per instruction with the
+        // lanes side by side over the channels (16 bytes each): the row was fetched a moment ago and
+        // comes from L2, its cluster id is wave-uniform, so the gamma / beta rows are scalar-addressed
+        // and everything is coalesced.  Four rows are in flight at a time (24 independent 16-byte loads
+        // per lane for D <= 512).
         if (p.assign && owner) p.assign[row0 + n] = idx;
         const int nv = (p.N - row0) < kRows ? (int)(p.N - row0) : kRows;
-        // 8 rows at a time: 24 independent loads per lane in flight
+        constexpr int EPL = BF16 ? 8 : 4;  // elements per lane per load
+        typedef typename std::conditional<BF16, bf16_t, float>::type T;
 #pragma unroll 1
-        for (int i0 = 0; i0 < kRows; i0 += 8) {
-            int a[8];
+        for (int i0 = 0; i0 < kRows; i0 += 4) {
+            // row pointers are wave-uniform (scalar registers).  Rows past the end repeat the last row and
+            // channels past D repeat channel 0: those lanes recompute and store again exactly what the
+            // owning lanes store, so neither the loads nor the stores are conditional
+            const T* xr[4];
+            const float* gr[4];
+            const float* br[4];
+            T* orow[4];
 #pragma unroll
-            for (int u = 0; u < 8; u++) a[u] = __builtin_amdgcn_readfirstlane(__shfl(idx, i0 + u, kWave));
-            if (BF16) {
-                for (int c2 = lane; 2 * c2 < p.D; c2 += kWave) {
-                    uint32_t w[8];
-                    f32x2 g[8], b[8];
+            for (int u = 0; u < 4; u++) {
+                const int iu = i0 + u < nv ? i0 + u : nv - 1;
+                const int a = __builtin_amdgcn_readfirstlane(__shfl(idx, iu, kWave));
+                xr[u] = (const T*)p.lq + (row0 + iu) * p.D;
+                orow[u] = (T*)p.out + (row0 + iu) * p.D;
+                gr[u] = p.gamma + (int64_t)a * p.D;
+                br[u] = p.beta + (int64_t)a * p.D;
+            }
+#pragma unroll 1
+            for (int cb = 0; cb < p.D; cb += 2 * EPL * kWave) {
+                int o[2];
 #pragma unroll
-                    for (int u = 0; u < 8; u++)
-                        if (i0 + u < nv) {
-                            w[u] = *((const uint32_t*)((const bf16_t*)p.lq + (row0 + i0 + u) * p.D) + c2);
-                            g[u] = *((const f32x2*)(p.gamma + (int64_t)a[u] * p.D) + c2);
-                            b[u] = *((const f32x2*)(p.beta + (int64_t)a[u] * p.D) + c2);
-                        }
-#pragma unroll
-                    for (int u = 0; u < 8; u++)
-                        if (i0 + u < nv)
-                            *((uint32_t*)((bf16_t*)p.out + (row0 + i0 + u) * p.D) + c2) =
-                                pack_bf16(fmaf(g[u].x, lo_half(w[u]), b[u].x), fmaf(g[u].y, hi_half(w[u]), b[u].y));
+                for (int j = 0; j < 2; j++) {
+                    const int ch = cb + (j * kWave + lane) * EPL;
+                    o[j] = ch < p.D ? ch : 0;
                 }
-            } else {
-                for (int ch = lane; ch < p.D; ch += kWave) {
-                    float x[8], g[8], b[8];
+                u32x4 xv[4][2];
+                f32x4 gv[4][2][BF16 ? 2 : 1], bv[4][2][BF16 ? 2 : 1];
 #pragma unroll
-                    for (int u = 0; u < 8; u++)
-                        if (i0 + u < nv) {
-                            x[u] = ((const float*)p.lq + (row0 + i0 + u) * p.D)[ch];
-                            g[u] = (p.gamma + (int64_t)a[u] * p.D)[ch];
-                            b[u] = (p.beta + (int64_t)a[u] * p.D)[ch];
+                for (int u = 0; u < 4; u++)
+#pragma unroll
+                    for (int j = 0; j < 2; j++) {
+                        xv[u][j] = *(const u32x4*)(xr[u] + o[j]);
+                        gv[u][j][0] = *(const f32x4*)(gr[u] + o[j]);
+                        bv[u][j][0] = *(const f32x4*)(br[u] + o[j]);
+                        if (BF16) {
+                            gv[u][j][1] = *(const f32x4*)(gr[u] + o[j] + 4);
+                            bv[u][j][1] = *(const f32x4*)(br[u] + o[j] + 4);
                         }
+                    }
 #pragma unroll
-                    for (int u = 0; u < 8; u++)
-                        if (i0 + u < nv)
-                            __builtin_nontemporal_store(fmaf(g[u], x[u], b[u]), (float*)p.out + (row0 + i0 + u) * p.D + ch);
-                }
+                for (int u = 0; u < 4; u++)
+#pragma unroll
+                    for (int j = 0; j < 2; j++) {
+                        u32x4 r;
+                        if (BF16) {
+                            const f32x4 g0 = gv[u][j][0], g1 = gv[u][j][BF16 ? 1 : 0], b0 = bv[u][j][0], b1 = bv[u][j][BF16 ? 1 : 0];
+                            const u32x4 w = xv[u][j];
+                            r.x = pack_bf16(fmaf(g0.x, lo_half(w.x), b0.x), fmaf(g0.y, hi_half(w.x), b0.y));
+                            r.y = pack_bf16(fmaf(g0.z, lo_half(w.y), b0.z), fmaf(g0.w, hi_half(w.y), b0.w));
+                            r.z = pack_bf16(fmaf(g1.x, lo_half(w.z), b1.x), fmaf(g1.y, hi_half(w.z), b1.y));
+                            r.w = pack_bf16(fmaf(g1.z, lo_half(w.w), b1.z), fmaf(g1.w, hi_half(w.w), b1.w));
+                        } else {
+                            const f32x4 g = gv[u][j][0], b = bv[u][j][0];
+                            r.x = __float_as_uint(fmaf(g.x, __uint_as_float(xv[u][j].x), b.x));
+                            r.y = __float_as_uint(fmaf(g.y, __uint_as_float(xv[u][j].y), b.y));
+                            r.z = __float_as_uint(fmaf(g.z, __uint_as_float(xv[u][j].z), b.z));
+                            r.w = __float_as_uint(fmaf(g.w, __uint_as_float(xv[u][j].w), b.w));
+                        }
+                        __builtin_nontemporal_store(r, (u32x4*)(orow[u] + o[j]));
+                    }
             }
         }
         return;
@@ -390,19 +395,17 @@ template <int KT, int PASSES, bool BF16, int MODE, bool CA>
 __global__ __launch_bounds__(kMaxWaves * kWave) void k_tile(const TileParams p) {
     extern __shared__ __align__(16) unsigned char smem[];
     const int lane = threadIdx.x & (kWave - 1);
-    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);  // wave-uniform: keeps tile/row math scalar
-    const int n = lane & 15, q = lane >> 4;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);  // wave-uniform: keeps tile math scalar
     constexpr int P = PASSES == 1 ? 1 : 2;
     float* s_cnorm = (float*)(smem + p.off_cnorm);
     int* s_hist = (int*)(smem + p.off_hist);
     unsigned long long* s_rep = (unsigned long long*)(smem + p.off_rep);
     int* s_misc = (int*)(smem + p.off_misc);  // [0] list count, [2..] doubles for the objective
-    uint32_t* stage = (uint32_t*)(smem + p.off_stage) + (size_t)wave * p.stage_planes * kStagePlane;
 
     const int ntiles = (int)p.ntiles;
     const int tstride = (int)gridDim.x * p.waves;
     const int tile0 = __builtin_amdgcn_readfirstlane((int)blockIdx.x * p.waves + wave);
-    // streaming modes: the first two chunks are requested before the prologue touches LDS
+    // the first two chunks are requested before the prologue touches LDS
     int tl = tile0, cl = 0;  // load cursor
     ChunkRegs<BF16> b0, b1, b2;
 #define CAT_ISSUE(buf)                            \
@@ -413,10 +416,8 @@ __global__ __launch_bounds__(kMaxWaves * kWave) void k_tile(const TileParams p) 
             tl += tstride;                        \
         }                                         \
     }
-    if (MODE != MODE_APPLY_RETAIN) {
-        CAT_ISSUE(b0)
-        CAT_ISSUE(b1)
-    }
+    CAT_ISSUE(b0)
+    CAT_ISSUE(b1)
 
     // prologue: centroids (operand order) and their norms into LDS
     {
@@ -432,77 +433,29 @@ __global__ __launch_bounds__(kMaxWaves * kWave) void k_tile(const TileParams p) 
         }
         if (threadIdx.x == 0) s_misc[0] = 0;
     }
+    // largest centroid norm (every wave reduces the table for itself: no extra barrier)
+    float cm2 = 0.f;
+    for (int k = lane; k < p.K; k += kWave) cm2 = fmaxf(cm2, p.cnorm[k]);
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) cm2 = fmaxf(cm2, __shfl_xor(cm2, o, kWave));
+    const float cmax = sqrtf(cm2);
     __syncthreads();
-    float cmax2 = 0.f;
-    for (int k = 0; k < p.K; k++) cmax2 = fmaxf(cmax2, s_cnorm[k]);
-    const float cmax = sqrtf(cmax2);
 
     double in_acc = 0.0;
 
-    if (MODE == MODE_APPLY_RETAIN) {
-        // the 16 rows stay in registers between ranking and the affine map
-        for (int tile = tile0; tile < ntiles; tile += tstride) {
-            const int64_t row0 = (int64_t)(p.reverse ? ntiles - 1 - tile : tile) * kRows;
-            ChunkRegs<false> xr[kRetainCols / 2];
-#pragma unroll
-            for (int c = 0; c < kRetainCols / 2; c++)
-                if (c < p.nchunks) load_chunk<false>(xr[c], p, tile, c, lane);
-            f32x4 acc[KT];
-            float nrm[kRows];
-#pragma unroll
-            for (int t = 0; t < KT; t++) acc[t] = (f32x4){0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-            for (int i = 0; i < kRows; i++) nrm[i] = 0.f;
-#pragma unroll
-            for (int c = 0; c < kRetainCols / 2; c++)
-                if (c < p.nchunks)
-                    contract_chunk<KT, PASSES, false>(xr[c], acc, nrm, smem + (size_t)c * 4 * KT * P * 1024, stage, lane, c,
-                                                      p.D);
-            const float xn2 = rowsum16(nrm, lane);
-            int idx;
-            float dmin;
-            rank_rows<KT, false>(p, acc, s_cnorm, xn2, cmax, row0, lane, idx, dmin);
-            if (p.assign && q == 0 && row0 + n < p.N) p.assign[row0 + n] = idx;
-            float* out = (float*)p.out + row0 * p.D;
-#pragma unroll
-            for (int i = 0; i < kRows; i++) {
-                const int a = __builtin_amdgcn_readlane(idx, i);
-                if (row0 + i < p.N) {
-                    const float* g = p.gamma + (int64_t)a * p.D;
-                    const float* b = p.beta + (int64_t)a * p.D;
-                    float* o = out + (int64_t)i * p.D;
-#pragma unroll
-                    for (int c = 0; c < kRetainCols / 2; c++) {
-                        const int ch = c * kChunk + 2 * lane;
-                        if (c < p.nchunks && ch < p.D) {
-                            const f32x2 gv = *(const f32x2*)(g + ch), bv = *(const f32x2*)(b + ch);
-                            f32x2 ov;
-                            ov.x = fmaf(gv.x, __uint_as_float(xr[c].w[i][0]), bv.x);
-                            ov.y = fmaf(gv.y, __uint_as_float(xr[c].w[i][1]), bv.y);
-                            __builtin_nontemporal_store(ov, (f32x2*)(o + ch));
-                        }
-                    }
-                }
-            }
-        }
-        return;
-    }
-
-    // streaming modes: a three-buffer register pipeline keeps two chunks of loads in flight
+    // a three-buffer register pipeline keeps two chunks of loads in flight
     // while a third is contracted; the (tile, chunk) cursors run across tile boundaries
     f32x4 acc[KT];
-    float nrm[kRows];
+    float nrm = 0.f;
 #pragma unroll
     for (int t = 0; t < KT; t++) acc[t] = (f32x4){0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-    for (int i = 0; i < kRows; i++) nrm[i] = 0.f;
     int tc = tile0, cc = 0;  // compute cursor
-#define CAT_STEP(buf)                                                                                              \
-    contract_chunk<KT, PASSES, BF16>(buf, acc, nrm, smem + (size_t)cc * 4 * KT * P * 1024, stage, lane, cc, p.D); \
-    if (++cc == p.nchunks) {                                                                                       \
-        finish_tile<KT, BF16, MODE>(p, smem, acc, nrm, tc, lane, cmax, in_acc);                                    \
-        cc = 0;                                                                                                    \
-        tc += tstride;                                                                                             \
+#define CAT_STEP(buf)                                                                                          \
+    contract_chunk<KT, PASSES, BF16>(buf, acc, nrm, smem + (size_t)cc * 4 * KT * P * 1024, lane, cc, p.D);     \
+    if (++cc == p.nchunks) {                                                                                   \
+        finish_tile<KT, BF16, MODE>(p, smem, acc, nrm, tc, lane, cmax, in_acc);                                \
+        cc = 0;                                                                                                \
+        tc += tstride;                                                                                         \
     }
     if (CA) {
         // The centroid operand does not fit in LDS: it streams through two LDS buffers one
@@ -529,7 +482,7 @@ __global__ __launch_bounds__(kMaxWaves * kWave) void k_tile(const TileParams p) 
         }                                                                                                     \
         CAT_ISSUE(bufnext)                                                                                    \
         if (tc < ntiles) {                                                                                    \
-            contract_chunk<KT, PASSES, BF16>(bufcur, acc, nrm, smem + (size_t)(s & 1) * chunkA, stage, lane, cc, p.D); \
+            contract_chunk<KT, PASSES, BF16>(bufcur, acc, nrm, smem + (size_t)(s & 1) * chunkA, lane, cc, p.D); \
             if (++cc == p.nchunks) {                                                                          \
                 finish_tile<KT, BF16, MODE>(p, smem, acc, nrm, tc, lane, cmax, in_acc);                       \
                 cc = 0;                                                                                       \
@@ -574,7 +527,6 @@ __global__ __launch_bounds__(kMaxWaves * kWave) void k_tile(const TileParams p) 
 
     // workgroup epilogue: counts, first rows, objective
     double* s_in = (double*)(s_misc + 2);
-    if (lane == 0) s_in[wave] = 0.0;
     in_acc = wave_sum(in_acc);
     if (lane == 0) s_in[wave] = in_acc;
     __syncthreads();
@@ -596,7 +548,7 @@ __global__ __launch_bounds__(kMaxWaves * kWave) void k_tile(const TileParams p) 
     const int64_t* l_row = (const int64_t*)(smem + p.off_list);
     const uint32_t* l_on = (const uint32_t*)(smem + p.off_list + (size_t)kListCap * 8);
     double* S = (double*)smem;
-    // panel width: everything below the norm table (operand + staging) is free now
+    // panel width: everything below the norm table is free now
     int CW = (int)((p.off_cnorm / 8 / p.K) & ~63u);
     if (CW > 1024) CW = 1024;
     if (cnt <= kDirectRows || CW == 0) {
@@ -650,11 +602,12 @@ __global__ __launch_bounds__(kMaxWaves * kWave) void k_tile(const TileParams p) 
     }
 }
 
+// ---- variant chosen on the host (cat_tile.hip: tile_config) ------------------------------------
 struct TileCfg {
     bool ok = false;
-    int KT = 0, P = 0, waves = 0, nchunks = 0, planes = 0, mode = MODE_ASSIGN;
+    int KT = 0, P = 0, waves = 0, nchunks = 0, mode = MODE_ASSIGN;
     bool chunked = false;  // the centroid operand streams through LDS instead of living there
-    uint32_t ldsA = 0, off_stage = 0, off_cnorm = 0, off_hist = 0, off_rep = 0, off_list = 0, off_misc = 0;
+    uint32_t ldsA = 0, off_cnorm = 0, off_hist = 0, off_rep = 0, off_list = 0, off_misc = 0;
     size_t lds_total = 0;
 };
 
@@ -677,11 +630,10 @@ template <int KT, int PASSES, bool BF16>
 static inline cat_status launch_mode(const TileParams& p, const TileCfg& c, hipStream_t st) {
     if (c.chunked) {
         if (c.mode == MODE_ASSIGN) return launch_one<KT, PASSES, BF16, MODE_ASSIGN, true>(p, c, st);
-        if (c.mode == MODE_APPLY_REREAD) return launch_one<KT, PASSES, BF16, MODE_APPLY_REREAD, true>(p, c, st);
+        if (c.mode == MODE_APPLY) return launch_one<KT, PASSES, BF16, MODE_APPLY, true>(p, c, st);
     } else {
         if (c.mode == MODE_ASSIGN) return launch_one<KT, PASSES, BF16, MODE_ASSIGN, false>(p, c, st);
-        if (c.mode == MODE_APPLY_REREAD) return launch_one<KT, PASSES, BF16, MODE_APPLY_REREAD, false>(p, c, st);
-        if (!BF16 && c.mode == MODE_APPLY_RETAIN) return launch_one<KT, PASSES, false, MODE_APPLY_RETAIN, false>(p, c, st);
+        if (c.mode == MODE_APPLY) return launch_one<KT, PASSES, BF16, MODE_APPLY, false>(p, c, st);
     }
     return set_error(CAT_ERR_UNSUPPORTED, "tile kernel: no instance for this mode");
 }
@@ -690,7 +642,6 @@ template <int KT, bool BF16>
 static inline cat_status launch_kt(const TileParams& p, const TileCfg& c, hipStream_t st) {
     return c.P == 2 ? launch_mode<KT, 3, BF16>(p, c, st) : launch_mode<KT, 1, BF16>(p, c, st);
 }
-
 
 // one translation unit per (KT, dtype), for compile time: cat_tile_k<KT>_<dtype>.hip
 cat_status launch_kt1_f32(const TileParams& p, const TileCfg& c, hipStream_t st);
