@@ -278,23 +278,24 @@ __device__ __forceinline__ void finish_tile(const TileParams& p, unsigned char* 
         // The affine map walks the 16 rows again, this time one row per instruction with the
         // lanes side by side over the channels (16 bytes each): the row was fetched a moment ago and
         // comes from L2, its cluster id is wave-uniform, so the gamma / beta rows are scalar-addressed
-        // and everything is coalesced.  Four rows are in flight at a time (24 independent 16-byte loads
-        // per lane for D <= 512).
+        // and everything is coalesced.  Four rows (fp32; two for bf16) are in flight at a time: 24
+        // independent 16-byte loads per lane.
         if (p.assign && owner) p.assign[row0 + n] = idx;
         const int nv = (p.N - row0) < kRows ? (int)(p.N - row0) : kRows;
         constexpr int EPL = BF16 ? 8 : 4;  // elements per lane per load
+        constexpr int RB = BF16 ? 2 : 4;   // rows in flight (bf16 rows need two gamma and two beta loads per x load)
         typedef typename std::conditional<BF16, bf16_t, float>::type T;
 #pragma unroll 1
-        for (int i0 = 0; i0 < kRows; i0 += 4) {
+        for (int i0 = 0; i0 < kRows; i0 += RB) {
             // row pointers are wave-uniform (scalar registers).  Rows past the end repeat the last row and
             // channels past D repeat channel 0: those lanes recompute and store again exactly what the
             // owning lanes store, so neither the loads nor the stores are conditional
-            const T* xr[4];
-            const float* gr[4];
-            const float* br[4];
-            T* orow[4];
+            const T* xr[RB];
+            const float* gr[RB];
+            const float* br[RB];
+            T* orow[RB];
 #pragma unroll
-            for (int u = 0; u < 4; u++) {
+            for (int u = 0; u < RB; u++) {
                 const int iu = i0 + u < nv ? i0 + u : nv - 1;
                 const int a = __builtin_amdgcn_readfirstlane(__shfl(idx, iu, kWave));
                 xr[u] = (const T*)p.lq + (row0 + iu) * p.D;
@@ -310,10 +311,10 @@ __device__ __forceinline__ void finish_tile(const TileParams& p, unsigned char* 
                     const int ch = cb + (j * kWave + lane) * EPL;
                     o[j] = ch < p.D ? ch : 0;
                 }
-                u32x4 xv[4][2];
-                f32x4 gv[4][2][BF16 ? 2 : 1], bv[4][2][BF16 ? 2 : 1];
+                u32x4 xv[RB][2];
+                f32x4 gv[RB][2][BF16 ? 2 : 1], bv[RB][2][BF16 ? 2 : 1];
 #pragma unroll
-                for (int u = 0; u < 4; u++)
+                for (int u = 0; u < RB; u++)
 #pragma unroll
                     for (int j = 0; j < 2; j++) {
                         xv[u][j] = *(const u32x4*)(xr[u] + o[j]);
@@ -325,7 +326,7 @@ __device__ __forceinline__ void finish_tile(const TileParams& p, unsigned char* 
                         }
                     }
 #pragma unroll
-                for (int u = 0; u < 4; u++)
+                for (int u = 0; u < RB; u++)
 #pragma unroll
                     for (int j = 0; j < 2; j++) {
                         u32x4 r;
@@ -467,19 +468,21 @@ __global__ __launch_bounds__(kMaxWaves * kWave) void k_tile(const TileParams p) 
         const int wg_tile0 = (int)blockIdx.x * p.waves;
         const int wg_tiles = wg_tile0 < ntiles ? (ntiles - 1 - wg_tile0) / tstride + 1 : 0;
         const int nsteps = wg_tiles * p.nchunks;
-        int s = 0, ca = 0;
-        u32x4 areg[AREG];
-#define CAT_CA_STEP(bufcur, bufnext)                                                                          \
-    {                                                                                                         \
-        const int cn_ = ca + 1 == p.nchunks ? 0 : ca + 1;                                                     \
-        const bool more_ = s + 1 < nsteps;                                                                    \
-        if (more_) {                                                                                          \
-            const u32x4* src_ = (const u32x4*)((const unsigned char*)p.packA + (size_t)cn_ * chunkA);         \
-            _Pragma("unroll") for (int i_ = 0; i_ < AREG; i_++) {                                             \
-                const int v_ = i_ * (int)blockDim.x + (int)threadIdx.x;                                       \
-                if (v_ < chunkA / 16) areg[i_] = src_[v_];                                                    \
-            }                                                                                                 \
+        int s = 0;
+        // the operand chunk of step s + 2 is requested during step s and written to LDS at the end of
+        // step s + 1 (into the buffer step s + 1 does not read), so an operand load has two steps to land
+        u32x4 ra[AREG], rb[AREG];
+#define CAT_CA_LOAD(reg, step_)                                                                               \
+    if ((step_) < nsteps) {                                                                                   \
+        const u32x4* src_ = (const u32x4*)((const unsigned char*)p.packA + (size_t)((step_) % p.nchunks) * chunkA); \
+        _Pragma("unroll") for (int i_ = 0; i_ < AREG; i_++) {                                                 \
+            const int v_ = i_ * (int)blockDim.x + (int)threadIdx.x;                                           \
+            if (v_ < chunkA / 16) reg[i_] = src_[v_];                                                         \
         }                                                                                                     \
+    }
+#define CAT_CA_STEP(bufcur, bufnext, regw, regl)                                                              \
+    {                                                                                                         \
+        CAT_CA_LOAD(regl, s + 2)                                                                              \
         CAT_ISSUE(bufnext)                                                                                    \
         if (tc < ntiles) {                                                                                    \
             contract_chunk<KT, PASSES, BF16>(bufcur, acc, nrm, smem + (size_t)(s & 1) * chunkA, lane, cc, p.D); \
@@ -489,24 +492,31 @@ __global__ __launch_bounds__(kMaxWaves * kWave) void k_tile(const TileParams p) 
                 tc += tstride;                                                                                \
             }                                                                                                 \
         }                                                                                                     \
-        if (more_) {                                                                                          \
+        if (s + 1 < nsteps) {                                                                                 \
             u32x4* dst_ = (u32x4*)(smem + (size_t)((s + 1) & 1) * chunkA);                                    \
             _Pragma("unroll") for (int i_ = 0; i_ < AREG; i_++) {                                             \
                 const int v_ = i_ * (int)blockDim.x + (int)threadIdx.x;                                       \
-                if (v_ < chunkA / 16) dst_[v_] = areg[i_];                                                    \
+                if (v_ < chunkA / 16) dst_[v_] = regw[i_];                                                    \
             }                                                                                                 \
         }                                                                                                     \
         __syncthreads();                                                                                      \
-        ca = cn_;                                                                                             \
         s++;                                                                                                  \
     }
+        CAT_CA_LOAD(rb, 1)
         while (s < nsteps) {
-            CAT_CA_STEP(b0, b2)
+            CAT_CA_STEP(b0, b2, rb, ra)
             if (s >= nsteps) break;
-            CAT_CA_STEP(b1, b0)
+            CAT_CA_STEP(b1, b0, ra, rb)
             if (s >= nsteps) break;
-            CAT_CA_STEP(b2, b1)
+            CAT_CA_STEP(b2, b1, rb, ra)
+            if (s >= nsteps) break;
+            CAT_CA_STEP(b0, b2, ra, rb)
+            if (s >= nsteps) break;
+            CAT_CA_STEP(b1, b0, rb, ra)
+            if (s >= nsteps) break;
+            CAT_CA_STEP(b2, b1, ra, rb)
         }
+#undef CAT_CA_LOAD
 #undef CAT_CA_STEP
     } else {
         while (tc < ntiles) {
@@ -615,11 +625,24 @@ template <int KT, int PASSES, bool BF16, int MODE, bool CA>
 static inline cat_status launch_one(const TileParams& p, const TileCfg& c, hipStream_t st) {
     auto kern = k_tile<KT, PASSES, BF16, MODE, CA>;
     CAT_HIP_TRY(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)c.lds_total));
+    // persistent grid: as many workgroups as are resident at once (registers and LDS decide), each
+    // walking its share of the tiles; asked from the runtime once per kernel variant and LDS size
+    static int cached_lds = -1, cached_per_cu = 1;
+    if (cached_lds != (int)c.lds_total) {
+        int nb = 0;
+        CAT_HIP_TRY(hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, (const void*)kern, c.waves * kWave, c.lds_total));
+        cached_per_cu = nb < 1 ? 1 : nb;
+        cached_lds = (int)c.lds_total;
+    }
     int64_t want = (p.ntiles + c.waves - 1) / c.waves;
-    int per_cu = (int)(kLdsLimit / c.lds_total);
-    if (per_cu > 2) per_cu = 2;
-    if (per_cu < 1) per_cu = 1;
-    int64_t cap = 256 * (int64_t)per_cu;
+    static int ncu = 0;
+    if (ncu == 0) {
+        int dev = 0, v = 0;
+        CAT_HIP_TRY(hipGetDevice(&dev));
+        CAT_HIP_TRY(hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev));
+        ncu = v > 0 ? v : 256;
+    }
+    int64_t cap = (int64_t)ncu * cached_per_cu;
     unsigned blocks = (unsigned)(want < cap ? want : cap);
     hipLaunchKernelGGL(kern, dim3(blocks), dim3(c.waves * kWave), c.lds_total, st, p);
     CAT_LAUNCH_CHECK("k_tile");
