@@ -406,8 +406,8 @@ __global__ __launch_bounds__(kMaxWaves * kWave) void k_tile(const TileParams p) 
     const int ntiles = (int)p.ntiles;
     const int tstride = (int)gridDim.x * p.waves;
     const int tile0 = __builtin_amdgcn_readfirstlane((int)blockIdx.x * p.waves + wave);
-    // the first two chunks are requested before the prologue touches LDS
     int tl = tile0, cl = 0;  // load cursor
+    float cmax_out;
     ChunkRegs<BF16> b0, b1, b2;
 #define CAT_ISSUE(buf)                            \
     if (tl < ntiles) {                            \
@@ -417,29 +417,50 @@ __global__ __launch_bounds__(kMaxWaves * kWave) void k_tile(const TileParams p) 
             tl += tstride;                        \
         }                                         \
     }
-    CAT_ISSUE(b0)
-    CAT_ISSUE(b1)
-
-    // prologue: centroids (operand order) and their norms into LDS
+    // prologue: centroids (operand order) and their norms into LDS.  Returns come back in issue order,
+    // so the operand copy goes first, in batches of eight independent loads, then the first two chunks
+    // of rows are requested, and only then does anything wait.
     {
         // resident operand: all of it; chunked operand (CA): the first chunk into the first of two buffers
         const u32x4* src = (const u32x4*)p.packA;
         u32x4* dst = (u32x4*)smem;
         const uint32_t nvec = CA ? (uint32_t)(4 * KT * P * 1024 / 16) : p.ldsA_bytes / 16;
-        for (uint32_t i = threadIdx.x; i < nvec; i += blockDim.x) dst[i] = src[i];
-        for (int k = threadIdx.x; k < p.K16; k += blockDim.x) s_cnorm[k] = p.cnorm[k];
+        const uint32_t nt = blockDim.x;
+        uint32_t i = threadIdx.x;
+        u32x4 t[8];
+        const bool first = i + 7 * nt < nvec;
+        if (first) {
+#pragma unroll
+            for (int u = 0; u < 8; u++) t[u] = src[i + u * nt];
+        }
+        const float cn_mine = (int)threadIdx.x < p.K16 ? p.cnorm[threadIdx.x] : 0.f;
+        float cm2 = 0.f;  // largest centroid norm: every wave reduces the table for itself
+        for (int k = lane; k < p.K; k += kWave) cm2 = fmaxf(cm2, p.cnorm[k]);
+        CAT_ISSUE(b0)
+        CAT_ISSUE(b1)
+        if (first) {
+#pragma unroll
+            for (int u = 0; u < 8; u++) dst[i + u * nt] = t[u];
+            i += 8 * nt;
+        }
+        for (; i + 7 * nt < nvec; i += 8 * nt) {
+#pragma unroll
+            for (int u = 0; u < 8; u++) t[u] = src[i + u * nt];
+#pragma unroll
+            for (int u = 0; u < 8; u++) dst[i + u * nt] = t[u];
+        }
+        for (; i < nvec; i += nt) dst[i] = src[i];
+        if ((int)threadIdx.x < p.K16) s_cnorm[threadIdx.x] = cn_mine;
         for (int k = threadIdx.x; k < p.K; k += blockDim.x) {
             s_hist[k] = 0;
             s_rep[k] = ~0ull;
         }
         if (threadIdx.x == 0) s_misc[0] = 0;
-    }
-    // largest centroid norm (every wave reduces the table for itself: no extra barrier)
-    float cm2 = 0.f;
-    for (int k = lane; k < p.K; k += kWave) cm2 = fmaxf(cm2, p.cnorm[k]);
 #pragma unroll
-    for (int o = 32; o > 0; o >>= 1) cm2 = fmaxf(cm2, __shfl_xor(cm2, o, kWave));
-    const float cmax = sqrtf(cm2);
+        for (int o = 32; o > 0; o >>= 1) cm2 = fmaxf(cm2, __shfl_xor(cm2, o, kWave));
+        cmax_out = sqrtf(cm2);
+    }
+    const float cmax = cmax_out;
     __syncthreads();
 
     double in_acc = 0.0;
