@@ -161,6 +161,18 @@ cat_status cat_stats(const void *lq, const void *fp, const int32_t *assignments,
  */
 cat_status cat_init_indices(int64_t N, int32_t K, uint64_t seed, int64_t *idx_out);
 
+/*
+ * Timing of the dominant kernel, for benchmarks.  While enabled, every launch of the tile
+ * kernel (the assignment / Lloyd / inference pass) made by the calling process is bracketed by
+ * two HIP events recorded on the launch stream.  cat_profile_read waits for those events and
+ * copies up to `cap` durations (milliseconds, launch order) to the HOST array ms_out; it
+ * returns the number of launches recorded since cat_profile_enable(1) (which also clears the
+ * record), or -1 on a HIP error.  Event objects are created on first use and kept; nothing is
+ * recorded, created or waited for while profiling is disabled (the default).  Not thread-safe.
+ */
+cat_status cat_profile_enable(int on);
+int cat_profile_read(float *ms_out, int cap);
+
 /* Message of the last non-OK status on the calling thread ("" if none).  The
  * pointer stays valid until the next failing call on the same thread. */
 const char *cat_last_error(void);

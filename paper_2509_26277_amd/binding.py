@@ -19,7 +19,8 @@ _STATUS = {0: "CAT_OK", 1: "CAT_ERR_INVALID_ARG", 2: "CAT_ERR_UNSUPPORTED", 3: "
            4: "CAT_ERR_DEVICE"}
 
 EXPORTS = ("cat_select_path", "cat_fit_workspace_bytes", "cat_apply_workspace_bytes", "cat_fit", "cat_apply",
-           "cat_assign", "cat_update", "cat_stats", "cat_init_indices", "cat_last_error")
+           "cat_assign", "cat_update", "cat_stats", "cat_init_indices", "cat_last_error", "cat_profile_enable",
+           "cat_profile_read")
 
 
 class CatError(RuntimeError):
@@ -61,6 +62,10 @@ def load_library():
     lib.cat_stats.restype = c.c_int
     lib.cat_init_indices.argtypes = [i64, i32, u64, c.POINTER(c.c_int64)]
     lib.cat_init_indices.restype = c.c_int
+    lib.cat_profile_enable.argtypes = [c.c_int]
+    lib.cat_profile_enable.restype = c.c_int
+    lib.cat_profile_read.argtypes = [c.POINTER(c.c_float), c.c_int]
+    lib.cat_profile_read.restype = c.c_int
     lib.cat_last_error.argtypes = []
     lib.cat_last_error.restype = c.c_char_p
     _lib = lib
@@ -98,6 +103,22 @@ def _stream():
 
 def select_path(path):
     _check(load_library().cat_select_path(int(path)))
+
+
+def profile_enable(on):
+    """Bracket every tile-kernel launch with HIP events on its stream (benchmarks only)."""
+    _check(load_library().cat_profile_enable(1 if on else 0))
+
+
+def profile_read():
+    """Durations (ms) of the tile-kernel launches recorded since profile_enable(True)."""
+    lib = load_library()
+    n = lib.cat_profile_read(None, 0)
+    if n < 0:
+        raise CatError(4, "cat_profile_read failed")
+    buf = (ctypes.c_float * max(n, 1))()
+    lib.cat_profile_read(buf, n)
+    return list(buf)[:n]
 
 
 def cat_fit_workspace_bytes(N, D, K, dt=CAT_F32):

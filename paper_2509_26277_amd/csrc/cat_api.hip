@@ -6,6 +6,7 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <vector>
 
 #include "cat_common.h"
 #include "cat_tile.h"
@@ -21,6 +22,25 @@ cat_status set_error(cat_status st, const char* fmt, ...) {
     vsnprintf(g_err, sizeof(g_err), fmt, ap);
     va_end(ap);
     return st;
+}
+
+// ---- kernel timing (cat_profile_enable / cat_profile_read) -------------------------------
+static bool g_prof = false;
+static std::vector<hipEvent_t> g_prof_ev;  // pairs (begin, end), reused across enables
+static size_t g_prof_used = 0;             // events recorded since the last enable
+
+bool profile_on() { return g_prof; }
+
+cat_status profile_mark(bool begin, hipStream_t st) {
+    (void)begin;
+    if (g_prof_used == g_prof_ev.size()) {
+        hipEvent_t e;
+        CAT_HIP_TRY(hipEventCreate(&e));
+        g_prof_ev.push_back(e);
+    }
+    CAT_HIP_TRY(hipEventRecord(g_prof_ev[g_prof_used], st));
+    g_prof_used++;
+    return CAT_OK;
 }
 
 // ---- workspace ------------------------------------------------------------------
@@ -167,6 +187,23 @@ using namespace cat;
 extern "C" {
 
 const char* cat_last_error(void) { return g_err; }
+
+cat_status cat_profile_enable(int on) {
+    g_prof = on != 0;
+    if (g_prof) g_prof_used = 0;
+    return CAT_OK;
+}
+
+int cat_profile_read(float* ms_out, int cap) {
+    const size_t pairs = g_prof_used / 2;
+    for (size_t i = 0; i < pairs; i++) {
+        if (hipEventSynchronize(g_prof_ev[2 * i + 1]) != hipSuccess) return -1;
+        float ms = 0.f;
+        if (hipEventElapsedTime(&ms, g_prof_ev[2 * i], g_prof_ev[2 * i + 1]) != hipSuccess) return -1;
+        if (ms_out && (int)i < cap) ms_out[i] = ms;
+    }
+    return (int)pairs;
+}
 
 cat_status cat_select_path(cat_path p) {
     if (p != CAT_PATH_AUTO && p != CAT_PATH_STREAM && p != CAT_PATH_TILE)

@@ -665,8 +665,14 @@ static inline cat_status launch_one(const TileParams& p, const TileCfg& c, hipSt
     }
     int64_t cap = (int64_t)ncu * cached_per_cu;
     unsigned blocks = (unsigned)(want < cap ? want : cap);
+    const bool prof = profile_on();
+    if (prof) {
+        cat_status ps = profile_mark(true, st);
+        if (ps != CAT_OK) return ps;
+    }
     hipLaunchKernelGGL(kern, dim3(blocks), dim3(c.waves * kWave), c.lds_total, st, p);
     CAT_LAUNCH_CHECK("k_tile");
+    if (prof) return profile_mark(false, st);
     return CAT_OK;
 }
 
