@@ -18,7 +18,9 @@ from parity_util import (RTOL, beta_scale, check_assignments, check_values, dev_
 
 pytestmark = pytest.mark.gpu
 
-PATHS = [binding.CAT_PATH_STREAM, binding.CAT_PATH_AUTO]
+# every shape below that is parametrised over PATHS fits the tile kernels, so the second entry
+# really runs them (a forced path that does not fit returns CAT_ERR_UNSUPPORTED)
+PATHS = [binding.CAT_PATH_STREAM, binding.CAT_PATH_TILE]
 
 
 @pytest.fixture(autouse=True)
@@ -132,7 +134,9 @@ def test_apply_end_to_end(alpha, path):
         assert (out == lq).all()
 
 
-def test_apply_bf16_rows():
+@pytest.mark.parametrize("path", PATHS)
+def test_apply_bf16_rows(path):
+    binding.select_path(path)
     w = small("cfg4", 900)
     K, D = w["K"], w["D"]
     rng = np.random.default_rng(5)
@@ -192,8 +196,14 @@ def test_empty_cluster_constant_channel_single_row(path):
     check_values(c, o["centroids"], 1e-4, "centroids")
 
 
-@pytest.mark.parametrize("path", PATHS)
-@pytest.mark.parametrize("N,D,K", [(1, 1, 1), (7, 1, 7), (65, 3, 2), (200, 130, 1), (333, 257, 19)])
+# (N, D, K, path): odd D only runs on the streaming kernels; D % 4 == 0 on both; K = 200 and 256 use the
+# widest cluster tiling of the tile kernel
+DEGENERATE = [(1, 1, 1, 1), (7, 1, 7, 1), (65, 3, 2, 1), (200, 130, 1, 1), (333, 257, 19, 1),
+              (1, 4, 1, 2), (9, 4, 9, 2), (65, 8, 2, 2), (200, 132, 1, 2), (333, 260, 19, 2), (700, 64, 200, 2),
+              (1200, 36, 256, 2), (65, 8, 2, 0), (333, 257, 19, 0)]
+
+
+@pytest.mark.parametrize("N,D,K,path", DEGENERATE)
 def test_degenerate_shapes(N, D, K, path):
     binding.select_path(path)
     rng = np.random.default_rng(N * 1000 + D)
@@ -211,6 +221,17 @@ def test_degenerate_shapes(N, D, K, path):
     ok = a.cpu().numpy() == o_a
     assert ok.mean() > 0.99
     check_values(host_matrix(out)[ok], o_out[ok], 1e-4, "corrected")
+
+
+def test_forced_tile_path_reports_shapes_it_cannot_run():
+    binding.select_path(binding.CAT_PATH_TILE)
+    lq = torch.zeros((64, 7), device="cuda")  # odd D: rows are not 16-byte aligned
+    with pytest.raises(binding.CatError) as e:
+        cat_assign(lq, lq[:4].contiguous())
+    assert e.value.status == 2
+    with pytest.raises(binding.CatError) as e:
+        cat_fit(lq, lq.clone(), 4, iters=1)
+    assert e.value.status == 2
 
 
 def test_device_errors_are_statuses_not_crashes():
