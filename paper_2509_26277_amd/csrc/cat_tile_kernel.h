@@ -74,23 +74,57 @@ __device__ __forceinline__ float readlane_f(float v, int l) {
     return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), l));
 }
 
-template <bool BF16>
-__device__ __forceinline__ double exact_dist(const void* lq, int64_t row, int64_t D, const float* c, int lane) {
-    double s = 0.0;
-    if (BF16) {
-        const bf16_t* x = (const bf16_t*)lq + row * D;
-        for (int64_t j = lane; j < D; j += kWave) {
-            double d = (double)bf16_to_f32(x[j]) - (double)c[j];
-            s = fma(d, d, s);
+// Exact squared distances (fp64, direct form) of one row to NC centroids at once, the whole wave
+// on the row: 16-byte loads, every lane's loads of a round issued before any is used.  D is a
+// multiple of the 16-byte group (4 fp32 / 8 bf16 channels), as everywhere in the tile path.
+template <bool BF16, int NC>
+__device__ __forceinline__ void exact_dists(const void* lq, int64_t row, int64_t D, const float* cent,
+                                            const int (&k)[NC], int lane, double (&out)[NC]) {
+    constexpr int EPL = BF16 ? 8 : 4;
+    double s[NC];
+#pragma unroll
+    for (int c = 0; c < NC; c++) s[c] = 0.0;
+    const unsigned char* xrow = (const unsigned char*)lq + row * D * (BF16 ? 2 : 4);
+    for (int64_t j0 = (int64_t)lane * EPL; j0 < D; j0 += 2 * kWave * EPL) {
+        const int64_t j1 = j0 + kWave * EPL;
+        const bool two = j1 < D;
+        const int64_t j[2] = {j0, two ? j1 : j0};
+        u32x4 xv[2];
+        f32x4 cv[2][NC][BF16 ? 2 : 1];
+#pragma unroll
+        for (int u = 0; u < 2; u++) {
+            xv[u] = *(const u32x4*)(xrow + j[u] * (BF16 ? 2 : 4));
+#pragma unroll
+            for (int c = 0; c < NC; c++) {
+                const float* cr = cent + (int64_t)k[c] * D + j[u];
+                cv[u][c][0] = *(const f32x4*)cr;
+                if (BF16) cv[u][c][BF16 ? 1 : 0] = *(const f32x4*)(cr + 4);
+            }
         }
-    } else {
-        const float* x = (const float*)lq + row * D;
-        for (int64_t j = lane; j < D; j += kWave) {
-            double d = (double)x[j] - (double)c[j];
-            s = fma(d, d, s);
+#pragma unroll
+        for (int u = 0; u < 2; u++) {
+            if (u == 1 && !two) break;
+            float x[EPL];
+#pragma unroll
+            for (int e = 0; e < 4; e++) {
+                if (BF16) {
+                    x[2 * e] = lo_half(xv[u][e]);
+                    x[2 * e + 1] = hi_half(xv[u][e]);
+                } else {
+                    x[e] = __uint_as_float(xv[u][e]);
+                }
+            }
+#pragma unroll
+            for (int c = 0; c < NC; c++)
+#pragma unroll
+                for (int e = 0; e < EPL; e++) {
+                    const double d = (double)x[e] - (double)cv[u][c][e >> 2][e & 3];
+                    s[c] = fma(d, d, s[c]);
+                }
         }
     }
-    return wave_sum(s);
+#pragma unroll
+    for (int c = 0; c < NC; c++) out[c] = wave_sum(s[c]);
 }
 
 // One chunk (128 channels) of the tile as loaded: per MFMA step s, lane (n, g) holds channels
@@ -98,19 +132,24 @@ __device__ __forceinline__ double exact_dist(const void* lq, int64_t row, int64_
 template <bool BF16>
 struct ChunkRegs {
     u32x4 v[BF16 ? 4 : 8];
+    int prev;  // previous assignment of row n (assignment passes only)
 };
 
 // Rows past N repeat the last row and channel groups past D read the start of the row (valid
 // addresses either way), so no load is conditional; the consumer masks the padding channels
 // (masking here would make the loads wait where they are issued).  D is a multiple of 4 (fp32)
 // or 8 (bf16): rows are 16-byte aligned and a 16-byte group is valid or padding as a whole.
-template <bool BF16>
+// With PREV the row's previous assignment rides along with every chunk: fetched inside the
+// tile's finishing code it would have to be waited for there, and since loads return in order
+// that wait would also drain the chunks requested ahead.
+template <bool BF16, bool PREV>
 __device__ __forceinline__ void load_chunk(ChunkRegs<BF16>& r, const TileParams& p, int tile, int chunk, int lane) {
     const int64_t row0 = (int64_t)(p.reverse ? (int)p.ntiles - 1 - tile : tile) * kRows;
     const int nv = (p.N - row0) < kRows ? (int)(p.N - row0) : kRows;
     const int n = lane & 15, g = lane >> 4;
     const int rn = n < nv ? n : nv - 1;
     const int ch = chunk * kChunk + 8 * g;
+    if (PREV) r.prev = p.assign[row0 + rn];
     if (BF16) {
         const bf16_t* x = (const bf16_t*)p.lq + (row0 + rn) * p.D;
 #pragma unroll
@@ -228,6 +267,34 @@ __device__ __forceinline__ void rank_rows(const TileParams& p, const f32x4 (&acc
         const int64_t row = row0 + r;
         double dbest = __builtin_inf();
         int kbest = 0x7fffffff;
+        // the candidates (scores within the bound of the best) are listed first, one per lane, then
+        // measured two at a time: the usual case is exactly two
+        int cand = 0, cnt = 0;
+        auto measure = [&]() {
+            for (int c0 = 0; c0 < cnt; c0 += 2) {
+                const int k0 = __builtin_amdgcn_readlane(cand, c0);
+                if (c0 + 1 < cnt) {
+                    const int kk[2] = {k0, __builtin_amdgcn_readlane(cand, c0 + 1)};
+                    double d[2];
+                    exact_dists<BF16, 2>(p.lq, row, p.D, p.cent, kk, lane, d);
+#pragma unroll
+                    for (int c = 0; c < 2; c++)
+                        if (d[c] < dbest || (d[c] == dbest && kk[c] < kbest)) {
+                            dbest = d[c];
+                            kbest = kk[c];
+                        }
+                } else {
+                    const int kk[1] = {k0};
+                    double d[1];
+                    exact_dists<BF16, 1>(p.lq, row, p.D, p.cent, kk, lane, d);
+                    if (d[0] < dbest || (d[0] == dbest && k0 < kbest)) {
+                        dbest = d[0];
+                        kbest = k0;
+                    }
+                }
+            }
+            cnt = 0;
+        };
 #pragma unroll
         for (int t = 0; t < KT; t++)
 #pragma unroll
@@ -239,14 +306,12 @@ __device__ __forceinline__ void rank_rows(const TileParams& p, const f32x4 (&acc
                     m &= m - 1;
                     const int k = 16 * t + 4 * (l >> 4) + i;
                     if (k < p.K) {
-                        double d = exact_dist<BF16>(p.lq, row, p.D, p.cent + (int64_t)k * p.D, lane);
-                        if (d < dbest || (d == dbest && k < kbest)) {
-                            dbest = d;
-                            kbest = k;
-                        }
+                        if (lane == cnt) cand = k;
+                        if (++cnt == kWave) measure();
                     }
                 }
             }
+        measure();
         if (n == r && kbest != 0x7fffffff) {
             i1 = kbest;
             dmin = (float)dbest;
@@ -258,7 +323,7 @@ __device__ __forceinline__ void rank_rows(const TileParams& p, const f32x4 (&acc
 // Per-tile finishing work of the streaming modes: rank, write, book-keep; resets acc / nrm.
 template <int KT, bool BF16, int MODE>
 __device__ __forceinline__ void finish_tile(const TileParams& p, unsigned char* smem, f32x4 (&acc)[KT], float& nrm,
-                                            int tile, int lane, float cmax, double& in_acc) {
+                                            int tile, int lane, float cmax, double& in_acc, int prev_in) {
     const int n = lane & 15, q = lane >> 4;
     const int64_t row0 = (int64_t)(p.reverse ? (int)p.ntiles - 1 - tile : tile) * kRows;
     const float* s_cnorm = (const float*)(smem + p.off_cnorm);
@@ -355,9 +420,8 @@ __device__ __forceinline__ void finish_tile(const TileParams& p, unsigned char* 
     int* s_hist = (int*)(smem + p.off_hist);
     unsigned long long* s_rep = (unsigned long long*)(smem + p.off_rep);
     int* s_misc = (int*)(smem + p.off_misc);
-    int prev = -1;
+    const int prev = p.delta_mode ? prev_in : -1;
     if (owner) {
-        if (p.delta_mode) prev = p.assign[row0 + n];
         p.assign[row0 + n] = idx;
         if (p.counts) atomicAdd(&s_hist[idx], 1);
         if (p.rep) atomicMin(&s_rep[idx], (unsigned long long)(row0 + n));
@@ -409,13 +473,17 @@ __global__ __launch_bounds__(kMaxWaves * kWave) void k_tile(const TileParams p) 
     int tl = tile0, cl = 0;  // load cursor
     float cmax_out;
     ChunkRegs<BF16> b0, b1, b2;
-#define CAT_ISSUE(buf)                            \
-    if (tl < ntiles) {                            \
-        load_chunk<BF16>(buf, p, tl, cl, lane);   \
-        if (++cl == p.nchunks) {                  \
-            cl = 0;                               \
-            tl += tstride;                        \
-        }                                         \
+    // Chunk loads are never conditional: once the cursor has run past the wave's last tile it keeps
+    // re-reading that tile (cache hits, results unused).  A load that is issued on one path only
+    // would make every later wait count as if it had not been issued, which drains the pipeline.
+    const int tlast = __builtin_amdgcn_readfirstlane(tile0 < ntiles ? tile0 + (ntiles - 1 - tile0) / tstride * tstride : ntiles - 1);
+#define CAT_ISSUE(buf)                                                                     \
+    {                                                                                      \
+        load_chunk<BF16, MODE == MODE_ASSIGN>(buf, p, tl < tlast ? tl : tlast, cl, lane);  \
+        if (++cl == p.nchunks) {                                                           \
+            cl = 0;                                                                        \
+            tl += tstride;                                                                 \
+        }                                                                                  \
     }
     // prologue: centroids (operand order) and their norms into LDS.  Returns come back in issue order,
     // so the operand copy goes first, in batches of eight independent loads, then the first two chunks
@@ -475,7 +543,7 @@ __global__ __launch_bounds__(kMaxWaves * kWave) void k_tile(const TileParams p) 
 #define CAT_STEP(buf)                                                                                          \
     contract_chunk<KT, PASSES, BF16>(buf, acc, nrm, smem + (size_t)cc * 4 * KT * P * 1024, lane, cc, p.D);     \
     if (++cc == p.nchunks) {                                                                                   \
-        finish_tile<KT, BF16, MODE>(p, smem, acc, nrm, tc, lane, cmax, in_acc);                                \
+        finish_tile<KT, BF16, MODE>(p, smem, acc, nrm, tc, lane, cmax, in_acc, buf.prev);                      \
         cc = 0;                                                                                                \
         tc += tstride;                                                                                         \
     }
@@ -493,37 +561,43 @@ __global__ __launch_bounds__(kMaxWaves * kWave) void k_tile(const TileParams p) 
         // the operand chunk of step s + 2 is requested during step s and written to LDS at the end of
         // step s + 1 (into the buffer step s + 1 does not read), so an operand load has two steps to land
         u32x4 ra[AREG], rb[AREG];
-#define CAT_CA_LOAD(reg, step_)                                                                               \
-    if ((step_) < nsteps) {                                                                                   \
-        const u32x4* src_ = (const u32x4*)((const unsigned char*)p.packA + (size_t)((step_) % p.nchunks) * chunkA); \
+        // Loads and LDS writes are unconditional (a lane past the end of the chunk repeats the last
+        // vector, a load past the last step fetches a chunk nobody reads): a conditional load would be
+        // waited for on the spot.  The workgroup is always kMaxWaves waves here (checked at launch).
+        constexpr int NT = kMaxWaves * kWave, NVEC = chunkA / 16;
+        int ca_next = 1 % p.nchunks;  // chunk index of the next operand load
+#define CAT_CA_LOAD(reg)                                                                                      \
+    {                                                                                                         \
+        const u32x4* src_ = (const u32x4*)((const unsigned char*)p.packA + (size_t)ca_next * chunkA);         \
         _Pragma("unroll") for (int i_ = 0; i_ < AREG; i_++) {                                                 \
-            const int v_ = i_ * (int)blockDim.x + (int)threadIdx.x;                                           \
-            if (v_ < chunkA / 16) reg[i_] = src_[v_];                                                         \
+            const int v_ = i_ * NT + (int)threadIdx.x;                                                        \
+            reg[i_] = src_[NVEC % NT == 0 ? v_ : (v_ < NVEC ? v_ : NVEC - 1)];                                \
         }                                                                                                     \
+        if (++ca_next == p.nchunks) ca_next = 0;                                                              \
     }
 #define CAT_CA_STEP(bufcur, bufnext, regw, regl)                                                              \
     {                                                                                                         \
-        CAT_CA_LOAD(regl, s + 2)                                                                              \
+        CAT_CA_LOAD(regl)                                                                                     \
         CAT_ISSUE(bufnext)                                                                                    \
         if (tc < ntiles) {                                                                                    \
             contract_chunk<KT, PASSES, BF16>(bufcur, acc, nrm, smem + (size_t)(s & 1) * chunkA, lane, cc, p.D); \
             if (++cc == p.nchunks) {                                                                          \
-                finish_tile<KT, BF16, MODE>(p, smem, acc, nrm, tc, lane, cmax, in_acc);                       \
+                finish_tile<KT, BF16, MODE>(p, smem, acc, nrm, tc, lane, cmax, in_acc, bufcur.prev);          \
                 cc = 0;                                                                                       \
                 tc += tstride;                                                                                \
             }                                                                                                 \
         }                                                                                                     \
-        if (s + 1 < nsteps) {                                                                                 \
+        {                                                                                                     \
             u32x4* dst_ = (u32x4*)(smem + (size_t)((s + 1) & 1) * chunkA);                                    \
             _Pragma("unroll") for (int i_ = 0; i_ < AREG; i_++) {                                             \
-                const int v_ = i_ * (int)blockDim.x + (int)threadIdx.x;                                       \
-                if (v_ < chunkA / 16) dst_[v_] = regw[i_];                                                    \
+                const int v_ = i_ * NT + (int)threadIdx.x;                                                    \
+                dst_[NVEC % NT == 0 ? v_ : (v_ < NVEC ? v_ : NVEC - 1)] = regw[i_];                           \
             }                                                                                                 \
         }                                                                                                     \
         __syncthreads();                                                                                      \
         s++;                                                                                                  \
     }
-        CAT_CA_LOAD(rb, 1)
+        CAT_CA_LOAD(rb)
         while (s < nsteps) {
             CAT_CA_STEP(b0, b2, rb, ra)
             if (s >= nsteps) break;
@@ -645,6 +719,9 @@ struct TileCfg {
 template <int KT, int PASSES, bool BF16, int MODE, bool CA>
 static inline cat_status launch_one(const TileParams& p, const TileCfg& c, hipStream_t st) {
     auto kern = k_tile<KT, PASSES, BF16, MODE, CA>;
+    if (CA && c.waves != kMaxWaves) {
+        return set_error(CAT_ERR_INVALID_ARG, "k_tile: the chunked-operand variant needs %d waves, got %d", kMaxWaves, c.waves);
+    }
     CAT_HIP_TRY(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)c.lds_total));
     // persistent grid: as many workgroups as are resident at once (registers and LDS decide), each
     // walking its share of the tiles; asked from the runtime once per kernel variant and LDS size
