@@ -68,11 +68,11 @@ struct FitWs {
     int64_t* idx;             // K           seeded initial rows
     double* inertia;          // 1
     TileWs tile;              // scratch of the MFMA tile kernels
+    LloydWs lloyd;            // changed-row list and counters of the fused Lloyd loop
     size_t bytes;
 };
 
 static FitWs carve_fit(void* base, int64_t N, int64_t D, int32_t K, cat_dtype dt) {
-    (void)N;
     Carver c(base);
     FitWs w;
     size_t KD = (size_t)K * (size_t)D;
@@ -88,6 +88,10 @@ static FitWs carve_fit(void* base, int64_t N, int64_t D, int32_t K, cat_dtype dt
     size_t tb = tile_workspace_bytes(D, K, dt);
     w.tile = tile_carve(base ? (void*)(c.base + c.off) : nullptr, D, K, dt);
     c.off += align256(tb);
+    if (tb) {
+        w.lloyd = lloyd_carve(base ? (void*)(c.base + c.off) : nullptr, N, D, K);
+        c.off += align256(w.lloyd.bytes);
+    }
     w.bytes = c.off;
     return w;
 }
@@ -331,7 +335,7 @@ cat_status cat_fit(const void* lq, const void* fp, int64_t N, int64_t D, int32_t
     }
     if (fused) {
         // one assignment launch per Lloyd iteration; only the rows that change cluster touch the sums
-        CAT_TRY(tile_lloyd(lq, dt, N, D, K, iters, centroids, w.acc, assignments, w.counts, inertia, w.rep, w.tile, st));
+        CAT_TRY(tile_lloyd(lq, dt, N, D, K, iters, centroids, w.acc, assignments, w.counts, inertia, w.rep, w.tile, w.lloyd, st));
     } else {
         int cur = 0;
         for (int32_t t = 0; t < iters; t++) {

@@ -26,12 +26,24 @@ cat_status tile_assign(const void* lq, cat_dtype dt, int64_t N, int64_t D, int32
                        int32_t* assign, int32_t* counts, double* inertia, unsigned long long* rep,
                        const float* gamma, const float* beta, void* corrected, const TileWs& ws, hipStream_t st);
 
+// Extra device scratch of tile_lloyd: the list of rows that changed cluster in a pass (worst case
+// all N), the counters of the update kernel and the per-slice shares of the centroid norms.
+struct LloydWs {
+    unsigned long long* list = nullptr;  // N entries
+    uint32_t* ctrl = nullptr;            // [0..1] list length (two halves), then 2 x slices finished-workgroup counters
+    double* norm_part = nullptr;         // slices x K
+    int32_t* counts2 = nullptr;          // K: the second half of the counts double buffer
+    size_t bytes = 0;
+};
+size_t lloyd_workspace_bytes(int64_t N, int64_t D, int32_t K);
+LloydWs lloyd_carve(void* base, int64_t N, int64_t D, int32_t K);
+
 // `iters` Lloyd iterations from cent0 plus the final assignment.  cent_io holds the initial
 // centroids on entry and the final ones on return; sums is 2 x K x D doubles of scratch.
 // Writes assignments, counts (K), inertia (iters + 1, nullable) and rep (K).
 cat_status tile_lloyd(const void* lq, cat_dtype dt, int64_t N, int64_t D, int32_t K, int32_t iters,
                       float* cent_io, double* sums, int32_t* assign, int32_t* counts, double* inertia,
-                      unsigned long long* rep, const TileWs& ws, hipStream_t st);
+                      unsigned long long* rep, const TileWs& ws, const LloydWs& lw, hipStream_t st);
 
 // Kernel timing hooks (see cat_profile_enable in cat.h): bracket one launch with events.
 bool profile_on();

@@ -7,10 +7,12 @@ namespace cat {
 // ---- centroid preparation: (sums -> centroids), split to bf16 (hi, lo), operand order ----
 // One workgroup per cluster slot k in [0, K16).  With `base` given: S = base + delta is
 // folded back into base, delta is cleared, centroid = S / count (kept if the cluster is
-// empty).  Then the row is split and scattered into packA, and its squared norm stored.  Last,
-// the outputs of the following pass are reset: counts (after its value was used), the objective
-// slot and the first-row table.
-__global__ __launch_bounds__(256) void k_tile_prep(float* cent, double* base, double* delta, int32_t* counts,
+// empty; the counts are those of the pass before, counts_read).  Then the row is split and
+// scattered into packA, and its squared norm stored.  Last, the outputs of the following pass are
+// reset: its counts (counts_reset, which may be the buffer just read), the objective slot and the
+// first-row table.
+__global__ __launch_bounds__(256) void k_tile_prep(float* cent, double* base, double* delta,
+                                                   const int32_t* counts_read, int32_t* counts_reset,
                                                    int64_t D, int32_t K, int32_t KT, int32_t P, int32_t nchunks,
                                                    uint16_t* packA, float* cnorm, double* inertia_slot,
                                                    unsigned long long* rep) {
@@ -19,7 +21,7 @@ __global__ __launch_bounds__(256) void k_tile_prep(float* cent, double* base, do
     const int t = k >> 4, m = k & 15;
     double nn = 0.0;
     const int64_t Dpad = (int64_t)nchunks * kChunk;
-    const int cntk = (base && k < K) ? counts[k] : 0;
+    const int cntk = (base && k < K) ? counts_read[k] : 0;
     for (int64_t ch = threadIdx.x; ch < Dpad; ch += blockDim.x) {
         float c = 0.f;
         if (k < K && ch < D) {
@@ -56,10 +58,164 @@ __global__ __launch_bounds__(256) void k_tile_prep(float* cent, double* base, do
         cnorm[k] = k < K ? (float)s_red[0] : kPadNorm;
         // outputs the following pass accumulates into (the count was read above, before the barriers)
         if (k < K) {
-            if (counts) counts[k] = 0;
+            if (counts_reset) counts_reset[k] = 0;
             if (rep) rep[k] = ~0ull;
         }
         if (k == 0 && inertia_slot) *inertia_slot = 0.0;
+    }
+}
+
+// ---- sums update from the changed-row list + centroid preparation, one launch -------------------
+// After a Lloyd pass that listed the rows that changed cluster: grid (G list shares) x (64-channel
+// slices) x (cluster ranges).  Every workgroup adds its share of the listed rows to (new cluster) and
+// subtracts them from (old cluster) in an LDS panel of doubles, and merges the panel into `delta`.
+// The workgroup that finishes a slice last (a counter per slice, no waiting) then does for that
+// slice what k_tile_prep does: S = base + delta folded into base, delta cleared, centroid = S /
+// count (kept if the cluster is empty), bf16 split into the operand, and the slice's share of
+// |c|^2 (the tile kernel adds the shares up in slice order, so the norms do not depend on which
+// slice finished first).  Everything the following pass accumulates into is double-buffered
+// (counts, list length, the slice counters), so the first workgroup can clear the other buffer at
+// once and nothing in this launch waits for anything else.
+struct DeltaParams {
+    const void* lq;
+    int64_t D;
+    int32_t K, KT, P, KC, G;
+    const unsigned long long* list;
+    const uint32_t* list_count;  // length of the list of the pass before
+    uint32_t* list_count_next;   // cleared: the following pass appends here
+    uint32_t* done;              // [slices] finished workgroups per slice, zero on entry
+    uint32_t* done_next;         // cleared for the next launch
+    double* base;
+    double* delta;
+    const int32_t* counts;       // of the pass before
+    int32_t* counts_next;        // cleared: the following pass counts here
+    float* cent;
+    uint16_t* packA;
+    double* norm_part;           // slices x K
+    double* inertia_slot;
+    unsigned long long* rep;
+};
+
+constexpr int kDeltaWaves = 8;
+constexpr int kDeltaSW = 64;  // channels per slice: one per lane
+
+template <typename T>
+__global__ __launch_bounds__(kDeltaWaves * kWave) void k_delta_prep(const DeltaParams q) {
+    extern __shared__ double s_panel[];  // KC x 64
+    __shared__ int s_flag;
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
+    const int slice = blockIdx.y, nslices = gridDim.y;
+    const int64_t ch = (int64_t)slice * kDeltaSW + lane;
+    const bool ch_ok = ch < q.D;
+    const int k0 = blockIdx.z * q.KC;
+    const int kc = (q.K - k0) < q.KC ? (q.K - k0) : q.KC;
+
+    const uint32_t len = *q.list_count;
+    if (blockIdx.x == 0 && blockIdx.y == 0 && blockIdx.z == 0) {  // the other halves of the double buffers
+        for (int k = threadIdx.x; k < q.K; k += blockDim.x) {
+            q.counts_next[k] = 0;
+            if (q.rep) q.rep[k] = ~0ull;
+        }
+        for (int s = threadIdx.x; s < nslices; s += blockDim.x) q.done_next[s] = 0;
+        if (threadIdx.x == 0) {
+            *q.list_count_next = 0;
+            if (q.inertia_slot) *q.inertia_slot = 0.0;
+        }
+    }
+    const uint32_t per = (len + q.G - 1) / q.G;
+    const uint32_t e0 = blockIdx.x * per;
+    const uint32_t e1 = (e0 + per < len) ? e0 + per : len;
+    if (e0 < e1) {
+        for (int i = threadIdx.x; i < kc * kDeltaSW; i += blockDim.x) s_panel[i] = 0.0;
+        __syncthreads();
+        // each wave takes a contiguous run of the share: 64 entries per load, then 8 rows in flight
+        const uint32_t pw = (e1 - e0 + kDeltaWaves - 1) / kDeltaWaves;
+        const uint32_t ws = e0 + wave * pw;
+        const uint32_t we = (ws + pw < e1) ? ws + pw : e1;
+        constexpr int RB = 8;
+        for (uint32_t b = ws; b < we; b += kWave) {
+            const unsigned long long ent = (b + lane < we) ? q.list[b + lane] : 0ull;
+            const uint32_t ent_lo = (uint32_t)ent, ent_hi = (uint32_t)(ent >> 32);
+            const int nb = (we - b) < (uint32_t)kWave ? (int)(we - b) : kWave;
+            for (int i0 = 0; i0 < nb; i0 += RB) {
+                int nw[RB], od[RB];
+                float x[RB];
+#pragma unroll
+                for (int u = 0; u < RB; u++) {
+                    nw[u] = od[u] = -1;
+                    x[u] = 0.f;
+                    if (i0 + u < nb) {
+                        const uint32_t lo = __builtin_amdgcn_readlane(ent_lo, i0 + u);
+                        const uint32_t hi = __builtin_amdgcn_readlane(ent_hi, i0 + u);
+                        const int64_t row = (int64_t)(((unsigned long long)hi << 8) | (lo >> 24));
+                        const int a = (int)(lo & 0xFFFu) - k0, c = (int)((lo >> 12) & 0xFFFu) - 1 - k0;
+                        nw[u] = (a >= 0 && a < kc) ? a : -1;
+                        od[u] = (c >= 0 && c < kc) ? c : -1;
+                        if ((nw[u] >= 0 || od[u] >= 0) && ch_ok) x[u] = ld_elem((const T*)q.lq + row * q.D + ch);
+                    }
+                }
+#pragma unroll
+                for (int u = 0; u < RB; u++) {
+                    if (nw[u] >= 0) atomicAdd(s_panel + nw[u] * kDeltaSW + lane, (double)x[u]);
+                    if (od[u] >= 0) atomicAdd(s_panel + od[u] * kDeltaSW + lane, -(double)x[u]);
+                }
+            }
+        }
+        __syncthreads();
+        for (int i = threadIdx.x; i < kc * kDeltaSW; i += blockDim.x) {
+            const int k = i / kDeltaSW, c = i - k * kDeltaSW;
+            const double v = s_panel[i];
+            const int64_t cg = (int64_t)slice * kDeltaSW + c;
+            if (v != 0.0 && cg < q.D) atomicAdd(q.delta + (int64_t)(k0 + k) * q.D + cg, v);
+        }
+    }
+
+    // ---- who finishes the slice? ----
+    // What crosses workgroups here (delta, the counter) goes through device-scope atomics, which
+    // are performed where every XCD sees them; waiting for this wave's own atomics to be
+    // acknowledged therefore orders them before the counter.  A device-scope fence would write
+    // back and invalidate the whole L2 once per workgroup, at several times the cost of the update.
+    __builtin_amdgcn_s_waitcnt(0);
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        const uint32_t total = gridDim.x * gridDim.z;
+        s_flag = atomicAdd(q.done + slice, 1u) == total - 1;
+    }
+    __syncthreads();
+    if (!s_flag) return;
+
+    // ---- this slice's centroids, operand parts, norm shares ----
+    for (int k = wave; k < q.K; k += kDeltaWaves) {
+        double nn = 0.0;
+        if (ch_ok) {
+            const int64_t i = (int64_t)k * q.D + ch;
+            const double S = q.base[i] + __hip_atomic_load(q.delta + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            q.base[i] = S;
+            q.delta[i] = 0.0;
+            const int n = q.counts[k];
+            float c;
+            if (n > 0) {
+                c = (float)(S / (double)n);
+                q.cent[i] = c;
+            } else {
+                c = q.cent[i];
+            }
+            nn = (double)c * (double)c;
+            const int t = k >> 4, m = k & 15;
+            const int cc = (int)(ch / kChunk), r = (int)(ch % kChunk);
+            const int s = r >> 5, g = (r >> 3) & 3, j = r & 7;
+            const int ol = g * 16 + m;
+            const uint32_t hw = pack_bf16(c, 0.f) & 0xFFFFu;
+            const size_t blk = ((size_t)(cc * 4 + s) * q.KT + t) * q.P;
+            q.packA[(blk * 64 + ol) * 8 + j] = (uint16_t)hw;
+            if (q.P == 2) {
+                const uint32_t lw = pack_bf16(c - lo_half(hw), 0.f) & 0xFFFFu;
+                q.packA[((blk + 1) * 64 + ol) * 8 + j] = (uint16_t)lw;
+            }
+        }
+        nn = wave_sum(nn);
+        if (lane == 0) q.norm_part[(size_t)slice * q.K + k] = nn;
     }
 }
 
@@ -93,7 +249,7 @@ static TileCfg tile_config(TileMode mode, int64_t D, int32_t K, cat_dtype dt) {
             t.off_rep = up16(off);
             off = t.off_rep + (size_t)K * 8;
             t.off_list = up16(off);
-            off = t.off_list + (lists ? (size_t)kListCap * 12 : 0);
+            off = t.off_list + (lists ? (size_t)kListCap * 8 : 0);
             t.off_misc = up16(off);
             off = t.off_misc + 16 + 8 * kMaxWaves;
             if (off > kLdsLimit) continue;
@@ -141,13 +297,77 @@ TileWs tile_carve(void* base, int64_t D, int32_t K, cat_dtype dt) {
     return w;
 }
 
-static cat_status launch_prep(cat_dtype dt, float* cent, double* base, double* delta, int32_t* counts, int64_t D,
-                              int32_t K, const TileCfg& c, const TileWs& ws, double* inertia_slot,
-                              unsigned long long* rep, hipStream_t st) {
+static inline int64_t delta_slices(int64_t D) { return (D + kDeltaSW - 1) / kDeltaSW; }
+
+static inline size_t lloyd_ctrl_words(int64_t D) { return (size_t)(2 + 2 * delta_slices(D)); }
+
+size_t lloyd_workspace_bytes(int64_t N, int64_t D, int32_t K) {
+    return a256((size_t)N * 8) + a256(lloyd_ctrl_words(D) * 4) + a256((size_t)delta_slices(D) * K * 8) +
+           a256((size_t)K * 4);
+}
+LloydWs lloyd_carve(void* base, int64_t N, int64_t D, int32_t K) {
+    LloydWs w;
+    w.bytes = lloyd_workspace_bytes(N, D, K);
+    if (!base) return w;
+    char* b = (char*)base;
+    w.list = (unsigned long long*)b;
+    b += a256((size_t)N * 8);
+    w.ctrl = (uint32_t*)b;
+    b += a256(lloyd_ctrl_words(D) * 4);
+    w.norm_part = (double*)b;
+    b += a256((size_t)delta_slices(D) * K * 8);
+    w.counts2 = (int32_t*)b;
+    return w;
+}
+
+// Sums update from the list of changed rows, then the centroid preparation of the next pass.
+// `par` is the parity of the pass that follows: it selects the halves of the double buffers.
+static cat_status launch_delta_prep(const void* lq, cat_dtype dt, int64_t D, int32_t K, const TileCfg& c,
+                                    const TileWs& ws, const LloydWs& lw, int par, float* cent, double* base,
+                                    double* delta, const int32_t* counts_prev, int32_t* counts_next,
+                                    double* inertia_slot, unsigned long long* rep, hipStream_t st) {
+    DeltaParams q = {};
+    q.lq = lq;
+    q.D = D;
+    q.K = K;
+    q.KT = c.KT;
+    q.P = c.P;
+    q.KC = K < 128 ? K : 128;  // LDS panel: KC x 64 doubles, at most 64 KB
+    const int64_t slices = delta_slices(D);
+    const int kchunks = (K + q.KC - 1) / q.KC;
+    int64_t G = 1024 / (slices * kchunks);  // about a thousand workgroups in all
+    q.G = (int32_t)(G < 1 ? 1 : (G > 256 ? 256 : G));
+    q.list = lw.list;
+    q.list_count = lw.ctrl + (par ^ 1);
+    q.list_count_next = lw.ctrl + par;
+    q.done = lw.ctrl + 2 + (size_t)par * slices;
+    q.done_next = lw.ctrl + 2 + (size_t)(par ^ 1) * slices;
+    q.base = base;
+    q.delta = delta;
+    q.counts = counts_prev;
+    q.counts_next = counts_next;
+    q.cent = cent;
+    q.packA = ws.packA;
+    q.norm_part = lw.norm_part;
+    q.inertia_slot = inertia_slot;
+    q.rep = rep;
+    dim3 grid((unsigned)q.G, (unsigned)slices, (unsigned)kchunks), block(kDeltaWaves * kWave);
+    const size_t lds = (size_t)q.KC * kDeltaSW * sizeof(double);
+    if (dt == CAT_BF16)
+        hipLaunchKernelGGL(k_delta_prep<bf16_t>, grid, block, lds, st, q);
+    else
+        hipLaunchKernelGGL(k_delta_prep<float>, grid, block, lds, st, q);
+    CAT_LAUNCH_CHECK("k_delta_prep");
+    return CAT_OK;
+}
+
+static cat_status launch_prep(cat_dtype dt, float* cent, double* base, double* delta, const int32_t* counts_read,
+                              int32_t* counts_reset, int64_t D, int32_t K, const TileCfg& c, const TileWs& ws,
+                              double* inertia_slot, unsigned long long* rep, hipStream_t st) {
     dim3 grid(c.KT * 16), block(256);
     (void)dt;
-    hipLaunchKernelGGL(k_tile_prep, grid, block, 0, st, cent, base, delta, counts, D, K, c.KT, c.P, c.nchunks, ws.packA,
-                       ws.cnorm, inertia_slot, rep);
+    hipLaunchKernelGGL(k_tile_prep, grid, block, 0, st, cent, base, delta, counts_read, counts_reset, D, K, c.KT, c.P,
+                       c.nchunks, ws.packA, ws.cnorm, inertia_slot, rep);
     CAT_LAUNCH_CHECK("k_tile_prep");
     return CAT_OK;
 }
@@ -203,7 +423,7 @@ cat_status tile_assign(const void* lq, cat_dtype dt, int64_t N, int64_t D, int32
     if (!c.ok) return set_error(CAT_ERR_UNSUPPORTED, "tile kernels do not fit D=%lld K=%d", (long long)D, (int)K);
     cat_status s = launch_copy_words(cent, ws.cent, (int64_t)K * D, st);
     if (s != CAT_OK) return s;
-    s = launch_prep(dt, ws.cent, nullptr, nullptr, nullptr, D, K, c, ws, nullptr, nullptr, st);
+    s = launch_prep(dt, ws.cent, nullptr, nullptr, nullptr, nullptr, D, K, c, ws, nullptr, nullptr, st);
     if (s != CAT_OK) return s;
     TileParams p = base_params(lq, N, D, K, c, ws, dt);
     p.cent = ws.cent;
@@ -219,7 +439,7 @@ cat_status tile_assign(const void* lq, cat_dtype dt, int64_t N, int64_t D, int32
 
 cat_status tile_lloyd(const void* lq, cat_dtype dt, int64_t N, int64_t D, int32_t K, int32_t iters,
                       float* cent_io, double* sums, int32_t* assign, int32_t* counts, double* inertia,
-                      unsigned long long* rep, const TileWs& ws, hipStream_t st) {
+                      unsigned long long* rep, const TileWs& ws, const LloydWs& lw, hipStream_t st) {
     TileCfg c = tile_config(TILE_LLOYD, D, K, dt);
     if (!c.ok) return set_error(CAT_ERR_UNSUPPORTED, "tile kernels do not fit D=%lld K=%d", (long long)D, (int)K);
     const size_t KD = (size_t)K * (size_t)D;
@@ -234,22 +454,38 @@ cat_status tile_lloyd(const void* lq, cat_dtype dt, int64_t N, int64_t D, int32_
     TileParams p = base_params(lq, N, D, K, c, ws, dt);
     p.cent = cent_io;
     p.assign = assign;
-    p.counts = counts;
+    if (iters > 1) CAT_T(launch_fill_zero(lw.ctrl, lloyd_ctrl_words(D) * 4, st));
+    // Pass 0 assigns with the initial centroids and is followed by one full segmented sum; every
+    // later pass lists the rows that changed cluster, and the launch between two passes moves just
+    // those rows between the running sums and prepares the next centroids (k_delta_prep; before
+    // pass 1 there is no list yet and k_tile_prep does the preparation).  The last pass only assigns.
+    // Counts alternate between two buffers so that a pass never accumulates into the buffer the
+    // preparation before it reads; the last pass uses the caller's.
+    int32_t* cb[2] = {counts, lw.counts2};
     for (int32_t t = 0; t <= iters; t++) {
         const bool last = t == iters;
-        // centroids of this pass: the initial ones, or the running sums over the counts of the last pass;
-        // the same launch resets what this pass accumulates into
-        CAT_T(launch_prep(dt, cent_io, t ? base : nullptr, t ? delta : nullptr, counts, D, K, c, ws,
-                          inertia ? inertia + t : nullptr, last ? rep : nullptr, st));
-        p.inertia = inertia ? inertia + t : nullptr;
+        double* slot = inertia ? inertia + t : nullptr;
+        int32_t* cnt_t = cb[(iters - t) & 1];
+        const int32_t* cnt_prev = cb[(iters - t + 1) & 1];
+        if (t <= 1)
+            CAT_T(launch_prep(dt, cent_io, t ? base : nullptr, t ? delta : nullptr, t ? cnt_prev : nullptr, cnt_t, D, K, c,
+                              ws, slot, last ? rep : nullptr, st));
+        else
+            CAT_T(launch_delta_prep(lq, dt, D, K, c, ws, lw, t & 1, cent_io, base, delta, cnt_prev, cnt_t, slot,
+                                    last ? rep : nullptr, st));
+        p.norm_part = t >= 2 ? lw.norm_part : nullptr;
+        p.norm_slices = t >= 2 ? (int32_t)delta_slices(D) : 0;
+        p.counts = cnt_t;
+        p.inertia = slot;
         p.rep = last ? rep : nullptr;  // the final pass describes the partition that is returned
-        p.delta = (t > 0 && !last) ? delta : nullptr;
-        p.delta_mode = p.delta ? 1 : 0;
+        p.list = (t > 0 && !last) ? lw.list : nullptr;
+        p.list_count = lw.ctrl + (t & 1);
+        p.delta_mode = p.list ? 1 : 0;
         // alternate the scan direction: the rows a pass reads last are the ones most likely still in
         // the memory-side cache when the next pass starts
         p.reverse = t & 1;
         CAT_T(launch_tile(p, c, dt, st));
-        if (t == 0 && iters > 0) {  // first full sums: one segmented pass; later passes only move the changed rows
+        if (t == 0 && iters > 0) {  // first full sums: one segmented pass
             CAT_T(launch_fill_zero(sums, 2 * KD * sizeof(double), st));
             CAT_T(launch_segsum(1, lq, nullptr, dt, assign, N, D, K, nullptr, nullptr, base, st));
         }

@@ -16,7 +16,7 @@
 //
 //   assign      writes assignments (+ counts, objective, first row of each cluster)
 //   lloyd       assign + the rows that changed cluster since the previous pass are
-//               added to / subtracted from the running per-cluster sums
+//               listed (row, old, new) for the sums update that follows (k_delta_prep)
 //   apply       assign + corrected = gamma[a] * x + beta[a] in the same pass
 #pragma once
 #include <type_traits>
@@ -34,8 +34,7 @@ typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 constexpr int kRows = 16;          // rows per wave tile (the N of the 16x16x32 MFMA)
 constexpr int kChunk = 128;        // channels per pipeline stage (4 MFMA steps of 32)
 constexpr int kMaxWaves = 8;
-constexpr int kListCap = 1024;     // changed rows a workgroup can defer per launch
-constexpr int kDirectRows = 8;     // up to this many deferred rows skip the LDS panel
+constexpr int kListCap = 1024;     // changed rows a workgroup collects in LDS before they go to the global list
 constexpr size_t kLdsLimit = 160 * 1024;
 constexpr float kPadNorm = 3.0e38f;
 
@@ -47,13 +46,16 @@ struct TileParams {
     int32_t K, K16, nchunks, waves;
     int64_t ntiles;
     const uint16_t* packA;   // [chunk][step][ktile][part][lane][8] bf16
-    const float* cnorm;      // K16
+    const float* cnorm;      // K16 squared centroid norms, or (norm_slices > 0) their per-slice shares:
+    const double* norm_part; //   norm_slices x K doubles, added up here in slice order
+    int32_t norm_slices;
     const float* cent;       // K x D fp32 (exact re-rank)
     int32_t* assign;         // nullable (apply)
     int32_t* counts;         // nullable
     double* inertia;         // nullable
     unsigned long long* rep; // nullable
-    double* delta;           // K x D, lloyd delta mode only
+    unsigned long long* list;  // lloyd: rows that changed cluster, (row << 24) | ((old + 1) << 12) | new
+    uint32_t* list_count;      // entries in list (appended to with atomics)
     int32_t delta_mode;      // 0: off, 1: rows carry a previous assignment
     int32_t reverse;         // walk the tiles from the last to the first (see tile_lloyd)
     const float* gamma;      // apply
@@ -427,30 +429,26 @@ __device__ __forceinline__ void finish_tile(const TileParams& p, unsigned char* 
         if (p.rep) atomicMin(&s_rep[idx], (unsigned long long)(row0 + n));
         in_acc += (double)dmin;
     }
-    if (p.delta) {
+    if (p.list) {
+        // rows that changed cluster: into the workgroup's LDS list; when that is full, straight to
+        // the global list (one reservation per tile)
         const bool changed = owner && prev != idx;
+        const unsigned long long entry =
+            ((unsigned long long)(row0 + n) << 24) | ((unsigned long long)(prev + 1) << 12) | (unsigned long long)idx;
         bool ovf = false;
         if (changed) {
             int pos = atomicAdd(&s_misc[0], 1);
-            if (pos < kListCap) {
-                ((int64_t*)(smem + p.off_list))[pos] = row0 + n;
-                ((uint32_t*)(smem + p.off_list + (size_t)kListCap * 8))[pos] = ((uint32_t)(prev + 1) << 16) | (uint32_t)idx;
-            } else {
+            if (pos < kListCap)
+                ((unsigned long long*)(smem + p.off_list))[pos] = entry;
+            else
                 ovf = true;
-            }
         }
-        unsigned long long om = __ballot(ovf);
-        while (om) {  // list full: this row goes straight to the global sums
-            const int r = __builtin_amdgcn_readfirstlane(__builtin_ctzll(om));
-            om &= om - 1;
-            const int nw = __builtin_amdgcn_readlane(idx, r), od = __builtin_amdgcn_readlane(prev, r);
-            const int64_t row = row0 + r;
-            for (int64_t ch = lane; ch < p.D; ch += kWave) {
-                double x = BF16 ? (double)bf16_to_f32(((const bf16_t*)p.lq)[row * p.D + ch])
-                                : (double)((const float*)p.lq)[row * p.D + ch];
-                atomicAdd(p.delta + (int64_t)nw * p.D + ch, x);
-                if (od >= 0) atomicAdd(p.delta + (int64_t)od * p.D + ch, -x);
-            }
+        const unsigned long long om = __ballot(ovf);
+        if (om) {
+            uint32_t base = 0;
+            if (lane == 0) base = atomicAdd(p.list_count, (uint32_t)__builtin_popcountll(om));
+            base = __builtin_amdgcn_readfirstlane(base);
+            if (ovf) p.list[base + __builtin_popcountll(om & ((1ull << lane) - 1ull))] = entry;
         }
     }
 }
@@ -473,13 +471,12 @@ __global__ __launch_bounds__(kMaxWaves * kWave) void k_tile(const TileParams p) 
     int tl = tile0, cl = 0;  // load cursor
     float cmax_out;
     ChunkRegs<BF16> b0, b1, b2;
-    // Chunk loads are never conditional: once the cursor has run past the wave's last tile it keeps
-    // re-reading that tile (cache hits, results unused).  A load that is issued on one path only
-    // would make every later wait count as if it had not been issued, which drains the pipeline.
-    const int tlast = __builtin_amdgcn_readfirstlane(tile0 < ntiles ? tile0 + (ntiles - 1 - tile0) / tstride * tstride : ntiles - 1);
+    // A wave stops requesting rows once its cursor has passed its last tile.  (Requesting them
+    // unconditionally, the last tile again, lets the compiler count on two chunks in flight at
+    // every wait instead of draining to one; measured, that was 2-5 % slower, not faster.)
 #define CAT_ISSUE(buf)                                                                     \
-    {                                                                                      \
-        load_chunk<BF16, MODE == MODE_ASSIGN>(buf, p, tl < tlast ? tl : tlast, cl, lane);  \
+    if (tl < ntiles) {                                                                     \
+        load_chunk<BF16, MODE == MODE_ASSIGN>(buf, p, tl, cl, lane);                       \
         if (++cl == p.nchunks) {                                                           \
             cl = 0;                                                                        \
             tl += tstride;                                                                 \
@@ -501,9 +498,27 @@ __global__ __launch_bounds__(kMaxWaves * kWave) void k_tile(const TileParams p) 
 #pragma unroll
             for (int u = 0; u < 8; u++) t[u] = src[i + u * nt];
         }
-        const float cn_mine = (int)threadIdx.x < p.K16 ? p.cnorm[threadIdx.x] : 0.f;
-        float cm2 = 0.f;  // largest centroid norm: every wave reduces the table for itself
-        for (int k = lane; k < p.K; k += kWave) cm2 = fmaxf(cm2, p.cnorm[k]);
+        float cn_mine = 0.f;
+        if ((int)threadIdx.x < p.K16) {
+            if (p.norm_slices > 0) {
+                double nn = 0.0;
+                if ((int)threadIdx.x < p.K) {
+                    const double* np = p.norm_part + threadIdx.x;
+                    int sl = 0;
+                    for (; sl + 8 <= p.norm_slices; sl += 8) {  // eight loads in flight, added in slice order
+                        double v[8];
+#pragma unroll
+                        for (int u = 0; u < 8; u++) v[u] = np[(size_t)(sl + u) * p.K];
+#pragma unroll
+                        for (int u = 0; u < 8; u++) nn += v[u];
+                    }
+                    for (; sl < p.norm_slices; sl++) nn += np[(size_t)sl * p.K];
+                }
+                cn_mine = (int)threadIdx.x < p.K ? (float)nn : kPadNorm;
+            } else {
+                cn_mine = p.cnorm[threadIdx.x];
+            }
+        }
         CAT_ISSUE(b0)
         CAT_ISSUE(b1)
         if (first) {
@@ -524,12 +539,16 @@ __global__ __launch_bounds__(kMaxWaves * kWave) void k_tile(const TileParams p) 
             s_rep[k] = ~0ull;
         }
         if (threadIdx.x == 0) s_misc[0] = 0;
+    }
+    __syncthreads();
+    {
+        float cm2 = 0.f;  // largest centroid norm: every wave reduces the table for itself
+        for (int k = lane; k < p.K; k += kWave) cm2 = fmaxf(cm2, s_cnorm[k]);
 #pragma unroll
         for (int o = 32; o > 0; o >>= 1) cm2 = fmaxf(cm2, __shfl_xor(cm2, o, kWave));
         cmax_out = sqrtf(cm2);
     }
     const float cmax = cmax_out;
-    __syncthreads();
 
     double in_acc = 0.0;
 
@@ -644,67 +663,16 @@ __global__ __launch_bounds__(kMaxWaves * kWave) void k_tile(const TileParams p) 
         for (int w = 0; w < p.waves; w++) tot += s_in[w];
         atomicAdd(p.inertia, tot);
     }
-    if (!p.delta) return;
+    if (!p.list) return;
 
-    // deferred sums of the rows that changed cluster: the centroid operand is dead now,
-    // its LDS becomes a K x CW panel of doubles, filled panel by panel over the channels
+    // the workgroup's changed rows join the global list: one reservation, then a coalesced copy
     const int cnt = s_misc[0] < kListCap ? s_misc[0] : kListCap;
     if (cnt == 0) return;  // uniform: s_misc[0] is final after the barrier above
-    const int64_t* l_row = (const int64_t*)(smem + p.off_list);
-    const uint32_t* l_on = (const uint32_t*)(smem + p.off_list + (size_t)kListCap * 8);
-    double* S = (double*)smem;
-    // panel width: everything below the norm table is free now
-    int CW = (int)((p.off_cnorm / 8 / p.K) & ~63u);
-    if (CW > 1024) CW = 1024;
-    if (cnt <= kDirectRows || CW == 0) {
-        // a handful of rows (the usual case once Lloyd has nearly converged), or no room for a
-        // panel: one wave per row, all loads first, then straight to the global sums
-        for (int e = wave; e < cnt; e += p.waves) {
-            const int64_t row = l_row[e];
-            const int nw = (int)(l_on[e] & 0xFFFFu), od = (int)(l_on[e] >> 16) - 1;
-            for (int64_t c0 = 0; c0 < p.D; c0 += 16 * kWave) {
-                float x[16];
-#pragma unroll
-                for (int u = 0; u < 16; u++) {
-                    const int64_t ch = c0 + u * kWave + lane;
-                    x[u] = ch < p.D ? (BF16 ? bf16_to_f32(((const bf16_t*)p.lq)[row * p.D + ch])
-                                            : ((const float*)p.lq)[row * p.D + ch])
-                                    : 0.f;
-                }
-#pragma unroll
-                for (int u = 0; u < 16; u++) {
-                    const int64_t ch = c0 + u * kWave + lane;
-                    if (ch < p.D) {
-                        atomicAdd(p.delta + (int64_t)nw * p.D + ch, (double)x[u]);
-                        if (od >= 0) atomicAdd(p.delta + (int64_t)od * p.D + ch, -(double)x[u]);
-                    }
-                }
-            }
-        }
-        return;
-    }
-    for (int64_t base = 0; base < p.D; base += CW) {
-        const int cw = (p.D - base) < CW ? (int)(p.D - base) : CW;
-        __syncthreads();
-        for (int i = threadIdx.x; i < p.K * CW; i += blockDim.x) S[i] = 0.0;
-        __syncthreads();
-        for (int e = wave; e < cnt; e += p.waves) {
-            const int64_t row = l_row[e];
-            const int nw = (int)(l_on[e] & 0xFFFFu), od = (int)(l_on[e] >> 16) - 1;
-            for (int c = lane; c < cw; c += kWave) {
-                double x = BF16 ? (double)bf16_to_f32(((const bf16_t*)p.lq)[row * p.D + base + c])
-                                : (double)((const float*)p.lq)[row * p.D + base + c];
-                atomicAdd(S + (size_t)nw * CW + c, x);
-                if (od >= 0) atomicAdd(S + (size_t)od * CW + c, -x);
-            }
-        }
-        __syncthreads();
-        for (int i = threadIdx.x; i < p.K * CW; i += blockDim.x) {
-            const int k = i / CW, c = i - k * CW;
-            const double v = S[i];
-            if (c < cw && v != 0.0) atomicAdd(p.delta + (int64_t)k * p.D + base + c, v);
-        }
-    }
+    if (threadIdx.x == 0) s_misc[1] = (int)atomicAdd(p.list_count, (uint32_t)cnt);
+    __syncthreads();
+    const uint32_t base = (uint32_t)s_misc[1];
+    const unsigned long long* l_ent = (const unsigned long long*)(smem + p.off_list);
+    for (int i = threadIdx.x; i < cnt; i += blockDim.x) p.list[base + i] = l_ent[i];
 }
 
 // ---- variant chosen on the host (cat_tile.hip: tile_config) ------------------------------------
