@@ -30,6 +30,7 @@ static std::vector<hipEvent_t> g_prof_ev;  // pairs (begin, end), reused across 
 static size_t g_prof_used = 0;             // events recorded since the last enable
 
 bool profile_on() { return g_prof; }
+bool fast_paths_forced() { return g_path.load() == CAT_PATH_TILE; }
 
 cat_status profile_mark(bool begin, hipStream_t st) {
     (void)begin;
@@ -69,6 +70,7 @@ struct FitWs {
     double* inertia;          // 1
     TileWs tile;              // scratch of the MFMA tile kernels
     LloydWs lloyd;            // changed-row list and counters of the fused Lloyd loop
+    uint32_t* sort;           // N + 2 K + 2  rows ordered by cluster, for the segmented sums
     size_t bytes;
 };
 
@@ -85,11 +87,13 @@ static FitWs carve_fit(void* base, int64_t N, int64_t D, int32_t K, cat_dtype dt
     w.rep = c.take<unsigned long long>(K);
     w.idx = c.take<int64_t>(K);
     w.inertia = c.take<double>(1);
+    w.sort = c.take<uint32_t>(sort_workspace_words(N, K));
     size_t tb = tile_workspace_bytes(D, K, dt);
     w.tile = tile_carve(base ? (void*)(c.base + c.off) : nullptr, D, K, dt);
     c.off += align256(tb);
     if (tb) {
         w.lloyd = lloyd_carve(base ? (void*)(c.base + c.off) : nullptr, N, D, K);
+        w.lloyd.sort_ws = w.sort;
         c.off += align256(w.lloyd.bytes);
     }
     w.bytes = c.off;
@@ -169,9 +173,13 @@ static cat_status step_assign(const void* lq, cat_dtype dt, int64_t N, int64_t D
 }
 
 static cat_status step_update(const void* lq, cat_dtype dt, const int32_t* assign, int64_t N, int64_t D, int32_t K,
-                              const int32_t* counts, const float* prev, float* cent, double* acc, hipStream_t st) {
+                              const int32_t* counts, const float* prev, float* cent, double* acc, uint32_t* sort_ws,
+                              hipStream_t st) {
     CAT_TRY(launch_fill_zero(acc, (size_t)K * D * sizeof(double), st));
-    CAT_TRY(launch_segsum(1, lq, nullptr, dt, assign, N, D, K, nullptr, nullptr, acc, st));
+    if (segsum_sorted_supported(1, N, D, dt))
+        CAT_TRY(launch_segsum_sorted(1, lq, nullptr, dt, assign, counts, N, D, K, nullptr, nullptr, acc, sort_ws, st));
+    else
+        CAT_TRY(launch_segsum(1, lq, nullptr, dt, assign, N, D, K, nullptr, nullptr, acc, st));
     return launch_finalize_centroids(acc, counts, prev, cent, D, K, st);
 }
 
@@ -180,7 +188,10 @@ static cat_status step_stats(const void* lq, const void* fp, cat_dtype dt, const
                              const FitWs& w, float* gamma, float* beta, hipStream_t st) {
     CAT_TRY(launch_gather_pivots(lq, fp, dt, D, K, rep, hint, w.pivx, w.pivy, st));
     CAT_TRY(launch_fill_zero(w.acc, (size_t)4 * K * D * sizeof(double), st));
-    CAT_TRY(launch_segsum(4, lq, fp, dt, assign, N, D, K, w.pivx, w.pivy, w.acc, st));
+    if (segsum_sorted_supported(4, N, D, dt))
+        CAT_TRY(launch_segsum_sorted(4, lq, fp, dt, assign, counts, N, D, K, w.pivx, w.pivy, w.acc, w.sort, st));
+    else
+        CAT_TRY(launch_segsum(4, lq, fp, dt, assign, N, D, K, w.pivx, w.pivy, w.acc, st));
     return launch_finalize_affine(w.acc, counts, w.pivx, w.pivy, gamma, beta, D, K, st);
 }
 
@@ -275,7 +286,7 @@ cat_status cat_update(const void* lq, const int32_t* assignments, int64_t N, int
     CAT_TRY(launch_fill_zero(w.counts, (size_t)K * sizeof(int32_t), st));
     CAT_TRY(launch_fill_u64(w.rep, K, ~0ull, st));
     CAT_TRY(launch_count_rep(assignments, N, K, w.counts, w.rep, st));
-    CAT_TRY(step_update(lq, dt, assignments, N, D, K, w.counts, prev_centroids, centroids, w.acc, st));
+    CAT_TRY(step_update(lq, dt, assignments, N, D, K, w.counts, prev_centroids, centroids, w.acc, w.sort, st));
     if (counts) CAT_TRY(launch_copy_words(w.counts, counts, K, st));
     return CAT_OK;
 }
@@ -342,7 +353,7 @@ cat_status cat_fit(const void* lq, const void* fp, int64_t N, int64_t D, int32_t
             CAT_TRY(step_assign(lq, dt, N, D, K, w.cent[cur], assignments, w.counts, inertia ? w.inertia : nullptr,
                                 nullptr, w.tile, st));
             if (inertia) CAT_TRY(launch_copy_words(w.inertia, inertia + t, 2, st));
-            CAT_TRY(step_update(lq, dt, assignments, N, D, K, w.counts, w.cent[cur], w.cent[cur ^ 1], w.acc, st));
+            CAT_TRY(step_update(lq, dt, assignments, N, D, K, w.counts, w.cent[cur], w.cent[cur ^ 1], w.acc, w.sort, st));
             cur ^= 1;
         }
         // final assignment against the final centroids

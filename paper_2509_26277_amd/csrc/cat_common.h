@@ -89,6 +89,18 @@ cat_status launch_count_rep(const int32_t* assign, int64_t N, int32_t K, int32_t
 cat_status launch_segsum(int nq, const void* lq, const void* fp, cat_dtype dt, const int32_t* assign,
                          int64_t N, int64_t D, int32_t K, const float* pivx, const float* pivy,
                          double* acc, hipStream_t st);
+// The same sums over rows that were first ordered by cluster (a counting sort on the assignments,
+// given the cluster sizes): each wave then keeps its sums in registers and touches memory only when
+// the cluster changes.  Scratch: N + 2 K + 2 words (sort_workspace_words).  segsum_sorted_supported
+// says whether the shape qualifies (16-byte channel groups, N below 2^31) and gains; otherwise use launch_segsum.
+bool segsum_sorted_supported(int nq, int64_t N, int64_t D, cat_dtype dt);
+// cat_select_path(CAT_PATH_TILE) is in force: take the tile / sorted kernels wherever they can run,
+// whatever the size heuristics say (this is how the tests reach them on small shapes)
+bool fast_paths_forced();
+size_t sort_workspace_words(int64_t N, int32_t K);
+cat_status launch_segsum_sorted(int nq, const void* lq, const void* fp, cat_dtype dt, const int32_t* assign,
+                                const int32_t* counts, int64_t N, int64_t D, int32_t K, const float* pivx,
+                                const float* pivy, double* acc, uint32_t* sort_ws, hipStream_t st);
 cat_status launch_finalize_centroids(const double* sums, const int32_t* counts, const float* prev,
                                      float* cent, int64_t D, int32_t K, hipStream_t st);
 // pivx = hint (if given) else lq[rep[k]]; pivy = fp[rep[k]]; rows of empty clusters are zero

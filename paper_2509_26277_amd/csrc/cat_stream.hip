@@ -358,6 +358,275 @@ cat_status launch_segsum(int nq, const void* lq, const void* fp, cat_dtype dt, c
 }
 
 // ---------------------------------------------------------------------------------
+// segmented sums over rows ordered by cluster
+// ---------------------------------------------------------------------------------
+// offs[k] = number of rows in clusters below k (offs[K] = all labelled rows); cursor[k] = offs[k]
+__global__ __launch_bounds__(1024) void k_sort_offsets(const int32_t* __restrict__ counts, int32_t K,
+                                                       uint32_t* __restrict__ offs, uint32_t* __restrict__ cursor) {
+    __shared__ uint32_t s[1024];
+    const int t = threadIdx.x;
+    const uint32_t mine = t < K ? (uint32_t)counts[t] : 0u;
+    s[t] = mine;
+    __syncthreads();
+    for (int o = 1; o < 1024; o <<= 1) {
+        uint32_t v = t >= o ? s[t - o] : 0u;
+        __syncthreads();
+        s[t] += v;
+        __syncthreads();
+    }
+    if (t < K) {
+        offs[t] = s[t] - mine;
+        cursor[t] = s[t] - mine;
+    }
+    if (t == K - 1) offs[K] = s[t];
+}
+
+// perm[offs[k] ..] = the rows of cluster k (in no particular order)
+constexpr int kSortRowsPerThread = 8;
+__global__ __launch_bounds__(256) void k_sort_scatter(const int32_t* __restrict__ assign, int64_t N, int32_t K,
+                                                      uint32_t* __restrict__ cursor, uint32_t* __restrict__ perm) {
+    __shared__ uint32_t s_cnt[CAT_MAX_K];  // rows of this block per cluster, then their first position
+    for (int k = threadIdx.x; k < K; k += blockDim.x) s_cnt[k] = 0;
+    __syncthreads();
+    const int64_t r0 = ((int64_t)blockIdx.x * blockDim.x) * kSortRowsPerThread + threadIdx.x;
+    int a[kSortRowsPerThread];
+    uint32_t rank[kSortRowsPerThread];
+#pragma unroll
+    for (int u = 0; u < kSortRowsPerThread; u++) {
+        const int64_t r = r0 + (int64_t)u * blockDim.x;
+        a[u] = r < N ? assign[r] : -1;
+        if (a[u] < 0 || a[u] >= K) a[u] = -1;  // rows with a label outside [0, K) are left out, as in the counts
+    }
+#pragma unroll
+    for (int u = 0; u < kSortRowsPerThread; u++)
+        if (a[u] >= 0) rank[u] = atomicAdd(&s_cnt[a[u]], 1u);
+    __syncthreads();
+    for (int k = threadIdx.x; k < K; k += blockDim.x) {
+        const uint32_t c = s_cnt[k];
+        if (c) s_cnt[k] = atomicAdd(&cursor[k], c);
+    }
+    __syncthreads();
+#pragma unroll
+    for (int u = 0; u < kSortRowsPerThread; u++)
+        if (a[u] >= 0) perm[s_cnt[a[u]] + rank[u]] = (uint32_t)(r0 + (int64_t)u * blockDim.x);
+}
+
+// One wave per (run of R positions of the ordered rows) x (64 V channels, V = channels per 16-byte
+// group).  The sums of the current cluster live in registers (doubles); when the run crosses into
+// the next cluster, and at its end, they are added to acc with atomics.
+constexpr int kSortWaves = 4;
+template <typename T, int NQ>
+__global__ __launch_bounds__(kSortWaves * kWave) void k_segsum_sorted(
+    const T* __restrict__ lq, const T* __restrict__ fp, const uint32_t* __restrict__ perm,
+    const uint32_t* __restrict__ offs, int64_t D, int32_t K, int32_t R, int32_t nsl, int64_t nitems,
+    const float* __restrict__ pivx, const float* __restrict__ pivy, double* __restrict__ acc) {
+    constexpr int V = sizeof(T) == 2 ? 8 : 4;
+    constexpr int RB = 4;  // rows per round; two rounds are in flight
+    __shared__ uint32_t s_offs[CAT_MAX_K + 1];
+    for (int k = threadIdx.x; k <= K; k += blockDim.x) s_offs[k] = offs[k];
+    __syncthreads();
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
+    const int64_t item = (int64_t)blockIdx.x * kSortWaves + wave;
+    if (item >= nitems) return;
+    const int slice = (int)(item % nsl);
+    const uint32_t total = s_offs[K];
+    const uint32_t p0 = (uint32_t)(item / nsl) * (uint32_t)R;
+    const uint32_t p1 = (p0 + (uint32_t)R < total) ? p0 + (uint32_t)R : total;
+    if (p0 >= p1) return;
+    const int64_t c0 = (int64_t)slice * (kWave * V) + (int64_t)lane * V;
+    const bool on = c0 < D;  // D is a multiple of V: a lane's group is inside or outside as a whole
+    const int64_t KD = (int64_t)K * D;
+
+    // cluster of position p0: the last k with offs[k] <= p0
+    int k = 0;
+    {
+        int lo = 0, hi = K - 1;
+        while (lo < hi) {
+            const int mid = (lo + hi + 1) >> 1;
+            if (s_offs[mid] <= p0) lo = mid; else hi = mid - 1;
+        }
+        k = lo;
+    }
+    uint32_t nextb = s_offs[k + 1];
+    double sx[V], sy[V], sxx[V], sxy[V];
+    float px[V], py[V];
+#pragma unroll
+    for (int v = 0; v < V; v++) {
+        sx[v] = sy[v] = sxx[v] = sxy[v] = 0.0;
+        px[v] = py[v] = 0.f;
+    }
+    auto load_piv = [&]() {
+        if (NQ == 4 && on) {
+#pragma unroll
+            for (int v = 0; v < V; v++) {
+                px[v] = pivx[(int64_t)k * D + c0 + v];
+                py[v] = pivy[(int64_t)k * D + c0 + v];
+            }
+        }
+    };
+    auto flush = [&]() {
+        if (on) {
+            double* o = acc + (int64_t)k * D + c0;
+#pragma unroll
+            for (int v = 0; v < V; v++) {
+                atomicAdd(o + v, sx[v]);
+                if (NQ == 4) {
+                    atomicAdd(o + KD + v, sy[v]);
+                    atomicAdd(o + 2 * KD + v, sxx[v]);
+                    atomicAdd(o + 3 * KD + v, sxy[v]);
+                }
+                sx[v] = sy[v] = sxx[v] = sxy[v] = 0.0;
+            }
+        }
+    };
+    load_piv();
+
+    // Rounds of RB rows, two register buffers: the loads of round r + 1 are requested before round r
+    // is added up (each round is a gather of RB rows from anywhere in the matrix, a full memory
+    // round trip).  The row numbers come 64 at a time (one per lane), one batch ahead.
+    typedef __attribute__((ext_vector_type(4))) uint32_t u4;
+    const uint32_t n = p1 - p0;
+    const int nr = (int)((n + RB - 1) / RB);
+    uint32_t cur = perm[p0 + ((uint32_t)lane < n ? lane : n - 1)];
+    uint32_t nxt = (n > (uint32_t)kWave) ? perm[p0 + (kWave + (uint32_t)lane < n ? kWave + lane : n - 1)] : 0u;
+    auto advance = [&](int r) {  // entering round r: cur / nxt hold the batch of round r and the one after
+        if (r > 0 && ((r * RB) & (kWave - 1)) == 0) {
+            cur = nxt;
+            const uint32_t nb0 = (uint32_t)(r * RB) + kWave;  // first position of the batch after this one
+            nxt = nb0 < n ? perm[p0 + (nb0 + lane < n ? nb0 + lane : n - 1)] : 0u;
+        }
+    };
+    auto issue = [&](int r, int rcur, u4 (&xv)[RB], u4 (&yv)[RB]) {  // rcur: the round being entered
+        const uint32_t src = ((r * RB) >> 6) == ((rcur * RB) >> 6) ? cur : nxt;
+#pragma unroll
+        for (int u = 0; u < RB; u++) {
+            uint32_t i = (uint32_t)(r * RB + u);
+            if (i >= n) i = n - 1;  // past the end: the last row again, unused
+            const int64_t row = (int64_t)__builtin_amdgcn_readlane(src, (int)(i & (kWave - 1)));
+            if (on) {
+                xv[u] = *(const u4*)(lq + row * D + c0);
+                if (NQ == 4) yv[u] = *(const u4*)(fp + row * D + c0);
+            }
+        }
+    };
+    auto consume = [&](int r, const u4 (&xv)[RB], const u4 (&yv)[RB]) {
+#pragma unroll
+        for (int u = 0; u < RB; u++) {
+            const uint32_t i = (uint32_t)(r * RB + u);
+            if (i >= n) break;
+            const uint32_t pos = p0 + i;
+            if (pos >= nextb) {  // wave-uniform: the run enters another cluster
+                flush();
+                do {
+                    k++;
+                    nextb = s_offs[k + 1];
+                } while (pos >= nextb);
+                load_piv();
+            }
+            if (on) {
+#pragma unroll
+                for (int v = 0; v < V; v++) {
+                    float x, y = 0.f;
+                    if (sizeof(T) == 2) {
+                        const uint32_t wx = xv[u][v >> 1];
+                        x = (v & 1) ? __uint_as_float(wx & 0xFFFF0000u) : __uint_as_float(wx << 16);
+                        if (NQ == 4) {
+                            const uint32_t wy = yv[u][v >> 1];
+                            y = (v & 1) ? __uint_as_float(wy & 0xFFFF0000u) : __uint_as_float(wy << 16);
+                        }
+                    } else {
+                        x = __uint_as_float(xv[u][v & 3]);
+                        if (NQ == 4) y = __uint_as_float(yv[u][v & 3]);
+                    }
+                    if (NQ == 1) {
+                        sx[v] += (double)x;
+                    } else {
+                        // the shifts keep the raw second moments close to the centred ones
+                        const float xs = x - px[v], ys = y - py[v];
+                        sx[v] += (double)xs;
+                        sy[v] += (double)ys;
+                        sxx[v] = fma((double)xs, (double)xs, sxx[v]);
+                        sxy[v] = fma((double)xs, (double)ys, sxy[v]);
+                    }
+                }
+            }
+        }
+    };
+    u4 xa[RB], ya[RB], xb[RB], yb[RB];
+    issue(0, 0, xa, ya);
+    for (int r = 0; r < nr; r += 2) {
+        advance(r);
+        if (r + 1 < nr) issue(r + 1, r, xb, yb);
+        consume(r, xa, ya);
+        if (r + 1 >= nr) break;
+        advance(r + 1);
+        if (r + 2 < nr) issue(r + 2, r + 1, xa, ya);
+        consume(r + 1, xb, yb);
+    }
+    flush();
+}
+
+bool segsum_sorted_supported(int nq, int64_t N, int64_t D, cat_dtype dt) {
+    if (N >= ((int64_t)1 << 31) || D % (dt == CAT_BF16 ? 8 : 4)) return false;
+    // Where it pays (measured): always for bf16 rows (the LDS-panel kernel reads them two bytes per
+    // lane); for fp32 rows only for the four-quantity statistics of a large matrix.  The plain sums of
+    // fp32 rows, and small matrices, are faster in launch_segsum, which reads the rows in order.
+    if (dt == CAT_BF16 || fast_paths_forced()) return true;
+    return nq == 4 && N * D >= ((int64_t)1 << 27);
+}
+size_t sort_workspace_words(int64_t N, int32_t K) { return (size_t)N + 2 * (size_t)K + 2; }
+
+cat_status launch_segsum_sorted(int nq, const void* lq, const void* fp, cat_dtype dt, const int32_t* assign,
+                                const int32_t* counts, int64_t N, int64_t D, int32_t K, const float* pivx,
+                                const float* pivy, double* acc, uint32_t* sort_ws, hipStream_t st) {
+    uint32_t* offs = sort_ws;            // K + 1
+    uint32_t* cursor = sort_ws + K + 1;  // K
+    uint32_t* perm = sort_ws + 2 * (size_t)K + 2;
+    hipLaunchKernelGGL(k_sort_offsets, dim3(1), dim3(1024), 0, st, counts, K, offs, cursor);
+    CAT_LAUNCH_CHECK("k_sort_offsets");
+    const int64_t per_block = 256 * kSortRowsPerThread;
+    hipLaunchKernelGGL(k_sort_scatter, dim3((unsigned)((N + per_block - 1) / per_block)), dim3(256), 0, st, assign, N, K,
+                       cursor, perm);
+    CAT_LAUNCH_CHECK("k_sort_scatter");
+    const int V = dt == CAT_BF16 ? 8 : 4;
+    const int nsl = (int)((D + kWave * V - 1) / (kWave * V));
+    // One wave per run: as many runs as waves are resident at once (or a multiple of that), so
+    // the launch has no ragged second round; a run is at least 64 rows (shorter runs only add
+    // merge traffic) and at most about a thousand.
+    static int slots_cache[2][2] = {{0, 0}, {0, 0}};
+    int& slots = slots_cache[dt == CAT_BF16][nq == 4];
+    if (slots == 0) {
+        const void* fn = dt == CAT_F32 ? (nq == 1 ? (const void*)k_segsum_sorted<float, 1> : (const void*)k_segsum_sorted<float, 4>)
+                                       : (nq == 1 ? (const void*)k_segsum_sorted<bf16_t, 1> : (const void*)k_segsum_sorted<bf16_t, 4>);
+        int nb = 0, dev = 0, ncu = 0;
+        CAT_HIP_TRY(hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, fn, kSortWaves * kWave, 0));
+        CAT_HIP_TRY(hipGetDevice(&dev));
+        CAT_HIP_TRY(hipDeviceGetAttribute(&ncu, hipDeviceAttributeMultiprocessorCount, dev));
+        slots = (nb < 1 ? 1 : nb) * (ncu < 1 ? 256 : ncu) * kSortWaves;
+    }
+    const int64_t work = N * nsl;
+    const int64_t m = (work + (int64_t)slots * 1024 - 1) / ((int64_t)slots * 1024);
+    int64_t runs = (int64_t)slots * m / nsl;
+    if (runs < 1) runs = 1;
+    int64_t R = (N + runs - 1) / runs;  // rows per run
+    if (R < 64) R = 64;
+    const int64_t nitems = ((N + R - 1) / R) * nsl;
+    dim3 grid((unsigned)((nitems + kSortWaves - 1) / kSortWaves)), block(kSortWaves * kWave);
+#define CAT_SEGS(T, NQ_)                                                                                          \
+    hipLaunchKernelGGL((k_segsum_sorted<T, NQ_>), grid, block, 0, st, (const T*)lq, (const T*)fp, perm, offs, D, K, \
+                       (int32_t)R, nsl, nitems, pivx, pivy, acc)
+    if (dt == CAT_F32) {
+        if (nq == 1) CAT_SEGS(float, 1); else CAT_SEGS(float, 4);
+    } else {
+        if (nq == 1) CAT_SEGS(bf16_t, 1); else CAT_SEGS(bf16_t, 4);
+    }
+#undef CAT_SEGS
+    CAT_LAUNCH_CHECK("k_segsum_sorted");
+    return CAT_OK;
+}
+
+// ---------------------------------------------------------------------------------
 // K x D finalisers
 // ---------------------------------------------------------------------------------
 __global__ void k_finalize_centroids(const double* __restrict__ sums, const int32_t* __restrict__ counts,

@@ -33,6 +33,7 @@ struct LloydWs {
     uint32_t* ctrl = nullptr;            // [0..1] list length (two halves), then 2 x slices finished-workgroup counters
     double* norm_part = nullptr;         // slices x K
     int32_t* counts2 = nullptr;          // K: the second half of the counts double buffer
+    uint32_t* sort_ws = nullptr;         // not carved here: the caller's scratch for launch_segsum_sorted
     size_t bytes = 0;
 };
 size_t lloyd_workspace_bytes(int64_t N, int64_t D, int32_t K);

@@ -186,36 +186,56 @@ __global__ __launch_bounds__(kDeltaWaves * kWave) void k_delta_prep(const DeltaP
     if (!s_flag) return;
 
     // ---- this slice's centroids, operand parts, norm shares ----
-    for (int k = wave; k < q.K; k += kDeltaWaves) {
-        double nn = 0.0;
-        if (ch_ok) {
-            const int64_t i = (int64_t)k * q.D + ch;
-            const double S = q.base[i] + __hip_atomic_load(q.delta + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            q.base[i] = S;
-            q.delta[i] = 0.0;
-            const int n = q.counts[k];
-            float c;
-            if (n > 0) {
-                c = (float)(S / (double)n);
-                q.cent[i] = c;
-            } else {
-                c = q.cent[i];
-            }
-            nn = (double)c * (double)c;
-            const int t = k >> 4, m = k & 15;
-            const int cc = (int)(ch / kChunk), r = (int)(ch % kChunk);
-            const int s = r >> 5, g = (r >> 3) & 3, j = r & 7;
-            const int ol = g * 16 + m;
-            const uint32_t hw = pack_bf16(c, 0.f) & 0xFFFFu;
-            const size_t blk = ((size_t)(cc * 4 + s) * q.KT + t) * q.P;
-            q.packA[(blk * 64 + ol) * 8 + j] = (uint16_t)hw;
-            if (q.P == 2) {
-                const uint32_t lw = pack_bf16(c - lo_half(hw), 0.f) & 0xFFFFu;
-                q.packA[((blk + 1) * 64 + ol) * 8 + j] = (uint16_t)lw;
+    // eight clusters per wave at a time: all their loads first (a load is not moved above the
+    // stores of the cluster before it, so one cluster at a time would cost a round trip each)
+    constexpr int KB = 8;
+    for (int kb = wave; kb < q.K; kb += kDeltaWaves * KB) {
+        double S[KB];
+        float cold[KB];
+        int n[KB];
+#pragma unroll
+        for (int u = 0; u < KB; u++) {
+            const int k = kb + u * kDeltaWaves;
+            S[u] = 0.0;
+            cold[u] = 0.f;
+            n[u] = 0;
+            if (k < q.K && ch_ok) {
+                const int64_t i = (int64_t)k * q.D + ch;
+                S[u] = q.base[i] + __hip_atomic_load(q.delta + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                cold[u] = q.cent[i];
+                n[u] = q.counts[k];
             }
         }
-        nn = wave_sum(nn);
-        if (lane == 0) q.norm_part[(size_t)slice * q.K + k] = nn;
+#pragma unroll
+        for (int u = 0; u < KB; u++) {
+            const int k = kb + u * kDeltaWaves;
+            if (k >= q.K) break;  // wave-uniform
+            double nn = 0.0;
+            if (ch_ok) {
+                const int64_t i = (int64_t)k * q.D + ch;
+                q.base[i] = S[u];
+                q.delta[i] = 0.0;
+                float c = cold[u];
+                if (n[u] > 0) {
+                    c = (float)(S[u] / (double)n[u]);
+                    q.cent[i] = c;
+                }
+                nn = (double)c * (double)c;
+                const int t = k >> 4, m = k & 15;
+                const int cc = (int)(ch / kChunk), r = (int)(ch % kChunk);
+                const int s = r >> 5, g = (r >> 3) & 3, j = r & 7;
+                const int ol = g * 16 + m;
+                const uint32_t hw = pack_bf16(c, 0.f) & 0xFFFFu;
+                const size_t blk = ((size_t)(cc * 4 + s) * q.KT + t) * q.P;
+                q.packA[(blk * 64 + ol) * 8 + j] = (uint16_t)hw;
+                if (q.P == 2) {
+                    const uint32_t lw = pack_bf16(c - lo_half(hw), 0.f) & 0xFFFFu;
+                    q.packA[((blk + 1) * 64 + ol) * 8 + j] = (uint16_t)lw;
+                }
+            }
+            nn = wave_sum(nn);
+            if (lane == 0) q.norm_part[(size_t)slice * q.K + k] = nn;
+        }
     }
 }
 
@@ -487,7 +507,10 @@ cat_status tile_lloyd(const void* lq, cat_dtype dt, int64_t N, int64_t D, int32_
         CAT_T(launch_tile(p, c, dt, st));
         if (t == 0 && iters > 0) {  // first full sums: one segmented pass
             CAT_T(launch_fill_zero(sums, 2 * KD * sizeof(double), st));
-            CAT_T(launch_segsum(1, lq, nullptr, dt, assign, N, D, K, nullptr, nullptr, base, st));
+            if (lw.sort_ws && segsum_sorted_supported(1, N, D, dt))
+                CAT_T(launch_segsum_sorted(1, lq, nullptr, dt, assign, cnt_t, N, D, K, nullptr, nullptr, base, lw.sort_ws, st));
+            else
+                CAT_T(launch_segsum(1, lq, nullptr, dt, assign, N, D, K, nullptr, nullptr, base, st));
         }
     }
 #undef CAT_T
