@@ -173,6 +173,16 @@ cat_status cat_init_indices(int64_t N, int32_t K, uint64_t seed, int64_t *idx_ou
 cat_status cat_profile_enable(int on);
 int cat_profile_read(float *ms_out, int cap);
 
+/*
+ * Test hook.  In the fused Lloyd loop (cat_fit on the tile path) every workgroup collects the rows
+ * that changed cluster in a list in fast memory before appending them to the device-wide list; a
+ * workgroup whose list is full appends tile by tile instead.  This call sets the capacity of that
+ * list for later cat_fit calls of the process (1 .. 1024 entries; 0 restores the default, 1024),
+ * so that the tile-by-tile path can be reached on small inputs.  Results never depend on it.
+ * CAT_ERR_INVALID_ARG outside that range.  Not thread-safe.
+ */
+cat_status cat_debug_list_capacity(int entries);
+
 /* Message of the last non-OK status on the calling thread ("" if none).  The
  * pointer stays valid until the next failing call on the same thread. */
 const char *cat_last_error(void);

@@ -20,7 +20,7 @@ _STATUS = {0: "CAT_OK", 1: "CAT_ERR_INVALID_ARG", 2: "CAT_ERR_UNSUPPORTED", 3: "
 
 EXPORTS = ("cat_select_path", "cat_fit_workspace_bytes", "cat_apply_workspace_bytes", "cat_fit", "cat_apply",
            "cat_assign", "cat_update", "cat_stats", "cat_init_indices", "cat_last_error", "cat_profile_enable",
-           "cat_profile_read")
+           "cat_profile_read", "cat_debug_list_capacity")
 
 
 class CatError(RuntimeError):
@@ -66,6 +66,8 @@ def load_library():
     lib.cat_profile_enable.restype = c.c_int
     lib.cat_profile_read.argtypes = [c.POINTER(c.c_float), c.c_int]
     lib.cat_profile_read.restype = c.c_int
+    lib.cat_debug_list_capacity.argtypes = [c.c_int]
+    lib.cat_debug_list_capacity.restype = c.c_int
     lib.cat_last_error.argtypes = []
     lib.cat_last_error.restype = c.c_char_p
     _lib = lib
@@ -103,6 +105,11 @@ def _stream():
 
 def select_path(path):
     _check(load_library().cat_select_path(int(path)))
+
+
+def debug_list_capacity(entries):
+    """Test hook: capacity of the per-workgroup changed-row list of the fused Lloyd loop (0 = default)."""
+    _check(load_library().cat_debug_list_capacity(int(entries)))
 
 
 def profile_enable(on):

@@ -31,6 +31,8 @@ static size_t g_prof_used = 0;             // events recorded since the last ena
 
 bool profile_on() { return g_prof; }
 bool fast_paths_forced() { return g_path.load() == CAT_PATH_TILE; }
+static std::atomic<int> g_list_cap{1024};
+int lloyd_list_capacity() { return g_list_cap.load(); }
 
 cat_status profile_mark(bool begin, hipStream_t st) {
     (void)begin;
@@ -218,6 +220,13 @@ int cat_profile_read(float* ms_out, int cap) {
         if (ms_out && (int)i < cap) ms_out[i] = ms;
     }
     return (int)pairs;
+}
+
+cat_status cat_debug_list_capacity(int entries) {
+    if (entries < 0 || entries > 1024)
+        return set_error(CAT_ERR_INVALID_ARG, "cat_debug_list_capacity: %d is outside 0 .. 1024", entries);
+    g_list_cap.store(entries == 0 ? 1024 : entries);
+    return CAT_OK;
 }
 
 cat_status cat_select_path(cat_path p) {

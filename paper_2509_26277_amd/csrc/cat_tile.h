@@ -46,6 +46,9 @@ cat_status tile_lloyd(const void* lq, cat_dtype dt, int64_t N, int64_t D, int32_
                       float* cent_io, double* sums, int32_t* assign, int32_t* counts, double* inertia,
                       unsigned long long* rep, const TileWs& ws, const LloydWs& lw, hipStream_t st);
 
+// Capacity of the per-workgroup changed-row list (cat_debug_list_capacity in cat.h).
+int lloyd_list_capacity();
+
 // Kernel timing hooks (see cat_profile_enable in cat.h): bracket one launch with events.
 bool profile_on();
 cat_status profile_mark(bool begin, hipStream_t st);

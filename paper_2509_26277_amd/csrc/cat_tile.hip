@@ -500,6 +500,7 @@ cat_status tile_lloyd(const void* lq, cat_dtype dt, int64_t N, int64_t D, int32_
         p.rep = last ? rep : nullptr;  // the final pass describes the partition that is returned
         p.list = (t > 0 && !last) ? lw.list : nullptr;
         p.list_count = lw.ctrl + (t & 1);
+        p.list_cap = lloyd_list_capacity();
         p.delta_mode = p.list ? 1 : 0;
         // alternate the scan direction: the rows a pass reads last are the ones most likely still in
         // the memory-side cache when the next pass starts

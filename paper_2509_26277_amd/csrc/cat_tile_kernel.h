@@ -57,6 +57,7 @@ struct TileParams {
     unsigned long long* list;  // lloyd: rows that changed cluster, (row << 24) | ((old + 1) << 12) | new
     uint32_t* list_count;      // entries in list (appended to with atomics)
     int32_t delta_mode;      // 0: off, 1: rows carry a previous assignment
+    int32_t list_cap;        // entries of the workgroup's LDS list in use (<= kListCap)
     int32_t reverse;         // walk the tiles from the last to the first (see tile_lloyd)
     const float* gamma;      // apply
     const float* beta;
@@ -438,7 +439,7 @@ __device__ __forceinline__ void finish_tile(const TileParams& p, unsigned char* 
         bool ovf = false;
         if (changed) {
             int pos = atomicAdd(&s_misc[0], 1);
-            if (pos < kListCap)
+            if (pos < p.list_cap)
                 ((unsigned long long*)(smem + p.off_list))[pos] = entry;
             else
                 ovf = true;
@@ -666,7 +667,7 @@ __global__ __launch_bounds__(kMaxWaves * kWave) void k_tile(const TileParams p) 
     if (!p.list) return;
 
     // the workgroup's changed rows join the global list: one reservation, then a coalesced copy
-    const int cnt = s_misc[0] < kListCap ? s_misc[0] : kListCap;
+    const int cnt = s_misc[0] < p.list_cap ? s_misc[0] : p.list_cap;
     if (cnt == 0) return;  // uniform: s_misc[0] is final after the barrier above
     if (threadIdx.x == 0) s_misc[1] = (int)atomicAdd(p.list_count, (uint32_t)cnt);
     __syncthreads();

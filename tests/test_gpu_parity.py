@@ -68,8 +68,11 @@ def test_assign_step(name, n, path):
     assert inertia.item() == pytest.approx(d1.sum(), rel=1e-4)
 
 
+@pytest.mark.parametrize("path", PATHS)
 @pytest.mark.parametrize("name,n", SMALL_FIT)
-def test_update_and_stats_steps(name, n):
+def test_update_and_stats_steps(name, n, path):
+    # the forced tile path also takes the segmented sums over cluster-ordered rows on every shape
+    binding.select_path(path)
     w = small(name, n)
     K, dt = w["K"], w["dtype"]
     o = oracle.fit(w["lq"], w["fp"], K, iters=3, seed=w["seed"])
@@ -115,6 +118,66 @@ def test_fit_end_to_end(name, n, path):
     same = (a2.cpu().numpy() == a_g)
     _, e1, e2 = oracle.assign(w["lq"], host_matrix(r["centroids"]), want_distances=True)
     assert ((e2 - e1)[~same] <= 1e-5 * e2[~same]).all()
+
+
+@pytest.mark.parametrize("cap", [1, 5, 64])
+@pytest.mark.parametrize("name,n", [("cfg1", 4096), ("cfg3", 6007), ("cfg4", 1100)])
+def test_fit_with_short_changed_row_lists(name, n, cap):
+    """The fused Lloyd loop when a workgroup's list of changed rows overflows (forced by a tiny capacity):
+    the overflowing tiles append to the device-wide list directly.  Same results as ever."""
+    binding.select_path(binding.CAT_PATH_TILE)
+    binding.debug_list_capacity(cap)
+    try:
+        w = small(name, n)
+        K, dt, iters = w["K"], w["dtype"], 6
+        r = cat_fit(dev_matrix(w["lq"], dt), dev_matrix(w["fp"], dt), K, iters, seed=w["seed"])
+    finally:
+        binding.debug_list_capacity(0)
+    o = oracle.fit(w["lq"], w["fp"], K, iters, seed=w["seed"])
+    _, d1, d2 = oracle.assign(w["lq"], o["centroids"], want_distances=True)
+    a_g = r["assignments"].cpu().numpy()
+    check_assignments(a_g, o["assignments"], d1, d2, f"{name} fit")
+    assert r["counts"].cpu().numpy().tolist() == np.bincount(a_g, minlength=K).tolist()
+    check_values(host_matrix(r["centroids"]), o["centroids"], RTOL[dt], f"{name} centroids")
+    check_values(host_matrix(r["gamma"]), o["gamma"], RTOL[dt], f"{name} gamma")
+    np.testing.assert_allclose(r["inertia"].cpu().numpy(), o["inertia"], rtol=1e-4)
+
+
+def test_list_capacity_hook_rejects_bad_values():
+    for bad in (-1, 1025):
+        with pytest.raises(binding.CatError) as e:
+            binding.debug_list_capacity(bad)
+        assert e.value.status == 1
+    binding.debug_list_capacity(0)
+
+
+@pytest.mark.parametrize("path", PATHS)
+@pytest.mark.parametrize("dt", ["f32", "bf16"])
+def test_update_and_stats_skip_rows_with_labels_outside_the_range(dt, path):
+    """cat_update / cat_stats on caller-made assignments: a label outside [0, K) leaves the row out."""
+    binding.select_path(path)
+    rng = np.random.default_rng(77)
+    N, D, K = 3001, 72, 5
+    lq = rng.standard_normal((N, D)).astype(np.float32)
+    fp = (1.1 * lq + 0.05 * rng.standard_normal((N, D))).astype(np.float32)
+    if dt == "bf16":
+        lq, fp = workloads.round_to_bf16(lq), workloads.round_to_bf16(fp)
+    a = rng.integers(0, K, N).astype(np.int32)
+    a[rng.random(N) < 0.1] = -1
+    a[rng.random(N) < 0.05] = K
+    a[a == 3] = 1  # and one empty cluster
+    keep = (a >= 0) & (a < K)
+    prev = rng.standard_normal((K, D)).astype(np.float32)
+    c_o, n_o = oracle.update(lq[keep], a[keep], prev)
+    g_o, b_o, _ = oracle.affine(lq[keep], fp[keep], a[keep], K)
+    lq_d, fp_d, a_d = dev_matrix(lq, dt), dev_matrix(fp, dt), torch.from_numpy(a).cuda()
+    c_g, n_g = cat_update(lq_d, a_d, torch.from_numpy(prev).cuda())
+    assert n_g.cpu().numpy().tolist() == n_o.tolist()
+    check_values(host_matrix(c_g), c_o, RTOL[dt], "update")
+    g_g, b_g, n2 = cat_stats(lq_d, fp_d, a_d, K)
+    assert n2.cpu().numpy().tolist() == n_o.tolist()
+    check_values(host_matrix(g_g), g_o, RTOL[dt], "gamma")
+    check_values(host_matrix(b_g), b_o, RTOL[dt], "beta", beta_scale(lq[keep], fp[keep], a[keep], K, g_o))
 
 
 @pytest.mark.parametrize("path", PATHS)
