@@ -13,7 +13,7 @@ namespace cat {
 // first-row table.
 __global__ __launch_bounds__(256) void k_tile_prep(float* cent, double* base, double* delta,
                                                    const int32_t* counts_read, int32_t* counts_reset,
-                                                   int64_t D, int32_t K, int32_t KT, int32_t P, int32_t nchunks,
+                                                   int64_t D, int32_t K, int32_t KT, int32_t P, int32_t nchunks, int f32_rows,
                                                    uint16_t* packA, float* cnorm, double* inertia_slot,
                                                    unsigned long long* rep) {
     __shared__ double s_red[256];
@@ -35,10 +35,12 @@ __global__ __launch_bounds__(256) void k_tile_prep(float* cent, double* base, do
             c = cent[i];
         }
         nn += (double)c * (double)c;
-        // position of channel ch in the operand: chunk, MFMA step s (32 channels), lane group g, then
-        // the 8 consecutive channels j that lane (m, g) feeds to one MFMA
+        // position of channel ch in the operand: chunk, MFMA step s (32 channels), then the lane group g
+        // and the element j of the 8 that lane (m, g) feeds to one MFMA (operand_slot)
         const int cc = (int)(ch / kChunk), r = (int)(ch % kChunk);
-        const int s = r >> 5, g = (r >> 3) & 3, j = r & 7;
+        const int s = r >> 5;
+        int g, j;
+        operand_slot(r & 31, f32_rows != 0, g, j);
         const int lane = g * 16 + m;
         const uint32_t hw = pack_bf16(c, 0.f) & 0xFFFFu;
         const size_t blk = ((size_t)(cc * 4 + s) * KT + t) * P;
@@ -79,7 +81,7 @@ __global__ __launch_bounds__(256) void k_tile_prep(float* cent, double* base, do
 struct DeltaParams {
     const void* lq;
     int64_t D;
-    int32_t K, KT, P, KC, G;
+    int32_t K, KT, P, KC, G, f32_rows;
     const unsigned long long* list;
     const uint32_t* list_count;  // length of the list of the pass before
     uint32_t* list_count_next;   // cleared: the following pass appends here
@@ -223,7 +225,9 @@ __global__ __launch_bounds__(kDeltaWaves * kWave) void k_delta_prep(const DeltaP
                 nn = (double)c * (double)c;
                 const int t = k >> 4, m = k & 15;
                 const int cc = (int)(ch / kChunk), r = (int)(ch % kChunk);
-                const int s = r >> 5, g = (r >> 3) & 3, j = r & 7;
+                const int s = r >> 5;
+                int g, j;
+                operand_slot(r & 31, q.f32_rows != 0, g, j);
                 const int ol = g * 16 + m;
                 const uint32_t hw = pack_bf16(c, 0.f) & 0xFFFFu;
                 const size_t blk = ((size_t)(cc * 4 + s) * q.KT + t) * q.P;
@@ -352,6 +356,7 @@ static cat_status launch_delta_prep(const void* lq, cat_dtype dt, int64_t D, int
     q.K = K;
     q.KT = c.KT;
     q.P = c.P;
+    q.f32_rows = dt == CAT_F32;
     q.KC = K < 128 ? K : 128;  // LDS panel: KC x 64 doubles, at most 64 KB
     const int64_t slices = delta_slices(D);
     const int kchunks = (K + q.KC - 1) / q.KC;
@@ -385,9 +390,8 @@ static cat_status launch_prep(cat_dtype dt, float* cent, double* base, double* d
                               int32_t* counts_reset, int64_t D, int32_t K, const TileCfg& c, const TileWs& ws,
                               double* inertia_slot, unsigned long long* rep, hipStream_t st) {
     dim3 grid(c.KT * 16), block(256);
-    (void)dt;
     hipLaunchKernelGGL(k_tile_prep, grid, block, 0, st, cent, base, delta, counts_read, counts_reset, D, K, c.KT, c.P,
-                       c.nchunks, ws.packA, ws.cnorm, inertia_slot, rep);
+                       c.nchunks, dt == CAT_F32 ? 1 : 0, ws.packA, ws.cnorm, inertia_slot, rep);
     CAT_LAUNCH_CHECK("k_tile_prep");
     return CAT_OK;
 }

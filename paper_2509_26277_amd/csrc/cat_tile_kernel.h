@@ -66,6 +66,22 @@ struct TileParams {
     uint32_t ldsA_bytes, off_cnorm, off_hist, off_rep, off_list, off_misc;
 };
 
+// Which lane group g (0..3) and which of its 8 operand elements j hold channel r (0..31) of a
+// 32-channel MFMA step.  The contraction does not care how channels map to the k index as long as
+// rows and centroids agree, so the map is chosen for the row loads: bf16 rows give a lane 8
+// consecutive channels (one 16-byte load); fp32 rows give it channels 4g..4g+3 and 16+4g..16+4g+3,
+// so that each of its two 16-byte loads forms, with the other three lanes of the row, 64
+// contiguous bytes (whole 32-byte sectors) instead of 16-byte pieces with gaps.
+__host__ __device__ __forceinline__ void operand_slot(int r, bool f32_rows, int& g, int& j) {
+    if (f32_rows) {
+        g = (r & 15) >> 2;
+        j = (r & 3) + ((r >> 4) << 2);
+    } else {
+        g = r >> 3;
+        j = r & 7;
+    }
+}
+
 // ---- small device helpers ---------------------------------------------------------
 __device__ __forceinline__ uint32_t pack_bf16(float a, float b) {  // a -> low half, b -> high half, RNE
     f32x2 v = {a, b};
@@ -130,8 +146,9 @@ __device__ __forceinline__ void exact_dists(const void* lq, int64_t row, int64_t
     for (int c = 0; c < NC; c++) out[c] = wave_sum(s[c]);
 }
 
-// One chunk (128 channels) of the tile as loaded: per MFMA step s, lane (n, g) holds channels
-// 128 c + 32 s + 8 g .. + 7 of row n: two 16-byte loads (fp32) or one (bf16).
+// One chunk (128 channels) of the tile as loaded: per MFMA step s, lane (n, g) holds 8 channels of
+// row n out of 128 c + 32 s .. + 31: 8 g .. 8 g + 7 in one 16-byte load (bf16), or 4 g .. 4 g + 3 and
+// 16 + 4 g .. 16 + 4 g + 3 in two (fp32); see operand_slot.
 template <bool BF16>
 struct ChunkRegs {
     u32x4 v[BF16 ? 4 : 8];
@@ -162,11 +179,12 @@ __device__ __forceinline__ void load_chunk(ChunkRegs<BF16>& r, const TileParams&
         }
     } else {
         const float* x = (const float*)p.lq + (row0 + rn) * p.D;
+        const int chf = chunk * kChunk + 4 * g;  // see operand_slot
 #pragma unroll
         for (int s = 0; s < 4; s++) {
-            const int c = ch + 32 * s;
+            const int c = chf + 32 * s;
             r.v[2 * s] = *(const u32x4*)(x + (c < p.D ? c : 0));
-            r.v[2 * s + 1] = *(const u32x4*)(x + (c + 4 < p.D ? c + 4 : 0));
+            r.v[2 * s + 1] = *(const u32x4*)(x + (c + 16 < p.D ? c + 16 : 0));
         }
     }
 }
@@ -193,7 +211,8 @@ __device__ __forceinline__ void contract_chunk(const ChunkRegs<BF16>& r, f32x4 (
             }
             bh = __builtin_bit_cast(bf16x8, w);
         } else {
-            const uint32_t m0 = c < D ? 0xFFFFFFFFu : 0u, m1 = c + 4 < D ? 0xFFFFFFFFu : 0u;
+            const int cf = chunk * kChunk + 4 * (lane >> 4) + 32 * s;  // see operand_slot
+            const uint32_t m0 = cf < D ? 0xFFFFFFFFu : 0u, m1 = cf + 16 < D ? 0xFFFFFFFFu : 0u;
             float x[8];
 #pragma unroll
             for (int j = 0; j < 4; j++) {
