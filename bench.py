@@ -10,7 +10,9 @@ assignment, per-cluster affine fit) followed by cat_apply on the same rows
 
 value        rows x Lloyd-iterations per second of whole-step time (cfg5: GB/s of
              cat_apply, read + write)
-roofline     the dominant kernel, k_tile (the assignment pass of a Lloyd iteration;
+roofline     (traffic: measured HBM bytes per launch from hardware counters, null when the
+             kernel source has changed since they were taken or --rows overrides the size)
+             the dominant kernel, k_tile (the assignment pass of a Lloyd iteration;
              cfg5: the fused inference pass): algorithmic bytes per launch (one read
              of lq; inference: one read + one write + the assignments) over its mean
              launch duration, measured with HIP events that the library records
@@ -30,6 +32,36 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0
+
+# HBM-side traffic of one k_tile launch, from two rocprofv3 --pmc runs of this file (FETCH_SIZE, then
+# WRITE_SIZE; profiles/k_tile_hbm_traffic.md has the commands and the raw figures).  Each counter is
+# scaled by what it reads for the plain device copy of the same matrix that this script also times
+# (a copy reads and writes exactly N*D*b bytes).  Per workload: (FETCH_SIZE of k_tile, FETCH_SIZE of the
+# copy, WRITE_SIZE of k_tile, WRITE_SIZE of the copy), counter units, mean per dispatch.  The figures
+# belong to one version of the kernel source: `traffic` is reported only while its hash still matches.
+TRAFFIC_KERNEL_SHA256 = "068e8e4fd940250cbed63955ea4e81e4ce5f5da2332aee5ee4c00cdeedc0b72e"
+TRAFFIC_COUNTERS = {
+    "cfg2": (133734.7, 128011.8, 301.8, 256000.0),
+    "cfg3": (527774.8, 524299.7, 4883.4, 1048576.0),
+    "cfg4": (560666.9, 524299.7, 1232.2, 1048576.0),
+    "cfg5": (8361529.5, 4194317.7, 8406453.6, 8388608.0),
+}
+
+
+def _traffic_bytes(workload, copy_bytes):
+    """measured HBM bytes per k_tile launch, or None (no counters for this workload / kernel changed)"""
+    import hashlib
+    src = os.path.join(ROOT, "paper_2509_26277_amd", "csrc", "cat_tile_kernel.h")
+    try:
+        with open(src, "rb") as f:
+            if hashlib.sha256(f.read()).hexdigest() != TRAFFIC_KERNEL_SHA256:
+                return None
+    except OSError:
+        return None
+    if workload not in TRAFFIC_COUNTERS:
+        return None
+    fk, fc, wk, wc = TRAFFIC_COUNTERS[workload]
+    return fk * (copy_bytes / fc) + wk * (copy_bytes / wc)
 
 
 def _events(fn, reps, torch):
@@ -133,7 +165,8 @@ def main():
         t_k = sum(ms) / len(ms)
         achieved = alg_bytes / t_k / 1e6
         roof = dict(bound="hbm", kernel="k_tile (assignment pass)", achieved=achieved, peak=HBM_PEAK_GBPS, unit="GB/s",
-                    frac=achieved / HBM_PEAK_GBPS, traffic=None, bytes_per_launch=alg_bytes,
+                    frac=achieved / HBM_PEAK_GBPS, traffic=None if args.rows else _traffic_bytes(w["name"], N * D * esize),
+                    bytes_per_launch=alg_bytes,
                     us_per_launch=1e3 * t_k, launches=len(ms))
         metric, unit = "cat_fit_lloyd_rows_per_s", "rows/s"
         value = N * iters / (ms_per_step * 1e-3)
@@ -149,7 +182,8 @@ def main():
         t_k = sum(ms) / len(ms)
         achieved = apply_bytes / t_k / 1e6
         roof = dict(bound="hbm", kernel="k_tile (fused inference pass)", achieved=achieved, peak=HBM_PEAK_GBPS,
-                    unit="GB/s", frac=achieved / HBM_PEAK_GBPS, traffic=None, bytes_per_launch=apply_bytes,
+                    unit="GB/s", frac=achieved / HBM_PEAK_GBPS, traffic=None if args.rows else _traffic_bytes(w["name"], N * D * esize),
+                    bytes_per_launch=apply_bytes,
                     us_per_launch=1e3 * t_k, launches=len(ms))
         metric, unit = "cat_apply_GBps", "GB/s"
         value = apply_bytes / (ms_per_step * 1e-3) / 1e9
