@@ -360,7 +360,8 @@ static cat_status launch_delta_prep(const void* lq, cat_dtype dt, int64_t D, int
     q.KC = K < 128 ? K : 128;  // LDS panel: KC x 64 doubles, at most 64 KB
     const int64_t slices = delta_slices(D);
     const int kchunks = (K + q.KC - 1) / q.KC;
-    int64_t G = 1024 / (slices * kchunks);  // about a thousand workgroups in all
+    int64_t G = 256 / (slices * kchunks);  // about one workgroup per CU in all: with 1024 the launch itself
+                                           // (dispatch, panel clears, counters) cost 10 us more than the work
     q.G = (int32_t)(G < 1 ? 1 : (G > 256 ? 256 : G));
     q.list = lw.list;
     q.list_count = lw.ctrl + (par ^ 1);
