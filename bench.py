@@ -39,7 +39,7 @@ HBM_PEAK_GBPS = 8000.0
 # (a copy reads and writes exactly N*D*b bytes).  Per workload: (FETCH_SIZE of k_tile, FETCH_SIZE of the
 # copy, WRITE_SIZE of k_tile, WRITE_SIZE of the copy), counter units, mean per dispatch.  The figures
 # belong to one version of the kernel source: `traffic` is reported only while its hash still matches.
-TRAFFIC_KERNEL_SHA256 = "068e8e4fd940250cbed63955ea4e81e4ce5f5da2332aee5ee4c00cdeedc0b72e"
+TRAFFIC_KERNEL_SHA256 = "a85837f0a7b73474559b4e56707c084d4db616d7b8911bf2654db1426a57ec1f"
 TRAFFIC_COUNTERS = {
     "cfg2": (133734.7, 128011.8, 301.8, 256000.0),
     "cfg3": (527774.8, 524299.7, 4883.4, 1048576.0),

@@ -165,7 +165,7 @@ static cat_status step_assign(const void* lq, cat_dtype dt, int64_t N, int64_t D
     if (inertia) CAT_TRY(launch_fill_zero(inertia, sizeof(double), st));
     if (rep) CAT_TRY(launch_fill_u64(rep, K, ~0ull, st));
     const int path = g_path.load();
-    const bool tile_ok = tile_supports(TILE_ASSIGN, D, K, dt);
+    const bool tile_ok = tile_supports(TILE_ASSIGN, N, D, K, dt);
     if (path == CAT_PATH_TILE && !tile_ok)
         return set_error(CAT_ERR_UNSUPPORTED, "tile path forced but D=%lld K=%d dt=%d does not fit it", (long long)D,
                          (int)K, (int)dt);
@@ -341,7 +341,7 @@ cat_status cat_fit(const void* lq, const void* fp, int64_t N, int64_t D, int32_t
     const size_t KD = (size_t)K * (size_t)D;
 
     const int path = g_path.load();
-    const bool fused = tile_supports(TILE_LLOYD, D, K, dt) && path != CAT_PATH_STREAM;
+    const bool fused = tile_supports(TILE_LLOYD, N, D, K, dt) && path != CAT_PATH_STREAM;
     if (path == CAT_PATH_TILE && !fused)
         return set_error(CAT_ERR_UNSUPPORTED, "tile path forced but D=%lld K=%d dt=%d does not fit it", (long long)D,
                          (int)K, (int)dt);
@@ -399,7 +399,7 @@ cat_status cat_apply(const void* lq, int64_t N, int64_t D, int32_t K, cat_dtype 
         b = w.b_eff;
     }
     const int path = g_path.load();
-    const bool tile_ok = tile_supports(TILE_APPLY, D, K, dt);
+    const bool tile_ok = tile_supports(TILE_APPLY, N, D, K, dt);
     if (path == CAT_PATH_TILE && !tile_ok)
         return set_error(CAT_ERR_UNSUPPORTED, "tile path forced but D=%lld K=%d dt=%d does not fit it", (long long)D,
                          (int)K, (int)dt);

@@ -594,14 +594,19 @@ cat_status launch_segsum_sorted(int nq, const void* lq, const void* fp, cat_dtyp
     // One wave per run: as many runs as waves are resident at once (or a multiple of that), so
     // the launch has no ragged second round; a run is at least 64 rows (shorter runs only add
     // merge traffic) and at most about a thousand.
-    static int slots_cache[2][2] = {{0, 0}, {0, 0}};
+    static int slots_cache[2][2] = {{0, 0}, {0, 0}}, slots_dev = -1;
+    int dev = 0;
+    CAT_HIP_TRY(hipGetDevice(&dev));
+    if (dev != slots_dev) {
+        slots_cache[0][0] = slots_cache[0][1] = slots_cache[1][0] = slots_cache[1][1] = 0;
+        slots_dev = dev;
+    }
     int& slots = slots_cache[dt == CAT_BF16][nq == 4];
     if (slots == 0) {
         const void* fn = dt == CAT_F32 ? (nq == 1 ? (const void*)k_segsum_sorted<float, 1> : (const void*)k_segsum_sorted<float, 4>)
                                        : (nq == 1 ? (const void*)k_segsum_sorted<bf16_t, 1> : (const void*)k_segsum_sorted<bf16_t, 4>);
-        int nb = 0, dev = 0, ncu = 0;
+        int nb = 0, ncu = 0;
         CAT_HIP_TRY(hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, fn, kSortWaves * kWave, 0));
-        CAT_HIP_TRY(hipGetDevice(&dev));
         CAT_HIP_TRY(hipDeviceGetAttribute(&ncu, hipDeviceAttributeMultiprocessorCount, dev));
         slots = (nb < 1 ? 1 : nb) * (ncu < 1 ? 256 : ncu) * kSortWaves;
     }

@@ -17,8 +17,8 @@ struct TileWs {
 size_t tile_workspace_bytes(int64_t D, int32_t K, cat_dtype dt);
 TileWs tile_carve(void* base, int64_t D, int32_t K, cat_dtype dt);
 
-// Whether the tile kernels can run `mode` on this shape (LDS and register budgets).
-bool tile_supports(TileMode mode, int64_t D, int32_t K, cat_dtype dt);
+// Whether the tile kernels can run `mode` on this shape (LDS and register budgets, index widths).
+bool tile_supports(TileMode mode, int64_t N, int64_t D, int32_t K, cat_dtype dt);
 
 // Assignment pass (gamma == NULL) or fused inference (gamma, beta, corrected given).
 // counts / inertia / rep are optional and pre-initialised by the caller.

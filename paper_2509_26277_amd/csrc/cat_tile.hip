@@ -293,7 +293,10 @@ static TileCfg tile_config(TileMode mode, int64_t D, int32_t K, cat_dtype dt) {
     return c;
 }
 
-bool tile_supports(TileMode mode, int64_t D, int32_t K, cat_dtype dt) { return tile_config(mode, D, K, dt).ok; }
+bool tile_supports(TileMode mode, int64_t N, int64_t D, int32_t K, cat_dtype dt) {
+    // tile indices are 32-bit in the kernels and a changed-row entry keeps 40 bits of row number
+    return N < ((int64_t)1 << 34) && tile_config(mode, D, K, dt).ok;
+}
 
 static size_t packA_bytes(int64_t D, int32_t K) {
     const int K16 = (K + 15) & ~15;

@@ -712,22 +712,20 @@ static inline cat_status launch_one(const TileParams& p, const TileCfg& c, hipSt
     }
     CAT_HIP_TRY(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)c.lds_total));
     // persistent grid: as many workgroups as are resident at once (registers and LDS decide), each
-    // walking its share of the tiles; asked from the runtime once per kernel variant and LDS size
-    static int cached_lds = -1, cached_per_cu = 1;
-    if (cached_lds != (int)c.lds_total) {
-        int nb = 0;
+    // walking its share of the tiles; asked from the runtime once per kernel variant, LDS size and device
+    static int cached_lds = -1, cached_dev = -1, cached_per_cu = 1, ncu = 256;
+    int dev = 0;
+    CAT_HIP_TRY(hipGetDevice(&dev));
+    if (cached_lds != (int)c.lds_total || cached_dev != dev) {
+        int nb = 0, v = 0;
         CAT_HIP_TRY(hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, (const void*)kern, c.waves * kWave, c.lds_total));
+        CAT_HIP_TRY(hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev));
         cached_per_cu = nb < 1 ? 1 : nb;
+        ncu = v > 0 ? v : 256;
         cached_lds = (int)c.lds_total;
+        cached_dev = dev;
     }
     int64_t want = (p.ntiles + c.waves - 1) / c.waves;
-    static int ncu = 0;
-    if (ncu == 0) {
-        int dev = 0, v = 0;
-        CAT_HIP_TRY(hipGetDevice(&dev));
-        CAT_HIP_TRY(hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev));
-        ncu = v > 0 ? v : 256;
-    }
     int64_t cap = (int64_t)ncu * cached_per_cu;
     unsigned blocks = (unsigned)(want < cap ? want : cap);
     const bool prof = profile_on();
