@@ -304,3 +304,45 @@ def test_device_errors_are_statuses_not_crashes():
     assert e.value.status == 3
     with pytest.raises(binding.CatError):
         cat_apply(lq, lq[:4].contiguous(), lq[:4].contiguous(), lq[:4].contiguous(), out=lq)
+
+
+def test_whole_path_captures_into_a_hip_graph_and_replays():
+    """Nothing on the path allocates, synchronises or uses a memset node, so cat_fit + cat_apply can be
+    captured once and replayed; every replay (with eager work in between) reproduces the eager result."""
+    w = small("cfg1", 4096)
+    K, iters = w["K"], 6
+    lq, fp = dev_matrix(w["lq"], "f32"), dev_matrix(w["fp"], "f32")
+    ws = torch.empty(binding.cat_fit_workspace_bytes(4096, w["D"], K, binding.CAT_F32), dtype=torch.uint8, device="cuda")
+    ws2 = torch.empty(max(256, binding.cat_apply_workspace_bytes(4096, w["D"], K, binding.CAT_F32)), dtype=torch.uint8,
+                      device="cuda")
+    out = torch.empty_like(lq)
+
+    def run():
+        r = cat_fit(lq, fp, K, iters, seed=5, workspace=ws)
+        o, a = cat_apply(lq, r["centroids"], r["gamma"], r["beta"], alpha=0.5, out=out, workspace=ws2)
+        return r, o, a
+
+    r0, o0, a0 = run()
+    ref = {k: v.clone() for k, v in r0.items()}
+    o_ref, a_ref = o0.clone(), a0.clone()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):  # warm-up on the capture stream's side, as torch asks for
+        run()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        r, o, a = run()
+    for _ in range(3):
+        for t in (r["centroids"], r["gamma"], r["beta"], r["assignments"], r["counts"], o, a):
+            t.zero_()  # eager work between replays; also proves the replay rewrites every output
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(r["assignments"], ref["assignments"]) and torch.equal(a, a_ref)
+        assert torch.equal(r["counts"], ref["counts"])
+        for k in ("centroids", "gamma", "beta"):
+            torch.testing.assert_close(r[k], ref[k], rtol=1e-6, atol=1e-7)
+        torch.testing.assert_close(o, o_ref, rtol=1e-6, atol=1e-6)
+        torch.testing.assert_close(r["inertia"], ref["inertia"], rtol=1e-9, atol=0)
