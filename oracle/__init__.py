@@ -16,4 +16,7 @@ from .cat_oracle import (  # noqa: F401
     affine,
     fit,
     apply,
+    covariance,
+    pca_fit,
+    pca_project,
 )

@@ -24,6 +24,9 @@
  *   - seeded initialisation: K distinct row indices drawn with SplitMix64
  *     (Steele, Lea, Flood, OOPSLA 2014) used as a counter-based generator,
  *     re-implemented here from its published definition.
+ *   - PCA front-end (Sec. 3.1; first step of Algorithms 1 and 2): column means,
+ *     population covariance, projection (at the end of this file); pinned in
+ *     tests/test_oracle_pca_pins.py.
  *
  * Inputs are float arrays (bf16 data is widened exactly by the caller); every
  * sum, mean, distance and quotient below is IEEE double, accumulated
@@ -272,4 +275,51 @@ void cat_oracle_apply(const float *lq, int64_t N, int64_t D, int32_t K,
         }
     }
     if (!assign) free(a);
+}
+
+/* ---------------------------------------------------------------------------
+ * PCA front-end (Sec. 3.1: the LQ vectors are reduced by a principal component
+ * analysis before clustering; Alg. 1 and Alg. 2, first step).  Written out as
+ * the textbook definition: column means, the D x D covariance of the centred
+ * data with the 1/N normalisation used everywhere else here (the directions do
+ * not depend on the divisor), and the projection of centred rows on given
+ * directions.  The symmetric eigendecomposition in between is a library
+ * routine called from the Python wrapper.  Sums are sequential in double;
+ * OpenMP only splits independent outputs.
+ * ------------------------------------------------------------------------- */
+void cat_oracle_colmean(const float *x, int64_t N, int64_t D, double *mean) {
+#pragma omp parallel for schedule(static)
+    for (int64_t j = 0; j < D; j++) {
+        double s = 0.0;
+        for (int64_t i = 0; i < N; i++) s += (double)x[i * D + j];
+        mean[j] = s / (double)N;
+    }
+}
+
+/* cov[a][b] = (1/N) sum_i (x[i][a] - mean[a]) (x[i][b] - mean[b]), full D x D */
+void cat_oracle_covariance(const float *x, int64_t N, int64_t D, const double *mean, double *cov) {
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int64_t a = 0; a < D; a++) {
+        for (int64_t b = a; b < D; b++) {
+            double s = 0.0;
+            for (int64_t i = 0; i < N; i++)
+                s += ((double)x[i * D + a] - mean[a]) * ((double)x[i * D + b] - mean[b]);
+            cov[a * D + b] = s / (double)N;
+        }
+    }
+    for (int64_t a = 0; a < D; a++)
+        for (int64_t b = 0; b < a; b++) cov[a * D + b] = cov[b * D + a];
+}
+
+/* z[i][c] = sum_j (x[i][j] - mean[j]) comps[c][j],  comps is p x D */
+void cat_oracle_project(const float *x, int64_t N, int64_t D, int32_t p, const double *mean,
+                        const double *comps, double *z) {
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < N; i++) {
+        for (int32_t c = 0; c < p; c++) {
+            double s = 0.0;
+            for (int64_t j = 0; j < D; j++) s += ((double)x[i * D + j] - mean[j]) * comps[(int64_t)c * D + j];
+            z[i * p + c] = s;
+        }
+    }
 }

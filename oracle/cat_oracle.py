@@ -44,6 +44,11 @@ def _load():
                                    f64p, f64p, f64p, f64p, i32p, i64p, f64p]
     lib.cat_oracle_apply.argtypes = [f32p, c.c_int64, c.c_int64, c.c_int32, f64p, f64p, f64p,
                                      c.c_double, f64p, i32p]
+    lib.cat_oracle_colmean.argtypes = [f32p, c.c_int64, c.c_int64, f64p]
+    lib.cat_oracle_covariance.argtypes = [f32p, c.c_int64, c.c_int64, f64p, f64p]
+    lib.cat_oracle_project.argtypes = [f32p, c.c_int64, c.c_int64, c.c_int32, f64p, f64p, f64p]
+    for fn in ("cat_oracle_colmean", "cat_oracle_covariance", "cat_oracle_project"):
+        getattr(lib, fn).restype = None
     for fn in ("cat_oracle_init_indices", "cat_oracle_assign", "cat_oracle_distances", "cat_oracle_update",
                "cat_oracle_affine", "cat_oracle_fit", "cat_oracle_apply"):
         getattr(lib, fn).restype = None
@@ -178,3 +183,50 @@ def apply(lq, centroids, gamma, beta, alpha=1.0):
     _load().cat_oracle_apply(plq, N, D, K, pc, pg, pb, float(alpha), _p(out, ctypes.c_double),
                              _p(a, ctypes.c_int32))
     return out, a
+
+
+# ---------------------------------------------------------------------------
+# PCA front-end (Sec. 3.1; Alg. 1 / Alg. 2, first step)
+# ---------------------------------------------------------------------------
+def covariance(lq):
+    """Column means (D) and the population covariance (D x D) of the rows, in double."""
+    lib = _load()
+    x, xp = _f32(lq)
+    N, D = x.shape
+    mean = np.empty(D, dtype=np.float64)
+    cov = np.empty((D, D), dtype=np.float64)
+    lib.cat_oracle_colmean(xp, N, D, _p(mean, ctypes.c_double))
+    lib.cat_oracle_covariance(xp, N, D, _p(mean, ctypes.c_double), _p(cov, ctypes.c_double))
+    return mean, cov
+
+
+def pca_fit(lq, p):
+    """The p leading principal directions of the rows of ``lq``.
+
+    Returns (mean D, components p x D, eigenvalues p): eigenvalues of the population covariance in
+    descending order (equal eigenvalues keep the order of the library routine, reversed), each
+    direction a unit vector whose entry of largest magnitude (the first such entry) is positive.
+    The symmetric eigendecomposition is numpy.linalg.eigh (LAPACK)."""
+    mean, cov = covariance(lq)
+    w, v = np.linalg.eigh(cov)  # ascending
+    order = np.arange(len(w))[::-1][:p]
+    evals = w[order].copy()
+    comps = v[:, order].T.copy()
+    for c in range(comps.shape[0]):
+        j = int(np.argmax(np.abs(comps[c])))
+        if comps[c, j] < 0:
+            comps[c] = -comps[c]
+    return mean, comps, evals
+
+
+def pca_project(lq, mean, comps):
+    """(lq - mean) @ comps.T in double: N x p."""
+    lib = _load()
+    x, xp = _f32(lq)
+    N, D = x.shape
+    m = np.ascontiguousarray(mean, dtype=np.float64)
+    w = np.ascontiguousarray(comps, dtype=np.float64)
+    pdim = w.shape[0]
+    z = np.empty((N, pdim), dtype=np.float64)
+    lib.cat_oracle_project(xp, N, D, pdim, _p(m, ctypes.c_double), _p(w, ctypes.c_double), _p(z, ctypes.c_double))
+    return z
