@@ -84,6 +84,9 @@ def main():
     ap.add_argument("--workload", default="cfg2", choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5"])
     ap.add_argument("--rows", type=int, default=None, help="override N (debugging; the result is then not the named workload)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
+    ap.add_argument("--pca-dim", type=int, default=50,
+                    help="also time the PCA front-end (fit, projection, labelled affine map) with this many "
+                         "components; reported under detail.pca_*; 0 skips it (fit workloads with D <= 2048 only)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build is single-GPU; run with --gpus 1 (rows shard trivially, see DESIGN.md)")
@@ -187,6 +190,22 @@ def main():
                     us_per_launch=1e3 * t_k, launches=len(ms))
         metric, unit = "cat_apply_GBps", "GB/s"
         value = apply_bytes / (ms_per_step * 1e-3) / 1e9
+
+    # ---- the PCA front-end (a separate row of the method: not part of `value` or `roofline`) ----
+    if fit_kind and args.pca_dim > 0 and D <= 2048:
+        from paper_2509_26277_amd import cat_apply_assigned, cat_pca_fit, cat_pca_project
+        pdim = min(args.pca_dim, D)
+        dtc = binding.CAT_F32 if dt == "f32" else binding.CAT_BF16
+        ws_pca = torch.empty(binding.load_library().cat_pca_workspace_bytes(N, D, pdim, dtc), dtype=torch.uint8, device="cuda")
+        mean_p, comps_p, _ = cat_pca_fit(lq, pdim, workspace=ws_pca)
+        t_pfit = _events(lambda: cat_pca_fit(lq, pdim, workspace=ws_pca), 2, torch)
+        t_proj = _events(lambda: cat_pca_project(lq, mean_p, comps_p), 5, torch)
+        r = state["fit"]
+        t_lab = _events(lambda: cat_apply_assigned(lq, r["assignments"], r["gamma"], r["beta"], out=out), 5, torch)
+        detail.update(pca_dim=pdim, pca_fit_ms=t_pfit, pca_project_us=1e3 * t_proj,
+                      pca_project_GBps=N * D * esize / t_proj / 1e6,
+                      pca_project_TFLOPs=2.0 * N * D * (16 * ((pdim + 15) // 16)) / t_proj / 1e9,
+                      apply_assigned_us=1e3 * t_lab, apply_assigned_GBps=2 * N * D * esize / t_lab / 1e6)
 
     # context: plain device copy of the same matrix
     t_copy = _events(lambda: out.copy_(lq), 5, torch)

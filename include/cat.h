@@ -161,6 +161,40 @@ cat_status cat_stats(const void *lq, const void *fp, const int32_t *assignments,
  */
 cat_status cat_init_indices(int64_t N, int32_t K, uint64_t seed, int64_t *idx_out);
 
+/* ---- PCA front-end (Sec. 3.1; the first step of Algorithms 1 and 2) --------
+ *
+ * The paper clusters the p leading principal components of the LQ vectors rather
+ * than the vectors themselves, and applies the affine correction of the cluster
+ * found there to the full vector.  With these three calls that pipeline is
+ *   fit:    cat_pca_fit -> cat_pca_project -> cat_fit on z (its assignments and
+ *           centroids) -> cat_stats(lq, fp, assignments)
+ *   apply:  cat_pca_project -> cat_assign on z -> cat_apply_assigned
+ *
+ * cat_pca_fit: column means of lq, the D x D covariance with the 1/N
+ * normalisation, its eigendecomposition (one-sided Jacobi rotations in double
+ * precision, `sweeps` sweeps over all pairs; 0 picks the default, 12), and the p
+ * directions of largest eigenvalue in descending order, each a unit vector whose
+ * entry of largest magnitude (the first such entry) is positive.  1 <= p <= D <=
+ * 2048.
+ *   mean         out, D float
+ *   components   out, p x D float, row c = direction c
+ *   eigenvalues  out, p doubles, nullable
+ * cat_pca_project: z[i][c] = sum_j (lq[i][j] - mean[j]) components[c][j];
+ *   z out, N x p float (fp32 accumulation).  No workspace.
+ * cat_apply_assigned: corrected_i = x_i + alpha (gamma_a x_i + beta_a - x_i) with
+ *   a = assignments[i] given by the caller; a label outside [0, K) copies the row.
+ *   corrected out, N x D of dt, may not alias lq.  No workspace.
+ */
+size_t cat_pca_workspace_bytes(int64_t N, int64_t D, int32_t p, cat_dtype dt);
+cat_status cat_pca_fit(const void *lq, int64_t N, int64_t D, int32_t p, cat_dtype dt, int32_t sweeps,
+                       float *mean, float *components, double *eigenvalues,
+                       void *workspace, size_t workspace_bytes, void *hip_stream);
+cat_status cat_pca_project(const void *lq, int64_t N, int64_t D, int32_t p, cat_dtype dt,
+                           const float *mean, const float *components, float *z, void *hip_stream);
+cat_status cat_apply_assigned(const void *lq, const int32_t *assignments, int64_t N, int64_t D,
+                              int32_t K, cat_dtype dt, const float *gamma, const float *beta,
+                              float alpha, void *corrected, void *hip_stream);
+
 /*
  * Timing of the dominant kernel, for benchmarks.  While enabled, every launch of the tile
  * kernel (the assignment / Lloyd / inference pass) made by the calling process is bracketed by

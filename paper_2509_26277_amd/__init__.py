@@ -13,6 +13,9 @@ from .binding import (  # noqa: F401
     cat_update,
     cat_stats,
     cat_init_indices,
+    cat_pca_fit,
+    cat_pca_project,
+    cat_apply_assigned,
     cat_fit_workspace_bytes,
     cat_apply_workspace_bytes,
     library_path,

@@ -20,7 +20,8 @@ _STATUS = {0: "CAT_OK", 1: "CAT_ERR_INVALID_ARG", 2: "CAT_ERR_UNSUPPORTED", 3: "
 
 EXPORTS = ("cat_select_path", "cat_fit_workspace_bytes", "cat_apply_workspace_bytes", "cat_fit", "cat_apply",
            "cat_assign", "cat_update", "cat_stats", "cat_init_indices", "cat_last_error", "cat_profile_enable",
-           "cat_profile_read", "cat_debug_list_capacity")
+           "cat_profile_read", "cat_debug_list_capacity", "cat_pca_workspace_bytes", "cat_pca_fit", "cat_pca_project",
+           "cat_apply_assigned")
 
 
 class CatError(RuntimeError):
@@ -66,6 +67,14 @@ def load_library():
     lib.cat_profile_enable.restype = c.c_int
     lib.cat_profile_read.argtypes = [c.POINTER(c.c_float), c.c_int]
     lib.cat_profile_read.restype = c.c_int
+    lib.cat_pca_workspace_bytes.argtypes = [i64, i64, i32, c.c_int]
+    lib.cat_pca_workspace_bytes.restype = sz
+    lib.cat_pca_fit.argtypes = [vp, i64, i64, i32, c.c_int, i32, vp, vp, vp, vp, sz, vp]
+    lib.cat_pca_fit.restype = c.c_int
+    lib.cat_pca_project.argtypes = [vp, i64, i64, i32, c.c_int, vp, vp, vp, vp]
+    lib.cat_pca_project.restype = c.c_int
+    lib.cat_apply_assigned.argtypes = [vp, vp, i64, i64, i32, c.c_int, vp, vp, c.c_float, vp, vp]
+    lib.cat_apply_assigned.restype = c.c_int
     lib.cat_debug_list_capacity.argtypes = [c.c_int]
     lib.cat_debug_list_capacity.restype = c.c_int
     lib.cat_last_error.argtypes = []
@@ -244,3 +253,43 @@ def cat_stats(lq, fp, assignments, K, centroids=None, workspace=None):
                          gamma.data_ptr(), beta.data_ptr(), counts.data_ptr(),
                          workspace.data_ptr(), workspace.numel(), _stream()))
     return gamma, beta, counts
+
+
+def cat_pca_fit(lq, p, sweeps=0, workspace=None):
+    """PCA front-end: returns (mean D float32, components p x D float32, eigenvalues p float64), device tensors."""
+    lib = load_library()
+    N, D = lq.shape
+    dt = _dt(lq)
+    dev = lq.device
+    if workspace is None:
+        workspace = _workspace(lib.cat_pca_workspace_bytes(N, D, p, dt), dev)
+    mean = torch.empty((D,), dtype=torch.float32, device=dev)
+    comps = torch.empty((p, D), dtype=torch.float32, device=dev)
+    evals = torch.empty((p,), dtype=torch.float64, device=dev)
+    _check(lib.cat_pca_fit(_dev(lq, name="lq"), N, D, p, dt, sweeps, mean.data_ptr(), comps.data_ptr(), evals.data_ptr(),
+                           workspace.data_ptr(), workspace.numel(), _stream()))
+    return mean, comps, evals
+
+
+def cat_pca_project(lq, mean, components):
+    """z = (lq - mean) @ components.T as float32 N x p."""
+    lib = load_library()
+    N, D = lq.shape
+    p = components.shape[0]
+    z = torch.empty((N, p), dtype=torch.float32, device=lq.device)
+    _check(lib.cat_pca_project(_dev(lq, name="lq"), N, D, p, _dt(lq), _dev(mean, torch.float32, (D,), "mean"),
+                               _dev(components, torch.float32, (p, D), "components"), z.data_ptr(), _stream()))
+    return z
+
+
+def cat_apply_assigned(lq, assignments, gamma, beta, alpha=1.0, out=None):
+    """Affine correction by given labels (the inference step when clusters are found in PCA space)."""
+    lib = load_library()
+    N, D = lq.shape
+    K = gamma.shape[0]
+    if out is None:
+        out = torch.empty_like(lq)
+    _check(lib.cat_apply_assigned(_dev(lq, name="lq"), _dev(assignments, torch.int32, (N,), "assignments"), N, D, K, _dt(lq),
+                                  _dev(gamma, torch.float32, (K, D), "gamma"), _dev(beta, torch.float32, (K, D), "beta"),
+                                  float(alpha), _dev(out, lq.dtype, (N, D), "out"), _stream()))
+    return out

@@ -1,0 +1,535 @@
+// PCA front-end of CAT (Sec. 3.1; first step of Algorithms 1 and 2): the LQ vectors are reduced to
+// their p leading principal components before clustering, and the affine correction is then applied
+// by the cluster found in that space.  Everything here runs on the device in double precision
+// except the projection (fp32 accumulation) and the labelled affine map:
+//
+//   cat_pca_fit       column means -> population covariance (D x D) -> symmetric eigendecomposition
+//                     (one-sided Jacobi on the rows) -> the p leading directions
+//   cat_pca_project   z = (x - mean) W^T
+//   cat_apply_assigned   corrected = x + alpha ((gamma_a x + beta_a) - x) for given labels a
+#include "cat_common.h"
+
+namespace cat {
+
+typedef __attribute__((ext_vector_type(4))) float f32x4_t;
+
+constexpr int kPcaMaxD = 2048;  // eigen workspace is 2 (D+1)^2 doubles; the selection kernel keeps D values in LDS
+
+// ---- column sums ---------------------------------------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(256) void k_pca_colsum(const T* __restrict__ x, int64_t N, int64_t D, int64_t rows_per_block,
+                                                    double* __restrict__ sum) {
+    const int64_t j = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int64_t r0 = (int64_t)blockIdx.y * rows_per_block;
+    const int64_t r1 = r0 + rows_per_block < N ? r0 + rows_per_block : N;
+    if (j >= D) return;
+    double s = 0.0;
+    for (int64_t i = r0; i < r1; i++) s += (double)ld_elem(x + i * D + j);
+    atomicAdd(sum + j, s);
+}
+
+__global__ void k_pca_mean(const double* __restrict__ sum, int64_t N, int64_t D, double* __restrict__ mean_d,
+                           float* __restrict__ mean_f) {
+    const int64_t j = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (j >= D) return;
+    const double m = sum[j] / (double)N;
+    mean_d[j] = m;
+    mean_f[j] = (float)m;
+}
+
+// ---- covariance: one workgroup per (32 x 32 tile of the upper triangle, row range) ----------------
+// 256 threads, each owns a 2 x 2 block of the tile; 64 centred rows of both column blocks are staged
+// in LDS as doubles per round.  W (ld = ldw) receives sum (x_a - m_a)(x_b - m_b); scaled and mirrored
+// afterwards.
+constexpr int kCovTile = 32, kCovRows = 64;
+template <typename T>
+__global__ __launch_bounds__(256) void k_pca_cov(const T* __restrict__ x, int64_t N, int64_t D, const double* __restrict__ mean,
+                                                 int64_t rows_per_block, int32_t ntile, double* __restrict__ W, int64_t ldw) {
+    __shared__ double sa[kCovRows][kCovTile + 1], sb[kCovRows][kCovTile + 1];
+    // tile index -> (ta <= tb)
+    int t = blockIdx.x, ta = 0;
+    while (t >= ntile - ta) {
+        t -= ntile - ta;
+        ta++;
+    }
+    const int tb = ta + t;
+    const int64_t a0 = (int64_t)ta * kCovTile, b0 = (int64_t)tb * kCovTile;
+    const int64_t r0 = (int64_t)blockIdx.y * rows_per_block;
+    const int64_t r1 = r0 + rows_per_block < N ? r0 + rows_per_block : N;
+    const int ty = threadIdx.x >> 4, tx = threadIdx.x & 15;  // 16 x 16 threads, 2 x 2 outputs each
+    double c00 = 0.0, c01 = 0.0, c10 = 0.0, c11 = 0.0;
+    for (int64_t rb = r0; rb < r1; rb += kCovRows) {
+        __syncthreads();
+        for (int i = threadIdx.x; i < kCovRows * kCovTile; i += blockDim.x) {
+            const int r = i / kCovTile, c = i - r * kCovTile;
+            const int64_t row = rb + r;
+            double va = 0.0, vb = 0.0;
+            if (row < r1) {
+                if (a0 + c < D) va = (double)ld_elem(x + row * D + a0 + c) - mean[a0 + c];
+                if (b0 + c < D) vb = (double)ld_elem(x + row * D + b0 + c) - mean[b0 + c];
+            }
+            sa[r][c] = va;
+            sb[r][c] = vb;
+        }
+        __syncthreads();
+#pragma unroll 8
+        for (int r = 0; r < kCovRows; r++) {
+            const double a_0 = sa[r][2 * ty], a_1 = sa[r][2 * ty + 1];
+            const double b_0 = sb[r][2 * tx], b_1 = sb[r][2 * tx + 1];
+            c00 = fma(a_0, b_0, c00);
+            c01 = fma(a_0, b_1, c01);
+            c10 = fma(a_1, b_0, c10);
+            c11 = fma(a_1, b_1, c11);
+        }
+    }
+    const int64_t ia = a0 + 2 * ty, ib = b0 + 2 * tx;
+    if (ia < D && ib < D) atomicAdd(W + ia * ldw + ib, c00);
+    if (ia < D && ib + 1 < D) atomicAdd(W + ia * ldw + ib + 1, c01);
+    if (ia + 1 < D && ib < D) atomicAdd(W + (ia + 1) * ldw + ib, c10);
+    if (ia + 1 < D && ib + 1 < D) atomicAdd(W + (ia + 1) * ldw + ib + 1, c11);
+}
+
+// scale the upper triangle by 1/N, set the padding row / column (an eigenvalue below every eigenvalue
+// of a covariance, so it is never selected), start Vt as the identity; then mirror into the lower
+// triangle (a second launch, so that it reads finished values)
+__global__ void k_pca_cov_finish(double* __restrict__ W, double* __restrict__ Vt, int64_t D, int64_t Dp, int64_t N) {
+    const int64_t i = (int64_t)blockIdx.y, j = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (j >= Dp) return;
+    Vt[i * Dp + j] = (i == j) ? 1.0 : 0.0;
+    if (i >= D || j >= D)
+        W[i * Dp + j] = (i == j) ? -1.0 : 0.0;
+    else if (i <= j)
+        W[i * Dp + j] = W[i * Dp + j] / (double)N;
+}
+__global__ void k_pca_mirror(double* __restrict__ W, int64_t D, int64_t Dp) {
+    const int64_t i = (int64_t)blockIdx.y, j = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < D && j < i) W[i * Dp + j] = W[j * Dp + i];
+}
+
+// ---- one-sided Jacobi on the rows of W (= the symmetric matrix at the start) ------------------------
+// A rotation of rows p and q makes them orthogonal; the same rotation is applied to Vt.  When all rows
+// are orthogonal, W = Lambda Q^T and Vt = Q^T for the eigendecomposition Q Lambda Q^T of the start
+// matrix: row i of Vt is the eigenvector, w_i . vt_i its eigenvalue.  One step rotates Dp / 2 disjoint
+// pairs chosen by the round-robin (tournament) schedule; Dp - 1 steps visit every pair once (a sweep).
+// Rows are contiguous, so every access is coalesced.  One workgroup per pair.
+__global__ __launch_bounds__(256) void k_pca_jacobi_step(double* __restrict__ W, double* __restrict__ Vt, int32_t Dp, int32_t step) {
+    __shared__ double s_red[3][4];
+    __shared__ double s_cs[2];
+    const int k = blockIdx.x, m = Dp - 1;
+    int p, q;
+    if (k == 0) {
+        p = step;
+        q = m;
+    } else {
+        p = (step + k) % m;
+        q = (step - k + m) % m;
+    }
+    double* wp = W + (int64_t)p * Dp;
+    double* wq = W + (int64_t)q * Dp;
+    double a = 0.0, b = 0.0, g = 0.0;
+    for (int j = threadIdx.x; j < Dp; j += blockDim.x) {
+        const double x = wp[j], y = wq[j];
+        a = fma(x, x, a);
+        b = fma(y, y, b);
+        g = fma(x, y, g);
+    }
+    a = wave_sum(a);
+    b = wave_sum(b);
+    g = wave_sum(g);
+    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+    if (lane == 0) {
+        s_red[0][wave] = a;
+        s_red[1][wave] = b;
+        s_red[2][wave] = g;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        a = s_red[0][0] + s_red[0][1] + s_red[0][2] + s_red[0][3];
+        b = s_red[1][0] + s_red[1][1] + s_red[1][2] + s_red[1][3];
+        g = s_red[2][0] + s_red[2][1] + s_red[2][2] + s_red[2][3];
+        double c = 1.0, s = 0.0;
+        if (fabs(g) > 1e-15 * sqrt(a * b) && g != 0.0) {
+            const double zeta = (b - a) / (2.0 * g);
+            const double t = (zeta >= 0.0 ? 1.0 : -1.0) / (fabs(zeta) + sqrt(1.0 + zeta * zeta));
+            c = 1.0 / sqrt(1.0 + t * t);
+            s = c * t;
+        }
+        s_cs[0] = c;
+        s_cs[1] = s;
+    }
+    __syncthreads();
+    const double c = s_cs[0], s = s_cs[1];
+    if (s == 0.0) return;  // uniform
+    double* vp = Vt + (int64_t)p * Dp;
+    double* vq = Vt + (int64_t)q * Dp;
+    for (int j = threadIdx.x; j < Dp; j += blockDim.x) {
+        const double x = wp[j], y = wq[j];
+        wp[j] = c * x - s * y;
+        wq[j] = s * x + c * y;
+        const double u = vp[j], v = vq[j];
+        vp[j] = c * u - s * v;
+        vq[j] = s * u + c * v;
+    }
+}
+
+// eigenvalue of row i: w_i . vt_i
+__global__ __launch_bounds__(256) void k_pca_rayleigh(const double* __restrict__ W, const double* __restrict__ Vt, int32_t Dp,
+                                                      double* __restrict__ lambda) {
+    __shared__ double s_red[4];
+    const int i = blockIdx.x;
+    double a = 0.0;
+    for (int j = threadIdx.x; j < Dp; j += blockDim.x) a = fma(W[(int64_t)i * Dp + j], Vt[(int64_t)i * Dp + j], a);
+    a = wave_sum(a);
+    if ((threadIdx.x & (kWave - 1)) == 0) s_red[threadIdx.x / kWave] = a;
+    __syncthreads();
+    if (threadIdx.x == 0) lambda[i] = s_red[0] + s_red[1] + s_red[2] + s_red[3];
+}
+
+// the p largest eigenvalues in descending order (lowest row index first among equals), their rows of Vt
+// as unit directions whose entry of largest magnitude (the first such) is positive.  One workgroup.
+__global__ __launch_bounds__(256) void k_pca_select(const double* __restrict__ lambda, const double* __restrict__ Vt, int32_t D,
+                                                    int32_t Dp, int32_t p, float* __restrict__ comps, double* __restrict__ evals) {
+    __shared__ double s_lam[kPcaMaxD + 2];
+    __shared__ double s_val[256];
+    __shared__ int s_idx[256];
+    for (int i = threadIdx.x; i < Dp; i += blockDim.x) s_lam[i] = lambda[i];
+    __syncthreads();
+    for (int c = 0; c < p; c++) {
+        double best = -1e300;
+        int bi = 0x7fffffff;
+        for (int i = threadIdx.x; i < Dp; i += blockDim.x) {
+            const double v = s_lam[i];
+            if (v > best || (v == best && i < bi)) {
+                best = v;
+                bi = i;
+            }
+        }
+        s_val[threadIdx.x] = best;
+        s_idx[threadIdx.x] = bi;
+        __syncthreads();
+        for (int o = 128; o > 0; o >>= 1) {
+            if ((int)threadIdx.x < o) {
+                const double v = s_val[threadIdx.x + o];
+                const int i = s_idx[threadIdx.x + o];
+                if (v > s_val[threadIdx.x] || (v == s_val[threadIdx.x] && i < s_idx[threadIdx.x])) {
+                    s_val[threadIdx.x] = v;
+                    s_idx[threadIdx.x] = i;
+                }
+            }
+            __syncthreads();
+        }
+        const int row = s_idx[0];
+        const double lam = s_val[0];
+        __syncthreads();
+        // sign: first entry of largest magnitude among the D real coordinates
+        double am = -1.0;
+        int aj = 0x7fffffff;
+        for (int j = threadIdx.x; j < D; j += blockDim.x) {
+            const double v = fabs(Vt[(int64_t)row * Dp + j]);
+            if (v > am || (v == am && j < aj)) {
+                am = v;
+                aj = j;
+            }
+        }
+        s_val[threadIdx.x] = am;
+        s_idx[threadIdx.x] = aj;
+        __syncthreads();
+        for (int o = 128; o > 0; o >>= 1) {
+            if ((int)threadIdx.x < o) {
+                const double v = s_val[threadIdx.x + o];
+                const int j = s_idx[threadIdx.x + o];
+                if (v > s_val[threadIdx.x] || (v == s_val[threadIdx.x] && j < s_idx[threadIdx.x])) {
+                    s_val[threadIdx.x] = v;
+                    s_idx[threadIdx.x] = j;
+                }
+            }
+            __syncthreads();
+        }
+        const double sgn = Vt[(int64_t)row * Dp + s_idx[0]] < 0.0 ? -1.0 : 1.0;
+        __syncthreads();
+        for (int j = threadIdx.x; j < D; j += blockDim.x) comps[(int64_t)c * D + j] = (float)(sgn * Vt[(int64_t)row * Dp + j]);
+        if (threadIdx.x == 0) {
+            if (evals) evals[c] = lam;
+            s_lam[row] = -1e301;  // taken
+        }
+        __syncthreads();
+    }
+}
+
+// ---- projection: z[i][c] = sum_j (x[i][j] - mean[j]) comps[c][j] -----------------------------------
+// A skinny GEMM in fp32 on the fp32 matrix cores (v_mfma_f32_16x16x4_f32: exact products, fp32
+// accumulation), one wave per tile of 16 rows, 8 waves per workgroup.  Directions are the M dimension
+// and rows the N dimension, so a lane ends up with 4 consecutive scores of one row (one 16-byte store).
+// The k index of the MFMA is free to be any channel as long as both operands agree: lane (n, g) loads
+// the four channels 16 s + 4 g .. + 3 of row n in one 16-byte load (64 contiguous bytes per row and
+// instruction) and feeds them to four MFMAs; the directions are staged per 128-channel chunk in LDS
+// in exactly that order ([step][tile][lane][4]), so their reads are 16 bytes per lane, conflict-free.
+// NT = 16-direction tiles per pass (p <= 16 NT per pass; more directions take more passes over the rows).
+constexpr int kProjWaves = 8, kProjChunk = 128;
+template <typename T, int NT>
+__global__ __launch_bounds__(kProjWaves * kWave) void k_pca_project(const T* __restrict__ x, int64_t N, int64_t D, int32_t p,
+                                                                    const float* __restrict__ mean, const float* __restrict__ comps,
+                                                                    float* __restrict__ z) {
+    __shared__ __align__(16) float s_w[(kProjChunk / 16) * NT * kWave * 4];  // 8 steps x NT tiles x 64 lanes x 4
+    __shared__ __align__(16) float s_m[kProjChunk];
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
+    const int n = lane & 15, g = lane >> 4;
+    const int64_t ntiles = (N + 15) / 16;
+    const int64_t tile = (int64_t)blockIdx.x * kProjWaves + wave;
+    const int64_t row = tile * 16 + n;
+    const int64_t rowc = row < N ? row : N - 1;  // rows past the end repeat the last row; never stored
+    const T* xr = x + rowc * D;
+    for (int c0 = 0; c0 < p; c0 += 16 * NT) {
+        f32x4_t acc[NT];
+#pragma unroll
+        for (int t = 0; t < NT; t++) acc[t] = (f32x4_t){0.f, 0.f, 0.f, 0.f};
+        for (int64_t j0 = 0; j0 < D; j0 += kProjChunk) {
+            __syncthreads();
+            // directions of this chunk into operand order; zero outside p x D
+            for (int i = threadIdx.x; i < 16 * NT * (kProjChunk / 4); i += blockDim.x) {
+                const int r = i / (kProjChunk / 4), q = i - r * (kProjChunk / 4);  // direction in pass, 4-channel group
+                const int64_t ch = j0 + 4 * q;
+                f32x4_t v = (f32x4_t){0.f, 0.f, 0.f, 0.f};
+                if (c0 + r < p) {
+                    const float* src = comps + (int64_t)(c0 + r) * D + ch;
+                    if (ch + 3 < D && ((D & 3) == 0)) {
+                        v = *(const f32x4_t*)src;
+                    } else {
+                        if (ch < D) v.x = src[0];
+                        if (ch + 1 < D) v.y = src[1];
+                        if (ch + 2 < D) v.z = src[2];
+                        if (ch + 3 < D) v.w = src[3];
+                    }
+                }
+                const int s_ = q >> 2, gg = q & 3, t = r >> 4, m = r & 15;
+                *(f32x4_t*)&s_w[(((s_ * NT + t) * kWave) + gg * 16 + m) * 4] = v;
+            }
+            for (int i = threadIdx.x; i < kProjChunk; i += blockDim.x) s_m[i] = j0 + i < D ? mean[j0 + i] : 0.f;
+            __syncthreads();
+            if (tile < ntiles) {
+                f32x4_t xv[kProjChunk / 16];
+#pragma unroll
+                for (int s_ = 0; s_ < kProjChunk / 16; s_++) {
+                    const int64_t ch = j0 + 16 * s_ + 4 * g;
+                    float e[4];
+                    if ((D & 3) == 0) {  // rows keep 16-byte (bf16: 8-byte) alignment: one load per group
+                        if (ch < D) {
+                            if (sizeof(T) == 4) {
+                                const f32x4_t v4 = *(const f32x4_t*)(xr + ch);
+                                e[0] = v4.x; e[1] = v4.y; e[2] = v4.z; e[3] = v4.w;
+                            } else {
+                                const uint2 w2 = *(const uint2*)(xr + ch);
+                                e[0] = __uint_as_float(w2.x << 16); e[1] = __uint_as_float(w2.x & 0xFFFF0000u);
+                                e[2] = __uint_as_float(w2.y << 16); e[3] = __uint_as_float(w2.y & 0xFFFF0000u);
+                            }
+                        } else {
+                            e[0] = e[1] = e[2] = e[3] = 0.f;
+                        }
+                    } else {
+#pragma unroll
+                        for (int u = 0; u < 4; u++) e[u] = ch + u < D ? ld_elem(xr + ch + u) : 0.f;
+                    }
+                    const f32x4_t mv = *(const f32x4_t*)&s_m[16 * s_ + 4 * g];
+                    xv[s_] = (f32x4_t){ch < D ? e[0] - mv.x : 0.f, ch + 1 < D ? e[1] - mv.y : 0.f, ch + 2 < D ? e[2] - mv.z : 0.f,
+                                       ch + 3 < D ? e[3] - mv.w : 0.f};
+                }
+#pragma unroll
+                for (int s_ = 0; s_ < kProjChunk / 16; s_++) {
+#pragma unroll
+                    for (int t = 0; t < NT; t++) {
+                        const f32x4_t wv = *(const f32x4_t*)&s_w[(((s_ * NT + t) * kWave) + lane) * 4];
+                        acc[t] = __builtin_amdgcn_mfma_f32_16x16x4f32(wv.x, xv[s_].x, acc[t], 0, 0, 0);
+                        acc[t] = __builtin_amdgcn_mfma_f32_16x16x4f32(wv.y, xv[s_].y, acc[t], 0, 0, 0);
+                        acc[t] = __builtin_amdgcn_mfma_f32_16x16x4f32(wv.z, xv[s_].z, acc[t], 0, 0, 0);
+                        acc[t] = __builtin_amdgcn_mfma_f32_16x16x4f32(wv.w, xv[s_].w, acc[t], 0, 0, 0);
+                    }
+                }
+            }
+        }
+        if (row < N) {
+#pragma unroll
+            for (int t = 0; t < NT; t++) {
+                const int c = c0 + 16 * t + 4 * g;
+                float* o = z + row * p + c;
+                if (c + 3 < p && ((p & 3) == 0)) {
+                    *(f32x4_t*)o = acc[t];
+                } else {
+                    if (c < p) o[0] = acc[t].x;
+                    if (c + 1 < p) o[1] = acc[t].y;
+                    if (c + 2 < p) o[2] = acc[t].z;
+                    if (c + 3 < p) o[3] = acc[t].w;
+                }
+            }
+        }
+    }
+}
+
+// ---- affine map by given labels ------------------------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(256) void k_apply_assigned(const T* __restrict__ x, const int32_t* __restrict__ assign, int64_t N,
+                                                        int64_t D, int32_t K, const float* __restrict__ gamma,
+                                                        const float* __restrict__ beta, float alpha, T* __restrict__ out) {
+    const int lane = threadIdx.x & (kWave - 1);
+    const int64_t row = (int64_t)blockIdx.x * (blockDim.x / kWave) + threadIdx.x / kWave;
+    if (row >= N) return;
+    const int a = assign[row];
+    const bool ok = a >= 0 && a < K;  // a label outside [0, K) leaves the row as it is
+    for (int64_t j = lane; j < D; j += kWave) {
+        const float v = ld_elem(x + row * D + j);
+        float r = v;
+        if (ok) {
+            const float g = 1.f + alpha * (gamma[(int64_t)a * D + j] - 1.f), b = alpha * beta[(int64_t)a * D + j];
+            r = fmaf(g, v, b);
+        }
+        st_elem(out + row * D + j, r);
+    }
+}
+
+// ---- host side ---------------------------------------------------------------------------------
+static inline size_t pad256(size_t x) { return (x + 255) & ~(size_t)255; }
+static inline int64_t even_up(int64_t D) { return D + (D & 1); }
+
+struct PcaWs {
+    double* sum;     // D
+    double* mean;    // D
+    double* lambda;  // Dp
+    double* W;       // Dp x Dp
+    double* Vt;      // Dp x Dp
+    size_t bytes;
+};
+static PcaWs pca_carve(void* base, int64_t D) {
+    const int64_t Dp = even_up(D);
+    PcaWs w;
+    char* b = (char*)base;
+    size_t off = 0;
+    w.sum = (double*)(b + off);
+    off += pad256((size_t)D * 8);
+    w.mean = (double*)(b + off);
+    off += pad256((size_t)D * 8);
+    w.lambda = (double*)(b + off);
+    off += pad256((size_t)Dp * 8);
+    w.W = (double*)(b + off);
+    off += pad256((size_t)Dp * Dp * 8);
+    w.Vt = (double*)(b + off);
+    off += pad256((size_t)Dp * Dp * 8);
+    w.bytes = off;
+    return w;
+}
+
+static bool pca_shape_ok(int64_t N, int64_t D, int32_t p, cat_dtype dt) {
+    return (dt == CAT_F32 || dt == CAT_BF16) && N >= 1 && D >= 1 && D <= kPcaMaxD && p >= 1 && (int64_t)p <= D &&
+           N <= ((int64_t)1 << 40);
+}
+
+}  // namespace cat
+
+using namespace cat;
+
+extern "C" {
+
+size_t cat_pca_workspace_bytes(int64_t N, int64_t D, int32_t p, cat_dtype dt) {
+    if (!pca_shape_ok(N, D, p, dt)) return 0;
+    return pca_carve(nullptr, D).bytes;
+}
+
+cat_status cat_pca_fit(const void* lq, int64_t N, int64_t D, int32_t p, cat_dtype dt, int32_t sweeps, float* mean,
+                       float* components, double* eigenvalues, void* workspace, size_t workspace_bytes, void* hip_stream) {
+    if (!pca_shape_ok(N, D, p, dt))
+        return set_error(CAT_ERR_INVALID_ARG, "cat_pca_fit: need 1 <= p <= D <= %d, N >= 1 (N=%lld D=%lld p=%d dt=%d)", kPcaMaxD,
+                         (long long)N, (long long)D, (int)p, (int)dt);
+    if (!lq || !mean || !components) return set_error(CAT_ERR_INVALID_ARG, "cat_pca_fit: null argument");
+    if (sweeps < 0 || sweeps > 64) return set_error(CAT_ERR_INVALID_ARG, "cat_pca_fit: sweeps must be in 0 .. 64");
+    if (sweeps == 0) sweeps = 12;
+    PcaWs w = pca_carve(workspace, D);
+    if (!workspace || workspace_bytes < w.bytes)
+        return set_error(CAT_ERR_WORKSPACE, "cat_pca_fit: workspace of %zu bytes needed, %zu given", w.bytes, workspace_bytes);
+    hipStream_t st = (hipStream_t)hip_stream;
+    const int64_t Dp = even_up(D);
+    cat_status s;
+    if ((s = launch_fill_zero(w.sum, (size_t)D * 8, st)) != CAT_OK) return s;
+    if ((s = launch_fill_zero(w.W, (size_t)Dp * Dp * 8, st)) != CAT_OK) return s;
+    // about 64 row ranges: enough workgroups for the covariance without drowning it in atomics
+    int64_t rpb = (N + 63) / 64;
+    rpb = (rpb + kCovRows - 1) / kCovRows * kCovRows;
+    const unsigned nrb = (unsigned)((N + rpb - 1) / rpb);
+    {
+        dim3 g((unsigned)((D + 255) / 256), nrb), b(256);
+        if (dt == CAT_F32)
+            hipLaunchKernelGGL(k_pca_colsum<float>, g, b, 0, st, (const float*)lq, N, D, rpb, w.sum);
+        else
+            hipLaunchKernelGGL(k_pca_colsum<bf16_t>, g, b, 0, st, (const bf16_t*)lq, N, D, rpb, w.sum);
+        CAT_LAUNCH_CHECK("k_pca_colsum");
+        hipLaunchKernelGGL(k_pca_mean, dim3((unsigned)((D + 255) / 256)), dim3(256), 0, st, w.sum, N, D, w.mean, mean);
+        CAT_LAUNCH_CHECK("k_pca_mean");
+    }
+    {
+        const int ntile = (int)((D + kCovTile - 1) / kCovTile);
+        dim3 g((unsigned)(ntile * (ntile + 1) / 2), nrb), b(256);
+        if (dt == CAT_F32)
+            hipLaunchKernelGGL(k_pca_cov<float>, g, b, 0, st, (const float*)lq, N, D, w.mean, rpb, ntile, w.W, Dp);
+        else
+            hipLaunchKernelGGL(k_pca_cov<bf16_t>, g, b, 0, st, (const bf16_t*)lq, N, D, w.mean, rpb, ntile, w.W, Dp);
+        CAT_LAUNCH_CHECK("k_pca_cov");
+        dim3 g2((unsigned)((Dp + 255) / 256), (unsigned)Dp);
+        hipLaunchKernelGGL(k_pca_cov_finish, g2, dim3(256), 0, st, w.W, w.Vt, D, Dp, N);
+        CAT_LAUNCH_CHECK("k_pca_cov_finish");
+        hipLaunchKernelGGL(k_pca_mirror, g2, dim3(256), 0, st, w.W, D, Dp);
+        CAT_LAUNCH_CHECK("k_pca_mirror");
+    }
+    if (Dp >= 2) {
+        for (int sw = 0; sw < sweeps; sw++)
+            for (int step = 0; step < Dp - 1; step++) {
+                hipLaunchKernelGGL(k_pca_jacobi_step, dim3((unsigned)(Dp / 2)), dim3(256), 0, st, w.W, w.Vt, (int32_t)Dp, step);
+                CAT_LAUNCH_CHECK("k_pca_jacobi_step");
+            }
+    }
+    hipLaunchKernelGGL(k_pca_rayleigh, dim3((unsigned)Dp), dim3(256), 0, st, w.W, w.Vt, (int32_t)Dp, w.lambda);
+    CAT_LAUNCH_CHECK("k_pca_rayleigh");
+    hipLaunchKernelGGL(k_pca_select, dim3(1), dim3(256), 0, st, w.lambda, w.Vt, (int32_t)D, (int32_t)Dp, p, components, eigenvalues);
+    CAT_LAUNCH_CHECK("k_pca_select");
+    return CAT_OK;
+}
+
+cat_status cat_pca_project(const void* lq, int64_t N, int64_t D, int32_t p, cat_dtype dt, const float* mean,
+                           const float* components, float* z, void* hip_stream) {
+    if ((dt != CAT_F32 && dt != CAT_BF16) || N < 1 || D < 1 || p < 1 || (int64_t)p > D)
+        return set_error(CAT_ERR_INVALID_ARG, "cat_pca_project: need N >= 1, 1 <= p <= D (N=%lld D=%lld p=%d dt=%d)", (long long)N,
+                         (long long)D, (int)p, (int)dt);
+    if (!lq || !mean || !components || !z) return set_error(CAT_ERR_INVALID_ARG, "cat_pca_project: null argument");
+    hipStream_t st = (hipStream_t)hip_stream;
+    const int64_t rows_per_block = kProjWaves * 16;
+    dim3 g((unsigned)((N + rows_per_block - 1) / rows_per_block)), b(kProjWaves * kWave);
+#define CAT_PROJ(T, NT) \
+    hipLaunchKernelGGL((k_pca_project<T, NT>), g, b, 0, st, (const T*)lq, N, D, p, mean, components, z)
+    if (dt == CAT_F32) {
+        if (p <= 16) CAT_PROJ(float, 1); else if (p <= 32) CAT_PROJ(float, 2); else CAT_PROJ(float, 4);
+    } else {
+        if (p <= 16) CAT_PROJ(bf16_t, 1); else if (p <= 32) CAT_PROJ(bf16_t, 2); else CAT_PROJ(bf16_t, 4);
+    }
+#undef CAT_PROJ
+    CAT_LAUNCH_CHECK("k_pca_project");
+    return CAT_OK;
+}
+
+cat_status cat_apply_assigned(const void* lq, const int32_t* assignments, int64_t N, int64_t D, int32_t K, cat_dtype dt,
+                              const float* gamma, const float* beta, float alpha, void* corrected, void* hip_stream) {
+    if ((dt != CAT_F32 && dt != CAT_BF16) || N < 1 || D < 1 || K < 1 || K > CAT_MAX_K)
+        return set_error(CAT_ERR_INVALID_ARG, "cat_apply_assigned: bad shape (N=%lld D=%lld K=%d dt=%d)", (long long)N, (long long)D,
+                         (int)K, (int)dt);
+    if (!lq || !assignments || !gamma || !beta || !corrected || corrected == lq)
+        return set_error(CAT_ERR_INVALID_ARG, "cat_apply_assigned: null or aliased argument");
+    if (!(alpha == alpha) || alpha - alpha != 0.f) return set_error(CAT_ERR_INVALID_ARG, "cat_apply_assigned: alpha must be finite");
+    hipStream_t st = (hipStream_t)hip_stream;
+    dim3 g((unsigned)((N + 3) / 4)), b(256);
+    if (dt == CAT_F32)
+        hipLaunchKernelGGL(k_apply_assigned<float>, g, b, 0, st, (const float*)lq, assignments, N, D, K, gamma, beta, alpha,
+                           (float*)corrected);
+    else
+        hipLaunchKernelGGL(k_apply_assigned<bf16_t>, g, b, 0, st, (const bf16_t*)lq, assignments, N, D, K, gamma, beta, alpha,
+                           (bf16_t*)corrected);
+    CAT_LAUNCH_CHECK("k_apply_assigned");
+    return CAT_OK;
+}
+
+}  // extern "C"
