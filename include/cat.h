@@ -185,6 +185,29 @@ cat_status cat_init_indices(int64_t N, int32_t K, uint64_t seed, int64_t *idx_ou
  *   a = assignments[i] given by the caller; a label outside [0, K) copies the row.
  *   corrected out, N x D of dt, may not alias lq.  No workspace.
  */
+/*
+ * Algorithm 1 and Algorithm 2 with pca_dim = p as single calls, composed of the steps above:
+ *   cat_fit_pca    PCA of lq -> scores -> init (seeded rows of the scores), `iters` Lloyd iterations and
+ *                  the final assignment in score space -> gamma, beta on the full vectors.
+ *                  mean (D), components (p x D), centroids_z (K x p), gamma, beta (K x D) out, float;
+ *                  assignments out N int32; counts (K) and inertia (iters + 1, of the score-space
+ *                  clustering) out, nullable.
+ *   cat_apply_pca  scores -> nearest centroid in score space -> affine map of the full vector with
+ *                  the alpha-blend.  corrected out (may not alias lq); assignments out, nullable.
+ */
+size_t cat_fit_pca_workspace_bytes(int64_t N, int64_t D, int32_t K, int32_t p, cat_dtype dt);
+cat_status cat_fit_pca(const void *lq, const void *fp, int64_t N, int64_t D, int32_t K, int32_t p,
+                       int32_t iters, uint64_t seed, cat_dtype dt,
+                       float *mean, float *components, float *centroids_z, float *gamma, float *beta,
+                       int32_t *assignments, int32_t *counts, double *inertia,
+                       void *workspace, size_t workspace_bytes, void *hip_stream);
+size_t cat_apply_pca_workspace_bytes(int64_t N, int64_t D, int32_t K, int32_t p, cat_dtype dt);
+cat_status cat_apply_pca(const void *lq, int64_t N, int64_t D, int32_t K, int32_t p, cat_dtype dt,
+                         const float *mean, const float *components, const float *centroids_z,
+                         const float *gamma, const float *beta, float alpha,
+                         void *corrected, int32_t *assignments,
+                         void *workspace, size_t workspace_bytes, void *hip_stream);
+
 size_t cat_pca_workspace_bytes(int64_t N, int64_t D, int32_t p, cat_dtype dt);
 cat_status cat_pca_fit(const void *lq, int64_t N, int64_t D, int32_t p, cat_dtype dt, int32_t sweeps,
                        float *mean, float *components, double *eigenvalues,

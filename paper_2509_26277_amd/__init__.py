@@ -16,6 +16,8 @@ from .binding import (  # noqa: F401
     cat_pca_fit,
     cat_pca_project,
     cat_apply_assigned,
+    cat_fit_pca,
+    cat_apply_pca,
     cat_fit_workspace_bytes,
     cat_apply_workspace_bytes,
     library_path,

@@ -21,7 +21,7 @@ _STATUS = {0: "CAT_OK", 1: "CAT_ERR_INVALID_ARG", 2: "CAT_ERR_UNSUPPORTED", 3: "
 EXPORTS = ("cat_select_path", "cat_fit_workspace_bytes", "cat_apply_workspace_bytes", "cat_fit", "cat_apply",
            "cat_assign", "cat_update", "cat_stats", "cat_init_indices", "cat_last_error", "cat_profile_enable",
            "cat_profile_read", "cat_debug_list_capacity", "cat_pca_workspace_bytes", "cat_pca_fit", "cat_pca_project",
-           "cat_apply_assigned")
+           "cat_apply_assigned", "cat_fit_pca_workspace_bytes", "cat_fit_pca", "cat_apply_pca_workspace_bytes", "cat_apply_pca")
 
 
 class CatError(RuntimeError):
@@ -75,6 +75,14 @@ def load_library():
     lib.cat_pca_project.restype = c.c_int
     lib.cat_apply_assigned.argtypes = [vp, vp, i64, i64, i32, c.c_int, vp, vp, c.c_float, vp, vp]
     lib.cat_apply_assigned.restype = c.c_int
+    lib.cat_fit_pca_workspace_bytes.argtypes = [i64, i64, i32, i32, c.c_int]
+    lib.cat_fit_pca_workspace_bytes.restype = sz
+    lib.cat_fit_pca.argtypes = [vp, vp, i64, i64, i32, i32, i32, u64, c.c_int, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.cat_fit_pca.restype = c.c_int
+    lib.cat_apply_pca_workspace_bytes.argtypes = [i64, i64, i32, i32, c.c_int]
+    lib.cat_apply_pca_workspace_bytes.restype = sz
+    lib.cat_apply_pca.argtypes = [vp, i64, i64, i32, i32, c.c_int, vp, vp, vp, vp, vp, c.c_float, vp, vp, vp, sz, vp]
+    lib.cat_apply_pca.restype = c.c_int
     lib.cat_debug_list_capacity.argtypes = [c.c_int]
     lib.cat_debug_list_capacity.restype = c.c_int
     lib.cat_last_error.argtypes = []
@@ -293,3 +301,47 @@ def cat_apply_assigned(lq, assignments, gamma, beta, alpha=1.0, out=None):
                                   _dev(gamma, torch.float32, (K, D), "gamma"), _dev(beta, torch.float32, (K, D), "beta"),
                                   float(alpha), _dev(out, lq.dtype, (N, D), "out"), _stream()))
     return out
+
+
+def cat_fit_pca(lq, fp, K, p, iters, seed=0, want_inertia=True, workspace=None):
+    """CAT Fitting with the PCA front-end (clusters from the p leading principal components).  Returns a dict:
+    mean, components, centroids_z (K x p), gamma, beta (K x D), assignments, counts, inertia."""
+    lib = load_library()
+    N, D = lq.shape
+    dt = _dt(lq)
+    dev = lq.device
+    if workspace is None:
+        workspace = _workspace(lib.cat_fit_pca_workspace_bytes(N, D, K, p, dt), dev)
+    f32 = dict(dtype=torch.float32, device=dev)
+    mean, comps = torch.empty((D,), **f32), torch.empty((p, D), **f32)
+    cz, gamma, beta = torch.empty((K, p), **f32), torch.empty((K, D), **f32), torch.empty((K, D), **f32)
+    a = torch.empty((N,), dtype=torch.int32, device=dev)
+    counts = torch.empty((K,), dtype=torch.int32, device=dev)
+    inertia = torch.empty((max(iters, 0) + 1,), dtype=torch.float64, device=dev) if want_inertia else None
+    _check(lib.cat_fit_pca(_dev(lq, name="lq"), _dev(fp, lq.dtype, (N, D), "fp"), N, D, K, p, iters, seed & (2**64 - 1), dt,
+                           mean.data_ptr(), comps.data_ptr(), cz.data_ptr(), gamma.data_ptr(), beta.data_ptr(), a.data_ptr(),
+                           counts.data_ptr(), None if inertia is None else inertia.data_ptr(),
+                           workspace.data_ptr(), workspace.numel(), _stream()))
+    return dict(mean=mean, components=comps, centroids_z=cz, gamma=gamma, beta=beta, assignments=a, counts=counts,
+                inertia=inertia)
+
+
+def cat_apply_pca(lq, mean, components, centroids_z, gamma, beta, alpha=1.0, want_assignments=True, out=None, workspace=None):
+    """CAT Inferencing with the PCA front-end.  Returns (corrected, assignments or None)."""
+    lib = load_library()
+    N, D = lq.shape
+    K, p = centroids_z.shape
+    dt = _dt(lq)
+    dev = lq.device
+    if workspace is None:
+        workspace = _workspace(lib.cat_apply_pca_workspace_bytes(N, D, K, p, dt), dev)
+    if out is None:
+        out = torch.empty_like(lq)
+    a = torch.empty((N,), dtype=torch.int32, device=dev) if want_assignments else None
+    _check(lib.cat_apply_pca(_dev(lq, name="lq"), N, D, K, p, dt, _dev(mean, torch.float32, (D,), "mean"),
+                             _dev(components, torch.float32, (p, D), "components"),
+                             _dev(centroids_z, torch.float32, (K, p), "centroids_z"),
+                             _dev(gamma, torch.float32, (K, D), "gamma"), _dev(beta, torch.float32, (K, D), "beta"),
+                             float(alpha), _dev(out, lq.dtype, (N, D), "out"), None if a is None else a.data_ptr(),
+                             workspace.data_ptr(), workspace.numel(), _stream()))
+    return out, a

@@ -197,6 +197,46 @@ static cat_status step_stats(const void* lq, const void* fp, cat_dtype dt, const
     return launch_finalize_affine(w.acc, counts, w.pivx, w.pivy, gamma, beta, D, K, st);
 }
 
+// Initialisation, `iters` Lloyd iterations and the final assignment (everything of cat_fit before the
+// affine fit).  Leaves the counts and the first row of every cluster in w.counts / w.rep.
+static cat_status run_lloyd(const void* lq, cat_dtype dt, int64_t N, int64_t D, int32_t K, int32_t iters, uint64_t seed,
+                            const float* init_centroids, float* centroids, int32_t* assignments, double* inertia,
+                            const FitWs& w, hipStream_t st) {
+    const size_t KD = (size_t)K * (size_t)D;
+    const int path = g_path.load();
+    const bool fused = tile_supports(TILE_LLOYD, N, D, K, dt) && path != CAT_PATH_STREAM;
+    if (path == CAT_PATH_TILE && !fused)
+        return set_error(CAT_ERR_UNSUPPORTED, "tile path forced but D=%lld K=%d dt=%d does not fit it", (long long)D,
+                         (int)K, (int)dt);
+    // init: the fused path iterates in place in the caller's `centroids`
+    float* c0 = fused ? centroids : w.cent[0];
+    if (init_centroids) {
+        CAT_TRY(launch_copy_words(init_centroids, c0, (int64_t)KD, st));
+    } else {
+        CAT_TRY(launch_init_indices(N, K, seed, w.idx, st));
+        CAT_TRY(launch_gather_rows(lq, dt, D, K, w.idx, c0, st));
+    }
+    if (fused) {
+        // one assignment launch per Lloyd iteration; only the rows that change cluster touch the sums
+        CAT_TRY(tile_lloyd(lq, dt, N, D, K, iters, centroids, w.acc, assignments, w.counts, inertia, w.rep, w.tile, w.lloyd, st));
+    } else {
+        int cur = 0;
+        for (int32_t t = 0; t < iters; t++) {
+            CAT_TRY(step_assign(lq, dt, N, D, K, w.cent[cur], assignments, w.counts, inertia ? w.inertia : nullptr,
+                                nullptr, w.tile, st));
+            if (inertia) CAT_TRY(launch_copy_words(w.inertia, inertia + t, 2, st));
+            CAT_TRY(step_update(lq, dt, assignments, N, D, K, w.counts, w.cent[cur], w.cent[cur ^ 1], w.acc, w.sort, st));
+            cur ^= 1;
+        }
+        // final assignment against the final centroids
+        CAT_TRY(step_assign(lq, dt, N, D, K, w.cent[cur], assignments, w.counts, inertia ? w.inertia : nullptr, w.rep,
+                            w.tile, st));
+        if (inertia) CAT_TRY(launch_copy_words(w.inertia, inertia + iters, 2, st));
+        CAT_TRY(launch_copy_words(w.cent[cur], centroids, (int64_t)KD, st));
+    }
+    return CAT_OK;
+}
+
 }  // namespace cat
 
 using namespace cat;
@@ -338,39 +378,7 @@ cat_status cat_fit(const void* lq, const void* fp, int64_t N, int64_t D, int32_t
     FitWs w = carve_fit(workspace, N, D, K, dt);
     CAT_TRY(check_ws("cat_fit", workspace, workspace_bytes, w.bytes));
     hipStream_t st = (hipStream_t)hip_stream;
-    const size_t KD = (size_t)K * (size_t)D;
-
-    const int path = g_path.load();
-    const bool fused = tile_supports(TILE_LLOYD, N, D, K, dt) && path != CAT_PATH_STREAM;
-    if (path == CAT_PATH_TILE && !fused)
-        return set_error(CAT_ERR_UNSUPPORTED, "tile path forced but D=%lld K=%d dt=%d does not fit it", (long long)D,
-                         (int)K, (int)dt);
-    // init: the fused path iterates in place in the caller's `centroids`
-    float* c0 = fused ? centroids : w.cent[0];
-    if (init_centroids) {
-        CAT_TRY(launch_copy_words(init_centroids, c0, (int64_t)KD, st));
-    } else {
-        CAT_TRY(launch_init_indices(N, K, seed, w.idx, st));
-        CAT_TRY(launch_gather_rows(lq, dt, D, K, w.idx, c0, st));
-    }
-    if (fused) {
-        // one assignment launch per Lloyd iteration; only the rows that change cluster touch the sums
-        CAT_TRY(tile_lloyd(lq, dt, N, D, K, iters, centroids, w.acc, assignments, w.counts, inertia, w.rep, w.tile, w.lloyd, st));
-    } else {
-        int cur = 0;
-        for (int32_t t = 0; t < iters; t++) {
-            CAT_TRY(step_assign(lq, dt, N, D, K, w.cent[cur], assignments, w.counts, inertia ? w.inertia : nullptr,
-                                nullptr, w.tile, st));
-            if (inertia) CAT_TRY(launch_copy_words(w.inertia, inertia + t, 2, st));
-            CAT_TRY(step_update(lq, dt, assignments, N, D, K, w.counts, w.cent[cur], w.cent[cur ^ 1], w.acc, w.sort, st));
-            cur ^= 1;
-        }
-        // final assignment against the final centroids
-        CAT_TRY(step_assign(lq, dt, N, D, K, w.cent[cur], assignments, w.counts, inertia ? w.inertia : nullptr, w.rep,
-                            w.tile, st));
-        if (inertia) CAT_TRY(launch_copy_words(w.inertia, inertia + iters, 2, st));
-        CAT_TRY(launch_copy_words(w.cent[cur], centroids, (int64_t)KD, st));
-    }
+    CAT_TRY(run_lloyd(lq, dt, N, D, K, iters, seed, init_centroids, centroids, assignments, inertia, w, st));
     // affine fit on that partition, shifted by the centroids
     CAT_TRY(step_stats(lq, fp, dt, assignments, N, D, K, w.counts, w.rep, centroids, w, gamma, beta, st));
     if (counts) CAT_TRY(launch_copy_words(w.counts, counts, K, st));
@@ -408,6 +416,121 @@ cat_status cat_apply(const void* lq, int64_t N, int64_t D, int32_t K, cat_dtype 
                            st);
     return launch_assign_stream(lq, dt, N, D, K, centroids, assignments, nullptr, nullptr, nullptr, g, b, corrected,
                                 st);
+}
+
+
+// ---- Algorithms 1 and 2 with the PCA front-end, as single calls -----------------------------------
+struct PcaFitWs {
+    void* pca;      // cat_pca_fit scratch
+    float* z;       // N x p scores
+    void* lloyd;    // cat_fit scratch for (N, p, K, float)
+    void* stats;    // cat_fit scratch for (N, D, K, dt)
+    size_t pca_bytes, lloyd_bytes, stats_bytes, bytes;
+};
+static PcaFitWs carve_pca_fit(void* base, int64_t N, int64_t D, int32_t K, int32_t p, cat_dtype dt) {
+    PcaFitWs w;
+    w.pca_bytes = cat_pca_workspace_bytes(N, D, p, dt);
+    w.lloyd_bytes = carve_fit(nullptr, N, p, K, CAT_F32).bytes;
+    w.stats_bytes = carve_fit(nullptr, N, D, K, dt).bytes;
+    char* b = (char*)base;
+    size_t off = 0;
+    w.pca = b + off;
+    off += align256(w.pca_bytes);
+    w.z = (float*)(b + off);
+    off += align256((size_t)N * (size_t)p * sizeof(float));
+    w.lloyd = b + off;
+    off += align256(w.lloyd_bytes);
+    w.stats = b + off;
+    off += align256(w.stats_bytes);
+    w.bytes = off;
+    return w;
+}
+
+size_t cat_fit_pca_workspace_bytes(int64_t N, int64_t D, int32_t K, int32_t p, cat_dtype dt) {
+    if (!shape_ok(N, D, K, dt) || p < 1 || (int64_t)p > D || cat_pca_workspace_bytes(N, D, p, dt) == 0) return 0;
+    return carve_pca_fit(nullptr, N, D, K, p, dt).bytes;
+}
+
+cat_status cat_fit_pca(const void* lq, const void* fp, int64_t N, int64_t D, int32_t K, int32_t p, int32_t iters, uint64_t seed,
+                       cat_dtype dt, float* mean, float* components, float* centroids_z, float* gamma, float* beta,
+                       int32_t* assignments, int32_t* counts, double* inertia, void* workspace, size_t workspace_bytes,
+                       void* hip_stream) {
+    CAT_TRY(check_shape("cat_fit_pca", N, D, K, dt));
+    if (iters < 0) return set_error(CAT_ERR_INVALID_ARG, "cat_fit_pca: iters = %d is negative", (int)iters);
+    if (p < 1 || (int64_t)p > D) return set_error(CAT_ERR_INVALID_ARG, "cat_fit_pca: need 1 <= p <= D (p=%d)", (int)p);
+    CAT_TRY(check_ptr("cat_fit_pca", "lq", lq, 16));
+    CAT_TRY(check_ptr("cat_fit_pca", "fp", fp, 16));
+    CAT_TRY(check_ptr("cat_fit_pca", "mean", mean, 4));
+    CAT_TRY(check_ptr("cat_fit_pca", "components", components, 16));
+    CAT_TRY(check_ptr("cat_fit_pca", "centroids_z", centroids_z, 16));
+    CAT_TRY(check_ptr("cat_fit_pca", "gamma", gamma, 16));
+    CAT_TRY(check_ptr("cat_fit_pca", "beta", beta, 16));
+    CAT_TRY(check_ptr("cat_fit_pca", "assignments", assignments, 4));
+    if (cat_pca_workspace_bytes(N, D, p, dt) == 0)
+        return set_error(CAT_ERR_UNSUPPORTED, "cat_fit_pca: the PCA front-end does not take D=%lld", (long long)D);
+    PcaFitWs w = carve_pca_fit(workspace, N, D, K, p, dt);
+    CAT_TRY(check_ws("cat_fit_pca", workspace, workspace_bytes, w.bytes));
+    hipStream_t st = (hipStream_t)hip_stream;
+    CAT_TRY(cat_pca_fit(lq, N, D, p, dt, 0, mean, components, nullptr, w.pca, w.pca_bytes, hip_stream));
+    CAT_TRY(cat_pca_project(lq, N, D, p, dt, mean, components, w.z, hip_stream));
+    // clusters from the scores ...
+    FitWs wz = carve_fit(w.lloyd, N, p, K, CAT_F32);
+    CAT_TRY(run_lloyd(w.z, CAT_F32, N, p, K, iters, seed, nullptr, centroids_z, assignments, inertia, wz, st));
+    // ... the affine fit on the full vectors (rows are shared, so the counts and first rows carry over)
+    FitWs wx = carve_fit(w.stats, N, D, K, dt);
+    CAT_TRY(step_stats(lq, fp, dt, assignments, N, D, K, wz.counts, wz.rep, nullptr, wx, gamma, beta, st));
+    if (counts) CAT_TRY(launch_copy_words(wz.counts, counts, K, st));
+    return CAT_OK;
+}
+
+struct PcaApplyWs {
+    float* z;
+    int32_t* assign;
+    void* step;  // cat_fit scratch for (N, p, K, float): the assignment step
+    size_t step_bytes, bytes;
+};
+static PcaApplyWs carve_pca_apply(void* base, int64_t N, int32_t K, int32_t p) {
+    PcaApplyWs w;
+    w.step_bytes = carve_fit(nullptr, N, p, K, CAT_F32).bytes;
+    char* b = (char*)base;
+    size_t off = 0;
+    w.z = (float*)(b + off);
+    off += align256((size_t)N * (size_t)p * sizeof(float));
+    w.assign = (int32_t*)(b + off);
+    off += align256((size_t)N * sizeof(int32_t));
+    w.step = b + off;
+    off += align256(w.step_bytes);
+    w.bytes = off;
+    return w;
+}
+
+size_t cat_apply_pca_workspace_bytes(int64_t N, int64_t D, int32_t K, int32_t p, cat_dtype dt) {
+    if (!shape_ok(N, D, K, dt) || p < 1 || (int64_t)p > D) return 0;
+    return carve_pca_apply(nullptr, N, K, p).bytes;
+}
+
+cat_status cat_apply_pca(const void* lq, int64_t N, int64_t D, int32_t K, int32_t p, cat_dtype dt, const float* mean,
+                         const float* components, const float* centroids_z, const float* gamma, const float* beta, float alpha,
+                         void* corrected, int32_t* assignments, void* workspace, size_t workspace_bytes, void* hip_stream) {
+    CAT_TRY(check_shape("cat_apply_pca", N, D, K, dt));
+    if (p < 1 || (int64_t)p > D) return set_error(CAT_ERR_INVALID_ARG, "cat_apply_pca: need 1 <= p <= D (p=%d)", (int)p);
+    CAT_TRY(check_ptr("cat_apply_pca", "lq", lq, 16));
+    CAT_TRY(check_ptr("cat_apply_pca", "mean", mean, 4));
+    CAT_TRY(check_ptr("cat_apply_pca", "components", components, 16));
+    CAT_TRY(check_ptr("cat_apply_pca", "centroids_z", centroids_z, 16));
+    CAT_TRY(check_ptr("cat_apply_pca", "gamma", gamma, 16));
+    CAT_TRY(check_ptr("cat_apply_pca", "beta", beta, 16));
+    CAT_TRY(check_ptr("cat_apply_pca", "corrected", corrected, 16));
+    if (corrected == lq) return set_error(CAT_ERR_INVALID_ARG, "cat_apply_pca: corrected may not alias lq");
+    if (!std::isfinite(alpha)) return set_error(CAT_ERR_INVALID_ARG, "cat_apply_pca: alpha is not finite");
+    PcaApplyWs w = carve_pca_apply(workspace, N, K, p);
+    CAT_TRY(check_ws("cat_apply_pca", workspace, workspace_bytes, w.bytes));
+    hipStream_t st = (hipStream_t)hip_stream;
+    int32_t* a = assignments ? assignments : w.assign;
+    CAT_TRY(cat_pca_project(lq, N, D, p, dt, mean, components, w.z, hip_stream));
+    FitWs ws = carve_fit(w.step, N, p, K, CAT_F32);
+    CAT_TRY(step_assign(w.z, CAT_F32, N, p, K, centroids_z, a, nullptr, nullptr, nullptr, ws.tile, st));
+    return cat_apply_assigned(lq, a, N, D, K, dt, gamma, beta, alpha, corrected, hip_stream);
 }
 
 }  // extern "C"

@@ -142,3 +142,46 @@ def test_pca_argument_errors_are_statuses():
     with pytest.raises(binding.CatError) as e:
         cat_pca_fit(torch.zeros((4, 4096), device="cuda"), 2, workspace=torch.empty(256, dtype=torch.uint8, device="cuda"))
     assert e.value.status == 1  # D above the limit
+
+
+@pytest.mark.parametrize("name,n,p", [("cfg1", 4096, 4), ("cfg2", 1531, 12), ("cfg4", 1100, 16)])
+def test_single_call_pipeline_equals_its_steps_and_the_oracle(name, n, p):
+    """cat_fit_pca / cat_apply_pca against the same pipeline composed from the step calls, and the oracle
+    on the boundary the steps share (the scores)."""
+    from paper_2509_26277_amd import cat_apply_pca, cat_fit_pca
+    w = workloads.make(name, n_rows=n)
+    K, dt, iters = w["K"], w["dtype"], 4
+    lq, fp = dev_matrix(w["lq"], dt), dev_matrix(w["fp"], dt)
+    r = cat_fit_pca(lq, fp, K, p, iters, seed=w["seed"])
+    # the steps, by hand
+    mean_g, comps_g, _ = cat_pca_fit(lq, p)
+    assert torch.equal(mean_g, r["mean"]) and torch.equal(comps_g, r["components"])
+    z_g = cat_pca_project(lq, mean_g, comps_g)
+    s = cat_fit(z_g, z_g, K, iters, seed=w["seed"])
+    assert torch.equal(s["assignments"], r["assignments"]) and torch.equal(s["counts"], r["counts"])
+    check_values(host_matrix(r["centroids_z"]), host_matrix(s["centroids"]), 1e-6, "score centroids")
+    # the oracle on the scores and on the full vectors
+    z = host_matrix(z_g).astype(np.float32)
+    o = oracle.fit(z, z, K, iters, seed=w["seed"])
+    _, d1, d2 = oracle.assign(z, o["centroids"], want_distances=True)
+    a_g = r["assignments"].cpu().numpy()
+    check_assignments(a_g, o["assignments"], d1, d2, f"{name} pca pipeline")
+    # the objective is a diagnostic formed as |z|^2 + (score) in float: tight clusters far from the origin of the
+    # score space lose a few digits to that cancellation
+    np.testing.assert_allclose(r["inertia"].cpu().numpy(), o["inertia"], rtol=1e-3)
+    g_o, b_o, n_o = oracle.affine(w["lq"], w["fp"], a_g, K)
+    assert r["counts"].cpu().numpy().tolist() == n_o.tolist()
+    check_values(host_matrix(r["gamma"]), g_o, RTOL[dt], "gamma")
+    check_values(host_matrix(r["beta"]), b_o, RTOL[dt], "beta", beta_scale(w["lq"], w["fp"], a_g, K, g_o))
+    # inference
+    for alpha in (1.0, 0.4):
+        out, a2 = cat_apply_pca(lq, r["mean"], r["components"], r["centroids_z"], r["gamma"], r["beta"], alpha=alpha)
+        al = a2.cpu().numpy()
+        same = al == a_g
+        _, e1, e2 = oracle.assign(z, host_matrix(r["centroids_z"]), want_distances=True)
+        assert ((e2 - e1)[~same] <= 1e-5 * e2[~same]).all()
+        xd = w["lq"].astype(np.float64)
+        want = xd + alpha * ((host_matrix(r["gamma"])[al] * xd + host_matrix(r["beta"])[al]) - xd)
+        check_values(host_matrix(out), want, RTOL[dt], f"corrected alpha={alpha}")
+    out2, none = cat_apply_pca(lq, r["mean"], r["components"], r["centroids_z"], r["gamma"], r["beta"], want_assignments=False)
+    assert none is None and torch.equal(out2, cat_apply_pca(lq, r["mean"], r["components"], r["centroids_z"], r["gamma"], r["beta"])[0])
