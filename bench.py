@@ -193,7 +193,7 @@ def main():
 
     # ---- the PCA front-end (a separate row of the method: not part of `value` or `roofline`) ----
     if fit_kind and args.pca_dim > 0 and D <= 2048:
-        from paper_2509_26277_amd import cat_apply_assigned, cat_pca_fit, cat_pca_project
+        from paper_2509_26277_amd import cat_apply_assigned, cat_apply_pca, cat_fit_pca, cat_pca_fit, cat_pca_project
         pdim = min(args.pca_dim, D)
         dtc = binding.CAT_F32 if dt == "f32" else binding.CAT_BF16
         ws_pca = torch.empty(binding.load_library().cat_pca_workspace_bytes(N, D, pdim, dtc), dtype=torch.uint8, device="cuda")
@@ -202,6 +202,14 @@ def main():
         t_proj = _events(lambda: cat_pca_project(lq, mean_p, comps_p), 5, torch)
         r = state["fit"]
         t_lab = _events(lambda: cat_apply_assigned(lq, r["assignments"], r["gamma"], r["beta"], out=out), 5, torch)
+        # Algorithm 1 / Algorithm 2 with pca_dim = pdim as single calls
+        ws_fp = torch.empty(binding.load_library().cat_fit_pca_workspace_bytes(N, D, K, pdim, dtc), dtype=torch.uint8, device="cuda")
+        ws_ap = torch.empty(binding.load_library().cat_apply_pca_workspace_bytes(N, D, K, pdim, dtc), dtype=torch.uint8, device="cuda")
+        rp = cat_fit_pca(lq, fp, K, pdim, iters, seed=w["seed"], workspace=ws_fp)
+        t_fpca = _events(lambda: cat_fit_pca(lq, fp, K, pdim, iters, seed=w["seed"], workspace=ws_fp), 2, torch)
+        t_apca = _events(lambda: cat_apply_pca(lq, rp["mean"], rp["components"], rp["centroids_z"], rp["gamma"], rp["beta"],
+                                                out=out, workspace=ws_ap), 5, torch)
+        detail.update(fit_pca_ms=t_fpca, apply_pca_ms=t_apca, apply_pca_GBps=apply_bytes / t_apca / 1e6)
         detail.update(pca_dim=pdim, pca_fit_ms=t_pfit, pca_project_us=1e3 * t_proj,
                       pca_project_GBps=N * D * esize / t_proj / 1e6,
                       pca_project_TFLOPs=2.0 * N * D * (16 * ((pdim + 15) // 16)) / t_proj / 1e9,
