@@ -89,7 +89,7 @@ def main():
                          "components; reported under detail.pca_*; 0 skips it (fit workloads with D <= 2048 only)")
     args = ap.parse_args()
     if args.gpus != 1:
-        sys.exit("bench.py: this build is single-GPU; run with --gpus 1 (rows shard trivially, see DESIGN.md)")
+        sys.exit("bench.py: this library is single-GPU; run with --gpus 1 (rows shard trivially: one all-reduce of K x D sums per iteration)")
 
     import numpy as np
     import torch
