@@ -104,3 +104,26 @@ def test_full_inference_stream_sampled():
     check_values(host_matrix(out[idx])[ok], o_out[ok], RTOL["f32"], "cfg5 corrected")
     # planted labels: every row sits ~1000 squared units closer to its own centroid
     assert (a.cpu().numpy() == w["labels"]).mean() > 0.99999
+
+    # The fused Lloyd loop at this size (4M rows, 262144 tiles; two full-sum passes, one pass of
+    # changed-row updates, the final pass), from centroids shifted off the planted ones.  fp = lq, so the
+    # affine fit must come out as the identity.
+    del out
+    K, D, iters = w["K"], w["D"], 3
+    init = torch.from_numpy((w["centroids"] + 0.5 * np.random.default_rng(5).standard_normal(w["centroids"].shape)).astype(np.float32)).cuda()
+    r = cat_fit(lq, lq, K, iters, init_centroids=init)
+    a_g = r["assignments"].cpu().numpy()
+    counts = r["counts"].cpu().numpy()
+    J = r["inertia"].cpu().numpy()
+    assert counts.sum() == N and counts.tolist() == np.bincount(a_g, minlength=K).tolist()
+    assert (np.diff(J) <= 1e-6 * J[:-1]).all() and J[-1] < J[0]
+    cent = host_matrix(r["centroids"])
+    a_o, d1, d2 = oracle.assign(w["lq"][rows], cent, want_distances=True)
+    check_assignments(a_g[rows], a_o, d1, d2, "cfg5 fit, sampled assignments")
+    cols = np.sort(rng.choice(D, 4, replace=False))
+    lq_c = np.ascontiguousarray(w["lq"][:, cols])
+    r1 = cat_fit(lq, lq, K, iters - 1, init_centroids=init, want_inertia=False)
+    c_o, _ = oracle.update(lq_c, r1["assignments"].cpu().numpy(), host_matrix(r1["centroids"])[:, cols])
+    check_values(cent[:, cols], c_o, RTOL["f32"], "cfg5 fit, centroids")
+    np.testing.assert_allclose(host_matrix(r["gamma"]), 1.0, atol=1e-5)
+    np.testing.assert_allclose(host_matrix(r["beta"]), 0.0, atol=1e-4)
