@@ -19,4 +19,5 @@ from .cat_oracle import (  # noqa: F401
     covariance,
     pca_fit,
     pca_project,
+    alpha_sweep,
 )

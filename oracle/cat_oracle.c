@@ -25,8 +25,11 @@
  *     (Steele, Lea, Flood, OOPSLA 2014) used as a counter-based generator,
  *     re-implemented here from its published definition.
  *   - PCA front-end (Sec. 3.1; first step of Algorithms 1 and 2): column means,
- *     population covariance, projection (at the end of this file); pinned in
+ *     population covariance, projection (near the end of this file); pinned in
  *     tests/test_oracle_pca_pins.py.
+ *   - sweep of the blending coefficient (Sec. 3.1 alpha display; the ablation on
+ *     alpha, Sec. 5): Top-1 index, Top-1 hits and squared error per alpha (last
+ *     function of this file); pinned in tests/test_oracle_sweep_pins.py.
  *
  * Inputs are float arrays (bf16 data is widened exactly by the caller); every
  * sum, mean, distance and quotient below is IEEE double, accumulated
@@ -321,5 +324,68 @@ void cat_oracle_project(const float *x, int64_t N, int64_t D, int32_t p, const d
             for (int64_t j = 0; j < D; j++) s += ((double)x[i * D + j] - mean[j]) * comps[(int64_t)c * D + j];
             z[i * p + c] = s;
         }
+    }
+}
+
+/* ---------------------------------------------------------------------------
+ * Sweep of the blending coefficient (the alpha display of Sec. 3.1; the ablation
+ * on alpha in Sec. 5 and its appendix evaluates one fitted transformation at a
+ * list of alpha values).  For every alpha in the list and every row i with
+ * cluster label a_i:
+ *     c_i(alpha) = q_i + alpha * (gamma_a q_i + beta_a - q_i)
+ * (a label outside [0, K) leaves the row uncorrected, c_i = q_i).  Reported per
+ * alpha: top1[i] = the position of the largest entry of c_i(alpha), the first
+ * one on ties; margin[i] = that entry minus the second largest (0 on a tie,
+ * +inf for D = 1); hits = the number of rows whose top1 equals labels[i]; sq_err =
+ * sum over all entries of (c - fp)^2.  Layouts: top1 and margin are N x n_alpha.
+ * fp, labels, top1, margin are optional (NULL).  Sums are sequential in row
+ * order, in double; OpenMP only splits the independent alpha values.
+ * ------------------------------------------------------------------------- */
+void cat_oracle_alpha_sweep(const float *lq, const float *fp, const int32_t *labels,
+                            const int32_t *assign, int64_t N, int64_t D, int32_t K,
+                            const double *gamma, const double *beta, const double *alphas,
+                            int32_t n_alpha, int64_t *hits, double *sq_err, int32_t *top1,
+                            double *margin) {
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int32_t s = 0; s < n_alpha; s++) {
+        const double alpha = alphas[s];
+        int64_t h = 0;
+        double err = 0.0;
+        for (int64_t i = 0; i < N; i++) {
+            const int32_t a = assign[i];
+            const int inside = a >= 0 && a < K;
+            const double *g = inside ? gamma + (int64_t)a * D : NULL;
+            const double *b = inside ? beta + (int64_t)a * D : NULL;
+            double best = 0.0, second = 0.0;
+            int64_t arg = -1;
+            for (int64_t j = 0; j < D; j++) {
+                const double q = (double)lq[i * D + j];
+                double c = q;
+                if (inside) {
+                    const double affine = g[j] * q + b[j];
+                    c = q + alpha * (affine - q);
+                }
+                if (fp) {
+                    const double e = c - (double)fp[i * D + j];
+                    err += e * e;
+                }
+                if (arg < 0) {
+                    best = c;
+                    arg = j;
+                    second = -HUGE_VAL;
+                } else if (c > best) {
+                    second = best;
+                    best = c;
+                    arg = j;
+                } else if (c > second) {
+                    second = c;
+                }
+            }
+            if (labels && (int64_t)labels[i] == arg) h++;
+            if (top1) top1[i * n_alpha + s] = (int32_t)arg;
+            if (margin) margin[i * n_alpha + s] = best - second;
+        }
+        if (hits) hits[s] = h;
+        if (sq_err) sq_err[s] = fp ? err : 0.0;
     }
 }

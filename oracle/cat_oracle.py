@@ -47,7 +47,9 @@ def _load():
     lib.cat_oracle_colmean.argtypes = [f32p, c.c_int64, c.c_int64, f64p]
     lib.cat_oracle_covariance.argtypes = [f32p, c.c_int64, c.c_int64, f64p, f64p]
     lib.cat_oracle_project.argtypes = [f32p, c.c_int64, c.c_int64, c.c_int32, f64p, f64p, f64p]
-    for fn in ("cat_oracle_colmean", "cat_oracle_covariance", "cat_oracle_project"):
+    lib.cat_oracle_alpha_sweep.argtypes = [f32p, f32p, i32p, i32p, c.c_int64, c.c_int64, c.c_int32, f64p, f64p,
+                                           f64p, c.c_int32, i64p, f64p, i32p, f64p]
+    for fn in ("cat_oracle_colmean", "cat_oracle_covariance", "cat_oracle_project", "cat_oracle_alpha_sweep"):
         getattr(lib, fn).restype = None
     for fn in ("cat_oracle_init_indices", "cat_oracle_assign", "cat_oracle_distances", "cat_oracle_update",
                "cat_oracle_affine", "cat_oracle_fit", "cat_oracle_apply"):
@@ -230,3 +232,47 @@ def pca_project(lq, mean, comps):
     z = np.empty((N, pdim), dtype=np.float64)
     lib.cat_oracle_project(xp, N, D, pdim, _p(m, ctypes.c_double), _p(w, ctypes.c_double), _p(z, ctypes.c_double))
     return z
+
+
+# ---------------------------------------------------------------------------
+# Sweep of the blending coefficient (Sec. 3.1 alpha display; ablation on alpha, Sec. 5)
+# ---------------------------------------------------------------------------
+def alpha_sweep(lq, assignments, gamma, beta, alphas, fp=None, labels=None):
+    """One fitted transformation evaluated at every alpha of a list, rows labelled by ``assignments``.
+
+    Returns a dict: ``top1`` (N x n int32, position of the largest corrected entry, first on ties),
+    ``margin`` (N x n, largest minus second largest corrected entry), ``hits`` (n int64, rows whose
+    top1 equals ``labels``; zeros without labels) and ``sq_err`` (n, summed squared difference to
+    ``fp``; zeros without fp)."""
+    lib = _load()
+    x, xp = _f32(lq)
+    N, D = x.shape
+    g, pg = _f64(gamma)
+    b, pb = _f64(beta)
+    K = g.shape[0]
+    assert g.shape == (K, D) and b.shape == (K, D)
+    a = np.ascontiguousarray(assignments, dtype=np.int32)
+    assert a.shape == (N,)
+    al = np.ascontiguousarray(alphas, dtype=np.float64)
+    n = al.shape[0]
+    null_f = ctypes.POINTER(ctypes.c_float)()
+    null_i = ctypes.POINTER(ctypes.c_int32)()
+    if fp is not None:
+        y, yp = _f32(fp)
+        assert y.shape == (N, D)
+    else:
+        yp = null_f
+    if labels is not None:
+        lab = np.ascontiguousarray(labels, dtype=np.int32)
+        assert lab.shape == (N,)
+        lp = _p(lab, ctypes.c_int32)
+    else:
+        lp = null_i
+    hits = np.zeros(n, dtype=np.int64)
+    sq = np.zeros(n, dtype=np.float64)
+    top1 = np.empty((N, n), dtype=np.int32)
+    margin = np.empty((N, n), dtype=np.float64)
+    lib.cat_oracle_alpha_sweep(xp, yp, lp, _p(a, ctypes.c_int32), N, D, K, pg, pb, _p(al, ctypes.c_double), n,
+                               _p(hits, ctypes.c_int64), _p(sq, ctypes.c_double), _p(top1, ctypes.c_int32),
+                               _p(margin, ctypes.c_double))
+    return dict(top1=top1, margin=margin, hits=hits, sq_err=sq)
