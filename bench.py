@@ -84,6 +84,10 @@ def main():
     ap.add_argument("--workload", default="cfg2", choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5"])
     ap.add_argument("--rows", type=int, default=None, help="override N (debugging; the result is then not the named workload)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
+    ap.add_argument("--alpha-grid", type=int, default=10,
+                    help="also time one pass that evaluates the fitted transformation at this many blending coefficients "
+                         "(1/n .. 1): Top-1 agreement with the FP rows and squared error; reported under detail.alpha_*; "
+                         "0 skips it, at most 16 (fit workloads only)")
     ap.add_argument("--pca-dim", type=int, default=50,
                     help="also time the PCA front-end (fit, projection, labelled affine map) with this many "
                          "components; reported under detail.pca_*; 0 skips it (fit workloads with D <= 2048 only)")
@@ -214,6 +218,22 @@ def main():
                       pca_project_GBps=N * D * esize / t_proj / 1e6,
                       pca_project_TFLOPs=2.0 * N * D * (16 * ((pdim + 15) // 16)) / t_proj / 1e9,
                       apply_assigned_us=1e3 * t_lab, apply_assigned_GBps=2 * N * D * esize / t_lab / 1e6)
+
+    # ---- the sweep of the blending coefficient (another separate row: the ablation grid of ten values in one pass) ----
+    if fit_kind and args.alpha_grid > 0:
+        from paper_2509_26277_amd import cat_alpha_sweep, cat_top1
+        r = state["fit"]
+        grid = [(k + 1) / args.alpha_grid for k in range(args.alpha_grid)]
+        ws_sw = torch.empty(binding.load_library().cat_alpha_sweep_workspace_bytes(), dtype=torch.uint8, device="cuda")
+        lab = cat_top1(fp)
+        t_top = _events(lambda: cat_top1(fp, out=lab), 5, torch)
+        sweep = lambda: cat_alpha_sweep(lq, r["assignments"], r["gamma"], r["beta"], grid, fp=fp, labels=lab, workspace=ws_sw)
+        res = sweep()
+        t_sw = _events(sweep, 5, torch)
+        hits = res["hits"].cpu().tolist()
+        detail.update(alpha_grid=args.alpha_grid, alpha_sweep_us=1e3 * t_sw, alpha_sweep_GBps=2 * N * D * esize / t_sw / 1e6,
+                      alpha_sweep_top1_agreement=[h / N for h in hits], top1_us=1e3 * t_top,
+                      top1_GBps=N * D * esize / t_top / 1e6)
 
     # context: plain device copy of the same matrix
     t_copy = _events(lambda: out.copy_(lq), 5, torch)

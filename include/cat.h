@@ -47,6 +47,7 @@ extern "C" {
 #endif
 
 #define CAT_MAX_K 1024
+#define CAT_MAX_ALPHAS 16 /* longest list of blending coefficients one cat_alpha_sweep call takes */
 
 typedef enum {
     CAT_OK = 0,
@@ -217,6 +218,41 @@ cat_status cat_pca_project(const void *lq, int64_t N, int64_t D, int32_t p, cat_
 cat_status cat_apply_assigned(const void *lq, const int32_t *assignments, int64_t N, int64_t D,
                               int32_t K, cat_dtype dt, const float *gamma, const float *beta,
                               float alpha, void *corrected, void *hip_stream);
+
+/* ---- sweep of the blending coefficient (the alpha display of Sec. 3.1; the ablation on
+ * alpha of Sec. 5 evaluates one fitted transformation at a list of alpha values) ----
+ *
+ * cat_alpha_sweep reads every row once and evaluates, for each of the n_alpha values,
+ *     c_i(alpha) = x_i + alpha (gamma_a x_i + beta_a - x_i),   a = assignments[i]
+ * (a label outside [0, K) leaves the row as it is), without writing c anywhere:
+ *   top1     out, nullable, N x n_alpha int32 (row-major): the position of the largest entry of
+ *            c_i(alpha), the first such position on ties.  The comparison is made on fp32 values
+ *            fma(alpha, fma(x, gamma - 1, beta), x), also for bf16 rows (no rounding to bf16).
+ *   labels   in, nullable, N int32; hits out, n_alpha int64: the number of rows whose top1 equals
+ *            labels[i] (a label outside [0, D) never matches).  Both or neither.
+ *   fp       in, nullable, N x D of dt.  sq_err out, nullable, n_alpha doubles: the sum over all
+ *            entries of (c - fp)^2.  moments out, nullable, 3 doubles S_aa, S_ab, S_bb with
+ *            a = x - fp and b = (gamma_a - 1) x + beta_a, so that the squared error at any alpha is
+ *            S_aa + 2 alpha S_ab + alpha^2 S_bb (its minimum is at alpha = -S_ab / S_bb); sq_err is
+ *            evaluated from them in double.  fp needs at least one of the two outputs.
+ *   alphas   HOST array of n_alpha finite floats, 1 <= n_alpha <= CAT_MAX_ALPHAS; read before
+ *            the call returns.
+ * All other pointers are device memory.  Inputs are taken as finite.  workspace: at least
+ * cat_alpha_sweep_workspace_bytes() bytes, 256-byte aligned, caller-owned.  Errors:
+ * CAT_ERR_INVALID_ARG (shape, null or mismatched optional arguments, non-finite alpha),
+ * CAT_ERR_WORKSPACE, CAT_ERR_DEVICE.
+ *
+ * cat_top1: top1[i] = the position of the largest entry of row i of x (N x D of dt), the first
+ * on ties; the Top-1 prediction of a logit vector, e.g. of the FP rows as `labels` above.
+ */
+size_t cat_alpha_sweep_workspace_bytes(void);
+cat_status cat_alpha_sweep(const void *lq, const void *fp, const int32_t *labels,
+                           const int32_t *assignments, int64_t N, int64_t D, int32_t K, cat_dtype dt,
+                           const float *gamma, const float *beta,
+                           const float *alphas, int32_t n_alpha,
+                           int64_t *hits, double *sq_err, double *moments, int32_t *top1,
+                           void *workspace, size_t workspace_bytes, void *hip_stream);
+cat_status cat_top1(const void *x, int64_t N, int64_t D, cat_dtype dt, int32_t *top1, void *hip_stream);
 
 /*
  * Timing of the dominant kernel, for benchmarks.  While enabled, every launch of the tile

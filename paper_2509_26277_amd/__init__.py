@@ -18,6 +18,8 @@ from .binding import (  # noqa: F401
     cat_apply_assigned,
     cat_fit_pca,
     cat_apply_pca,
+    cat_alpha_sweep,
+    cat_top1,
     cat_fit_workspace_bytes,
     cat_apply_workspace_bytes,
     library_path,

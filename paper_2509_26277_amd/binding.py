@@ -21,7 +21,8 @@ _STATUS = {0: "CAT_OK", 1: "CAT_ERR_INVALID_ARG", 2: "CAT_ERR_UNSUPPORTED", 3: "
 EXPORTS = ("cat_select_path", "cat_fit_workspace_bytes", "cat_apply_workspace_bytes", "cat_fit", "cat_apply",
            "cat_assign", "cat_update", "cat_stats", "cat_init_indices", "cat_last_error", "cat_profile_enable",
            "cat_profile_read", "cat_debug_list_capacity", "cat_pca_workspace_bytes", "cat_pca_fit", "cat_pca_project",
-           "cat_apply_assigned", "cat_fit_pca_workspace_bytes", "cat_fit_pca", "cat_apply_pca_workspace_bytes", "cat_apply_pca")
+           "cat_apply_assigned", "cat_fit_pca_workspace_bytes", "cat_fit_pca", "cat_apply_pca_workspace_bytes", "cat_apply_pca",
+           "cat_alpha_sweep_workspace_bytes", "cat_alpha_sweep", "cat_top1")
 
 
 class CatError(RuntimeError):
@@ -83,6 +84,13 @@ def load_library():
     lib.cat_apply_pca_workspace_bytes.restype = sz
     lib.cat_apply_pca.argtypes = [vp, i64, i64, i32, i32, c.c_int, vp, vp, vp, vp, vp, c.c_float, vp, vp, vp, sz, vp]
     lib.cat_apply_pca.restype = c.c_int
+    lib.cat_alpha_sweep_workspace_bytes.argtypes = []
+    lib.cat_alpha_sweep_workspace_bytes.restype = sz
+    lib.cat_alpha_sweep.argtypes = [vp, vp, vp, vp, i64, i64, i32, c.c_int, vp, vp, c.POINTER(c.c_float), i32, vp, vp, vp, vp,
+                                    vp, sz, vp]
+    lib.cat_alpha_sweep.restype = c.c_int
+    lib.cat_top1.argtypes = [vp, i64, i64, c.c_int, vp, vp]
+    lib.cat_top1.restype = c.c_int
     lib.cat_debug_list_capacity.argtypes = [c.c_int]
     lib.cat_debug_list_capacity.restype = c.c_int
     lib.cat_last_error.argtypes = []
@@ -300,6 +308,41 @@ def cat_apply_assigned(lq, assignments, gamma, beta, alpha=1.0, out=None):
     _check(lib.cat_apply_assigned(_dev(lq, name="lq"), _dev(assignments, torch.int32, (N,), "assignments"), N, D, K, _dt(lq),
                                   _dev(gamma, torch.float32, (K, D), "gamma"), _dev(beta, torch.float32, (K, D), "beta"),
                                   float(alpha), _dev(out, lq.dtype, (N, D), "out"), _stream()))
+    return out
+
+
+def cat_alpha_sweep(lq, assignments, gamma, beta, alphas, fp=None, labels=None, want_top1=False, workspace=None):
+    """One fitted transformation evaluated at every alpha of a list in one pass over the rows (the ablation on
+    the blending coefficient).  Returns a dict of device tensors: ``hits`` (n int64; with labels), ``sq_err``
+    (n float64) and ``moments`` (3 float64; with fp), ``top1`` (N x n int32; with want_top1)."""
+    lib = load_library()
+    N, D = lq.shape
+    K = gamma.shape[0]
+    dev = lq.device
+    al = [float(a) for a in alphas]
+    n = len(al)
+    arr = (ctypes.c_float * max(n, 1))(*al)
+    if workspace is None:
+        workspace = _workspace(lib.cat_alpha_sweep_workspace_bytes(), dev)
+    hits = torch.empty((n,), dtype=torch.int64, device=dev) if labels is not None else None
+    sq = torch.empty((n,), dtype=torch.float64, device=dev) if fp is not None else None
+    mom = torch.empty((3,), dtype=torch.float64, device=dev) if fp is not None else None
+    top1 = torch.empty((N, n), dtype=torch.int32, device=dev) if want_top1 else None
+    _check(lib.cat_alpha_sweep(_dev(lq, name="lq"), _dev(fp, lq.dtype, (N, D), "fp"), _dev(labels, torch.int32, (N,), "labels"),
+                               _dev(assignments, torch.int32, (N,), "assignments"), N, D, K, _dt(lq),
+                               _dev(gamma, torch.float32, (K, D), "gamma"), _dev(beta, torch.float32, (K, D), "beta"),
+                               arr, n, _dev(hits), _dev(sq), _dev(mom), _dev(top1),
+                               workspace.data_ptr(), workspace.numel(), _stream()))
+    return dict(hits=hits, sq_err=sq, moments=mom, top1=top1)
+
+
+def cat_top1(x, out=None):
+    """Position of the largest entry of every row (first on ties): N int32."""
+    lib = load_library()
+    N, D = x.shape
+    if out is None:
+        out = torch.empty((N,), dtype=torch.int32, device=x.device)
+    _check(lib.cat_top1(_dev(x, name="x"), N, D, _dt(x), _dev(out, torch.int32, (N,), "out"), _stream()))
     return out
 
 

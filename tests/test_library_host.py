@@ -25,7 +25,7 @@ def lib():
 def test_every_declared_symbol_is_exported(lib):
     with open(os.path.join(ROOT, "include", "cat.h")) as f:
         text = re.sub(r"/\*.*?\*/", "", f.read(), flags=re.S)
-    declared = set(re.findall(r"\b(cat_[a-z_]+)\s*\(", text))
+    declared = set(re.findall(r"\b(cat_[a-z0-9_]+)\s*\(", text))
     assert declared == set(binding.EXPORTS)
     for name in declared:
         assert getattr(lib, name) is not None
