@@ -21,10 +21,12 @@ struct SweepAlphas {
 constexpr int kSweepWaves = 4;
 constexpr int kSweepMaxGrid = 2048;  // 8 workgroups of 4 waves per CU walk the rows
 
-// what one workgroup of the sweep leaves behind
+// What the workgroups of the sweep leave behind: quantity-major, one slot per workgroup, so that the
+// launch that adds them reads consecutive words.  Quantities 0..2 are the three sums (doubles), 3 + s the
+// Top-1 hits of alpha s (64-bit counts).
+constexpr int kSweepQuantities = 3 + CAT_MAX_ALPHAS;
 struct SweepPartial {
-    double mom[3];
-    unsigned long long hits[CAT_MAX_ALPHAS];
+    unsigned long long slot[kSweepQuantities][kSweepMaxGrid];
 };
 
 __device__ __forceinline__ void ld_vec4(const float* p, float (&o)[4]) {
@@ -212,17 +214,16 @@ __global__ __launch_bounds__(kSweepWaves* kWave) void k_alpha_sweep(
     mbb = wave_sum(mbb);
     if (lane == 0) s_mom[wave][0] = maa, s_mom[wave][1] = mab, s_mom[wave][2] = mbb;
     __syncthreads();
-    SweepPartial* rec = part + blockIdx.x;
     if (threadIdx.x < 3) {
         double v = 0.0;
         for (int w = 0; w < kSweepWaves; w++) v += s_mom[w][threadIdx.x];
-        rec->mom[threadIdx.x] = v;
+        part->slot[threadIdx.x][blockIdx.x] = (unsigned long long)__double_as_longlong(v);
     }
     if (threadIdx.x < CAT_MAX_ALPHAS) {
         unsigned long long v = 0ull;
         if ((int)threadIdx.x < NA)
             for (int w = 0; w < kSweepWaves; w++) v += s_hit[w][threadIdx.x];
-        rec->hits[threadIdx.x] = v;
+        part->slot[3 + threadIdx.x][blockIdx.x] = v;
     }
 }
 
@@ -262,43 +263,50 @@ __global__ __launch_bounds__(kSweepWaves* kWave) void k_row_top1(const T* __rest
     }
 }
 
-// adds the workgroup records in index order; squared error per alpha from the three sums
-__global__ __launch_bounds__(256) void k_sweep_finish(const SweepPartial* part, int nrec, const SweepAlphas al, int n_alpha,
-                                                       unsigned long long* hits, double* sq_err, double* moments) {
-    __shared__ double s_d[3][256];
-    __shared__ unsigned long long s_h[256];
-    __shared__ double s_mom[3];
-    const int t = threadIdx.x;
-    for (int q = 0; q < 3; q++) {
-        double v = 0.0;
-        for (int r = t; r < nrec; r += 256) v += part[r].mom[q];
-        s_d[q][t] = v;
+// Adds what the workgroups left, in a fixed order (lane-strided, then a butterfly over the wave).  Workgroup 0
+// (one wave): the three sums and the squared error per alpha from them; workgroup 1 + s: the hits of alpha s.
+// a lane's share of one quantity: every slot is requested before the first is used (a slot past the
+// last record is read from slot 0 and not counted)
+__device__ __forceinline__ void sweep_slots(const unsigned long long* q, int nrec, int lane,
+                                            unsigned long long (&v)[kSweepMaxGrid / kWave]) {
+#pragma unroll
+    for (int i = 0; i < kSweepMaxGrid / kWave; i++) {
+        const int r = i * kWave + lane;
+        v[i] = q[r < nrec ? r : 0];
     }
-    __syncthreads();
-    if (t < 3) {
-        double v = 0.0;
-        for (int i = 0; i < 256; i++) v += s_d[t][i];
-        s_mom[t] = v;
-        if (moments) moments[t] = v;
-    }
-    __syncthreads();
-    if (sq_err && t < n_alpha) {
-        const double a = (double)al.v[t];
-        sq_err[t] = s_mom[0] + 2.0 * a * s_mom[1] + a * a * s_mom[2];
+}
+__global__ __launch_bounds__(kWave) void k_sweep_finish(const SweepPartial* part, int nrec, const SweepAlphas al, int n_alpha,
+                                                         unsigned long long* hits, double* sq_err, double* moments) {
+    const int lane = threadIdx.x;
+    unsigned long long v[kSweepMaxGrid / kWave];
+    if (blockIdx.x == 0) {
+        if (!sq_err && !moments) return;
+        double m[3];
+#pragma unroll
+        for (int q = 0; q < 3; q++) {
+            sweep_slots(part->slot[q], nrec, lane, v);
+            double t = 0.0;
+#pragma unroll
+            for (int i = 0; i < kSweepMaxGrid / kWave; i++)
+                t += i * kWave + lane < nrec ? __longlong_as_double((long long)v[i]) : 0.0;
+            m[q] = wave_sum(t);
+        }
+        if (moments && lane < 3) moments[lane] = lane == 0 ? m[0] : (lane == 1 ? m[1] : m[2]);
+        if (sq_err && lane < n_alpha) {
+            const double a = (double)al.v[lane];
+            sq_err[lane] = m[0] + 2.0 * a * m[1] + a * a * m[2];
+        }
+        return;
     }
     if (!hits) return;
-    for (int s = 0; s < n_alpha; s++) {
-        unsigned long long v = 0ull;
-        for (int r = t; r < nrec; r += 256) v += part[r].hits[s];
-        __syncthreads();
-        s_h[t] = v;
-        __syncthreads();
-        if (t == 0) {
-            unsigned long long tot = 0ull;
-            for (int i = 0; i < 256; i++) tot += s_h[i];
-            hits[s] = tot;
-        }
-    }
+    const int s = (int)blockIdx.x - 1;
+    sweep_slots(part->slot[3 + s], nrec, lane, v);
+    unsigned long long t = 0ull;
+#pragma unroll
+    for (int i = 0; i < kSweepMaxGrid / kWave; i++) t += i * kWave + lane < nrec ? v[i] : 0ull;
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) t += __shfl_xor(t, o, kWave);
+    if (lane == 0) hits[s] = t;
 }
 
 template <typename T, int VEC, bool ERR>
@@ -315,6 +323,7 @@ static void launch_sweep_arg(int na_inst, dim3 g, hipStream_t st, const T* x, co
         case 2: CAT_SWEEP(2); break;
         case 4: CAT_SWEEP(4); break;
         case 8: CAT_SWEEP(8); break;
+        case 10: CAT_SWEEP(10); break;
         case 12: CAT_SWEEP(12); break;
         default: CAT_SWEEP(16); break;
     }
@@ -329,7 +338,7 @@ static cat_status launch_sweep(const void* lq, const void* fp, const int32_t* la
     const T* f = (const T*)fp;
     const bool arg = labels || top1;
     int na_inst = 16;
-    for (int c : {12, 8, 4, 2, 1})
+    for (int c : {12, 10, 8, 4, 2, 1})
         if (n_alpha <= c) na_inst = c;
     const int64_t rows_per_wg = (int64_t)kSweepWaves * kRowsPerWave;
     const int64_t want = (N + rows_per_wg - 1) / rows_per_wg;
@@ -368,7 +377,7 @@ using namespace cat;
 
 extern "C" {
 
-size_t cat_alpha_sweep_workspace_bytes(void) { return (size_t)kSweepMaxGrid * sizeof(SweepPartial); }
+size_t cat_alpha_sweep_workspace_bytes(void) { return sizeof(SweepPartial); }
 
 cat_status cat_alpha_sweep(const void* lq, const void* fp, const int32_t* labels, const int32_t* assignments, int64_t N,
                            int64_t D, int32_t K, cat_dtype dt, const float* gamma, const float* beta,
@@ -408,7 +417,7 @@ cat_status cat_alpha_sweep(const void* lq, const void* fp, const int32_t* labels
                                                         &nrec, top1, vec4, st);
     if (s != CAT_OK) return s;
     if (fp || hits) {
-        hipLaunchKernelGGL(k_sweep_finish, dim3(1), dim3(256), 0, st, part, nrec, al, (int)n_alpha, (unsigned long long*)hits,
+        hipLaunchKernelGGL(k_sweep_finish, dim3(1 + (hits ? n_alpha : 0)), dim3(kWave), 0, st, part, nrec, al, (int)n_alpha, (unsigned long long*)hits,
                            sq_err, moments);
         CAT_LAUNCH_CHECK("k_sweep_finish");
     }
