@@ -20,4 +20,5 @@ from .cat_oracle import (  # noqa: F401
     pca_fit,
     pca_project,
     alpha_sweep,
+    kmeanspp,
 )

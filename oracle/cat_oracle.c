@@ -28,8 +28,11 @@
  *     population covariance, projection (near the end of this file); pinned in
  *     tests/test_oracle_pca_pins.py.
  *   - sweep of the blending coefficient (Sec. 3.1 alpha display; the ablation on
- *     alpha, Sec. 5): Top-1 index, Top-1 hits and squared error per alpha (last
- *     function of this file); pinned in tests/test_oracle_sweep_pins.py.
+ *     alpha, Sec. 5): Top-1 index, Top-1 hits and squared error per alpha (the
+ *     sweep function near the end of this file); pinned in tests/test_oracle_sweep_pins.py.
+ *   - D^2-weighted seeding (k-means++, Arthur and Vassilvitskii 2007) as an
+ *     alternative initialisation (last function); pinned in
+ *     tests/test_oracle_seeding_pins.py.
  *
  * Inputs are float arrays (bf16 data is widened exactly by the caller); every
  * sum, mean, distance and quotient below is IEEE double, accumulated
@@ -388,4 +391,62 @@ void cat_oracle_alpha_sweep(const float *lq, const float *fp, const int32_t *lab
         if (hits) hits[s] = h;
         if (sq_err) sq_err[s] = fp ? err : 0.0;
     }
+}
+
+/* ---------------------------------------------------------------------------
+ * D^2-weighted seeding ("k-means++", Arthur and Vassilvitskii, SODA 2007), an
+ * alternative to the seeded distinct rows above; the paper fixes no k-means
+ * initialisation (Sec. 4, Setup).  The published procedure: the first centre is a
+ * row drawn uniformly; every further centre is a row drawn with probability
+ * proportional to its squared distance to the nearest centre chosen so far.
+ * The draws: u_t = (SplitMix64 output t of the seed >> 11) * 2^-53 in [0, 1),
+ * t = 0 .. K-1.  First row: floor(u_0 * N).  Row t >= 1: with d2[i] the current
+ * squared distance of row i to its nearest centre and S the sum of all d2 in row
+ * order, the row is the first i whose running sum d2[0] + .. + d2[i] exceeds
+ * u_t * S.  If S = 0 (every row coincides with a centre) the row is the lowest
+ * index not chosen yet.  Distances are direct-form sums over the channels in
+ * double.  idx receives the K row indices in the order drawn.
+ * ------------------------------------------------------------------------- */
+void cat_oracle_kmeanspp(const float *lq, int64_t N, int64_t D, int32_t K, uint64_t seed,
+                         int64_t *idx) {
+    double *d2 = (double *)malloc((size_t)N * sizeof(double));
+    for (int32_t t = 0; t < K; t++) {
+        const double u = (double)(cat_oracle_splitmix64(seed, (uint64_t)t) >> 11) * 0x1.0p-53;
+        int64_t pick = -1;
+        if (t == 0) {
+            pick = (int64_t)(u * (double)N);
+            if (pick > N - 1) pick = N - 1;
+        } else {
+            double S = 0.0;
+            for (int64_t i = 0; i < N; i++) S += d2[i];
+            if (S > 0.0) {
+                const double target = u * S;
+                double run = 0.0;
+                for (int64_t i = 0; i < N; i++) {
+                    run += d2[i];
+                    if (run > target) { pick = i; break; }
+                }
+            }
+            if (pick < 0) { /* S = 0: lowest index not chosen yet */
+                for (int64_t c = 0; c < N && pick < 0; c++) {
+                    int taken = 0;
+                    for (int32_t q = 0; q < t; q++)
+                        if (idx[q] == c) { taken = 1; break; }
+                    if (!taken) pick = c;
+                }
+            }
+        }
+        idx[t] = pick;
+        const float *cr = lq + pick * D;
+#pragma omp parallel for schedule(static)
+        for (int64_t i = 0; i < N; i++) {
+            double s = 0.0;
+            for (int64_t j = 0; j < D; j++) {
+                const double d = (double)lq[i * D + j] - (double)cr[j];
+                s += d * d;
+            }
+            if (t == 0 || s < d2[i]) d2[i] = s;
+        }
+    }
+    free(d2);
 }

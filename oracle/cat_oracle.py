@@ -49,7 +49,9 @@ def _load():
     lib.cat_oracle_project.argtypes = [f32p, c.c_int64, c.c_int64, c.c_int32, f64p, f64p, f64p]
     lib.cat_oracle_alpha_sweep.argtypes = [f32p, f32p, i32p, i32p, c.c_int64, c.c_int64, c.c_int32, f64p, f64p,
                                            f64p, c.c_int32, i64p, f64p, i32p, f64p]
-    for fn in ("cat_oracle_colmean", "cat_oracle_covariance", "cat_oracle_project", "cat_oracle_alpha_sweep"):
+    lib.cat_oracle_kmeanspp.argtypes = [f32p, c.c_int64, c.c_int64, c.c_int32, c.c_uint64, i64p]
+    for fn in ("cat_oracle_colmean", "cat_oracle_covariance", "cat_oracle_project", "cat_oracle_alpha_sweep",
+               "cat_oracle_kmeanspp"):
         getattr(lib, fn).restype = None
     for fn in ("cat_oracle_init_indices", "cat_oracle_assign", "cat_oracle_distances", "cat_oracle_update",
                "cat_oracle_affine", "cat_oracle_fit", "cat_oracle_apply"):
@@ -276,3 +278,17 @@ def alpha_sweep(lq, assignments, gamma, beta, alphas, fp=None, labels=None):
                                _p(hits, ctypes.c_int64), _p(sq, ctypes.c_double), _p(top1, ctypes.c_int32),
                                _p(margin, ctypes.c_double))
     return dict(top1=top1, margin=margin, hits=hits, sq_err=sq)
+
+
+# ---------------------------------------------------------------------------
+# D^2-weighted seeding (k-means++, Arthur and Vassilvitskii 2007)
+# ---------------------------------------------------------------------------
+def kmeanspp(lq, K, seed=0):
+    """K row indices (int64, in the order drawn): the first uniform, each further one with probability
+    proportional to the squared distance to the nearest row chosen so far."""
+    x, xp = _f32(lq)
+    N, D = x.shape
+    assert 1 <= K <= N
+    idx = np.empty(K, dtype=np.int64)
+    _load().cat_oracle_kmeanspp(xp, N, D, K, seed & (2**64 - 1), _p(idx, ctypes.c_int64))
+    return idx
