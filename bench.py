@@ -84,6 +84,8 @@ def main():
     ap.add_argument("--workload", default="cfg2", choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5"])
     ap.add_argument("--rows", type=int, default=None, help="override N (debugging; the result is then not the named workload)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
+    ap.add_argument("--no-seeding", action="store_true",
+                    help="skip the timing of the D^2-weighted seeding (detail.kmeanspp_*; fit workloads only)")
     ap.add_argument("--alpha-grid", type=int, default=10,
                     help="also time one pass that evaluates the fitted transformation at this many blending coefficients "
                          "(1/n .. 1): Top-1 agreement with the FP rows and squared error; reported under detail.alpha_*; "
@@ -234,6 +236,13 @@ def main():
         detail.update(alpha_grid=args.alpha_grid, alpha_sweep_us=1e3 * t_sw, alpha_sweep_GBps=2 * N * D * esize / t_sw / 1e6,
                       alpha_sweep_top1_agreement=[h / N for h in hits], top1_us=1e3 * t_top,
                       top1_GBps=N * D * esize / t_top / 1e6)
+
+    # ---- D^2-weighted seeding (another separate row): K - 1 reads of the rows ----
+    if fit_kind and not args.no_seeding:
+        from paper_2509_26277_amd import cat_init_kmeanspp
+        ws_pp = torch.empty(binding.load_library().cat_init_kmeanspp_workspace_bytes(N, K), dtype=torch.uint8, device="cuda")
+        t_pp = _events(lambda: cat_init_kmeanspp(lq, K, seed=w["seed"], workspace=ws_pp), 3, torch)
+        detail.update(kmeanspp_ms=t_pp, kmeanspp_GBps=(K - 1) * N * D * esize / t_pp / 1e6)
 
     # context: plain device copy of the same matrix
     t_copy = _events(lambda: out.copy_(lq), 5, torch)

@@ -254,6 +254,28 @@ cat_status cat_alpha_sweep(const void *lq, const void *fp, const int32_t *labels
                            void *workspace, size_t workspace_bytes, void *hip_stream);
 cat_status cat_top1(const void *x, int64_t N, int64_t D, cat_dtype dt, int32_t *top1, void *hip_stream);
 
+/* ---- D^2-weighted seeding ("k-means++", Arthur and Vassilvitskii, SODA 2007) ----
+ * An alternative to the seeded distinct rows of cat_init_indices; the paper fixes no k-means
+ * initialisation (Sec. 4, Setup).  Use: cat_init_kmeanspp -> cat_fit(..., init_centroids = centroids).
+ *
+ * The draws are u_t = (SplitMix64 output t of `seed` >> 11) * 2^-53, t = 0 .. K-1 (the counter
+ * stream documented at cat_init_indices).  Row 0 of the result is row floor(u_0 N) of lq.  For
+ * t >= 1, with d2[i] the squared distance (direct form, double) of row i to the nearest row chosen
+ * so far and S the sum of all d2, the row chosen is the first i whose running sum
+ * d2[0] + .. + d2[i] exceeds u_t S; if S = 0 it is the lowest row not chosen yet.  All sums are
+ * taken in a fixed order (rows in groups of 64, groups in index order), so a seed always gives the
+ * same rows; they equal those of the same rule with one sequential running sum unless u_t S falls
+ * within rounding of a running sum.
+ *   centroids  out, K x D float: the chosen rows, in the order drawn
+ *   indices    out, nullable, K int64 (device): their row numbers
+ * 1 <= K <= min(N, CAT_MAX_K).  K - 1 reads of lq.  workspace: cat_init_kmeanspp_workspace_bytes(N, K)
+ * bytes, 256-byte aligned, caller-owned.  Errors: CAT_ERR_INVALID_ARG, CAT_ERR_WORKSPACE, CAT_ERR_DEVICE.
+ */
+size_t cat_init_kmeanspp_workspace_bytes(int64_t N, int32_t K);
+cat_status cat_init_kmeanspp(const void *lq, int64_t N, int64_t D, int32_t K, uint64_t seed, cat_dtype dt,
+                             float *centroids, int64_t *indices,
+                             void *workspace, size_t workspace_bytes, void *hip_stream);
+
 /*
  * Timing of the dominant kernel, for benchmarks.  While enabled, every launch of the tile
  * kernel (the assignment / Lloyd / inference pass) made by the calling process is bracketed by

@@ -20,6 +20,7 @@ from .binding import (  # noqa: F401
     cat_apply_pca,
     cat_alpha_sweep,
     cat_top1,
+    cat_init_kmeanspp,
     cat_fit_workspace_bytes,
     cat_apply_workspace_bytes,
     library_path,

@@ -22,7 +22,8 @@ EXPORTS = ("cat_select_path", "cat_fit_workspace_bytes", "cat_apply_workspace_by
            "cat_assign", "cat_update", "cat_stats", "cat_init_indices", "cat_last_error", "cat_profile_enable",
            "cat_profile_read", "cat_debug_list_capacity", "cat_pca_workspace_bytes", "cat_pca_fit", "cat_pca_project",
            "cat_apply_assigned", "cat_fit_pca_workspace_bytes", "cat_fit_pca", "cat_apply_pca_workspace_bytes", "cat_apply_pca",
-           "cat_alpha_sweep_workspace_bytes", "cat_alpha_sweep", "cat_top1")
+           "cat_alpha_sweep_workspace_bytes", "cat_alpha_sweep", "cat_top1",
+           "cat_init_kmeanspp_workspace_bytes", "cat_init_kmeanspp")
 
 
 class CatError(RuntimeError):
@@ -90,6 +91,10 @@ def load_library():
                                     vp, sz, vp]
     lib.cat_alpha_sweep.restype = c.c_int
     lib.cat_top1.argtypes = [vp, i64, i64, c.c_int, vp, vp]
+    lib.cat_init_kmeanspp_workspace_bytes.argtypes = [i64, i32]
+    lib.cat_init_kmeanspp_workspace_bytes.restype = sz
+    lib.cat_init_kmeanspp.argtypes = [vp, i64, i64, i32, u64, c.c_int, vp, vp, vp, sz, vp]
+    lib.cat_init_kmeanspp.restype = c.c_int
     lib.cat_top1.restype = c.c_int
     lib.cat_debug_list_capacity.argtypes = [c.c_int]
     lib.cat_debug_list_capacity.restype = c.c_int
@@ -344,6 +349,20 @@ def cat_top1(x, out=None):
         out = torch.empty((N,), dtype=torch.int32, device=x.device)
     _check(lib.cat_top1(_dev(x, name="x"), N, D, _dt(x), _dev(out, torch.int32, (N,), "out"), _stream()))
     return out
+
+
+def cat_init_kmeanspp(lq, K, seed=0, workspace=None):
+    """D^2-weighted seeding (k-means++).  Returns (centroids K x D float32, row indices K int64), device tensors;
+    pass the centroids to ``cat_fit(..., init_centroids=...)``."""
+    lib = load_library()
+    N, D = lq.shape
+    if workspace is None:
+        workspace = _workspace(lib.cat_init_kmeanspp_workspace_bytes(N, K), lq.device)
+    cent = torch.empty((K, D), dtype=torch.float32, device=lq.device)
+    idx = torch.empty((K,), dtype=torch.int64, device=lq.device)
+    _check(lib.cat_init_kmeanspp(_dev(lq, name="lq"), N, D, K, seed & (2**64 - 1), _dt(lq), cent.data_ptr(), idx.data_ptr(),
+                                 workspace.data_ptr(), workspace.numel(), _stream()))
+    return cent, idx
 
 
 def cat_fit_pca(lq, fp, K, p, iters, seed=0, want_inertia=True, workspace=None):
