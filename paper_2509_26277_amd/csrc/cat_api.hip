@@ -420,24 +420,31 @@ cat_status cat_apply(const void* lq, int64_t N, int64_t D, int32_t K, cat_dtype 
 
 
 // ---- Algorithms 1 and 2 with the PCA front-end, as single calls -----------------------------------
+// The scores are kept with rows of pad4(p) floats, the padding columns zero (they add nothing to a distance):
+// rows then keep the 16-byte alignment the tile kernels need, whatever p is.
+static inline int32_t pad4(int32_t p) { return (p + 3) & ~3; }
 struct PcaFitWs {
     void* pca;      // cat_pca_fit scratch
-    float* z;       // N x p scores
-    void* lloyd;    // cat_fit scratch for (N, p, K, float)
+    float* z;       // N x pad4(p) scores
+    float* cz;      // K x pad4(p) centroids in score space
+    void* lloyd;    // cat_fit scratch for (N, pad4(p), K, float)
     void* stats;    // cat_fit scratch for (N, D, K, dt)
     size_t pca_bytes, lloyd_bytes, stats_bytes, bytes;
 };
 static PcaFitWs carve_pca_fit(void* base, int64_t N, int64_t D, int32_t K, int32_t p, cat_dtype dt) {
     PcaFitWs w;
     w.pca_bytes = cat_pca_workspace_bytes(N, D, p, dt);
-    w.lloyd_bytes = carve_fit(nullptr, N, p, K, CAT_F32).bytes;
+    const int32_t pp = pad4(p);
+    w.lloyd_bytes = carve_fit(nullptr, N, pp, K, CAT_F32).bytes;
     w.stats_bytes = carve_fit(nullptr, N, D, K, dt).bytes;
     char* b = (char*)base;
     size_t off = 0;
     w.pca = b + off;
     off += align256(w.pca_bytes);
     w.z = (float*)(b + off);
-    off += align256((size_t)N * (size_t)p * sizeof(float));
+    off += align256((size_t)N * (size_t)pp * sizeof(float));
+    w.cz = (float*)(b + off);
+    off += align256((size_t)K * (size_t)pp * sizeof(float));
     w.lloyd = b + off;
     off += align256(w.lloyd_bytes);
     w.stats = b + off;
@@ -472,10 +479,13 @@ cat_status cat_fit_pca(const void* lq, const void* fp, int64_t N, int64_t D, int
     CAT_TRY(check_ws("cat_fit_pca", workspace, workspace_bytes, w.bytes));
     hipStream_t st = (hipStream_t)hip_stream;
     CAT_TRY(cat_pca_fit(lq, N, D, p, dt, 0, mean, components, nullptr, w.pca, w.pca_bytes, hip_stream));
-    CAT_TRY(cat_pca_project(lq, N, D, p, dt, mean, components, w.z, hip_stream));
+    const int32_t pp = pad4(p);
+    CAT_TRY(pca_project_ld(lq, N, D, p, dt, mean, components, w.z, pp, st));
     // clusters from the scores ...
-    FitWs wz = carve_fit(w.lloyd, N, p, K, CAT_F32);
-    CAT_TRY(run_lloyd(w.z, CAT_F32, N, p, K, iters, seed, nullptr, centroids_z, assignments, inertia, wz, st));
+    FitWs wz = carve_fit(w.lloyd, N, pp, K, CAT_F32);
+    float* cz = pp == p ? centroids_z : w.cz;
+    CAT_TRY(run_lloyd(w.z, CAT_F32, N, pp, K, iters, seed, nullptr, cz, assignments, inertia, wz, st));
+    if (pp != p) CAT_TRY(launch_copy_cols(cz, K, pp, centroids_z, p, p, st));
     // ... the affine fit on the full vectors (rows are shared, so the counts and first rows carry over)
     FitWs wx = carve_fit(w.stats, N, D, K, dt);
     CAT_TRY(step_stats(lq, fp, dt, assignments, N, D, K, wz.counts, wz.rep, nullptr, wx, gamma, beta, st));
@@ -484,18 +494,22 @@ cat_status cat_fit_pca(const void* lq, const void* fp, int64_t N, int64_t D, int
 }
 
 struct PcaApplyWs {
-    float* z;
+    float* z;    // N x pad4(p)
+    float* cz;   // K x pad4(p)
     int32_t* assign;
-    void* step;  // cat_fit scratch for (N, p, K, float): the assignment step
+    void* step;  // cat_fit scratch for (N, pad4(p), K, float): the assignment step
     size_t step_bytes, bytes;
 };
 static PcaApplyWs carve_pca_apply(void* base, int64_t N, int32_t K, int32_t p) {
     PcaApplyWs w;
-    w.step_bytes = carve_fit(nullptr, N, p, K, CAT_F32).bytes;
+    const int32_t pp = pad4(p);
+    w.step_bytes = carve_fit(nullptr, N, pp, K, CAT_F32).bytes;
     char* b = (char*)base;
     size_t off = 0;
     w.z = (float*)(b + off);
-    off += align256((size_t)N * (size_t)p * sizeof(float));
+    off += align256((size_t)N * (size_t)pp * sizeof(float));
+    w.cz = (float*)(b + off);
+    off += align256((size_t)K * (size_t)pp * sizeof(float));
     w.assign = (int32_t*)(b + off);
     off += align256((size_t)N * sizeof(int32_t));
     w.step = b + off;
@@ -527,9 +541,15 @@ cat_status cat_apply_pca(const void* lq, int64_t N, int64_t D, int32_t K, int32_
     CAT_TRY(check_ws("cat_apply_pca", workspace, workspace_bytes, w.bytes));
     hipStream_t st = (hipStream_t)hip_stream;
     int32_t* a = assignments ? assignments : w.assign;
-    CAT_TRY(cat_pca_project(lq, N, D, p, dt, mean, components, w.z, hip_stream));
-    FitWs ws = carve_fit(w.step, N, p, K, CAT_F32);
-    CAT_TRY(step_assign(w.z, CAT_F32, N, p, K, centroids_z, a, nullptr, nullptr, nullptr, ws.tile, st));
+    const int32_t pp = pad4(p);
+    CAT_TRY(pca_project_ld(lq, N, D, p, dt, mean, components, w.z, pp, st));
+    const float* cz = centroids_z;
+    if (pp != p) {
+        CAT_TRY(launch_copy_cols(centroids_z, K, p, w.cz, pp, p, st));
+        cz = w.cz;
+    }
+    FitWs ws = carve_fit(w.step, N, pp, K, CAT_F32);
+    CAT_TRY(step_assign(w.z, CAT_F32, N, pp, K, cz, a, nullptr, nullptr, nullptr, ws.tile, st));
     return cat_apply_assigned(lq, a, N, D, K, dt, gamma, beta, alpha, corrected, hip_stream);
 }
 

@@ -115,5 +115,11 @@ cat_status launch_fold_alpha(const float* gamma, const float* beta, float alpha,
 // device-to-device copy of 32-bit words (any 4-byte-aligned buffers)
 cat_status launch_copy_words(const void* src, void* dst, int64_t nwords, hipStream_t st);
 cat_status launch_fill_u64(unsigned long long* p, int64_t n, unsigned long long v, hipStream_t st);
+// dst (rows x dst_ld) <- the first `cols` columns of src (rows x src_ld), zeros in the columns from `cols` on
+cat_status launch_copy_cols(const float* src, int64_t rows, int32_t src_ld, float* dst, int32_t dst_ld, int32_t cols,
+                            hipStream_t st);
+// PCA scores (cat_pca.hip) with rows ldz >= p floats apart; the padding columns are written as zeros
+cat_status pca_project_ld(const void* lq, int64_t N, int64_t D, int32_t p, cat_dtype dt, const float* mean,
+                          const float* components, float* z, int32_t ldz, hipStream_t st);
 
 }  // namespace cat

@@ -269,7 +269,7 @@ constexpr int kProjWaves = 8, kProjChunk = 128;
 template <typename T, int NT>
 __global__ __launch_bounds__(kProjWaves * kWave) void k_pca_project(const T* __restrict__ x, int64_t N, int64_t D, int32_t p,
                                                                     const float* __restrict__ mean, const float* __restrict__ comps,
-                                                                    float* __restrict__ z) {
+                                                                    float* __restrict__ z, int32_t ldz) {
     __shared__ __align__(16) float s_w[(kProjChunk / 16) * NT * kWave * 4];  // 8 steps x NT tiles x 64 lanes x 4
     __shared__ __align__(16) float s_m[kProjChunk];
     const int lane = threadIdx.x & (kWave - 1);
@@ -351,14 +351,15 @@ __global__ __launch_bounds__(kProjWaves * kWave) void k_pca_project(const T* __r
 #pragma unroll
             for (int t = 0; t < NT; t++) {
                 const int c = c0 + 16 * t + 4 * g;
-                float* o = z + row * p + c;
-                if (c + 3 < p && ((p & 3) == 0)) {
+                // rows of z are ldz >= p floats apart; columns p .. ldz - 1 receive the zeros the padded directions give
+                float* o = z + row * ldz + c;
+                if (c + 3 < ldz && ((ldz & 3) == 0)) {
                     *(f32x4_t*)o = acc[t];
                 } else {
-                    if (c < p) o[0] = acc[t].x;
-                    if (c + 1 < p) o[1] = acc[t].y;
-                    if (c + 2 < p) o[2] = acc[t].z;
-                    if (c + 3 < p) o[3] = acc[t].w;
+                    if (c < ldz) o[0] = acc[t].x;
+                    if (c + 1 < ldz) o[1] = acc[t].y;
+                    if (c + 2 < ldz) o[2] = acc[t].z;
+                    if (c + 3 < ldz) o[3] = acc[t].w;
                 }
             }
         }
@@ -420,6 +421,27 @@ static PcaWs pca_carve(void* base, int64_t D) {
 static bool pca_shape_ok(int64_t N, int64_t D, int32_t p, cat_dtype dt) {
     return (dt == CAT_F32 || dt == CAT_BF16) && N >= 1 && D >= 1 && D <= kPcaMaxD && p >= 1 && (int64_t)p <= D &&
            N <= ((int64_t)1 << 40);
+}
+
+// scores with rows ldz >= p floats apart (the padding columns are written as zeros); ldz < p + 16
+cat_status pca_project_ld(const void* lq, int64_t N, int64_t D, int32_t p, cat_dtype dt, const float* mean,
+                          const float* components, float* z, int32_t ldz, hipStream_t st) {
+    if ((dt != CAT_F32 && dt != CAT_BF16) || N < 1 || D < 1 || p < 1 || (int64_t)p > D || ldz < p || ldz > ((p + 15) & ~15))
+        return set_error(CAT_ERR_INVALID_ARG, "cat_pca_project: need N >= 1, 1 <= p <= D (N=%lld D=%lld p=%d dt=%d ld=%d)", (long long)N,
+                         (long long)D, (int)p, (int)dt, (int)ldz);
+    if (!lq || !mean || !components || !z) return set_error(CAT_ERR_INVALID_ARG, "cat_pca_project: null argument");
+    const int64_t rows_per_block = kProjWaves * 16;
+    dim3 g((unsigned)((N + rows_per_block - 1) / rows_per_block)), b(kProjWaves * kWave);
+#define CAT_PROJ(T, NT) \
+    hipLaunchKernelGGL((k_pca_project<T, NT>), g, b, 0, st, (const T*)lq, N, D, p, mean, components, z, ldz)
+    if (dt == CAT_F32) {
+        if (p <= 16) CAT_PROJ(float, 1); else if (p <= 32) CAT_PROJ(float, 2); else CAT_PROJ(float, 4);
+    } else {
+        if (p <= 16) CAT_PROJ(bf16_t, 1); else if (p <= 32) CAT_PROJ(bf16_t, 2); else CAT_PROJ(bf16_t, 4);
+    }
+#undef CAT_PROJ
+    CAT_LAUNCH_CHECK("k_pca_project");
+    return CAT_OK;
 }
 
 }  // namespace cat
@@ -493,23 +515,7 @@ cat_status cat_pca_fit(const void* lq, int64_t N, int64_t D, int32_t p, cat_dtyp
 
 cat_status cat_pca_project(const void* lq, int64_t N, int64_t D, int32_t p, cat_dtype dt, const float* mean,
                            const float* components, float* z, void* hip_stream) {
-    if ((dt != CAT_F32 && dt != CAT_BF16) || N < 1 || D < 1 || p < 1 || (int64_t)p > D)
-        return set_error(CAT_ERR_INVALID_ARG, "cat_pca_project: need N >= 1, 1 <= p <= D (N=%lld D=%lld p=%d dt=%d)", (long long)N,
-                         (long long)D, (int)p, (int)dt);
-    if (!lq || !mean || !components || !z) return set_error(CAT_ERR_INVALID_ARG, "cat_pca_project: null argument");
-    hipStream_t st = (hipStream_t)hip_stream;
-    const int64_t rows_per_block = kProjWaves * 16;
-    dim3 g((unsigned)((N + rows_per_block - 1) / rows_per_block)), b(kProjWaves * kWave);
-#define CAT_PROJ(T, NT) \
-    hipLaunchKernelGGL((k_pca_project<T, NT>), g, b, 0, st, (const T*)lq, N, D, p, mean, components, z)
-    if (dt == CAT_F32) {
-        if (p <= 16) CAT_PROJ(float, 1); else if (p <= 32) CAT_PROJ(float, 2); else CAT_PROJ(float, 4);
-    } else {
-        if (p <= 16) CAT_PROJ(bf16_t, 1); else if (p <= 32) CAT_PROJ(bf16_t, 2); else CAT_PROJ(bf16_t, 4);
-    }
-#undef CAT_PROJ
-    CAT_LAUNCH_CHECK("k_pca_project");
-    return CAT_OK;
+    return pca_project_ld(lq, N, D, p, dt, mean, components, z, p, (hipStream_t)hip_stream);
 }
 
 cat_status cat_apply_assigned(const void* lq, const int32_t* assignments, int64_t N, int64_t D, int32_t K, cat_dtype dt,

@@ -23,6 +23,22 @@ cat_status launch_fill_zero(void* p, size_t bytes, hipStream_t st) {
     return CAT_OK;
 }
 
+__global__ void k_copy_cols(const float* __restrict__ src, int64_t rows, int32_t src_ld, float* __restrict__ dst,
+                            int32_t dst_ld, int32_t cols) {
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= rows * dst_ld) return;
+    const int64_t r = i / dst_ld;
+    const int32_t c = (int32_t)(i - r * dst_ld);
+    dst[i] = c < cols ? src[r * src_ld + c] : 0.f;
+}
+cat_status launch_copy_cols(const float* src, int64_t rows, int32_t src_ld, float* dst, int32_t dst_ld, int32_t cols,
+                            hipStream_t st) {
+    const int64_t n = rows * dst_ld;
+    hipLaunchKernelGGL(k_copy_cols, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, src, rows, src_ld, dst, dst_ld, cols);
+    CAT_LAUNCH_CHECK("k_copy_cols");
+    return CAT_OK;
+}
+
 __global__ void k_fill_u64(unsigned long long* p, int64_t n, unsigned long long v) {
     int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i < n) p[i] = v;
