@@ -39,12 +39,12 @@ HBM_PEAK_GBPS = 8000.0
 # (a copy reads and writes exactly N*D*b bytes).  Per workload: (FETCH_SIZE of k_tile, FETCH_SIZE of the
 # copy, WRITE_SIZE of k_tile, WRITE_SIZE of the copy), counter units, mean per dispatch.  The figures
 # belong to one version of the kernel source: `traffic` is reported only while its hash still matches.
-TRAFFIC_KERNEL_SHA256 = "a85837f0a7b73474559b4e56707c084d4db616d7b8911bf2654db1426a57ec1f"
+TRAFFIC_KERNEL_SHA256 = "5be413f6cf254f4e59e61865ce4a21f43242e1158f25d2d3918536261c9051c4"
 TRAFFIC_COUNTERS = {
-    "cfg2": (133734.7, 128011.8, 301.8, 256000.0),
-    "cfg3": (527774.8, 524299.7, 4883.4, 1048576.0),
-    "cfg4": (560666.9, 524299.7, 1232.2, 1048576.0),
-    "cfg5": (8361529.5, 4194317.7, 8406453.6, 8388608.0),
+    "cfg2": (133730.9, 128011.7, 298.8, 256000.0),
+    "cfg3": (527766.4, 524300.7, 4723.0, 1048576.0),
+    "cfg4": (560592.9, 524300.5, 1190.7, 1048576.0),
+    "cfg5": (8362201.7, 4194317.6, 8406456.9, 8388608.0),
 }
 
 

@@ -7,9 +7,10 @@
  *                    per cluster and per channel, gamma = cov(LQ,FP) / var(LQ) and
  *                    beta = mean(FP) - gamma * mean(LQ).
  *   CAT Inferencing  nearest centroid, then  q + alpha * (gamma_k * q + beta_k - q).
- * The paper reduces the LQ vectors with PCA before clustering; this library
- * clusters in the full dimension D (the pca_dim = D case: a full-rank PCA is a
- * rigid motion and leaves every distance unchanged).
+ * The paper reduces the LQ vectors with PCA before clustering.  cat_fit and
+ * cat_apply cluster in the full dimension D (the pca_dim = D case: a full-rank
+ * PCA is a rigid motion and leaves every distance unchanged); cat_fit_pca and
+ * cat_apply_pca are the same two phases with the PCA front-end (further down).
  *
  * Conventions, valid for every entry point unless stated otherwise
  *   - Every data pointer is a DEVICE pointer owned by the caller.  The library
@@ -29,7 +30,8 @@
  *   - Inputs are never modified; outputs are fully overwritten.  Nullable
  *     outputs are marked.  No exception crosses the ABI.
  *   - Non-finite input values give unspecified results (no crash, no hang).
- *   - Calls are re-entrant across distinct streams and workspaces.
+ *   - Calls are re-entrant across distinct streams and workspaces, also from
+ *     several host threads (what the library caches between calls is per thread).
  *
  * Distances are squared Euclidean.  A tie goes to the LOWEST cluster index.
  * The assignment is exact up to rounding: a fast bf16-split MFMA pass ranks the

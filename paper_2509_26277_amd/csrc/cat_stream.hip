@@ -610,7 +610,7 @@ cat_status launch_segsum_sorted(int nq, const void* lq, const void* fp, cat_dtyp
     // One wave per run: as many runs as waves are resident at once (or a multiple of that), so
     // the launch has no ragged second round; a run is at least 64 rows (shorter runs only add
     // merge traffic) and at most about a thousand.
-    static int slots_cache[2][2] = {{0, 0}, {0, 0}}, slots_dev = -1;
+    static thread_local int slots_cache[2][2] = {{0, 0}, {0, 0}}, slots_dev = -1;
     int dev = 0;
     CAT_HIP_TRY(hipGetDevice(&dev));
     if (dev != slots_dev) {

@@ -713,7 +713,7 @@ static inline cat_status launch_one(const TileParams& p, const TileCfg& c, hipSt
     CAT_HIP_TRY(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)c.lds_total));
     // persistent grid: as many workgroups as are resident at once (registers and LDS decide), each
     // walking its share of the tiles; asked from the runtime once per kernel variant, LDS size and device
-    static int cached_lds = -1, cached_dev = -1, cached_per_cu = 1, ncu = 256;
+    static thread_local int cached_lds = -1, cached_dev = -1, cached_per_cu = 1, ncu = 256;
     int dev = 0;
     CAT_HIP_TRY(hipGetDevice(&dev));
     if (cached_lds != (int)c.lds_total || cached_dev != dev) {
