@@ -67,6 +67,11 @@ typedef enum { CAT_F32 = 0, CAT_BF16 = 1 } cat_dtype;
  * both on any shape).  Forcing CAT_PATH_TILE on a shape it cannot run makes the
  * call return CAT_ERR_UNSUPPORTED.  Process-wide; default CAT_PATH_AUTO. */
 typedef enum { CAT_PATH_AUTO = 0, CAT_PATH_STREAM = 1, CAT_PATH_TILE = 2 } cat_path;
+
+/* How cat_fit_restarts seeds the centroids of a run: the distinct rows of cat_init_indices, or the
+ * D^2-weighted seeding of cat_init_kmeanspp. */
+typedef enum { CAT_SEED_ROWS = 0, CAT_SEED_KMEANSPP = 1 } cat_seeding;
+#define CAT_MAX_RESTARTS 1024
 cat_status cat_select_path(cat_path p);
 
 /* Bytes of device scratch cat_fit / cat_assign / cat_update / cat_stats need
@@ -277,6 +282,30 @@ size_t cat_init_kmeanspp_workspace_bytes(int64_t N, int32_t K);
 cat_status cat_init_kmeanspp(const void *lq, int64_t N, int64_t D, int32_t K, uint64_t seed, cat_dtype dt,
                              float *centroids, int64_t *indices,
                              void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/* ---- several runs, the best kept (the paper gives neither the k-means initialisation nor a number
+ * of restarts, Sec. 4 Setup; this is the usual remedy for Lloyd's dependence on its start) ----
+ *
+ * cat_fit_restarts runs the clustering part of cat_fit `restarts` times, run r with the seed
+ * `seed + r` (seeding CAT_SEED_ROWS: the rows of cat_init_indices; CAT_SEED_KMEANSPP: those of
+ * cat_init_kmeanspp), keeps the run whose final objective (the sum of squared distances of the final
+ * assignment, as reported in `inertia`) is lowest, the first such run on ties, and fits gamma and
+ * beta on its partition.  With restarts = 1 and CAT_SEED_ROWS it is cat_fit without init_centroids.
+ * Outputs as cat_fit, all of the kept run, plus
+ *   best_run       out, nullable, 1 int32 (device): r of the kept run
+ *   final_inertia  out, nullable, `restarts` doubles (device): the final objective of every run
+ * The comparison between runs is made on the device, on the objective as the library computes it
+ * (fp32 scores summed in double, about 1e-6 relative): runs closer than that may be ordered
+ * differently than by their exact objectives.  1 <= restarts <= CAT_MAX_RESTARTS.  workspace:
+ * cat_fit_restarts_workspace_bytes(N, D, K, iters, dt).
+ */
+size_t cat_fit_restarts_workspace_bytes(int64_t N, int64_t D, int32_t K, int32_t iters, cat_dtype dt);
+cat_status cat_fit_restarts(const void *lq, const void *fp, int64_t N, int64_t D, int32_t K,
+                            int32_t iters, uint64_t seed, int32_t restarts, cat_seeding seeding, cat_dtype dt,
+                            float *centroids, float *gamma, float *beta,
+                            int32_t *assignments, int32_t *counts, double *inertia,
+                            int32_t *best_run, double *final_inertia,
+                            void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /*
  * Timing of the dominant kernel, for benchmarks.  While enabled, every launch of the tile

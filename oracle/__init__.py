@@ -21,4 +21,5 @@ from .cat_oracle import (  # noqa: F401
     pca_project,
     alpha_sweep,
     kmeanspp,
+    fit_restarts,
 )

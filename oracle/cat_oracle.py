@@ -292,3 +292,23 @@ def kmeanspp(lq, K, seed=0):
     idx = np.empty(K, dtype=np.int64)
     _load().cat_oracle_kmeanspp(xp, N, D, K, seed & (2**64 - 1), _p(idx, ctypes.c_int64))
     return idx
+
+
+# ---------------------------------------------------------------------------
+# Several runs, the best kept
+# ---------------------------------------------------------------------------
+def fit_restarts(lq, fp, K, iters, seed=0, restarts=4, kmeanspp_seeding=False):
+    """``restarts`` runs of ``fit`` (run r seeded with ``seed + r``; the D^2-weighted rows of ``kmeanspp`` as initial
+    centroids if asked), the run with the lowest final objective kept, the first one on ties.  Returns the dict of
+    the kept run plus ``best_run`` and ``final_inertia`` (the final objective of every run)."""
+    best, finals = None, []
+    for r in range(restarts):
+        init = None
+        if kmeanspp_seeding:
+            init = np.asarray(lq, dtype=np.float32)[kmeanspp(lq, K, seed=seed + r)].astype(np.float64)
+        run = fit(lq, fp, K, iters, seed=seed + r, init_centroids=init)
+        finals.append(float(run["inertia"][-1]))
+        if best is None or finals[-1] < best["inertia"][-1]:
+            best = dict(run, best_run=r)
+    best["final_inertia"] = np.asarray(finals)
+    return best

@@ -23,7 +23,8 @@ EXPORTS = ("cat_select_path", "cat_fit_workspace_bytes", "cat_apply_workspace_by
            "cat_profile_read", "cat_debug_list_capacity", "cat_pca_workspace_bytes", "cat_pca_fit", "cat_pca_project",
            "cat_apply_assigned", "cat_fit_pca_workspace_bytes", "cat_fit_pca", "cat_apply_pca_workspace_bytes", "cat_apply_pca",
            "cat_alpha_sweep_workspace_bytes", "cat_alpha_sweep", "cat_top1",
-           "cat_init_kmeanspp_workspace_bytes", "cat_init_kmeanspp")
+           "cat_init_kmeanspp_workspace_bytes", "cat_init_kmeanspp",
+           "cat_fit_restarts_workspace_bytes", "cat_fit_restarts")
 
 
 class CatError(RuntimeError):
@@ -96,6 +97,11 @@ def load_library():
     lib.cat_init_kmeanspp.argtypes = [vp, i64, i64, i32, u64, c.c_int, vp, vp, vp, sz, vp]
     lib.cat_init_kmeanspp.restype = c.c_int
     lib.cat_top1.restype = c.c_int
+    lib.cat_fit_restarts_workspace_bytes.argtypes = [i64, i64, i32, i32, c.c_int]
+    lib.cat_fit_restarts_workspace_bytes.restype = sz
+    lib.cat_fit_restarts.argtypes = [vp, vp, i64, i64, i32, i32, u64, i32, c.c_int, c.c_int, vp, vp, vp, vp, vp, vp, vp, vp,
+                                     vp, sz, vp]
+    lib.cat_fit_restarts.restype = c.c_int
     lib.cat_debug_list_capacity.argtypes = [c.c_int]
     lib.cat_debug_list_capacity.restype = c.c_int
     lib.cat_last_error.argtypes = []
@@ -363,6 +369,34 @@ def cat_init_kmeanspp(lq, K, seed=0, workspace=None):
     _check(lib.cat_init_kmeanspp(_dev(lq, name="lq"), N, D, K, seed & (2**64 - 1), _dt(lq), cent.data_ptr(), idx.data_ptr(),
                                  workspace.data_ptr(), workspace.numel(), _stream()))
     return cent, idx
+
+
+CAT_SEED_ROWS, CAT_SEED_KMEANSPP = 0, 1
+
+
+def cat_fit_restarts(lq, fp, K, iters, seed=0, restarts=4, seeding=CAT_SEED_ROWS, workspace=None):
+    """``restarts`` runs of the clustering (run r seeded with ``seed + r``), the one with the lowest final objective
+    kept, then the affine fit on its partition.  Returns the dict of ``cat_fit`` plus ``best_run`` (1 int32) and
+    ``final_inertia`` (restarts float64), all device tensors."""
+    lib = load_library()
+    N, D = lq.shape
+    dt = _dt(lq)
+    dev = lq.device
+    if workspace is None:
+        workspace = _workspace(lib.cat_fit_restarts_workspace_bytes(N, D, K, iters, dt), dev)
+    f32 = dict(dtype=torch.float32, device=dev)
+    cent, gamma, beta = torch.empty((K, D), **f32), torch.empty((K, D), **f32), torch.empty((K, D), **f32)
+    a = torch.empty((N,), dtype=torch.int32, device=dev)
+    counts = torch.empty((K,), dtype=torch.int32, device=dev)
+    inertia = torch.empty((max(iters, 0) + 1,), dtype=torch.float64, device=dev)
+    best = torch.empty((1,), dtype=torch.int32, device=dev)
+    finals = torch.empty((max(restarts, 1),), dtype=torch.float64, device=dev)
+    _check(lib.cat_fit_restarts(_dev(lq, name="lq"), _dev(fp, lq.dtype, (N, D), "fp"), N, D, K, iters, seed & (2**64 - 1),
+                                restarts, int(seeding), dt, cent.data_ptr(), gamma.data_ptr(), beta.data_ptr(), a.data_ptr(),
+                                counts.data_ptr(), inertia.data_ptr(), best.data_ptr(), finals.data_ptr(),
+                                workspace.data_ptr(), workspace.numel(), _stream()))
+    return dict(centroids=cent, gamma=gamma, beta=beta, assignments=a, counts=counts, inertia=inertia, best_run=best,
+                final_inertia=finals)
 
 
 def cat_fit_pca(lq, fp, K, p, iters, seed=0, want_inertia=True, workspace=None):

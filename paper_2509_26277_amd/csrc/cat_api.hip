@@ -385,6 +385,92 @@ cat_status cat_fit(const void* lq, const void* fp, int64_t N, int64_t D, int32_t
     return CAT_OK;
 }
 
+// ---- several runs of the clustering, the one with the lowest final objective kept ---------------------
+struct RestartWs {
+    void* fit;           // cat_fit scratch
+    void* pp;            // cat_init_kmeanspp scratch
+    float* init;         // K x D   seeded centroids of the run
+    float* cent;         // K x D   centroids of the run
+    int32_t* assign;     // N       assignments of the run
+    double* inertia;     // iters + 1 objective values of the run
+    double* best;        // lowest final objective so far
+    int32_t* state;      // [0] the run just finished is the best so far, [1] its index
+    size_t fit_bytes, pp_bytes, bytes;
+};
+static RestartWs carve_restarts(void* base, int64_t N, int64_t D, int32_t K, int32_t iters, cat_dtype dt) {
+    RestartWs w;
+    w.fit_bytes = carve_fit(nullptr, N, D, K, dt).bytes;
+    w.pp_bytes = cat_init_kmeanspp_workspace_bytes(N, K);
+    char* b = (char*)base;
+    size_t off = 0;
+    auto take = [&](size_t bytes) {
+        char* ptr = b + off;
+        off += align256(bytes);
+        return ptr;
+    };
+    w.fit = take(w.fit_bytes);
+    w.pp = take(w.pp_bytes);
+    w.init = (float*)take((size_t)K * (size_t)D * sizeof(float));
+    w.cent = (float*)take((size_t)K * (size_t)D * sizeof(float));
+    w.assign = (int32_t*)take((size_t)N * sizeof(int32_t));
+    w.inertia = (double*)take(((size_t)(iters < 0 ? 0 : iters) + 1) * sizeof(double));
+    w.best = (double*)take(sizeof(double));
+    w.state = (int32_t*)take(2 * sizeof(int32_t));
+    w.bytes = off;
+    return w;
+}
+
+size_t cat_fit_restarts_workspace_bytes(int64_t N, int64_t D, int32_t K, int32_t iters, cat_dtype dt) {
+    if (!shape_ok(N, D, K, dt) || iters < 0) return 0;
+    return carve_restarts(nullptr, N, D, K, iters, dt).bytes;
+}
+
+cat_status cat_fit_restarts(const void* lq, const void* fp, int64_t N, int64_t D, int32_t K, int32_t iters, uint64_t seed,
+                            int32_t restarts, cat_seeding seeding, cat_dtype dt, float* centroids, float* gamma, float* beta,
+                            int32_t* assignments, int32_t* counts, double* inertia, int32_t* best_run, double* final_inertia,
+                            void* workspace, size_t workspace_bytes, void* hip_stream) {
+    CAT_TRY(check_shape("cat_fit_restarts", N, D, K, dt));
+    if (iters < 0) return set_error(CAT_ERR_INVALID_ARG, "cat_fit_restarts: iters = %d is negative", (int)iters);
+    if (restarts < 1 || restarts > CAT_MAX_RESTARTS)
+        return set_error(CAT_ERR_INVALID_ARG, "cat_fit_restarts: need 1 <= restarts <= %d (got %d)", CAT_MAX_RESTARTS, (int)restarts);
+    if (seeding != CAT_SEED_ROWS && seeding != CAT_SEED_KMEANSPP)
+        return set_error(CAT_ERR_INVALID_ARG, "cat_fit_restarts: unknown seeding %d", (int)seeding);
+    CAT_TRY(check_ptr("cat_fit_restarts", "lq", lq, 16));
+    CAT_TRY(check_ptr("cat_fit_restarts", "fp", fp, 16));
+    CAT_TRY(check_ptr("cat_fit_restarts", "centroids", centroids, 16));
+    CAT_TRY(check_ptr("cat_fit_restarts", "gamma", gamma, 16));
+    CAT_TRY(check_ptr("cat_fit_restarts", "beta", beta, 16));
+    CAT_TRY(check_ptr("cat_fit_restarts", "assignments", assignments, 4));
+    if (inertia) CAT_TRY(check_ptr("cat_fit_restarts", "inertia", inertia, 8));
+    if (final_inertia) CAT_TRY(check_ptr("cat_fit_restarts", "final_inertia", final_inertia, 8));
+    RestartWs w = carve_restarts(workspace, N, D, K, iters, dt);
+    CAT_TRY(check_ws("cat_fit_restarts", workspace, workspace_bytes, w.bytes));
+    hipStream_t st = (hipStream_t)hip_stream;
+    FitWs fw = carve_fit(w.fit, N, D, K, dt);
+    const size_t KD = (size_t)K * (size_t)D;
+    for (int32_t r = 0; r < restarts; r++) {
+        const uint64_t seed_r = seed + (uint64_t)r;
+        const float* init = nullptr;
+        if (seeding == CAT_SEED_KMEANSPP) {
+            CAT_TRY(cat_init_kmeanspp(lq, N, D, K, seed_r, dt, w.init, nullptr, w.pp, w.pp_bytes, hip_stream));
+            init = w.init;
+        }
+        CAT_TRY(run_lloyd(lq, dt, N, D, K, iters, seed_r, init, w.cent, w.assign, w.inertia, fw, st));
+        CAT_TRY(launch_keep_best(w.inertia + iters, w.best, w.state, r, final_inertia, st));
+        CAT_TRY(launch_copy_words_if(w.state, w.cent, centroids, (int64_t)KD, st));
+        CAT_TRY(launch_copy_words_if(w.state, w.assign, assignments, N, st));
+        if (inertia) CAT_TRY(launch_copy_words_if(w.state, w.inertia, inertia, 2 * ((int64_t)iters + 1), st));
+    }
+    // the kept partition: counts and first rows again (the scratch holds those of the last run), then the affine fit
+    CAT_TRY(launch_fill_zero(fw.counts, (size_t)K * sizeof(int32_t), st));
+    CAT_TRY(launch_fill_u64(fw.rep, K, ~0ull, st));
+    CAT_TRY(launch_count_rep(assignments, N, K, fw.counts, fw.rep, st));
+    CAT_TRY(step_stats(lq, fp, dt, assignments, N, D, K, fw.counts, fw.rep, centroids, fw, gamma, beta, st));
+    if (counts) CAT_TRY(launch_copy_words(fw.counts, counts, K, st));
+    if (best_run) CAT_TRY(launch_copy_words(w.state + 1, best_run, 1, st));
+    return CAT_OK;
+}
+
 cat_status cat_apply(const void* lq, int64_t N, int64_t D, int32_t K, cat_dtype dt, const float* centroids,
                      const float* gamma, const float* beta, float alpha, void* corrected, int32_t* assignments,
                      void* workspace, size_t workspace_bytes, void* hip_stream) {

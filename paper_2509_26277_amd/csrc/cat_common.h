@@ -118,6 +118,10 @@ cat_status launch_fill_u64(unsigned long long* p, int64_t n, unsigned long long 
 // dst (rows x dst_ld) <- the first `cols` columns of src (rows x src_ld), zeros in the columns from `cols` on
 cat_status launch_copy_cols(const float* src, int64_t rows, int32_t src_ld, float* dst, int32_t dst_ld, int32_t cols,
                             hipStream_t st);
+// best-of-several bookkeeping on the device: state[0] = 1 if `cur` beats `best` (or run == 0), state[1] = best run;
+// finals (nullable) receives cur at index run.  launch_copy_words_if copies only while *flag != 0.
+cat_status launch_keep_best(const double* cur, double* best, int32_t* state, int32_t run, double* finals, hipStream_t st);
+cat_status launch_copy_words_if(const int32_t* flag, const void* src, void* dst, int64_t nwords, hipStream_t st);
 // PCA scores (cat_pca.hip) with rows ldz >= p floats apart; the padding columns are written as zeros
 cat_status pca_project_ld(const void* lq, int64_t N, int64_t D, int32_t p, cat_dtype dt, const float* mean,
                           const float* components, float* z, int32_t ldz, hipStream_t st);

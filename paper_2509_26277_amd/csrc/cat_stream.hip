@@ -23,6 +23,40 @@ cat_status launch_fill_zero(void* p, size_t bytes, hipStream_t st) {
     return CAT_OK;
 }
 
+// Best-of-several bookkeeping, all on the device so that nothing waits for the host.  state[0]: 1 if the run
+// just finished is the best so far (strictly lower objective, or the first run), state[1]: index of the best run.
+__global__ void k_keep_best(const double* cur, double* best, int32_t* state, int32_t run, double* finals) {
+    if (threadIdx.x != 0 || blockIdx.x != 0) return;
+    const double v = *cur;
+    if (finals) finals[run] = v;
+    const bool take = run == 0 || v < *best;
+    state[0] = take ? 1 : 0;
+    if (take) {
+        *best = v;
+        state[1] = run;
+    }
+}
+cat_status launch_keep_best(const double* cur, double* best, int32_t* state, int32_t run, double* finals, hipStream_t st) {
+    hipLaunchKernelGGL(k_keep_best, dim3(1), dim3(64), 0, st, cur, best, state, run, finals);
+    CAT_LAUNCH_CHECK("k_keep_best");
+    return CAT_OK;
+}
+__global__ void k_copy_words_if(const int32_t* __restrict__ flag, const uint32_t* __restrict__ src, uint32_t* __restrict__ dst,
+                                int64_t n) {
+    if (*flag == 0) return;  // uniform
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int64_t step = (int64_t)gridDim.x * blockDim.x;
+    for (; i < n; i += step) dst[i] = src[i];
+}
+cat_status launch_copy_words_if(const int32_t* flag, const void* src, void* dst, int64_t nwords, hipStream_t st) {
+    if (nwords <= 0) return CAT_OK;
+    const int64_t want = (nwords + 255) / 256;
+    hipLaunchKernelGGL(k_copy_words_if, dim3((unsigned)(want < 4096 ? want : 4096)), dim3(256), 0, st, flag, (const uint32_t*)src,
+                       (uint32_t*)dst, nwords);
+    CAT_LAUNCH_CHECK("k_copy_words_if");
+    return CAT_OK;
+}
+
 __global__ void k_copy_cols(const float* __restrict__ src, int64_t rows, int32_t src_ld, float* __restrict__ dst,
                             int32_t dst_ld, int32_t cols) {
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;

@@ -1,0 +1,94 @@
+"""GPU-vs-oracle parity of the best-of-several-runs fit (cat_fit_restarts).
+
+Which run is kept is an integer decided by comparing objectives in floating point.  The library compares its own
+objectives (fp32 scores summed in double); the test therefore checks that the kept run is the first minimum of the
+library's own list, that this list agrees with the oracle's run by run, that the oracle's choice, if it differs, is
+within the objective's tolerance of the library's, and that everything returned equals the single fit of the kept
+seed (bit for bit) and the oracle's fit of that seed (to the usual tolerances)."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2509_26277_amd import cat_fit, cat_fit_restarts, cat_init_kmeanspp, workloads
+from paper_2509_26277_amd.binding import CAT_SEED_KMEANSPP, CAT_SEED_ROWS, CatError
+
+from parity_util import RTOL, beta_scale, check_values, dev_matrix, host_matrix
+
+pytestmark = pytest.mark.gpu
+
+
+def _mixture(seed, N, D, K, dt):
+    rng = np.random.default_rng(seed)
+    centres = rng.standard_normal((K, D)) * 2.0
+    lab = rng.integers(0, K, N)
+    y = (centres[lab] + rng.standard_normal((N, D))).astype(np.float32)
+    x = (y * rng.uniform(0.6, 1.4, D).astype(np.float32) + 0.2 * rng.standard_normal((N, D)).astype(np.float32)).astype(np.float32)
+    if dt == "bf16":
+        x, y = workloads.round_to_bf16(x), workloads.round_to_bf16(y)
+    return x, y
+
+
+@pytest.mark.parametrize("N,D,K,iters,restarts,dt,seeding", [
+    (3000, 64, 6, 5, 6, "f32", CAT_SEED_ROWS),
+    (3000, 64, 6, 5, 6, "f32", CAT_SEED_KMEANSPP),
+    (2500, 136, 9, 4, 5, "bf16", CAT_SEED_ROWS),
+    (1500, 37, 4, 3, 4, "f32", CAT_SEED_KMEANSPP),   # the streaming kernels (D not a multiple of 4)
+    (800, 16, 3, 0, 3, "f32", CAT_SEED_ROWS),        # no iterations: the seeds themselves are compared
+])
+def test_best_run_matches_the_oracle(N, D, K, iters, restarts, dt, seeding):
+    x, y = _mixture(N + D, N, D, K, dt)
+    xd, yd = dev_matrix(x, dt), dev_matrix(y, dt)
+    seed = 40
+    r = cat_fit_restarts(xd, yd, K, iters, seed=seed, restarts=restarts, seeding=seeding)
+    finals = r["final_inertia"].cpu().numpy()
+    best = int(r["best_run"])
+    assert best == int(np.argmin(finals))  # first minimum of the library's own objectives
+    o = oracle.fit_restarts(x, y, K, iters, seed=seed, restarts=restarts, kmeanspp_seeding=seeding == CAT_SEED_KMEANSPP)
+    np.testing.assert_allclose(finals, o["final_inertia"], rtol=1e-4)
+    if o["best_run"] != best:
+        assert abs(o["final_inertia"][o["best_run"]] - o["final_inertia"][best]) <= 1e-4 * o["final_inertia"][best]
+    # the single fit of the kept seed, through the library ...
+    init = cat_init_kmeanspp(xd, K, seed=seed + best)[0] if seeding == CAT_SEED_KMEANSPP else None
+    single = cat_fit(xd, yd, K, iters, seed=seed + best, init_centroids=init)
+    for key in ("centroids", "gamma", "beta", "assignments", "counts"):
+        assert torch.equal(r[key], single[key]), key
+    # (the objective is summed with atomics: equal up to the order of the additions)
+    np.testing.assert_allclose(r["inertia"].cpu().numpy(), single["inertia"].cpu().numpy(), rtol=1e-12)
+    # ... and through the oracle
+    oinit = x[oracle.kmeanspp(x, K, seed=seed + best)].astype(np.float64) if seeding == CAT_SEED_KMEANSPP else None
+    ob = oracle.fit(x, y, K, iters, seed=seed + best, init_centroids=oinit)
+    assert (r["assignments"].cpu().numpy() == ob["assignments"]).all()
+    assert (r["counts"].cpu().numpy() == ob["counts"]).all()
+    check_values(host_matrix(r["centroids"]), ob["centroids"], RTOL[dt], "centroids")
+    check_values(host_matrix(r["gamma"]), ob["gamma"], RTOL[dt], "gamma")
+    check_values(host_matrix(r["beta"]), ob["beta"], RTOL[dt], "beta", scale=beta_scale(x, y, ob["assignments"], K, ob["gamma"]))
+
+
+def test_one_run_is_cat_fit():
+    x, y = _mixture(5, 2000, 48, 5, "f32")
+    xd, yd = dev_matrix(x, "f32"), dev_matrix(y, "f32")
+    a = cat_fit_restarts(xd, yd, 5, 4, seed=9, restarts=1)
+    b = cat_fit(xd, yd, 5, 4, seed=9)
+    for key in ("centroids", "gamma", "beta", "assignments", "counts"):
+        assert torch.equal(a[key], b[key]), key
+    np.testing.assert_allclose(a["inertia"].cpu().numpy(), b["inertia"].cpu().numpy(), rtol=1e-12)
+    assert int(a["best_run"]) == 0
+
+
+def test_more_runs_never_end_higher():
+    x, y = _mixture(6, 4000, 32, 12, "f32")
+    xd, yd = dev_matrix(x, "f32"), dev_matrix(y, "f32")
+    j1 = float(cat_fit_restarts(xd, yd, 12, 8, seed=1, restarts=1)["inertia"][-1])
+    j8 = float(cat_fit_restarts(xd, yd, 12, 8, seed=1, restarts=8)["inertia"][-1])
+    assert j8 <= j1
+
+
+def test_bad_arguments_are_refused():
+    x = torch.zeros((64, 8), device="cuda")
+    with pytest.raises(CatError):
+        cat_fit_restarts(x, x, 2, 1, restarts=0)
+    with pytest.raises(CatError):
+        cat_fit_restarts(x, x, 2, 1, restarts=2, seeding=7)
+    with pytest.raises(CatError):
+        cat_fit_restarts(x, x, 2, 1, restarts=2, workspace=torch.empty(256, dtype=torch.uint8, device="cuda"))

@@ -99,3 +99,29 @@ def test_degenerate_inputs():
         assert idx[2] == min(i for i in range(4) if i not in idx[:2].tolist())
     assert oracle.kmeanspp(x, 1, seed=9).shape == (1,)
     assert sorted(oracle.kmeanspp(x, 4, seed=2).tolist()) == [0, 1, 2, 3]
+
+
+def test_best_of_several_runs_is_one_of_the_single_runs_and_none_is_better():
+    """fit_restarts is a selection among fit runs: its result must be, field by field, the single run of the seed it
+    names, that run must have the lowest final objective, and the objective must be what scipy's distance routine
+    gives for the returned partition"""
+    from scipy.spatial.distance import cdist
+    rng = np.random.default_rng(8)
+    K, D = 5, 6
+    centres = rng.standard_normal((K, D)) * 2.5
+    x = (centres[rng.integers(0, K, 400)] + rng.standard_normal((400, D))).astype(np.float32)
+    y = (x * 0.8 + 0.1 * rng.standard_normal((400, D))).astype(np.float32)
+    for pp in (False, True):
+        r = oracle.fit_restarts(x, y, K, 6, seed=20, restarts=7, kmeanspp_seeding=pp)
+        b = int(r["best_run"])
+        init = x[oracle.kmeanspp(x, K, seed=20 + b)].astype(np.float64) if pp else None
+        single = oracle.fit(x, y, K, 6, seed=20 + b, init_centroids=init)
+        for key in ("centroids", "gamma", "beta", "assignments", "counts", "inertia"):
+            assert (np.asarray(r[key]) == np.asarray(single[key])).all(), key
+        finals = r["final_inertia"]
+        assert finals.shape == (7,) and b == int(np.argmin(finals)) and finals[b] == r["inertia"][-1]
+        d = cdist(x.astype(np.float64), r["centroids"], "sqeuclidean")
+        np.testing.assert_allclose(finals[b], d[np.arange(400), r["assignments"]].sum(), rtol=1e-12)
+        assert (r["assignments"] == d.argmin(axis=1)).all()
+    # the runs do differ on this input: the selection is not vacuous
+    assert len(set(np.round(oracle.fit_restarts(x, y, K, 6, seed=20, restarts=7)["final_inertia"], 6))) > 1
