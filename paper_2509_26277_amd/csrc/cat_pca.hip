@@ -367,7 +367,9 @@ __global__ __launch_bounds__(kProjWaves * kWave) void k_pca_project(const T* __r
 }
 
 // ---- affine map by given labels ------------------------------------------------------------------
-template <typename T>
+// One wave per row.  WIDE: 16-byte loads and stores, all of a lane's requests for the row issued before the
+// first is used (rows of whole 16-byte groups, aligned bases); else one channel per lane and step.
+template <typename T, bool WIDE>
 __global__ __launch_bounds__(256) void k_apply_assigned(const T* __restrict__ x, const int32_t* __restrict__ assign, int64_t N,
                                                         int64_t D, int32_t K, const float* __restrict__ gamma,
                                                         const float* __restrict__ beta, float alpha, T* __restrict__ out) {
@@ -376,14 +378,72 @@ __global__ __launch_bounds__(256) void k_apply_assigned(const T* __restrict__ x,
     if (row >= N) return;
     const int a = assign[row];
     const bool ok = a >= 0 && a < K;  // a label outside [0, K) leaves the row as it is
-    for (int64_t j = lane; j < D; j += kWave) {
-        const float v = ld_elem(x + row * D + j);
-        float r = v;
-        if (ok) {
-            const float g = 1.f + alpha * (gamma[(int64_t)a * D + j] - 1.f), b = alpha * beta[(int64_t)a * D + j];
-            r = fmaf(g, v, b);
+    const float* gr = gamma + (int64_t)(ok ? a : 0) * D;
+    const float* br = beta + (int64_t)(ok ? a : 0) * D;
+    const T* xr = x + row * D;
+    T* orow = out + row * D;
+    if (WIDE) {
+        constexpr int EPL = (int)(16 / sizeof(T));  // channels per 16-byte group: 4 (fp32) or 8 (bf16)
+        constexpr int U = 4;                        // groups per lane in flight
+        for (int64_t j0 = (int64_t)lane * EPL; j0 < D; j0 += (int64_t)U * kWave * EPL) {
+            uint4 xv[U];
+            f32x4_t gv[U][EPL / 4], bv[U][EPL / 4];
+            int64_t j[U];
+#pragma unroll
+            for (int u = 0; u < U; u++) {
+                const int64_t jj = j0 + (int64_t)u * kWave * EPL;
+                j[u] = jj < D ? jj : j0;  // past the end: the first group again, not stored
+                xv[u] = *(const uint4*)(xr + j[u]);
+#pragma unroll
+                for (int h = 0; h < EPL / 4; h++) {
+                    gv[u][h] = *(const f32x4_t*)(gr + j[u] + 4 * h);
+                    bv[u][h] = *(const f32x4_t*)(br + j[u] + 4 * h);
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < U; u++) {
+                if (j0 + (int64_t)u * kWave * EPL >= D) break;
+                float v[EPL];
+                if (sizeof(T) == 4) {
+                    v[0] = __uint_as_float(xv[u].x), v[1] = __uint_as_float(xv[u].y);
+                    v[2] = __uint_as_float(xv[u].z), v[3] = __uint_as_float(xv[u].w);
+                } else {
+                    const uint32_t w[4] = {xv[u].x, xv[u].y, xv[u].z, xv[u].w};
+#pragma unroll
+                    for (int e = 0; e < 4; e++) {
+                        v[2 * e] = __uint_as_float(w[e] << 16);
+                        v[(2 * e + 1) % EPL] = __uint_as_float(w[e] & 0xFFFF0000u);
+                    }
+                }
+                float r[EPL];
+#pragma unroll
+                for (int e = 0; e < EPL; e++) {
+                    const float g = 1.f + alpha * (gv[u][e / 4][e % 4] - 1.f), b = alpha * bv[u][e / 4][e % 4];
+                    r[e] = ok ? fmaf(g, v[e], b) : v[e];
+                }
+                uint4 o;
+                if (sizeof(T) == 4) {
+                    o = make_uint4(__float_as_uint(r[0]), __float_as_uint(r[1]), __float_as_uint(r[2]), __float_as_uint(r[3]));
+                } else {
+                    uint32_t w[4];
+#pragma unroll
+                    for (int e = 0; e < 4; e++)
+                        w[e] = (uint32_t)f32_to_bf16(r[2 * e]) | ((uint32_t)f32_to_bf16(r[(2 * e + 1) % EPL]) << 16);
+                    o = make_uint4(w[0], w[1], w[2], w[3]);
+                }
+                *(uint4*)(orow + j[u]) = o;
+            }
         }
-        st_elem(out + row * D + j, r);
+    } else {
+        for (int64_t j = lane; j < D; j += kWave) {
+            const float v = ld_elem(xr + j);
+            float r = v;
+            if (ok) {
+                const float g = 1.f + alpha * (gr[j] - 1.f), b = alpha * br[j];
+                r = fmaf(g, v, b);
+            }
+            st_elem(orow + j, r);
+        }
     }
 }
 
@@ -528,12 +588,17 @@ cat_status cat_apply_assigned(const void* lq, const int32_t* assignments, int64_
     if (!(alpha == alpha) || alpha - alpha != 0.f) return set_error(CAT_ERR_INVALID_ARG, "cat_apply_assigned: alpha must be finite");
     hipStream_t st = (hipStream_t)hip_stream;
     dim3 g((unsigned)((N + 3) / 4)), b(256);
-    if (dt == CAT_F32)
-        hipLaunchKernelGGL(k_apply_assigned<float>, g, b, 0, st, (const float*)lq, assignments, N, D, K, gamma, beta, alpha,
-                           (float*)corrected);
-    else
-        hipLaunchKernelGGL(k_apply_assigned<bf16_t>, g, b, 0, st, (const bf16_t*)lq, assignments, N, D, K, gamma, beta, alpha,
-                           (bf16_t*)corrected);
+    const size_t esz = dt == CAT_F32 ? 4 : 2;
+    const bool wide = (D * esz) % 16 == 0 && (((uintptr_t)lq | (uintptr_t)corrected | (uintptr_t)gamma | (uintptr_t)beta) & 15u) == 0 &&
+                      (D * 4) % 16 == 0;
+#define CAT_AA(T, W) \
+    hipLaunchKernelGGL((k_apply_assigned<T, W>), g, b, 0, st, (const T*)lq, assignments, N, D, K, gamma, beta, alpha, (T*)corrected)
+    if (dt == CAT_F32) {
+        if (wide) CAT_AA(float, true); else CAT_AA(float, false);
+    } else {
+        if (wide) CAT_AA(bf16_t, true); else CAT_AA(bf16_t, false);
+    }
+#undef CAT_AA
     CAT_LAUNCH_CHECK("k_apply_assigned");
     return CAT_OK;
 }

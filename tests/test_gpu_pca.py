@@ -69,9 +69,10 @@ def test_projection_matches_the_oracle(N, D, p, dt):
     check_values(host_matrix(z_g), z_o, 1e-4, "scores")
 
 
-def test_apply_assigned_matches_the_definition():
-    rng = np.random.default_rng(3)
-    N, D, K = 1000, 37, 5
+@pytest.mark.parametrize("D", [37, 1000, 264, 2048, 8])  # one channel per lane; 16-byte groups with and without a ragged last step
+def test_apply_assigned_matches_the_definition(D):
+    rng = np.random.default_rng(3 + D)
+    N, K = 1000, 5
     for dt in ("f32", "bf16"):
         x = rng.standard_normal((N, D)).astype(np.float32)
         if dt == "bf16":
