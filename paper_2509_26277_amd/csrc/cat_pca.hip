@@ -366,6 +366,127 @@ __global__ __launch_bounds__(kProjWaves * kWave) void k_pca_project(const T* __r
     }
 }
 
+// The same projection with the staging of the directions software-pipelined, for rows of whole 16-byte groups (D a
+// multiple of 4, aligned bases): while chunk j is contracted, the directions and the means of chunk j + 1 are
+// already on their way into registers; they then go into the LDS buffer chunk j does not use, and one barrier per
+// chunk separates the two.  Registers are capped at 128 so that two workgroups share a CU (four waves per SIMD).  Every load is unconditional (a position past the end is
+// clamped to a valid one and its value dropped), so none is waited for where it is issued.
+template <typename T, int NT>
+__global__ __launch_bounds__(kProjWaves * kWave, 4) void k_pca_project_pipe(const T* __restrict__ x, int64_t N, int64_t D, int32_t p,
+                                                                         const float* __restrict__ mean,
+                                                                         const float* __restrict__ comps, float* __restrict__ z,
+                                                                         int32_t ldz) {
+    constexpr int SW = (kProjChunk / 16) * NT * kWave * 4;  // floats of directions per chunk
+    constexpr int XS = kProjChunk / 16;                     // 16-channel steps per chunk
+    __shared__ __align__(16) float s_w[2][SW];
+    __shared__ __align__(16) float s_m[2][kProjChunk];
+    const int tid = threadIdx.x, lane = tid & (kWave - 1);
+    const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);
+    const int n = lane & 15, g = lane >> 4;
+    const int64_t ntiles = (N + 15) / 16;
+    const int64_t tile = (int64_t)blockIdx.x * kProjWaves + wave;
+    const int64_t row = tile * 16 + n;
+    const int64_t rowc = row < N ? row : N - 1;  // rows past the end repeat the last row; never stored
+    const T* xr = x + rowc * D;
+    const int nch = (int)((D + kProjChunk - 1) / kProjChunk);
+    // this thread's share of the staging: direction m of every tile, 4-channel group q of the chunk
+    const int sm = tid >> 5, sq = tid & 31;
+    const int s_slot = (((sq >> 2) * NT) * kWave + (sq & 3) * 16 + sm) * 4;  // + t * kWave * 4 for tile t
+
+    typedef uint32_t __attribute__((ext_vector_type(sizeof(T) == 4 ? 4 : 2))) xraw_t;
+    auto load_w = [&](int c0, int jc, f32x4_t (&w)[NT]) {
+        const int64_t ch = (int64_t)jc * kProjChunk + 4 * sq;
+        const int64_t chc = ch < D ? ch : 0;
+#pragma unroll
+        for (int t = 0; t < NT; t++) {
+            const int r = c0 + 16 * t + sm;
+            const f32x4_t v = *(const f32x4_t*)(comps + (int64_t)(r < p ? r : 0) * D + chc);
+            const bool ok = r < p && ch < D;
+            w[t] = (f32x4_t){ok ? v.x : 0.f, ok ? v.y : 0.f, ok ? v.z : 0.f, ok ? v.w : 0.f};
+        }
+    };
+    auto load_m = [&](int jc) {
+        const int64_t ch = (int64_t)jc * kProjChunk + (tid & (kProjChunk - 1));
+        const float v = mean[ch < D ? ch : 0];
+        return ch < D ? v : 0.f;
+    };
+    auto load_x = [&](int jc, xraw_t (&xv)[XS]) {
+#pragma unroll
+        for (int s_ = 0; s_ < XS; s_++) {
+            const int64_t ch = (int64_t)jc * kProjChunk + 16 * s_ + 4 * g;
+            xv[s_] = *(const xraw_t*)(xr + (ch < D ? ch : 0));
+        }
+    };
+
+    for (int c0 = 0; c0 < p; c0 += 16 * NT) {
+        f32x4_t acc[NT];
+#pragma unroll
+        for (int t = 0; t < NT; t++) acc[t] = (f32x4_t){0.f, 0.f, 0.f, 0.f};
+        f32x4_t wreg[NT];
+        xraw_t xcur[XS];
+        __syncthreads();  // the buffers of the previous pass are no longer read
+        load_w(c0, 0, wreg);
+        float mreg = load_m(0);
+#pragma unroll
+        for (int t = 0; t < NT; t++) *(f32x4_t*)&s_w[0][s_slot + t * kWave * 4] = wreg[t];
+        if (tid < kProjChunk) s_m[0][tid] = mreg;
+        __syncthreads();
+        for (int jc = 0; jc < nch; jc++) {
+            const int cur = jc & 1;
+            const int jn = jc + 1 < nch ? jc + 1 : jc;  // past the last chunk: loaded again, never used
+            load_x(jc, xcur);  // this chunk's rows first (the other waves of the SIMD cover their latency), then the next chunk's directions
+            load_w(c0, jn, wreg);
+            mreg = load_m(jn);
+            if (tile < ntiles) {
+#pragma unroll
+                for (int s_ = 0; s_ < XS; s_++) {
+                    const int64_t ch = (int64_t)jc * kProjChunk + 16 * s_ + 4 * g;
+                    float e[4];
+                    if (sizeof(T) == 4) {
+                        e[0] = __uint_as_float(xcur[s_][0]), e[1] = __uint_as_float(xcur[s_][1]);
+                        e[2] = __uint_as_float(xcur[s_][sizeof(T) == 4 ? 2 : 0]), e[3] = __uint_as_float(xcur[s_][sizeof(T) == 4 ? 3 : 1]);
+                    } else {
+                        e[0] = __uint_as_float(xcur[s_][0] << 16), e[1] = __uint_as_float(xcur[s_][0] & 0xFFFF0000u);
+                        e[2] = __uint_as_float(xcur[s_][1] << 16), e[3] = __uint_as_float(xcur[s_][1] & 0xFFFF0000u);
+                    }
+                    const f32x4_t mv = *(const f32x4_t*)&s_m[cur][16 * s_ + 4 * g];
+                    const bool in = ch < D;  // D is a multiple of 4: a group is inside the row or wholly outside
+                    const f32x4_t xv = (f32x4_t){in ? e[0] - mv.x : 0.f, in ? e[1] - mv.y : 0.f, in ? e[2] - mv.z : 0.f,
+                                                 in ? e[3] - mv.w : 0.f};
+#pragma unroll
+                    for (int t = 0; t < NT; t++) {
+                        const f32x4_t wv = *(const f32x4_t*)&s_w[cur][(((s_ * NT + t) * kWave) + lane) * 4];
+                        acc[t] = __builtin_amdgcn_mfma_f32_16x16x4f32(wv.x, xv.x, acc[t], 0, 0, 0);
+                        acc[t] = __builtin_amdgcn_mfma_f32_16x16x4f32(wv.y, xv.y, acc[t], 0, 0, 0);
+                        acc[t] = __builtin_amdgcn_mfma_f32_16x16x4f32(wv.z, xv.z, acc[t], 0, 0, 0);
+                        acc[t] = __builtin_amdgcn_mfma_f32_16x16x4f32(wv.w, xv.w, acc[t], 0, 0, 0);
+                    }
+                }
+            }
+            // the other buffer was last read one chunk ago, before the barrier that ended that chunk
+#pragma unroll
+            for (int t = 0; t < NT; t++) *(f32x4_t*)&s_w[cur ^ 1][s_slot + t * kWave * 4] = wreg[t];
+            if (tid < kProjChunk) s_m[cur ^ 1][tid] = mreg;
+            __syncthreads();
+        }
+        if (row < N) {
+#pragma unroll
+            for (int t = 0; t < NT; t++) {
+                const int c = c0 + 16 * t + 4 * g;
+                float* o = z + row * ldz + c;
+                if (c + 3 < ldz && ((ldz & 3) == 0)) {
+                    *(f32x4_t*)o = acc[t];
+                } else {
+                    if (c < ldz) o[0] = acc[t].x;
+                    if (c + 1 < ldz) o[1] = acc[t].y;
+                    if (c + 2 < ldz) o[2] = acc[t].z;
+                    if (c + 3 < ldz) o[3] = acc[t].w;
+                }
+            }
+        }
+    }
+}
+
 // ---- affine map by given labels ------------------------------------------------------------------
 // One wave per row.  WIDE: 16-byte loads and stores, all of a lane's requests for the row issued before the
 // first is used (rows of whole 16-byte groups, aligned bases); else one channel per lane and step.
@@ -492,8 +613,15 @@ cat_status pca_project_ld(const void* lq, int64_t N, int64_t D, int32_t p, cat_d
     if (!lq || !mean || !components || !z) return set_error(CAT_ERR_INVALID_ARG, "cat_pca_project: null argument");
     const int64_t rows_per_block = kProjWaves * 16;
     dim3 g((unsigned)((N + rows_per_block - 1) / rows_per_block)), b(kProjWaves * kWave);
-#define CAT_PROJ(T, NT) \
-    hipLaunchKernelGGL((k_pca_project<T, NT>), g, b, 0, st, (const T*)lq, N, D, p, mean, components, z, ldz)
+    // rows of whole 16-byte groups (bf16: 8-byte) on aligned bases take the software-pipelined kernel
+    const bool pipe = (D & 3) == 0 && (((uintptr_t)lq | (uintptr_t)components | (uintptr_t)mean) & 15u) == 0;
+#define CAT_PROJ(T, NT)                                                                                                         \
+    do {                                                                                                                        \
+        if (pipe)                                                                                                               \
+            hipLaunchKernelGGL((k_pca_project_pipe<T, NT>), g, b, 0, st, (const T*)lq, N, D, p, mean, components, z, ldz);      \
+        else                                                                                                                    \
+            hipLaunchKernelGGL((k_pca_project<T, NT>), g, b, 0, st, (const T*)lq, N, D, p, mean, components, z, ldz);           \
+    } while (0)
     if (dt == CAT_F32) {
         if (p <= 16) CAT_PROJ(float, 1); else if (p <= 32) CAT_PROJ(float, 2); else CAT_PROJ(float, 4);
     } else {
