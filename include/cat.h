@@ -202,6 +202,8 @@ cat_status cat_init_indices(int64_t N, int32_t K, uint64_t seed, int64_t *idx_ou
  *                  clustering) out, nullable.
  *   cat_apply_pca  scores -> nearest centroid in score space -> affine map of the full vector with
  *                  the alpha-blend.  corrected out (may not alias lq); assignments out, nullable.
+ *                  One kernel when D is a multiple of 4, p <= 64 and K <= 256 (the scores never leave
+ *                  the chip); the three steps one after the other otherwise, with identical results.
  */
 size_t cat_fit_pca_workspace_bytes(int64_t N, int64_t D, int32_t K, int32_t p, cat_dtype dt);
 cat_status cat_fit_pca(const void *lq, const void *fp, int64_t N, int64_t D, int32_t K, int32_t p,

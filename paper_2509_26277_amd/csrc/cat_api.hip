@@ -626,6 +626,10 @@ cat_status cat_apply_pca(const void* lq, int64_t N, int64_t D, int32_t K, int32_
     PcaApplyWs w = carve_pca_apply(workspace, N, K, p);
     CAT_TRY(check_ws("cat_apply_pca", workspace, workspace_bytes, w.bytes));
     hipStream_t st = (hipStream_t)hip_stream;
+    // one kernel where the shape allows it (not with the streaming path forced: that selects the step-by-step sequence)
+    if (g_path.load() != CAT_PATH_STREAM && apply_pca_fused_supported(lq, D, K, p, mean, components, gamma, beta, corrected))
+        return launch_apply_pca_fused(lq, N, D, K, p, dt, mean, components, centroids_z, gamma, beta, alpha, corrected,
+                                      assignments, st);
     int32_t* a = assignments ? assignments : w.assign;
     const int32_t pp = pad4(p);
     CAT_TRY(pca_project_ld(lq, N, D, p, dt, mean, components, w.z, pp, st));

@@ -118,6 +118,12 @@ cat_status launch_fill_u64(unsigned long long* p, int64_t n, unsigned long long 
 // dst (rows x dst_ld) <- the first `cols` columns of src (rows x src_ld), zeros in the columns from `cols` on
 cat_status launch_copy_cols(const float* src, int64_t rows, int32_t src_ld, float* dst, int32_t dst_ld, int32_t cols,
                             hipStream_t st);
+// inference with the PCA front-end in one kernel (cat_pca.hip), where the shape allows it
+bool apply_pca_fused_supported(const void* lq, int64_t D, int32_t K, int32_t p, const float* mean, const float* components,
+                               const float* gamma, const float* beta, const void* corrected);
+cat_status launch_apply_pca_fused(const void* lq, int64_t N, int64_t D, int32_t K, int32_t p, cat_dtype dt, const float* mean,
+                                  const float* components, const float* centroids_z, const float* gamma, const float* beta,
+                                  float alpha, void* corrected, int32_t* assignments, hipStream_t st);
 // best-of-several bookkeeping on the device: state[0] = 1 if `cur` beats `best` (or run == 0), state[1] = best run;
 // finals (nullable) receives cur at index run.  launch_copy_words_if copies only while *flag != 0.
 cat_status launch_keep_best(const double* cur, double* best, int32_t* state, int32_t run, double* finals, hipStream_t st);

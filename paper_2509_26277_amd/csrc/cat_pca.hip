@@ -371,11 +371,25 @@ __global__ __launch_bounds__(kProjWaves * kWave) void k_pca_project(const T* __r
 // already on their way into registers; they then go into the LDS buffer chunk j does not use, and one barrier per
 // chunk separates the two.  Registers are capped at 128 so that two workgroups share a CU (four waves per SIMD).  Every load is unconditional (a position past the end is
 // clamped to a valid one and its value dropped), so none is waited for where it is issued.
-template <typename T, int NT>
+//
+// FUSED: Algorithm 2 with the PCA front-end in one kernel (p <= 16 NT, K <= 256).  The scores of a tile stay
+// in registers; the centroids of score space go into the LDS the directions no longer need; every row takes the
+// centroid of smallest squared distance (direct form, doubles, lowest index on ties), and the wave then reads its
+// 16 rows once more, four at a time with 16-byte (bf16: 8-byte) loads, and writes the blended affine map.
+struct ProjFuse {
+    const float* cz;     // K x p centroids in score space
+    const float* gamma;  // K x D
+    const float* beta;
+    void* out;           // N x D of the row type
+    int32_t* assign;     // nullable
+    int32_t K;
+    float alpha;
+};
+template <typename T, int NT, bool FUSED>
 __global__ __launch_bounds__(kProjWaves * kWave, 4) void k_pca_project_pipe(const T* __restrict__ x, int64_t N, int64_t D, int32_t p,
                                                                          const float* __restrict__ mean,
                                                                          const float* __restrict__ comps, float* __restrict__ z,
-                                                                         int32_t ldz) {
+                                                                         int32_t ldz, const ProjFuse f) {
     constexpr int SW = (kProjChunk / 16) * NT * kWave * 4;  // floats of directions per chunk
     constexpr int XS = kProjChunk / 16;                     // 16-channel steps per chunk
     __shared__ __align__(16) float s_w[2][SW];
@@ -469,18 +483,104 @@ __global__ __launch_bounds__(kProjWaves * kWave, 4) void k_pca_project_pipe(cons
             if (tid < kProjChunk) s_m[cur ^ 1][tid] = mreg;
             __syncthreads();
         }
-        if (row < N) {
+        if (!FUSED) {
+            if (row < N) {
+#pragma unroll
+                for (int t = 0; t < NT; t++) {
+                    const int c = c0 + 16 * t + 4 * g;
+                    float* o = z + row * ldz + c;
+                    if (c + 3 < ldz && ((ldz & 3) == 0)) {
+                        *(f32x4_t*)o = acc[t];
+                    } else {
+                        if (c < ldz) o[0] = acc[t].x;
+                        if (c + 1 < ldz) o[1] = acc[t].y;
+                        if (c + 2 < ldz) o[2] = acc[t].z;
+                        if (c + 3 < ldz) o[3] = acc[t].w;
+                    }
+                }
+            }
+            continue;
+        }
+        // ---- FUSED (one pass: c0 = 0).  Centroids of score space into LDS, padded to 16 NT columns of zeros.
+        constexpr int CW = 16 * NT;
+        float* s_cz = &s_w[0][0];  // 2 SW floats: room for 256 centroids; the last barrier of the loop has passed
+        for (int i = tid; i < f.K * CW; i += kProjWaves * kWave) {
+            const int k = i / CW, c = i - k * CW;
+            s_cz[i] = c < p ? f.cz[(int64_t)k * p + c] : 0.f;
+        }
+        __syncthreads();
+        if (tile >= ntiles) continue;
+        double dbest = __builtin_inf();
+        int kbest = 0;
+        for (int k = 0; k < f.K; k++) {
+            double d = 0.0;
 #pragma unroll
             for (int t = 0; t < NT; t++) {
-                const int c = c0 + 16 * t + 4 * g;
-                float* o = z + row * ldz + c;
-                if (c + 3 < ldz && ((ldz & 3) == 0)) {
-                    *(f32x4_t*)o = acc[t];
-                } else {
-                    if (c < ldz) o[0] = acc[t].x;
-                    if (c + 1 < ldz) o[1] = acc[t].y;
-                    if (c + 2 < ldz) o[2] = acc[t].z;
-                    if (c + 3 < ldz) o[3] = acc[t].w;
+                const f32x4_t cv = *(const f32x4_t*)&s_cz[k * CW + 16 * t + 4 * g];
+                const double d0 = (double)acc[t].x - (double)cv.x, d1 = (double)acc[t].y - (double)cv.y;
+                const double d2 = (double)acc[t].z - (double)cv.z, d3 = (double)acc[t].w - (double)cv.w;
+                d = fma(d0, d0, d);
+                d = fma(d1, d1, d);
+                d = fma(d2, d2, d);
+                d = fma(d3, d3, d);
+            }
+            d += __shfl_xor(d, 16, kWave);  // the four lanes of a row end with the same bits (addition commutes)
+            d += __shfl_xor(d, 32, kWave);
+            if (d < dbest) {
+                dbest = d;
+                kbest = k;
+            }
+        }
+        if (f.assign && g == 0 && row < N) f.assign[row] = kbest;
+        // the affine map of the 16 rows, four rows at a time: the whole wave on each row
+        T* outp = (T*)f.out;
+        const int64_t tile_row0 = tile * 16;
+        for (int r0 = 0; r0 < 16; r0 += 4) {
+            if (tile_row0 + r0 >= N) break;  // wave-uniform
+            int a[4];
+            int64_t rr[4];
+            bool ok[4];
+#pragma unroll
+            for (int u = 0; u < 4; u++) {
+                a[u] = __builtin_amdgcn_readlane(kbest, r0 + u);
+                ok[u] = tile_row0 + r0 + u < N;
+                rr[u] = ok[u] ? tile_row0 + r0 + u : N - 1;  // past the end: the last row again, not stored
+            }
+            for (int64_t j = (int64_t)lane * 4; j < D; j += kWave * 4) {
+                xraw_t xv[4];
+                f32x4_t gv[4], bv[4];
+#pragma unroll
+                for (int u = 0; u < 4; u++) {
+                    xv[u] = *(const xraw_t*)(x + rr[u] * D + j);
+                    gv[u] = *(const f32x4_t*)(f.gamma + (int64_t)a[u] * D + j);
+                    bv[u] = *(const f32x4_t*)(f.beta + (int64_t)a[u] * D + j);
+                }
+#pragma unroll
+                for (int u = 0; u < 4; u++) {
+                    float e[4], r[4];
+                    if (sizeof(T) == 4) {
+                        e[0] = __uint_as_float(xv[u][0]), e[1] = __uint_as_float(xv[u][1]);
+                        e[2] = __uint_as_float(xv[u][sizeof(T) == 4 ? 2 : 0]), e[3] = __uint_as_float(xv[u][sizeof(T) == 4 ? 3 : 1]);
+                    } else {
+                        e[0] = __uint_as_float(xv[u][0] << 16), e[1] = __uint_as_float(xv[u][0] & 0xFFFF0000u);
+                        e[2] = __uint_as_float(xv[u][1] << 16), e[3] = __uint_as_float(xv[u][1] & 0xFFFF0000u);
+                    }
+#pragma unroll
+                    for (int c = 0; c < 4; c++) {
+                        const float gg = 1.f + f.alpha * (gv[u][c] - 1.f), bb = f.alpha * bv[u][c];
+                        r[c] = fmaf(gg, e[c], bb);
+                    }
+                    if (ok[u]) {
+                        xraw_t o;
+                        if (sizeof(T) == 4) {
+                            o[0] = __float_as_uint(r[0]), o[1] = __float_as_uint(r[1]);
+                            o[sizeof(T) == 4 ? 2 : 0] = __float_as_uint(r[2]), o[sizeof(T) == 4 ? 3 : 1] = __float_as_uint(r[3]);
+                        } else {
+                            o[0] = (uint32_t)f32_to_bf16(r[0]) | ((uint32_t)f32_to_bf16(r[1]) << 16);
+                            o[1] = (uint32_t)f32_to_bf16(r[2]) | ((uint32_t)f32_to_bf16(r[3]) << 16);
+                        }
+                        *(xraw_t*)(outp + rr[u] * D + j) = o;
+                    }
                 }
             }
         }
@@ -618,7 +718,8 @@ cat_status pca_project_ld(const void* lq, int64_t N, int64_t D, int32_t p, cat_d
 #define CAT_PROJ(T, NT)                                                                                                         \
     do {                                                                                                                        \
         if (pipe)                                                                                                               \
-            hipLaunchKernelGGL((k_pca_project_pipe<T, NT>), g, b, 0, st, (const T*)lq, N, D, p, mean, components, z, ldz);      \
+            hipLaunchKernelGGL((k_pca_project_pipe<T, NT, false>), g, b, 0, st, (const T*)lq, N, D, p, mean, components, z, ldz, \
+                               ProjFuse{});                                                                                    \
         else                                                                                                                    \
             hipLaunchKernelGGL((k_pca_project<T, NT>), g, b, 0, st, (const T*)lq, N, D, p, mean, components, z, ldz);           \
     } while (0)
@@ -629,6 +730,33 @@ cat_status pca_project_ld(const void* lq, int64_t N, int64_t D, int32_t p, cat_d
     }
 #undef CAT_PROJ
     CAT_LAUNCH_CHECK("k_pca_project");
+    return CAT_OK;
+}
+
+// Algorithm 2 with the PCA front-end in one kernel, where the shape allows it (see k_pca_project_pipe).
+bool apply_pca_fused_supported(const void* lq, int64_t D, int32_t K, int32_t p, const float* mean, const float* components,
+                               const float* gamma, const float* beta, const void* corrected) {
+    const uintptr_t bases = (uintptr_t)lq | (uintptr_t)components | (uintptr_t)mean | (uintptr_t)gamma | (uintptr_t)beta |
+                            (uintptr_t)corrected;
+    return (D & 3) == 0 && (bases & 15u) == 0 && p <= 64 && K <= 256;
+}
+cat_status launch_apply_pca_fused(const void* lq, int64_t N, int64_t D, int32_t K, int32_t p, cat_dtype dt, const float* mean,
+                                  const float* components, const float* centroids_z, const float* gamma, const float* beta,
+                                  float alpha, void* corrected, int32_t* assignments, hipStream_t st) {
+    if (!apply_pca_fused_supported(lq, D, K, p, mean, components, gamma, beta, corrected))
+        return set_error(CAT_ERR_UNSUPPORTED, "fused PCA inference does not take D=%lld K=%d p=%d", (long long)D, (int)K, (int)p);
+    ProjFuse f{centroids_z, gamma, beta, corrected, assignments, K, alpha};
+    const int64_t rows_per_block = kProjWaves * 16;
+    dim3 g((unsigned)((N + rows_per_block - 1) / rows_per_block)), b(kProjWaves * kWave);
+#define CAT_FUSE(T, NT) \
+    hipLaunchKernelGGL((k_pca_project_pipe<T, NT, true>), g, b, 0, st, (const T*)lq, N, D, p, mean, components, nullptr, 0, f)
+    if (dt == CAT_F32) {
+        if (p <= 16) CAT_FUSE(float, 1); else if (p <= 32) CAT_FUSE(float, 2); else CAT_FUSE(float, 4);
+    } else {
+        if (p <= 16) CAT_FUSE(bf16_t, 1); else if (p <= 32) CAT_FUSE(bf16_t, 2); else CAT_FUSE(bf16_t, 4);
+    }
+#undef CAT_FUSE
+    CAT_LAUNCH_CHECK("k_pca_project_pipe (fused inference)");
     return CAT_OK;
 }
 

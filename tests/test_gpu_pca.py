@@ -186,3 +186,26 @@ def test_single_call_pipeline_equals_its_steps_and_the_oracle(name, n, p):
         check_values(host_matrix(out), want, RTOL[dt], f"corrected alpha={alpha}")
     out2, none = cat_apply_pca(lq, r["mean"], r["components"], r["centroids_z"], r["gamma"], r["beta"], want_assignments=False)
     assert none is None and torch.equal(out2, cat_apply_pca(lq, r["mean"], r["components"], r["centroids_z"], r["gamma"], r["beta"])[0])
+
+
+@pytest.mark.parametrize("name,n,p", [("cfg2", 2000, 50), ("cfg2", 777, 20), ("cfg4", 1500, 7), ("cfg1", 4096, 64)])
+def test_fused_inference_equals_the_step_sequence(name, n, p):
+    """cat_apply_pca runs as one kernel where the shape allows it; with the streaming path selected it runs
+    projection, assignment in score space and the labelled affine map one after the other.  Same scores (the same
+    MFMA sequence), the same exact nearest centroid, the same fp32 affine map: identical outputs."""
+    from paper_2509_26277_amd import cat_apply_pca, cat_fit_pca
+    w = workloads.make(name, n_rows=n)
+    K, dt = w["K"], w["dtype"]
+    lq, fp = dev_matrix(w["lq"], dt), dev_matrix(w["fp"], dt)
+    r = cat_fit_pca(lq, fp, K, p, 3, seed=w["seed"])
+    args = (lq, r["mean"], r["components"], r["centroids_z"], r["gamma"], r["beta"])
+    try:
+        fused, a_fused = cat_apply_pca(*args, alpha=0.7)
+        binding.select_path(binding.CAT_PATH_STREAM)
+        steps, a_steps = cat_apply_pca(*args, alpha=0.7)
+    finally:
+        binding.select_path(binding.CAT_PATH_AUTO)
+    assert torch.equal(a_fused, a_steps)
+    assert torch.equal(fused, steps)
+    # and the assignments are those of the fit on the same rows
+    assert torch.equal(a_fused, r["assignments"])
