@@ -92,3 +92,43 @@ def test_bad_arguments_are_refused():
         cat_fit_restarts(x, x, 2, 1, restarts=2, seeding=7)
     with pytest.raises(CatError):
         cat_fit_restarts(x, x, 2, 1, restarts=2, workspace=torch.empty(256, dtype=torch.uint8, device="cuda"))
+
+
+def test_seeding_restarts_and_sweep_capture_into_a_hip_graph_and_replay():
+    """The best-of-several fit selects on the device and the sweep leaves its sums in per-workgroup records, so the
+    whole sequence (D^2-weighted seeding, several runs, Top-1 of the FP rows, sweep over alpha) has no host round
+    trip, allocation or memset node: captured once, every replay reproduces the eager result."""
+    from paper_2509_26277_amd import cat_alpha_sweep, cat_top1
+    x, y = _mixture(11, 4096, 64, 6, "f32")
+    xd, yd = dev_matrix(x, "f32"), dev_matrix(y, "f32")
+    grid = [0.25, 0.5, 0.75, 1.0]
+
+    def run():
+        r = cat_fit_restarts(xd, yd, 6, 5, seed=2, restarts=3, seeding=CAT_SEED_KMEANSPP)
+        lab = cat_top1(yd)
+        s = cat_alpha_sweep(xd, r["assignments"], r["gamma"], r["beta"], grid, fp=yd, labels=lab, want_top1=True)
+        return r, s
+
+    r0, s0 = run()
+    ref_r = {k: v.clone() for k, v in r0.items()}
+    ref_s = {k: v.clone() for k, v in s0.items()}
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        run()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        r, s = run()
+    for _ in range(3):
+        for t in list(r.values()) + list(s.values()):
+            t.zero_()  # eager work between replays; also proves the replay rewrites every output
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        for k in ("assignments", "counts", "best_run", "centroids", "gamma", "beta"):
+            assert torch.equal(r[k], ref_r[k]), k
+        torch.testing.assert_close(r["final_inertia"], ref_r["final_inertia"], rtol=1e-12, atol=0)
+        for k in ("hits", "top1", "sq_err", "moments"):
+            assert torch.equal(s[k], ref_s[k]), k  # fixed summation order: bit for bit
