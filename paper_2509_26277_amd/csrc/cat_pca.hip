@@ -14,6 +14,7 @@ namespace cat {
 typedef __attribute__((ext_vector_type(4))) float f32x4_t;
 
 constexpr int kPcaMaxD = 2048;  // eigen workspace is 2 (D+1)^2 doubles; the selection kernel keeps D values in LDS
+static_assert(kPcaMaxD % 2 == 0 && kPcaMaxD <= 8 * 256, "a Jacobi step keeps a row in 8 x 256 registers at most");
 
 // ---- column sums ---------------------------------------------------------------------------------
 template <typename T>
@@ -112,6 +113,7 @@ __global__ void k_pca_mirror(double* __restrict__ W, int64_t D, int64_t Dp) {
 // matrix: row i of Vt is the eigenvector, w_i . vt_i its eigenvalue.  One step rotates Dp / 2 disjoint
 // pairs chosen by the round-robin (tournament) schedule; Dp - 1 steps visit every pair once (a sweep).
 // Rows are contiguous, so every access is coalesced.  One workgroup per pair.
+template <int NI>  // elements per thread and row: Dp <= 256 NI
 __global__ __launch_bounds__(256) void k_pca_jacobi_step(double* __restrict__ W, double* __restrict__ Vt, int32_t Dp, int32_t step) {
     __shared__ double s_red[3][4];
     __shared__ double s_cs[2];
@@ -126,12 +128,29 @@ __global__ __launch_bounds__(256) void k_pca_jacobi_step(double* __restrict__ W,
     }
     double* wp = W + (int64_t)p * Dp;
     double* wq = W + (int64_t)q * Dp;
+    double* vp = Vt + (int64_t)p * Dp;
+    double* vq = Vt + (int64_t)q * Dp;
+    // The four rows are requested at once and stay in registers (NI elements per thread and row), so the step
+    // has one memory latency in front of the reduction instead of one before and one after it.
+    constexpr int MAXI = NI;
+    double x[MAXI], y[MAXI], u[MAXI], v[MAXI];
+#pragma unroll
+    for (int i = 0; i < MAXI; i++) {
+        const int j = threadIdx.x + i * 256;
+        const int jc = j < Dp ? j : 0;  // past the end: element 0 again, dropped below
+        x[i] = wp[jc];
+        y[i] = wq[jc];
+        u[i] = vp[jc];
+        v[i] = vq[jc];
+    }
     double a = 0.0, b = 0.0, g = 0.0;
-    for (int j = threadIdx.x; j < Dp; j += blockDim.x) {
-        const double x = wp[j], y = wq[j];
-        a = fma(x, x, a);
-        b = fma(y, y, b);
-        g = fma(x, y, g);
+#pragma unroll
+    for (int i = 0; i < MAXI; i++) {
+        if (threadIdx.x + i * 256 < Dp) {
+            a = fma(x[i], x[i], a);
+            b = fma(y[i], y[i], b);
+            g = fma(x[i], y[i], g);
+        }
     }
     a = wave_sum(a);
     b = wave_sum(b);
@@ -160,15 +179,15 @@ __global__ __launch_bounds__(256) void k_pca_jacobi_step(double* __restrict__ W,
     __syncthreads();
     const double c = s_cs[0], s = s_cs[1];
     if (s == 0.0) return;  // uniform
-    double* vp = Vt + (int64_t)p * Dp;
-    double* vq = Vt + (int64_t)q * Dp;
-    for (int j = threadIdx.x; j < Dp; j += blockDim.x) {
-        const double x = wp[j], y = wq[j];
-        wp[j] = c * x - s * y;
-        wq[j] = s * x + c * y;
-        const double u = vp[j], v = vq[j];
-        vp[j] = c * u - s * v;
-        vq[j] = s * u + c * v;
+#pragma unroll
+    for (int i = 0; i < MAXI; i++) {
+        const int j = threadIdx.x + i * 256;
+        if (j < Dp) {
+            wp[j] = c * x[i] - s * y[i];
+            wq[j] = s * x[i] + c * y[i];
+            vp[j] = c * u[i] - s * v[i];
+            vq[j] = s * u[i] + c * v[i];
+        }
     }
 }
 
@@ -818,7 +837,17 @@ cat_status cat_pca_fit(const void* lq, int64_t N, int64_t D, int32_t p, cat_dtyp
     if (Dp >= 2) {
         for (int sw = 0; sw < sweeps; sw++)
             for (int step = 0; step < Dp - 1; step++) {
-                hipLaunchKernelGGL(k_pca_jacobi_step, dim3((unsigned)(Dp / 2)), dim3(256), 0, st, w.W, w.Vt, (int32_t)Dp, step);
+                const dim3 jg((unsigned)(Dp / 2)), jb(256);
+                switch ((int)((Dp + 255) / 256)) {
+                    case 1: hipLaunchKernelGGL(k_pca_jacobi_step<1>, jg, jb, 0, st, w.W, w.Vt, (int32_t)Dp, step); break;
+                    case 2: hipLaunchKernelGGL(k_pca_jacobi_step<2>, jg, jb, 0, st, w.W, w.Vt, (int32_t)Dp, step); break;
+                    case 3: hipLaunchKernelGGL(k_pca_jacobi_step<3>, jg, jb, 0, st, w.W, w.Vt, (int32_t)Dp, step); break;
+                    case 4: hipLaunchKernelGGL(k_pca_jacobi_step<4>, jg, jb, 0, st, w.W, w.Vt, (int32_t)Dp, step); break;
+                    case 5: hipLaunchKernelGGL(k_pca_jacobi_step<5>, jg, jb, 0, st, w.W, w.Vt, (int32_t)Dp, step); break;
+                    case 6: hipLaunchKernelGGL(k_pca_jacobi_step<6>, jg, jb, 0, st, w.W, w.Vt, (int32_t)Dp, step); break;
+                    case 7: hipLaunchKernelGGL(k_pca_jacobi_step<7>, jg, jb, 0, st, w.W, w.Vt, (int32_t)Dp, step); break;
+                    default: hipLaunchKernelGGL(k_pca_jacobi_step<8>, jg, jb, 0, st, w.W, w.Vt, (int32_t)Dp, step); break;
+                }
                 CAT_LAUNCH_CHECK("k_pca_jacobi_step");
             }
     }
