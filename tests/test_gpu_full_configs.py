@@ -127,3 +127,57 @@ def test_full_inference_stream_sampled():
     check_values(cent[:, cols], c_o, RTOL["f32"], "cfg5 fit, centroids")
     np.testing.assert_allclose(host_matrix(r["gamma"]), 1.0, atol=1e-5)
     np.testing.assert_allclose(host_matrix(r["beta"]), 0.0, atol=1e-4)
+
+
+def test_full_pca_front_end_on_the_logit_workload():
+    """The PCA front-end at cfg2's full size with the paper's 50 components, as bench.py runs it.  The oracle's
+    covariance (a plain triple loop) does not finish at this size, so: the eigenpairs are checked against their
+    definition without forming the covariance (C v = X_c^T (X_c v) / N with numpy's matrix product in double), their
+    values against LAPACK on the covariance numpy's product gives, and the oracle is called on what it can
+    compute one by one: scores, assignments in score space and corrected rows of sampled rows."""
+    from paper_2509_26277_amd import cat_apply_pca, cat_fit_pca
+    w = workloads.make("cfg2")
+    N, D, K, p = w["N"], w["D"], w["K"], 50
+    lq, fp = dev_matrix(w["lq"], "f32"), dev_matrix(w["fp"], "f32")
+    r = cat_fit_pca(lq, fp, K, p, 8, seed=w["seed"])
+    mean, comps = host_matrix(r["mean"]), host_matrix(r["components"])
+    x64 = w["lq"].astype(np.float64)
+    np.testing.assert_allclose(mean, x64.mean(axis=0), rtol=1e-6, atol=1e-6)
+    xc = x64 - x64.mean(axis=0)
+    # unit, mutually orthogonal directions with the shared sign convention
+    gram = comps @ comps.T
+    np.testing.assert_allclose(gram, np.eye(p), atol=1e-6)
+    for c in range(p):
+        assert comps[c, np.argmax(np.abs(comps[c]))] > 0
+    # eigen equation, and the values against LAPACK
+    cv = xc.T @ (xc @ comps.T) / N                      # D x p: C v for every direction
+    lam = (cv * comps.T).sum(axis=0)                    # Rayleigh quotients
+    resid = np.linalg.norm(cv - comps.T * lam, axis=0)
+    assert (resid <= 1e-5 * lam[0]).all(), resid.max() / lam[0]
+    evals = np.linalg.eigvalsh(xc.T @ xc / N)[::-1][:p]
+    np.testing.assert_allclose(lam, evals, rtol=1e-6)
+    assert (np.diff(lam) <= 1e-9 * lam[0]).all()
+    # sampled rows through the oracle, teacher-forced on the library's mean, directions and score centroids
+    rng = np.random.default_rng(31)
+    rows = np.unique(np.concatenate([rng.choice(N, 4096, replace=False), np.arange(40), np.arange(N - 40, N)]))
+    z_o = oracle.pca_project(w["lq"][rows], mean, comps)
+    cz = host_matrix(r["centroids_z"])
+    a_o, d1, d2 = oracle.assign(z_o.astype(np.float32), cz, want_distances=True)
+    out, a = cat_apply_pca(lq, r["mean"], r["components"], r["centroids_z"], r["gamma"], r["beta"], alpha=0.6)
+    a_g = a.cpu().numpy()
+    assert (a_g == r["assignments"].cpu().numpy()).all()  # inference reproduces the fitted partition
+    # the scores the decision was taken on differ from the oracle's by fp32 rounding: rows whose two nearest
+    # centroids are closer than that are exempt
+    differ = a_g[rows] != a_o
+    assert ((d2 - d1)[differ] <= 1e-4 * d2[differ]).all() and differ.mean() < 1e-3
+    g, b = host_matrix(r["gamma"]), host_matrix(r["beta"])
+    xs = x64[rows]
+    want = xs + 0.6 * ((g[a_g[rows]] * xs + b[a_g[rows]]) - xs)
+    check_values(host_matrix(out[torch.from_numpy(rows).cuda()]), want, RTOL["f32"], "cfg2 corrected with PCA")
+    # the affine fit on the library's partition, all rows, sampled channels
+    cols = np.sort(rng.choice(D, 6, replace=False))
+    g_o, b_o, n_o = oracle.affine(np.ascontiguousarray(w["lq"][:, cols]), np.ascontiguousarray(w["fp"][:, cols]), a_g, K)
+    assert r["counts"].cpu().numpy().tolist() == n_o.tolist()
+    check_values(g[:, cols], g_o, RTOL["f32"], "gamma")
+    check_values(b[:, cols], b_o, RTOL["f32"], "beta",
+                 beta_scale(w["lq"][:, cols], w["fp"][:, cols], a_g, K, g_o))
