@@ -449,12 +449,19 @@ cat_status tile_assign(const void* lq, cat_dtype dt, int64_t N, int64_t D, int32
     const TileMode mode = gamma ? TILE_APPLY : TILE_ASSIGN;
     TileCfg c = tile_config(mode, D, K, dt);
     if (!c.ok) return set_error(CAT_ERR_UNSUPPORTED, "tile kernels do not fit D=%lld K=%d", (long long)D, (int)K);
-    cat_status s = launch_copy_words(cent, ws.cent, (int64_t)K * D, st);
-    if (s != CAT_OK) return s;
-    s = launch_prep(dt, ws.cent, nullptr, nullptr, nullptr, nullptr, D, K, c, ws, nullptr, nullptr, st);
+    // The preparation only reads the centroids here (no sums to fold), and the exact re-rank reads them with
+    // 16-byte loads: the caller's array serves both as it is when it is aligned, else a copy in the workspace.
+    const float* cw = cent;
+    cat_status s = CAT_OK;
+    if (((uintptr_t)cent & 15u) != 0) {
+        s = launch_copy_words(cent, ws.cent, (int64_t)K * D, st);
+        if (s != CAT_OK) return s;
+        cw = ws.cent;
+    }
+    s = launch_prep(dt, const_cast<float*>(cw), nullptr, nullptr, nullptr, nullptr, D, K, c, ws, nullptr, nullptr, st);
     if (s != CAT_OK) return s;
     TileParams p = base_params(lq, N, D, K, c, ws, dt);
-    p.cent = ws.cent;
+    p.cent = cw;
     p.assign = assign;
     p.counts = counts;
     p.inertia = inertia;
