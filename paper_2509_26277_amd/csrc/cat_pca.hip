@@ -110,16 +110,23 @@ __global__ void k_pca_mirror(double* __restrict__ W, int64_t D, int64_t Dp) {
 // ---- one-sided Jacobi on the rows of W (= the symmetric matrix at the start) ------------------------
 // A rotation of rows p and q makes them orthogonal; the same rotation is applied to Vt.  When all rows
 // are orthogonal, W = Lambda Q^T and Vt = Q^T for the eigendecomposition Q Lambda Q^T of the start
-// matrix: row i of Vt is the eigenvector, w_i . vt_i its eigenvalue.  One step rotates Dp / 2 disjoint
-// pairs chosen by the round-robin (tournament) schedule; Dp - 1 steps visit every pair once (a sweep).
-// Rows are contiguous, so every access is coalesced.  One workgroup per pair.
+// matrix: row i of Vt is the eigenvector, w_i . vt_i its eigenvalue.  A sweep visits every pair of rows
+// once; disjoint pairs are rotated side by side.  Rows are contiguous, so every access is coalesced.
+//
+// k_pca_jacobi_step: one workgroup per pair, Dp / 2 pairs per launch.  With step >= 0 the pairs are
+// those of step `step` of the round-robin (tournament) schedule over the rows (Dp - 1 steps make a sweep);
+// with step < 0 they are the neighbours (2k, 2k + 1), which is how the sweeps below use it (the pairs
+// inside the blocks of k_pca_jacobi_block).
 template <int NI>  // elements per thread and row: Dp <= 256 NI
 __global__ __launch_bounds__(256) void k_pca_jacobi_step(double* __restrict__ W, double* __restrict__ Vt, int32_t Dp, int32_t step) {
     __shared__ double s_red[3][4];
     __shared__ double s_cs[2];
     const int k = blockIdx.x, m = Dp - 1;
     int p, q;
-    if (k == 0) {
+    if (step < 0) {  // the two rows of every block of two (see k_pca_jacobi_quad)
+        p = 2 * k;
+        q = 2 * k + 1;
+    } else if (k == 0) {
         p = step;
         q = m;
     } else {
@@ -191,6 +198,123 @@ __global__ __launch_bounds__(256) void k_pca_jacobi_step(double* __restrict__ W,
     }
 }
 
+// BR tournament steps per launch.  Rows are taken in blocks of BR (2 or 4); a round of the tournament over the
+// Dp / BR blocks pairs block bp with block bq, and one workgroup holds the 2 BR rows of both matrices in
+// registers and rotates, in BR steps of BR disjoint pairs, every row of bp against every row of bq: one load and
+// one store of the rows for BR steps.  A launch is bound by its memory latencies (load, store and drain) and by
+// the barriers and square roots of a step, not by bandwidth or arithmetic, so fewer, longer launches shorten a
+// sweep.  A sweep: the pairs inside the blocks (k_pca_jacobi_step with step < 0 for the blocks of two, and for
+// BR = 4 this kernel with BR = 2 and round < 0 for the two halves of every block), then Dp / BR - 1 rounds.
+// Dp is a multiple of 2 BR.
+template <int NI, int BR>
+__global__ __launch_bounds__(256) void k_pca_jacobi_block(double* __restrict__ W, double* __restrict__ Vt, int32_t Dp, int32_t round) {
+    __shared__ double s_part[3 * BR][256];  // every thread's share of the three sums of each pair
+    __shared__ double s_cs[2 * BR];
+    const int k = blockIdx.x, m = Dp / BR - 1;  // tournament over Dp / BR blocks
+    int bp, bq;
+    if (round < 0) {  // neighbouring blocks: the two halves of a block of 2 BR rows
+        bp = 2 * k;
+        bq = 2 * k + 1;
+    } else if (k == 0) {
+        bp = round;
+        bq = m;
+    } else {
+        bp = (round + k) % m;
+        bq = (round - k + m) % m;
+    }
+    double w[2 * BR][NI], v[2 * BR][NI];
+#pragma unroll
+    for (int r = 0; r < 2 * BR; r++) {
+        const int64_t row = (int64_t)(r < BR ? bp : bq) * BR + (r % BR);
+#pragma unroll
+        for (int i = 0; i < NI; i++) {
+            const int j = threadIdx.x + i * 256;
+            const int jc = j < Dp ? j : 0;  // past the end: element 0 again, never used
+            w[r][i] = W[row * Dp + jc];
+            v[r][i] = Vt[row * Dp + jc];
+        }
+    }
+    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+    bool any = false;
+#pragma unroll
+    for (int st = 0; st < BR; st++) {
+        // step st: row i of bp against row (i + st) mod BR of bq, i = 0 .. BR - 1.  Every thread leaves its
+        // share of the sums in LDS; wave i adds the shares of pair i (256 values per sum: four per lane, then one
+        // butterfly), so a step costs three butterflies per wave instead of 3 BR, and two barriers.
+#pragma unroll
+        for (int i = 0; i < BR; i++) {
+            const int q = BR + (i + st) % BR;
+            double a = 0.0, b = 0.0, g = 0.0;
+#pragma unroll
+            for (int e = 0; e < NI; e++) {
+                if ((int)threadIdx.x + e * 256 < Dp) {
+                    a = fma(w[i][e], w[i][e], a);
+                    b = fma(w[q][e], w[q][e], b);
+                    g = fma(w[i][e], w[q][e], g);
+                }
+            }
+            s_part[3 * i][threadIdx.x] = a;
+            s_part[3 * i + 1][threadIdx.x] = b;
+            s_part[3 * i + 2][threadIdx.x] = g;
+        }
+        __syncthreads();
+        if (wave < BR) {  // BR <= 4 waves
+            const int i = wave;
+            double a = (s_part[3 * i][lane] + s_part[3 * i][lane + 64]) + (s_part[3 * i][lane + 128] + s_part[3 * i][lane + 192]);
+            double b = (s_part[3 * i + 1][lane] + s_part[3 * i + 1][lane + 64]) +
+                       (s_part[3 * i + 1][lane + 128] + s_part[3 * i + 1][lane + 192]);
+            double g = (s_part[3 * i + 2][lane] + s_part[3 * i + 2][lane + 64]) +
+                       (s_part[3 * i + 2][lane + 128] + s_part[3 * i + 2][lane + 192]);
+            a = wave_sum(a);
+            b = wave_sum(b);
+            g = wave_sum(g);
+            if (lane == 0) {
+                double c = 1.0, sn = 0.0;
+                if (fabs(g) > 1e-15 * sqrt(a * b) && g != 0.0) {
+                    const double zeta = (b - a) / (2.0 * g);
+                    const double t = (zeta >= 0.0 ? 1.0 : -1.0) / (fabs(zeta) + sqrt(1.0 + zeta * zeta));
+                    c = 1.0 / sqrt(1.0 + t * t);
+                    sn = c * t;
+                }
+                s_cs[2 * i] = c;
+                s_cs[2 * i + 1] = sn;
+            }
+        }
+        __syncthreads();
+        // (the shares of the next step are written after this barrier and read before the next one; the
+        // angles are read here, before the next step's first barrier, and written after it)
+#pragma unroll
+        for (int i = 0; i < BR; i++) {
+            const int q = BR + (i + st) % BR;
+            const double c = s_cs[2 * i], sn = s_cs[2 * i + 1];
+            if (sn != 0.0) {  // uniform
+                any = true;
+#pragma unroll
+                for (int e = 0; e < NI; e++) {
+                    const double x = w[i][e], y = w[q][e], u = v[i][e], z = v[q][e];
+                    w[i][e] = c * x - sn * y;
+                    w[q][e] = sn * x + c * y;
+                    v[i][e] = c * u - sn * z;
+                    v[q][e] = sn * u + c * z;
+                }
+            }
+        }
+    }
+    if (!any) return;  // uniform
+#pragma unroll
+    for (int r = 0; r < 2 * BR; r++) {
+        const int64_t row = (int64_t)(r < BR ? bp : bq) * BR + (r % BR);
+#pragma unroll
+        for (int i = 0; i < NI; i++) {
+            const int j = threadIdx.x + i * 256;
+            if (j < Dp) {
+                W[row * Dp + j] = w[r][i];
+                Vt[row * Dp + j] = v[r][i];
+            }
+        }
+    }
+}
+
 // eigenvalue of row i: w_i . vt_i
 __global__ __launch_bounds__(256) void k_pca_rayleigh(const double* __restrict__ W, const double* __restrict__ Vt, int32_t Dp,
                                                       double* __restrict__ lambda) {
@@ -208,7 +332,7 @@ __global__ __launch_bounds__(256) void k_pca_rayleigh(const double* __restrict__
 // as unit directions whose entry of largest magnitude (the first such) is positive.  One workgroup.
 __global__ __launch_bounds__(256) void k_pca_select(const double* __restrict__ lambda, const double* __restrict__ Vt, int32_t D,
                                                     int32_t Dp, int32_t p, float* __restrict__ comps, double* __restrict__ evals) {
-    __shared__ double s_lam[kPcaMaxD + 2];
+    __shared__ double s_lam[kPcaMaxD + 4];
     __shared__ double s_val[256];
     __shared__ int s_idx[256];
     for (int i = threadIdx.x; i < Dp; i += blockDim.x) s_lam[i] = lambda[i];
@@ -689,7 +813,7 @@ __global__ __launch_bounds__(256) void k_apply_assigned(const T* __restrict__ x,
 
 // ---- host side ---------------------------------------------------------------------------------
 static inline size_t pad256(size_t x) { return (x + 255) & ~(size_t)255; }
-static inline int64_t even_up(int64_t D) { return D + (D & 1); }
+static inline int64_t even_up(int64_t D) { return (D + 7) & ~(int64_t)7; }  // rows of the eigen workspace: a multiple of 8
 
 struct PcaWs {
     double* sum;     // D
@@ -834,22 +958,44 @@ cat_status cat_pca_fit(const void* lq, int64_t N, int64_t D, int32_t p, cat_dtyp
         hipLaunchKernelGGL(k_pca_mirror, g2, dim3(256), 0, st, w.W, D, Dp);
         CAT_LAUNCH_CHECK("k_pca_mirror");
     }
-    if (Dp >= 2) {
-        for (int sw = 0; sw < sweeps; sw++)
-            for (int step = 0; step < Dp - 1; step++) {
-                const dim3 jg((unsigned)(Dp / 2)), jb(256);
-                switch ((int)((Dp + 255) / 256)) {
-                    case 1: hipLaunchKernelGGL(k_pca_jacobi_step<1>, jg, jb, 0, st, w.W, w.Vt, (int32_t)Dp, step); break;
-                    case 2: hipLaunchKernelGGL(k_pca_jacobi_step<2>, jg, jb, 0, st, w.W, w.Vt, (int32_t)Dp, step); break;
-                    case 3: hipLaunchKernelGGL(k_pca_jacobi_step<3>, jg, jb, 0, st, w.W, w.Vt, (int32_t)Dp, step); break;
-                    case 4: hipLaunchKernelGGL(k_pca_jacobi_step<4>, jg, jb, 0, st, w.W, w.Vt, (int32_t)Dp, step); break;
-                    case 5: hipLaunchKernelGGL(k_pca_jacobi_step<5>, jg, jb, 0, st, w.W, w.Vt, (int32_t)Dp, step); break;
-                    case 6: hipLaunchKernelGGL(k_pca_jacobi_step<6>, jg, jb, 0, st, w.W, w.Vt, (int32_t)Dp, step); break;
-                    case 7: hipLaunchKernelGGL(k_pca_jacobi_step<7>, jg, jb, 0, st, w.W, w.Vt, (int32_t)Dp, step); break;
-                    default: hipLaunchKernelGGL(k_pca_jacobi_step<8>, jg, jb, 0, st, w.W, w.Vt, (int32_t)Dp, step); break;
+    {
+        const int ni = (int)((Dp + 255) / 256);
+        const dim3 jb(256), gpair((unsigned)(Dp / 2)), gquad((unsigned)(Dp / 4)), goct((unsigned)(Dp / 8));
+#define CAT_JACOBI_CASES(KERNEL, GRID, ARG, FROM)                                                              \
+        case FROM: hipLaunchKernelGGL(KERNEL<FROM>, GRID, jb, 0, st, w.W, w.Vt, (int32_t)Dp, ARG); break;
+#define CAT_STEP(NI_) CAT_JACOBI_CASES(k_pca_jacobi_step, gpair, -1, NI_)
+        // rows in registers: 4 BR NI doubles per thread, so blocks of four up to Dp = 1024, of two beyond
+        const bool br4 = ni <= 4;
+        for (int sw = 0; sw < sweeps; sw++) {
+            switch (ni) { CAT_STEP(1) CAT_STEP(2) CAT_STEP(3) CAT_STEP(4) CAT_STEP(5) CAT_STEP(6) CAT_STEP(7) default: CAT_STEP(8) }
+            CAT_LAUNCH_CHECK("k_pca_jacobi_step");
+            if (br4) {
+                // the two halves of every block of four, then every pair of blocks of four
+                for (int round = -1; round < (int)(Dp / 4) - 1; round++) {
+                    const bool halves = round < 0;
+#define CAT_B(NI_)                                                                                                          \
+    case NI_:                                                                                                               \
+        if (halves)                                                                                                         \
+            hipLaunchKernelGGL((k_pca_jacobi_block<NI_, 2>), gquad, jb, 0, st, w.W, w.Vt, (int32_t)Dp, -1);                  \
+        else                                                                                                                \
+            hipLaunchKernelGGL((k_pca_jacobi_block<NI_, 4>), goct, jb, 0, st, w.W, w.Vt, (int32_t)Dp, round);                \
+        break;
+                    switch (ni) { CAT_B(1) CAT_B(2) CAT_B(3) default: CAT_B(4) }
+#undef CAT_B
+                    CAT_LAUNCH_CHECK("k_pca_jacobi_block");
                 }
-                CAT_LAUNCH_CHECK("k_pca_jacobi_step");
+            } else {
+                for (int round = 0; round < (int)(Dp / 2) - 1; round++) {
+#define CAT_B(NI_) \
+    case NI_: hipLaunchKernelGGL((k_pca_jacobi_block<NI_, 2>), gquad, jb, 0, st, w.W, w.Vt, (int32_t)Dp, round); break;
+                    switch (ni) { CAT_B(5) CAT_B(6) CAT_B(7) default: CAT_B(8) }
+#undef CAT_B
+                    CAT_LAUNCH_CHECK("k_pca_jacobi_block");
+                }
             }
+        }
+#undef CAT_STEP
+#undef CAT_JACOBI_CASES
     }
     hipLaunchKernelGGL(k_pca_rayleigh, dim3((unsigned)Dp), dim3(256), 0, st, w.W, w.Vt, (int32_t)Dp, w.lambda);
     CAT_LAUNCH_CHECK("k_pca_rayleigh");
