@@ -206,9 +206,9 @@ __global__ __launch_bounds__(256) void k_pca_jacobi_step(double* __restrict__ W,
 // sweep.  A sweep: the pairs inside the blocks (k_pca_jacobi_step with step < 0 for the blocks of two, and for
 // BR = 4 this kernel with BR = 2 and round < 0 for the two halves of every block), then Dp / BR - 1 rounds.
 // Dp is a multiple of 2 BR.
-template <int NI, int BR>
-__global__ __launch_bounds__(256) void k_pca_jacobi_block(double* __restrict__ W, double* __restrict__ Vt, int32_t Dp, int32_t round) {
-    __shared__ double s_part[3 * BR][256];  // every thread's share of the three sums of each pair
+template <int NI, int BR, int T>  // T threads, NI elements per thread and row: Dp <= T NI
+__global__ __launch_bounds__(T) void k_pca_jacobi_block(double* __restrict__ W, double* __restrict__ Vt, int32_t Dp, int32_t round) {
+    __shared__ double s_part[3 * BR][T];  // every thread's share of the three sums of each pair
     __shared__ double s_cs[2 * BR];
     const int k = blockIdx.x, m = Dp / BR - 1;  // tournament over Dp / BR blocks
     int bp, bq;
@@ -228,7 +228,7 @@ __global__ __launch_bounds__(256) void k_pca_jacobi_block(double* __restrict__ W
         const int64_t row = (int64_t)(r < BR ? bp : bq) * BR + (r % BR);
 #pragma unroll
         for (int i = 0; i < NI; i++) {
-            const int j = threadIdx.x + i * 256;
+            const int j = threadIdx.x + i * T;
             const int jc = j < Dp ? j : 0;  // past the end: element 0 again, never used
             w[r][i] = W[row * Dp + jc];
             v[r][i] = Vt[row * Dp + jc];
@@ -239,7 +239,7 @@ __global__ __launch_bounds__(256) void k_pca_jacobi_block(double* __restrict__ W
 #pragma unroll
     for (int st = 0; st < BR; st++) {
         // step st: row i of bp against row (i + st) mod BR of bq, i = 0 .. BR - 1.  Every thread leaves its
-        // share of the sums in LDS; wave i adds the shares of pair i (256 values per sum: four per lane, then one
+        // share of the sums in LDS; wave i adds the shares of pair i (T values per sum: T / 64 per lane, then one
         // butterfly), so a step costs three butterflies per wave instead of 3 BR, and two barriers.
 #pragma unroll
         for (int i = 0; i < BR; i++) {
@@ -247,7 +247,7 @@ __global__ __launch_bounds__(256) void k_pca_jacobi_block(double* __restrict__ W
             double a = 0.0, b = 0.0, g = 0.0;
 #pragma unroll
             for (int e = 0; e < NI; e++) {
-                if ((int)threadIdx.x + e * 256 < Dp) {
+                if ((int)threadIdx.x + e * T < Dp) {
                     a = fma(w[i][e], w[i][e], a);
                     b = fma(w[q][e], w[q][e], b);
                     g = fma(w[i][e], w[q][e], g);
@@ -258,13 +258,15 @@ __global__ __launch_bounds__(256) void k_pca_jacobi_block(double* __restrict__ W
             s_part[3 * i + 2][threadIdx.x] = g;
         }
         __syncthreads();
-        if (wave < BR) {  // BR <= 4 waves
+        if (wave < BR) {  // BR <= 4 <= T / 64 waves
             const int i = wave;
-            double a = (s_part[3 * i][lane] + s_part[3 * i][lane + 64]) + (s_part[3 * i][lane + 128] + s_part[3 * i][lane + 192]);
-            double b = (s_part[3 * i + 1][lane] + s_part[3 * i + 1][lane + 64]) +
-                       (s_part[3 * i + 1][lane + 128] + s_part[3 * i + 1][lane + 192]);
-            double g = (s_part[3 * i + 2][lane] + s_part[3 * i + 2][lane + 64]) +
-                       (s_part[3 * i + 2][lane + 128] + s_part[3 * i + 2][lane + 192]);
+            double a = 0.0, b = 0.0, g = 0.0;
+#pragma unroll
+            for (int h = 0; h < T / kWave; h++) {
+                a += s_part[3 * i][lane + h * kWave];
+                b += s_part[3 * i + 1][lane + h * kWave];
+                g += s_part[3 * i + 2][lane + h * kWave];
+            }
             a = wave_sum(a);
             b = wave_sum(b);
             g = wave_sum(g);
@@ -306,7 +308,7 @@ __global__ __launch_bounds__(256) void k_pca_jacobi_block(double* __restrict__ W
         const int64_t row = (int64_t)(r < BR ? bp : bq) * BR + (r % BR);
 #pragma unroll
         for (int i = 0; i < NI; i++) {
-            const int j = threadIdx.x + i * 256;
+            const int j = threadIdx.x + i * T;
             if (j < Dp) {
                 W[row * Dp + j] = w[r][i];
                 Vt[row * Dp + j] = v[r][i];
@@ -964,34 +966,27 @@ cat_status cat_pca_fit(const void* lq, int64_t N, int64_t D, int32_t p, cat_dtyp
 #define CAT_JACOBI_CASES(KERNEL, GRID, ARG, FROM)                                                              \
         case FROM: hipLaunchKernelGGL(KERNEL<FROM>, GRID, jb, 0, st, w.W, w.Vt, (int32_t)Dp, ARG); break;
 #define CAT_STEP(NI_) CAT_JACOBI_CASES(k_pca_jacobi_step, gpair, -1, NI_)
-        // rows in registers: 4 BR NI doubles per thread, so blocks of four up to Dp = 1024, of two beyond
-        const bool br4 = ni <= 4;
+        // rows in registers: 4 BR NI doubles per thread with blocks of BR = 4 rows: 256 threads up to Dp = 1024,
+        // 512 beyond, so that NI stays at 4 or below
+        const bool wide = ni > 4;
+        const int nb = wide ? (int)((Dp + 511) / 512) : ni;
+        const dim3 jbb(wide ? 512 : 256);
         for (int sw = 0; sw < sweeps; sw++) {
             switch (ni) { CAT_STEP(1) CAT_STEP(2) CAT_STEP(3) CAT_STEP(4) CAT_STEP(5) CAT_STEP(6) CAT_STEP(7) default: CAT_STEP(8) }
             CAT_LAUNCH_CHECK("k_pca_jacobi_step");
-            if (br4) {
-                // the two halves of every block of four, then every pair of blocks of four
-                for (int round = -1; round < (int)(Dp / 4) - 1; round++) {
-                    const bool halves = round < 0;
-#define CAT_B(NI_)                                                                                                          \
-    case NI_:                                                                                                               \
-        if (halves)                                                                                                         \
-            hipLaunchKernelGGL((k_pca_jacobi_block<NI_, 2>), gquad, jb, 0, st, w.W, w.Vt, (int32_t)Dp, -1);                  \
-        else                                                                                                                \
-            hipLaunchKernelGGL((k_pca_jacobi_block<NI_, 4>), goct, jb, 0, st, w.W, w.Vt, (int32_t)Dp, round);                \
-        break;
-                    switch (ni) { CAT_B(1) CAT_B(2) CAT_B(3) default: CAT_B(4) }
+            // the two halves of every block of four, then every pair of blocks of four
+            for (int round = -1; round < (int)(Dp / 4) - 1; round++) {
+                const bool halves = round < 0;
+#define CAT_B(NI_, T_)                                                                                                      \
+    if (halves)                                                                                                             \
+        hipLaunchKernelGGL((k_pca_jacobi_block<NI_, 2, T_>), gquad, jbb, 0, st, w.W, w.Vt, (int32_t)Dp, -1);                 \
+    else                                                                                                                    \
+        hipLaunchKernelGGL((k_pca_jacobi_block<NI_, 4, T_>), goct, jbb, 0, st, w.W, w.Vt, (int32_t)Dp, round);
+                if (wide) {
+                    if (nb <= 3) { CAT_B(3, 512) } else { CAT_B(4, 512) }
+                } else if (nb == 1) { CAT_B(1, 256) } else if (nb == 2) { CAT_B(2, 256) } else if (nb == 3) { CAT_B(3, 256) } else { CAT_B(4, 256) }
 #undef CAT_B
-                    CAT_LAUNCH_CHECK("k_pca_jacobi_block");
-                }
-            } else {
-                for (int round = 0; round < (int)(Dp / 2) - 1; round++) {
-#define CAT_B(NI_) \
-    case NI_: hipLaunchKernelGGL((k_pca_jacobi_block<NI_, 2>), gquad, jb, 0, st, w.W, w.Vt, (int32_t)Dp, round); break;
-                    switch (ni) { CAT_B(5) CAT_B(6) CAT_B(7) default: CAT_B(8) }
-#undef CAT_B
-                    CAT_LAUNCH_CHECK("k_pca_jacobi_block");
-                }
+                CAT_LAUNCH_CHECK("k_pca_jacobi_block");
             }
         }
 #undef CAT_STEP
