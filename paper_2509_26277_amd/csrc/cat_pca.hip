@@ -198,6 +198,32 @@ __global__ __launch_bounds__(256) void k_pca_jacobi_step(double* __restrict__ W,
     }
 }
 
+// Sum of a double over the wave, valid in lane 0: four steps inside each row of 16 lanes as lane permutations
+// fused into the moves (no LDS round trip as with a butterfly of shuffles), then the four row sums from lanes
+// 0, 16, 32 and 48.  All 64 lanes must be active.
+template <int CTRL>
+__device__ __forceinline__ double dpp_move(double v) {
+    const long long b = __double_as_longlong(v);
+    const int lo = __builtin_amdgcn_update_dpp(0, (int)(b & 0xFFFFFFFFll), CTRL, 0xF, 0xF, true);
+    const int hi = __builtin_amdgcn_update_dpp(0, (int)(b >> 32), CTRL, 0xF, 0xF, true);
+    return __longlong_as_double(((long long)hi << 32) | (unsigned int)lo);
+}
+__device__ __forceinline__ double wave_sum_lane0(double v) {
+    v += dpp_move<0xB1>(v);   // quad_perm [1, 0, 3, 2]
+    v += dpp_move<0x4E>(v);   // quad_perm [2, 3, 0, 1]
+    v += dpp_move<0x141>(v);  // row_half_mirror
+    v += dpp_move<0x140>(v);  // row_mirror
+    const long long b = __double_as_longlong(v);
+    double r[4];
+#pragma unroll
+    for (int q = 0; q < 4; q++) {
+        const int lo = __builtin_amdgcn_readlane((int)(b & 0xFFFFFFFFll), 16 * q);
+        const int hi = __builtin_amdgcn_readlane((int)(b >> 32), 16 * q);
+        r[q] = __longlong_as_double(((long long)hi << 32) | (unsigned int)lo);
+    }
+    return (r[0] + r[1]) + (r[2] + r[3]);
+}
+
 // BR tournament steps per launch.  Rows are taken in blocks of BR (2 or 4); a round of the tournament over the
 // Dp / BR blocks pairs block bp with block bq, and one workgroup holds the 2 BR rows of both matrices in
 // registers and rotates, in BR steps of BR disjoint pairs, every row of bp against every row of bq: one load and
@@ -267,12 +293,12 @@ __global__ __launch_bounds__(T) void k_pca_jacobi_block(double* __restrict__ W, 
                 b += s_part[3 * i + 1][lane + h * kWave];
                 g += s_part[3 * i + 2][lane + h * kWave];
             }
-            a = wave_sum(a);
-            b = wave_sum(b);
-            g = wave_sum(g);
+            a = wave_sum_lane0(a);
+            b = wave_sum_lane0(b);
+            g = wave_sum_lane0(g);
             if (lane == 0) {
                 double c = 1.0, sn = 0.0;
-                if (fabs(g) > 1e-15 * sqrt(a * b) && g != 0.0) {
+                if (g * g > 1e-30 * (a * b) && g != 0.0) {  // |g| > 1e-15 sqrt(a b)
                     const double zeta = (b - a) / (2.0 * g);
                     const double t = (zeta >= 0.0 ? 1.0 : -1.0) / (fabs(zeta) + sqrt(1.0 + zeta * zeta));
                     c = 1.0 / sqrt(1.0 + t * t);
