@@ -90,6 +90,81 @@ __global__ __launch_bounds__(256) void k_pca_cov(const T* __restrict__ x, int64_
     if (ia + 1 < D && ib + 1 < D) atomicAdd(W + (ia + 1) * ldw + ib + 1, c11);
 }
 
+// The same sums on the fp64 matrix cores (v_mfma_f64_16x16x4_f64), used from D = 64 on.  One wave per
+// (64 x 64 tile of the upper triangle, row range): lane (m, k) = (lane & 15, lane >> 4) loads entry m of a
+// 16-column piece of row i0 + k, centres and widens it, and that is at once the A operand (for the piece of the
+// tile's rows) and the B operand (for the piece of its columns) of a 16 x 16 x 4 product; 4 + 4 pieces feed 16
+// products per step of four rows, 16 rows are requested ahead of their use.  No LDS, no barriers; the 64 x 64
+// doubles of a wave stay in registers until they are added to W with atomics.
+typedef double f64x4_t __attribute__((ext_vector_type(4)));
+constexpr int kCovM = 64;     // tile edge of a wave
+constexpr int kCovAhead = 4;  // steps of four rows requested together
+template <typename T>
+__global__ __launch_bounds__(256) void k_pca_cov_mfma(const T* __restrict__ x, int64_t N, int64_t D, const double* __restrict__ mean,
+                                                      int64_t rows_per_wave, int32_t ntile, double* __restrict__ W, int64_t ldw) {
+    int t = blockIdx.x, ta = 0;  // tile index -> (ta <= tb)
+    while (t >= ntile - ta) {
+        t -= ntile - ta;
+        ta++;
+    }
+    const int tb = ta + t;
+    const int64_t a0 = (int64_t)ta * kCovM, b0 = (int64_t)tb * kCovM;
+    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+    const int m = lane & 15, kk = lane >> 4;
+    const int64_t range = (int64_t)blockIdx.y * (blockDim.x / kWave) + wave;
+    const int64_t r0 = range * rows_per_wave;
+    const int64_t r1 = r0 + rows_per_wave < N ? r0 + rows_per_wave : N;
+    if (r0 >= N) return;  // wave-uniform
+    // this lane's eight columns (four of the tile's rows, four of its columns), clamped to valid positions
+    int64_t col[8];
+    double mu[8];
+    bool ok[8];
+#pragma unroll
+    for (int s = 0; s < 8; s++) {
+        const int64_t c = (s < 4 ? a0 : b0) + 16 * (s & 3) + m;
+        ok[s] = c < D;
+        col[s] = ok[s] ? c : 0;
+        mu[s] = mean[col[s]];
+    }
+    f64x4_t acc[4][4];
+#pragma unroll
+    for (int i = 0; i < 4; i++)
+#pragma unroll
+        for (int j = 0; j < 4; j++) acc[i][j] = (f64x4_t){0.0, 0.0, 0.0, 0.0};
+    for (int64_t rb = r0; rb < r1; rb += 4 * kCovAhead) {
+        float raw[kCovAhead][8];
+#pragma unroll
+        for (int u = 0; u < kCovAhead; u++) {
+            const int64_t i = rb + 4 * u + kk;
+            const T* xr = x + (i < r1 ? i : r0) * D;  // past the range: a valid row, its values dropped below
+#pragma unroll
+            for (int s = 0; s < 8; s++) raw[u][s] = ld_elem(xr + col[s]);
+        }
+#pragma unroll
+        for (int u = 0; u < kCovAhead; u++) {
+            const bool in = rb + 4 * u + kk < r1;
+            double v[8];
+#pragma unroll
+            for (int s = 0; s < 8; s++) v[s] = (in && ok[s]) ? (double)raw[u][s] - mu[s] : 0.0;
+#pragma unroll
+            for (int i = 0; i < 4; i++)
+#pragma unroll
+                for (int j = 0; j < 4; j++) acc[i][j] = __builtin_amdgcn_mfma_f64_16x16x4f64(v[i], v[4 + j], acc[i][j], 0, 0, 0);
+        }
+    }
+    // entry r of acc[i][j]: row a0 + 16 i + 4 r + (lane >> 4) of W, column b0 + 16 j + (lane & 15) (the fp64
+    // product interleaves its result rows over the lane groups, unlike the fp32 one)
+#pragma unroll
+    for (int i = 0; i < 4; i++)
+#pragma unroll
+        for (int j = 0; j < 4; j++)
+#pragma unroll
+            for (int r = 0; r < 4; r++) {
+                const int64_t ia = a0 + 16 * i + 4 * r + kk, ib = b0 + 16 * j + m;
+                if (ia < D && ib < D && ia <= ib) atomicAdd(W + ia * ldw + ib, acc[i][j][r]);
+            }
+}
+
 // scale the upper triangle by 1/N, set the padding row / column (an eigenvalue below every eigenvalue
 // of a covariance, so it is never selected), start Vt as the identity; then mirror into the lower
 // triangle (a second launch, so that it reads finished values)
@@ -973,12 +1048,28 @@ cat_status cat_pca_fit(const void* lq, int64_t N, int64_t D, int32_t p, cat_dtyp
         CAT_LAUNCH_CHECK("k_pca_mean");
     }
     {
-        const int ntile = (int)((D + kCovTile - 1) / kCovTile);
-        dim3 g((unsigned)(ntile * (ntile + 1) / 2), nrb), b(256);
-        if (dt == CAT_F32)
-            hipLaunchKernelGGL(k_pca_cov<float>, g, b, 0, st, (const float*)lq, N, D, w.mean, rpb, ntile, w.W, Dp);
-        else
-            hipLaunchKernelGGL(k_pca_cov<bf16_t>, g, b, 0, st, (const bf16_t*)lq, N, D, w.mean, rpb, ntile, w.W, Dp);
+        if (D >= kCovM) {
+            // matrix cores: 64 x 64 tiles, the rows split so that about 6144 waves are at work, four per workgroup
+            const int ntile = (int)((D + kCovM - 1) / kCovM);
+            const int ntri = ntile * (ntile + 1) / 2;
+            int64_t split = (6144 + ntri - 1) / ntri;
+            split = (split + 3) / 4 * 4;
+            int64_t rpw = (N + split - 1) / split;
+            rpw = (rpw + 15) / 16 * 16;
+            const int64_t nranges = (N + rpw - 1) / rpw;
+            dim3 g((unsigned)ntri, (unsigned)((nranges + 3) / 4)), b(256);
+            if (dt == CAT_F32)
+                hipLaunchKernelGGL(k_pca_cov_mfma<float>, g, b, 0, st, (const float*)lq, N, D, w.mean, rpw, ntile, w.W, Dp);
+            else
+                hipLaunchKernelGGL(k_pca_cov_mfma<bf16_t>, g, b, 0, st, (const bf16_t*)lq, N, D, w.mean, rpw, ntile, w.W, Dp);
+        } else {
+            const int ntile = (int)((D + kCovTile - 1) / kCovTile);
+            dim3 g((unsigned)(ntile * (ntile + 1) / 2), nrb), b(256);
+            if (dt == CAT_F32)
+                hipLaunchKernelGGL(k_pca_cov<float>, g, b, 0, st, (const float*)lq, N, D, w.mean, rpb, ntile, w.W, Dp);
+            else
+                hipLaunchKernelGGL(k_pca_cov<bf16_t>, g, b, 0, st, (const bf16_t*)lq, N, D, w.mean, rpb, ntile, w.W, Dp);
+        }
         CAT_LAUNCH_CHECK("k_pca_cov");
         dim3 g2((unsigned)((Dp + 255) / 256), (unsigned)Dp);
         hipLaunchKernelGGL(k_pca_cov_finish, g2, dim3(256), 0, st, w.W, w.Vt, D, Dp, N);
