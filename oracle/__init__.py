@@ -22,4 +22,5 @@ from .cat_oracle import (  # noqa: F401
     alpha_sweep,
     kmeanspp,
     fit_restarts,
+    fit_early_stop,
 )

@@ -312,3 +312,34 @@ def fit_restarts(lq, fp, K, iters, seed=0, restarts=4, kmeanspp_seeding=False):
             best = dict(run, best_run=r)
     best["final_inertia"] = np.asarray(finals)
     return best
+
+
+def fit_early_stop(lq, fp, K, iters, seed=0, init_centroids=None):
+    """``fit`` with the Lloyd loop left at the first pass whose assignments repeat those of the pass before
+    (the partition is then a fixed point of the iteration: the means, hence every later pass, cannot change).
+
+    Written as the sequence of the oracle's own steps: assign, compare with the previous assignments, update.
+    The objective of the passes that are not run is the one of the last pass that was.  Returns the dict of
+    ``fit`` plus ``stable_at``: the index t >= 1 of the first repeating pass, or -1 if none of the iters + 1
+    passes repeats its predecessor."""
+    x = np.ascontiguousarray(lq, dtype=np.float32)
+    N, D = x.shape
+    if init_centroids is None:
+        cent = x[init_indices(N, K, seed)].astype(np.float64)
+    else:
+        cent = np.array(init_centroids, dtype=np.float64)
+    inertia = np.empty(iters + 1, dtype=np.float64)
+    prev, stable_at = None, -1
+    for t in range(iters + 1):
+        a, d1, _ = assign(x, cent, want_distances=True)
+        inertia[t] = d1.sum()
+        if prev is not None and (a == prev).all():
+            stable_at = t
+            inertia[t:] = inertia[t]
+            break
+        if t < iters:
+            cent, _ = update(x, a, cent)
+            prev = a
+    gamma, beta, counts = affine(x, fp, a, K)
+    return dict(centroids=cent, gamma=gamma, beta=beta, assignments=a, counts=counts, inertia=inertia,
+                stable_at=stable_at)
