@@ -39,12 +39,12 @@ HBM_PEAK_GBPS = 8000.0
 # (a copy reads and writes exactly N*D*b bytes).  Per workload: (FETCH_SIZE of k_tile, FETCH_SIZE of the
 # copy, WRITE_SIZE of k_tile, WRITE_SIZE of the copy), counter units, mean per dispatch.  The figures
 # belong to one version of the kernel source: `traffic` is reported only while its hash still matches.
-TRAFFIC_KERNEL_SHA256 = "5be413f6cf254f4e59e61865ce4a21f43242e1158f25d2d3918536261c9051c4"
+TRAFFIC_KERNEL_SHA256 = "c368204e0d3cb727b427eb617db98ee9711a7f8d82ac8120400e7d1b9dc3b32c"
 TRAFFIC_COUNTERS = {
-    "cfg2": (133730.9, 128011.7, 298.8, 256000.0),
-    "cfg3": (527766.4, 524300.7, 4723.0, 1048576.0),
-    "cfg4": (560592.9, 524300.5, 1190.7, 1048576.0),
-    "cfg5": (8362201.7, 4194317.6, 8406456.9, 8388608.0),
+    "cfg2": (133758.9, 128011.7, 298.9, 256000.0),
+    "cfg3": (527761.6, 524299.7, 4719.2, 1048576.0),
+    "cfg4": (560549.3, 524299.7, 1191.5, 1048576.0),
+    "cfg5": (8363420.5, 4194317.9, 8406407.7, 8388608.0),
 }
 
 
@@ -243,6 +243,12 @@ def main():
         ws_pp = torch.empty(binding.load_library().cat_init_kmeanspp_workspace_bytes(N, K), dtype=torch.uint8, device="cuda")
         t_pp = _events(lambda: cat_init_kmeanspp(lq, K, seed=w["seed"], workspace=ws_pp), 3, torch)
         detail.update(kmeanspp_ms=t_pp, kmeanspp_GBps=(K - 1) * N * D * esize / t_pp / 1e6)
+
+    # ---- the same fit with the early stop allowed (a separate row: the headline runs every pass) ----
+    if fit_kind and not args.no_seeding:
+        es = lambda: cat_fit(lq, fp, K, iters, seed=w["seed"], workspace=ws_fit, early_stop=True)
+        skipped = int(es()["passes_skipped"].item())
+        detail.update(fit_early_stop_ms=_events(es, 5, torch), passes_skipped=skipped)
 
     # context: plain device copy of the same matrix
     t_copy = _events(lambda: out.copy_(lq), 5, torch)

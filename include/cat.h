@@ -114,6 +114,31 @@ cat_status cat_fit(const void *lq, const void *fp, int64_t N, int64_t D, int32_t
                    void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /*
+ * cat_fit with the Lloyd loop allowed to stop early.  The paper names k-means without a stopping
+ * rule (Sec. 4, Setup); the rule here changes the work done, not the result: once a pass assigns
+ * every row to the cluster it already had, the means and so every later pass repeat themselves,
+ * and the passes between that one and the final one are not run.  All outputs are those of
+ * cat_fit with the same arguments (the inertia entries of the passes not run repeat the entry
+ * before them).  The decision is taken on the device from the number of rows that changed
+ * cluster; nothing waits on the host, and the call can be captured in a HIP graph.
+ *
+ * passes_skipped  out, 1 int32: the number of assignment passes not run, between 0 and
+ *                 iters - 3.  The library starts to look from pass 2 on: if pass t >= 1 is the
+ *                 first whose assignments equal those of pass t - 1, this is
+ *                 max(0, iters - 1 - max(t, 2)); 0 if there is none.  Shapes the tile kernels do
+ *                 not take (D not a multiple of 4 (8 for bf16), K > 256, or the streaming path
+ *                 selected) run every pass and report 0.
+ * Other arguments, workspace and errors: as cat_fit.
+ */
+cat_status cat_fit_early_stop(const void *lq, const void *fp, int64_t N, int64_t D, int32_t K,
+                              int32_t iters, uint64_t seed, cat_dtype dt,
+                              const float *init_centroids,
+                              float *centroids, float *gamma, float *beta,
+                              int32_t *assignments, int32_t *counts, double *inertia,
+                              int32_t *passes_skipped,
+                              void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
  * CAT Inferencing (Algorithm 2; the alpha-blend at the end of Sec. 3.1), fused:
  * corrected_i = x_i + alpha * (gamma_a * x_i + beta_a - x_i),  a = nearest centroid
  * of x_i.  alpha is folded once into gamma' = 1 + alpha * (gamma - 1), beta' =

@@ -24,7 +24,7 @@ EXPORTS = ("cat_select_path", "cat_fit_workspace_bytes", "cat_apply_workspace_by
            "cat_apply_assigned", "cat_fit_pca_workspace_bytes", "cat_fit_pca", "cat_apply_pca_workspace_bytes", "cat_apply_pca",
            "cat_alpha_sweep_workspace_bytes", "cat_alpha_sweep", "cat_top1",
            "cat_init_kmeanspp_workspace_bytes", "cat_init_kmeanspp",
-           "cat_fit_restarts_workspace_bytes", "cat_fit_restarts")
+           "cat_fit_restarts_workspace_bytes", "cat_fit_restarts", "cat_fit_early_stop")
 
 
 class CatError(RuntimeError):
@@ -56,6 +56,8 @@ def load_library():
     lib.cat_apply_workspace_bytes.restype = sz
     lib.cat_fit.argtypes = [vp, vp, i64, i64, i32, i32, u64, c.c_int, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.cat_fit.restype = c.c_int
+    lib.cat_fit_early_stop.argtypes = [vp, vp, i64, i64, i32, i32, u64, c.c_int, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.cat_fit_early_stop.restype = c.c_int
     lib.cat_apply.argtypes = [vp, i64, i64, i32, c.c_int, vp, vp, vp, c.c_float, vp, vp, vp, sz, vp]
     lib.cat_apply.restype = c.c_int
     lib.cat_assign.argtypes = [vp, i64, i64, i32, c.c_int, vp, vp, vp, vp, vp, sz, vp]
@@ -183,10 +185,11 @@ def cat_init_indices(N, K, seed):
     return list(buf)[:K]
 
 
-def cat_fit(lq, fp, K, iters, seed=0, init_centroids=None, want_inertia=True, workspace=None):
+def cat_fit(lq, fp, K, iters, seed=0, init_centroids=None, want_inertia=True, workspace=None, early_stop=False):
     """CAT Fitting on device tensors.  Returns a dict of device tensors:
     centroids, gamma, beta (K x D float32), assignments (N int32), counts (K int32),
-    inertia (iters+1 float64, or None)."""
+    inertia (iters+1 float64, or None).  With ``early_stop`` (cat_fit_early_stop) the passes after the partition has
+    stopped changing are not run, the outputs stay those of the full loop, and ``passes_skipped`` (1 int32) is added."""
     lib = load_library()
     N, D = lq.shape
     dt = _dt(lq)
@@ -199,12 +202,18 @@ def cat_fit(lq, fp, K, iters, seed=0, init_centroids=None, want_inertia=True, wo
     a = torch.empty((N,), dtype=torch.int32, device=dev)
     counts = torch.empty((K,), dtype=torch.int32, device=dev)
     inertia = torch.empty((max(iters, 0) + 1,), dtype=torch.float64, device=dev) if want_inertia else None
-    _check(lib.cat_fit(_dev(lq, name="lq"), _dev(fp, lq.dtype, (N, D), "fp"), N, D, K, iters,
-                       seed & (2**64 - 1), dt, _dev(init_centroids, torch.float32, (K, D), "init_centroids"),
-                       cent.data_ptr(), gamma.data_ptr(), beta.data_ptr(), a.data_ptr(), counts.data_ptr(),
-                       None if inertia is None else inertia.data_ptr(),
-                       workspace.data_ptr(), workspace.numel(), _stream()))
-    return dict(centroids=cent, gamma=gamma, beta=beta, assignments=a, counts=counts, inertia=inertia)
+    head = (_dev(lq, name="lq"), _dev(fp, lq.dtype, (N, D), "fp"), N, D, K, iters,
+            seed & (2**64 - 1), dt, _dev(init_centroids, torch.float32, (K, D), "init_centroids"),
+            cent.data_ptr(), gamma.data_ptr(), beta.data_ptr(), a.data_ptr(), counts.data_ptr(),
+            None if inertia is None else inertia.data_ptr())
+    tail = (workspace.data_ptr(), workspace.numel(), _stream())
+    res = dict(centroids=cent, gamma=gamma, beta=beta, assignments=a, counts=counts, inertia=inertia)
+    if early_stop:
+        res["passes_skipped"] = torch.empty((1,), dtype=torch.int32, device=dev)
+        _check(lib.cat_fit_early_stop(*head, res["passes_skipped"].data_ptr(), *tail))
+    else:
+        _check(lib.cat_fit(*head, *tail))
+    return res
 
 
 def cat_apply(lq, centroids, gamma, beta, alpha=1.0, want_assignments=True, out=None, workspace=None):

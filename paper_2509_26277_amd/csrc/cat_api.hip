@@ -198,10 +198,11 @@ static cat_status step_stats(const void* lq, const void* fp, cat_dtype dt, const
 }
 
 // Initialisation, `iters` Lloyd iterations and the final assignment (everything of cat_fit before the
-// affine fit).  Leaves the counts and the first row of every cluster in w.counts / w.rep.
+// affine fit).  Leaves the counts and the first row of every cluster in w.counts / w.rep.  With `skipped`
+// given the loop may stop early (see tile_lloyd); the outputs are those of the full loop.
 static cat_status run_lloyd(const void* lq, cat_dtype dt, int64_t N, int64_t D, int32_t K, int32_t iters, uint64_t seed,
                             const float* init_centroids, float* centroids, int32_t* assignments, double* inertia,
-                            const FitWs& w, hipStream_t st) {
+                            const FitWs& w, hipStream_t st, int32_t* skipped = nullptr) {
     const size_t KD = (size_t)K * (size_t)D;
     const int path = g_path.load();
     const bool fused = tile_supports(TILE_LLOYD, N, D, K, dt) && path != CAT_PATH_STREAM;
@@ -218,8 +219,10 @@ static cat_status run_lloyd(const void* lq, cat_dtype dt, int64_t N, int64_t D, 
     }
     if (fused) {
         // one assignment launch per Lloyd iteration; only the rows that change cluster touch the sums
-        CAT_TRY(tile_lloyd(lq, dt, N, D, K, iters, centroids, w.acc, assignments, w.counts, inertia, w.rep, w.tile, w.lloyd, st));
+        CAT_TRY(tile_lloyd(lq, dt, N, D, K, iters, centroids, w.acc, assignments, w.counts, inertia, w.rep, skipped, w.tile, w.lloyd, st));
     } else {
+        // the streaming kernels keep no record of the rows that move: every pass runs
+        if (skipped) CAT_TRY(launch_fill_zero(skipped, sizeof(int32_t), st));
         int cur = 0;
         for (int32_t t = 0; t < iters; t++) {
             CAT_TRY(step_assign(lq, dt, N, D, K, w.cent[cur], assignments, w.counts, inertia ? w.inertia : nullptr,
@@ -361,28 +364,45 @@ cat_status cat_stats(const void* lq, const void* fp, const int32_t* assignments,
     return CAT_OK;
 }
 
-cat_status cat_fit(const void* lq, const void* fp, int64_t N, int64_t D, int32_t K, int32_t iters, uint64_t seed,
-                   cat_dtype dt, const float* init_centroids, float* centroids, float* gamma, float* beta,
-                   int32_t* assignments, int32_t* counts, double* inertia, void* workspace, size_t workspace_bytes,
-                   void* hip_stream) {
-    CAT_TRY(check_shape("cat_fit", N, D, K, dt));
-    if (iters < 0) return set_error(CAT_ERR_INVALID_ARG, "cat_fit: iters = %d is negative", (int)iters);
-    CAT_TRY(check_ptr("cat_fit", "lq", lq, 16));
-    CAT_TRY(check_ptr("cat_fit", "fp", fp, 16));
-    if (init_centroids) CAT_TRY(check_ptr("cat_fit", "init_centroids", init_centroids, 16));
-    CAT_TRY(check_ptr("cat_fit", "centroids", centroids, 16));
-    CAT_TRY(check_ptr("cat_fit", "gamma", gamma, 16));
-    CAT_TRY(check_ptr("cat_fit", "beta", beta, 16));
-    CAT_TRY(check_ptr("cat_fit", "assignments", assignments, 4));
-    if (inertia) CAT_TRY(check_ptr("cat_fit", "inertia", inertia, 8));
+static cat_status fit_impl(const char* who, const void* lq, const void* fp, int64_t N, int64_t D, int32_t K,
+                           int32_t iters, uint64_t seed, cat_dtype dt, const float* init_centroids, float* centroids,
+                           float* gamma, float* beta, int32_t* assignments, int32_t* counts, double* inertia,
+                           int32_t* skipped, void* workspace, size_t workspace_bytes, void* hip_stream) {
+    CAT_TRY(check_shape(who, N, D, K, dt));
+    if (iters < 0) return set_error(CAT_ERR_INVALID_ARG, "%s: iters = %d is negative", who, (int)iters);
+    CAT_TRY(check_ptr(who, "lq", lq, 16));
+    CAT_TRY(check_ptr(who, "fp", fp, 16));
+    if (init_centroids) CAT_TRY(check_ptr(who, "init_centroids", init_centroids, 16));
+    CAT_TRY(check_ptr(who, "centroids", centroids, 16));
+    CAT_TRY(check_ptr(who, "gamma", gamma, 16));
+    CAT_TRY(check_ptr(who, "beta", beta, 16));
+    CAT_TRY(check_ptr(who, "assignments", assignments, 4));
+    if (inertia) CAT_TRY(check_ptr(who, "inertia", inertia, 8));
     FitWs w = carve_fit(workspace, N, D, K, dt);
-    CAT_TRY(check_ws("cat_fit", workspace, workspace_bytes, w.bytes));
+    CAT_TRY(check_ws(who, workspace, workspace_bytes, w.bytes));
     hipStream_t st = (hipStream_t)hip_stream;
-    CAT_TRY(run_lloyd(lq, dt, N, D, K, iters, seed, init_centroids, centroids, assignments, inertia, w, st));
+    CAT_TRY(run_lloyd(lq, dt, N, D, K, iters, seed, init_centroids, centroids, assignments, inertia, w, st, skipped));
     // affine fit on that partition, shifted by the centroids
     CAT_TRY(step_stats(lq, fp, dt, assignments, N, D, K, w.counts, w.rep, centroids, w, gamma, beta, st));
     if (counts) CAT_TRY(launch_copy_words(w.counts, counts, K, st));
     return CAT_OK;
+}
+
+cat_status cat_fit(const void* lq, const void* fp, int64_t N, int64_t D, int32_t K, int32_t iters, uint64_t seed,
+                   cat_dtype dt, const float* init_centroids, float* centroids, float* gamma, float* beta,
+                   int32_t* assignments, int32_t* counts, double* inertia, void* workspace, size_t workspace_bytes,
+                   void* hip_stream) {
+    return fit_impl("cat_fit", lq, fp, N, D, K, iters, seed, dt, init_centroids, centroids, gamma, beta, assignments,
+                    counts, inertia, nullptr, workspace, workspace_bytes, hip_stream);
+}
+
+cat_status cat_fit_early_stop(const void* lq, const void* fp, int64_t N, int64_t D, int32_t K, int32_t iters,
+                              uint64_t seed, cat_dtype dt, const float* init_centroids, float* centroids, float* gamma,
+                              float* beta, int32_t* assignments, int32_t* counts, double* inertia,
+                              int32_t* passes_skipped, void* workspace, size_t workspace_bytes, void* hip_stream) {
+    CAT_TRY(check_ptr("cat_fit_early_stop", "passes_skipped", passes_skipped, 4));
+    return fit_impl("cat_fit_early_stop", lq, fp, N, D, K, iters, seed, dt, init_centroids, centroids, gamma, beta,
+                    assignments, counts, inertia, passes_skipped, workspace, workspace_bytes, hip_stream);
 }
 
 // ---- several runs of the clustering, the one with the lowest final objective kept ---------------------

@@ -41,10 +41,12 @@ LloydWs lloyd_carve(void* base, int64_t N, int64_t D, int32_t K);
 
 // `iters` Lloyd iterations from cent0 plus the final assignment.  cent_io holds the initial
 // centroids on entry and the final ones on return; sums is 2 x K x D doubles of scratch.
-// Writes assignments, counts (K), inertia (iters + 1, nullable) and rep (K).
+// Writes assignments, counts (K), inertia (iters + 1, nullable) and rep (K).  skipped (one device int32,
+// nullable) allows the early stop: passes after the partition has stopped changing are not run, and their
+// number is written there; every other output is what the full loop gives.
 cat_status tile_lloyd(const void* lq, cat_dtype dt, int64_t N, int64_t D, int32_t K, int32_t iters,
                       float* cent_io, double* sums, int32_t* assign, int32_t* counts, double* inertia,
-                      unsigned long long* rep, const TileWs& ws, const LloydWs& lw, hipStream_t st);
+                      unsigned long long* rep, int32_t* skipped, const TileWs& ws, const LloydWs& lw, hipStream_t st);
 
 // Capacity of the per-workgroup changed-row list (cat_debug_list_capacity in cat.h).
 int lloyd_list_capacity();

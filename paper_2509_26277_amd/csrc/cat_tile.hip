@@ -96,6 +96,7 @@ struct DeltaParams {
     double* norm_part;           // slices x K
     double* inertia_slot;
     unsigned long long* rep;
+    int32_t* skipped;            // nullable: early stop allowed; counts the passes that were not run
 };
 
 constexpr int kDeltaWaves = 8;
@@ -114,6 +115,22 @@ __global__ __launch_bounds__(kDeltaWaves * kWave) void k_delta_prep(const DeltaP
     const int kc = (q.K - k0) < q.KC ? (q.K - k0) : q.KC;
 
     const uint32_t len = *q.list_count;
+    if (q.skipped && len == 0u) {
+        // No row changed cluster in the pass before: the sums, the centroids and therefore the pass that would
+        // follow are what they were.  That pass is not run (its kernel reads the same word); what it would have
+        // written is carried forward instead, and the double buffers are left as a pass with an empty list
+        // leaves them, so that the next launch of this kernel takes the same branch.
+        if (blockIdx.x == 0 && blockIdx.y == 0 && blockIdx.z == 0) {
+            for (int k = threadIdx.x; k < q.K; k += blockDim.x) q.counts_next[k] = q.counts[k];
+            for (int s = threadIdx.x; s < nslices; s += blockDim.x) q.done_next[s] = 0;
+            if (threadIdx.x == 0) {
+                *q.list_count_next = 0;
+                if (q.inertia_slot) q.inertia_slot[0] = q.inertia_slot[-1];
+                q.skipped[0] += 1;
+            }
+        }
+        return;
+    }
     if (blockIdx.x == 0 && blockIdx.y == 0 && blockIdx.z == 0) {  // the other halves of the double buffers
         for (int k = threadIdx.x; k < q.K; k += blockDim.x) {
             q.counts_next[k] = 0;
@@ -352,7 +369,7 @@ LloydWs lloyd_carve(void* base, int64_t N, int64_t D, int32_t K) {
 static cat_status launch_delta_prep(const void* lq, cat_dtype dt, int64_t D, int32_t K, const TileCfg& c,
                                     const TileWs& ws, const LloydWs& lw, int par, float* cent, double* base,
                                     double* delta, const int32_t* counts_prev, int32_t* counts_next,
-                                    double* inertia_slot, unsigned long long* rep, hipStream_t st) {
+                                    double* inertia_slot, unsigned long long* rep, int32_t* skipped, hipStream_t st) {
     DeltaParams q = {};
     q.lq = lq;
     q.D = D;
@@ -380,6 +397,7 @@ static cat_status launch_delta_prep(const void* lq, cat_dtype dt, int64_t D, int
     q.norm_part = lw.norm_part;
     q.inertia_slot = inertia_slot;
     q.rep = rep;
+    q.skipped = skipped;
     dim3 grid((unsigned)q.G, (unsigned)slices, (unsigned)kchunks), block(kDeltaWaves * kWave);
     const size_t lds = (size_t)q.KC * kDeltaSW * sizeof(double);
     if (dt == CAT_BF16)
@@ -474,7 +492,7 @@ cat_status tile_assign(const void* lq, cat_dtype dt, int64_t N, int64_t D, int32
 
 cat_status tile_lloyd(const void* lq, cat_dtype dt, int64_t N, int64_t D, int32_t K, int32_t iters,
                       float* cent_io, double* sums, int32_t* assign, int32_t* counts, double* inertia,
-                      unsigned long long* rep, const TileWs& ws, const LloydWs& lw, hipStream_t st) {
+                      unsigned long long* rep, int32_t* skipped, const TileWs& ws, const LloydWs& lw, hipStream_t st) {
     TileCfg c = tile_config(TILE_LLOYD, D, K, dt);
     if (!c.ok) return set_error(CAT_ERR_UNSUPPORTED, "tile kernels do not fit D=%lld K=%d", (long long)D, (int)K);
     const size_t KD = (size_t)K * (size_t)D;
@@ -490,11 +508,15 @@ cat_status tile_lloyd(const void* lq, cat_dtype dt, int64_t N, int64_t D, int32_
     p.cent = cent_io;
     p.assign = assign;
     if (iters > 2) CAT_T(launch_fill_zero(lw.ctrl, lloyd_ctrl_words(D) * 4, st));
+    if (skipped) CAT_T(launch_fill_zero(skipped, sizeof(int32_t), st));
     // Passes 0 and 1 are each followed by a full segmented sum: after the first reassignment most
     // rows still move, and moving them one by one costs several times a fresh sum (measured: 0.97 ms
     // against 0.33 ms on a 262144 x 2048 bf16 matrix).  From pass 2 on a pass lists the rows that
     // changed cluster, and the launch between two passes moves just those rows between the running
     // sums and prepares the next centroids (k_delta_prep).  The last pass only assigns.
+    // With `skipped` given, a pass t in kFullPasses < t < iters whose predecessor listed no row is not run: the
+    // partition has stopped changing, so it would reproduce its predecessor.  Both of its launches then return at
+    // once (they read the list length on the device; nothing waits on the host), and the final pass runs as always.
     // Counts alternate between two buffers so that a pass never accumulates into the buffer the
     // preparation before it reads; the last pass uses the caller's.
     constexpr int32_t kFullPasses = 2;
@@ -509,7 +531,7 @@ cat_status tile_lloyd(const void* lq, cat_dtype dt, int64_t N, int64_t D, int32_
                               ws, slot, last ? rep : nullptr, st));
         else
             CAT_T(launch_delta_prep(lq, dt, D, K, c, ws, lw, t & 1, cent_io, base, delta, cnt_prev, cnt_t, slot,
-                                    last ? rep : nullptr, st));
+                                    last ? rep : nullptr, last ? nullptr : skipped, st));
         p.norm_part = t > kFullPasses ? lw.norm_part : nullptr;
         p.norm_slices = t > kFullPasses ? (int32_t)delta_slices(D) : 0;
         p.counts = cnt_t;
@@ -522,6 +544,7 @@ cat_status tile_lloyd(const void* lq, cat_dtype dt, int64_t N, int64_t D, int32_
         // alternate the scan direction: the rows a pass reads last are the ones most likely still in
         // the memory-side cache when the next pass starts
         p.reverse = t & 1;
+        p.skip_when_zero = (skipped && t > kFullPasses && !last) ? lw.ctrl + ((t - 1) & 1) : nullptr;
         CAT_T(launch_tile(p, c, dt, st));
         if (t < kFullPasses && !last) {  // full sums of this pass's partition
             CAT_T(launch_fill_zero(sums, (t == 0 ? 2 : 1) * KD * sizeof(double), st));

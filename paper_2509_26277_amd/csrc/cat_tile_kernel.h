@@ -59,6 +59,8 @@ struct TileParams {
     int32_t delta_mode;      // 0: off, 1: rows carry a previous assignment
     int32_t list_cap;        // entries of the workgroup's LDS list in use (<= kListCap)
     int32_t reverse;         // walk the tiles from the last to the first (see tile_lloyd)
+    const uint32_t* skip_when_zero;  // nullable: the launch does nothing if this word is zero (tile_lloyd: the
+                                     // list length of the pass before, when the loop may stop early)
     const float* gamma;      // apply
     const float* beta;
     void* out;
@@ -477,6 +479,7 @@ __device__ __forceinline__ void finish_tile(const TileParams& p, unsigned char* 
 template <int KT, int PASSES, bool BF16, int MODE, bool CA>
 __global__ __launch_bounds__(kMaxWaves * kWave) void k_tile(const TileParams p) {
     extern __shared__ __align__(16) unsigned char smem[];
+    if (p.skip_when_zero && *p.skip_when_zero == 0u) return;  // uniform over the grid, before any barrier
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);  // wave-uniform: keeps tile math scalar
     constexpr int P = PASSES == 1 ? 1 : 2;
