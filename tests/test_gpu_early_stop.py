@@ -91,6 +91,26 @@ def test_same_outputs_as_the_full_loop(dt):
     torch.testing.assert_close(r["inertia"], full["inertia"], rtol=1e-12, atol=0)
 
 
+@pytest.mark.parametrize("cap", [1, 64])
+def test_with_short_changed_row_lists_and_given_initial_centroids(cap):
+    """the length the decision reads counts every changed row, also those a workgroup appends to the device-wide
+    list directly because its own list is full (forced by a tiny capacity); initial centroids given by the caller"""
+    x, y = _mixture(1, 6007, 256, 8, 1.5, "f32")
+    init = x[oracle.kmeanspp(x, 8, seed=3)]
+    o = oracle.fit_early_stop(x, y, 8, 25, init_centroids=init.astype(np.float64))
+    binding.select_path(binding.CAT_PATH_TILE)
+    binding.debug_list_capacity(cap)
+    try:
+        r = cat_fit(dev_matrix(x, "f32"), dev_matrix(y, "f32"), 8, 25, early_stop=True,
+                    init_centroids=torch.from_numpy(init).cuda())
+    finally:
+        binding.debug_list_capacity(0)
+    assert (r["assignments"].cpu().numpy() == o["assignments"]).all()
+    assert int(r["passes_skipped"].item()) == _expected_skips(int(o["stable_at"]), 25) > 0
+    check_values(host_matrix(r["centroids"]), o["centroids"], RTOL["f32"], "centroids")
+    np.testing.assert_allclose(r["inertia"].cpu().numpy(), o["inertia"], rtol=1e-4)
+
+
 @pytest.mark.parametrize("D,path", [(37, binding.CAT_PATH_AUTO), (64, binding.CAT_PATH_STREAM)])
 def test_shapes_outside_the_tile_kernels_run_every_pass(D, path):
     binding.select_path(path)
