@@ -25,7 +25,16 @@ __global__ __launch_bounds__(256) void k_pca_colsum(const T* __restrict__ x, int
     const int64_t r1 = r0 + rows_per_block < N ? r0 + rows_per_block : N;
     if (j >= D) return;
     double s = 0.0;
-    for (int64_t i = r0; i < r1; i++) s += (double)ld_elem(x + i * D + j);
+    constexpr int U = 8;  // loads in flight per thread; the adds stay in row order
+    int64_t i = r0;
+    for (; i + U <= r1; i += U) {
+        float v[U];
+#pragma unroll
+        for (int u = 0; u < U; u++) v[u] = ld_elem(x + (i + u) * D + j);
+#pragma unroll
+        for (int u = 0; u < U; u++) s += (double)v[u];
+    }
+    for (; i < r1; i++) s += (double)ld_elem(x + i * D + j);
     atomicAdd(sum + j, s);
 }
 
@@ -432,74 +441,58 @@ __global__ __launch_bounds__(256) void k_pca_rayleigh(const double* __restrict__
 }
 
 // the p largest eigenvalues in descending order (lowest row index first among equals), their rows of Vt
-// as unit directions whose entry of largest magnitude (the first such) is positive.  One workgroup.
+// as unit directions whose entry of largest magnitude (the first such) is positive.  Workgroup c finds the
+// entry with exactly c entries ahead of it in that order (a count per entry against all others, the values
+// in LDS) and writes direction c.
 __global__ __launch_bounds__(256) void k_pca_select(const double* __restrict__ lambda, const double* __restrict__ Vt, int32_t D,
-                                                    int32_t Dp, int32_t p, float* __restrict__ comps, double* __restrict__ evals) {
-    __shared__ double s_lam[kPcaMaxD + 4];
+                                                    int32_t Dp, float* __restrict__ comps, double* __restrict__ evals) {
+    __shared__ double s_lam[kPcaMaxD + 16];
     __shared__ double s_val[256];
     __shared__ int s_idx[256];
+    __shared__ int s_row;
+    const int c = blockIdx.x;
     for (int i = threadIdx.x; i < Dp; i += blockDim.x) s_lam[i] = lambda[i];
+    if (threadIdx.x == 0) s_row = 0;  // stays in range even if no entry qualifies (NaN input)
     __syncthreads();
-    for (int c = 0; c < p; c++) {
-        double best = -1e300;
-        int bi = 0x7fffffff;
-        for (int i = threadIdx.x; i < Dp; i += blockDim.x) {
-            const double v = s_lam[i];
-            if (v > best || (v == best && i < bi)) {
-                best = v;
-                bi = i;
-            }
+    for (int i = threadIdx.x; i < Dp; i += blockDim.x) {
+        const double v = s_lam[i];
+        int ahead = 0;
+        for (int j = 0; j < Dp; j++) {
+            const double u = s_lam[j];
+            ahead += (u > v || (u == v && j < i)) ? 1 : 0;
         }
-        s_val[threadIdx.x] = best;
-        s_idx[threadIdx.x] = bi;
-        __syncthreads();
-        for (int o = 128; o > 0; o >>= 1) {
-            if ((int)threadIdx.x < o) {
-                const double v = s_val[threadIdx.x + o];
-                const int i = s_idx[threadIdx.x + o];
-                if (v > s_val[threadIdx.x] || (v == s_val[threadIdx.x] && i < s_idx[threadIdx.x])) {
-                    s_val[threadIdx.x] = v;
-                    s_idx[threadIdx.x] = i;
-                }
-            }
-            __syncthreads();
+        if (ahead == c) s_row = i;  // the order is total: exactly one entry
+    }
+    __syncthreads();
+    const int row = s_row;
+    // sign: first entry of largest magnitude among the D real coordinates
+    double am = -1.0;
+    int aj = 0x7fffffff;
+    for (int j = threadIdx.x; j < D; j += blockDim.x) {
+        const double v = fabs(Vt[(int64_t)row * Dp + j]);
+        if (v > am || (v == am && j < aj)) {
+            am = v;
+            aj = j;
         }
-        const int row = s_idx[0];
-        const double lam = s_val[0];
-        __syncthreads();
-        // sign: first entry of largest magnitude among the D real coordinates
-        double am = -1.0;
-        int aj = 0x7fffffff;
-        for (int j = threadIdx.x; j < D; j += blockDim.x) {
-            const double v = fabs(Vt[(int64_t)row * Dp + j]);
-            if (v > am || (v == am && j < aj)) {
-                am = v;
-                aj = j;
+    }
+    s_val[threadIdx.x] = am;
+    s_idx[threadIdx.x] = aj;
+    __syncthreads();
+    for (int o = 128; o > 0; o >>= 1) {
+        if ((int)threadIdx.x < o) {
+            const double v = s_val[threadIdx.x + o];
+            const int j = s_idx[threadIdx.x + o];
+            if (v > s_val[threadIdx.x] || (v == s_val[threadIdx.x] && j < s_idx[threadIdx.x])) {
+                s_val[threadIdx.x] = v;
+                s_idx[threadIdx.x] = j;
             }
-        }
-        s_val[threadIdx.x] = am;
-        s_idx[threadIdx.x] = aj;
-        __syncthreads();
-        for (int o = 128; o > 0; o >>= 1) {
-            if ((int)threadIdx.x < o) {
-                const double v = s_val[threadIdx.x + o];
-                const int j = s_idx[threadIdx.x + o];
-                if (v > s_val[threadIdx.x] || (v == s_val[threadIdx.x] && j < s_idx[threadIdx.x])) {
-                    s_val[threadIdx.x] = v;
-                    s_idx[threadIdx.x] = j;
-                }
-            }
-            __syncthreads();
-        }
-        const double sgn = Vt[(int64_t)row * Dp + s_idx[0]] < 0.0 ? -1.0 : 1.0;
-        __syncthreads();
-        for (int j = threadIdx.x; j < D; j += blockDim.x) comps[(int64_t)c * D + j] = (float)(sgn * Vt[(int64_t)row * Dp + j]);
-        if (threadIdx.x == 0) {
-            if (evals) evals[c] = lam;
-            s_lam[row] = -1e301;  // taken
         }
         __syncthreads();
     }
+    const int jmax = s_idx[0] < D ? s_idx[0] : 0;
+    const double sgn = Vt[(int64_t)row * Dp + jmax] < 0.0 ? -1.0 : 1.0;
+    for (int j = threadIdx.x; j < D; j += blockDim.x) comps[(int64_t)c * D + j] = (float)(sgn * Vt[(int64_t)row * Dp + j]);
+    if (threadIdx.x == 0 && evals) evals[c] = s_lam[row];
 }
 
 // ---- projection: z[i][c] = sum_j (x[i][j] - mean[j]) comps[c][j] -----------------------------------
@@ -1038,11 +1031,17 @@ cat_status cat_pca_fit(const void* lq, int64_t N, int64_t D, int32_t p, cat_dtyp
     rpb = (rpb + kCovRows - 1) / kCovRows * kCovRows;
     const unsigned nrb = (unsigned)((N + rpb - 1) / rpb);
     {
-        dim3 g((unsigned)((D + 255) / 256), nrb), b(256);
+        // about 1024 workgroups: 256 or more row ranges (256 atomics per column at most)
+        const int64_t cblocks = (D + 255) / 256;
+        int64_t ranges = (1024 + cblocks - 1) / cblocks;
+        ranges = ranges < 256 ? 256 : ranges;
+        int64_t rps = (N + ranges - 1) / ranges;
+        rps = (rps + 7) & ~(int64_t)7;
+        dim3 g((unsigned)cblocks, (unsigned)((N + rps - 1) / rps)), b(256);
         if (dt == CAT_F32)
-            hipLaunchKernelGGL(k_pca_colsum<float>, g, b, 0, st, (const float*)lq, N, D, rpb, w.sum);
+            hipLaunchKernelGGL(k_pca_colsum<float>, g, b, 0, st, (const float*)lq, N, D, rps, w.sum);
         else
-            hipLaunchKernelGGL(k_pca_colsum<bf16_t>, g, b, 0, st, (const bf16_t*)lq, N, D, rpb, w.sum);
+            hipLaunchKernelGGL(k_pca_colsum<bf16_t>, g, b, 0, st, (const bf16_t*)lq, N, D, rps, w.sum);
         CAT_LAUNCH_CHECK("k_pca_colsum");
         hipLaunchKernelGGL(k_pca_mean, dim3((unsigned)((D + 255) / 256)), dim3(256), 0, st, w.sum, N, D, w.mean, mean);
         CAT_LAUNCH_CHECK("k_pca_mean");
@@ -1083,9 +1082,9 @@ cat_status cat_pca_fit(const void* lq, int64_t N, int64_t D, int32_t p, cat_dtyp
 #define CAT_JACOBI_CASES(KERNEL, GRID, ARG, FROM)                                                              \
         case FROM: hipLaunchKernelGGL(KERNEL<FROM>, GRID, jb, 0, st, w.W, w.Vt, (int32_t)Dp, ARG); break;
 #define CAT_STEP(NI_) CAT_JACOBI_CASES(k_pca_jacobi_step, gpair, -1, NI_)
-        // rows in registers: 4 BR NI doubles per thread with blocks of BR = 4 rows: 256 threads up to Dp = 1024,
-        // 512 beyond, so that NI stays at 4 or below
-        const bool wide = ni > 4;
+        // rows in registers: 4 BR NI doubles per thread with blocks of BR = 4 rows: 256 threads up to Dp = 512,
+        // 512 beyond (NI <= 4; twice the waves to issue the loads and stores of a launch: 3 % faster at Dp = 1000)
+        const bool wide = ni > 2;
         const int nb = wide ? (int)((Dp + 511) / 512) : ni;
         const dim3 jbb(wide ? 512 : 256);
         for (int sw = 0; sw < sweeps; sw++) {
@@ -1100,7 +1099,7 @@ cat_status cat_pca_fit(const void* lq, int64_t N, int64_t D, int32_t p, cat_dtyp
     else                                                                                                                    \
         hipLaunchKernelGGL((k_pca_jacobi_block<NI_, 4, T_>), goct, jbb, 0, st, w.W, w.Vt, (int32_t)Dp, round);
                 if (wide) {
-                    if (nb <= 3) { CAT_B(3, 512) } else { CAT_B(4, 512) }
+                    if (nb <= 2) { CAT_B(2, 512) } else if (nb == 3) { CAT_B(3, 512) } else { CAT_B(4, 512) }
                 } else if (nb == 1) { CAT_B(1, 256) } else if (nb == 2) { CAT_B(2, 256) } else if (nb == 3) { CAT_B(3, 256) } else { CAT_B(4, 256) }
 #undef CAT_B
                 CAT_LAUNCH_CHECK("k_pca_jacobi_block");
@@ -1111,7 +1110,7 @@ cat_status cat_pca_fit(const void* lq, int64_t N, int64_t D, int32_t p, cat_dtyp
     }
     hipLaunchKernelGGL(k_pca_rayleigh, dim3((unsigned)Dp), dim3(256), 0, st, w.W, w.Vt, (int32_t)Dp, w.lambda);
     CAT_LAUNCH_CHECK("k_pca_rayleigh");
-    hipLaunchKernelGGL(k_pca_select, dim3(1), dim3(256), 0, st, w.lambda, w.Vt, (int32_t)D, (int32_t)Dp, p, components, eigenvalues);
+    hipLaunchKernelGGL(k_pca_select, dim3((unsigned)p), dim3(256), 0, st, w.lambda, w.Vt, (int32_t)D, (int32_t)Dp, components, eigenvalues);
     CAT_LAUNCH_CHECK("k_pca_select");
     return CAT_OK;
 }
