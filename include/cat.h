@@ -129,7 +129,13 @@ cat_status cat_fit(const void *lq, const void *fp, int64_t N, int64_t D, int32_t
  *                 not take (D not a multiple of 4 (8 for bf16), K > 256, or the streaming path
  *                 selected) run every pass and report 0.
  * Other arguments, workspace and errors: as cat_fit.
+ *
+ * cat_allow_early_stop(on != 0) lets every Lloyd loop the library runs stop in the same way
+ * (cat_fit, each run of cat_fit_restarts, the clustering of the scores in cat_fit_pca), without
+ * the count of passes left out; their outputs do not change.  Process-wide, default off; returns
+ * CAT_OK.
  */
+cat_status cat_allow_early_stop(int on);
 cat_status cat_fit_early_stop(const void *lq, const void *fp, int64_t N, int64_t D, int32_t K,
                               int32_t iters, uint64_t seed, cat_dtype dt,
                               const float *init_centroids,

@@ -24,7 +24,7 @@ EXPORTS = ("cat_select_path", "cat_fit_workspace_bytes", "cat_apply_workspace_by
            "cat_apply_assigned", "cat_fit_pca_workspace_bytes", "cat_fit_pca", "cat_apply_pca_workspace_bytes", "cat_apply_pca",
            "cat_alpha_sweep_workspace_bytes", "cat_alpha_sweep", "cat_top1",
            "cat_init_kmeanspp_workspace_bytes", "cat_init_kmeanspp",
-           "cat_fit_restarts_workspace_bytes", "cat_fit_restarts", "cat_fit_early_stop")
+           "cat_fit_restarts_workspace_bytes", "cat_fit_restarts", "cat_fit_early_stop", "cat_allow_early_stop")
 
 
 class CatError(RuntimeError):
@@ -58,6 +58,8 @@ def load_library():
     lib.cat_fit.restype = c.c_int
     lib.cat_fit_early_stop.argtypes = [vp, vp, i64, i64, i32, i32, u64, c.c_int, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.cat_fit_early_stop.restype = c.c_int
+    lib.cat_allow_early_stop.argtypes = [c.c_int]
+    lib.cat_allow_early_stop.restype = c.c_int
     lib.cat_apply.argtypes = [vp, i64, i64, i32, c.c_int, vp, vp, vp, c.c_float, vp, vp, vp, sz, vp]
     lib.cat_apply.restype = c.c_int
     lib.cat_assign.argtypes = [vp, i64, i64, i32, c.c_int, vp, vp, vp, vp, vp, sz, vp]
@@ -143,6 +145,11 @@ def _stream():
 
 def select_path(path):
     _check(load_library().cat_select_path(int(path)))
+
+
+def allow_early_stop(on):
+    """Let every Lloyd loop of the library leave out the passes after the partition has stopped changing (same outputs)."""
+    _check(load_library().cat_allow_early_stop(1 if on else 0))
 
 
 def debug_list_capacity(entries):

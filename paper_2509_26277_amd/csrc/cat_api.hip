@@ -15,6 +15,7 @@ namespace cat {
 
 static thread_local char g_err[512] = "";
 static std::atomic<int> g_path{CAT_PATH_AUTO};
+static std::atomic<int> g_early_stop{0};  // cat_allow_early_stop
 
 cat_status set_error(cat_status st, const char* fmt, ...) {
     va_list ap;
@@ -218,6 +219,7 @@ static cat_status run_lloyd(const void* lq, cat_dtype dt, int64_t N, int64_t D, 
         CAT_TRY(launch_gather_rows(lq, dt, D, K, w.idx, c0, st));
     }
     if (fused) {
+        if (!skipped && g_early_stop.load()) skipped = w.lloyd.skipped;
         // one assignment launch per Lloyd iteration; only the rows that change cluster touch the sums
         CAT_TRY(tile_lloyd(lq, dt, N, D, K, iters, centroids, w.acc, assignments, w.counts, inertia, w.rep, skipped, w.tile, w.lloyd, st));
     } else {
@@ -269,6 +271,11 @@ cat_status cat_debug_list_capacity(int entries) {
     if (entries < 0 || entries > 1024)
         return set_error(CAT_ERR_INVALID_ARG, "cat_debug_list_capacity: %d is outside 0 .. 1024", entries);
     g_list_cap.store(entries == 0 ? 1024 : entries);
+    return CAT_OK;
+}
+
+cat_status cat_allow_early_stop(int on) {
+    g_early_stop.store(on != 0);
     return CAT_OK;
 }
 

@@ -30,7 +30,8 @@ cat_status tile_assign(const void* lq, cat_dtype dt, int64_t N, int64_t D, int32
 // all N), the counters of the update kernel and the per-slice shares of the centroid norms.
 struct LloydWs {
     unsigned long long* list = nullptr;  // N entries
-    uint32_t* ctrl = nullptr;            // [0..1] list length (two halves), then 2 x slices finished-workgroup counters
+    uint32_t* ctrl = nullptr;            // [0..1] list length (two halves), then 2 x slices finished-workgroup counters,
+    int32_t* skipped = nullptr;          //   then one word: passes left out, for callers that bring no word of their own
     double* norm_part = nullptr;         // slices x K
     int32_t* counts2 = nullptr;          // K: the second half of the counts double buffer
     uint32_t* sort_ws = nullptr;         // not carved here: the caller's scratch for launch_segsum_sorted

@@ -343,7 +343,7 @@ TileWs tile_carve(void* base, int64_t D, int32_t K, cat_dtype dt) {
 
 static inline int64_t delta_slices(int64_t D) { return (D + kDeltaSW - 1) / kDeltaSW; }
 
-static inline size_t lloyd_ctrl_words(int64_t D) { return (size_t)(2 + 2 * delta_slices(D)); }
+static inline size_t lloyd_ctrl_words(int64_t D) { return (size_t)(3 + 2 * delta_slices(D)); }
 
 size_t lloyd_workspace_bytes(int64_t N, int64_t D, int32_t K) {
     return a256((size_t)N * 8) + a256(lloyd_ctrl_words(D) * 4) + a256((size_t)delta_slices(D) * K * 8) +
@@ -358,6 +358,7 @@ LloydWs lloyd_carve(void* base, int64_t N, int64_t D, int32_t K) {
     b += a256((size_t)N * 8);
     w.ctrl = (uint32_t*)b;
     b += a256(lloyd_ctrl_words(D) * 4);
+    w.skipped = (int32_t*)(w.ctrl + lloyd_ctrl_words(D) - 1);
     w.norm_part = (double*)b;
     b += a256((size_t)delta_slices(D) * K * 8);
     w.counts2 = (int32_t*)b;
