@@ -66,6 +66,39 @@ def test_outputs_and_skipped_passes_match_the_oracle(seed, N, D, K, spread, dt, 
     assert 0 <= int(r["passes_skipped"].item()) <= max(0, iters - 3)
 
 
+def test_empty_clusters_and_duplicate_rows():
+    """rows drawn from three distinct vectors, K = 5: duplicate initial centroids leave clusters empty (they keep
+    their centroid, gamma = 1, beta = 0), the partition repeats at once"""
+    rng = np.random.default_rng(12)
+    base = rng.standard_normal((3, 64)).astype(np.float32)
+    x = base[rng.integers(0, 3, 2000)]
+    y = (0.9 * x + 0.1).astype(np.float32)
+    o = oracle.fit_early_stop(x, y, 5, 12, seed=4)
+    assert (o["counts"] == 0).any() and 1 <= o["stable_at"] <= 2
+    r = cat_fit(dev_matrix(x, "f32"), dev_matrix(y, "f32"), 5, 12, seed=4, early_stop=True)
+    assert (r["assignments"].cpu().numpy() == o["assignments"]).all()
+    assert r["counts"].cpu().numpy().tolist() == o["counts"].tolist()
+    assert int(r["passes_skipped"].item()) == _expected_skips(int(o["stable_at"]), 12) == 9
+    check_values(host_matrix(r["centroids"]), o["centroids"], RTOL["f32"], "centroids")
+    empty = o["counts"] == 0
+    assert (host_matrix(r["gamma"])[empty] == 1.0).all() and (host_matrix(r["beta"])[empty] == 0.0).all()
+    # every row coincides with its centroid: the objective is zero up to the rounding of the fp32 scores
+    np.testing.assert_allclose(r["inertia"].cpu().numpy(), o["inertia"], rtol=1e-4, atol=1e-5 * float((x.astype(np.float64) ** 2).sum()))
+
+
+def test_full_logit_workload_never_settles_and_matches_the_full_fit():
+    """all of cfg2 (65,536 x 1000, K = 16, 30 iterations): no pass repeats its predecessor, nothing is left out"""
+    w = workloads.make("cfg2")
+    o = oracle.fit_early_stop(w["lq"], w["fp"], w["K"], w["iters"], seed=w["seed"])
+    assert o["stable_at"] == -1
+    r = cat_fit(dev_matrix(w["lq"], "f32"), dev_matrix(w["fp"], "f32"), w["K"], w["iters"], seed=w["seed"], early_stop=True)
+    assert int(r["passes_skipped"].item()) == 0
+    _, d1, d2 = oracle.assign(w["lq"], o["centroids"], want_distances=True)
+    check_assignments(r["assignments"].cpu().numpy(), o["assignments"], d1, d2, "cfg2 early stop")
+    check_values(host_matrix(r["centroids"]), o["centroids"], RTOL["f32"], "centroids")
+    np.testing.assert_allclose(r["inertia"].cpu().numpy(), o["inertia"], rtol=1e-4)
+
+
 def test_the_cases_cover_both_outcomes():
     """guards the case table: at least one case stops early by a wide margin, one never settles (CPU only)"""
     stops = []
