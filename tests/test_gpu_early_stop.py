@@ -189,6 +189,22 @@ def test_captures_into_a_hip_graph_and_replays():
         for k in ("gamma", "beta"):
             torch.testing.assert_close(r[k], ref[k], rtol=1e-5, atol=1e-6)
         torch.testing.assert_close(r["inertia"], ref["inertia"], rtol=1e-12, atol=0)
+    # the same graph on other rows in the same buffers: one that settles a pass later, one that never does
+    for seed, spread, skips in ((7, 0.8, 26), (5, 1.0, 0)):
+        x2, y2 = _mixture(seed, 4096, 64, 4, spread, "f32")
+        assert _expected_skips(int(oracle.fit_early_stop(x2, y2, 4, 30, seed=0)["stable_at"]), 30) == skips
+        xd.copy_(torch.from_numpy(x2))
+        yd.copy_(torch.from_numpy(y2))
+        eager = {k: v.clone() for k, v in run().items()}
+        for t in r.values():
+            t.zero_()
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        assert int(r["passes_skipped"].item()) == skips
+        for k in ("assignments", "counts", "centroids", "passes_skipped"):
+            assert torch.equal(r[k], eager[k]), k
+        torch.testing.assert_close(r["inertia"], eager["inertia"], rtol=1e-12, atol=0)
 
 
 def test_process_wide_switch_leaves_the_other_fits_unchanged():
