@@ -159,6 +159,25 @@ cat_status cat_apply(const void *lq, int64_t N, int64_t D, int32_t K, cat_dtype 
                      float alpha, void *corrected, int32_t *assignments,
                      void *workspace, size_t workspace_bytes, void *hip_stream);
 
+/*
+ * cat_apply for callers that cannot allocate device memory or carry a workspace around: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, results
+ * and errors as cat_apply, without the workspace: the scratch memory (the alpha-folded gamma / beta,
+ * the centroids in matrix-core operand order and their norms) lives in a device array built into the
+ * library, CAT_APPLY_STATIC_SCRATCH_BYTES long, one copy per GPU, held until the process ends.  The
+ * call allocates and frees nothing.  A shape whose cat_apply_workspace_bytes() exceeds the array
+ * returns CAT_ERR_UNSUPPORTED (K * D up to about 500,000 fits; cat_apply_static_max_workspace_bytes()
+ * returns the limit).  Every call on a GPU uses that GPU's one array: calls that overlap in time on
+ * the same GPU (different streams or threads) race and give unspecified results; calls on one stream
+ * are ordered and safe.  The array keeps the last call's contents; nothing in it has to be cleared
+ * (every byte the inference pass reads is written earlier in the same call).
+ */
+#define CAT_APPLY_STATIC_SCRATCH_BYTES (8u << 20)
+size_t cat_apply_static_max_workspace_bytes(void);
+cat_status cat_apply_static(const void *lq, int64_t N, int64_t D, int32_t K, cat_dtype dt,
+                            const float *centroids, const float *gamma, const float *beta,
+                            float alpha, void *corrected, int32_t *assignments, void *hip_stream);
+
 /* ---- step-level entry points (the pieces cat_fit is made of) ------------- */
 
 /* Assignment step (the Cluster-Model "predict" of Algorithms 1 and 2).

@@ -9,6 +9,7 @@ from .binding import (  # noqa: F401
     CatError,
     cat_fit,
     cat_apply,
+    cat_apply_static,
     cat_assign,
     cat_update,
     cat_stats,

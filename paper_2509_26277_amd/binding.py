@@ -24,7 +24,8 @@ EXPORTS = ("cat_select_path", "cat_fit_workspace_bytes", "cat_apply_workspace_by
            "cat_apply_assigned", "cat_fit_pca_workspace_bytes", "cat_fit_pca", "cat_apply_pca_workspace_bytes", "cat_apply_pca",
            "cat_alpha_sweep_workspace_bytes", "cat_alpha_sweep", "cat_top1",
            "cat_init_kmeanspp_workspace_bytes", "cat_init_kmeanspp",
-           "cat_fit_restarts_workspace_bytes", "cat_fit_restarts", "cat_fit_early_stop", "cat_allow_early_stop")
+           "cat_fit_restarts_workspace_bytes", "cat_fit_restarts", "cat_fit_early_stop", "cat_allow_early_stop",
+           "cat_apply_static", "cat_apply_static_max_workspace_bytes")
 
 
 class CatError(RuntimeError):
@@ -62,6 +63,10 @@ def load_library():
     lib.cat_allow_early_stop.restype = c.c_int
     lib.cat_apply.argtypes = [vp, i64, i64, i32, c.c_int, vp, vp, vp, c.c_float, vp, vp, vp, sz, vp]
     lib.cat_apply.restype = c.c_int
+    lib.cat_apply_static.argtypes = [vp, i64, i64, i32, c.c_int, vp, vp, vp, c.c_float, vp, vp, vp]
+    lib.cat_apply_static.restype = c.c_int
+    lib.cat_apply_static_max_workspace_bytes.argtypes = []
+    lib.cat_apply_static_max_workspace_bytes.restype = sz
     lib.cat_assign.argtypes = [vp, i64, i64, i32, c.c_int, vp, vp, vp, vp, vp, sz, vp]
     lib.cat_assign.restype = c.c_int
     lib.cat_update.argtypes = [vp, vp, i64, i64, i32, c.c_int, vp, vp, vp, vp, sz, vp]
@@ -241,6 +246,23 @@ def cat_apply(lq, centroids, gamma, beta, alpha=1.0, want_assignments=True, out=
                          None if a is None else a.data_ptr(),
                          workspace.data_ptr(), workspace.numel(), _stream()))
     return out, a
+
+
+def cat_apply_static(lq, centroids, gamma, beta, alpha=1.0, out=None, assignments=None):
+    """cat_apply without a workspace (the library's built-in scratch array).  The library call allocates nothing;
+    pass ``out`` (and ``assignments``, or leave it None to skip them) to keep this wrapper from allocating too.
+    Returns (corrected, assignments or None)."""
+    lib = load_library()
+    N, D = lq.shape
+    K = centroids.shape[0]
+    dt = _dt(lq)
+    if out is None:
+        out = torch.empty_like(lq)
+    _check(lib.cat_apply_static(_dev(lq, name="lq"), N, D, K, dt, _dev(centroids, torch.float32, (K, D), "centroids"),
+                                _dev(gamma, torch.float32, (K, D), "gamma"), _dev(beta, torch.float32, (K, D), "beta"),
+                                float(alpha), _dev(out, lq.dtype, (N, D), "out"),
+                                _dev(assignments, torch.int32, (N,), "assignments"), _stream()))
+    return out, assignments
 
 
 def cat_assign(lq, centroids, workspace=None):

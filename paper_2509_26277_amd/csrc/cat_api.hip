@@ -498,20 +498,21 @@ cat_status cat_fit_restarts(const void* lq, const void* fp, int64_t N, int64_t D
     return CAT_OK;
 }
 
-cat_status cat_apply(const void* lq, int64_t N, int64_t D, int32_t K, cat_dtype dt, const float* centroids,
-                     const float* gamma, const float* beta, float alpha, void* corrected, int32_t* assignments,
-                     void* workspace, size_t workspace_bytes, void* hip_stream) {
-    CAT_TRY(check_shape("cat_apply", N, D, K, dt));
-    CAT_TRY(check_ptr("cat_apply", "lq", lq, 16));
-    CAT_TRY(check_ptr("cat_apply", "centroids", centroids, 16));
-    CAT_TRY(check_ptr("cat_apply", "gamma", gamma, 16));
-    CAT_TRY(check_ptr("cat_apply", "beta", beta, 16));
-    CAT_TRY(check_ptr("cat_apply", "corrected", corrected, 16));
-    if (corrected == lq) return set_error(CAT_ERR_INVALID_ARG, "cat_apply: corrected may not alias lq");
-    if (!std::isfinite(alpha)) return set_error(CAT_ERR_INVALID_ARG, "cat_apply: alpha is not finite");
+// Argument checks and launches of CAT Inferencing over a scratch buffer of `workspace_bytes` bytes at `workspace`
+// (the caller's for cat_apply, the library's own for cat_apply_static).
+static cat_status apply_impl(const char* who, const void* lq, int64_t N, int64_t D, int32_t K, cat_dtype dt,
+                             const float* centroids, const float* gamma, const float* beta, float alpha, void* corrected,
+                             int32_t* assignments, void* workspace, size_t workspace_bytes, hipStream_t st) {
+    CAT_TRY(check_shape(who, N, D, K, dt));
+    CAT_TRY(check_ptr(who, "lq", lq, 16));
+    CAT_TRY(check_ptr(who, "centroids", centroids, 16));
+    CAT_TRY(check_ptr(who, "gamma", gamma, 16));
+    CAT_TRY(check_ptr(who, "beta", beta, 16));
+    CAT_TRY(check_ptr(who, "corrected", corrected, 16));
+    if (corrected == lq) return set_error(CAT_ERR_INVALID_ARG, "%s: corrected may not alias lq", who);
+    if (!std::isfinite(alpha)) return set_error(CAT_ERR_INVALID_ARG, "%s: alpha is not finite", who);
     ApplyWs w = carve_apply(workspace, D, K, dt);
-    CAT_TRY(check_ws("cat_apply", workspace, workspace_bytes, w.bytes));
-    hipStream_t st = (hipStream_t)hip_stream;
+    CAT_TRY(check_ws(who, workspace, workspace_bytes, w.bytes));
     const float* g = gamma;
     const float* b = beta;
     if (alpha != 1.0f) {
@@ -529,6 +530,57 @@ cat_status cat_apply(const void* lq, int64_t N, int64_t D, int32_t K, cat_dtype 
                            st);
     return launch_assign_stream(lq, dt, N, D, K, centroids, assignments, nullptr, nullptr, nullptr, g, b, corrected,
                                 st);
+}
+
+cat_status cat_apply(const void* lq, int64_t N, int64_t D, int32_t K, cat_dtype dt, const float* centroids,
+                     const float* gamma, const float* beta, float alpha, void* corrected, int32_t* assignments,
+                     void* workspace, size_t workspace_bytes, void* hip_stream) {
+    return apply_impl("cat_apply", lq, N, D, K, dt, centroids, gamma, beta, alpha, corrected, assignments, workspace,
+                      workspace_bytes, (hipStream_t)hip_stream);
+}
+
+// ---- cat_apply for callers that cannot allocate: the scratch memory is a device array of the library ----
+// One copy of the array exists on every GPU the library runs on, at an address of its own, and stays there until the
+// process ends.  The name of the array is a host-side stand-in, not a device address: host code only ever uses the
+// per-device address that hipGetSymbolAddress returns (asked once per device, with that device current).
+static __device__ __align__(256) unsigned char scratch[CAT_APPLY_STATIC_SCRATCH_BYTES];
+
+constexpr int kMaxDevices = 64;
+static std::atomic<void*> g_scratch_ptr[kMaxDevices];
+
+static cat_status static_scratch(void** out) {
+    int dev = 0;
+    CAT_HIP_TRY(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) return set_error(CAT_ERR_DEVICE, "cat_apply_static: device ordinal %d out of range", dev);
+    void* ptr = g_scratch_ptr[dev].load(std::memory_order_acquire);
+    if (!ptr) {
+        // two threads racing here ask twice and store the same address
+        CAT_HIP_TRY(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));
+        if (!ptr) return set_error(CAT_ERR_DEVICE, "cat_apply_static: the scratch array has no address on device %d", dev);
+        g_scratch_ptr[dev].store(ptr, std::memory_order_release);
+    }
+    *out = ptr;
+    return CAT_OK;
+}
+
+size_t cat_apply_static_max_workspace_bytes(void) { return CAT_APPLY_STATIC_SCRATCH_BYTES; }
+
+cat_status cat_apply_static(const void* lq, int64_t N, int64_t D, int32_t K, cat_dtype dt, const float* centroids,
+                            const float* gamma, const float* beta, float alpha, void* corrected, int32_t* assignments,
+                            void* hip_stream) {
+    CAT_TRY(check_shape("cat_apply_static", N, D, K, dt));
+    const size_t need = carve_apply(nullptr, D, K, dt).bytes;
+    if (need > (size_t)CAT_APPLY_STATIC_SCRATCH_BYTES)
+        return set_error(CAT_ERR_UNSUPPORTED,
+                         "cat_apply_static: D=%lld K=%d needs %zu bytes of scratch, the built-in array holds %zu; use "
+                         "cat_apply with a workspace",
+                         (long long)D, (int)K, need, (size_t)CAT_APPLY_STATIC_SCRATCH_BYTES);
+    void* ptr = nullptr;
+    CAT_TRY(static_scratch(&ptr));
+    // nothing in the scratch has to start at zero: the fold of alpha and the centroid preparation overwrite every
+    // byte the inference pass reads
+    return apply_impl("cat_apply_static", lq, N, D, K, dt, centroids, gamma, beta, alpha, corrected, assignments, ptr,
+                      (size_t)CAT_APPLY_STATIC_SCRATCH_BYTES, (hipStream_t)hip_stream);
 }
 
 
