@@ -9,7 +9,7 @@ import torch
 import oracle
 from paper_2509_26277_amd import binding, cat_fit, workloads
 
-from parity_util import RTOL, beta_scale, check_assignments, check_values, dev_matrix, host_matrix
+from parity_util import RTOL, check_assignments, check_values, dev_matrix, host_matrix
 
 pytestmark = pytest.mark.gpu
 
@@ -59,7 +59,7 @@ def test_outputs_and_skipped_passes_match_the_oracle(seed, N, D, K, spread, dt, 
     assert r["counts"].cpu().numpy().tolist() == np.bincount(a_g, minlength=K).tolist()
     check_values(host_matrix(r["centroids"]), o["centroids"], RTOL[dt], "centroids")
     check_values(host_matrix(r["gamma"]), o["gamma"], RTOL[dt], "gamma")
-    check_values(host_matrix(r["beta"]), o["beta"], RTOL[dt], "beta", beta_scale(x, y, o["assignments"], K, o["gamma"]))
+    check_values(host_matrix(r["beta"]), o["beta"], RTOL[dt], "beta")
     np.testing.assert_allclose(r["inertia"].cpu().numpy(), o["inertia"], rtol=1e-4)
     if moved == 0:  # the two sides saw the same partitions: the same passes repeat
         assert int(r["passes_skipped"].item()) == _expected_skips(int(o["stable_at"]), iters), o["stable_at"]

@@ -1,13 +1,12 @@
 """Parity at the full sizes of the five workloads, in the launch configuration bench.py times.
 
-cfg1 and cfg2 are compared with the oracle element by element, end to end.  For
-cfg3 / cfg4 / cfg5 the oracle cannot run the whole fit in seconds, so it is
-called on what it can compute one by one -- sampled rows for assignments and
-corrected outputs, sampled channels (over ALL rows) for centroid sums and the
-affine parameters -- plus properties that hold at any size: counts add up to N,
-the objective never increases, inference reproduces the fitted partition, and
-the centroids of a T-iteration fit are the means of the partition a (T-1)-
-iteration fit returns.
+cfg1, cfg2 and cfg3: the whole fit against the whole oracle, every output, element by element.
+cfg4: the oracle walks the fit pass by pass (its own assignment of ALL rows against its own double-precision
+centroids at every pass, compared with the partition the library holds after that many iterations under the
+top-2-gap rule; where an exempt near-tie is decided differently the oracle continues from the library's
+partition, which is the step at which a difference may arise), then every output.
+cfg5: the oracle's inference on ALL rows, in row chunks.
+The sampled checks of cfg3 / cfg4 / cfg5 stay as they were (they also cover a Lloyd run at cfg5's row count).
 """
 import numpy as np
 import pytest
@@ -16,32 +15,97 @@ import torch
 import oracle
 from paper_2509_26277_amd import cat_apply, cat_fit, workloads
 
-from parity_util import (RTOL, beta_scale, check_assignments, check_values, dev_matrix, f32_round, host_matrix)
+from parity_util import (CENTROID_RTOL, RTOL, check_assignments, check_assignments_lazy, check_values, dev_matrix,
+                         host_matrix)
 
 pytestmark = pytest.mark.gpu
 
 
-@pytest.mark.parametrize("name", ["cfg1", "cfg2"])
+def _check_inference_on_the_fitting_rows(w, lq, r, name):
+    """cat_apply with the fitted parameters against the oracle's inference on the same parameters, all rows."""
+    dt = w["dtype"]
+    cent = host_matrix(r["centroids"])
+    out, a2 = cat_apply(lq, r["centroids"], r["gamma"], r["beta"])
+    o_out, o_a2 = oracle.apply(w["lq"], cent, host_matrix(r["gamma"]), host_matrix(r["beta"]))
+    a2 = a2.cpu().numpy()
+    check_assignments_lazy(a2, o_a2, w["lq"], cent, f"{name} inference, assignments")
+    same = a2 == o_a2  # an exempt row takes another cluster's parameters: compared where the clusters agree
+    check_values(host_matrix(out)[same], o_out[same], RTOL[dt], f"{name} corrected")
+    return a2
+
+
+@pytest.mark.parametrize("name", ["cfg1", "cfg2", "cfg3"])
 def test_full_fit_against_the_whole_oracle(name):
     w = workloads.make(name)
     K, dt, iters = w["K"], w["dtype"], w["iters"]
     lq, fp = dev_matrix(w["lq"], dt), dev_matrix(w["fp"], dt)
     r = cat_fit(lq, fp, K, iters, seed=w["seed"])
     o = oracle.fit(w["lq"], w["fp"], K, iters, seed=w["seed"])
-    _, d1, d2 = oracle.assign(w["lq"], o["centroids"], want_distances=True)
     a_g = r["assignments"].cpu().numpy()
-    check_assignments(a_g, o["assignments"], d1, d2, f"{name} fit")
+    exempt = check_assignments_lazy(a_g, o["assignments"], w["lq"], o["centroids"], f"{name} fit")
     assert r["counts"].cpu().numpy().tolist() == np.bincount(a_g, minlength=K).tolist()
-    check_values(host_matrix(r["centroids"]), o["centroids"], RTOL[dt], f"{name} centroids")
+    # same partition history on both sides: the centroids are the same means, rounded once to fp32
+    check_values(host_matrix(r["centroids"]), o["centroids"], CENTROID_RTOL if exempt == 0 else RTOL[dt], f"{name} centroids")
     check_values(host_matrix(r["gamma"]), o["gamma"], RTOL[dt], f"{name} gamma")
-    check_values(host_matrix(r["beta"]), o["beta"], RTOL[dt], f"{name} beta",
-                 beta_scale(w["lq"], w["fp"], o["assignments"], K, o["gamma"]))
+    check_values(host_matrix(r["beta"]), o["beta"], RTOL[dt], f"{name} beta")
     np.testing.assert_allclose(r["inertia"].cpu().numpy(), o["inertia"], rtol=1e-4)
-    out, a2 = cat_apply(lq, r["centroids"], r["gamma"], r["beta"])
-    o_out, o_a2 = oracle.apply(w["lq"], host_matrix(r["centroids"]), host_matrix(r["gamma"]), host_matrix(r["beta"]))
-    ok = a2.cpu().numpy() == o_a2
-    assert ok.mean() > 0.9999
-    check_values(host_matrix(out)[ok], o_out[ok], RTOL[dt], f"{name} corrected")
+    a2 = _check_inference_on_the_fitting_rows(w, lq, r, name)
+    diff = np.flatnonzero(a2 != a_g)  # inference reproduces the fitted partition (up to exempt near-ties)
+    if diff.size:
+        _, e1, e2 = oracle.assign(w["lq"][diff], host_matrix(r["centroids"]), want_distances=True)
+        assert ((e2 - e1) < 1e-5 * e2).all()
+
+
+def test_full_fit_pass_by_pass_cfg4():
+    """The bf16 workload with 64 skewed clusters, all rows, every pass.  The library rounds its centroids to fp32
+    between passes and the oracle keeps doubles, so over 5 million row-passes a row whose two nearest centroids are
+    equidistant to within ~1e-8 can go either way; from there the two trajectories would drift apart.  The oracle
+    therefore assigns all rows itself at every pass, the difference must be exempt by the top-2-gap rule, and it
+    then averages the library's partition: every later pass is again compared exactly."""
+    w = workloads.make("cfg4")
+    N, K, dt, iters = w["N"], w["K"], w["dtype"], w["iters"]
+    lq, fp = dev_matrix(w["lq"], dt), dev_matrix(w["fp"], dt)
+    cent = w["lq"][oracle.init_indices(N, K, w["seed"])].astype(np.float64)
+    exempt_total = 0
+    J = np.empty(iters + 1)
+    for t in range(iters + 1):
+        r = cat_fit(lq, fp, K, t, seed=w["seed"])
+        a_g = r["assignments"].cpu().numpy()
+        # the library's centroids after t iterations: the means of the partition it held at pass t - 1
+        check_values(host_matrix(r["centroids"]), cent, CENTROID_RTOL, f"cfg4 centroids after {t} iterations")
+        a_o, d1, d2 = oracle.assign(w["lq"], cent, want_distances=True)
+        exempt_total += check_assignments(a_g, a_o, d1, d2, f"cfg4 pass {t}")
+        J[t] = d1.sum()
+        assert r["counts"].cpu().numpy().tolist() == np.bincount(a_g, minlength=K).tolist()
+        if t < iters:
+            cent, _ = oracle.update(w["lq"], a_g, cent)
+    assert exempt_total <= 4, exempt_total  # a handful in 5.5 million row-passes, not a systematic difference
+    assert (np.diff(J) <= 0).all()
+    np.testing.assert_allclose(r["inertia"].cpu().numpy(), J, rtol=1e-4)
+    g_o, b_o, n_o = oracle.affine(w["lq"], w["fp"], a_g, K)
+    assert n_o.tolist() == r["counts"].cpu().numpy().tolist()
+    check_values(host_matrix(r["gamma"]), g_o, RTOL[dt], "cfg4 gamma")
+    check_values(host_matrix(r["beta"]), b_o, RTOL[dt], "cfg4 beta")
+    _check_inference_on_the_fitting_rows(w, lq, r, "cfg4")
+
+
+def test_full_inference_all_rows_cfg5():
+    """cat_apply on all 4,194,304 rows against the oracle's inference, 262,144 rows at a time."""
+    w = workloads.make("cfg5")
+    N = w["N"]
+    lq = torch.from_numpy(w["lq"]).cuda()
+    args = [torch.from_numpy(w[k]).cuda() for k in ("centroids", "gamma", "beta")]
+    out, a = cat_apply(lq, *args)
+    a = a.cpu().numpy()
+    cent64 = w["centroids"].astype(np.float64)
+    step = 1 << 18
+    for r0 in range(0, N, step):
+        rows = slice(r0, min(N, r0 + step))
+        o_out, o_a = oracle.apply(w["lq"][rows], w["centroids"], w["gamma"], w["beta"])
+        check_assignments_lazy(a[rows], o_a, w["lq"][rows], cent64, f"cfg5 assignments, rows from {r0}")
+        same = a[rows] == o_a
+        check_values(host_matrix(out[rows])[same], o_out[same], RTOL["f32"], f"cfg5 corrected, rows from {r0}")
+    assert (a == w["labels"]).mean() > 0.99999  # planted labels (a property of the data, not the parity bar)
 
 
 @pytest.mark.parametrize("name", ["cfg3", "cfg4"])
@@ -70,7 +134,7 @@ def test_full_fit_sampled(name):
     g_o, b_o, n_o = oracle.affine(lq_c, fp_c, a_g, K)
     assert n_o.tolist() == counts.tolist()
     check_values(host_matrix(r["gamma"])[:, cols], g_o, RTOL[dt], f"{name} gamma")
-    check_values(host_matrix(r["beta"])[:, cols], b_o, RTOL[dt], f"{name} beta", beta_scale(lq_c, fp_c, a_g, K, g_o))
+    check_values(host_matrix(r["beta"])[:, cols], b_o, RTOL[dt], f"{name} beta")
     # Lloyd at full size: the centroids after `iters` iterations are the means of the partition
     # returned by a fit with one iteration less (its final assignment is pass `iters - 1`)
     r1 = cat_fit(lq, fp, K, iters - 1, seed=w["seed"], want_inertia=False)
@@ -179,5 +243,4 @@ def test_full_pca_front_end_on_the_logit_workload():
     g_o, b_o, n_o = oracle.affine(np.ascontiguousarray(w["lq"][:, cols]), np.ascontiguousarray(w["fp"][:, cols]), a_g, K)
     assert r["counts"].cpu().numpy().tolist() == n_o.tolist()
     check_values(g[:, cols], g_o, RTOL["f32"], "gamma")
-    check_values(b[:, cols], b_o, RTOL["f32"], "beta",
-                 beta_scale(w["lq"][:, cols], w["fp"][:, cols], a_g, K, g_o))
+    check_values(b[:, cols], b_o, RTOL["f32"], "beta")

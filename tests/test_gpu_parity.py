@@ -14,7 +14,7 @@ import oracle
 from paper_2509_26277_amd import binding, workloads
 from paper_2509_26277_amd import cat_apply, cat_assign, cat_fit, cat_stats, cat_update
 
-from parity_util import (RTOL, beta_scale, check_assignments, check_values, dev_matrix, f32_round, host_matrix)
+from parity_util import (CENTROID_RTOL, RTOL, check_assignments, check_values, dev_matrix, f32_round, host_matrix)
 
 pytestmark = pytest.mark.gpu
 
@@ -83,13 +83,13 @@ def test_update_and_stats_steps(name, n, path):
     c_o, n_o = oracle.update(w["lq"], a, prev)
     c_g, n_g = cat_update(lq, a_dev, torch.from_numpy(prev.astype(np.float32)).cuda())
     assert n_g.cpu().numpy().tolist() == n_o.tolist()
-    check_values(host_matrix(c_g), c_o, RTOL[dt], f"{name} update")
+    check_values(host_matrix(c_g), c_o, CENTROID_RTOL, f"{name} update")
     g_o, b_o, _ = oracle.affine(w["lq"], w["fp"], a, K)
     for hint in (None, c_g):
         g_g, b_g, n2 = cat_stats(lq, fp, a_dev, K, centroids=hint)
         assert n2.cpu().numpy().tolist() == n_o.tolist()
         check_values(host_matrix(g_g), g_o, RTOL[dt], f"{name} gamma")
-        check_values(host_matrix(b_g), b_o, RTOL[dt], f"{name} beta", beta_scale(w["lq"], w["fp"], a, K, g_o))
+        check_values(host_matrix(b_g), b_o, RTOL[dt], f"{name} beta")
 
 
 # ---------------------------------------------------------------------------
@@ -106,12 +106,11 @@ def test_fit_end_to_end(name, n, path):
     o = oracle.fit(w["lq"], w["fp"], K, iters, seed=w["seed"])
     _, d1, d2 = oracle.assign(w["lq"], o["centroids"], want_distances=True)
     a_g = r["assignments"].cpu().numpy()
-    check_assignments(a_g, o["assignments"], d1, d2, f"{name} fit")
+    exempt = check_assignments(a_g, o["assignments"], d1, d2, f"{name} fit")
     assert r["counts"].cpu().numpy().tolist() == np.bincount(a_g, minlength=K).tolist()
-    check_values(host_matrix(r["centroids"]), o["centroids"], RTOL[dt], f"{name} centroids")
+    check_values(host_matrix(r["centroids"]), o["centroids"], RTOL[dt] if exempt else CENTROID_RTOL, f"{name} centroids")
     check_values(host_matrix(r["gamma"]), o["gamma"], RTOL[dt], f"{name} gamma")
-    check_values(host_matrix(r["beta"]), o["beta"], RTOL[dt], f"{name} beta",
-                 beta_scale(w["lq"], w["fp"], o["assignments"], K, o["gamma"]))
+    check_values(host_matrix(r["beta"]), o["beta"], RTOL[dt], f"{name} beta")
     np.testing.assert_allclose(r["inertia"].cpu().numpy(), o["inertia"], rtol=1e-4)
     # fit <-> apply: inference on the fitting rows reproduces the partition
     out, a2 = cat_apply(lq, r["centroids"], r["gamma"], r["beta"])
@@ -136,9 +135,9 @@ def test_fit_with_short_changed_row_lists(name, n, cap):
     o = oracle.fit(w["lq"], w["fp"], K, iters, seed=w["seed"])
     _, d1, d2 = oracle.assign(w["lq"], o["centroids"], want_distances=True)
     a_g = r["assignments"].cpu().numpy()
-    check_assignments(a_g, o["assignments"], d1, d2, f"{name} fit")
+    exempt = check_assignments(a_g, o["assignments"], d1, d2, f"{name} fit")
     assert r["counts"].cpu().numpy().tolist() == np.bincount(a_g, minlength=K).tolist()
-    check_values(host_matrix(r["centroids"]), o["centroids"], RTOL[dt], f"{name} centroids")
+    check_values(host_matrix(r["centroids"]), o["centroids"], RTOL[dt] if exempt else CENTROID_RTOL, f"{name} centroids")
     check_values(host_matrix(r["gamma"]), o["gamma"], RTOL[dt], f"{name} gamma")
     np.testing.assert_allclose(r["inertia"].cpu().numpy(), o["inertia"], rtol=1e-4)
 
@@ -173,11 +172,11 @@ def test_update_and_stats_skip_rows_with_labels_outside_the_range(dt, path):
     lq_d, fp_d, a_d = dev_matrix(lq, dt), dev_matrix(fp, dt), torch.from_numpy(a).cuda()
     c_g, n_g = cat_update(lq_d, a_d, torch.from_numpy(prev).cuda())
     assert n_g.cpu().numpy().tolist() == n_o.tolist()
-    check_values(host_matrix(c_g), c_o, RTOL[dt], "update")
+    check_values(host_matrix(c_g), c_o, CENTROID_RTOL, "update")
     g_g, b_g, n2 = cat_stats(lq_d, fp_d, a_d, K)
     assert n2.cpu().numpy().tolist() == n_o.tolist()
     check_values(host_matrix(g_g), g_o, RTOL[dt], "gamma")
-    check_values(host_matrix(b_g), b_o, RTOL[dt], "beta", beta_scale(lq[keep], fp[keep], a[keep], K, g_o))
+    check_values(host_matrix(b_g), b_o, RTOL[dt], "beta")
 
 
 @pytest.mark.parametrize("path", PATHS)
@@ -254,7 +253,7 @@ def test_empty_cluster_constant_channel_single_row(path):
     assert (g[2] == 1.0).all() and (b[2] == 0.0).all() and (c[2] == -300.0).all()
     assert (g[3] == 0.0).all() and (b[3] == fp_h[499].astype(np.float64)).all()
     check_values(g, o["gamma"], 1e-4, "gamma")
-    check_values(b, o["beta"], 1e-4, "beta", beta_scale(lq_h, fp_h, o["assignments"], 4, o["gamma"]))
+    check_values(b, o["beta"], 1e-4, "beta")
     assert np.abs(g[:2, 3]).max() < 1e-4  # constant channel: gamma 0, beta = mean FP
     check_values(c, o["centroids"], 1e-4, "centroids")
 
@@ -278,11 +277,12 @@ def test_degenerate_shapes(N, D, K, path):
     check_assignments(r["assignments"].cpu().numpy(), o["assignments"], d1, d2, "degenerate")
     check_values(host_matrix(r["centroids"]), o["centroids"], 1e-4, "centroids")
     check_values(host_matrix(r["gamma"]), o["gamma"], 1e-4, "gamma")
-    check_values(host_matrix(r["beta"]), o["beta"], 1e-4, "beta", beta_scale(lq, fp, o["assignments"], K, o["gamma"]))
+    check_values(host_matrix(r["beta"]), o["beta"], 1e-4, "beta")
     out, a = cat_apply(torch.from_numpy(lq).cuda(), r["centroids"], r["gamma"], r["beta"], alpha=0.7)
     o_out, o_a = oracle.apply(lq, host_matrix(r["centroids"]), host_matrix(r["gamma"]), host_matrix(r["beta"]), 0.7)
+    _, e1, e2 = oracle.assign(lq, host_matrix(r["centroids"]), want_distances=True)
+    check_assignments(a.cpu().numpy(), o_a, e1, e2, "degenerate, inference")
     ok = a.cpu().numpy() == o_a
-    assert ok.mean() > 0.99
     check_values(host_matrix(out)[ok], o_out[ok], 1e-4, "corrected")
 
 

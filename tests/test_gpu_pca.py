@@ -13,7 +13,7 @@ import oracle
 from paper_2509_26277_amd import binding, workloads
 from paper_2509_26277_amd import (cat_apply_assigned, cat_assign, cat_fit, cat_pca_fit, cat_pca_project, cat_stats)
 
-from parity_util import RTOL, beta_scale, check_assignments, check_values, dev_matrix, host_matrix
+from parity_util import RTOL, check_assignments, check_values, dev_matrix, host_matrix
 
 pytestmark = pytest.mark.gpu
 
@@ -115,7 +115,7 @@ def test_pipeline_with_pca_front_end(name, n, p):
     g_o, b_o, n_o = oracle.affine(w["lq"], w["fp"], a_g, K)
     assert n_g.cpu().numpy().tolist() == n_o.tolist()
     check_values(host_matrix(g_g), g_o, RTOL[dt], "gamma")
-    check_values(host_matrix(b_g), b_o, RTOL[dt], "beta", beta_scale(w["lq"], w["fp"], a_g, K, g_o))
+    check_values(host_matrix(b_g), b_o, RTOL[dt], "beta")
     # inference on the same rows reproduces the partition and applies the correction
     a2, _, _ = cat_assign(cat_pca_project(lq, mean_g, comps_g), r["centroids"])
     same = a2.cpu().numpy() == a_g
@@ -175,7 +175,7 @@ def test_single_call_pipeline_equals_its_steps_and_the_oracle(name, n, p):
     g_o, b_o, n_o = oracle.affine(w["lq"], w["fp"], a_g, K)
     assert r["counts"].cpu().numpy().tolist() == n_o.tolist()
     check_values(host_matrix(r["gamma"]), g_o, RTOL[dt], "gamma")
-    check_values(host_matrix(r["beta"]), b_o, RTOL[dt], "beta", beta_scale(w["lq"], w["fp"], a_g, K, g_o))
+    check_values(host_matrix(r["beta"]), b_o, RTOL[dt], "beta")
     # inference
     for alpha in (1.0, 0.4):
         out, a2 = cat_apply_pca(lq, r["mean"], r["components"], r["centroids_z"], r["gamma"], r["beta"], alpha=alpha)

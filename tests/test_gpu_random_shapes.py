@@ -13,7 +13,7 @@ import oracle
 from paper_2509_26277_amd import binding, workloads
 from paper_2509_26277_amd import cat_apply, cat_fit
 
-from parity_util import RTOL, beta_scale, check_assignments, check_values, dev_matrix, host_matrix
+from parity_util import CENTROID_RTOL, RTOL, check_assignments, check_values, dev_matrix, host_matrix
 
 pytestmark = pytest.mark.gpu
 
@@ -60,11 +60,11 @@ def test_random_shape(case, dt, path, N, D, K, iters):
     _, d1, d2 = oracle.assign(lq, o["centroids"], want_distances=True)
     a_g = r["assignments"].cpu().numpy()
     what = f"case {case} {dt} N={N} D={D} K={K} iters={iters}"
-    check_assignments(a_g, o["assignments"], d1, d2, what)
+    exempt = check_assignments(a_g, o["assignments"], d1, d2, what)
     assert r["counts"].cpu().numpy().tolist() == np.bincount(a_g, minlength=K).tolist()
-    check_values(host_matrix(r["centroids"]), o["centroids"], RTOL[dt], what + " centroids")
+    check_values(host_matrix(r["centroids"]), o["centroids"], RTOL[dt] if exempt else CENTROID_RTOL, what + " centroids")
     check_values(host_matrix(r["gamma"]), o["gamma"], RTOL[dt], what + " gamma")
-    check_values(host_matrix(r["beta"]), o["beta"], RTOL[dt], what + " beta", beta_scale(lq, fp, o["assignments"], K, o["gamma"]))
+    check_values(host_matrix(r["beta"]), o["beta"], RTOL[dt], what + " beta")
     alpha = 0.25 * (case % 5)
     out, a2 = cat_apply(dev_matrix(lq, dt), r["centroids"], r["gamma"], r["beta"], alpha=alpha)
     o_out, o_a = oracle.apply(lq, host_matrix(r["centroids"]), host_matrix(r["gamma"]), host_matrix(r["beta"]), alpha)

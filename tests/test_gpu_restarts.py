@@ -13,7 +13,7 @@ import oracle
 from paper_2509_26277_amd import cat_fit, cat_fit_restarts, cat_init_kmeanspp, workloads
 from paper_2509_26277_amd.binding import CAT_SEED_KMEANSPP, CAT_SEED_ROWS, CatError
 
-from parity_util import RTOL, beta_scale, check_values, dev_matrix, host_matrix
+from parity_util import RTOL, check_values, dev_matrix, host_matrix
 
 pytestmark = pytest.mark.gpu
 
@@ -62,7 +62,7 @@ def test_best_run_matches_the_oracle(N, D, K, iters, restarts, dt, seeding):
     assert (r["counts"].cpu().numpy() == ob["counts"]).all()
     check_values(host_matrix(r["centroids"]), ob["centroids"], RTOL[dt], "centroids")
     check_values(host_matrix(r["gamma"]), ob["gamma"], RTOL[dt], "gamma")
-    check_values(host_matrix(r["beta"]), ob["beta"], RTOL[dt], "beta", scale=beta_scale(x, y, ob["assignments"], K, ob["gamma"]))
+    check_values(host_matrix(r["beta"]), ob["beta"], RTOL[dt], "beta")
 
 
 def test_one_run_is_cat_fit():
