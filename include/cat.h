@@ -381,6 +381,15 @@ int cat_profile_read(float *ms_out, int cap);
  */
 cat_status cat_debug_list_capacity(int entries);
 
+/*
+ * Test hook.  cat_apply (and cat_apply_static) on the fused path has two kernels: one that keeps a tile of rows
+ * on the chip between the ranking and the affine map (used whenever it has an instance for the shape), and the
+ * tile kernel shared with cat_assign.  0 = automatic (default), 1 = never the row-tile kernel, 2 = only the
+ * row-tile kernel (CAT_ERR_UNSUPPORTED on a shape it has no instance for).  Results never depend on it beyond
+ * rounding-equivalent ties.  Process-wide.  CAT_ERR_INVALID_ARG for other values.
+ */
+cat_status cat_debug_apply_kernel(int which);
+
 /* Message of the last non-OK status on the calling thread ("" if none).  The
  * pointer stays valid until the next failing call on the same thread. */
 const char *cat_last_error(void);

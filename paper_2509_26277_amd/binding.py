@@ -25,7 +25,7 @@ EXPORTS = ("cat_select_path", "cat_fit_workspace_bytes", "cat_apply_workspace_by
            "cat_alpha_sweep_workspace_bytes", "cat_alpha_sweep", "cat_top1",
            "cat_init_kmeanspp_workspace_bytes", "cat_init_kmeanspp",
            "cat_fit_restarts_workspace_bytes", "cat_fit_restarts", "cat_fit_early_stop", "cat_allow_early_stop",
-           "cat_apply_static", "cat_apply_static_max_workspace_bytes")
+           "cat_apply_static", "cat_apply_static_max_workspace_bytes", "cat_debug_apply_kernel")
 
 
 class CatError(RuntimeError):
@@ -111,6 +111,8 @@ def load_library():
     lib.cat_fit_restarts.argtypes = [vp, vp, i64, i64, i32, i32, u64, i32, c.c_int, c.c_int, vp, vp, vp, vp, vp, vp, vp, vp,
                                      vp, sz, vp]
     lib.cat_fit_restarts.restype = c.c_int
+    lib.cat_debug_apply_kernel.argtypes = [c.c_int]
+    lib.cat_debug_apply_kernel.restype = c.c_int
     lib.cat_debug_list_capacity.argtypes = [c.c_int]
     lib.cat_debug_list_capacity.restype = c.c_int
     lib.cat_last_error.argtypes = []
@@ -160,6 +162,11 @@ def allow_early_stop(on):
 def debug_list_capacity(entries):
     """Test hook: capacity of the per-workgroup changed-row list of the fused Lloyd loop (0 = default)."""
     _check(load_library().cat_debug_list_capacity(int(entries)))
+
+
+def debug_apply_kernel(which):
+    """Test hook: 0 automatic, 1 never the row-tile inference kernel, 2 only the row-tile inference kernel."""
+    _check(load_library().cat_debug_apply_kernel(int(which)))
 
 
 def profile_enable(on):

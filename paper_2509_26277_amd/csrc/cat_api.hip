@@ -9,6 +9,7 @@
 #include <vector>
 
 #include "cat_common.h"
+#include "cat_infer.h"
 #include "cat_tile.h"
 
 namespace cat {
@@ -32,6 +33,7 @@ static size_t g_prof_used = 0;             // events recorded since the last ena
 
 bool profile_on() { return g_prof; }
 bool fast_paths_forced() { return g_path.load() == CAT_PATH_TILE; }
+static std::atomic<int> g_apply_kernel{0};  // cat_debug_apply_kernel
 static std::atomic<int> g_list_cap{1024};
 int lloyd_list_capacity() { return g_list_cap.load(); }
 
@@ -271,6 +273,12 @@ cat_status cat_debug_list_capacity(int entries) {
     if (entries < 0 || entries > 1024)
         return set_error(CAT_ERR_INVALID_ARG, "cat_debug_list_capacity: %d is outside 0 .. 1024", entries);
     g_list_cap.store(entries == 0 ? 1024 : entries);
+    return CAT_OK;
+}
+
+cat_status cat_debug_apply_kernel(int which) {
+    if (which < 0 || which > 2) return set_error(CAT_ERR_INVALID_ARG, "cat_debug_apply_kernel: 0, 1 or 2, got %d", which);
+    g_apply_kernel.store(which);
     return CAT_OK;
 }
 
@@ -525,6 +533,15 @@ static cat_status apply_impl(const char* who, const void* lq, int64_t N, int64_t
     if (path == CAT_PATH_TILE && !tile_ok)
         return set_error(CAT_ERR_UNSUPPORTED, "tile path forced but D=%lld K=%d dt=%d does not fit it", (long long)D,
                          (int)K, (int)dt);
+    // two fused kernels: the row-tile kernel reads every row once (its instances cover the shapes whose centroid
+    // operand the 8 waves of a workgroup can hold in registers), the tile kernel takes the rest
+    const int which = g_apply_kernel.load();
+    const bool rowtile_ok = infer_supported(N, D, K, dt);
+    if (which == 2 && !rowtile_ok)
+        return set_error(CAT_ERR_UNSUPPORTED, "row-tile inference kernel forced but D=%lld K=%d dt=%d does not fit it",
+                         (long long)D, (int)K, (int)dt);
+    if (rowtile_ok && path != CAT_PATH_STREAM && which != 1)
+        return infer_apply(lq, dt, N, D, K, centroids, g, b, corrected, assignments, w.tile, st);
     if (tile_ok && path != CAT_PATH_STREAM)
         return tile_assign(lq, dt, N, D, K, centroids, assignments, nullptr, nullptr, nullptr, g, b, corrected, w.tile,
                            st);

@@ -419,6 +419,19 @@ static cat_status launch_prep(cat_dtype dt, float* cent, double* base, double* d
     return CAT_OK;
 }
 
+// Centroids as they are (no sums to fold) -> operand parts and norms, for kernels outside this file that choose
+// their own cluster tiling, part count and channel order.
+cat_status launch_tile_prep_plain(cat_dtype dt, const float* cent, int64_t D, int32_t K, int32_t KT, int32_t P,
+                                  int32_t nchunks, int rows_layout_f32, uint16_t* packA, float* cnorm, hipStream_t st) {
+    (void)dt;
+    dim3 grid(KT * 16), block(256);
+    hipLaunchKernelGGL(k_tile_prep, grid, block, 0, st, const_cast<float*>(cent), (double*)nullptr, (double*)nullptr,
+                       (const int32_t*)nullptr, (int32_t*)nullptr, D, K, KT, P, nchunks, rows_layout_f32, packA, cnorm,
+                       (double*)nullptr, (unsigned long long*)nullptr);
+    CAT_LAUNCH_CHECK("k_tile_prep");
+    return CAT_OK;
+}
+
 static cat_status launch_tile(const TileParams& p, const TileCfg& c, cat_dtype dt, hipStream_t st) {
     const bool bf = dt == CAT_BF16;
     switch (c.KT) {
