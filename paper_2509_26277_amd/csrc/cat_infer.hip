@@ -22,11 +22,13 @@ struct InferCfg {
 struct Inst {
     bool bf16;
     int KW, SC, SPW, P, RGT, VPR;
-    const void* fn;
+    const void* fn;      // tiles at a fixed stride
+    const void* fn_dyn;  // tiles handed out in order
 };
 
 #define CAT_INST(BF, KW, SC, SPW, P, RGT, VPR) \
-    { BF, KW, SC, SPW, P, RGT, VPR, (const void*)k_infer<BF, KW, SC, SPW, P, RGT, VPR> }
+    { BF, KW, SC, SPW, P, RGT, VPR, (const void*)k_infer<BF, KW, SC, SPW, P, RGT, VPR, false>, \
+      (const void*)k_infer<BF, KW, SC, SPW, P, RGT, VPR, true> }
 // Instances.  The 8 waves of a workgroup are 8 / SC cluster shares (KW tiles of 16 clusters each) times SC channel
 // shares (SPW steps of 32 channels each): an instance runs K <= 16 KW (8 / SC), D <= 32 SPW SC, rows of at most VPR
 // KB.  For a shape several can run, the first in this list is taken (least padding work first).  A shape no instance
@@ -127,12 +129,13 @@ cat_status infer_apply(const void* lq, cat_dtype dt, int64_t N, int64_t D, int32
     p.off_s = c.off_s;
     p.off_cnorm = c.off_cnorm;
 
-    CAT_HIP_TRY(hipFuncSetAttribute(in.fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)c.lds));
     static thread_local int cached_inst = -1, cached_lds = -1, cached_dev = -1, per_cu = 1, ncu = 256;
     int dev = 0;
     CAT_HIP_TRY(hipGetDevice(&dev));
     if (cached_inst != c.inst || cached_lds != (int)c.lds || cached_dev != dev) {
         int nb = 0, v = 0;
+        CAT_HIP_TRY(hipFuncSetAttribute(in.fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)c.lds));
+        CAT_HIP_TRY(hipFuncSetAttribute(in.fn_dyn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)c.lds));
         CAT_HIP_TRY(hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, in.fn, kInferWaves * kWave, c.lds));
         CAT_HIP_TRY(hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev));
         per_cu = nb < 1 ? 1 : nb;
@@ -143,13 +146,21 @@ cat_status infer_apply(const void* lq, cat_dtype dt, int64_t N, int64_t D, int32
     }
     const int64_t cap = (int64_t)ncu * per_cu;
     const unsigned blocks = (unsigned)(p.ntiles < cap ? p.ntiles : cap);
+    // tiles in order pay from a few dozen tiles per workgroup on (the counters are cleared by a launch of their own)
+    const bool dyn = p.ntiles >= 64 * (int64_t)blocks && p.ntiles < ((int64_t)1 << 31) - 8 * (int64_t)blocks;
+    const void* fn = dyn ? in.fn_dyn : in.fn;
+    if (dyn) {
+        p.counters = (unsigned int*)(ws.cnorm + 512);  // the norms take at most 256 of the 1024 floats
+        cat_status fs = launch_fill_zero(p.counters, 8 * 16 * sizeof(unsigned int), st);
+        if (fs != CAT_OK) return fs;
+    }
     const bool prof = profile_on();
     if (prof) {
         cat_status ps = profile_mark(true, st);
         if (ps != CAT_OK) return ps;
     }
     void* args[] = {(void*)&p};
-    CAT_HIP_TRY(hipLaunchKernel(in.fn, dim3(blocks), dim3(kInferWaves * kWave), args, c.lds, st));
+    CAT_HIP_TRY(hipLaunchKernel(fn, dim3(blocks), dim3(kInferWaves * kWave), args, c.lds, st));
     CAT_LAUNCH_CHECK("k_infer");
     if (prof) return profile_mark(false, st);
     return CAT_OK;

@@ -13,8 +13,9 @@
 //   - ranks the centroids of its own rows from the partial products (summed in a fixed order), re-ranks the rows
 //     inside the error bound of the split arithmetic with direct-form double-precision distances (same rule as
 //     the tile kernel: the exact nearest centroid, lowest index on ties), applies gamma / beta and stores.
-// Two barriers per tile: rows staged -> contraction -> scores complete -> ranking.  The loads of the next tile are
-// in flight during the whole step, the gamma / beta rows of this tile during the contraction of the next.
+// Two barriers per tile: rows staged -> contraction -> scores complete -> ranking.  The rows of the following two or
+// three tiles are on their way at any time (one register buffer each, rotating by name), the gamma / beta rows of
+// this tile during the contraction of the next.
 #pragma once
 #include <type_traits>
 
@@ -47,6 +48,7 @@ struct InferParams {
     uint32_t xstride;       // bytes between rows of one bf16 part in LDS
     uint32_t xpart;         // bytes between the hi and the lo part
     uint32_t off_s, off_cnorm;  // LDS: [0, off_s) row tile, then the partial dot products, then the norms
+    unsigned int* counters;     // DYN: 8 x 16 words, zero on entry: the next tile of each group of workgroups
 };
 
 __device__ __forceinline__ uint32_t ipack_bf16(float a, float b) {  // a -> low half, b -> high half, RNE
@@ -70,8 +72,23 @@ __device__ __forceinline__ float wave_all(float v, Op op) {
     auto q = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
     return op(__uint_as_float(q[0]), __uint_as_float(q[1]));
 }
-__device__ __forceinline__ float wave_min_all(float v) {
-    return wave_all(v, [](float a, float b) { return fminf(a, b); });
+// Scores are ranked as integers: key(x) orders like x for all finite floats and infinities (sign-magnitude to two's
+// complement), so the minimum steps are v_min_i32 with the DPP lane pattern folded in, one instruction each (a float
+// minimum would quiet its operands first).
+__device__ __forceinline__ int score_key(float x) {
+    const int b = __float_as_int(x);
+    return b ^ ((b >> 31) & 0x7fffffff);
+}
+__device__ __forceinline__ float key_score(int k) { return __int_as_float(k ^ ((k >> 31) & 0x7fffffff)); }
+__device__ __forceinline__ int wave_min_all(int v) {
+    v = min(v, __builtin_amdgcn_update_dpp(0, v, 0xB1, 0xF, 0xF, true));
+    v = min(v, __builtin_amdgcn_update_dpp(0, v, 0x4E, 0xF, 0xF, true));
+    v = min(v, __builtin_amdgcn_update_dpp(0, v, 0x141, 0xF, 0xF, true));
+    v = min(v, __builtin_amdgcn_update_dpp(0, v, 0x140, 0xF, 0xF, true));
+    auto r = __builtin_amdgcn_permlane16_swap((unsigned)v, (unsigned)v, false, false);
+    v = min((int)r[0], (int)r[1]);
+    auto q = __builtin_amdgcn_permlane32_swap((unsigned)v, (unsigned)v, false, false);
+    return min((int)q[0], (int)q[1]);
 }
 __device__ __forceinline__ float wave_sum_all(float v) {
     return wave_all(v, [](float a, float b) { return a + b; });
@@ -80,8 +97,8 @@ __device__ __forceinline__ float wave_sum_all(float v) {
 // BF16: dtype of the rows.  KW: cluster tiles per wave.  SC: channel shares (the 8 waves are 8 / SC cluster shares
 // times SC channel shares).  SPW: MFMA steps per wave and tile.  P: parts of the centroid operand (2: hi + lo, 1: hi
 // only, wider re-rank bound).  RGT: 16-row groups per tile.  VPR: 16-byte vectors per lane and row
-// (ceil(D * b / 1024)).
-template <bool BF16, int KW, int SC, int SPW, int P, int RGT, int VPR>
+// (ceil(D * b / 1024)).  DYN: tiles handed out in order by counters instead of a fixed stride.
+template <bool BF16, int KW, int SC, int SPW, int P, int RGT, int VPR, bool DYN>
 __global__ __launch_bounds__(kInferWaves * kWave) void k_infer(const InferParams p) {
     extern __shared__ __align__(16) unsigned char smem[];
     constexpr int SK = kInferWaves / SC;           // cluster shares
@@ -91,6 +108,7 @@ __global__ __launch_bounds__(kInferWaves * kWave) void k_infer(const InferParams
     constexpr int EPL = BF16 ? 8 : 4;              // channels per 16-byte vector
     constexpr int XP = (!BF16 && P == 2) ? 2 : 1;  // bf16 parts of a row in LDS
     constexpr int NSLOT = (K16 + kWave - 1) / kWave;  // clusters per lane in the ranking
+    constexpr int DEPTH = VPR <= 2 ? 3 : 2;        // tiles requested ahead (a register buffer each)
     typedef typename std::conditional<BF16, bf16_t, float>::type T;
     typedef iu32x4 Rows[RPW][VPR];
 
@@ -117,9 +135,23 @@ __global__ __launch_bounds__(kInferWaves * kWave) void k_infer(const InferParams
                 A[kw][sl][part] = __builtin_bit_cast(ibf16x8, v);
             }
 
-    // this workgroup's tiles: blockIdx.x + i * gridDim.x, i < nst
-    const int64_t tstride = gridDim.x;
-    const int64_t nst = blockIdx.x < p.ntiles ? (p.ntiles - 1 - blockIdx.x) / tstride + 1 : 0;
+    // The tiles of this workgroup, numbered j = 0, 1, ...: a fixed stride, or (DYN) handed out in order: workgroup b
+    // belongs to group b % 8 and takes the tiles g + 8 c, c from its group's counter; the numbers of the next tiles wait
+    // in a small LDS queue, fetched DEPTH + 1 steps ahead.  Tiles in order keep the rows that the whole chip is reading
+    // and writing at any moment within a narrow band of memory, which the memory system rewards; the counters cost a
+    // launch to clear and a round trip each, so short launches keep the fixed stride.  A tile number past the last
+    // tile is harmless to load (its rows are clamped) and ends the loop.
+    __shared__ long long s_queue[8];
+    const int grp = blockIdx.x & 7;
+    auto fetch = [&]() -> long long { return (long long)grp + 8ll * (long long)atomicAdd(p.counters + grp * 16, 1u); };
+    if (DYN) {
+        if (threadIdx.x <= DEPTH) s_queue[threadIdx.x] = fetch();
+        __syncthreads();
+    }
+    auto tile_at = [&](int64_t j) -> int64_t {
+        if (DYN) return __builtin_amdgcn_readfirstlane((int)s_queue[j & 7]);
+        return (int64_t)blockIdx.x + j * (int64_t)gridDim.x;
+    };
     // per-lane channel of each vector, and whether it exists
     int ch[VPR];
     bool ch_ok[VPR];
@@ -132,7 +164,7 @@ __global__ __launch_bounds__(kInferWaves * kWave) void k_infer(const InferParams
     // rows of tile number i of this workgroup as loaded (rows past N repeat the last row, vectors past D the first
     // one, a tile number past the last repeats the last: no load is conditional)
     auto load_rows = [&](Rows& G, int64_t i) {
-        const int64_t tile = blockIdx.x + (i < nst ? i : nst - 1) * tstride;
+        const int64_t tile = tile_at(i);
 #pragma unroll
         for (int r = 0; r < RPW; r++) {
             int64_t row = tile * ROWS + wave * RPW + r;
@@ -212,7 +244,10 @@ __global__ __launch_bounds__(kInferWaves * kWave) void k_infer(const InferParams
     // are in LDS, the rows of tile i + 1 are on their way into Xn, Xf is free.
     float cmax = 0.f;
     auto step = [&](Rows& Xc, Rows& Xn, Rows& Xf, int64_t i) {
-        const int64_t t = blockIdx.x + i * tstride;
+        const int64_t t = tile_at(i);
+        long long fetched = 0;
+        if (DYN && threadIdx.x == 0) fetched = fetch();  // the tile of step i + DEPTH + 1; queued at the end of the step
+        load_rows(Xf, i + DEPTH);  // the rows DEPTH tiles ahead are requested first: nothing below has to precede them
         // ---- rank the centroids of this wave's rows of tile i ----
         int idx[RPW];
 #pragma unroll
@@ -220,36 +255,36 @@ __global__ __launch_bounds__(kInferWaves * kWave) void k_infer(const InferParams
             const int trow = wave * RPW + r;
             const int64_t row = t * ROWS + trow;
             // best score, its cluster (the lowest index among equal scores), and the best of the others
-            float sc[NSLOT];
-            float m1 = __builtin_inff();
+            int sc[NSLOT];  // score keys
+            int m1 = 0x7fffffff;
 #pragma unroll
             for (int j = 0; j < NSLOT; j++) {
                 const int k = lane + kWave * j;
-                sc[j] = __builtin_inff();
+                sc[j] = 0x7fffffff;
                 if (K16 % kWave == 0 || k < K16) {
                     const float* sp = s_dots + (size_t)trow * SC * K16 + k;
                     float dot = sp[0];
 #pragma unroll
                     for (int c = 1; c < SC; c++) dot += sp[c * K16];
-                    sc[j] = fmaf(-2.f, dot, s_cnorm[k]);
+                    sc[j] = score_key(fmaf(-2.f, dot, s_cnorm[k]));
                 }
-                m1 = fminf(m1, sc[j]);
+                m1 = min(m1, sc[j]);
             }
-            const float b1 = wave_min_all(m1);
+            const int kb1 = wave_min_all(m1);
             int i1 = 0;
             bool found = false;
-            float m2 = __builtin_inff();
+            int m2 = 0x7fffffff;
 #pragma unroll
             for (int j = 0; j < NSLOT; j++) {
-                const unsigned long long hit = __ballot(sc[j] == b1);
+                const unsigned long long hit = __ballot(sc[j] == kb1);
                 const int wl = (!found && hit) ? (int)__builtin_ctzll(hit) : -1;  // wave-uniform
                 if (wl >= 0) {
                     i1 = wl + kWave * j;
                     found = true;
                 }
-                m2 = fminf(m2, lane == wl ? __builtin_inff() : sc[j]);
+                m2 = min(m2, lane == wl ? 0x7fffffff : sc[j]);
             }
-            const float b2 = wave_min_all(m2);
+            const float b1 = key_score(kb1), b2 = key_score(wave_min_all(m2));
             // |x|^2 of the row, from the registers
             float xn2 = 0.f;
 #pragma unroll
@@ -268,7 +303,8 @@ __global__ __launch_bounds__(kInferWaves * kWave) void k_infer(const InferParams
                 }
             }
             xn2 = wave_sum_all(xn2);
-            const float T = p.tau * sqrtf(xn2) * cmax + p.tau2 * cmax * cmax;
+            // (the hardware square root is good to 1 ulp; the bound only has to err on the large side)
+            const float T = p.tau * (1.000001f * __builtin_amdgcn_sqrtf(xn2)) * cmax + p.tau2 * cmax * cmax;
             if (row < p.N && !(b2 - b1 > T)) {  // wave-uniform: every lane holds the row's b1, b2
                 // exact re-rank: direct-form double-precision distance to every centroid whose score is inside the bound
                 const float thr = b1 + T;
@@ -276,7 +312,7 @@ __global__ __launch_bounds__(kInferWaves * kWave) void k_infer(const InferParams
                 int kbest = 0x7fffffff;
 #pragma unroll
                 for (int j = 0; j < NSLOT; j++) {
-                    unsigned long long m = __ballot(sc[j] <= thr && lane + kWave * j < p.K);
+                    unsigned long long m = __ballot(sc[j] <= score_key(thr) && lane + kWave * j < p.K);
                     while (m) {
                         const int l = __builtin_amdgcn_readfirstlane(__builtin_ctzll(m));
                         m &= m - 1;
@@ -337,7 +373,6 @@ __global__ __launch_bounds__(kInferWaves * kWave) void k_infer(const InferParams
             }
         }
         // ---- the rows of tile i + 2 are requested, those of tile i + 1 (in flight since the last step) go to LDS ----
-        load_rows(Xf, i + 2);
         stage(Xn);
         __syncthreads();
         contract();  // tile i + 1 (after the last tile: the last tile once more, to no effect)
@@ -367,32 +402,46 @@ __global__ __launch_bounds__(kInferWaves * kWave) void k_infer(const InferParams
                 if (row < p.N && ch_ok[v]) __builtin_nontemporal_store(o, (iu32x4*)(orow + ch[v]));
             }
         }
+        if (DYN && threadIdx.x == 0) s_queue[(i + DEPTH + 1) & 7] = fetched;
         __syncthreads();  // the partial dot products of tile i + 1 are complete
     };
 
-    Rows X0, X1, X2;
-    if (nst > 0) {
-        load_rows(X0, 0);
-        load_rows(X1, 1);
-    }
+    Rows X0, X1, X2, X3;  // X3 only with DEPTH == 3
+    load_rows(X0, 0);
+    load_rows(X1, 1);
+    if (DEPTH == 3) load_rows(X2, 2);
     __syncthreads();  // the zeroed tile and the norms are in place
     {
         float cm2 = 0.f;
         for (int k = lane; k < p.K; k += kWave) cm2 = fmaxf(cm2, s_cnorm[k]);
         cmax = sqrtf(wave_all(cm2, [](float a, float b) { return fmaxf(a, b); }));
     }
-    if (nst == 0) return;  // uniform over the workgroup
+    if (tile_at(0) >= p.ntiles) return;  // uniform over the workgroup
     stage(X0);
     __syncthreads();
     contract();
     __syncthreads();
-    for (int64_t i = 0;;) {
-        step(X0, X1, X2, i);
-        if (++i == nst) break;
-        step(X1, X2, X0, i);
-        if (++i == nst) break;
-        step(X2, X0, X1, i);
-        if (++i == nst) break;
+    // the buffers rotate by name: (rows of tile i, rows of tile i + 1, free buffer)
+    if (DEPTH == 3) {
+        for (int64_t i = 0;;) {
+            step(X0, X1, X3, i);
+            if (tile_at(++i) >= p.ntiles) break;
+            step(X1, X2, X0, i);
+            if (tile_at(++i) >= p.ntiles) break;
+            step(X2, X3, X1, i);
+            if (tile_at(++i) >= p.ntiles) break;
+            step(X3, X0, X2, i);
+            if (tile_at(++i) >= p.ntiles) break;
+        }
+    } else {
+        for (int64_t i = 0;;) {
+            step(X0, X1, X2, i);
+            if (tile_at(++i) >= p.ntiles) break;
+            step(X1, X2, X0, i);
+            if (tile_at(++i) >= p.ntiles) break;
+            step(X2, X0, X1, i);
+            if (tile_at(++i) >= p.ntiles) break;
+        }
     }
 }
 
