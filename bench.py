@@ -1,12 +1,20 @@
 #!/usr/bin/env python3
 """Benchmark of the CAT hot path on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg2] [--no-cpu]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload all|cfg1..cfg5] [--no-cpu]
 
 One step = one pass of the whole hot path over one synthetic batch that is
 already resident in HBM: cat_fit (seeded init, `iters` Lloyd iterations, final
 assignment, per-cluster affine fit) followed by cat_apply on the same rows
 (inference-only workload cfg5: cat_apply alone).  Prints ONE JSON line.
+
+With no --workload (or "all") the five workloads run one after the other in this
+process.  The top-level fields are those of cfg3, the largest fitting workload
+(1 GiB of rows like cfg4, and the most rows: the metric counts rows); `configs`
+holds, for every workload, the same figures: value, ms_per_step, roofline (the
+assignment pass), apply_roofline (the fused inference pass), the whole Lloyd
+iteration as a fraction of the roofline, and cpu_baseline.  --workload cfgN runs
+that workload alone and prints its figures at the top level.
 
 value        rows x Lloyd-iterations per second of whole-step time (cfg5: GB/s of
              cat_apply, read + write)
@@ -33,34 +41,37 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBPS = 8000.0
 
-# HBM-side traffic of one k_tile launch, from two rocprofv3 --pmc runs of this file (FETCH_SIZE, then
-# WRITE_SIZE; profiles/k_tile_hbm_traffic.md has the commands and the raw figures).  Each counter is
-# scaled by what it reads for the plain device copy of the same matrix that this script also times
-# (a copy reads and writes exactly N*D*b bytes).  Per workload: (FETCH_SIZE of k_tile, FETCH_SIZE of the
-# copy, WRITE_SIZE of k_tile, WRITE_SIZE of the copy), counter units, mean per dispatch.  The figures
-# belong to one version of the kernel source: `traffic` is reported only while its hash still matches.
-TRAFFIC_KERNEL_SHA256 = "c368204e0d3cb727b427eb617db98ee9711a7f8d82ac8120400e7d1b9dc3b32c"
+# HBM-side traffic of one launch of the two dominant kernels, from rocprofv3 --pmc runs of this file (FETCH_SIZE,
+# then WRITE_SIZE; profiles/k_tile_hbm_traffic.md and profiles/k_infer_hbm_traffic.md have the commands and the raw
+# figures).  Each counter is scaled by what it reads for the plain device copy of the same matrix that this script
+# also times (a copy reads and writes exactly N*D*b bytes).  Per entry: (FETCH_SIZE of the kernel, FETCH_SIZE of the
+# copy, WRITE_SIZE of the kernel, WRITE_SIZE of the copy), counter units, mean per dispatch.  The figures belong to
+# one version of a kernel's source file: `traffic` is reported only while the hash of that file still matches, and the
+# line says that it comes from profiles/, not from this run.
+TRAFFIC_SOURCES = {
+    "k_tile": ("cat_tile_kernel.h", "c368204e0d3cb727b427eb617db98ee9711a7f8d82ac8120400e7d1b9dc3b32c"),
+    "k_infer": ("cat_infer_kernel.h", ""),
+}
 TRAFFIC_COUNTERS = {
-    "cfg2": (133758.9, 128011.7, 298.9, 256000.0),
-    "cfg3": (527761.6, 524299.7, 4719.2, 1048576.0),
-    "cfg4": (560549.3, 524299.7, 1191.5, 1048576.0),
-    "cfg5": (8363420.5, 4194317.9, 8406407.7, 8388608.0),
+    "cfg2": ("k_tile", (133758.9, 128011.7, 298.9, 256000.0)),
+    "cfg3": ("k_tile", (527761.6, 524299.7, 4719.2, 1048576.0)),
+    "cfg4": ("k_tile", (560549.3, 524299.7, 1191.5, 1048576.0)),
 }
 
 
-def _traffic_bytes(workload, copy_bytes):
-    """measured HBM bytes per k_tile launch, or None (no counters for this workload / kernel changed)"""
+def _traffic_bytes(key, copy_bytes):
+    """measured HBM bytes per launch, or None (no counters for this workload and kernel / its source changed)"""
     import hashlib
-    src = os.path.join(ROOT, "paper_2509_26277_amd", "csrc", "cat_tile_kernel.h")
+    if key not in TRAFFIC_COUNTERS:
+        return None
+    kernel, (fk, fc, wk, wc) = TRAFFIC_COUNTERS[key]
+    fname, sha = TRAFFIC_SOURCES[kernel]
     try:
-        with open(src, "rb") as f:
-            if hashlib.sha256(f.read()).hexdigest() != TRAFFIC_KERNEL_SHA256:
+        with open(os.path.join(ROOT, "paper_2509_26277_amd", "csrc", fname), "rb") as f:
+            if hashlib.sha256(f.read()).hexdigest() != sha:
                 return None
     except OSError:
         return None
-    if workload not in TRAFFIC_COUNTERS:
-        return None
-    fk, fc, wk, wc = TRAFFIC_COUNTERS[workload]
     return fk * (copy_bytes / fc) + wk * (copy_bytes / wc)
 
 
@@ -76,40 +87,14 @@ def _events(fn, reps, torch):
     return e0.elapsed_time(e1) / reps
 
 
-def main():
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=5)
-    ap.add_argument("--warmup", type=int, default=2)
-    ap.add_argument("--workload", default="cfg2", choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5"])
-    ap.add_argument("--rows", type=int, default=None, help="override N (debugging; the result is then not the named workload)")
-    ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
-    ap.add_argument("--no-seeding", action="store_true",
-                    help="skip the timing of the D^2-weighted seeding (detail.kmeanspp_*; fit workloads only)")
-    ap.add_argument("--alpha-grid", type=int, default=10,
-                    help="also time one pass that evaluates the fitted transformation at this many blending coefficients "
-                         "(1/n .. 1): Top-1 agreement with the FP rows and squared error; reported under detail.alpha_*; "
-                         "0 skips it, at most 16 (fit workloads only)")
-    ap.add_argument("--pca-dim", type=int, default=50,
-                    help="also time the PCA front-end (fit, projection, labelled affine map) with this many "
-                         "components; reported under detail.pca_*; 0 skips it (fit workloads with D <= 2048 only)")
-    args = ap.parse_args()
-    if args.gpus != 1:
-        sys.exit("bench.py: this library is single-GPU; run with --gpus 1 (rows shard trivially: one all-reduce of K x D sums per iteration)")
-
-    import numpy as np
-    import torch
-
+def _run_workload(name, args, torch, np, cpu_budget_s, extras):
+    """All figures of one workload: a dict with the fields of the JSON line."""
     from paper_2509_26277_amd import binding, cat_apply, cat_fit, workloads
-
-    assert torch.cuda.is_available(), "bench.py needs a GPU"
-    torch.cuda.set_device(0)
-    binding.load_library()  # no fallback: fails here if the HIP library is missing
-
-    w = workloads.make(args.workload, n_rows=args.rows)
+    w = workloads.make(name, n_rows=args.rows)
     N, D, K, iters, dt = w["N"], w["D"], w["K"], w["iters"], w["dtype"]
     esize = 4 if dt == "f32" else 2
     fit_kind = w["kind"] == "fit"
+    dtc = binding.CAT_F32 if dt == "f32" else binding.CAT_BF16
 
     def dev(x):
         if dt == "f32":
@@ -121,12 +106,10 @@ def main():
     out = torch.empty_like(lq)
     if fit_kind:
         fp = dev(w["fp"])
-        ws_fit = torch.empty(binding.cat_fit_workspace_bytes(N, D, K, binding.CAT_F32 if dt == "f32" else binding.CAT_BF16),
-                             dtype=torch.uint8, device="cuda")
+        ws_fit = torch.empty(binding.cat_fit_workspace_bytes(N, D, K, dtc), dtype=torch.uint8, device="cuda")
     else:
         cent, gamma, beta = (torch.from_numpy(w[k]).cuda() for k in ("centroids", "gamma", "beta"))
-    ws_apply = torch.empty(max(256, binding.cat_apply_workspace_bytes(N, D, K, binding.CAT_F32 if dt == "f32" else binding.CAT_BF16)),
-                           dtype=torch.uint8, device="cuda")
+    ws_apply = torch.empty(max(256, binding.cat_apply_workspace_bytes(N, D, K, dtc)), dtype=torch.uint8, device="cuda")
     state = {}
 
     def step():
@@ -150,20 +133,17 @@ def main():
     # ---- per-launch figures, HIP events on the launch stream (torch's current stream) ----
     detail = {}
     apply_bytes = N * D * esize * 2 + 4 * N
+    reps = max(5, args.steps)
     if fit_kind:
         r = state["fit"]
-        reps = max(3, args.steps)
+        apply_args = (r["centroids"], r["gamma"], r["beta"])
         t_fit = _events(lambda: cat_fit(lq, fp, K, iters, seed=w["seed"], workspace=ws_fit), reps, torch)
         t_fit0 = _events(lambda: cat_fit(lq, fp, K, 0, seed=w["seed"], workspace=ws_fit), reps, torch)
-        t_apply = _events(lambda: cat_apply(lq, r["centroids"], r["gamma"], r["beta"], out=out, workspace=ws_apply),
-                          reps, torch)
         t_iter = (t_fit - t_fit0) / iters  # one Lloyd iteration
+        alg_bytes = N * D * esize
         detail.update(fit_ms=t_fit, fit_iters0_ms=t_fit0, lloyd_iter_us=1e3 * t_iter,
                       lloyd_iters_per_s=1e3 / t_iter, lloyd_rows_per_s=N * 1e3 / t_iter,
-                      apply_ms=t_apply, apply_GBps=apply_bytes / t_apply / 1e6,
-                      apply_frac_hbm=apply_bytes / t_apply / 1e6 / HBM_PEAK_GBPS)
-        alg_bytes = N * D * esize
-        detail["lloyd_iter_frac_hbm"] = alg_bytes / t_iter / 1e6 / HBM_PEAK_GBPS
+                      lloyd_iter_frac_hbm=alg_bytes / t_iter / 1e6 / HBM_PEAK_GBPS)
         # the dominant kernel by itself: events around every k_tile launch of `reps` fits
         binding.profile_enable(True)
         for _ in range(reps):
@@ -173,35 +153,40 @@ def main():
         assert len(ms) == reps * (iters + 1), "expected one k_tile launch per assignment pass"
         t_k = sum(ms) / len(ms)
         achieved = alg_bytes / t_k / 1e6
-        roof = dict(bound="hbm", kernel="k_tile (assignment pass)", achieved=achieved, peak=HBM_PEAK_GBPS, unit="GB/s",
-                    frac=achieved / HBM_PEAK_GBPS, traffic=None if args.rows else _traffic_bytes(w["name"], N * D * esize),
-                    bytes_per_launch=alg_bytes,
-                    us_per_launch=1e3 * t_k, launches=len(ms))
+        roof = dict(bound="hbm", kernel="k_tile (assignment pass of a Lloyd iteration)", achieved=achieved,
+                    peak=HBM_PEAK_GBPS, unit="GB/s", frac=achieved / HBM_PEAK_GBPS,
+                    traffic=None if args.rows else _traffic_bytes(w["name"], N * D * esize),
+                    traffic_source="profiles/k_tile_hbm_traffic.md (hardware counters of an earlier run of this kernel, not this run)",
+                    bytes_per_launch=alg_bytes, us_per_launch=1e3 * t_k, launches=len(ms))
         metric, unit = "cat_fit_lloyd_rows_per_s", "rows/s"
         value = N * iters / (ms_per_step * 1e-3)
     else:
-        reps = max(5, args.steps)
-        t_apply = _events(lambda: cat_apply(lq, cent, gamma, beta, out=out, workspace=ws_apply), reps, torch)
-        detail.update(apply_ms=t_apply, apply_GBps=apply_bytes / t_apply / 1e6, apply_rows_per_s=N * 1e3 / t_apply)
-        binding.profile_enable(True)
-        for _ in range(reps):
-            cat_apply(lq, cent, gamma, beta, out=out, workspace=ws_apply)
-        ms = binding.profile_read()
-        binding.profile_enable(False)
-        t_k = sum(ms) / len(ms)
-        achieved = apply_bytes / t_k / 1e6
-        roof = dict(bound="hbm", kernel="k_tile (fused inference pass)", achieved=achieved, peak=HBM_PEAK_GBPS,
-                    unit="GB/s", frac=achieved / HBM_PEAK_GBPS, traffic=None if args.rows else _traffic_bytes(w["name"], N * D * esize),
-                    bytes_per_launch=apply_bytes,
-                    us_per_launch=1e3 * t_k, launches=len(ms))
+        apply_args = (cent, gamma, beta)
+        roof = None
         metric, unit = "cat_apply_GBps", "GB/s"
         value = apply_bytes / (ms_per_step * 1e-3) / 1e9
+    # the fused inference pass: whole call, and its kernel by itself
+    t_apply = _events(lambda: cat_apply(lq, *apply_args, out=out, workspace=ws_apply), reps, torch)
+    binding.profile_enable(True)
+    for _ in range(reps):
+        cat_apply(lq, *apply_args, out=out, workspace=ws_apply)
+    ms = binding.profile_read()
+    binding.profile_enable(False)
+    t_ka = sum(ms) / len(ms)
+    apply_roof = dict(bound="hbm", kernel="fused inference pass (assign + gather + affine)", achieved=apply_bytes / t_ka / 1e6,
+                      peak=HBM_PEAK_GBPS, unit="GB/s", frac=apply_bytes / t_ka / 1e6 / HBM_PEAK_GBPS,
+                      traffic=None if args.rows else _traffic_bytes(w["name"] + "_apply", N * D * esize),
+                      traffic_source="profiles/k_infer_hbm_traffic.md (hardware counters of an earlier run of this kernel, not this run)",
+                      bytes_per_launch=apply_bytes, us_per_launch=1e3 * t_ka, launches=len(ms))
+    detail.update(apply_ms=t_apply, apply_GBps=apply_bytes / t_apply / 1e6, apply_frac_hbm=apply_bytes / t_apply / 1e6 / HBM_PEAK_GBPS,
+                  apply_rows_per_s=N * 1e3 / t_apply)
+    if roof is None:
+        roof = apply_roof
 
     # ---- the PCA front-end (a separate row of the method: not part of `value` or `roofline`) ----
-    if fit_kind and args.pca_dim > 0 and D <= 2048:
+    if extras and fit_kind and args.pca_dim > 0 and D <= 2048:
         from paper_2509_26277_amd import cat_apply_assigned, cat_apply_pca, cat_fit_pca, cat_pca_fit, cat_pca_project
         pdim = min(args.pca_dim, D)
-        dtc = binding.CAT_F32 if dt == "f32" else binding.CAT_BF16
         ws_pca = torch.empty(binding.load_library().cat_pca_workspace_bytes(N, D, pdim, dtc), dtype=torch.uint8, device="cuda")
         mean_p, comps_p, _ = cat_pca_fit(lq, pdim, workspace=ws_pca)
         t_pfit = _events(lambda: cat_pca_fit(lq, pdim, workspace=ws_pca), 2, torch)
@@ -222,7 +207,7 @@ def main():
                       apply_assigned_us=1e3 * t_lab, apply_assigned_GBps=2 * N * D * esize / t_lab / 1e6)
 
     # ---- the sweep of the blending coefficient (another separate row: the ablation grid of ten values in one pass) ----
-    if fit_kind and args.alpha_grid > 0:
+    if extras and fit_kind and args.alpha_grid > 0:
         from paper_2509_26277_amd import cat_alpha_sweep, cat_top1
         r = state["fit"]
         grid = [(k + 1) / args.alpha_grid for k in range(args.alpha_grid)]
@@ -238,14 +223,14 @@ def main():
                       top1_GBps=N * D * esize / t_top / 1e6)
 
     # ---- D^2-weighted seeding (another separate row): K - 1 reads of the rows ----
-    if fit_kind and not args.no_seeding:
+    if extras and fit_kind and not args.no_seeding:
         from paper_2509_26277_amd import cat_init_kmeanspp
         ws_pp = torch.empty(binding.load_library().cat_init_kmeanspp_workspace_bytes(N, K), dtype=torch.uint8, device="cuda")
         t_pp = _events(lambda: cat_init_kmeanspp(lq, K, seed=w["seed"], workspace=ws_pp), 3, torch)
         detail.update(kmeanspp_ms=t_pp, kmeanspp_GBps=(K - 1) * N * D * esize / t_pp / 1e6)
 
     # ---- the same fit with the early stop allowed (a separate row: the headline runs every pass) ----
-    if fit_kind and not args.no_seeding:
+    if extras and fit_kind and not args.no_seeding:
         es = lambda: cat_fit(lq, fp, K, iters, seed=w["seed"], workspace=ws_fit, early_stop=True)
         skipped = int(es()["passes_skipped"].item())
         detail.update(fit_early_stop_ms=_events(es, 5, torch), passes_skipped=skipped)
@@ -256,7 +241,7 @@ def main():
 
     # ---- the oracle on the host cores, bounded sample ----
     cpu = None
-    if not args.no_cpu:
+    if not args.no_cpu and cpu_budget_s > 0:
         import oracle
         probe = min(N, max(K, 4096))
         t = time.perf_counter()
@@ -265,7 +250,7 @@ def main():
         else:
             oracle.apply(w["lq"][:probe], w["centroids"], w["gamma"], w["beta"], 1.0)
         per_row_pass = (time.perf_counter() - t) / (probe * (3 if fit_kind else 1))
-        budget = 20.0  # seconds of oracle time
+        budget = float(cpu_budget_s)  # seconds of oracle time
         if fit_kind:
             # passes of a fit: iters + 1 assignments, iters updates (cheap), 2 for the affine fit
             it_s = iters if per_row_pass * N * (iters + 3) <= budget else max(1, int(budget / (per_row_pass * N)) - 3)
@@ -274,7 +259,7 @@ def main():
             oracle.fit(w["lq"][:rows_s], w["fp"][:rows_s], K, it_s, seed=w["seed"])
             sec = time.perf_counter() - t
             cpu = dict(value=rows_s * it_s / sec, unit="rows/s", cores=oracle.threads(), kind="oracle",
-                       sample=f"oracle.fit on {'all' if rows_s == N else 'the first'} {rows_s} rows, {it_s} Lloyd "
+                       sample=f"oracle.fit on {'all' if rows_s == N else 'the first'} {rows_s} rows of {w['name']}, {it_s} Lloyd "
                               f"iterations + final assign + affine fit, {sec:.1f} s; rows x iterations / whole time")
         else:
             rows_s = int(min(N, max(K, budget / max(per_row_pass, 1e-12))))
@@ -282,16 +267,73 @@ def main():
             oracle.apply(w["lq"][:rows_s], w["centroids"], w["gamma"], w["beta"], 1.0)
             sec = time.perf_counter() - t
             cpu = dict(value=rows_s * D * esize * 2 / sec / 1e9, unit="GB/s", cores=oracle.threads(), kind="oracle",
-                       sample=f"oracle.apply on the first {rows_s} rows, {sec:.1f} s; bytes read + written / time")
+                       sample=f"oracle.apply on the first {rows_s} rows of {w['name']}, {sec:.1f} s; bytes read + written / time")
 
-    line = {
-        "metric": metric, "value": value, "unit": unit, "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f32" if dt == "f32" else "bf16", "data": "synthetic",
+    return {
+        "metric": metric, "value": value, "unit": unit, "ms_per_step": ms_per_step,
+        "dtype": "f32" if dt == "f32" else "bf16",
         "config": {"workload": f"{w['name']}: N={N} D={D} K={K} {dt} iters={iters}", "N": N, "D": D, "K": K,
                    "iters": iters, "step": "cat_fit + cat_apply" if fit_kind else "cat_apply"},
-        "roofline": roof, "cpu_baseline": cpu, "detail": detail,
+        "roofline": roof, "apply_roofline": apply_roof,
+        "lloyd_iter_frac_hbm": detail.get("lloyd_iter_frac_hbm"), "cpu_baseline": cpu, "detail": detail,
     }
+
+
+HEADLINE = "cfg3"  # the largest fitting workload: 1 GiB of rows like cfg4, and the most rows (the metric counts rows)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--workload", default="all", choices=["all", "cfg1", "cfg2", "cfg3", "cfg4", "cfg5"])
+    ap.add_argument("--rows", type=int, default=None, help="override N (debugging; the result is then not the named workload)")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
+    ap.add_argument("--no-seeding", action="store_true",
+                    help="skip the timing of the D^2-weighted seeding (detail.kmeanspp_*; cfg2 only)")
+    ap.add_argument("--alpha-grid", type=int, default=10,
+                    help="also time one pass that evaluates the fitted transformation at this many blending coefficients "
+                         "(1/n .. 1): Top-1 agreement with the FP rows and squared error; reported under detail.alpha_*; "
+                         "0 skips it, at most 16 (cfg2, or the workload named with --workload)")
+    ap.add_argument("--pca-dim", type=int, default=50,
+                    help="also time the PCA front-end (fit, projection, labelled affine map) with this many "
+                         "components; reported under detail.pca_*; 0 skips it (cfg2, or the workload named with --workload)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this library is single-GPU; run with --gpus 1 (rows shard trivially: one all-reduce of K x D sums per iteration)")
+
+    import numpy as np
+    import torch
+
+    from paper_2509_26277_amd import binding
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    binding.load_library()  # no fallback: fails here if the HIP library is missing
+
+    if args.workload != "all":
+        top = _run_workload(args.workload, args, torch, np, 20.0, extras=True)
+        configs = None
+    else:
+        # the oracle's time is shared out: most of it to the headline workload, a few seconds to each of the others
+        per = {}
+        for name in ("cfg1", "cfg2", "cfg3", "cfg4", "cfg5"):
+            per[name] = _run_workload(name, args, torch, np, 12.0 if name == HEADLINE else 4.0, extras=(name == "cfg2"))
+            torch.cuda.empty_cache()
+        top = per[HEADLINE]
+        configs = [dict(name=k, **{f: v[f] for f in ("metric", "value", "unit", "ms_per_step", "dtype", "config", "roofline",
+                                                     "apply_roofline", "lloyd_iter_frac_hbm", "cpu_baseline", "detail")})
+                   for k, v in per.items()]
+    line = {
+        "metric": top["metric"], "value": top["value"], "unit": top["unit"], "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": top["ms_per_step"], "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": top["dtype"], "data": "synthetic", "config": top["config"],
+        "roofline": top["roofline"], "apply_roofline": top["apply_roofline"],
+        "lloyd_iter_frac_hbm": top["lloyd_iter_frac_hbm"], "cpu_baseline": top["cpu_baseline"], "detail": top["detail"],
+    }
+    if configs is not None:
+        line["configs"] = configs
     print(json.dumps(line))
 
 
