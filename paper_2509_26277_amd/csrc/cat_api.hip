@@ -36,7 +36,6 @@ bool fast_paths_forced() { return g_path.load() == CAT_PATH_TILE; }
 static std::atomic<int> g_apply_kernel{0};  // cat_debug_apply_kernel
 static std::atomic<int> g_list_cap{1024};
 int lloyd_list_capacity() { return g_list_cap.load(); }
-bool rowtile_disabled() { return g_apply_kernel.load() == 1; }
 
 cat_status profile_mark(bool begin, hipStream_t st) {
     (void)begin;

@@ -31,8 +31,6 @@ typedef __attribute__((ext_vector_type(4))) uint32_t iu32x4;
 typedef __attribute__((ext_vector_type(2))) uint32_t iu32x2;
 
 constexpr int kInferWaves = 8;
-enum { INFER_APPLY = 0, INFER_ASSIGN = 1 };
-constexpr float kInferPadNorm = 3.0e38f;
 
 struct InferParams {
     const void* lq;
@@ -51,19 +49,6 @@ struct InferParams {
     uint32_t xpart;         // bytes between the hi and the lo part
     uint32_t off_s, off_cnorm;  // LDS: [0, off_s) row tile, then the partial dot products, then the norms
     unsigned int* counters;     // DYN: 8 x 16 words, zero on entry: the next tile of each group of workgroups
-    // assignment pass (INFER_ASSIGN): the outputs and bookkeeping of a Lloyd pass, as in the tile kernel
-    int32_t* counts;            // nullable, accumulated into
-    double* inertia;            // nullable, accumulated into
-    unsigned long long* rep;    // nullable, min-combined: first row of each cluster
-    unsigned long long* list;   // nullable: rows that changed cluster, (row << 24) | ((old + 1) << 12) | new
-    uint32_t* list_count;
-    int32_t delta_mode;         // rows carry a previous assignment (in `assign`)
-    int32_t list_cap;           // entries of the workgroup's LDS list in use
-    int32_t reverse;            // walk the tiles from the last to the first
-    const uint32_t* skip_when_zero;  // nullable: the launch does nothing if this word is zero
-    const double* norm_part;    // norm_slices x K shares of the squared norms, added up here in slice order
-    int32_t norm_slices;        //   (0: cnorm holds the norms)
-    uint32_t off_hist, off_rep, off_list, off_misc;  // LDS of the bookkeeping
 };
 
 __device__ __forceinline__ uint32_t ipack_bf16(float a, float b) {  // a -> low half, b -> high half, RNE
@@ -113,10 +98,9 @@ __device__ __forceinline__ float wave_sum_all(float v) {
 // times SC channel shares).  SPW: MFMA steps per wave and tile.  P: parts of the centroid operand (2: hi + lo, 1: hi
 // only, wider re-rank bound).  RGT: 16-row groups per tile.  VPR: 16-byte vectors per lane and row
 // (ceil(D * b / 1024)).  DYN: tiles handed out in order by counters instead of a fixed stride.
-template <bool BF16, int KW, int SC, int SPW, int P, int RGT, int VPR, bool DYN, int MODE>
+template <bool BF16, int KW, int SC, int SPW, int P, int RGT, int VPR, bool DYN>
 __global__ __launch_bounds__(kInferWaves * kWave) void k_infer(const InferParams p) {
     extern __shared__ __align__(16) unsigned char smem[];
-    if (MODE == INFER_ASSIGN && p.skip_when_zero && *p.skip_when_zero == 0u) return;  // uniform over the grid
     constexpr int SK = kInferWaves / SC;           // cluster shares
     constexpr int K16 = 16 * KW * SK;              // padded clusters
     constexpr int RPW = 2 * RGT;                   // rows of the tile a wave loads, ranks and writes
@@ -126,10 +110,7 @@ __global__ __launch_bounds__(kInferWaves * kWave) void k_infer(const InferParams
     constexpr int NSLOT = (K16 + kWave - 1) / kWave;  // clusters per lane in the ranking
     constexpr int DEPTH = VPR <= 2 ? 3 : 2;        // tiles requested ahead (a register buffer each)
     typedef typename std::conditional<BF16, bf16_t, float>::type T;
-    struct Rows {
-        iu32x4 x[RPW][VPR];
-        int prev[RPW];  // assignment pass: the row's previous cluster
-    };
+    typedef iu32x4 Rows[RPW][VPR];
 
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
@@ -140,29 +121,7 @@ __global__ __launch_bounds__(kInferWaves * kWave) void k_infer(const InferParams
 
     // ---- prologue: zero the row tile (its padding channels stay zero for good), norms, operand share ----
     for (uint32_t i = threadIdx.x; i < p.off_s / 16; i += blockDim.x) ((iu32x4*)smem)[i] = (iu32x4){0u, 0u, 0u, 0u};
-    for (int k = threadIdx.x; k < K16; k += blockDim.x) {
-        float cn;
-        if (MODE == INFER_ASSIGN && p.norm_slices > 0) {
-            double nn = 0.0;
-            if (k < p.K)
-                for (int sl = 0; sl < p.norm_slices; sl++) nn += p.norm_part[(size_t)sl * p.K + k];
-            cn = k < p.K ? (float)nn : kInferPadNorm;
-        } else {
-            cn = p.cnorm[k];
-        }
-        s_cnorm[k] = cn;
-    }
-    int* s_hist = (int*)(smem + p.off_hist);
-    unsigned long long* s_rep = (unsigned long long*)(smem + p.off_rep);
-    int* s_misc = (int*)(smem + p.off_misc);  // [0] list count, [1] list base, [2..] doubles for the objective
-    if (MODE == INFER_ASSIGN) {
-        for (int k = threadIdx.x; k < p.K; k += blockDim.x) {
-            s_hist[k] = 0;
-            s_rep[k] = ~0ull;
-        }
-        if (threadIdx.x == 0) s_misc[0] = 0;
-    }
-    double in_acc = 0.0;
+    for (int k = threadIdx.x; k < K16; k += blockDim.x) s_cnorm[k] = p.cnorm[k];
     ibf16x8 A[KW][SPW][P];
 #pragma unroll
     for (int kw = 0; kw < KW; kw++)
@@ -189,13 +148,9 @@ __global__ __launch_bounds__(kInferWaves * kWave) void k_infer(const InferParams
         if (threadIdx.x <= DEPTH) s_queue[threadIdx.x] = fetch();
         __syncthreads();
     }
-    auto tile_seq = [&](int64_t j) -> int64_t {  // position in the walk; past the last tile: the loop ends
+    auto tile_at = [&](int64_t j) -> int64_t {
         if (DYN) return __builtin_amdgcn_readfirstlane((int)s_queue[j & 7]);
         return (int64_t)blockIdx.x + j * (int64_t)gridDim.x;
-    };
-    auto tile_at = [&](int64_t j) -> int64_t {  // the tile at that position
-        const int64_t q = tile_seq(j);
-        return (MODE == INFER_ASSIGN && p.reverse && q < p.ntiles) ? p.ntiles - 1 - q : q;
     };
     // per-lane channel of each vector, and whether it exists
     int ch[VPR];
@@ -216,9 +171,7 @@ __global__ __launch_bounds__(kInferWaves * kWave) void k_infer(const InferParams
             row = row < p.N ? row : p.N - 1;
             const T* x = (const T*)p.lq + row * p.D;
 #pragma unroll
-            for (int v = 0; v < VPR; v++) G.x[r][v] = *(const iu32x4*)(x + (ch_ok[v] ? ch[v] : 0));
-            // the previous assignment rides along: fetched where it is used it would have to be waited for there
-            G.prev[r] = (MODE == INFER_ASSIGN && p.delta_mode) ? p.assign[row] : -1;
+            for (int v = 0; v < VPR; v++) G[r][v] = *(const iu32x4*)(x + (ch_ok[v] ? ch[v] : 0));
         }
     };
     // bf16 copy of the wave's rows into the LDS tile
@@ -230,10 +183,10 @@ __global__ __launch_bounds__(kInferWaves * kWave) void k_infer(const InferParams
             for (int v = 0; v < VPR; v++) {
                 if (ch_ok[v]) {
                     if (BF16) {
-                        *(iu32x4*)(xr + ch[v] * 2) = G.x[r][v];
+                        *(iu32x4*)(xr + ch[v] * 2) = G[r][v];
                     } else {
-                        const float x0 = __uint_as_float(G.x[r][v].x), x1 = __uint_as_float(G.x[r][v].y);
-                        const float x2 = __uint_as_float(G.x[r][v].z), x3 = __uint_as_float(G.x[r][v].w);
+                        const float x0 = __uint_as_float(G[r][v].x), x1 = __uint_as_float(G[r][v].y);
+                        const float x2 = __uint_as_float(G[r][v].z), x3 = __uint_as_float(G[r][v].w);
                         iu32x2 h = {ipack_bf16(x0, x1), ipack_bf16(x2, x3)};
                         *(iu32x2*)(xr + ch[v] * 2) = h;
                         if (XP == 2) {
@@ -287,138 +240,122 @@ __global__ __launch_bounds__(kInferWaves * kWave) void k_infer(const InferParams
             }
     };
 
+    // One step of the pipeline.  On entry: Xc holds this wave's rows of tile i, the partial dot products of tile i
+    // are in LDS, the rows of tile i + 1 are on their way into Xn, Xf is free.
     float cmax = 0.f;
-    // |x|^2 of the wave's rows, taken when they are staged (every lane ends up with the sums)
-    auto row_norms = [&](const Rows& G, float (&xn2)[RPW]) {
+    auto step = [&](Rows& Xc, Rows& Xn, Rows& Xf, int64_t i) {
+        const int64_t t = tile_at(i);
+        long long fetched = 0;
+        if (DYN && threadIdx.x == 0) fetched = fetch();  // the tile of step i + DEPTH + 1; queued at the end of the step
+        load_rows(Xf, i + DEPTH);  // the rows DEPTH tiles ahead are requested first: nothing below has to precede them
+        // ---- rank the centroids of this wave's rows of tile i ----
+        int idx[RPW];
 #pragma unroll
         for (int r = 0; r < RPW; r++) {
-            float a = 0.f;
+            const int trow = wave * RPW + r;
+            const int64_t row = t * ROWS + trow;
+            // best score, its cluster (the lowest index among equal scores), and the best of the others
+            int sc[NSLOT];  // score keys
+            int m1 = 0x7fffffff;
+#pragma unroll
+            for (int j = 0; j < NSLOT; j++) {
+                const int k = lane + kWave * j;
+                sc[j] = 0x7fffffff;
+                if (K16 % kWave == 0 || k < K16) {
+                    const float* sp = s_dots + (size_t)trow * SC * K16 + k;
+                    float dot = sp[0];
+#pragma unroll
+                    for (int c = 1; c < SC; c++) dot += sp[c * K16];
+                    sc[j] = score_key(fmaf(-2.f, dot, s_cnorm[k]));
+                }
+                m1 = min(m1, sc[j]);
+            }
+            const int kb1 = wave_min_all(m1);
+            int i1 = 0;
+            bool found = false;
+            int m2 = 0x7fffffff;
+#pragma unroll
+            for (int j = 0; j < NSLOT; j++) {
+                const unsigned long long hit = __ballot(sc[j] == kb1);
+                const int wl = (!found && hit) ? (int)__builtin_ctzll(hit) : -1;  // wave-uniform
+                if (wl >= 0) {
+                    i1 = wl + kWave * j;
+                    found = true;
+                }
+                m2 = min(m2, lane == wl ? 0x7fffffff : sc[j]);
+            }
+            const float b1 = key_score(kb1), b2 = key_score(wave_min_all(m2));
+            // |x|^2 of the row, from the registers
+            float xn2 = 0.f;
 #pragma unroll
             for (int v = 0; v < VPR; v++) {
                 if (ch_ok[v]) {
 #pragma unroll
                     for (int e = 0; e < 4; e++) {
                         if (BF16) {
-                            const float x0 = ilo_half(G.x[r][v][e]), x1 = ihi_half(G.x[r][v][e]);
-                            a = fmaf(x0, x0, fmaf(x1, x1, a));
+                            const float x0 = ilo_half(Xc[r][v][e]), x1 = ihi_half(Xc[r][v][e]);
+                            xn2 = fmaf(x0, x0, fmaf(x1, x1, xn2));
                         } else {
-                            const float x0 = __uint_as_float(G.x[r][v][e]);
-                            a = fmaf(x0, x0, a);
+                            const float x0 = __uint_as_float(Xc[r][v][e]);
+                            xn2 = fmaf(x0, x0, xn2);
                         }
                     }
                 }
             }
-            xn2[r] = wave_sum_all(a);
-        }
-    };
-    // Nearest centroid of row `trow` of the tile whose partial dot products are in LDS (row number `row`, squared
-    // norm xn2; getx(v) gives vector v of the row).  Returns the cluster; dmin = squared distance to it.
-    auto rank_row = [&](int trow, int64_t row, float xn2, auto getx, float& dmin) -> int {
-        // best score, its cluster (the lowest index among equal scores), and the best of the others
-        int sc[NSLOT];  // score keys
-        int m1 = 0x7fffffff;
+            xn2 = wave_sum_all(xn2);
+            // (the hardware square root is good to 1 ulp; the bound only has to err on the large side)
+            const float T = p.tau * (1.000001f * __builtin_amdgcn_sqrtf(xn2)) * cmax + p.tau2 * cmax * cmax;
+            if (row < p.N && !(b2 - b1 > T)) {  // wave-uniform: every lane holds the row's b1, b2
+                // exact re-rank: direct-form double-precision distance to every centroid whose score is inside the bound
+                const float thr = b1 + T;
+                double dbest = __builtin_inf();
+                int kbest = 0x7fffffff;
 #pragma unroll
-        for (int j = 0; j < NSLOT; j++) {
-            const int k = lane + kWave * j;
-            sc[j] = 0x7fffffff;
-            if (K16 % kWave == 0 || k < K16) {
-                const float* sp = s_dots + (size_t)trow * SC * K16 + k;
-                float dot = sp[0];
+                for (int j = 0; j < NSLOT; j++) {
+                    unsigned long long m = __ballot(sc[j] <= score_key(thr) && lane + kWave * j < p.K);
+                    while (m) {
+                        const int l = __builtin_amdgcn_readfirstlane(__builtin_ctzll(m));
+                        m &= m - 1;
+                        const int k = l + kWave * j;
+                        const float* cr = p.cent + (int64_t)k * p.D;
+                        double d = 0.0;
 #pragma unroll
-                for (int c = 1; c < SC; c++) dot += sp[c * K16];
-                sc[j] = score_key(fmaf(-2.f, dot, s_cnorm[k]));
-            }
-            m1 = min(m1, sc[j]);
-        }
-        const int kb1 = wave_min_all(m1);
-        int i1 = 0;
-        bool found = false;
-        int m2 = 0x7fffffff;
+                        for (int v = 0; v < VPR; v++) {
+                            if (ch_ok[v]) {
+                                const if32x4 c0 = *(const if32x4*)(cr + ch[v]);
+                                if (BF16) {
+                                    const if32x4 c1 = *(const if32x4*)(cr + ch[v] + 4);
 #pragma unroll
-        for (int j = 0; j < NSLOT; j++) {
-            const unsigned long long hit = __ballot(sc[j] == kb1);
-            const int wl = (!found && hit) ? (int)__builtin_ctzll(hit) : -1;  // wave-uniform
-            if (wl >= 0) {
-                i1 = wl + kWave * j;
-                found = true;
-            }
-            m2 = min(m2, lane == wl ? 0x7fffffff : sc[j]);
-        }
-        const float b1 = key_score(kb1), b2 = key_score(wave_min_all(m2));
-        // (the hardware square root is good to 1 ulp; the bound only has to err on the large side)
-        const float T = p.tau * (1.000001f * __builtin_amdgcn_sqrtf(xn2)) * cmax + p.tau2 * cmax * cmax;
-        dmin = fmaxf(xn2 + b1, 0.f);
-        if (row < p.N && !(b2 - b1 > T)) {  // wave-uniform: every lane holds the row's b1, b2
-            // exact re-rank: direct-form double-precision distance to every centroid whose score is inside the bound
-            const int kthr = score_key(b1 + T);
-            double dbest = __builtin_inf();
-            int kbest = 0x7fffffff;
-            iu32x4 xv[VPR];
+                                    for (int e = 0; e < 4; e++) {
+                                        const double d0 = (double)ilo_half(Xc[r][v][e]) - (double)(e < 2 ? c0[2 * e] : c1[2 * e - 4]);
+                                        const double d1 = (double)ihi_half(Xc[r][v][e]) - (double)(e < 2 ? c0[2 * e + 1] : c1[2 * e - 3]);
+                                        d = fma(d0, d0, d);
+                                        d = fma(d1, d1, d);
+                                    }
+                                } else {
 #pragma unroll
-            for (int v = 0; v < VPR; v++) xv[v] = getx(v);
-#pragma unroll
-            for (int j = 0; j < NSLOT; j++) {
-                unsigned long long m = __ballot(sc[j] <= kthr && lane + kWave * j < p.K);
-                while (m) {
-                    const int l = __builtin_amdgcn_readfirstlane(__builtin_ctzll(m));
-                    m &= m - 1;
-                    const int k = l + kWave * j;
-                    const float* cr = p.cent + (int64_t)k * p.D;
-                    double d = 0.0;
-#pragma unroll
-                    for (int v = 0; v < VPR; v++) {
-                        if (ch_ok[v]) {
-                            const if32x4 c0 = *(const if32x4*)(cr + ch[v]);
-                            if (BF16) {
-                                const if32x4 c1 = *(const if32x4*)(cr + ch[v] + 4);
-#pragma unroll
-                                for (int e = 0; e < 4; e++) {
-                                    const double d0 = (double)ilo_half(xv[v][e]) - (double)(e < 2 ? c0[2 * e] : c1[2 * e - 4]);
-                                    const double d1 = (double)ihi_half(xv[v][e]) - (double)(e < 2 ? c0[2 * e + 1] : c1[2 * e - 3]);
-                                    d = fma(d0, d0, d);
-                                    d = fma(d1, d1, d);
-                                }
-                            } else {
-#pragma unroll
-                                for (int e = 0; e < 4; e++) {
-                                    const double d0 = (double)__uint_as_float(xv[v][e]) - (double)c0[e];
-                                    d = fma(d0, d0, d);
+                                    for (int e = 0; e < 4; e++) {
+                                        const double d0 = (double)__uint_as_float(Xc[r][v][e]) - (double)c0[e];
+                                        d = fma(d0, d0, d);
+                                    }
                                 }
                             }
                         }
-                    }
-                    d = wave_sum(d);
-                    if (d < dbest || (d == dbest && k < kbest)) {
-                        dbest = d;
-                        kbest = k;
+                        d = wave_sum(d);
+                        if (d < dbest || (d == dbest && k < kbest)) {
+                            dbest = d;
+                            kbest = k;
+                        }
                     }
                 }
+                if (kbest != 0x7fffffff) i1 = kbest;
             }
-            if (kbest != 0x7fffffff) {
-                i1 = kbest;
-                dmin = (float)dbest;
-            }
-        }
-        // (non-finite rows have no defined result; whatever they rank first, the index stays inside the tables)
-        return __builtin_amdgcn_readfirstlane(i1 < p.K ? i1 : p.K - 1);
-    };
-
-    // ---- inference.  One step; on entry: Xc holds this wave's rows of tile i (squared norms xc), the partial dot
-    // products of tile i are in LDS, the rows of tile i + 1 are on their way into Xn, Xf is free. ----
-    auto step_apply = [&](Rows& Xc, Rows& Xn, Rows& Xf, float (&xc)[RPW], int64_t i) {
-        const int64_t t = tile_at(i);
-        long long fetched = 0;
-        if (DYN && threadIdx.x == 0) fetched = fetch();  // the tile of step i + DEPTH + 1; queued at the end of the step
-        load_rows(Xf, i + DEPTH);  // the rows DEPTH tiles ahead are requested first: nothing below has to precede them
-        int idx[RPW];
-#pragma unroll
-        for (int r = 0; r < RPW; r++) {
-            const int64_t row = t * ROWS + wave * RPW + r;
-            float dmin;
-            idx[r] = rank_row(wave * RPW + r, row, xc[r], [&](int v) { return Xc.x[r][v]; }, dmin);
+            // (non-finite rows have no defined result; whatever they rank first, the index stays inside the tables)
+            idx[r] = __builtin_amdgcn_readfirstlane(i1 < p.K ? i1 : p.K - 1);
             if (p.assign && lane == 0 && row < p.N) p.assign[row] = idx[r];
         }
-        // gamma / beta rows of tile i: requested now, used after the contraction of the next tile
+
+        // ---- gamma / beta rows of tile i: requested now, used after the contraction of the next tile ----
         if32x4 gv[RPW][VPR][BF16 ? 2 : 1], bv[RPW][VPR][BF16 ? 2 : 1];
 #pragma unroll
         for (int r = 0; r < RPW; r++) {
@@ -435,13 +372,12 @@ __global__ __launch_bounds__(kInferWaves * kWave) void k_infer(const InferParams
                 }
             }
         }
-        // the rows of tile i + 1 (in flight since an earlier step) go to LDS
+        // ---- the rows of tile i + 2 are requested, those of tile i + 1 (in flight since the last step) go to LDS ----
         stage(Xn);
-        float xnext[RPW];
-        row_norms(Xn, xnext);
         __syncthreads();
-        contract();  // tile i + 1 (after the last tile: rows past the end, to no effect)
-        // affine map of this wave's rows of tile i, from the registers
+        contract();  // tile i + 1 (after the last tile: the last tile once more, to no effect)
+
+        // ---- affine map of this wave's rows of tile i, from the registers ----
 #pragma unroll
         for (int r = 0; r < RPW; r++) {
             const int64_t row = t * ROWS + wave * RPW + r;
@@ -451,159 +387,62 @@ __global__ __launch_bounds__(kInferWaves * kWave) void k_infer(const InferParams
                 iu32x4 o;
                 if (BF16) {
                     const if32x4 g0 = gv[r][v][0], g1 = gv[r][v][BF16 ? 1 : 0], b0 = bv[r][v][0], b1 = bv[r][v][BF16 ? 1 : 0];
-                    const iu32x4 w = Xc.x[r][v];
+                    const iu32x4 w = Xc[r][v];
                     o.x = ipack_bf16(fmaf(g0.x, ilo_half(w.x), b0.x), fmaf(g0.y, ihi_half(w.x), b0.y));
                     o.y = ipack_bf16(fmaf(g0.z, ilo_half(w.y), b0.z), fmaf(g0.w, ihi_half(w.y), b0.w));
                     o.z = ipack_bf16(fmaf(g1.x, ilo_half(w.z), b1.x), fmaf(g1.y, ihi_half(w.z), b1.y));
                     o.w = ipack_bf16(fmaf(g1.z, ilo_half(w.w), b1.z), fmaf(g1.w, ihi_half(w.w), b1.w));
                 } else {
                     const if32x4 gg = gv[r][v][0], bb = bv[r][v][0];
-                    o.x = __float_as_uint(fmaf(gg.x, __uint_as_float(Xc.x[r][v].x), bb.x));
-                    o.y = __float_as_uint(fmaf(gg.y, __uint_as_float(Xc.x[r][v].y), bb.y));
-                    o.z = __float_as_uint(fmaf(gg.z, __uint_as_float(Xc.x[r][v].z), bb.z));
-                    o.w = __float_as_uint(fmaf(gg.w, __uint_as_float(Xc.x[r][v].w), bb.w));
+                    o.x = __float_as_uint(fmaf(gg.x, __uint_as_float(Xc[r][v].x), bb.x));
+                    o.y = __float_as_uint(fmaf(gg.y, __uint_as_float(Xc[r][v].y), bb.y));
+                    o.z = __float_as_uint(fmaf(gg.z, __uint_as_float(Xc[r][v].z), bb.z));
+                    o.w = __float_as_uint(fmaf(gg.w, __uint_as_float(Xc[r][v].w), bb.w));
                 }
                 if (row < p.N && ch_ok[v]) __builtin_nontemporal_store(o, (iu32x4*)(orow + ch[v]));
             }
         }
-#pragma unroll
-        for (int r = 0; r < RPW; r++) xc[r] = xnext[r];
         if (DYN && threadIdx.x == 0) s_queue[(i + DEPTH + 1) & 7] = fetched;
         __syncthreads();  // the partial dot products of tile i + 1 are complete
     };
 
-    // ---- assignment pass.  The rows are not needed once they are staged (the rare exact re-rank fetches its row
-    // again), so a buffer is free as soon as its tile is in LDS: DEPTH buffers.  On entry: the partial dot products
-    // of tile i are in LDS, xc / pc hold the squared norms and previous clusters of this wave's rows of tile i, the
-    // rows of tile i + 1 are on their way into Xn, Xf is free. ----
-    auto step_assign = [&](Rows& Xn, Rows& Xf, float (&xc)[RPW], int (&pc)[RPW], int64_t i) {
-        const int64_t t = tile_at(i);
-        long long fetched = 0;
-        if (DYN && threadIdx.x == 0) fetched = fetch();
-        load_rows(Xf, i + DEPTH);
-#pragma unroll
-        for (int r = 0; r < RPW; r++) {
-            const int64_t row = t * ROWS + wave * RPW + r;
-            const T* xrow = (const T*)p.lq + (row < p.N ? row : p.N - 1) * p.D;
-            float dmin;
-            const int a = rank_row(wave * RPW + r, row, xc[r],
-                                   [&](int v) { return *(const iu32x4*)(xrow + (ch_ok[v] ? ch[v] : 0)); }, dmin);
-            if (lane == 0 && row < p.N) {
-                // assignment, counts, first rows, objective; a row whose cluster changed joins the workgroup's list
-                // in LDS, or the device-wide list directly once that is full
-                p.assign[row] = a;
-                if (p.counts) atomicAdd(&s_hist[a], 1);
-                if (p.rep) atomicMin(&s_rep[a], (unsigned long long)row);
-                in_acc += (double)dmin;
-                const int prev = p.delta_mode ? pc[r] : -1;
-                if (p.list && prev != a) {
-                    const unsigned long long entry =
-                        ((unsigned long long)row << 24) | ((unsigned long long)(prev + 1) << 12) | (unsigned long long)a;
-                    const int pos = atomicAdd(&s_misc[0], 1);
-                    if (pos < p.list_cap)
-                        ((unsigned long long*)(smem + p.off_list))[pos] = entry;
-                    else
-                        p.list[atomicAdd(p.list_count, 1u)] = entry;
-                }
-            }
-        }
-        stage(Xn);
-        row_norms(Xn, xc);
-#pragma unroll
-        for (int r = 0; r < RPW; r++) pc[r] = Xn.prev[r];
-        __syncthreads();
-        contract();
-        if (DYN && threadIdx.x == 0) s_queue[(i + DEPTH + 1) & 7] = fetched;
-        __syncthreads();
-    };
-
-    Rows X0, X1, X2, X3;  // as many as the mode and DEPTH need
-    float xc[RPW];
-    int pc[RPW];
+    Rows X0, X1, X2, X3;  // X3 only with DEPTH == 3
     load_rows(X0, 0);
     load_rows(X1, 1);
     if (DEPTH == 3) load_rows(X2, 2);
-    __syncthreads();  // the zeroed tile, the norms and the bookkeeping tables are in place
+    __syncthreads();  // the zeroed tile and the norms are in place
     {
         float cm2 = 0.f;
         for (int k = lane; k < p.K; k += kWave) cm2 = fmaxf(cm2, s_cnorm[k]);
         cmax = sqrtf(wave_all(cm2, [](float a, float b) { return fmaxf(a, b); }));
     }
-    if (tile_seq(0) >= p.ntiles) return;  // uniform over the workgroup (nothing was counted or listed)
+    if (tile_at(0) >= p.ntiles) return;  // uniform over the workgroup
     stage(X0);
-    row_norms(X0, xc);
-#pragma unroll
-    for (int r = 0; r < RPW; r++) pc[r] = X0.prev[r];
     __syncthreads();
     contract();
     __syncthreads();
-    // the buffers rotate by name
-    if (MODE == INFER_APPLY) {
-        // (rows of tile i, rows of tile i + 1, free buffer)
-        if (DEPTH == 3) {
-            for (int64_t i = 0;;) {
-                step_apply(X0, X1, X3, xc, i);
-                if (tile_seq(++i) >= p.ntiles) break;
-                step_apply(X1, X2, X0, xc, i);
-                if (tile_seq(++i) >= p.ntiles) break;
-                step_apply(X2, X3, X1, xc, i);
-                if (tile_seq(++i) >= p.ntiles) break;
-                step_apply(X3, X0, X2, xc, i);
-                if (tile_seq(++i) >= p.ntiles) break;
-            }
-        } else {
-            for (int64_t i = 0;;) {
-                step_apply(X0, X1, X2, xc, i);
-                if (tile_seq(++i) >= p.ntiles) break;
-                step_apply(X1, X2, X0, xc, i);
-                if (tile_seq(++i) >= p.ntiles) break;
-                step_apply(X2, X0, X1, xc, i);
-                if (tile_seq(++i) >= p.ntiles) break;
-            }
+    // the buffers rotate by name: (rows of tile i, rows of tile i + 1, free buffer)
+    if (DEPTH == 3) {
+        for (int64_t i = 0;;) {
+            step(X0, X1, X3, i);
+            if (tile_at(++i) >= p.ntiles) break;
+            step(X1, X2, X0, i);
+            if (tile_at(++i) >= p.ntiles) break;
+            step(X2, X3, X1, i);
+            if (tile_at(++i) >= p.ntiles) break;
+            step(X3, X0, X2, i);
+            if (tile_at(++i) >= p.ntiles) break;
         }
     } else {
-        // (rows of tile i + 1, free buffer): X0 was staged above and is free
-        if (DEPTH == 3) {
-            for (int64_t i = 0;;) {
-                step_assign(X1, X0, xc, pc, i);
-                if (tile_seq(++i) >= p.ntiles) break;
-                step_assign(X2, X1, xc, pc, i);
-                if (tile_seq(++i) >= p.ntiles) break;
-                step_assign(X0, X2, xc, pc, i);
-                if (tile_seq(++i) >= p.ntiles) break;
-            }
-        } else {
-            for (int64_t i = 0;;) {
-                step_assign(X1, X0, xc, pc, i);
-                if (tile_seq(++i) >= p.ntiles) break;
-                step_assign(X0, X1, xc, pc, i);
-                if (tile_seq(++i) >= p.ntiles) break;
-            }
+        for (int64_t i = 0;;) {
+            step(X0, X1, X2, i);
+            if (tile_at(++i) >= p.ntiles) break;
+            step(X1, X2, X0, i);
+            if (tile_at(++i) >= p.ntiles) break;
+            step(X2, X0, X1, i);
+            if (tile_at(++i) >= p.ntiles) break;
         }
     }
-    if (MODE != INFER_ASSIGN) return;
-
-    // ---- workgroup epilogue of an assignment pass: counts, first rows, objective, changed rows ----
-    double* s_in = (double*)(s_misc + 2);
-    if (lane == 0) s_in[wave] = in_acc;
-    __syncthreads();
-    for (int k = threadIdx.x; k < p.K; k += blockDim.x) {
-        if (p.counts && s_hist[k]) atomicAdd(&p.counts[k], s_hist[k]);
-        if (p.rep && s_rep[k] != ~0ull) atomicMin(&p.rep[k], s_rep[k]);
-    }
-    if (p.inertia && threadIdx.x == 0) {
-        double tot = 0.0;
-        for (int w = 0; w < kInferWaves; w++) tot += s_in[w];
-        atomicAdd(p.inertia, tot);
-    }
-    if (!p.list) return;
-    const int cnt = s_misc[0] < p.list_cap ? s_misc[0] : p.list_cap;
-    if (cnt == 0) return;  // uniform: s_misc[0] is final after the barrier above
-    if (threadIdx.x == 0) s_misc[1] = (int)atomicAdd(p.list_count, (uint32_t)cnt);
-    __syncthreads();
-    const uint32_t base = (uint32_t)s_misc[1];
-    const unsigned long long* l_ent = (const unsigned long long*)(smem + p.off_list);
-    for (int i = threadIdx.x; i < cnt; i += blockDim.x) p.list[base + i] = l_ent[i];
 }
 
 }  // namespace cat

@@ -2,8 +2,6 @@
 // driver) and the centroid preparation kernel.  The tile kernel itself is in cat_tile_kernel.h.
 #include "cat_tile_kernel.h"
 
-#include "cat_infer.h"
-
 namespace cat {
 
 // ---- centroid preparation: (sums -> centroids), split to bf16 (hi, lo), operand order ----
@@ -312,22 +310,6 @@ static TileCfg tile_config(TileMode mode, int64_t D, int32_t K, cat_dtype dt) {
     return c;
 }
 
-// The assignment passes (cat_assign, the Lloyd loop) run on the row-tile kernel where it has an instance for the
-// shape: the centroid operand in the registers of the workgroup's waves, the rows through one LDS tile.  It shares
-// the preparation kernels, with its own cluster tiling, part count and channel order.
-static TileCfg pass_config(TileMode mode, int64_t N, int64_t D, int32_t K, cat_dtype dt) {
-    TileCfg c = tile_config(mode, D, K, dt);
-    int KT = 0, P = 0;
-    // (the workspace holds the operand for the tile kernel's cluster tiling: the row-tile kernel's may not exceed it)
-    if (c.ok && mode != TILE_APPLY && !rowtile_disabled() && rowtile_assign_config(mode == TILE_LLOYD, N, D, K, dt, &KT, &P) &&
-        KT <= c.KT) {
-        c.rowtile = true;
-        c.KT = KT;
-        c.P = P;
-    }
-    return c;
-}
-
 bool tile_supports(TileMode mode, int64_t N, int64_t D, int32_t K, cat_dtype dt) {
     // tile indices are 32-bit in the kernels and a changed-row entry keeps 40 bits of row number
     return N < ((int64_t)1 << 34) && tile_config(mode, D, K, dt).ok;
@@ -395,7 +377,7 @@ static cat_status launch_delta_prep(const void* lq, cat_dtype dt, int64_t D, int
     q.K = K;
     q.KT = c.KT;
     q.P = c.P;
-    q.f32_rows = dt == CAT_F32 && !c.rowtile;  // the row-tile kernel takes the channels of a step in plain order
+    q.f32_rows = dt == CAT_F32;
     q.KC = K < 128 ? K : 128;  // LDS panel: KC x 64 doubles, at most 64 KB
     const int64_t slices = delta_slices(D);
     const int kchunks = (K + q.KC - 1) / q.KC;
@@ -432,7 +414,7 @@ static cat_status launch_prep(cat_dtype dt, float* cent, double* base, double* d
                               double* inertia_slot, unsigned long long* rep, hipStream_t st) {
     dim3 grid(c.KT * 16), block(256);
     hipLaunchKernelGGL(k_tile_prep, grid, block, 0, st, cent, base, delta, counts_read, counts_reset, D, K, c.KT, c.P,
-                       c.nchunks, (dt == CAT_F32 && !c.rowtile) ? 1 : 0, ws.packA, ws.cnorm, inertia_slot, rep);
+                       c.nchunks, dt == CAT_F32 ? 1 : 0, ws.packA, ws.cnorm, inertia_slot, rep);
     CAT_LAUNCH_CHECK("k_tile_prep");
     return CAT_OK;
 }
@@ -451,7 +433,6 @@ cat_status launch_tile_prep_plain(cat_dtype dt, const float* cent, int64_t D, in
 }
 
 static cat_status launch_tile(const TileParams& p, const TileCfg& c, cat_dtype dt, hipStream_t st) {
-    if (c.rowtile) return rowtile_assign(p, dt, const_cast<float*>(p.cnorm), st);
     const bool bf = dt == CAT_BF16;
     switch (c.KT) {
         case 1: return bf ? launch_kt1_bf16(p, c, st) : launch_kt1_f32(p, c, st);
@@ -498,7 +479,7 @@ cat_status tile_assign(const void* lq, cat_dtype dt, int64_t N, int64_t D, int32
                        int32_t* assign, int32_t* counts, double* inertia, unsigned long long* rep,
                        const float* gamma, const float* beta, void* corrected, const TileWs& ws, hipStream_t st) {
     const TileMode mode = gamma ? TILE_APPLY : TILE_ASSIGN;
-    TileCfg c = pass_config(mode, N, D, K, dt);
+    TileCfg c = tile_config(mode, D, K, dt);
     if (!c.ok) return set_error(CAT_ERR_UNSUPPORTED, "tile kernels do not fit D=%lld K=%d", (long long)D, (int)K);
     // The preparation only reads the centroids here (no sums to fold), and the exact re-rank reads them with
     // 16-byte loads: the caller's array serves both as it is when it is aligned, else a copy in the workspace.
@@ -526,7 +507,7 @@ cat_status tile_assign(const void* lq, cat_dtype dt, int64_t N, int64_t D, int32
 cat_status tile_lloyd(const void* lq, cat_dtype dt, int64_t N, int64_t D, int32_t K, int32_t iters,
                       float* cent_io, double* sums, int32_t* assign, int32_t* counts, double* inertia,
                       unsigned long long* rep, int32_t* skipped, const TileWs& ws, const LloydWs& lw, hipStream_t st) {
-    TileCfg c = pass_config(TILE_LLOYD, N, D, K, dt);
+    TileCfg c = tile_config(TILE_LLOYD, D, K, dt);
     if (!c.ok) return set_error(CAT_ERR_UNSUPPORTED, "tile kernels do not fit D=%lld K=%d", (long long)D, (int)K);
     const size_t KD = (size_t)K * (size_t)D;
     double* base = sums;

@@ -703,7 +703,6 @@ struct TileCfg {
     bool ok = false;
     int KT = 0, P = 0, waves = 0, nchunks = 0, mode = MODE_ASSIGN;
     bool chunked = false;  // the centroid operand streams through LDS instead of living there
-    bool rowtile = false;  // the pass runs on the row-tile kernel (cat_infer.hip): KT and P are that kernel's
     uint32_t ldsA = 0, off_cnorm = 0, off_hist = 0, off_rep = 0, off_list = 0, off_misc = 0;
     size_t lds_total = 0;
 };

@@ -64,6 +64,20 @@ def test_row_tile_kernel_against_the_oracle(N, D, K, spread, alpha):
     assert torch.equal(out[torch.from_numpy(both).cuda()], out1[torch.from_numpy(both).cuda()])
 
 
+@pytest.mark.parametrize("N,D,K,spread", [(5003, 512, 16, 1.0), (3001, 1024, 30, 0.3), (2000, 256, 64, 0.05), (777, 8, 3, 1.0)])
+def test_row_tile_kernel_on_bf16_rows(N, D, K, spread):
+    lq, cent, gamma, beta = _mixture(N, D, K, seed=N + D, spread=spread, dtype="bf16")
+    out, a = _run(lq, cent, gamma, beta, "bf16", 0.8, which=2)
+    o_out, o_a = oracle.apply(lq, cent, gamma, beta, 0.8)
+    _, d1, d2 = oracle.assign(lq, cent.astype(np.float64), want_distances=True)
+    check_assignments(a, o_a, d1, d2, "row-tile kernel, bf16 rows, assignments")
+    same = a == o_a
+    check_values(host_matrix(out)[same], o_out[same], RTOL["bf16"], "row-tile kernel, bf16 rows, corrected")
+    out1, a1 = _run(lq, cent, gamma, beta, "bf16", 0.8, which=1)
+    both = torch.from_numpy(a == a1).cuda()
+    assert torch.equal(out[both].view(torch.int16), out1[both].view(torch.int16))
+
+
 def test_exact_ties_go_to_the_lowest_index():
     """Duplicated centroids and rows at exact midpoints, in half-integers so that all arithmetic is exact."""
     rng = np.random.default_rng(7)
