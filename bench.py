@@ -50,12 +50,16 @@ HBM_PEAK_GBPS = 8000.0
 # line says that it comes from profiles/, not from this run.
 TRAFFIC_SOURCES = {
     "k_tile": ("cat_tile_kernel.h", "c368204e0d3cb727b427eb617db98ee9711a7f8d82ac8120400e7d1b9dc3b32c"),
-    "k_infer": ("cat_infer_kernel.h", ""),
+    "k_infer": ("cat_infer_kernel.h", "3e0ddd9413898f44c15d9f8ddc35f7bc8085df908c46f96441599018b67b4c5f"),
 }
 TRAFFIC_COUNTERS = {
-    "cfg2": ("k_tile", (133758.9, 128011.7, 298.9, 256000.0)),
-    "cfg3": ("k_tile", (527761.6, 524299.7, 4719.2, 1048576.0)),
-    "cfg4": ("k_tile", (560549.3, 524299.7, 1191.5, 1048576.0)),
+    "cfg2": ("k_tile", (133759.4, 128011.7, 298.9, 256000.0)),
+    "cfg2_apply": ("k_infer", (129270.6, 128011.7, 266032.0, 256000.0)),
+    "cfg3": ("k_tile", (527767.7, 524299.7, 4721.1, 1048576.0)),
+    "cfg3_apply": ("k_infer", (524864.2, 524299.7, 1054739.0, 1048576.0)),
+    "cfg4": ("k_tile", (560461.8, 524299.7, 1191.4, 1048576.0)),
+    "cfg4_apply": ("k_tile", (1144058.5, 524299.7, 1049648.1, 1048576.0)),
+    "cfg5_apply": ("k_infer", (4197616.1, 4194318.0, 8413246.5, 8388608.0)),
 }
 
 
@@ -73,6 +77,11 @@ def _traffic_bytes(key, copy_bytes):
     except OSError:
         return None
     return fk * (copy_bytes / fc) + wk * (copy_bytes / wc)
+
+
+def _traffic_source(key):
+    kernel = TRAFFIC_COUNTERS[key][0] if key in TRAFFIC_COUNTERS else "k_tile"
+    return f"profiles/{kernel}_hbm_traffic.md (hardware counters of an earlier run of this kernel, not this run)"
 
 
 def _events(fn, reps, torch):
@@ -156,7 +165,7 @@ def _run_workload(name, args, torch, np, cpu_budget_s, extras):
         roof = dict(bound="hbm", kernel="k_tile (assignment pass of a Lloyd iteration)", achieved=achieved,
                     peak=HBM_PEAK_GBPS, unit="GB/s", frac=achieved / HBM_PEAK_GBPS,
                     traffic=None if args.rows else _traffic_bytes(w["name"], N * D * esize),
-                    traffic_source="profiles/k_tile_hbm_traffic.md (hardware counters of an earlier run of this kernel, not this run)",
+                    traffic_source=_traffic_source(w["name"]),
                     bytes_per_launch=alg_bytes, us_per_launch=1e3 * t_k, launches=len(ms))
         metric, unit = "cat_fit_lloyd_rows_per_s", "rows/s"
         value = N * iters / (ms_per_step * 1e-3)
@@ -176,7 +185,7 @@ def _run_workload(name, args, torch, np, cpu_budget_s, extras):
     apply_roof = dict(bound="hbm", kernel="fused inference pass (assign + gather + affine)", achieved=apply_bytes / t_ka / 1e6,
                       peak=HBM_PEAK_GBPS, unit="GB/s", frac=apply_bytes / t_ka / 1e6 / HBM_PEAK_GBPS,
                       traffic=None if args.rows else _traffic_bytes(w["name"] + "_apply", N * D * esize),
-                      traffic_source="profiles/k_infer_hbm_traffic.md (hardware counters of an earlier run of this kernel, not this run)",
+                      traffic_source=_traffic_source(w["name"] + "_apply"),
                       bytes_per_launch=apply_bytes, us_per_launch=1e3 * t_ka, launches=len(ms))
     detail.update(apply_ms=t_apply, apply_GBps=apply_bytes / t_apply / 1e6, apply_frac_hbm=apply_bytes / t_apply / 1e6 / HBM_PEAK_GBPS,
                   apply_rows_per_s=N * 1e3 / t_apply)
