@@ -174,6 +174,9 @@ static cat_status step_assign(const void* lq, cat_dtype dt, int64_t N, int64_t D
                          (int)K, (int)dt);
     if (tile_ok && path != CAT_PATH_STREAM)
         return tile_assign(lq, dt, N, D, K, cent, assign, counts, inertia, rep, nullptr, nullptr, nullptr, tw, st);
+    // shapes outside the matrix-core kernels: the LDS streaming kernel; the direct-form kernel only when asked for
+    if (path != CAT_PATH_STREAM)
+        return launch_assign_lds(lq, dt, N, D, K, cent, assign, counts, inertia, rep, nullptr, nullptr, nullptr, st);
     return launch_assign_stream(lq, dt, N, D, K, cent, assign, counts, inertia, rep, nullptr, nullptr, nullptr, st);
 }
 
@@ -545,6 +548,8 @@ static cat_status apply_impl(const char* who, const void* lq, int64_t N, int64_t
     if (tile_ok && path != CAT_PATH_STREAM)
         return tile_assign(lq, dt, N, D, K, centroids, assignments, nullptr, nullptr, nullptr, g, b, corrected, w.tile,
                            st);
+    if (path != CAT_PATH_STREAM)
+        return launch_assign_lds(lq, dt, N, D, K, centroids, assignments, nullptr, nullptr, nullptr, g, b, corrected, st);
     return launch_assign_stream(lq, dt, N, D, K, centroids, assignments, nullptr, nullptr, nullptr, g, b, corrected,
                                 st);
 }

@@ -80,6 +80,11 @@ cat_status launch_assign_stream(const void* lq, cat_dtype dt, int64_t N, int64_t
                                 const float* cent, int32_t* assign, int32_t* counts, double* inertia,
                                 unsigned long long* rep, const float* gamma, const float* beta,
                                 void* corrected, hipStream_t st);
+// The same contract on the LDS streaming kernel (cat_lds.hip): fp32 scores with the centroids staged in LDS, exact
+// double-precision re-rank of the rows inside the rounding bound.  Any D, K and row alignment.
+cat_status launch_assign_lds(const void* lq, cat_dtype dt, int64_t N, int64_t D, int32_t K, const float* cent,
+                             int32_t* assign, int32_t* counts, double* inertia, unsigned long long* rep,
+                             const float* gamma, const float* beta, void* corrected, hipStream_t st);
 // counts[k] and rep[k] from given assignments (both pre-initialised as above)
 cat_status launch_count_rep(const int32_t* assign, int64_t N, int32_t K, int32_t* counts,
                             unsigned long long* rep, hipStream_t st);
