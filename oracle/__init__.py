@@ -23,4 +23,7 @@ from .cat_oracle import (  # noqa: F401
     kmeanspp,
     fit_restarts,
     fit_early_stop,
+    fit_multi_k,
+    to_bf16,
+    apply_lp,
 )

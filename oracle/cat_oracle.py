@@ -343,3 +343,39 @@ def fit_early_stop(lq, fp, K, iters, seed=0, init_centroids=None):
     gamma, beta, counts = affine(x, fp, a, K)
     return dict(centroids=cent, gamma=gamma, beta=beta, assignments=a, counts=counts, inertia=inertia,
                 stable_at=stable_at)
+
+
+# ---------------------------------------------------------------------------
+# Fits for several cluster counts (the paper's ablation on the number of clusters, Sec. 5 and its appendix,
+# sweeps a grid of K at fixed PCA dimension and blending coefficient)
+# ---------------------------------------------------------------------------
+def fit_multi_k(lq, fp, Ks, iters, seed=0):
+    """One independent ``fit`` per cluster count in ``Ks``, each seeded with ``seed``.  Returns the list of
+    their dicts, in the order of ``Ks``.  (Sharing the reads of the rows between the fits is an implementation
+    matter: it changes nothing that is computed.)"""
+    return [fit(lq, fp, int(K), iters, seed=seed) for K in Ks]
+
+
+# ---------------------------------------------------------------------------
+# Low-precision deployment (Sec. 3.1 remarks that the clustering yields low-precision gamma, beta; the paper
+# gives no mechanism): parameters stored as bfloat16, inference output stored as bfloat16
+# ---------------------------------------------------------------------------
+def to_bf16(x):
+    """The bfloat16 value nearest to each entry of ``x`` (8 significant bits, ties to the even significand),
+    returned as float64.  From the definition: x = m * 2^e with 1/2 <= |m| < 1, so the spacing of bfloat16 numbers
+    around x is 2^(e - 8).  Exponent range is not modelled (no overflow / subnormal handling): finite inputs of
+    ordinary size only."""
+    x = np.asarray(x, dtype=np.float64)
+    m, e = np.frexp(x)
+    return np.ldexp(np.rint(m * 256.0), e - 8)  # rint rounds halves to even
+
+
+def apply_lp(lq, centroids, gamma, beta, alpha=1.0, bf16_out=True):
+    """CAT Inferencing with parameters that are stored in bfloat16: the parameters are rounded with ``to_bf16``
+    first, the method (``apply``) then runs on those values as it stands, and the corrected rows are rounded to
+    bfloat16 at the end if ``bf16_out``.  Returns (corrected, assignments, (centroids_q, gamma_q, beta_q))."""
+    cq, gq, bq = to_bf16(centroids), to_bf16(gamma), to_bf16(beta)
+    out, a = apply(lq, cq, gq, bq, alpha)
+    if bf16_out:
+        out = to_bf16(out)
+    return out, a, (cq, gq, bq)
