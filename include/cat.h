@@ -313,6 +313,33 @@ cat_status cat_alpha_sweep(const void *lq, const void *fp, const int32_t *labels
                            void *workspace, size_t workspace_bytes, void *hip_stream);
 cat_status cat_top1(const void *x, int64_t N, int64_t D, cat_dtype dt, int32_t *top1, void *hip_stream);
 
+/* ---- fits for a grid of cluster counts ----
+ * The paper's ablation on the number of clusters (Sec. 5 and the appendix on the number of clusters) fits CAT for
+ * a list of cluster counts on the same calibration rows.  cat_fit_multi_k returns, for every K in the list, what
+ * cat_fit(lq, fp, N, D, K, iters, seed, dt, NULL, ...) returns: the fits are independent and every one starts from
+ * the rows cat_init_indices(N, K, seed) picks.  Where the shape fits the matrix-core kernels, consecutive entries of
+ * the list whose clusters fill at most 128 slots together (each K rounded up to a multiple of 16) run their Lloyd
+ * loops side by side, so that one read of lq per pass serves all of them; other entries run one after the other.
+ *
+ * Ks           in, HOST array of nK cluster counts, 1 <= nK <= CAT_MAX_MULTI_K, each 1 <= K <= min(N, CAT_MAX_K)
+ * centroids, gamma, beta
+ *              out, device, (sum of Ks) x D floats each: the K rows of entry i start at row Ks[0] + .. + Ks[i-1]
+ * assignments  out, device, nK x N int32: row i holds the assignments of entry i
+ * counts       out, device, (sum of Ks) int32, nullable, laid out as the rows of centroids
+ * inertia      out, device, nK x (iters + 1) doubles, nullable
+ * workspace    cat_fit_multi_k_workspace_bytes(N, D, Ks, nK, iters, dt) bytes (0 for invalid arguments)
+ * Other arguments and errors: as cat_fit.  Enqueues on the stream; no allocation, no synchronisation.
+ * cat_debug_multi_group_tiles(t), t in {1, 2, 4, 8}: at most t 16-cluster tiles per group (default 8; 1 runs
+ * every entry on its own); process-wide, for measurements and tests; results do not depend on it. */
+#define CAT_MAX_MULTI_K 64
+size_t cat_fit_multi_k_workspace_bytes(int64_t N, int64_t D, const int32_t *Ks, int32_t nK, int32_t iters, cat_dtype dt);
+cat_status cat_fit_multi_k(const void *lq, const void *fp, int64_t N, int64_t D, const int32_t *Ks, int32_t nK,
+                           int32_t iters, uint64_t seed, cat_dtype dt,
+                           float *centroids, float *gamma, float *beta,
+                           int32_t *assignments, int32_t *counts, double *inertia,
+                           void *workspace, size_t workspace_bytes, void *hip_stream);
+cat_status cat_debug_multi_group_tiles(int tiles);
+
 /* ---- D^2-weighted seeding ("k-means++", Arthur and Vassilvitskii, SODA 2007) ----
  * An alternative to the seeded distinct rows of cat_init_indices; the paper fixes no k-means
  * initialisation (Sec. 4, Setup).  Use: cat_init_kmeanspp -> cat_fit(..., init_centroids = centroids).

@@ -23,6 +23,7 @@ from .binding import (  # noqa: F401
     cat_top1,
     cat_init_kmeanspp,
     cat_fit_restarts,
+    cat_fit_multi_k,
     cat_fit_workspace_bytes,
     cat_apply_workspace_bytes,
     library_path,

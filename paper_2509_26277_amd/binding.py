@@ -25,7 +25,8 @@ EXPORTS = ("cat_select_path", "cat_fit_workspace_bytes", "cat_apply_workspace_by
            "cat_alpha_sweep_workspace_bytes", "cat_alpha_sweep", "cat_top1",
            "cat_init_kmeanspp_workspace_bytes", "cat_init_kmeanspp",
            "cat_fit_restarts_workspace_bytes", "cat_fit_restarts", "cat_fit_early_stop", "cat_allow_early_stop",
-           "cat_apply_static", "cat_apply_static_max_workspace_bytes", "cat_debug_apply_kernel")
+           "cat_apply_static", "cat_apply_static_max_workspace_bytes", "cat_debug_apply_kernel",
+           "cat_fit_multi_k_workspace_bytes", "cat_fit_multi_k", "cat_debug_multi_group_tiles")
 
 
 class CatError(RuntimeError):
@@ -111,6 +112,13 @@ def load_library():
     lib.cat_fit_restarts.argtypes = [vp, vp, i64, i64, i32, i32, u64, i32, c.c_int, c.c_int, vp, vp, vp, vp, vp, vp, vp, vp,
                                      vp, sz, vp]
     lib.cat_fit_restarts.restype = c.c_int
+    i32p = c.POINTER(c.c_int32)
+    lib.cat_fit_multi_k_workspace_bytes.argtypes = [i64, i64, i32p, i32, i32, c.c_int]
+    lib.cat_fit_multi_k_workspace_bytes.restype = sz
+    lib.cat_fit_multi_k.argtypes = [vp, vp, i64, i64, i32p, i32, i32, u64, c.c_int, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.cat_fit_multi_k.restype = c.c_int
+    lib.cat_debug_multi_group_tiles.argtypes = [c.c_int]
+    lib.cat_debug_multi_group_tiles.restype = c.c_int
     lib.cat_debug_apply_kernel.argtypes = [c.c_int]
     lib.cat_debug_apply_kernel.restype = c.c_int
     lib.cat_debug_list_capacity.argtypes = [c.c_int]
@@ -442,6 +450,42 @@ def cat_fit_restarts(lq, fp, K, iters, seed=0, restarts=4, seeding=CAT_SEED_ROWS
                                 workspace.data_ptr(), workspace.numel(), _stream()))
     return dict(centroids=cent, gamma=gamma, beta=beta, assignments=a, counts=counts, inertia=inertia, best_run=best,
                 final_inertia=finals)
+
+
+def debug_multi_group_tiles(tiles):
+    """At most ``tiles`` 16-cluster tiles per group of ``cat_fit_multi_k`` (1 runs every entry on its own)."""
+    _check(load_library().cat_debug_multi_group_tiles(int(tiles)))
+
+
+def cat_fit_multi_k(lq, fp, Ks, iters, seed=0, want_inertia=True, workspace=None):
+    """CAT Fitting for every cluster count in ``Ks`` (cat_fit_multi_k): the fits share the reads of the rows where the
+    shape allows it.  Returns a list of dicts like ``cat_fit``'s, one per entry of ``Ks``; their tensors are views of the
+    concatenated outputs of the call."""
+    lib = load_library()
+    N, D = lq.shape
+    dt = _dt(lq)
+    dev = lq.device
+    Ks = [int(k) for k in Ks]
+    nK = len(Ks)
+    ks = (ctypes.c_int32 * max(nK, 1))(*Ks)
+    if workspace is None:
+        workspace = _workspace(lib.cat_fit_multi_k_workspace_bytes(N, D, ks, nK, iters, dt), dev)
+    tot = sum(Ks)
+    f32 = dict(dtype=torch.float32, device=dev)
+    cent, gamma, beta = torch.empty((tot, D), **f32), torch.empty((tot, D), **f32), torch.empty((tot, D), **f32)
+    a = torch.empty((nK, N), dtype=torch.int32, device=dev)
+    counts = torch.empty((tot,), dtype=torch.int32, device=dev)
+    inertia = torch.empty((nK, max(iters, 0) + 1), dtype=torch.float64, device=dev) if want_inertia else None
+    _check(lib.cat_fit_multi_k(_dev(lq, name="lq"), _dev(fp, lq.dtype, (N, D), "fp"), N, D, ks, nK, iters, seed & (2**64 - 1), dt,
+                               cent.data_ptr(), gamma.data_ptr(), beta.data_ptr(), a.data_ptr(), counts.data_ptr(),
+                               None if inertia is None else inertia.data_ptr(), workspace.data_ptr(), workspace.numel(),
+                               _stream()))
+    out, r = [], 0
+    for i, K in enumerate(Ks):
+        out.append(dict(centroids=cent[r:r + K], gamma=gamma[r:r + K], beta=beta[r:r + K], assignments=a[i],
+                        counts=counts[r:r + K], inertia=None if inertia is None else inertia[i]))
+        r += K
+    return out
 
 
 def cat_fit_pca(lq, fp, K, p, iters, seed=0, want_inertia=True, workspace=None):

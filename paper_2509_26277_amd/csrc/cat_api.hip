@@ -509,6 +509,198 @@ cat_status cat_fit_restarts(const void* lq, const void* fp, int64_t N, int64_t D
     return CAT_OK;
 }
 
+// ---- fits for a grid of cluster counts that share the reads of the rows --------------------------------
+// Consecutive entries of Ks whose 16-cluster tiles fit one launch of the tile kernel together form a group and run
+// their Lloyd loops side by side (tile_lloyd_multi); an entry the tile kernels cannot take, or one left alone, runs
+// the ordinary loop.  The plan depends on the arguments only, so the workspace query and the call agree.
+// Tiles per group.  Measured on the paper's grid of eleven counts (1 .. 256): groups pay where a pass is bound by the
+// read of the rows (counts up to about 32: 0.6 of the time of separate fits); from 8 tiles on a pass is bound by the
+// contraction and sharing the read gains nothing, and the 16-tile instances of the kernel spill registers.
+static std::atomic<int> g_multi_tiles{8};  // cat_debug_multi_group_tiles
+
+struct MultiGroup {
+    int first = 0, count = 0;
+    MultiSets ms;
+};
+static std::vector<MultiGroup> plan_multi(int64_t N, int64_t D, const int32_t* Ks, int32_t nK, cat_dtype dt) {
+    std::vector<MultiGroup> groups;
+    int cap = g_multi_tiles.load();
+    const bool tiles_allowed = g_path.load() != CAT_PATH_STREAM;
+    while (cap > 1 && !tile_multi_supports(N, D, 16 * cap, 1, dt)) cap /= 2;
+    if (!tiles_allowed || !tile_multi_supports(N, D, 16 * cap, 1, dt)) cap = 0;
+    MultiGroup cur;
+    auto flush = [&]() {
+        if (cur.count) groups.push_back(cur);
+        cur = MultiGroup();
+    };
+    for (int i = 0; i < nK; i++) {
+        const int tiles = (Ks[i] + 15) / 16;
+        const bool fits = cap > 0 && tiles <= cap;
+        if (!fits) {
+            flush();
+            cur.first = i;
+            cur.count = 1;
+            cur.ms.nsets = 0;  // marks a set that runs the ordinary loop
+            flush();
+            continue;
+        }
+        if (cur.count && (cur.ms.t0[cur.ms.nsets] + tiles > cap || cur.ms.nsets == 16 ||
+                          N * (int64_t)(cur.ms.nsets + 1) >= ((int64_t)1 << 32)))
+            flush();
+        if (!cur.count) cur.first = i;
+        cur.ms.k[cur.ms.nsets] = Ks[i];
+        cur.ms.t0[cur.ms.nsets + 1] = cur.ms.t0[cur.ms.nsets] + tiles;
+        cur.ms.nsets++;
+        cur.count++;
+    }
+    flush();
+    for (auto& g : groups)
+        if (g.count == 1) g.ms.nsets = 0;  // alone: the ordinary loop (no table of 16 assignments per row)
+    return groups;
+}
+
+struct MultiWs {
+    void* fit;            // cat_fit scratch, large enough for every K of the call (ordinary loops, the affine fits)
+    float* cent;          // slots x D   centroids of a group, by slot
+    double* sums;         // 2 x slots x D
+    int32_t* assign16;    // N x 16
+    int32_t* counts;      // slots
+    unsigned long long* rep;  // slots
+    double* inertia16;    // (iters + 1) x 16
+    int32_t* column;      // N
+    TileWs tile;
+    LloydWs lloyd;
+    size_t fit_bytes, bytes;
+};
+static MultiWs carve_multi(void* base, int64_t N, int64_t D, const int32_t* Ks, int32_t nK, int32_t slots, int32_t nsets,
+                           int32_t iters, cat_dtype dt) {
+    MultiWs w = {};
+    w.fit_bytes = 0;  // the scratch of one fit is not monotone in K (the tile kernels take some K and not others)
+    for (int i = 0; i < nK; i++) {
+        const size_t b = carve_fit(nullptr, N, D, Ks[i], dt).bytes;
+        w.fit_bytes = b > w.fit_bytes ? b : w.fit_bytes;
+    }
+    Carver c(base);
+    w.fit = c.take<char>(w.fit_bytes);
+    if (slots > 0) {
+        const size_t SD = (size_t)slots * (size_t)D;
+        w.cent = c.take<float>(SD);
+        w.sums = c.take<double>(2 * SD);
+        w.assign16 = c.take<int32_t>((size_t)N * 16);
+        w.counts = c.take<int32_t>(slots);
+        w.rep = c.take<unsigned long long>(slots);
+        w.inertia16 = c.take<double>(((size_t)iters + 1) * 16);
+        w.column = c.take<int32_t>((size_t)N);
+        const size_t tb = tile_workspace_bytes(D, slots, dt);
+        w.tile = tile_carve(base ? (void*)(c.base + c.off) : nullptr, D, slots, dt);
+        c.off += align256(tb);
+        w.lloyd = lloyd_carve(base ? (void*)(c.base + c.off) : nullptr, N * (int64_t)nsets, D, slots);
+        c.off += align256(w.lloyd.bytes);
+    }
+    w.bytes = c.off;
+    return w;
+}
+
+static cat_status check_multi(const char* who, int64_t N, int64_t D, const int32_t* Ks, int32_t nK, int32_t iters, cat_dtype dt) {
+    if (!Ks || nK < 1 || nK > CAT_MAX_MULTI_K)
+        return set_error(CAT_ERR_INVALID_ARG, "%s: need a host array of 1 .. %d cluster counts (got %d)", who, CAT_MAX_MULTI_K, (int)nK);
+    if (iters < 0) return set_error(CAT_ERR_INVALID_ARG, "%s: iters = %d is negative", who, (int)iters);
+    for (int i = 0; i < nK; i++) CAT_TRY(check_shape(who, N, D, Ks[i], dt));
+    return CAT_OK;
+}
+
+static void multi_extent(const std::vector<MultiGroup>& groups, const int32_t* Ks, int32_t nK, int32_t& Kmax, int32_t& slots,
+                         int32_t& nsets) {
+    Kmax = 1, slots = 0, nsets = 0;
+    for (int i = 0; i < nK; i++) Kmax = Ks[i] > Kmax ? Ks[i] : Kmax;
+    for (const auto& g : groups) {
+        if (!g.ms.nsets) continue;
+        slots = 16 * g.ms.t0[g.ms.nsets] > slots ? 16 * g.ms.t0[g.ms.nsets] : slots;
+        nsets = g.ms.nsets > nsets ? g.ms.nsets : nsets;
+    }
+}
+
+cat_status cat_debug_multi_group_tiles(int tiles) {
+    if (tiles != 1 && tiles != 2 && tiles != 4 && tiles != 8)
+        return set_error(CAT_ERR_INVALID_ARG, "cat_debug_multi_group_tiles: %d is not 1, 2, 4 or 8", tiles);
+    g_multi_tiles.store(tiles);
+    return CAT_OK;
+}
+
+size_t cat_fit_multi_k_workspace_bytes(int64_t N, int64_t D, const int32_t* Ks, int32_t nK, int32_t iters, cat_dtype dt) {
+    if (!Ks || nK < 1 || nK > CAT_MAX_MULTI_K || iters < 0) return 0;
+    for (int i = 0; i < nK; i++)
+        if (!shape_ok(N, D, Ks[i], dt)) return 0;
+    int32_t Kmax, slots, nsets;
+    multi_extent(plan_multi(N, D, Ks, nK, dt), Ks, nK, Kmax, slots, nsets);
+    return carve_multi(nullptr, N, D, Ks, nK, slots, nsets, iters, dt).bytes;
+}
+
+cat_status cat_fit_multi_k(const void* lq, const void* fp, int64_t N, int64_t D, const int32_t* Ks, int32_t nK, int32_t iters,
+                           uint64_t seed, cat_dtype dt, float* centroids, float* gamma, float* beta, int32_t* assignments,
+                           int32_t* counts, double* inertia, void* workspace, size_t workspace_bytes, void* hip_stream) {
+    const char* who = "cat_fit_multi_k";
+    CAT_TRY(check_multi(who, N, D, Ks, nK, iters, dt));
+    CAT_TRY(check_ptr(who, "lq", lq, 16));
+    CAT_TRY(check_ptr(who, "fp", fp, 16));
+    CAT_TRY(check_ptr(who, "centroids", centroids, 16));
+    CAT_TRY(check_ptr(who, "gamma", gamma, 16));
+    CAT_TRY(check_ptr(who, "beta", beta, 16));
+    CAT_TRY(check_ptr(who, "assignments", assignments, 4));
+    if (inertia) CAT_TRY(check_ptr(who, "inertia", inertia, 8));
+    const std::vector<MultiGroup> groups = plan_multi(N, D, Ks, nK, dt);
+    int32_t Kmax, slots, nsets;
+    multi_extent(groups, Ks, nK, Kmax, slots, nsets);
+    MultiWs w = carve_multi(workspace, N, D, Ks, nK, slots, nsets, iters, dt);
+    CAT_TRY(check_ws(who, workspace, workspace_bytes, w.bytes));
+    hipStream_t st = (hipStream_t)hip_stream;
+    std::vector<int64_t> row0(nK + 1, 0);  // first row of set i in centroids / gamma / beta / counts
+    for (int i = 0; i < nK; i++) row0[i + 1] = row0[i] + Ks[i];
+    const int64_t nin = (int64_t)iters + 1;
+    for (const auto& g : groups) {
+        if (!g.ms.nsets) {  // the ordinary fit
+            const int i = g.first;
+            const int32_t K = Ks[i];
+            FitWs fw = carve_fit(w.fit, N, D, K, dt);
+            float* cent_i = centroids + row0[i] * D;
+            int32_t* asg_i = assignments + (int64_t)i * N;
+            CAT_TRY(run_lloyd(lq, dt, N, D, K, iters, seed, nullptr, cent_i, asg_i, inertia ? inertia + i * nin : nullptr, fw, st));
+            CAT_TRY(step_stats(lq, fp, dt, asg_i, N, D, K, fw.counts, fw.rep, cent_i, fw, gamma + row0[i] * D,
+                               beta + row0[i] * D, st));
+            if (counts) CAT_TRY(launch_copy_words(fw.counts, counts + row0[i], K, st));
+            continue;
+        }
+        const MultiSets& ms = g.ms;
+        const int32_t gslots = 16 * ms.t0[ms.nsets];
+        // seeded rows of every set into its slots; the other slots stay zero rows with zero counts
+        CAT_TRY(launch_fill_zero(w.cent, (size_t)gslots * D * sizeof(float), st));
+        FitWs fw = carve_fit(w.fit, N, D, Kmax, dt);
+        for (int j = 0; j < ms.nsets; j++) {
+            CAT_TRY(launch_init_indices(N, ms.k[j], seed, fw.idx, st));
+            CAT_TRY(launch_gather_rows(lq, dt, D, ms.k[j], fw.idx, w.cent + (size_t)16 * ms.t0[j] * D, st));
+        }
+        LloydWs lw = w.lloyd;
+        lw.sort_ws = fw.sort;
+        CAT_TRY(tile_lloyd_multi(lq, dt, N, D, ms, iters, w.cent, w.sums, w.assign16, w.counts, inertia ? w.inertia16 : nullptr,
+                                 w.rep, w.column, w.tile, lw, st));
+        for (int j = 0; j < ms.nsets; j++) {
+            const int i = g.first + j;
+            const int32_t K = ms.k[j], slot0 = 16 * ms.t0[j];
+            float* cent_i = centroids + row0[i] * D;
+            int32_t* asg_i = assignments + (int64_t)i * N;
+            CAT_TRY(launch_multi_column(w.assign16, N, j, slot0, asg_i, st));
+            CAT_TRY(launch_copy_words(w.cent + (size_t)slot0 * D, cent_i, (int64_t)K * D, st));
+            FitWs fk = carve_fit(w.fit, N, D, K, dt);
+            CAT_TRY(step_stats(lq, fp, dt, asg_i, N, D, K, w.counts + slot0, w.rep + slot0, cent_i, fk, gamma + row0[i] * D,
+                               beta + row0[i] * D, st));
+            if (counts) CAT_TRY(launch_copy_words(w.counts + slot0, counts + row0[i], K, st));
+            if (inertia)
+                CAT_TRY(launch_copy_cols((const float*)(w.inertia16 + j), nin, 32, (float*)(inertia + i * nin), 2, 2, st));
+        }
+    }
+    return CAT_OK;
+}
+
 // Argument checks and launches of CAT Inferencing over a scratch buffer of `workspace_bytes` bytes at `workspace`
 // (the caller's for cat_apply, the library's own for cat_apply_static).
 static cat_status apply_impl(const char* who, const void* lq, int64_t N, int64_t D, int32_t K, cat_dtype dt,

@@ -49,6 +49,25 @@ cat_status tile_lloyd(const void* lq, cat_dtype dt, int64_t N, int64_t D, int32_
                       float* cent_io, double* sums, int32_t* assign, int32_t* counts, double* inertia,
                       unsigned long long* rep, int32_t* skipped, const TileWs& ws, const LloydWs& lw, hipStream_t st);
 
+// Several independent centroid sets side by side: Lloyd loops for a grid of cluster counts that share every read of
+// the rows.  Set s owns the 16-cluster tiles t0[s] .. t0[s + 1] - 1 of the concatenation, of whose slots the first
+// k[s] hold centroids (the others stay empty).
+struct MultiSets {
+    int32_t nsets = 0;
+    int32_t k[16] = {};
+    int32_t t0[17] = {};
+};
+bool tile_multi_supports(int64_t N, int64_t D, int32_t slots, int32_t nsets, cat_dtype dt);
+// tile_lloyd over the concatenated slots.  cent_io, counts, rep are indexed by slot (empty slots: zero rows, zero
+// counts); sums is 2 x slots x D doubles; assign16 is the N x 16 table of slot numbers (set s in column s);
+// inertia16 (nullable) takes (iters + 1) x 16 doubles, set s in column s; `column` is N int32 of scratch; the
+// changed-row list of lw holds N x nsets entries.
+cat_status tile_lloyd_multi(const void* lq, cat_dtype dt, int64_t N, int64_t D, const MultiSets& ms, int32_t iters,
+                            float* cent_io, double* sums, int32_t* assign16, int32_t* counts, double* inertia16,
+                            unsigned long long* rep, int32_t* column, const TileWs& ws, const LloydWs& lw, hipStream_t st);
+// column s of the N x 16 table as cluster numbers of the set (slot number minus slot0)
+cat_status launch_multi_column(const int32_t* assign16, int64_t N, int32_t s, int32_t slot0, int32_t* out, hipStream_t st);
+
 // Capacity of the per-workgroup changed-row list (cat_debug_list_capacity in cat.h).
 int lloyd_list_capacity();
 

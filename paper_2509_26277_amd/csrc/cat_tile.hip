@@ -15,7 +15,7 @@ __global__ __launch_bounds__(256) void k_tile_prep(float* cent, double* base, do
                                                    const int32_t* counts_read, int32_t* counts_reset,
                                                    int64_t D, int32_t K, int32_t KT, int32_t P, int32_t nchunks, int f32_rows,
                                                    uint16_t* packA, float* cnorm, double* inertia_slot,
-                                                   unsigned long long* rep) {
+                                                   int32_t inertia_n, unsigned long long* rep) {
     __shared__ double s_red[256];
     const int k = blockIdx.x;
     const int t = k >> 4, m = k & 15;
@@ -63,7 +63,7 @@ __global__ __launch_bounds__(256) void k_tile_prep(float* cent, double* base, do
             if (counts_reset) counts_reset[k] = 0;
             if (rep) rep[k] = ~0ull;
         }
-        if (k == 0 && inertia_slot) *inertia_slot = 0.0;
+        if (k < inertia_n && inertia_slot) inertia_slot[k] = 0.0;  // one per centroid set (at most 16 <= gridDim.x)
     }
 }
 
@@ -95,6 +95,7 @@ struct DeltaParams {
     uint16_t* packA;
     double* norm_part;           // slices x K
     double* inertia_slot;
+    int32_t inertia_n;           // objective entries at inertia_slot (one per centroid set)
     unsigned long long* rep;
     int32_t* skipped;            // nullable: early stop allowed; counts the passes that were not run
 };
@@ -137,10 +138,8 @@ __global__ __launch_bounds__(kDeltaWaves * kWave) void k_delta_prep(const DeltaP
             if (q.rep) q.rep[k] = ~0ull;
         }
         for (int s = threadIdx.x; s < nslices; s += blockDim.x) q.done_next[s] = 0;
-        if (threadIdx.x == 0) {
-            *q.list_count_next = 0;
-            if (q.inertia_slot) *q.inertia_slot = 0.0;
-        }
+        if (threadIdx.x == 0) *q.list_count_next = 0;
+        if ((int)threadIdx.x < q.inertia_n && q.inertia_slot) q.inertia_slot[threadIdx.x] = 0.0;
     }
     const uint32_t per = (len + q.G - 1) / q.G;
     const uint32_t e0 = blockIdx.x * per;
@@ -264,7 +263,7 @@ __global__ __launch_bounds__(kDeltaWaves * kWave) void k_delta_prep(const DeltaP
 
 static inline uint32_t up16(size_t x) { return (uint32_t)((x + 15) & ~(size_t)15); }
 
-static TileCfg tile_config(TileMode mode, int64_t D, int32_t K, cat_dtype dt) {
+static TileCfg tile_config(TileMode mode, int64_t D, int32_t K, cat_dtype dt, bool two_parts_only = false) {
     TileCfg c;
     const int K16 = (K + 15) & ~15;
     int KT = 1;
@@ -279,6 +278,7 @@ static TileCfg tile_config(TileMode mode, int64_t D, int32_t K, cat_dtype dt) {
     for (int pass = 0; pass < 4; pass++) {
         const bool chunked = pass >= 2;
         const int P = (pass & 1) ? 1 : 2;
+        if (two_parts_only && P != 2) continue;
         const size_t ldsA = chunked ? (size_t)2 * 4 * KT * P * 1024 : (size_t)nchunks * 4 * KT * P * 1024;
         for (int waves = kMaxWaves; waves >= kMaxWaves; waves -= 2) {
             size_t off = ldsA;
@@ -292,7 +292,7 @@ static TileCfg tile_config(TileMode mode, int64_t D, int32_t K, cat_dtype dt) {
             t.off_list = up16(off);
             off = t.off_list + (lists ? (size_t)kListCap * 8 : 0);
             t.off_misc = up16(off);
-            off = t.off_misc + 16 + 8 * kMaxWaves;
+            off = t.off_misc + 16 + 8 * kMaxWaves + 8 * 16;  // list count, objective per wave, objective per centroid set
             if (off > kLdsLimit) continue;
             t.ok = true;
             t.KT = KT;
@@ -370,7 +370,8 @@ LloydWs lloyd_carve(void* base, int64_t N, int64_t D, int32_t K) {
 static cat_status launch_delta_prep(const void* lq, cat_dtype dt, int64_t D, int32_t K, const TileCfg& c,
                                     const TileWs& ws, const LloydWs& lw, int par, float* cent, double* base,
                                     double* delta, const int32_t* counts_prev, int32_t* counts_next,
-                                    double* inertia_slot, unsigned long long* rep, int32_t* skipped, hipStream_t st) {
+                                    double* inertia_slot, unsigned long long* rep, int32_t* skipped, hipStream_t st,
+                                    int32_t inertia_n = 1) {
     DeltaParams q = {};
     q.lq = lq;
     q.D = D;
@@ -397,6 +398,7 @@ static cat_status launch_delta_prep(const void* lq, cat_dtype dt, int64_t D, int
     q.packA = ws.packA;
     q.norm_part = lw.norm_part;
     q.inertia_slot = inertia_slot;
+    q.inertia_n = inertia_n;
     q.rep = rep;
     q.skipped = skipped;
     dim3 grid((unsigned)q.G, (unsigned)slices, (unsigned)kchunks), block(kDeltaWaves * kWave);
@@ -411,10 +413,10 @@ static cat_status launch_delta_prep(const void* lq, cat_dtype dt, int64_t D, int
 
 static cat_status launch_prep(cat_dtype dt, float* cent, double* base, double* delta, const int32_t* counts_read,
                               int32_t* counts_reset, int64_t D, int32_t K, const TileCfg& c, const TileWs& ws,
-                              double* inertia_slot, unsigned long long* rep, hipStream_t st) {
+                              double* inertia_slot, unsigned long long* rep, hipStream_t st, int32_t inertia_n = 1) {
     dim3 grid(c.KT * 16), block(256);
     hipLaunchKernelGGL(k_tile_prep, grid, block, 0, st, cent, base, delta, counts_read, counts_reset, D, K, c.KT, c.P,
-                       c.nchunks, dt == CAT_F32 ? 1 : 0, ws.packA, ws.cnorm, inertia_slot, rep);
+                       c.nchunks, dt == CAT_F32 ? 1 : 0, ws.packA, ws.cnorm, inertia_slot, inertia_n, rep);
     CAT_LAUNCH_CHECK("k_tile_prep");
     return CAT_OK;
 }
@@ -427,7 +429,7 @@ cat_status launch_tile_prep_plain(cat_dtype dt, const float* cent, int64_t D, in
     dim3 grid(KT * 16), block(256);
     hipLaunchKernelGGL(k_tile_prep, grid, block, 0, st, const_cast<float*>(cent), (double*)nullptr, (double*)nullptr,
                        (const int32_t*)nullptr, (int32_t*)nullptr, D, K, KT, P, nchunks, rows_layout_f32, packA, cnorm,
-                       (double*)nullptr, (unsigned long long*)nullptr);
+                       (double*)nullptr, 0, (unsigned long long*)nullptr);
     CAT_LAUNCH_CHECK("k_tile_prep");
     return CAT_OK;
 }
@@ -566,6 +568,97 @@ cat_status tile_lloyd(const void* lq, cat_dtype dt, int64_t N, int64_t D, int32_
                 CAT_T(launch_segsum_sorted(1, lq, nullptr, dt, assign, cnt_t, N, D, K, nullptr, nullptr, base, lw.sort_ws, st));
             else
                 CAT_T(launch_segsum(1, lq, nullptr, dt, assign, N, D, K, nullptr, nullptr, base, st));
+        }
+    }
+#undef CAT_T
+    return CAT_OK;
+}
+
+// ---- several centroid sets side by side: fits for a grid of cluster counts that share every read of the rows ----
+// Column `s` of the N x 16 assignment table of the multi-set passes (slot numbers of the concatenation), as cluster
+// numbers of that set.
+__global__ __launch_bounds__(256) void k_multi_column(const int32_t* assign16, int64_t N, int32_t s, int32_t slot0,
+                                                      int32_t* out) {
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < N) out[i] = assign16[i * 16 + s] - slot0;
+}
+
+cat_status launch_multi_column(const int32_t* assign16, int64_t N, int32_t s, int32_t slot0, int32_t* out, hipStream_t st) {
+    const int64_t blocks = (N + 255) / 256;
+    hipLaunchKernelGGL(k_multi_column, dim3((unsigned)blocks), dim3(256), 0, st, assign16, N, s, slot0, out);
+    CAT_LAUNCH_CHECK("k_multi_column");
+    return CAT_OK;
+}
+
+bool tile_multi_supports(int64_t N, int64_t D, int32_t slots, int32_t nsets, cat_dtype dt) {
+    // only with the two-part operand: the one-part variants rank with a wide error bound (many exact re-ranks) and
+    // leave an objective of a few digits, which a set would not get when fitted alone
+    return nsets >= 1 && nsets <= 16 && slots % 16 == 0 && N * (int64_t)nsets < ((int64_t)1 << 32) &&
+           N < ((int64_t)1 << 34) && tile_config(TILE_LLOYD, D, slots, dt, true).ok;
+}
+
+cat_status tile_lloyd_multi(const void* lq, cat_dtype dt, int64_t N, int64_t D, const MultiSets& ms, int32_t iters,
+                            float* cent_io, double* sums, int32_t* assign16, int32_t* counts, double* inertia16,
+                            unsigned long long* rep, int32_t* column, const TileWs& ws, const LloydWs& lw, hipStream_t st) {
+    const int32_t K = 16 * ms.t0[ms.nsets];  // slots of the concatenation
+    if (!tile_multi_supports(N, D, K, ms.nsets, dt))
+        return set_error(CAT_ERR_UNSUPPORTED, "tile kernels do not fit D=%lld with %d cluster slots in %d sets", (long long)D,
+                         (int)K, (int)ms.nsets);
+    TileCfg c = tile_config(TILE_LLOYD, D, K, dt, true);
+    const size_t KD = (size_t)K * (size_t)D;
+    double* base = sums;
+    double* delta = sums + KD;
+    cat_status s;
+#define CAT_T(expr)            \
+    do {                       \
+        s = (expr);            \
+        if (s != CAT_OK) return s; \
+    } while (0)
+    TileParams p = base_params(lq, N, D, K, c, ws, dt);
+    p.cent = cent_io;
+    p.assign = assign16;
+    p.nsets = ms.nsets;
+    for (int i = 0; i < ms.nsets; i++) p.set_k[i] = (int16_t)ms.k[i];
+    for (int i = 0; i <= ms.nsets; i++) p.set_t0[i] = (uint8_t)ms.t0[i];
+    if (iters > 2) CAT_T(launch_fill_zero(lw.ctrl, lloyd_ctrl_words(D) * 4, st));
+    // The same sequence as tile_lloyd over the concatenated cluster slots (no early stop: the sets settle at
+    // different passes).  The full sums after passes 0 and 1 run set by set on that set's column of the table.
+    constexpr int32_t kFullPasses = 2;
+    int32_t* cb[2] = {counts, lw.counts2};
+    for (int32_t t = 0; t <= iters; t++) {
+        const bool last = t == iters;
+        double* slot = inertia16 ? inertia16 + (size_t)t * 16 : nullptr;
+        int32_t* cnt_t = cb[(iters - t) & 1];
+        const int32_t* cnt_prev = cb[(iters - t + 1) & 1];
+        if (t <= kFullPasses)
+            CAT_T(launch_prep(dt, cent_io, t ? base : nullptr, t ? delta : nullptr, t ? cnt_prev : nullptr, cnt_t, D, K, c,
+                              ws, slot, last ? rep : nullptr, st, ms.nsets));
+        else
+            CAT_T(launch_delta_prep(lq, dt, D, K, c, ws, lw, t & 1, cent_io, base, delta, cnt_prev, cnt_t, slot,
+                                    last ? rep : nullptr, nullptr, st, ms.nsets));
+        p.norm_part = t > kFullPasses ? lw.norm_part : nullptr;
+        p.norm_slices = t > kFullPasses ? (int32_t)delta_slices(D) : 0;
+        p.counts = cnt_t;
+        p.inertia = slot;
+        p.rep = last ? rep : nullptr;
+        p.list = (t >= kFullPasses && !last) ? lw.list : nullptr;
+        p.list_count = lw.ctrl + (t & 1);
+        p.list_cap = lloyd_list_capacity();
+        p.delta_mode = p.list ? 1 : 0;
+        p.reverse = t & 1;
+        CAT_T(dt == CAT_BF16 ? launch_multi_bf16(p, c, st) : launch_multi_f32(p, c, st));
+        if (t < kFullPasses && !last) {
+            CAT_T(launch_fill_zero(sums, (t == 0 ? 2 : 1) * KD * sizeof(double), st));
+            for (int i = 0; i < ms.nsets; i++) {
+                const int32_t slot0 = 16 * ms.t0[i];
+                CAT_T(launch_multi_column(assign16, N, i, slot0, column, st));
+                double* acc = base + (size_t)slot0 * D;
+                if (lw.sort_ws && segsum_sorted_supported(1, N, D, dt))
+                    CAT_T(launch_segsum_sorted(1, lq, nullptr, dt, column, cnt_t + slot0, N, D, ms.k[i], nullptr, nullptr, acc,
+                                               lw.sort_ws, st));
+                else
+                    CAT_T(launch_segsum(1, lq, nullptr, dt, column, N, D, ms.k[i], nullptr, nullptr, acc, st));
+            }
         }
     }
 #undef CAT_T

@@ -66,6 +66,14 @@ struct TileParams {
     void* out;
     float tau, tau2;         // re-rank threshold T = tau |x| cmax + tau2 cmax^2
     uint32_t ldsA_bytes, off_cnorm, off_hist, off_rep, off_list, off_misc;
+    // Several independent centroid sets side by side (fits for a grid of cluster counts that share every read of
+    // the rows; MULTI instantiations only).  Set s owns the cluster tiles set_t0[s] .. set_t0[s + 1] - 1, of whose
+    // 16-cluster slots the first set_k[s] hold centroids.  Cluster numbers everywhere (assignments, counts, list
+    // entries, first rows) are slot numbers of the concatenation.  `assign` then holds 16 int32 per row (set s at
+    // [row * 16 + s]) and `inertia` one double per set.
+    int32_t nsets;
+    int16_t set_k[16];
+    uint8_t set_t0[17];
 };
 
 // Which lane group g (0..3) and which of its 8 operand elements j hold channel r (0..31) of a
@@ -154,7 +162,8 @@ __device__ __forceinline__ void exact_dists(const void* lq, int64_t row, int64_t
 template <bool BF16>
 struct ChunkRegs {
     u32x4 v[BF16 ? 4 : 8];
-    int prev;  // previous assignment of row n (assignment passes only)
+    int prev;     // previous assignment of row n (assignment passes only)
+    u32x4 prevv;  // several sets: previous assignments of row n in the sets 4 g .. 4 g + 3
 };
 
 // Rows past N repeat the last row and channel groups past D read the start of the row (valid
@@ -164,14 +173,15 @@ struct ChunkRegs {
 // With PREV the row's previous assignment rides along with every chunk: fetched inside the
 // tile's finishing code it would have to be waited for there, and since loads return in order
 // that wait would also drain the chunks requested ahead.
-template <bool BF16, bool PREV>
+template <bool BF16, int PREV>  // PREV: 0 none, 1 the row's previous assignment, 2 its previous assignments in all sets
 __device__ __forceinline__ void load_chunk(ChunkRegs<BF16>& r, const TileParams& p, int tile, int chunk, int lane) {
     const int64_t row0 = (int64_t)(p.reverse ? (int)p.ntiles - 1 - tile : tile) * kRows;
     const int nv = (p.N - row0) < kRows ? (int)(p.N - row0) : kRows;
     const int n = lane & 15, g = lane >> 4;
     const int rn = n < nv ? n : nv - 1;
     const int ch = chunk * kChunk + 8 * g;
-    if (PREV) r.prev = p.assign[row0 + rn];
+    if (PREV == 1) r.prev = p.assign[row0 + rn];
+    if (PREV == 2) r.prevv = *(const u32x4*)(p.assign + (row0 + rn) * 16 + 4 * g);
     if (BF16) {
         const bf16_t* x = (const bf16_t*)p.lq + (row0 + rn) * p.D;
 #pragma unroll
@@ -249,14 +259,17 @@ __device__ __forceinline__ void contract_chunk(const ChunkRegs<BF16>& r, f32x4 (
 
 // Rank the centroids of the 16 rows from the accumulated dot products; exact re-rank of
 // the rows inside the error bound.  On return every lane (n, *) holds row n's result.
+// (t0, t1: the cluster tiles that take part, wave-uniform; all of them unless several sets share the kernel)
 template <int KT, bool BF16>
 __device__ __forceinline__ void rank_rows(const TileParams& p, const f32x4 (&acc)[KT], const float* s_cnorm,
-                                          float xn2, float cmax, int64_t row0, int lane, int& idx, float& dmin) {
+                                          float xn2, float cmax, int64_t row0, int lane, int& idx, float& dmin,
+                                          int t0 = 0, int t1 = KT) {
     const int n = lane & 15, q = lane >> 4;
     float b1 = __builtin_inff(), b2 = __builtin_inff();
-    int i1 = 0;
+    int i1 = 16 * t0;
 #pragma unroll
-    for (int t = 0; t < KT; t++)
+    for (int t = 0; t < KT; t++) {
+        if (t < t0 || t >= t1) continue;
 #pragma unroll
         for (int i = 0; i < 4; i++) {
             int k = 16 * t + 4 * q + i;
@@ -269,6 +282,7 @@ __device__ __forceinline__ void rank_rows(const TileParams& p, const f32x4 (&acc
                 b2 = s;
             }
         }
+    }
 #pragma unroll
     for (int o = 16; o <= 32; o <<= 1) {
         float ob1 = __shfl_xor(b1, o, kWave), ob2 = __shfl_xor(b2, o, kWave);
@@ -320,7 +334,8 @@ __device__ __forceinline__ void rank_rows(const TileParams& p, const f32x4 (&acc
             cnt = 0;
         };
 #pragma unroll
-        for (int t = 0; t < KT; t++)
+        for (int t = 0; t < KT; t++) {
+            if (t < t0 || t >= t1) continue;
 #pragma unroll
             for (int i = 0; i < 4; i++) {
                 float s = fmaf(-2.f, acc[t][i], s_cnorm[16 * t + 4 * q + i]);
@@ -335,6 +350,7 @@ __device__ __forceinline__ void rank_rows(const TileParams& p, const f32x4 (&acc
                     }
                 }
             }
+        }
         measure();
         if (n == r && kbest != 0x7fffffff) {
             i1 = kbest;
@@ -475,8 +491,72 @@ __device__ __forceinline__ void finish_tile(const TileParams& p, unsigned char* 
     }
 }
 
+// Several centroid sets side by side (assignment passes of a fit for a grid of cluster counts): the same finishing
+// work once per set, over that set's cluster tiles.  The previous assignments of the row in the sets 4 g .. 4 g + 3
+// came with the chunk loads (prevv); lane (n, s / 4) owns row n in set s: it counts, lists the row if its cluster
+// changed, and keeps the new assignment, and the 16 int32 of the row are written back with one 16-byte store per
+// lane.  The objective of each set is accumulated in LDS doubles.
+template <int KT, bool BF16>
+__device__ __forceinline__ void finish_tile_multi(const TileParams& p, unsigned char* smem, f32x4 (&acc)[KT], float& nrm,
+                                                  int tile, int lane, float cmax, u32x4 prevv) {
+    const int n = lane & 15, q = lane >> 4;
+    const int64_t row0 = (int64_t)(p.reverse ? (int)p.ntiles - 1 - tile : tile) * kRows;
+    const float* s_cnorm = (const float*)(smem + p.off_cnorm);
+    int* s_hist = (int*)(smem + p.off_hist);
+    unsigned long long* s_rep = (unsigned long long*)(smem + p.off_rep);
+    int* s_misc = (int*)(smem + p.off_misc);
+    double* s_inset = (double*)(s_misc + 2) + kMaxWaves;
+    float xn2 = nrm;
+    xn2 += __shfl_xor(xn2, 16, kWave);
+    xn2 += __shfl_xor(xn2, 32, kWave);
+    const bool valid = row0 + n < p.N;
+    u32x4 newa = prevv;
+#pragma unroll 1
+    for (int s = 0; s < p.nsets; s++) {
+        int idx;
+        float dmin;
+        rank_rows<KT, BF16>(p, acc, s_cnorm, xn2, cmax, row0, lane, idx, dmin, (int)p.set_t0[s], (int)p.set_t0[s + 1]);
+        const bool owner = valid && q == (s >> 2);
+        const int e = s & 3;
+        const int prev = p.delta_mode ? (int)(e == 0 ? prevv.x : e == 1 ? prevv.y : e == 2 ? prevv.z : prevv.w) : -1;
+        if (owner) {
+            if (e == 0) newa.x = (uint32_t)idx;
+            if (e == 1) newa.y = (uint32_t)idx;
+            if (e == 2) newa.z = (uint32_t)idx;
+            if (e == 3) newa.w = (uint32_t)idx;
+            if (p.counts) atomicAdd(&s_hist[idx], 1);
+            if (p.rep) atomicMin(&s_rep[idx], (unsigned long long)(row0 + n));
+            atomicAdd(&s_inset[s], (double)dmin);
+        }
+        if (p.list) {
+            const bool changed = owner && prev != idx;
+            const unsigned long long entry =
+                ((unsigned long long)(row0 + n) << 24) | ((unsigned long long)(prev + 1) << 12) | (unsigned long long)idx;
+            bool ovf = false;
+            if (changed) {
+                int pos = atomicAdd(&s_misc[0], 1);
+                if (pos < p.list_cap)
+                    ((unsigned long long*)(smem + p.off_list))[pos] = entry;
+                else
+                    ovf = true;
+            }
+            const unsigned long long om = __ballot(ovf);
+            if (om) {
+                uint32_t base = 0;
+                if (lane == 0) base = atomicAdd(p.list_count, (uint32_t)__builtin_popcountll(om));
+                base = __builtin_amdgcn_readfirstlane(base);
+                if (ovf) p.list[base + __builtin_popcountll(om & ((1ull << lane) - 1ull))] = entry;
+            }
+        }
+    }
+#pragma unroll
+    for (int t = 0; t < KT; t++) acc[t] = (f32x4){0.f, 0.f, 0.f, 0.f};
+    nrm = 0.f;
+    if (valid) *(u32x4*)(p.assign + (row0 + n) * 16 + 4 * q) = newa;
+}
+
 // ---- the kernel ----------------------------------------------------------------------
-template <int KT, int PASSES, bool BF16, int MODE, bool CA>
+template <int KT, int PASSES, bool BF16, int MODE, bool CA, bool MULTI = false>
 __global__ __launch_bounds__(kMaxWaves * kWave) void k_tile(const TileParams p) {
     extern __shared__ __align__(16) unsigned char smem[];
     if (p.skip_when_zero && *p.skip_when_zero == 0u) return;  // uniform over the grid, before any barrier
@@ -499,7 +579,7 @@ __global__ __launch_bounds__(kMaxWaves * kWave) void k_tile(const TileParams p) 
     // every wait instead of draining to one; measured, that was 2-5 % slower, not faster.)
 #define CAT_ISSUE(buf)                                                                     \
     if (tl < ntiles) {                                                                     \
-        load_chunk<BF16, MODE == MODE_ASSIGN>(buf, p, tl, cl, lane);                       \
+        load_chunk<BF16, MODE == MODE_ASSIGN ? (MULTI ? 2 : 1) : 0>(buf, p, tl, cl, lane); \
         if (++cl == p.nchunks) {                                                           \
             cl = 0;                                                                        \
             tl += tstride;                                                                 \
@@ -556,7 +636,15 @@ __global__ __launch_bounds__(kMaxWaves * kWave) void k_tile(const TileParams p) 
             for (int u = 0; u < 8; u++) dst[i + u * nt] = t[u];
         }
         for (; i < nvec; i += nt) dst[i] = src[i];
+        if (MULTI && (int)threadIdx.x < p.K) {
+            // slots past the clusters of their set hold no centroid
+            const int t_ = (int)threadIdx.x >> 4;
+            int s_ = 0;
+            while (s_ + 1 < p.nsets && t_ >= (int)p.set_t0[s_ + 1]) s_++;
+            if ((int)threadIdx.x - 16 * (int)p.set_t0[s_] >= (int)p.set_k[s_]) cn_mine = kPadNorm;
+        }
         if ((int)threadIdx.x < p.K16) s_cnorm[threadIdx.x] = cn_mine;
+        if (MULTI && threadIdx.x < 16) ((double*)(s_misc + 2) + kMaxWaves)[threadIdx.x] = 0.0;
         for (int k = threadIdx.x; k < p.K; k += blockDim.x) {
             s_hist[k] = 0;
             s_rep[k] = ~0ull;
@@ -566,7 +654,10 @@ __global__ __launch_bounds__(kMaxWaves * kWave) void k_tile(const TileParams p) 
     __syncthreads();
     {
         float cm2 = 0.f;  // largest centroid norm: every wave reduces the table for itself
-        for (int k = lane; k < p.K; k += kWave) cm2 = fmaxf(cm2, s_cnorm[k]);
+        for (int k = lane; k < p.K; k += kWave) {
+            const float v = s_cnorm[k];
+            cm2 = fmaxf(cm2, (MULTI && v == kPadNorm) ? 0.f : v);
+        }
 #pragma unroll
         for (int o = 32; o > 0; o >>= 1) cm2 = fmaxf(cm2, __shfl_xor(cm2, o, kWave));
         cmax_out = sqrtf(cm2);
@@ -585,7 +676,10 @@ __global__ __launch_bounds__(kMaxWaves * kWave) void k_tile(const TileParams p) 
 #define CAT_STEP(buf)                                                                                          \
     contract_chunk<KT, PASSES, BF16>(buf, acc, nrm, smem + (size_t)cc * 4 * KT * P * 1024, lane, cc, p.D);     \
     if (++cc == p.nchunks) {                                                                                   \
-        finish_tile<KT, BF16, MODE>(p, smem, acc, nrm, tc, lane, cmax, in_acc, buf.prev);                      \
+        if (MULTI)                                                                                             \
+            finish_tile_multi<KT, BF16>(p, smem, acc, nrm, tc, lane, cmax, buf.prevv);                         \
+        else                                                                                                   \
+            finish_tile<KT, BF16, MODE>(p, smem, acc, nrm, tc, lane, cmax, in_acc, buf.prev);                  \
         cc = 0;                                                                                                \
         tc += tstride;                                                                                         \
     }
@@ -624,7 +718,10 @@ __global__ __launch_bounds__(kMaxWaves * kWave) void k_tile(const TileParams p) 
         if (tc < ntiles) {                                                                                    \
             contract_chunk<KT, PASSES, BF16>(bufcur, acc, nrm, smem + (size_t)(s & 1) * chunkA, lane, cc, p.D); \
             if (++cc == p.nchunks) {                                                                          \
-                finish_tile<KT, BF16, MODE>(p, smem, acc, nrm, tc, lane, cmax, in_acc, bufcur.prev);          \
+                if (MULTI)                                                                                    \
+                    finish_tile_multi<KT, BF16>(p, smem, acc, nrm, tc, lane, cmax, bufcur.prevv);             \
+                else                                                                                          \
+                    finish_tile<KT, BF16, MODE>(p, smem, acc, nrm, tc, lane, cmax, in_acc, bufcur.prev);      \
                 cc = 0;                                                                                       \
                 tc += tstride;                                                                                \
             }                                                                                                 \
@@ -681,7 +778,9 @@ __global__ __launch_bounds__(kMaxWaves * kWave) void k_tile(const TileParams p) 
         if (p.counts && s_hist[k]) atomicAdd(&p.counts[k], s_hist[k]);
         if (p.rep && s_rep[k] != ~0ull) atomicMin(&p.rep[k], s_rep[k]);
     }
-    if (p.inertia && threadIdx.x == 0) {
+    if (MULTI) {
+        if (p.inertia && (int)threadIdx.x < p.nsets) atomicAdd(p.inertia + threadIdx.x, (s_in + kMaxWaves)[threadIdx.x]);
+    } else if (p.inertia && threadIdx.x == 0) {
         double tot = 0.0;
         for (int w = 0; w < p.waves; w++) tot += s_in[w];
         atomicAdd(p.inertia, tot);
@@ -707,9 +806,9 @@ struct TileCfg {
     size_t lds_total = 0;
 };
 
-template <int KT, int PASSES, bool BF16, int MODE, bool CA>
+template <int KT, int PASSES, bool BF16, int MODE, bool CA, bool MULTI = false>
 static inline cat_status launch_one(const TileParams& p, const TileCfg& c, hipStream_t st) {
-    auto kern = k_tile<KT, PASSES, BF16, MODE, CA>;
+    auto kern = k_tile<KT, PASSES, BF16, MODE, CA, MULTI>;
     if (CA && c.waves != kMaxWaves) {
         return set_error(CAT_ERR_INVALID_ARG, "k_tile: the chunked-operand variant needs %d waves, got %d", kMaxWaves, c.waves);
     }
@@ -759,6 +858,16 @@ static inline cat_status launch_kt(const TileParams& p, const TileCfg& c, hipStr
     return c.P == 2 ? launch_mode<KT, 3, BF16>(p, c, st) : launch_mode<KT, 1, BF16>(p, c, st);
 }
 
+// several centroid sets side by side: assignment passes only
+template <int KT, bool BF16>
+static inline cat_status launch_kt_multi(const TileParams& p, const TileCfg& c, hipStream_t st) {
+    if (c.chunked)
+        return c.P == 2 ? launch_one<KT, 3, BF16, MODE_ASSIGN, true, true>(p, c, st)
+                        : launch_one<KT, 1, BF16, MODE_ASSIGN, true, true>(p, c, st);
+    return c.P == 2 ? launch_one<KT, 3, BF16, MODE_ASSIGN, false, true>(p, c, st)
+                    : launch_one<KT, 1, BF16, MODE_ASSIGN, false, true>(p, c, st);
+}
+
 // one translation unit per (KT, dtype), for compile time: cat_tile_k<KT>_<dtype>.hip
 cat_status launch_kt1_f32(const TileParams& p, const TileCfg& c, hipStream_t st);
 cat_status launch_kt1_bf16(const TileParams& p, const TileCfg& c, hipStream_t st);
@@ -770,5 +879,8 @@ cat_status launch_kt8_f32(const TileParams& p, const TileCfg& c, hipStream_t st)
 cat_status launch_kt8_bf16(const TileParams& p, const TileCfg& c, hipStream_t st);
 cat_status launch_kt16_f32(const TileParams& p, const TileCfg& c, hipStream_t st);
 cat_status launch_kt16_bf16(const TileParams& p, const TileCfg& c, hipStream_t st);
+// the instantiations for several centroid sets: cat_tile_multi_<dtype>.hip
+cat_status launch_multi_f32(const TileParams& p, const TileCfg& c, hipStream_t st);
+cat_status launch_multi_bf16(const TileParams& p, const TileCfg& c, hipStream_t st);
 
 }  // namespace cat
