@@ -313,6 +313,28 @@ cat_status cat_alpha_sweep(const void *lq, const void *fp, const int32_t *labels
                            void *workspace, size_t workspace_bytes, void *hip_stream);
 cat_status cat_top1(const void *x, int64_t N, int64_t D, cat_dtype dt, int32_t *top1, void *hip_stream);
 
+/* ---- low-precision deployment ----
+ * Sec. 3.1 of the paper remarks that the clustering yields gamma and beta of low precision and gives no mechanism.
+ * The reading taken here: the fitted parameters (centroids, gamma, beta) are stored as bfloat16, rounded to nearest
+ * with ties to the even significand, and CAT Inferencing (Algorithm 2) runs on the stored values as it stands:
+ * nearest stored centroid (exact, lowest index on ties), x + alpha ((gamma - 1) x + beta) with the stored gamma,
+ * beta in fp32 arithmetic.  The corrected rows of fp32 inputs may be written as bfloat16 (one more rounding to
+ * nearest even), which takes a quarter off the bytes of the pass.
+ *
+ * cat_params_to_bf16: dst[i] = bfloat16 nearest to src[i] (device arrays of n elements; finite values).
+ * cat_apply_lp:
+ *   centroids, gamma, beta   in, device, K x D bfloat16 each (uint16 storage, 2-byte aligned)
+ *   out_dt                   type of `corrected`: dt, or CAT_BF16 for fp32 rows
+ *   corrected                out, device, N x D of out_dt, 16-byte aligned, not aliasing lq
+ *   workspace                cat_apply_lp_workspace_bytes(N, D, K, dt) bytes
+ * Other arguments and errors: as cat_apply. */
+cat_status cat_params_to_bf16(const float *src, int64_t n, uint16_t *dst, void *hip_stream);
+size_t cat_apply_lp_workspace_bytes(int64_t N, int64_t D, int32_t K, cat_dtype dt);
+cat_status cat_apply_lp(const void *lq, int64_t N, int64_t D, int32_t K, cat_dtype dt,
+                        const uint16_t *centroids, const uint16_t *gamma, const uint16_t *beta, float alpha,
+                        cat_dtype out_dt, void *corrected, int32_t *assignments,
+                        void *workspace, size_t workspace_bytes, void *hip_stream);
+
 /* ---- fits for a grid of cluster counts ----
  * The paper's ablation on the number of clusters (Sec. 5 and the appendix on the number of clusters) fits CAT for
  * a list of cluster counts on the same calibration rows.  cat_fit_multi_k returns, for every K in the list, what

@@ -24,6 +24,8 @@ from .binding import (  # noqa: F401
     cat_init_kmeanspp,
     cat_fit_restarts,
     cat_fit_multi_k,
+    cat_params_to_bf16,
+    cat_apply_lp,
     cat_fit_workspace_bytes,
     cat_apply_workspace_bytes,
     library_path,

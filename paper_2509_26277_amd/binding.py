@@ -26,7 +26,8 @@ EXPORTS = ("cat_select_path", "cat_fit_workspace_bytes", "cat_apply_workspace_by
            "cat_init_kmeanspp_workspace_bytes", "cat_init_kmeanspp",
            "cat_fit_restarts_workspace_bytes", "cat_fit_restarts", "cat_fit_early_stop", "cat_allow_early_stop",
            "cat_apply_static", "cat_apply_static_max_workspace_bytes", "cat_debug_apply_kernel",
-           "cat_fit_multi_k_workspace_bytes", "cat_fit_multi_k", "cat_debug_multi_group_tiles")
+           "cat_fit_multi_k_workspace_bytes", "cat_fit_multi_k", "cat_debug_multi_group_tiles",
+           "cat_params_to_bf16", "cat_apply_lp_workspace_bytes", "cat_apply_lp")
 
 
 class CatError(RuntimeError):
@@ -117,6 +118,12 @@ def load_library():
     lib.cat_fit_multi_k_workspace_bytes.restype = sz
     lib.cat_fit_multi_k.argtypes = [vp, vp, i64, i64, i32p, i32, i32, u64, c.c_int, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.cat_fit_multi_k.restype = c.c_int
+    lib.cat_params_to_bf16.argtypes = [vp, i64, vp, vp]
+    lib.cat_params_to_bf16.restype = c.c_int
+    lib.cat_apply_lp_workspace_bytes.argtypes = [i64, i64, i32, c.c_int]
+    lib.cat_apply_lp_workspace_bytes.restype = sz
+    lib.cat_apply_lp.argtypes = [vp, i64, i64, i32, c.c_int, vp, vp, vp, c.c_float, c.c_int, vp, vp, vp, sz, vp]
+    lib.cat_apply_lp.restype = c.c_int
     lib.cat_debug_multi_group_tiles.argtypes = [c.c_int]
     lib.cat_debug_multi_group_tiles.restype = c.c_int
     lib.cat_debug_apply_kernel.argtypes = [c.c_int]
@@ -486,6 +493,35 @@ def cat_fit_multi_k(lq, fp, Ks, iters, seed=0, want_inertia=True, workspace=None
                         counts=counts[r:r + K], inertia=None if inertia is None else inertia[i]))
         r += K
     return out
+
+
+def cat_params_to_bf16(x):
+    """The bfloat16 values nearest to a float32 device tensor (cat_params_to_bf16), as a torch.bfloat16 tensor."""
+    x = x.contiguous()
+    out = torch.empty(x.shape, dtype=torch.bfloat16, device=x.device)
+    _check(load_library().cat_params_to_bf16(_dev(x, torch.float32, name="x"), x.numel(), out.data_ptr(), _stream()))
+    return out
+
+
+def cat_apply_lp(lq, centroids, gamma, beta, alpha=1.0, bf16_out=True, want_assignments=True, out=None, workspace=None):
+    """CAT Inferencing with parameters stored as bfloat16 tensors (cat_apply_lp).  ``bf16_out``: the corrected rows of
+    float32 inputs are written as bfloat16.  Returns (corrected, assignments or None)."""
+    lib = load_library()
+    N, D = lq.shape
+    K = centroids.shape[0]
+    dt = _dt(lq)
+    dev = lq.device
+    out_dt = CAT_BF16 if (bf16_out or dt == CAT_BF16) else CAT_F32
+    if workspace is None:
+        workspace = _workspace(lib.cat_apply_lp_workspace_bytes(N, D, K, dt), dev)
+    if out is None:
+        out = torch.empty((N, D), dtype=torch.bfloat16 if out_dt == CAT_BF16 else torch.float32, device=dev)
+    a = torch.empty((N,), dtype=torch.int32, device=dev) if want_assignments else None
+    _check(lib.cat_apply_lp(_dev(lq, name="lq"), N, D, K, dt, _dev(centroids, torch.bfloat16, (K, D), "centroids"),
+                            _dev(gamma, torch.bfloat16, (K, D), "gamma"), _dev(beta, torch.bfloat16, (K, D), "beta"),
+                            float(alpha), out_dt, out.data_ptr(), None if a is None else a.data_ptr(),
+                            workspace.data_ptr(), workspace.numel(), _stream()))
+    return out, a
 
 
 def cat_fit_pca(lq, fp, K, p, iters, seed=0, want_inertia=True, workspace=None):

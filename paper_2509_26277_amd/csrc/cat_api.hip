@@ -753,6 +753,74 @@ cat_status cat_apply(const void* lq, int64_t N, int64_t D, int32_t K, cat_dtype 
                       workspace_bytes, (hipStream_t)hip_stream);
 }
 
+// ---- low-precision deployment: parameters stored as bfloat16, corrected rows optionally written as bfloat16 ----
+struct ApplyLpWs {
+    float* cent;      // K x D   the stored parameters as fp32 working arrays (alpha folded into g, b)
+    float* g;
+    float* b;
+    int32_t* labels;  // N       for the shapes that assign first and map afterwards
+    void* apply;      // cat_apply scratch
+    size_t apply_bytes, bytes;
+};
+static ApplyLpWs carve_apply_lp(void* base, int64_t N, int64_t D, int32_t K, cat_dtype dt) {
+    Carver c(base);
+    ApplyLpWs w;
+    const size_t KD = (size_t)K * (size_t)D;
+    w.cent = c.take<float>(KD);
+    w.g = c.take<float>(KD);
+    w.b = c.take<float>(KD);
+    w.labels = c.take<int32_t>((size_t)N);
+    w.apply_bytes = carve_apply(nullptr, D, K, dt).bytes;
+    w.apply = c.take<char>(w.apply_bytes);
+    w.bytes = c.off;
+    return w;
+}
+
+cat_status cat_params_to_bf16(const float* src, int64_t n, uint16_t* dst, void* hip_stream) {
+    CAT_TRY(check_ptr("cat_params_to_bf16", "src", src, 4));
+    CAT_TRY(check_ptr("cat_params_to_bf16", "dst", dst, 2));
+    if (n < 0) return set_error(CAT_ERR_INVALID_ARG, "cat_params_to_bf16: n = %lld is negative", (long long)n);
+    if (n == 0) return CAT_OK;
+    return launch_to_bf16(src, n, dst, (hipStream_t)hip_stream);
+}
+
+size_t cat_apply_lp_workspace_bytes(int64_t N, int64_t D, int32_t K, cat_dtype dt) {
+    if (!shape_ok(N, D, K, dt)) return 0;
+    return carve_apply_lp(nullptr, N, D, K, dt).bytes;
+}
+
+cat_status cat_apply_lp(const void* lq, int64_t N, int64_t D, int32_t K, cat_dtype dt, const uint16_t* centroids,
+                        const uint16_t* gamma, const uint16_t* beta, float alpha, cat_dtype out_dt, void* corrected,
+                        int32_t* assignments, void* workspace, size_t workspace_bytes, void* hip_stream) {
+    const char* who = "cat_apply_lp";
+    CAT_TRY(check_shape(who, N, D, K, dt));
+    if (out_dt != CAT_F32 && out_dt != CAT_BF16) return set_error(CAT_ERR_INVALID_ARG, "%s: unknown out_dt %d", who, (int)out_dt);
+    if (dt == CAT_BF16 && out_dt != CAT_BF16)
+        return set_error(CAT_ERR_INVALID_ARG, "%s: bf16 rows are corrected into bf16 rows (out_dt = CAT_BF16)", who);
+    CAT_TRY(check_ptr(who, "lq", lq, 16));
+    CAT_TRY(check_ptr(who, "centroids", centroids, 2));
+    CAT_TRY(check_ptr(who, "gamma", gamma, 2));
+    CAT_TRY(check_ptr(who, "beta", beta, 2));
+    CAT_TRY(check_ptr(who, "corrected", corrected, 16));
+    if (corrected == lq) return set_error(CAT_ERR_INVALID_ARG, "%s: corrected may not alias lq", who);
+    if (!std::isfinite(alpha)) return set_error(CAT_ERR_INVALID_ARG, "%s: alpha is not finite", who);
+    ApplyLpWs w = carve_apply_lp(workspace, N, D, K, dt);
+    CAT_TRY(check_ws(who, workspace, workspace_bytes, w.bytes));
+    hipStream_t st = (hipStream_t)hip_stream;
+    CAT_TRY(launch_expand_params(centroids, gamma, beta, alpha, (int64_t)K * D, w.cent, w.g, w.b, st));
+    if (out_dt == dt)  // the ordinary inference on the expanded parameters (alpha is folded in already)
+        return apply_impl(who, lq, N, D, K, dt, w.cent, w.g, w.b, 1.0f, corrected, assignments, w.apply, w.apply_bytes, st);
+    // fp32 rows, bfloat16 out: the row-tile kernel writes the narrower rows itself; shapes it has no instance for
+    // assign first and map by the labels afterwards (a second read of the rows)
+    ApplyWs aw = carve_apply(w.apply, D, K, dt);
+    const int path = g_path.load();
+    if (infer_supported(N, D, K, dt) && path != CAT_PATH_STREAM && g_apply_kernel.load() != 1)
+        return infer_apply(lq, dt, N, D, K, w.cent, w.g, w.b, corrected, assignments, aw.tile, st, true);
+    int32_t* labels = assignments ? assignments : w.labels;
+    CAT_TRY(step_assign(lq, dt, N, D, K, w.cent, labels, nullptr, nullptr, nullptr, aw.tile, st));
+    return launch_affine_to_bf16((const float*)lq, labels, N, D, w.g, w.b, (uint16_t*)corrected, st);
+}
+
 // ---- cat_apply for callers that cannot allocate: the scratch memory is a device array of the library ----
 // One copy of the array exists on every GPU the library runs on, at an address of its own, and stays there until the
 // process ends.  The name of the array is a host-side stand-in, not a device address: host code only ever uses the

@@ -89,7 +89,7 @@ bool infer_supported(int64_t N, int64_t D, int32_t K, cat_dtype dt) {
 
 cat_status infer_apply(const void* lq, cat_dtype dt, int64_t N, int64_t D, int32_t K, const float* cent,
                        const float* gamma, const float* beta, void* corrected, int32_t* assign, const TileWs& ws,
-                       hipStream_t st) {
+                       hipStream_t st, bool out_bf16) {
     const InferCfg c = infer_config(D, K, dt);
     if (!c.ok) return set_error(CAT_ERR_UNSUPPORTED, "row-tile inference kernel does not fit D=%lld K=%d", (long long)D, (int)K);
     const Inst& in = kInst[c.inst];
@@ -107,6 +107,7 @@ cat_status infer_apply(const void* lq, cat_dtype dt, int64_t N, int64_t D, int32
     p.lq = lq;
     p.out = corrected;
     p.assign = assign;
+    p.out_bf16 = (out_bf16 && dt == CAT_F32) ? 1 : 0;
     p.N = N;
     p.D = D;
     const int rows = 16 * in.RGT;

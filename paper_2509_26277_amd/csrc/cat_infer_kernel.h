@@ -49,6 +49,7 @@ struct InferParams {
     uint32_t xpart;         // bytes between the hi and the lo part
     uint32_t off_s, off_cnorm;  // LDS: [0, off_s) row tile, then the partial dot products, then the norms
     unsigned int* counters;     // DYN: 8 x 16 words, zero on entry: the next tile of each group of workgroups
+    int32_t out_bf16;           // fp32 rows only: the corrected rows are written as bfloat16 (rounded to nearest even)
 };
 
 __device__ __forceinline__ uint32_t ipack_bf16(float a, float b) {  // a -> low half, b -> high half, RNE
@@ -399,7 +400,13 @@ __global__ __launch_bounds__(kInferWaves * kWave) void k_infer(const InferParams
                     o.z = __float_as_uint(fmaf(gg.z, __uint_as_float(Xc[r][v].z), bb.z));
                     o.w = __float_as_uint(fmaf(gg.w, __uint_as_float(Xc[r][v].w), bb.w));
                 }
-                if (row < p.N && ch_ok[v]) __builtin_nontemporal_store(o, (iu32x4*)(orow + ch[v]));
+                if (!BF16 && p.out_bf16) {  // uniform over the launch
+                    const iu32x2 o2 = {ipack_bf16(__uint_as_float(o.x), __uint_as_float(o.y)),
+                                       ipack_bf16(__uint_as_float(o.z), __uint_as_float(o.w))};
+                    if (row < p.N && ch_ok[v]) __builtin_nontemporal_store(o2, (iu32x2*)((bf16_t*)p.out + row * p.D + ch[v]));
+                } else if (row < p.N && ch_ok[v]) {
+                    __builtin_nontemporal_store(o, (iu32x4*)(orow + ch[v]));
+                }
             }
         }
         if (DYN && threadIdx.x == 0) s_queue[(i + DEPTH + 1) & 7] = fetched;
