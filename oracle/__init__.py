@@ -26,4 +26,5 @@ from .cat_oracle import (  # noqa: F401
     fit_multi_k,
     to_bf16,
     apply_lp,
+    fit_bounds,
 )
