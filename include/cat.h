@@ -313,6 +313,32 @@ cat_status cat_alpha_sweep(const void *lq, const void *fp, const int32_t *labels
                            void *workspace, size_t workspace_bytes, void *hip_stream);
 cat_status cat_top1(const void *x, int64_t N, int64_t D, cat_dtype dt, int32_t *top1, void *hip_stream);
 
+/* ---- CAT Fitting whose Lloyd loop leaves out distance evaluations by bounds ----
+ * The paper names k-means without fixing a variant (Sec. 4, Setup).  cat_fit_bounds returns what cat_fit returns and
+ * does less work: after Hamerly ("Making k-means even faster", SDM 2010) every row carries a bound on how far the
+ * centroids may move before its nearest centroid can change.  When a pass evaluates a row it records the gap
+ * between the distances to its nearest and second nearest centroid (a lower bound of it, given the rounding of the
+ * scores); every update adds the two largest centroid movements to a running drift; a row whose gap exceeds the drift
+ * accumulated since its evaluation keeps its centroid (its distance to its own centroid grew by at most one movement,
+ * its distance to any other shrank by at most another) and is neither read nor ranked in that pass.  Coarser than the
+ * published algorithm (one gap per row instead of separate upper and lower bounds, no centre-to-centre test, no
+ * tightening step): a pass reads a row or it does not.  Passes 0, 1, 2 and the last evaluate every row.
+ *
+ * rows_evaluated  out, device, iters + 1 int32, nullable: rows read and ranked by each pass
+ * inertia         as cat_fit, but only the entries of the passes that evaluate every row (0, 1, 2, iters) are
+ *                 defined; the others are NaN where rows were left out
+ * workspace       cat_fit_bounds_workspace_bytes(N, D, K, iters, dt) bytes
+ * Other arguments and errors: as cat_fit.  N below 2^31.  Shapes the matrix-core kernels do not take, the streaming
+ * path selected, or iters < 4: the plain loop runs and every pass reports N rows.  centroids, assignments, counts,
+ * gamma and beta are those of cat_fit bit for bit. */
+size_t cat_fit_bounds_workspace_bytes(int64_t N, int64_t D, int32_t K, int32_t iters, cat_dtype dt);
+cat_status cat_fit_bounds(const void *lq, const void *fp, int64_t N, int64_t D, int32_t K,
+                          int32_t iters, uint64_t seed, cat_dtype dt,
+                          const float *init_centroids,
+                          float *centroids, float *gamma, float *beta,
+                          int32_t *assignments, int32_t *counts, double *inertia, int32_t *rows_evaluated,
+                          void *workspace, size_t workspace_bytes, void *hip_stream);
+
 /* ---- low-precision deployment ----
  * Sec. 3.1 of the paper remarks that the clustering yields gamma and beta of low precision and gives no mechanism.
  * The reading taken here: the fitted parameters (centroids, gamma, beta) are stored as bfloat16, rounded to nearest

@@ -27,7 +27,8 @@ EXPORTS = ("cat_select_path", "cat_fit_workspace_bytes", "cat_apply_workspace_by
            "cat_fit_restarts_workspace_bytes", "cat_fit_restarts", "cat_fit_early_stop", "cat_allow_early_stop",
            "cat_apply_static", "cat_apply_static_max_workspace_bytes", "cat_debug_apply_kernel",
            "cat_fit_multi_k_workspace_bytes", "cat_fit_multi_k", "cat_debug_multi_group_tiles",
-           "cat_params_to_bf16", "cat_apply_lp_workspace_bytes", "cat_apply_lp")
+           "cat_params_to_bf16", "cat_apply_lp_workspace_bytes", "cat_apply_lp",
+           "cat_fit_bounds_workspace_bytes", "cat_fit_bounds")
 
 
 class CatError(RuntimeError):
@@ -118,6 +119,10 @@ def load_library():
     lib.cat_fit_multi_k_workspace_bytes.restype = sz
     lib.cat_fit_multi_k.argtypes = [vp, vp, i64, i64, i32p, i32, i32, u64, c.c_int, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.cat_fit_multi_k.restype = c.c_int
+    lib.cat_fit_bounds_workspace_bytes.argtypes = [i64, i64, i32, i32, c.c_int]
+    lib.cat_fit_bounds_workspace_bytes.restype = sz
+    lib.cat_fit_bounds.argtypes = [vp, vp, i64, i64, i32, i32, u64, c.c_int, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.cat_fit_bounds.restype = c.c_int
     lib.cat_params_to_bf16.argtypes = [vp, i64, vp, vp]
     lib.cat_params_to_bf16.restype = c.c_int
     lib.cat_apply_lp_workspace_bytes.argtypes = [i64, i64, i32, c.c_int]
@@ -219,17 +224,22 @@ def cat_init_indices(N, K, seed):
     return list(buf)[:K]
 
 
-def cat_fit(lq, fp, K, iters, seed=0, init_centroids=None, want_inertia=True, workspace=None, early_stop=False):
+def cat_fit(lq, fp, K, iters, seed=0, init_centroids=None, want_inertia=True, workspace=None, early_stop=False,
+            bounds=False):
     """CAT Fitting on device tensors.  Returns a dict of device tensors:
     centroids, gamma, beta (K x D float32), assignments (N int32), counts (K int32),
     inertia (iters+1 float64, or None).  With ``early_stop`` (cat_fit_early_stop) the passes after the partition has
-    stopped changing are not run, the outputs stay those of the full loop, and ``passes_skipped`` (1 int32) is added."""
+    stopped changing are not run, the outputs stay those of the full loop, and ``passes_skipped`` (1 int32) is added.
+    With ``bounds`` (cat_fit_bounds) rows are left out of a pass by distance bounds, same outputs, and
+    ``rows_evaluated`` (iters+1 int32) is added."""
     lib = load_library()
     N, D = lq.shape
     dt = _dt(lq)
     dev = lq.device
     if workspace is None:
-        workspace = _workspace(lib.cat_fit_workspace_bytes(N, D, K, dt), dev)
+        nbytes = (lib.cat_fit_bounds_workspace_bytes(N, D, K, iters, dt) if bounds
+                  else lib.cat_fit_workspace_bytes(N, D, K, dt))
+        workspace = _workspace(nbytes, dev)
     cent = torch.empty((K, D), dtype=torch.float32, device=dev)
     gamma = torch.empty((K, D), dtype=torch.float32, device=dev)
     beta = torch.empty((K, D), dtype=torch.float32, device=dev)
@@ -242,7 +252,10 @@ def cat_fit(lq, fp, K, iters, seed=0, init_centroids=None, want_inertia=True, wo
             None if inertia is None else inertia.data_ptr())
     tail = (workspace.data_ptr(), workspace.numel(), _stream())
     res = dict(centroids=cent, gamma=gamma, beta=beta, assignments=a, counts=counts, inertia=inertia)
-    if early_stop:
+    if bounds:
+        res["rows_evaluated"] = torch.empty((max(iters, 0) + 1,), dtype=torch.int32, device=dev)
+        _check(lib.cat_fit_bounds(*head, res["rows_evaluated"].data_ptr(), *tail))
+    elif early_stop:
         res["passes_skipped"] = torch.empty((1,), dtype=torch.int32, device=dev)
         _check(lib.cat_fit_early_stop(*head, res["passes_skipped"].data_ptr(), *tail))
     else:

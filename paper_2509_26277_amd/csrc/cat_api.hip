@@ -208,7 +208,7 @@ static cat_status step_stats(const void* lq, const void* fp, cat_dtype dt, const
 // given the loop may stop early (see tile_lloyd); the outputs are those of the full loop.
 static cat_status run_lloyd(const void* lq, cat_dtype dt, int64_t N, int64_t D, int32_t K, int32_t iters, uint64_t seed,
                             const float* init_centroids, float* centroids, int32_t* assignments, double* inertia,
-                            const FitWs& w, hipStream_t st, int32_t* skipped = nullptr) {
+                            const FitWs& w, hipStream_t st, int32_t* skipped = nullptr, const BoundsWs* bw = nullptr) {
     const size_t KD = (size_t)K * (size_t)D;
     const int path = g_path.load();
     const bool fused = tile_supports(TILE_LLOYD, N, D, K, dt) && path != CAT_PATH_STREAM;
@@ -226,7 +226,7 @@ static cat_status run_lloyd(const void* lq, cat_dtype dt, int64_t N, int64_t D, 
     if (fused) {
         if (!skipped && g_early_stop.load()) skipped = w.lloyd.skipped;
         // one assignment launch per Lloyd iteration; only the rows that change cluster touch the sums
-        CAT_TRY(tile_lloyd(lq, dt, N, D, K, iters, centroids, w.acc, assignments, w.counts, inertia, w.rep, skipped, w.tile, w.lloyd, st));
+        CAT_TRY(tile_lloyd(lq, dt, N, D, K, iters, centroids, w.acc, assignments, w.counts, inertia, w.rep, skipped, w.tile, w.lloyd, st, bw));
     } else {
         // the streaming kernels keep no record of the rows that move: every pass runs
         if (skipped) CAT_TRY(launch_fill_zero(skipped, sizeof(int32_t), st));
@@ -385,7 +385,8 @@ cat_status cat_stats(const void* lq, const void* fp, const int32_t* assignments,
 static cat_status fit_impl(const char* who, const void* lq, const void* fp, int64_t N, int64_t D, int32_t K,
                            int32_t iters, uint64_t seed, cat_dtype dt, const float* init_centroids, float* centroids,
                            float* gamma, float* beta, int32_t* assignments, int32_t* counts, double* inertia,
-                           int32_t* skipped, void* workspace, size_t workspace_bytes, void* hip_stream) {
+                           int32_t* skipped, void* workspace, size_t workspace_bytes, void* hip_stream,
+                           bool with_bounds = false, int32_t* evaluated = nullptr) {
     CAT_TRY(check_shape(who, N, D, K, dt));
     if (iters < 0) return set_error(CAT_ERR_INVALID_ARG, "%s: iters = %d is negative", who, (int)iters);
     CAT_TRY(check_ptr(who, "lq", lq, 16));
@@ -397,9 +398,17 @@ static cat_status fit_impl(const char* who, const void* lq, const void* fp, int6
     CAT_TRY(check_ptr(who, "assignments", assignments, 4));
     if (inertia) CAT_TRY(check_ptr(who, "inertia", inertia, 8));
     FitWs w = carve_fit(workspace, N, D, K, dt);
-    CAT_TRY(check_ws(who, workspace, workspace_bytes, w.bytes));
+    BoundsWs bw;
+    size_t need = w.bytes;
+    if (with_bounds) {
+        bw = bounds_carve(workspace ? (char*)workspace + align256(w.bytes) : nullptr, N, D, K, iters);
+        bw.evaluated = evaluated;
+        need = align256(w.bytes) + bw.bytes;
+    }
+    CAT_TRY(check_ws(who, workspace, workspace_bytes, need));
     hipStream_t st = (hipStream_t)hip_stream;
-    CAT_TRY(run_lloyd(lq, dt, N, D, K, iters, seed, init_centroids, centroids, assignments, inertia, w, st, skipped));
+    CAT_TRY(run_lloyd(lq, dt, N, D, K, iters, seed, init_centroids, centroids, assignments, inertia, w, st, skipped,
+                      with_bounds ? &bw : nullptr));
     // affine fit on that partition, shifted by the centroids
     CAT_TRY(step_stats(lq, fp, dt, assignments, N, D, K, w.counts, w.rep, centroids, w, gamma, beta, st));
     if (counts) CAT_TRY(launch_copy_words(w.counts, counts, K, st));
@@ -421,6 +430,27 @@ cat_status cat_fit_early_stop(const void* lq, const void* fp, int64_t N, int64_t
     CAT_TRY(check_ptr("cat_fit_early_stop", "passes_skipped", passes_skipped, 4));
     return fit_impl("cat_fit_early_stop", lq, fp, N, D, K, iters, seed, dt, init_centroids, centroids, gamma, beta,
                     assignments, counts, inertia, passes_skipped, workspace, workspace_bytes, hip_stream);
+}
+
+size_t cat_fit_bounds_workspace_bytes(int64_t N, int64_t D, int32_t K, int32_t iters, cat_dtype dt) {
+    if (!shape_ok(N, D, K, dt) || iters < 0) return 0;
+    return align256(carve_fit(nullptr, N, D, K, dt).bytes) + bounds_workspace_bytes(N, D, K, iters);
+}
+
+cat_status cat_fit_bounds(const void* lq, const void* fp, int64_t N, int64_t D, int32_t K, int32_t iters, uint64_t seed,
+                          cat_dtype dt, const float* init_centroids, float* centroids, float* gamma, float* beta,
+                          int32_t* assignments, int32_t* counts, double* inertia, int32_t* rows_evaluated, void* workspace,
+                          size_t workspace_bytes, void* hip_stream) {
+    if (rows_evaluated) CAT_TRY(check_ptr("cat_fit_bounds", "rows_evaluated", rows_evaluated, 4));
+    if (N >= ((int64_t)1 << 31))
+        return set_error(CAT_ERR_UNSUPPORTED, "cat_fit_bounds: N = %lld does not fit the 32-bit row numbers of its lists", (long long)N);
+    const bool fused = tile_supports(TILE_LLOYD, N, D, K, dt) && g_path.load() != CAT_PATH_STREAM;
+    cat_status s = fit_impl("cat_fit_bounds", lq, fp, N, D, K, iters, seed, dt, init_centroids, centroids, gamma, beta,
+                            assignments, counts, inertia, nullptr, workspace, workspace_bytes, hip_stream, true, rows_evaluated);
+    if (s != CAT_OK) return s;
+    // the kernels outside the matrix-core family keep no bounds: every pass evaluates every row
+    if (!fused && rows_evaluated) return launch_fill_i32(rows_evaluated, (int64_t)iters + 1, (int32_t)N, (hipStream_t)hip_stream);
+    return CAT_OK;
 }
 
 // ---- several runs of the clustering, the one with the lowest final objective kept ---------------------

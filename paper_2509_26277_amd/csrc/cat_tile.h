@@ -40,14 +40,35 @@ struct LloydWs {
 size_t lloyd_workspace_bytes(int64_t N, int64_t D, int32_t K);
 LloydWs lloyd_carve(void* base, int64_t N, int64_t D, int32_t K);
 
+// Scratch of the loops that leave rows out by distance bounds (Hamerly, SDM 2010): see tile_lloyd.
+struct BoundsWs {
+    double* expire = nullptr;         // N        per row: the drift at which it has to be evaluated again
+    int32_t* rows = nullptr;          // N        the rows of the coming pass
+    uint32_t* n_rows = nullptr;       // 1        their number
+    double* drift = nullptr;          // iters+1  accumulated centroid drift up to each pass
+    double* move_part = nullptr;      // slices x K
+    int32_t* slice_counts = nullptr;  // slices x K
+    int32_t* evaluated = nullptr;     // iters+1  out: rows evaluated by each pass (the caller's array, nullable)
+    size_t bytes = 0;
+};
+size_t bounds_workspace_bytes(int64_t N, int64_t D, int32_t K, int32_t iters);
+BoundsWs bounds_carve(void* base, int64_t N, int64_t D, int32_t K, int32_t iters);
+bool tile_bounds_supports(int64_t N, int64_t D, int32_t K, cat_dtype dt);
+cat_status launch_fill_i32(int32_t* p, int64_t n, int32_t v, hipStream_t st);
+
 // `iters` Lloyd iterations from cent0 plus the final assignment.  cent_io holds the initial
 // centroids on entry and the final ones on return; sums is 2 x K x D doubles of scratch.
 // Writes assignments, counts (K), inertia (iters + 1, nullable) and rep (K).  skipped (one device int32,
 // nullable) allows the early stop: passes after the partition has stopped changing are not run, and their
 // number is written there; every other output is what the full loop gives.
+// With bw given (and tile_bounds_supports, iters >= 4): from the first pass that lists the rows that changed cluster
+// on, a pass also leaves every row's distance bound, and the passes between that one and the last evaluate only the
+// rows whose bound the centroid drift has used up.  Same centroids, assignments, counts and rep; of the objective
+// only the entries of the passes that evaluate every row (0, 1, 2 and the last) are written, the others are NaN.
 cat_status tile_lloyd(const void* lq, cat_dtype dt, int64_t N, int64_t D, int32_t K, int32_t iters,
                       float* cent_io, double* sums, int32_t* assign, int32_t* counts, double* inertia,
-                      unsigned long long* rep, int32_t* skipped, const TileWs& ws, const LloydWs& lw, hipStream_t st);
+                      unsigned long long* rep, int32_t* skipped, const TileWs& ws, const LloydWs& lw, hipStream_t st,
+                      const BoundsWs* bw = nullptr);
 
 // Several independent centroid sets side by side: Lloyd loops for a grid of cluster counts that share every read of
 // the rows.  Set s owns the 16-cluster tiles t0[s] .. t0[s + 1] - 1 of the concatenation, of whose slots the first

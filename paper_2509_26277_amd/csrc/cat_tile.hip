@@ -98,6 +98,14 @@ struct DeltaParams {
     int32_t inertia_n;           // objective entries at inertia_slot (one per centroid set)
     unsigned long long* rep;
     int32_t* skipped;            // nullable: early stop allowed; counts the passes that were not run
+    // Loops that skip rows by distance bounds: the passes between the first listed pass and the last do not count the
+    // rows of every cluster again, so every slice keeps running counts of its own (slice_counts, slices x K): seeded
+    // from `counts` (seed_counts != 0; the pass before counted all rows), afterwards moved along with the listed rows
+    // and used instead of `counts`.  move_part (slices x K) receives the slice's share of |c_new - c_old|^2.
+    int32_t* slice_counts;
+    int32_t seed_counts;
+    double* move_part;
+    uint32_t* n_rows_clear;      // nullable: cleared (the row selection that follows counts into it)
 };
 
 constexpr int kDeltaWaves = 8;
@@ -107,6 +115,7 @@ template <typename T>
 __global__ __launch_bounds__(kDeltaWaves * kWave) void k_delta_prep(const DeltaParams q) {
     extern __shared__ double s_panel[];  // KC x 64
     __shared__ int s_flag;
+    __shared__ int s_moved[128];         // KC: rows that joined minus rows that left, per cluster of the range
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
     const int slice = blockIdx.y, nslices = gridDim.y;
@@ -138,14 +147,20 @@ __global__ __launch_bounds__(kDeltaWaves * kWave) void k_delta_prep(const DeltaP
             if (q.rep) q.rep[k] = ~0ull;
         }
         for (int s = threadIdx.x; s < nslices; s += blockDim.x) q.done_next[s] = 0;
-        if (threadIdx.x == 0) *q.list_count_next = 0;
+        if (threadIdx.x == 0) {
+            *q.list_count_next = 0;
+            if (q.n_rows_clear) *q.n_rows_clear = 0;
+        }
         if ((int)threadIdx.x < q.inertia_n && q.inertia_slot) q.inertia_slot[threadIdx.x] = 0.0;
     }
     const uint32_t per = (len + q.G - 1) / q.G;
     const uint32_t e0 = blockIdx.x * per;
     const uint32_t e1 = (e0 + per < len) ? e0 + per : len;
+    const bool moving_counts = q.slice_counts && !q.seed_counts;
     if (e0 < e1) {
         for (int i = threadIdx.x; i < kc * kDeltaSW; i += blockDim.x) s_panel[i] = 0.0;
+        if (moving_counts)
+            for (int i = threadIdx.x; i < kc; i += blockDim.x) s_moved[i] = 0;
         __syncthreads();
         // each wave takes a contiguous run of the share: 64 entries per load, then 8 rows in flight
         const uint32_t pw = (e1 - e0 + kDeltaWaves - 1) / kDeltaWaves;
@@ -156,6 +171,11 @@ __global__ __launch_bounds__(kDeltaWaves * kWave) void k_delta_prep(const DeltaP
             const unsigned long long ent = (b + lane < we) ? q.list[b + lane] : 0ull;
             const uint32_t ent_lo = (uint32_t)ent, ent_hi = (uint32_t)(ent >> 32);
             const int nb = (we - b) < (uint32_t)kWave ? (int)(we - b) : kWave;
+            if (moving_counts && lane < nb) {  // every lane holds one entry
+                const int a = (int)(ent_lo & 0xFFFu) - k0, c = (int)((ent_lo >> 12) & 0xFFFu) - 1 - k0;
+                if (a >= 0 && a < kc) atomicAdd(&s_moved[a], 1);
+                if (c >= 0 && c < kc) atomicAdd(&s_moved[c], -1);
+            }
             for (int i0 = 0; i0 < nb; i0 += RB) {
                 int nw[RB], od[RB];
                 float x[RB];
@@ -187,6 +207,9 @@ __global__ __launch_bounds__(kDeltaWaves * kWave) void k_delta_prep(const DeltaP
             const int64_t cg = (int64_t)slice * kDeltaSW + c;
             if (v != 0.0 && cg < q.D) atomicAdd(q.delta + (int64_t)(k0 + k) * q.D + cg, v);
         }
+        if (moving_counts)
+            for (int i = threadIdx.x; i < kc; i += blockDim.x)
+                if (s_moved[i]) atomicAdd(q.slice_counts + (size_t)slice * q.K + k0 + i, s_moved[i]);
     }
 
     // ---- who finishes the slice? ----
@@ -221,14 +244,16 @@ __global__ __launch_bounds__(kDeltaWaves * kWave) void k_delta_prep(const DeltaP
                 const int64_t i = (int64_t)k * q.D + ch;
                 S[u] = q.base[i] + __hip_atomic_load(q.delta + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 cold[u] = q.cent[i];
-                n[u] = q.counts[k];
+                n[u] = moving_counts ? __hip_atomic_load(q.slice_counts + (size_t)slice * q.K + k, __ATOMIC_RELAXED,
+                                                         __HIP_MEMORY_SCOPE_AGENT)
+                                     : q.counts[k];
             }
         }
 #pragma unroll
         for (int u = 0; u < KB; u++) {
             const int k = kb + u * kDeltaWaves;
             if (k >= q.K) break;  // wave-uniform
-            double nn = 0.0;
+            double nn = 0.0, mv = 0.0;
             if (ch_ok) {
                 const int64_t i = (int64_t)k * q.D + ch;
                 q.base[i] = S[u];
@@ -239,6 +264,7 @@ __global__ __launch_bounds__(kDeltaWaves * kWave) void k_delta_prep(const DeltaP
                     q.cent[i] = c;
                 }
                 nn = (double)c * (double)c;
+                mv = ((double)c - (double)cold[u]) * ((double)c - (double)cold[u]);
                 const int t = k >> 4, m = k & 15;
                 const int cc = (int)(ch / kChunk), r = (int)(ch % kChunk);
                 const int s = r >> 5;
@@ -255,7 +281,95 @@ __global__ __launch_bounds__(kDeltaWaves * kWave) void k_delta_prep(const DeltaP
             }
             nn = wave_sum(nn);
             if (lane == 0) q.norm_part[(size_t)slice * q.K + k] = nn;
+            if (q.move_part) {
+                mv = wave_sum(mv);
+                if (lane == 0) {
+                    q.move_part[(size_t)slice * q.K + k] = mv;
+                    if (q.seed_counts) q.slice_counts[(size_t)slice * q.K + k] = q.counts[k];
+                }
+            }
         }
+    }
+}
+
+// ---- which rows does the next pass have to evaluate? (distance bounds; Hamerly, SDM 2010) ----
+// The update just done moved centroid k by p(k) = sqrt(sum over the slices of move_part[.][k]).  A row's distance to
+// its own centroid grew by at most p(own) and its distance to any other shrank by at most the largest p among the
+// others, so the difference of the two shrank by at most the sum of the two largest movements.  That sum is added
+// to the running drift G; a row whose bound expire[i] (the drift at its last evaluation plus its margin then) is
+// still above G keeps its nearest centroid and is left out.  Every workgroup computes the same G (same data, same
+// order); the rows are taken in contiguous pieces and the kept ones appended to `rows` with one reservation per piece.
+constexpr int kSelThreads = 256;
+constexpr int kSelPerThread = 8;
+__global__ __launch_bounds__(kSelThreads) void k_bound_select(const double* __restrict__ move_part, int32_t slices, int32_t K,
+                                                              const double* __restrict__ g_prev, double* __restrict__ g_now,
+                                                              const double* __restrict__ expire, int64_t N,
+                                                              int32_t* __restrict__ rows, uint32_t* __restrict__ n_rows) {
+    __shared__ double s_p[256];
+    __shared__ double s_g;
+    __shared__ uint32_t s_wave[kSelThreads / kWave + 1];
+    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+    double pk = 0.0;
+    if ((int)threadIdx.x < K) {
+        double m2 = 0.0;
+        for (int sl = 0; sl < slices; sl++) m2 += move_part[(size_t)sl * K + threadIdx.x];
+        pk = sqrt(m2);
+    }
+    s_p[threadIdx.x] = pk;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        double t1 = 0.0, t2 = 0.0;
+        for (int k = 0; k < K; k++) {
+            const double v = s_p[k];
+            if (v > t1) {
+                t2 = t1;
+                t1 = v;
+            } else if (v > t2) {
+                t2 = v;
+            }
+        }
+        s_g = *g_prev + (t1 + t2) * (1.0 + 1e-9);
+        if (blockIdx.x == 0) *g_now = s_g;
+    }
+    __syncthreads();
+    const double G = s_g;
+    constexpr int64_t kPiece = (int64_t)kSelThreads * kSelPerThread;
+    for (int64_t r0 = (int64_t)blockIdx.x * kPiece; r0 < N; r0 += (int64_t)gridDim.x * kPiece) {
+        // thread t takes rows r0 + t * 8 .. + 7: the kept rows of a piece stay in row order
+        const int64_t mine = r0 + (int64_t)threadIdx.x * kSelPerThread;
+        uint32_t keep = 0;
+        int cnt = 0;
+#pragma unroll
+        for (int j = 0; j < kSelPerThread; j++) {
+            const int64_t i = mine + j;
+            const bool k = i < N && !(G < expire[i]);
+            keep |= (uint32_t)k << j;
+            cnt += k;
+        }
+        // exclusive prefix over the workgroup: shuffle scan per wave, wave totals through LDS
+        int incl = cnt;
+#pragma unroll
+        for (int o = 1; o < kWave; o <<= 1) {
+            const int v = __shfl_up(incl, o, kWave);
+            if (lane >= o) incl += v;
+        }
+        if (lane == kWave - 1) s_wave[wave] = (uint32_t)incl;
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            uint32_t tot = 0;
+            for (int w = 0; w < kSelThreads / kWave; w++) {
+                const uint32_t v = s_wave[w];
+                s_wave[w] = tot;
+                tot += v;
+            }
+            s_wave[kSelThreads / kWave] = tot ? atomicAdd(n_rows, tot) : 0u;
+        }
+        __syncthreads();
+        uint32_t pos = s_wave[kSelThreads / kWave] + s_wave[wave] + (uint32_t)(incl - cnt);
+#pragma unroll
+        for (int j = 0; j < kSelPerThread; j++)
+            if (keep >> j & 1u) rows[pos++] = (int32_t)(mine + j);
+        __syncthreads();
     }
 }
 
@@ -365,14 +479,58 @@ LloydWs lloyd_carve(void* base, int64_t N, int64_t D, int32_t K) {
     return w;
 }
 
+bool tile_bounds_supports(int64_t N, int64_t D, int32_t K, cat_dtype dt) {
+    // row numbers in the list of rows are 32-bit; the bounds are derived for the two-part operand
+    return N < ((int64_t)1 << 31) && tile_config(TILE_LLOYD, D, K, dt, true).ok;
+}
+size_t bounds_workspace_bytes(int64_t N, int64_t D, int32_t K, int32_t iters) {
+    const size_t sk = (size_t)delta_slices(D) * (size_t)K;
+    return a256((size_t)N * 8) + a256((size_t)N * 4) + a256(4) + a256(((size_t)iters + 1) * 8) + a256(sk * 8) + a256(sk * 4);
+}
+BoundsWs bounds_carve(void* base, int64_t N, int64_t D, int32_t K, int32_t iters) {
+    BoundsWs w;
+    w.bytes = bounds_workspace_bytes(N, D, K, iters);
+    if (!base) return w;
+    const size_t sk = (size_t)delta_slices(D) * (size_t)K;
+    char* b = (char*)base;
+    w.expire = (double*)b;
+    b += a256((size_t)N * 8);
+    w.rows = (int32_t*)b;
+    b += a256((size_t)N * 4);
+    w.n_rows = (uint32_t*)b;
+    b += a256(4);
+    w.drift = (double*)b;
+    b += a256(((size_t)iters + 1) * 8);
+    w.move_part = (double*)b;
+    b += a256(sk * 8);
+    w.slice_counts = (int32_t*)b;
+    return w;
+}
+
+__global__ void k_fill_i32(int32_t* p, int64_t n, int32_t v) {
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = v;
+}
+cat_status launch_fill_i32(int32_t* p, int64_t n, int32_t v, hipStream_t st) {
+    hipLaunchKernelGGL(k_fill_i32, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, p, n, v);
+    CAT_LAUNCH_CHECK("k_fill_i32");
+    return CAT_OK;
+}
+
 // Sums update from the list of changed rows, then the centroid preparation of the next pass.
 // `par` is the parity of the pass that follows: it selects the halves of the double buffers.
 static cat_status launch_delta_prep(const void* lq, cat_dtype dt, int64_t D, int32_t K, const TileCfg& c,
                                     const TileWs& ws, const LloydWs& lw, int par, float* cent, double* base,
                                     double* delta, const int32_t* counts_prev, int32_t* counts_next,
                                     double* inertia_slot, unsigned long long* rep, int32_t* skipped, hipStream_t st,
-                                    int32_t inertia_n = 1) {
+                                    int32_t inertia_n = 1, const BoundsWs* bw = nullptr, bool seed_counts = false) {
     DeltaParams q = {};
+    if (bw) {
+        q.slice_counts = bw->slice_counts;
+        q.seed_counts = seed_counts ? 1 : 0;
+        q.move_part = bw->move_part;
+        q.n_rows_clear = bw->n_rows;
+    }
     q.lq = lq;
     q.D = D;
     q.K = K;
@@ -508,8 +666,12 @@ cat_status tile_assign(const void* lq, cat_dtype dt, int64_t N, int64_t D, int32
 
 cat_status tile_lloyd(const void* lq, cat_dtype dt, int64_t N, int64_t D, int32_t K, int32_t iters,
                       float* cent_io, double* sums, int32_t* assign, int32_t* counts, double* inertia,
-                      unsigned long long* rep, int32_t* skipped, const TileWs& ws, const LloydWs& lw, hipStream_t st) {
-    TileCfg c = tile_config(TILE_LLOYD, D, K, dt);
+                      unsigned long long* rep, int32_t* skipped, const TileWs& ws, const LloydWs& lw, hipStream_t st,
+                      const BoundsWs* bw) {
+    // rows are left out by their bounds in the passes 3 .. iters - 1
+    const bool bounds = bw && bw->expire && iters >= 4 && tile_bounds_supports(N, D, K, dt);
+    if (bounds) skipped = nullptr;  // (a pass over an empty list of rows costs next to nothing already)
+    TileCfg c = tile_config(TILE_LLOYD, D, K, dt, bounds);
     if (!c.ok) return set_error(CAT_ERR_UNSUPPORTED, "tile kernels do not fit D=%lld K=%d", (long long)D, (int)K);
     const size_t KD = (size_t)K * (size_t)D;
     double* base = sums;
@@ -525,6 +687,8 @@ cat_status tile_lloyd(const void* lq, cat_dtype dt, int64_t N, int64_t D, int32_
     p.assign = assign;
     if (iters > 2) CAT_T(launch_fill_zero(lw.ctrl, lloyd_ctrl_words(D) * 4, st));
     if (skipped) CAT_T(launch_fill_zero(skipped, sizeof(int32_t), st));
+    if (bw && bw->evaluated) CAT_T(launch_fill_i32(bw->evaluated, (int64_t)iters + 1, (int32_t)N, st));
+    if (bounds) CAT_T(launch_fill_zero(bw->drift, ((size_t)iters + 1) * sizeof(double), st));
     // Passes 0 and 1 are each followed by a full segmented sum: after the first reassignment most
     // rows still move, and moving them one by one costs several times a fresh sum (measured: 0.97 ms
     // against 0.33 ms on a 262144 x 2048 bf16 matrix).  From pass 2 on a pass lists the rows that
@@ -547,11 +711,29 @@ cat_status tile_lloyd(const void* lq, cat_dtype dt, int64_t N, int64_t D, int32_
                               ws, slot, last ? rep : nullptr, st));
         else
             CAT_T(launch_delta_prep(lq, dt, D, K, c, ws, lw, t & 1, cent_io, base, delta, cnt_prev, cnt_t, slot,
-                                    last ? rep : nullptr, last ? nullptr : skipped, st));
+                                    last ? rep : nullptr, last ? nullptr : skipped, st, 1, bounds ? bw : nullptr,
+                                    t == kFullPasses + 1));
+        // With bounds: pass 2 evaluates every row and leaves its bound; the passes 3 .. iters - 1 evaluate the rows
+        // whose bound the drift of the centroids has used up (selected here, after the update that moved them)
+        const bool keeps_bounds = bounds && t >= kFullPasses && !last;
+        const bool listed = keeps_bounds && t > kFullPasses;
+        if (listed) {
+            const int64_t piece = (int64_t)kSelThreads * kSelPerThread;
+            int64_t blocks = (N + piece - 1) / piece;
+            blocks = blocks > 2048 ? 2048 : blocks;
+            hipLaunchKernelGGL(k_bound_select, dim3((unsigned)blocks), dim3(kSelThreads), 0, st, bw->move_part,
+                               (int32_t)delta_slices(D), K, bw->drift + t - 1, bw->drift + t, bw->expire, N, bw->rows, bw->n_rows);
+            CAT_LAUNCH_CHECK("k_bound_select");
+        }
+        p.expire = keeps_bounds ? bw->expire : nullptr;
+        p.gnow = keeps_bounds ? bw->drift + t : nullptr;
+        p.rows = listed ? bw->rows : nullptr;
+        p.n_rows = listed ? bw->n_rows : nullptr;
+        p.evaluated_slot = (keeps_bounds && bw->evaluated) ? bw->evaluated + t : nullptr;
         p.norm_part = t > kFullPasses ? lw.norm_part : nullptr;
         p.norm_slices = t > kFullPasses ? (int32_t)delta_slices(D) : 0;
-        p.counts = cnt_t;
-        p.inertia = slot;
+        p.counts = listed ? nullptr : cnt_t;  // (a pass over listed rows cannot count: the slices keep running counts)
+        p.inertia = listed ? nullptr : slot;
         p.rep = last ? rep : nullptr;  // the final pass describes the partition that is returned
         p.list = (t >= kFullPasses && !last) ? lw.list : nullptr;
         p.list_count = lw.ctrl + (t & 1);
@@ -559,9 +741,12 @@ cat_status tile_lloyd(const void* lq, cat_dtype dt, int64_t N, int64_t D, int32_
         p.delta_mode = p.list ? 1 : 0;
         // alternate the scan direction: the rows a pass reads last are the ones most likely still in
         // the memory-side cache when the next pass starts
-        p.reverse = t & 1;
+        p.reverse = listed ? 0 : (t & 1);
         p.skip_when_zero = (skipped && t > kFullPasses && !last) ? lw.ctrl + ((t - 1) & 1) : nullptr;
-        CAT_T(launch_tile(p, c, dt, st));
+        if (keeps_bounds)
+            CAT_T(dt == CAT_BF16 ? launch_bounds_bf16(p, c, st) : launch_bounds_f32(p, c, st));
+        else
+            CAT_T(launch_tile(p, c, dt, st));
         if (t < kFullPasses && !last) {  // full sums of this pass's partition
             CAT_T(launch_fill_zero(sums, (t == 0 ? 2 : 1) * KD * sizeof(double), st));
             if (lw.sort_ws && segsum_sorted_supported(1, N, D, dt))
@@ -570,6 +755,8 @@ cat_status tile_lloyd(const void* lq, cat_dtype dt, int64_t N, int64_t D, int32_
                 CAT_T(launch_segsum(1, lq, nullptr, dt, assign, N, D, K, nullptr, nullptr, base, st));
         }
     }
+    if (bounds && inertia && iters > kFullPasses + 1)  // the objective of a pass over listed rows is not known
+        CAT_T(launch_fill_u64((unsigned long long*)(inertia + kFullPasses + 1), iters - kFullPasses - 1, 0x7ff8000000000000ull, st));
 #undef CAT_T
     return CAT_OK;
 }

@@ -74,6 +74,16 @@ struct TileParams {
     int32_t nsets;
     int16_t set_k[16];
     uint8_t set_t0[17];
+    // Distance bounds (BOUNDS instantiations only; Hamerly, SDM 2010).  A pass that evaluates a row leaves in
+    // expire[row] the value the accumulated centroid drift *gnow must reach before the row's nearest centroid can
+    // change: the drift at the evaluation plus a lower bound of (distance to the second nearest) - (distance to the
+    // nearest).  With `rows` given the pass walks only the *n_rows listed rows (16 to a tile, in list order) instead
+    // of all N; row numbers everywhere (assignments, list entries, expire) are the real ones.
+    double* expire;            // N doubles, nullable
+    const double* gnow;        // accumulated drift up to this pass
+    const int32_t* rows;       // nullable: listed rows
+    const uint32_t* n_rows;    // their number
+    int32_t* evaluated_slot;   // nullable: receives the number of rows this pass evaluates
 };
 
 // Which lane group g (0..3) and which of its 8 operand elements j hold channel r (0..31) of a
@@ -164,6 +174,7 @@ struct ChunkRegs {
     u32x4 v[BF16 ? 4 : 8];
     int prev;     // previous assignment of row n (assignment passes only)
     u32x4 prevv;  // several sets: previous assignments of row n in the sets 4 g .. 4 g + 3
+    int row;      // listed rows: the number of row n
 };
 
 // Rows past N repeat the last row and channel groups past D read the start of the row (valid
@@ -173,24 +184,31 @@ struct ChunkRegs {
 // With PREV the row's previous assignment rides along with every chunk: fetched inside the
 // tile's finishing code it would have to be waited for there, and since loads return in order
 // that wait would also drain the chunks requested ahead.
-template <bool BF16, int PREV>  // PREV: 0 none, 1 the row's previous assignment, 2 its previous assignments in all sets
-__device__ __forceinline__ void load_chunk(ChunkRegs<BF16>& r, const TileParams& p, int tile, int chunk, int lane) {
-    const int64_t row0 = (int64_t)(p.reverse ? (int)p.ntiles - 1 - tile : tile) * kRows;
-    const int nv = (p.N - row0) < kRows ? (int)(p.N - row0) : kRows;
+// LISTED: the tile's rows are not consecutive; lrow is the number of the row this lane loads (already clamped).
+template <bool BF16, int PREV, bool LISTED = false>  // PREV: 0 none, 1 the row's previous assignment, 2 its previous assignments in all sets
+__device__ __forceinline__ void load_chunk(ChunkRegs<BF16>& r, const TileParams& p, int tile, int chunk, int lane, int lrow = 0) {
     const int n = lane & 15, g = lane >> 4;
-    const int rn = n < nv ? n : nv - 1;
+    int64_t row;
+    if (LISTED) {
+        row = lrow;
+        r.row = lrow;
+    } else {
+        const int64_t row0 = (int64_t)(p.reverse ? (int)p.ntiles - 1 - tile : tile) * kRows;
+        const int nv = (p.N - row0) < kRows ? (int)(p.N - row0) : kRows;
+        row = row0 + (n < nv ? n : nv - 1);
+    }
     const int ch = chunk * kChunk + 8 * g;
-    if (PREV == 1) r.prev = p.assign[row0 + rn];
-    if (PREV == 2) r.prevv = *(const u32x4*)(p.assign + (row0 + rn) * 16 + 4 * g);
+    if (PREV == 1) r.prev = p.assign[row];
+    if (PREV == 2) r.prevv = *(const u32x4*)(p.assign + row * 16 + 4 * g);
     if (BF16) {
-        const bf16_t* x = (const bf16_t*)p.lq + (row0 + rn) * p.D;
+        const bf16_t* x = (const bf16_t*)p.lq + row * p.D;
 #pragma unroll
         for (int s = 0; s < 4; s++) {
             const int c = ch + 32 * s;
             r.v[s] = *(const u32x4*)(x + (c < p.D ? c : 0));
         }
     } else {
-        const float* x = (const float*)p.lq + (row0 + rn) * p.D;
+        const float* x = (const float*)p.lq + row * p.D;
         const int chf = chunk * kChunk + 4 * g;  // see operand_slot
 #pragma unroll
         for (int s = 0; s < 4; s++) {
@@ -260,10 +278,14 @@ __device__ __forceinline__ void contract_chunk(const ChunkRegs<BF16>& r, f32x4 (
 // Rank the centroids of the 16 rows from the accumulated dot products; exact re-rank of
 // the rows inside the error bound.  On return every lane (n, *) holds row n's result.
 // (t0, t1: the cluster tiles that take part, wave-uniform; all of them unless several sets share the kernel)
+// myrow: the number of row n (lanes of q = 0 at least), valid: whether it exists.  first / second / reranked / bound
+// (optional outputs): the best score, the best among the other centroids, whether the row goes through the exact
+// re-rank, and the threshold of that decision.
 template <int KT, bool BF16>
 __device__ __forceinline__ void rank_rows(const TileParams& p, const f32x4 (&acc)[KT], const float* s_cnorm,
-                                          float xn2, float cmax, int64_t row0, int lane, int& idx, float& dmin,
-                                          int t0 = 0, int t1 = KT) {
+                                          float xn2, float cmax, int64_t myrow, bool valid, int lane, int& idx, float& dmin,
+                                          int t0 = 0, int t1 = KT, float* first = nullptr, float* second = nullptr,
+                                          bool* reranked = nullptr, float* bound = nullptr) {
     const int n = lane & 15, q = lane >> 4;
     float b1 = __builtin_inff(), b2 = __builtin_inff();
     int i1 = 16 * t0;
@@ -294,15 +316,19 @@ __device__ __forceinline__ void rank_rows(const TileParams& p, const f32x4 (&acc
         b2 = fminf(fminf(b2, ob2), loser);
     }
     const float T = p.tau * sqrtf(xn2) * cmax + p.tau2 * cmax * cmax;
-    const bool valid = row0 + n < p.N;
     const bool flag = valid && !(b2 - b1 > T);
+    if (first) *first = b1;
+    if (second) *second = b2;
+    if (reranked) *reranked = flag;
+    if (bound) *bound = T;
     dmin = fmaxf(xn2 + b1, 0.f);
     unsigned long long mask = __ballot(flag && q == 0);
     while (mask) {
         const int r = __builtin_amdgcn_readfirstlane(__builtin_ctzll(mask));
         mask &= mask - 1;
         const float thr = readlane_f(b1, r) + readlane_f(T, r);
-        const int64_t row = row0 + r;
+        const int64_t row = ((int64_t)__builtin_amdgcn_readlane((int)(myrow >> 32), r) << 32) |
+                            (int64_t)(uint32_t)__builtin_amdgcn_readlane((int)myrow, r);
         double dbest = __builtin_inf();
         int kbest = 0x7fffffff;
         // the candidates (scores within the bound of the best) are listed first, one per lane, then
@@ -361,22 +387,29 @@ __device__ __forceinline__ void rank_rows(const TileParams& p, const f32x4 (&acc
 }
 
 // Per-tile finishing work of the streaming modes: rank, write, book-keep; resets acc / nrm.
-template <int KT, bool BF16, int MODE>
+// BOUNDS: the pass also leaves the row's distance bound (TileParams::expire); with listed rows (row_in >= 0 is the
+// number of row n, n_listed their count) the tile is 16 entries of the list instead of 16 consecutive rows.
+template <int KT, bool BF16, int MODE, bool BOUNDS = false>
 __device__ __forceinline__ void finish_tile(const TileParams& p, unsigned char* smem, f32x4 (&acc)[KT], float& nrm,
-                                            int tile, int lane, float cmax, double& in_acc, int prev_in) {
+                                            int tile, int lane, float cmax, double& in_acc, int prev_in, int row_in = -1,
+                                            uint32_t n_listed = 0, double gnow = 0.0) {
     const int n = lane & 15, q = lane >> 4;
-    const int64_t row0 = (int64_t)(p.reverse ? (int)p.ntiles - 1 - tile : tile) * kRows;
+    const bool listed = BOUNDS && p.rows != nullptr;
+    const int64_t row0 = listed ? 0 : (int64_t)(p.reverse ? (int)p.ntiles - 1 - tile : tile) * kRows;
+    const int64_t myrow = listed ? (int64_t)row_in : row0 + n;
+    const bool valid = listed ? (uint32_t)(tile * kRows + n) < n_listed : myrow < p.N;
     const float* s_cnorm = (const float*)(smem + p.off_cnorm);
     float xn2 = nrm;
     xn2 += __shfl_xor(xn2, 16, kWave);
     xn2 += __shfl_xor(xn2, 32, kWave);
     int idx;
-    float dmin;
-    rank_rows<KT, BF16>(p, acc, s_cnorm, xn2, cmax, row0, lane, idx, dmin);
+    float dmin, first = 0.f, second = 0.f, bound = 0.f;
+    bool reranked = false;
+    rank_rows<KT, BF16>(p, acc, s_cnorm, xn2, cmax, myrow, valid, lane, idx, dmin, 0, KT, BOUNDS ? &first : nullptr,
+                        BOUNDS ? &second : nullptr, BOUNDS ? &reranked : nullptr, BOUNDS ? &bound : nullptr);
 #pragma unroll
     for (int t = 0; t < KT; t++) acc[t] = (f32x4){0.f, 0.f, 0.f, 0.f};
     nrm = 0.f;
-    const bool valid = row0 + n < p.N;
     const bool owner = q == 0 && valid;
 
     if (MODE == MODE_APPLY) {
@@ -462,17 +495,32 @@ __device__ __forceinline__ void finish_tile(const TileParams& p, unsigned char* 
     int* s_misc = (int*)(smem + p.off_misc);
     const int prev = p.delta_mode ? prev_in : -1;
     if (owner) {
-        p.assign[row0 + n] = idx;
+        p.assign[myrow] = idx;
         if (p.counts) atomicAdd(&s_hist[idx], 1);
-        if (p.rep) atomicMin(&s_rep[idx], (unsigned long long)(row0 + n));
+        if (p.rep) atomicMin(&s_rep[idx], (unsigned long long)myrow);
         in_acc += (double)dmin;
+    }
+    if (BOUNDS && p.expire && owner) {
+        // How far the centroids may drift before this row's nearest centroid can change: with e the error bound of
+        // a score (the re-rank threshold, which bounds a difference of two scores, plus the rounding of |x|^2), the
+        // nearest centroid is at most sqrt(|x|^2 + s1 + e) away and every other at least sqrt(|x|^2 + s2 - e).  A row
+        // that was re-ranked has two centroids within the bound of each other: no margin.  No second centroid
+        // (s2 = inf): never again.
+        double m = 0.0;
+        if (!reranked) {
+            const double e = (double)bound + (double)xn2 * (double)p.D * 1.5e-8;
+            const double hi1 = (double)xn2 + (double)first + e;
+            const double lo2 = (double)xn2 + (double)second - e;
+            if (lo2 > hi1) m = (sqrt(lo2) - sqrt(hi1 > 0.0 ? hi1 : 0.0)) * (1.0 - 1e-9);
+        }
+        p.expire[myrow] = gnow + m;
     }
     if (p.list) {
         // rows that changed cluster: into the workgroup's LDS list; when that is full, straight to
         // the global list (one reservation per tile)
         const bool changed = owner && prev != idx;
         const unsigned long long entry =
-            ((unsigned long long)(row0 + n) << 24) | ((unsigned long long)(prev + 1) << 12) | (unsigned long long)idx;
+            ((unsigned long long)myrow << 24) | ((unsigned long long)(prev + 1) << 12) | (unsigned long long)idx;
         bool ovf = false;
         if (changed) {
             int pos = atomicAdd(&s_misc[0], 1);
@@ -515,7 +563,7 @@ __device__ __forceinline__ void finish_tile_multi(const TileParams& p, unsigned 
     for (int s = 0; s < p.nsets; s++) {
         int idx;
         float dmin;
-        rank_rows<KT, BF16>(p, acc, s_cnorm, xn2, cmax, row0, lane, idx, dmin, (int)p.set_t0[s], (int)p.set_t0[s + 1]);
+        rank_rows<KT, BF16>(p, acc, s_cnorm, xn2, cmax, row0 + n, valid, lane, idx, dmin, (int)p.set_t0[s], (int)p.set_t0[s + 1]);
         const bool owner = valid && q == (s >> 2);
         const int e = s & 3;
         const int prev = p.delta_mode ? (int)(e == 0 ? prevv.x : e == 1 ? prevv.y : e == 2 ? prevv.z : prevv.w) : -1;
@@ -556,10 +604,21 @@ __device__ __forceinline__ void finish_tile_multi(const TileParams& p, unsigned 
 }
 
 // ---- the kernel ----------------------------------------------------------------------
-template <int KT, int PASSES, bool BF16, int MODE, bool CA, bool MULTI = false>
+// VAR: 0 the plain pass, 1 several centroid sets side by side (finish_tile_multi), 2 a pass that keeps distance
+// bounds and may walk a list of rows instead of all of them (TileParams::expire, rows).
+enum { VAR_PLAIN = 0, VAR_MULTI = 1, VAR_BOUNDS = 2 };
+template <int KT, int PASSES, bool BF16, int MODE, bool CA, int VAR = VAR_PLAIN>
 __global__ __launch_bounds__(kMaxWaves * kWave) void k_tile(const TileParams p) {
     extern __shared__ __align__(16) unsigned char smem[];
+    constexpr bool MULTI = VAR == VAR_MULTI, BOUNDS = VAR == VAR_BOUNDS;
     if (p.skip_when_zero && *p.skip_when_zero == 0u) return;  // uniform over the grid, before any barrier
+    const bool listed = BOUNDS && p.rows != nullptr;
+    const uint32_t n_listed = listed ? *p.n_rows : 0u;
+    const double gnow = (BOUNDS && p.gnow) ? *p.gnow : 0.0;
+    if (BOUNDS && p.evaluated_slot && blockIdx.x == 0 && threadIdx.x == 0)
+        *p.evaluated_slot = listed ? (int32_t)n_listed : (int32_t)p.N;
+    // listed rows: a workgroup none of whose waves has a tile leaves before any barrier
+    if (listed && (uint32_t)blockIdx.x * (uint32_t)p.waves * kRows >= n_listed) return;
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);  // wave-uniform: keeps tile math scalar
     constexpr int P = PASSES == 1 ? 1 : 2;
@@ -568,21 +627,40 @@ __global__ __launch_bounds__(kMaxWaves * kWave) void k_tile(const TileParams p) 
     unsigned long long* s_rep = (unsigned long long*)(smem + p.off_rep);
     int* s_misc = (int*)(smem + p.off_misc);  // [0] list count, [2..] doubles for the objective
 
-    const int ntiles = (int)p.ntiles;
+    const int ntiles = listed ? (int)((n_listed + kRows - 1) / kRows) : (int)p.ntiles;
     const int tstride = (int)gridDim.x * p.waves;
     const int tile0 = __builtin_amdgcn_readfirstlane((int)blockIdx.x * p.waves + wave);
     int tl = tile0, cl = 0;  // load cursor
     float cmax_out;
     ChunkRegs<BF16> b0, b1, b2;
+    // listed rows: the number of the row this lane loads in the tile at the load cursor, and in the tile after it
+    // (requested a whole tile ahead: waiting for it where it is needed would drain the chunks in flight)
+    int lrow = 0, lrow_nx = 0;
+    auto listed_row = [&](int tile) -> int {
+        uint32_t e = (uint32_t)tile * kRows + (uint32_t)(lane & 15);
+        e = e < n_listed ? e : n_listed - 1u;  // n_listed > 0 here (the workgroup has a tile)
+        return p.rows[e];
+    };
+    if (listed) {
+        lrow = listed_row(tile0 < ntiles ? tile0 : 0);
+        lrow_nx = listed_row(tile0 + tstride < ntiles ? tile0 + tstride : 0);
+    }
     // A wave stops requesting rows once its cursor has passed its last tile.  (Requesting them
     // unconditionally, the last tile again, lets the compiler count on two chunks in flight at
     // every wait instead of draining to one; measured, that was 2-5 % slower, not faster.)
 #define CAT_ISSUE(buf)                                                                     \
     if (tl < ntiles) {                                                                     \
-        load_chunk<BF16, MODE == MODE_ASSIGN ? (MULTI ? 2 : 1) : 0>(buf, p, tl, cl, lane); \
+        if (listed)                                                                        \
+            load_chunk<BF16, 1, true>(buf, p, tl, cl, lane, lrow);                         \
+        else                                                                               \
+            load_chunk<BF16, MODE == MODE_ASSIGN ? (MULTI ? 2 : 1) : 0>(buf, p, tl, cl, lane); \
         if (++cl == p.nchunks) {                                                           \
             cl = 0;                                                                        \
             tl += tstride;                                                                 \
+            if (listed) {                                                                  \
+                lrow = lrow_nx;                                                            \
+                lrow_nx = listed_row(tl + tstride < ntiles ? tl + tstride : 0);            \
+            }                                                                              \
         }                                                                                  \
     }
     // prologue: centroids (operand order) and their norms into LDS.  Returns come back in issue order,
@@ -678,6 +756,8 @@ __global__ __launch_bounds__(kMaxWaves * kWave) void k_tile(const TileParams p) 
     if (++cc == p.nchunks) {                                                                                   \
         if (MULTI)                                                                                             \
             finish_tile_multi<KT, BF16>(p, smem, acc, nrm, tc, lane, cmax, buf.prevv);                         \
+        else if (BOUNDS)                                                                                       \
+            finish_tile<KT, BF16, MODE, true>(p, smem, acc, nrm, tc, lane, cmax, in_acc, buf.prev, buf.row, n_listed, gnow); \
         else                                                                                                   \
             finish_tile<KT, BF16, MODE>(p, smem, acc, nrm, tc, lane, cmax, in_acc, buf.prev);                  \
         cc = 0;                                                                                                \
@@ -720,6 +800,8 @@ __global__ __launch_bounds__(kMaxWaves * kWave) void k_tile(const TileParams p) 
             if (++cc == p.nchunks) {                                                                          \
                 if (MULTI)                                                                                    \
                     finish_tile_multi<KT, BF16>(p, smem, acc, nrm, tc, lane, cmax, bufcur.prevv);             \
+                else if (BOUNDS)                                                                              \
+                    finish_tile<KT, BF16, MODE, true>(p, smem, acc, nrm, tc, lane, cmax, in_acc, bufcur.prev, bufcur.row, n_listed, gnow); \
                 else                                                                                          \
                     finish_tile<KT, BF16, MODE>(p, smem, acc, nrm, tc, lane, cmax, in_acc, bufcur.prev);      \
                 cc = 0;                                                                                       \
@@ -806,9 +888,9 @@ struct TileCfg {
     size_t lds_total = 0;
 };
 
-template <int KT, int PASSES, bool BF16, int MODE, bool CA, bool MULTI = false>
+template <int KT, int PASSES, bool BF16, int MODE, bool CA, int VAR = VAR_PLAIN>
 static inline cat_status launch_one(const TileParams& p, const TileCfg& c, hipStream_t st) {
-    auto kern = k_tile<KT, PASSES, BF16, MODE, CA, MULTI>;
+    auto kern = k_tile<KT, PASSES, BF16, MODE, CA, VAR>;
     if (CA && c.waves != kMaxWaves) {
         return set_error(CAT_ERR_INVALID_ARG, "k_tile: the chunked-operand variant needs %d waves, got %d", kMaxWaves, c.waves);
     }
@@ -862,10 +944,18 @@ static inline cat_status launch_kt(const TileParams& p, const TileCfg& c, hipStr
 template <int KT, bool BF16>
 static inline cat_status launch_kt_multi(const TileParams& p, const TileCfg& c, hipStream_t st) {
     if (c.chunked)
-        return c.P == 2 ? launch_one<KT, 3, BF16, MODE_ASSIGN, true, true>(p, c, st)
-                        : launch_one<KT, 1, BF16, MODE_ASSIGN, true, true>(p, c, st);
-    return c.P == 2 ? launch_one<KT, 3, BF16, MODE_ASSIGN, false, true>(p, c, st)
-                    : launch_one<KT, 1, BF16, MODE_ASSIGN, false, true>(p, c, st);
+        return c.P == 2 ? launch_one<KT, 3, BF16, MODE_ASSIGN, true, VAR_MULTI>(p, c, st)
+                        : launch_one<KT, 1, BF16, MODE_ASSIGN, true, VAR_MULTI>(p, c, st);
+    return c.P == 2 ? launch_one<KT, 3, BF16, MODE_ASSIGN, false, VAR_MULTI>(p, c, st)
+                    : launch_one<KT, 1, BF16, MODE_ASSIGN, false, VAR_MULTI>(p, c, st);
+}
+
+// assignment passes that keep distance bounds (two-part operand only)
+template <int KT, bool BF16>
+static inline cat_status launch_kt_bounds(const TileParams& p, const TileCfg& c, hipStream_t st) {
+    if (c.P != 2) return set_error(CAT_ERR_UNSUPPORTED, "tile kernel with distance bounds: two-part operand only");
+    if (c.chunked) return launch_one<KT, 3, BF16, MODE_ASSIGN, true, VAR_BOUNDS>(p, c, st);
+    return launch_one<KT, 3, BF16, MODE_ASSIGN, false, VAR_BOUNDS>(p, c, st);
 }
 
 // one translation unit per (KT, dtype), for compile time: cat_tile_k<KT>_<dtype>.hip
@@ -882,5 +972,8 @@ cat_status launch_kt16_bf16(const TileParams& p, const TileCfg& c, hipStream_t s
 // the instantiations for several centroid sets: cat_tile_multi_<dtype>.hip
 cat_status launch_multi_f32(const TileParams& p, const TileCfg& c, hipStream_t st);
 cat_status launch_multi_bf16(const TileParams& p, const TileCfg& c, hipStream_t st);
+// the instantiations that keep distance bounds: cat_tile_bounds_<dtype>.hip
+cat_status launch_bounds_f32(const TileParams& p, const TileCfg& c, hipStream_t st);
+cat_status launch_bounds_bf16(const TileParams& p, const TileCfg& c, hipStream_t st);
 
 }  // namespace cat
