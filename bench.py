@@ -14,7 +14,12 @@ process.  The top-level fields are those of cfg3, the largest fitting workload
 holds, for every workload, the same figures: value, ms_per_step, roofline (the
 assignment pass), apply_roofline (the fused inference pass), the whole Lloyd
 iteration as a fraction of the roofline, and cpu_baseline.  --workload cfgN runs
-that workload alone and prints its figures at the top level.
+that workload alone and prints its figures at the top level.  `detail` carries the
+rows beside the two calls: the fit with distance bounds (fit_bounds_ms,
+lloyd_iter_frac_hbm_bounds: same outputs, its average iteration against the same
+algorithmic bytes), the low-precision inference (apply_lp_bf16_*), and on cfg2 the
+PCA front-end, the sweep of the blending coefficient, the seeding, the early stop,
+the fits for a grid of cluster counts and a shape on the LDS streaming kernel.
 
 value        rows x Lloyd-iterations per second of whole-step time (cfg5: GB/s of
              cat_apply, read + write)
@@ -169,6 +174,17 @@ def _run_workload(name, args, torch, np, cpu_budget_s, extras):
                     bytes_per_launch=alg_bytes, us_per_launch=1e3 * t_k, launches=len(ms))
         metric, unit = "cat_fit_lloyd_rows_per_s", "rows/s"
         value = N * iters / (ms_per_step * 1e-3)
+        # the same fit with rows left out by distance bounds (same outputs; a separate figure, never the headline):
+        # its average iteration against the same algorithmic bytes, and the share of the rows its passes evaluate
+        ws_b = torch.empty(binding.load_library().cat_fit_bounds_workspace_bytes(N, D, K, iters, dtc), dtype=torch.uint8, device="cuda")
+        fb = lambda: cat_fit(lq, fp, K, iters, seed=w["seed"], workspace=ws_b, bounds=True)
+        ev = fb()["rows_evaluated"].cpu().numpy()
+        t_fb = _events(fb, reps, torch)
+        t_iter_b = (t_fb - t_fit0) / iters
+        detail.update(fit_bounds_ms=t_fb, lloyd_iter_us_bounds=1e3 * t_iter_b,
+                      lloyd_iter_frac_hbm_bounds=alg_bytes / t_iter_b / 1e6 / HBM_PEAK_GBPS,
+                      bounds_rows_evaluated_frac=float(ev.mean()) / N)
+        del ws_b
     else:
         apply_args = (cent, gamma, beta)
         roof = None
@@ -191,6 +207,17 @@ def _run_workload(name, args, torch, np, cpu_budget_s, extras):
                   apply_rows_per_s=N * 1e3 / t_apply)
     if roof is None:
         roof = apply_roof
+    # low-precision deployment of the same transformation: bfloat16 parameters, bfloat16 corrected rows (fp32 rows only)
+    if dt == "f32":
+        from paper_2509_26277_amd import cat_apply_lp, cat_params_to_bf16
+        cq, gq, bq = (cat_params_to_bf16(t) for t in apply_args)
+        out16 = torch.empty((N, D), dtype=torch.bfloat16, device="cuda")
+        ws_lp = torch.empty(binding.load_library().cat_apply_lp_workspace_bytes(N, D, K, dtc), dtype=torch.uint8, device="cuda")
+        t_lp = _events(lambda: cat_apply_lp(lq, cq, gq, bq, bf16_out=True, out=out16, workspace=ws_lp), reps, torch)
+        lp_bytes = N * D * (esize + 2) + 4 * N
+        detail.update(apply_lp_bf16_ms=t_lp, apply_lp_bf16_GBps=lp_bytes / t_lp / 1e6,
+                      apply_lp_bf16_frac_hbm=lp_bytes / t_lp / 1e6 / HBM_PEAK_GBPS)
+        del out16, ws_lp
 
     # ---- the PCA front-end (a separate row of the method: not part of `value` or `roofline`) ----
     if extras and fit_kind and args.pca_dim > 0 and D <= 2048:
@@ -243,6 +270,18 @@ def _run_workload(name, args, torch, np, cpu_budget_s, extras):
         es = lambda: cat_fit(lq, fp, K, iters, seed=w["seed"], workspace=ws_fit, early_stop=True)
         skipped = int(es()["passes_skipped"].item())
         detail.update(fit_early_stop_ms=_events(es, 5, torch), passes_skipped=skipped)
+
+    # ---- fits for the grid of cluster counts of the paper's ablation, one call against eleven (another separate row) ----
+    if extras and fit_kind and not args.no_seeding:
+        from paper_2509_26277_amd import cat_fit_multi_k
+        grid_k = [k for k in (1, 8, 16, 24, 32, 48, 64, 96, 128, 192, 256) if k <= N]
+        t_sep = {k: _events(lambda: cat_fit(lq, fp, k, iters, seed=w["seed"]), 2, torch) for k in grid_k}
+        t_multi = _events(lambda: cat_fit_multi_k(lq, fp, grid_k, iters, seed=w["seed"]), 2, torch)
+        small = [k for k in grid_k if k <= 32]
+        t_small = _events(lambda: cat_fit_multi_k(lq, fp, small, iters, seed=w["seed"]), 2, torch)
+        detail.update(multi_k_grid=grid_k, multi_k_ms=t_multi, multi_k_separate_ms=sum(t_sep.values()),
+                      multi_k_ratio=t_multi / sum(t_sep.values()), multi_k_upto32_ms=t_small,
+                      multi_k_upto32_separate_ms=sum(t_sep[k] for k in small))
 
     # ---- a shape outside the matrix-core kernels (one more channel: rows are no longer whole 16-byte groups), which
     # takes the LDS streaming kernel; beside it the same calls on the workload's own, aligned shape ----
