@@ -34,6 +34,8 @@ struct LloydWs {
     int32_t* skipped = nullptr;          //   then one word: passes left out, for callers that bring no word of their own
     double* norm_part = nullptr;         // slices x K
     int32_t* counts2 = nullptr;          // K: the second half of the counts double buffer
+    float2* carry = nullptr;             // N pairs, only for more than 128 clusters: what the first of two launches that
+    float* carry_cmax = nullptr;         //   split the clusters hands to the second (per row; the largest centroid norm)
     uint32_t* sort_ws = nullptr;         // not carved here: the caller's scratch for launch_segsum_sorted
     size_t bytes = 0;
 };

@@ -10,12 +10,12 @@ namespace cat {
 // empty; the counts are those of the pass before, counts_read).  Then the row is split and
 // scattered into packA, and its squared norm stored.  Last, the outputs of the following pass are
 // reset: its counts (counts_reset, which may be the buffer just read), the objective slot and the
-// first-row table.
+// first-row table.  (KT is not used for the layout any more: KTs, the cluster tiles per operand array, is.)
 __global__ __launch_bounds__(256) void k_tile_prep(float* cent, double* base, double* delta,
                                                    const int32_t* counts_read, int32_t* counts_reset,
                                                    int64_t D, int32_t K, int32_t KT, int32_t P, int32_t nchunks, int f32_rows,
                                                    uint16_t* packA, float* cnorm, double* inertia_slot,
-                                                   int32_t inertia_n, unsigned long long* rep) {
+                                                   int32_t inertia_n, unsigned long long* rep, int32_t KTs) {
     __shared__ double s_red[256];
     const int k = blockIdx.x;
     const int t = k >> 4, m = k & 15;
@@ -43,7 +43,8 @@ __global__ __launch_bounds__(256) void k_tile_prep(float* cent, double* base, do
         operand_slot(r & 31, f32_rows != 0, g, j);
         const int lane = g * 16 + m;
         const uint32_t hw = pack_bf16(c, 0.f) & 0xFFFFu;
-        const size_t blk = ((size_t)(cc * 4 + s) * KT + t) * P;
+        // (KTs < KT: the operand is laid out as KT / KTs arrays of KTs cluster tiles each, one after the other)
+        const size_t blk = (size_t)(t / KTs) * ((size_t)nchunks * 4 * KTs * P) + ((size_t)(cc * 4 + s) * KTs + t % KTs) * P;
         packA[(blk * 64 + lane) * 8 + j] = (uint16_t)hw;
         if (P == 2) {
             const uint32_t lw = pack_bf16(c - lo_half(hw), 0.f) & 0xFFFFu;
@@ -81,7 +82,7 @@ __global__ __launch_bounds__(256) void k_tile_prep(float* cent, double* base, do
 struct DeltaParams {
     const void* lq;
     int64_t D;
-    int32_t K, KT, P, KC, G, f32_rows;
+    int32_t K, KT, KTs, P, KC, G, f32_rows;  // KTs: cluster tiles per operand array (KT unless the clusters are split)
     const unsigned long long* list;
     const uint32_t* list_count;  // length of the list of the pass before
     uint32_t* list_count_next;   // cleared: the following pass appends here
@@ -272,7 +273,8 @@ __global__ __launch_bounds__(kDeltaWaves * kWave) void k_delta_prep(const DeltaP
                 operand_slot(r & 31, q.f32_rows != 0, g, j);
                 const int ol = g * 16 + m;
                 const uint32_t hw = pack_bf16(c, 0.f) & 0xFFFFu;
-                const size_t blk = ((size_t)(cc * 4 + s) * q.KT + t) * q.P;
+                const size_t nch = (size_t)((q.D + kChunk - 1) / kChunk);
+                const size_t blk = (size_t)(t / q.KTs) * (nch * 4 * q.KTs * q.P) + ((size_t)(cc * 4 + s) * q.KTs + t % q.KTs) * q.P;
                 q.packA[(blk * 64 + ol) * 8 + j] = (uint16_t)hw;
                 if (q.P == 2) {
                     const uint32_t lw = pack_bf16(c - lo_half(hw), 0.f) & 0xFFFFu;
@@ -377,7 +379,7 @@ __global__ __launch_bounds__(kSelThreads) void k_bound_select(const double* __re
 
 static inline uint32_t up16(size_t x) { return (uint32_t)((x + 15) & ~(size_t)15); }
 
-static TileCfg tile_config(TileMode mode, int64_t D, int32_t K, cat_dtype dt, bool two_parts_only = false) {
+static TileCfg tile_config(TileMode mode, int64_t D, int32_t K, cat_dtype dt, bool two_parts_only = false, int32_t hist_k = 0) {
     TileCfg c;
     const int K16 = (K + 15) & ~15;
     int KT = 1;
@@ -399,10 +401,11 @@ static TileCfg tile_config(TileMode mode, int64_t D, int32_t K, cat_dtype dt, bo
             TileCfg t;
             t.off_cnorm = up16(off);
             off = t.off_cnorm + (size_t)KT * 16 * 4;
+            const size_t KH = hist_k > K ? hist_k : K;  // clusters the per-cluster tables span
             t.off_hist = up16(off);
-            off = t.off_hist + (size_t)K * 4;
+            off = t.off_hist + KH * 4;
             t.off_rep = up16(off);
-            off = t.off_rep + (size_t)K * 8;
+            off = t.off_rep + KH * 8;
             t.off_list = up16(off);
             off = t.off_list + (lists ? (size_t)kListCap * 8 : 0);
             t.off_misc = up16(off);
@@ -456,12 +459,13 @@ TileWs tile_carve(void* base, int64_t D, int32_t K, cat_dtype dt) {
 }
 
 static inline int64_t delta_slices(int64_t D) { return (D + kDeltaSW - 1) / kDeltaSW; }
+constexpr int kSplitTiles = 8;  // cluster tiles per launch when the clusters of a pass are split over two
 
 static inline size_t lloyd_ctrl_words(int64_t D) { return (size_t)(3 + 2 * delta_slices(D)); }
 
 size_t lloyd_workspace_bytes(int64_t N, int64_t D, int32_t K) {
     return a256((size_t)N * 8) + a256(lloyd_ctrl_words(D) * 4) + a256((size_t)delta_slices(D) * K * 8) +
-           a256((size_t)K * 4);
+           a256((size_t)K * 4) + (K > kSplitTiles * 16 ? a256((size_t)N * 8) + 256 : 0);
 }
 LloydWs lloyd_carve(void* base, int64_t N, int64_t D, int32_t K) {
     LloydWs w;
@@ -476,7 +480,24 @@ LloydWs lloyd_carve(void* base, int64_t N, int64_t D, int32_t K) {
     w.norm_part = (double*)b;
     b += a256((size_t)delta_slices(D) * K * 8);
     w.counts2 = (int32_t*)b;
+    b += a256((size_t)K * 4);
+    if (K > kSplitTiles * 16) {
+        w.carry = (float2*)b;
+        b += a256((size_t)N * 8);
+        w.carry_cmax = (float*)b;
+    }
     return w;
+}
+
+// More than 128 clusters need 16 cluster tiles, whose two-part operand fits LDS only for short rows; otherwise the
+// clusters are ranked by two launches of 8 tiles each (k_tile<..., VAR_SPLIT>), the first handing its best on.
+static bool split_config(int64_t D, int32_t K, cat_dtype dt, TileCfg* out) {
+    if (K <= kSplitTiles * 16 || K > 2 * kSplitTiles * 16) return false;
+    if (tile_config(TILE_LLOYD, D, K, dt, true).ok) return false;  // one launch ranks them all with two parts
+    TileCfg c = tile_config(TILE_LLOYD, D, kSplitTiles * 16, dt, true, K);
+    if (!c.ok || c.KT != kSplitTiles) return false;
+    if (out) *out = c;
+    return true;
 }
 
 bool tile_bounds_supports(int64_t N, int64_t D, int32_t K, cat_dtype dt) {
@@ -523,8 +544,10 @@ static cat_status launch_delta_prep(const void* lq, cat_dtype dt, int64_t D, int
                                     const TileWs& ws, const LloydWs& lw, int par, float* cent, double* base,
                                     double* delta, const int32_t* counts_prev, int32_t* counts_next,
                                     double* inertia_slot, unsigned long long* rep, int32_t* skipped, hipStream_t st,
-                                    int32_t inertia_n = 1, const BoundsWs* bw = nullptr, bool seed_counts = false) {
+                                    int32_t inertia_n = 1, const BoundsWs* bw = nullptr, bool seed_counts = false,
+                                    int32_t split_tiles = 0) {
     DeltaParams q = {};
+    q.KTs = split_tiles ? split_tiles : c.KT;
     if (bw) {
         q.slice_counts = bw->slice_counts;
         q.seed_counts = seed_counts ? 1 : 0;
@@ -571,10 +594,11 @@ static cat_status launch_delta_prep(const void* lq, cat_dtype dt, int64_t D, int
 
 static cat_status launch_prep(cat_dtype dt, float* cent, double* base, double* delta, const int32_t* counts_read,
                               int32_t* counts_reset, int64_t D, int32_t K, const TileCfg& c, const TileWs& ws,
-                              double* inertia_slot, unsigned long long* rep, hipStream_t st, int32_t inertia_n = 1) {
-    dim3 grid(c.KT * 16), block(256);
-    hipLaunchKernelGGL(k_tile_prep, grid, block, 0, st, cent, base, delta, counts_read, counts_reset, D, K, c.KT, c.P,
-                       c.nchunks, dt == CAT_F32 ? 1 : 0, ws.packA, ws.cnorm, inertia_slot, inertia_n, rep);
+                              double* inertia_slot, unsigned long long* rep, hipStream_t st, int32_t inertia_n = 1,
+                              int32_t split_arrays = 1) {
+    dim3 grid(c.KT * 16 * split_arrays), block(256);
+    hipLaunchKernelGGL(k_tile_prep, grid, block, 0, st, cent, base, delta, counts_read, counts_reset, D, K, c.KT * split_arrays,
+                       c.P, c.nchunks, dt == CAT_F32 ? 1 : 0, ws.packA, ws.cnorm, inertia_slot, inertia_n, rep, c.KT);
     CAT_LAUNCH_CHECK("k_tile_prep");
     return CAT_OK;
 }
@@ -587,7 +611,7 @@ cat_status launch_tile_prep_plain(cat_dtype dt, const float* cent, int64_t D, in
     dim3 grid(KT * 16), block(256);
     hipLaunchKernelGGL(k_tile_prep, grid, block, 0, st, const_cast<float*>(cent), (double*)nullptr, (double*)nullptr,
                        (const int32_t*)nullptr, (int32_t*)nullptr, D, K, KT, P, nchunks, rows_layout_f32, packA, cnorm,
-                       (double*)nullptr, 0, (unsigned long long*)nullptr);
+                       (double*)nullptr, 0, (unsigned long long*)nullptr, KT);
     CAT_LAUNCH_CHECK("k_tile_prep");
     return CAT_OK;
 }
@@ -673,6 +697,8 @@ cat_status tile_lloyd(const void* lq, cat_dtype dt, int64_t N, int64_t D, int32_
     if (bounds) skipped = nullptr;  // (a pass over an empty list of rows costs next to nothing already)
     TileCfg c = tile_config(TILE_LLOYD, D, K, dt, bounds);
     if (!c.ok) return set_error(CAT_ERR_UNSUPPORTED, "tile kernels do not fit D=%lld K=%d", (long long)D, (int)K);
+    const bool split = !bounds && lw.carry && split_config(D, K, dt, &c);  // (c then describes one of the two launches)
+    const int32_t arrays = split ? 2 : 1;
     const size_t KD = (size_t)K * (size_t)D;
     double* base = sums;
     double* delta = sums + KD;
@@ -708,11 +734,11 @@ cat_status tile_lloyd(const void* lq, cat_dtype dt, int64_t N, int64_t D, int32_
         const int32_t* cnt_prev = cb[(iters - t + 1) & 1];
         if (t <= kFullPasses)
             CAT_T(launch_prep(dt, cent_io, t ? base : nullptr, t ? delta : nullptr, t ? cnt_prev : nullptr, cnt_t, D, K, c,
-                              ws, slot, last ? rep : nullptr, st));
+                              ws, slot, last ? rep : nullptr, st, 1, arrays));
         else
             CAT_T(launch_delta_prep(lq, dt, D, K, c, ws, lw, t & 1, cent_io, base, delta, cnt_prev, cnt_t, slot,
                                     last ? rep : nullptr, last ? nullptr : skipped, st, 1, bounds ? bw : nullptr,
-                                    t == kFullPasses + 1));
+                                    t == kFullPasses + 1, split ? kSplitTiles : 0));
         // With bounds: pass 2 evaluates every row and leaves its bound; the passes 3 .. iters - 1 evaluate the rows
         // whose bound the drift of the centroids has used up (selected here, after the update that moved them)
         const bool keeps_bounds = bounds && t >= kFullPasses && !last;
@@ -743,7 +769,34 @@ cat_status tile_lloyd(const void* lq, cat_dtype dt, int64_t N, int64_t D, int32_
         // the memory-side cache when the next pass starts
         p.reverse = listed ? 0 : (t & 1);
         p.skip_when_zero = (skipped && t > kFullPasses && !last) ? lw.ctrl + ((t - 1) & 1) : nullptr;
-        if (keeps_bounds)
+        if (split) {
+            // first launch: clusters 0 .. 127, no bookkeeping, leaves (best score, nearest centroid) per row
+            const int32_t K0 = kSplitTiles * 16;
+            TileParams a = p;
+            a.K = K0;
+            a.k_base = 0;
+            a.k_hist = K;
+            a.norm_stride = K;
+            a.carry_out = lw.carry;
+            a.cmax_io = lw.carry_cmax;
+            a.counts = nullptr;
+            a.inertia = nullptr;
+            a.rep = nullptr;
+            a.list = nullptr;
+            a.delta_mode = 0;
+            CAT_T(dt == CAT_BF16 ? launch_split_bf16(a, c, st) : launch_split_f32(a, c, st));
+            // second launch: the other clusters beside that pair, and the bookkeeping of the pass
+            TileParams b = p;
+            b.K = K - K0;
+            b.k_base = K0;
+            b.k_hist = K;
+            b.norm_stride = K;
+            b.packA = ws.packA + (size_t)c.nchunks * 4 * kSplitTiles * c.P * 512;
+            b.cnorm = ws.cnorm + K0;
+            b.carry_in = lw.carry;
+            b.cmax_io = lw.carry_cmax;
+            CAT_T(dt == CAT_BF16 ? launch_split_bf16(b, c, st) : launch_split_f32(b, c, st));
+        } else if (keeps_bounds)
             CAT_T(dt == CAT_BF16 ? launch_bounds_bf16(p, c, st) : launch_bounds_f32(p, c, st));
         else
             CAT_T(launch_tile(p, c, dt, st));

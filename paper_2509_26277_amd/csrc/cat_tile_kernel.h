@@ -84,6 +84,15 @@ struct TileParams {
     const int32_t* rows;       // nullable: listed rows
     const uint32_t* n_rows;    // their number
     int32_t* evaluated_slot;   // nullable: receives the number of rows this pass evaluates
+    // More clusters than one launch ranks with the two-part operand (SPLIT instantiations only): the clusters are
+    // split over two launches.  This launch ranks the K clusters k_base .. k_base + K - 1 (packA, cnorm point at its
+    // share).  The first launch (carry_out given) only leaves, per row, the best score of its share and the exact
+    // nearest centroid of its share; the second (carry_in given) ranks that pair as one more cluster beside its own
+    // and does the bookkeeping of the pass.  Tables per cluster (counts, first rows) span k_hist clusters.
+    int32_t k_base, k_hist, norm_stride;
+    const float2* carry_in;
+    float2* carry_out;
+    float* cmax_io;  // the first launch leaves the largest centroid norm of its share, the second takes the larger of the two
 };
 
 // Which lane group g (0..3) and which of its 8 operand elements j hold channel r (0..31) of a
@@ -175,6 +184,7 @@ struct ChunkRegs {
     int prev;     // previous assignment of row n (assignment passes only)
     u32x4 prevv;  // several sets: previous assignments of row n in the sets 4 g .. 4 g + 3
     int row;      // listed rows: the number of row n
+    float2 carry; // split clusters: (best score, its cluster as int bits) of row n in the clusters ranked before
 };
 
 // Rows past N repeat the last row and channel groups past D read the start of the row (valid
@@ -185,7 +195,7 @@ struct ChunkRegs {
 // tile's finishing code it would have to be waited for there, and since loads return in order
 // that wait would also drain the chunks requested ahead.
 // LISTED: the tile's rows are not consecutive; lrow is the number of the row this lane loads (already clamped).
-template <bool BF16, int PREV, bool LISTED = false>  // PREV: 0 none, 1 the row's previous assignment, 2 its previous assignments in all sets
+template <bool BF16, int PREV, bool LISTED = false>  // PREV: 0 none, 1 the row's previous assignment, 2 its previous assignments in all sets, 3 as 1 plus the carried pair of a split ranking
 __device__ __forceinline__ void load_chunk(ChunkRegs<BF16>& r, const TileParams& p, int tile, int chunk, int lane, int lrow = 0) {
     const int n = lane & 15, g = lane >> 4;
     int64_t row;
@@ -198,7 +208,8 @@ __device__ __forceinline__ void load_chunk(ChunkRegs<BF16>& r, const TileParams&
         row = row0 + (n < nv ? n : nv - 1);
     }
     const int ch = chunk * kChunk + 8 * g;
-    if (PREV == 1) r.prev = p.assign[row];
+    if (PREV == 1 || PREV == 3) r.prev = p.assign[row];
+    if (PREV == 3 && p.carry_in) r.carry = p.carry_in[row];
     if (PREV == 2) r.prevv = *(const u32x4*)(p.assign + row * 16 + 4 * g);
     if (BF16) {
         const bf16_t* x = (const bf16_t*)p.lq + row * p.D;
@@ -285,7 +296,8 @@ template <int KT, bool BF16>
 __device__ __forceinline__ void rank_rows(const TileParams& p, const f32x4 (&acc)[KT], const float* s_cnorm,
                                           float xn2, float cmax, int64_t myrow, bool valid, int lane, int& idx, float& dmin,
                                           int t0 = 0, int t1 = KT, float* first = nullptr, float* second = nullptr,
-                                          bool* reranked = nullptr, float* bound = nullptr) {
+                                          bool* reranked = nullptr, float* bound = nullptr, int k_base = 0,
+                                          bool has_carry = false, float carry_s = 0.f, int carry_i = 0) {
     const int n = lane & 15, q = lane >> 4;
     float b1 = __builtin_inff(), b2 = __builtin_inff();
     int i1 = 16 * t0;
@@ -314,6 +326,18 @@ __device__ __forceinline__ void rank_rows(const TileParams& p, const f32x4 (&acc
         b1 = take ? ob1 : b1;
         i1 = take ? oi1 : i1;
         b2 = fminf(fminf(b2, ob2), loser);
+    }
+    i1 += k_base;
+    if (has_carry) {
+        // the clusters ranked by the launch before count as one more cluster: its score is the best score there, its
+        // index the exact nearest centroid there (lower than every index here, so it wins an equal score)
+        if (carry_s <= b1) {
+            b2 = b1;
+            b1 = carry_s;
+            i1 = carry_i;
+        } else if (carry_s < b2) {
+            b2 = carry_s;
+        }
     }
     const float T = p.tau * sqrtf(xn2) * cmax + p.tau2 * cmax * cmax;
     const bool flag = valid && !(b2 - b1 > T);
@@ -359,6 +383,11 @@ __device__ __forceinline__ void rank_rows(const TileParams& p, const f32x4 (&acc
             }
             cnt = 0;
         };
+        if (has_carry && readlane_f(carry_s, r) <= thr) {
+            const int ka = __builtin_amdgcn_readlane(carry_i, r);
+            if (lane == cnt) cand = ka;
+            ++cnt;
+        }
 #pragma unroll
         for (int t = 0; t < KT; t++) {
             if (t < t0 || t >= t1) continue;
@@ -371,7 +400,7 @@ __device__ __forceinline__ void rank_rows(const TileParams& p, const f32x4 (&acc
                     m &= m - 1;
                     const int k = 16 * t + 4 * (l >> 4) + i;
                     if (k < p.K) {
-                        if (lane == cnt) cand = k;
+                        if (lane == cnt) cand = k + k_base;
                         if (++cnt == kWave) measure();
                     }
                 }
@@ -389,10 +418,11 @@ __device__ __forceinline__ void rank_rows(const TileParams& p, const f32x4 (&acc
 // Per-tile finishing work of the streaming modes: rank, write, book-keep; resets acc / nrm.
 // BOUNDS: the pass also leaves the row's distance bound (TileParams::expire); with listed rows (row_in >= 0 is the
 // number of row n, n_listed their count) the tile is 16 entries of the list instead of 16 consecutive rows.
-template <int KT, bool BF16, int MODE, bool BOUNDS = false>
+// SPLIT: the clusters of the pass are ranked by two launches (TileParams::carry_in / carry_out).
+template <int KT, bool BF16, int MODE, bool BOUNDS = false, bool SPLIT = false>
 __device__ __forceinline__ void finish_tile(const TileParams& p, unsigned char* smem, f32x4 (&acc)[KT], float& nrm,
                                             int tile, int lane, float cmax, double& in_acc, int prev_in, int row_in = -1,
-                                            uint32_t n_listed = 0, double gnow = 0.0) {
+                                            uint32_t n_listed = 0, double gnow = 0.0, float2 carry = float2{0.f, 0.f}) {
     const int n = lane & 15, q = lane >> 4;
     const bool listed = BOUNDS && p.rows != nullptr;
     const int64_t row0 = listed ? 0 : (int64_t)(p.reverse ? (int)p.ntiles - 1 - tile : tile) * kRows;
@@ -405,12 +435,20 @@ __device__ __forceinline__ void finish_tile(const TileParams& p, unsigned char* 
     int idx;
     float dmin, first = 0.f, second = 0.f, bound = 0.f;
     bool reranked = false;
-    rank_rows<KT, BF16>(p, acc, s_cnorm, xn2, cmax, myrow, valid, lane, idx, dmin, 0, KT, BOUNDS ? &first : nullptr,
-                        BOUNDS ? &second : nullptr, BOUNDS ? &reranked : nullptr, BOUNDS ? &bound : nullptr);
+    if (SPLIT)
+        rank_rows<KT, BF16>(p, acc, s_cnorm, xn2, cmax, myrow, valid, lane, idx, dmin, 0, KT, &first, nullptr, nullptr, nullptr,
+                            p.k_base, p.carry_in != nullptr, carry.x, __float_as_int(carry.y));
+    else
+        rank_rows<KT, BF16>(p, acc, s_cnorm, xn2, cmax, myrow, valid, lane, idx, dmin, 0, KT, BOUNDS ? &first : nullptr,
+                            BOUNDS ? &second : nullptr, BOUNDS ? &reranked : nullptr, BOUNDS ? &bound : nullptr);
 #pragma unroll
     for (int t = 0; t < KT; t++) acc[t] = (f32x4){0.f, 0.f, 0.f, 0.f};
     nrm = 0.f;
     const bool owner = q == 0 && valid;
+    if (SPLIT && p.carry_out) {  // the first of the two launches: hand the pair on, nothing else
+        if (owner) p.carry_out[myrow] = float2{first, __int_as_float(idx)};
+        return;
+    }
 
     if (MODE == MODE_APPLY) {
         // The affine map walks the 16 rows again, this time one row per instruction with the
@@ -605,12 +643,13 @@ __device__ __forceinline__ void finish_tile_multi(const TileParams& p, unsigned 
 
 // ---- the kernel ----------------------------------------------------------------------
 // VAR: 0 the plain pass, 1 several centroid sets side by side (finish_tile_multi), 2 a pass that keeps distance
-// bounds and may walk a list of rows instead of all of them (TileParams::expire, rows).
-enum { VAR_PLAIN = 0, VAR_MULTI = 1, VAR_BOUNDS = 2 };
+// bounds and may walk a list of rows instead of all of them (TileParams::expire, rows), 3 one of the two launches
+// that rank the halves of a large cluster set (TileParams::carry_in, carry_out).
+enum { VAR_PLAIN = 0, VAR_MULTI = 1, VAR_BOUNDS = 2, VAR_SPLIT = 3 };
 template <int KT, int PASSES, bool BF16, int MODE, bool CA, int VAR = VAR_PLAIN>
 __global__ __launch_bounds__(kMaxWaves * kWave) void k_tile(const TileParams p) {
     extern __shared__ __align__(16) unsigned char smem[];
-    constexpr bool MULTI = VAR == VAR_MULTI, BOUNDS = VAR == VAR_BOUNDS;
+    constexpr bool MULTI = VAR == VAR_MULTI, BOUNDS = VAR == VAR_BOUNDS, SPLIT = VAR == VAR_SPLIT;
     if (p.skip_when_zero && *p.skip_when_zero == 0u) return;  // uniform over the grid, before any barrier
     const bool listed = BOUNDS && p.rows != nullptr;
     const uint32_t n_listed = listed ? *p.n_rows : 0u;
@@ -653,7 +692,7 @@ __global__ __launch_bounds__(kMaxWaves * kWave) void k_tile(const TileParams p) 
         if (listed)                                                                        \
             load_chunk<BF16, 1, true>(buf, p, tl, cl, lane, lrow);                         \
         else                                                                               \
-            load_chunk<BF16, MODE == MODE_ASSIGN ? (MULTI ? 2 : 1) : 0>(buf, p, tl, cl, lane); \
+            load_chunk<BF16, MODE == MODE_ASSIGN ? (MULTI ? 2 : SPLIT ? 3 : 1) : 0>(buf, p, tl, cl, lane); \
         if (++cl == p.nchunks) {                                                           \
             cl = 0;                                                                        \
             tl += tstride;                                                                 \
@@ -683,17 +722,18 @@ __global__ __launch_bounds__(kMaxWaves * kWave) void k_tile(const TileParams p) 
         if ((int)threadIdx.x < p.K16) {
             if (p.norm_slices > 0) {
                 double nn = 0.0;
+                const size_t nstride = SPLIT ? (size_t)p.norm_stride : (size_t)p.K;
                 if ((int)threadIdx.x < p.K) {
-                    const double* np = p.norm_part + threadIdx.x;
+                    const double* np = p.norm_part + (SPLIT ? p.k_base : 0) + threadIdx.x;
                     int sl = 0;
                     for (; sl + 8 <= p.norm_slices; sl += 8) {  // eight loads in flight, added in slice order
                         double v[8];
 #pragma unroll
-                        for (int u = 0; u < 8; u++) v[u] = np[(size_t)(sl + u) * p.K];
+                        for (int u = 0; u < 8; u++) v[u] = np[(size_t)(sl + u) * nstride];
 #pragma unroll
                         for (int u = 0; u < 8; u++) nn += v[u];
                     }
-                    for (; sl < p.norm_slices; sl++) nn += np[(size_t)sl * p.K];
+                    for (; sl < p.norm_slices; sl++) nn += np[(size_t)sl * nstride];
                 }
                 cn_mine = (int)threadIdx.x < p.K ? (float)nn : kPadNorm;
             } else {
@@ -723,7 +763,7 @@ __global__ __launch_bounds__(kMaxWaves * kWave) void k_tile(const TileParams p) 
         }
         if ((int)threadIdx.x < p.K16) s_cnorm[threadIdx.x] = cn_mine;
         if (MULTI && threadIdx.x < 16) ((double*)(s_misc + 2) + kMaxWaves)[threadIdx.x] = 0.0;
-        for (int k = threadIdx.x; k < p.K; k += blockDim.x) {
+        for (int k = threadIdx.x; k < (SPLIT ? p.k_hist : p.K); k += blockDim.x) {
             s_hist[k] = 0;
             s_rep[k] = ~0ull;
         }
@@ -739,6 +779,11 @@ __global__ __launch_bounds__(kMaxWaves * kWave) void k_tile(const TileParams p) 
 #pragma unroll
         for (int o = 32; o > 0; o >>= 1) cm2 = fmaxf(cm2, __shfl_xor(cm2, o, kWave));
         cmax_out = sqrtf(cm2);
+        if (SPLIT) {
+            // the error bound of a comparison involves the norms of both shares
+            if (p.carry_in) cmax_out = fmaxf(cmax_out, *p.cmax_io);
+            if (p.carry_out && blockIdx.x == 0 && threadIdx.x == 0) *p.cmax_io = cmax_out;
+        }
     }
     const float cmax = cmax_out;
 
@@ -758,6 +803,8 @@ __global__ __launch_bounds__(kMaxWaves * kWave) void k_tile(const TileParams p) 
             finish_tile_multi<KT, BF16>(p, smem, acc, nrm, tc, lane, cmax, buf.prevv);                         \
         else if (BOUNDS)                                                                                       \
             finish_tile<KT, BF16, MODE, true>(p, smem, acc, nrm, tc, lane, cmax, in_acc, buf.prev, buf.row, n_listed, gnow); \
+        else if (SPLIT)                                                                                        \
+            finish_tile<KT, BF16, MODE, false, true>(p, smem, acc, nrm, tc, lane, cmax, in_acc, buf.prev, -1, 0, 0.0, buf.carry); \
         else                                                                                                   \
             finish_tile<KT, BF16, MODE>(p, smem, acc, nrm, tc, lane, cmax, in_acc, buf.prev);                  \
         cc = 0;                                                                                                \
@@ -802,6 +849,8 @@ __global__ __launch_bounds__(kMaxWaves * kWave) void k_tile(const TileParams p) 
                     finish_tile_multi<KT, BF16>(p, smem, acc, nrm, tc, lane, cmax, bufcur.prevv);             \
                 else if (BOUNDS)                                                                              \
                     finish_tile<KT, BF16, MODE, true>(p, smem, acc, nrm, tc, lane, cmax, in_acc, bufcur.prev, bufcur.row, n_listed, gnow); \
+                else if (SPLIT)                                                                               \
+                    finish_tile<KT, BF16, MODE, false, true>(p, smem, acc, nrm, tc, lane, cmax, in_acc, bufcur.prev, -1, 0, 0.0, bufcur.carry); \
                 else                                                                                          \
                     finish_tile<KT, BF16, MODE>(p, smem, acc, nrm, tc, lane, cmax, in_acc, bufcur.prev);      \
                 cc = 0;                                                                                       \
@@ -856,7 +905,7 @@ __global__ __launch_bounds__(kMaxWaves * kWave) void k_tile(const TileParams p) 
     in_acc = wave_sum(in_acc);
     if (lane == 0) s_in[wave] = in_acc;
     __syncthreads();
-    for (int k = threadIdx.x; k < p.K; k += blockDim.x) {
+    for (int k = threadIdx.x; k < (SPLIT ? p.k_hist : p.K); k += blockDim.x) {
         if (p.counts && s_hist[k]) atomicAdd(&p.counts[k], s_hist[k]);
         if (p.rep && s_rep[k] != ~0ull) atomicMin(&p.rep[k], s_rep[k]);
     }
@@ -958,6 +1007,14 @@ static inline cat_status launch_kt_bounds(const TileParams& p, const TileCfg& c,
     return launch_one<KT, 3, BF16, MODE_ASSIGN, false, VAR_BOUNDS>(p, c, st);
 }
 
+// one of the two launches over the halves of a large cluster set (8 cluster tiles each, two-part operand)
+template <bool BF16>
+static inline cat_status launch_split(const TileParams& p, const TileCfg& c, hipStream_t st) {
+    if (c.KT != 8 || c.P != 2) return set_error(CAT_ERR_UNSUPPORTED, "split ranking: 8 cluster tiles and the two-part operand only");
+    if (c.chunked) return launch_one<8, 3, BF16, MODE_ASSIGN, true, VAR_SPLIT>(p, c, st);
+    return launch_one<8, 3, BF16, MODE_ASSIGN, false, VAR_SPLIT>(p, c, st);
+}
+
 // one translation unit per (KT, dtype), for compile time: cat_tile_k<KT>_<dtype>.hip
 cat_status launch_kt1_f32(const TileParams& p, const TileCfg& c, hipStream_t st);
 cat_status launch_kt1_bf16(const TileParams& p, const TileCfg& c, hipStream_t st);
@@ -972,6 +1029,9 @@ cat_status launch_kt16_bf16(const TileParams& p, const TileCfg& c, hipStream_t s
 // the instantiations for several centroid sets: cat_tile_multi_<dtype>.hip
 cat_status launch_multi_f32(const TileParams& p, const TileCfg& c, hipStream_t st);
 cat_status launch_multi_bf16(const TileParams& p, const TileCfg& c, hipStream_t st);
+// the instantiations for the halves of a large cluster set: cat_tile_split.hip
+cat_status launch_split_f32(const TileParams& p, const TileCfg& c, hipStream_t st);
+cat_status launch_split_bf16(const TileParams& p, const TileCfg& c, hipStream_t st);
 // the instantiations that keep distance bounds: cat_tile_bounds_<dtype>.hip
 cat_status launch_bounds_f32(const TileParams& p, const TileCfg& c, hipStream_t st);
 cat_status launch_bounds_bf16(const TileParams& p, const TileCfg& c, hipStream_t st);
