@@ -314,15 +314,27 @@ __global__ __launch_bounds__(kSelThreads) void k_bound_select(const double* __re
     double pk = 0.0;
     if ((int)threadIdx.x < K) {
         double m2 = 0.0;
-        for (int sl = 0; sl < slices; sl++) m2 += move_part[(size_t)sl * K + threadIdx.x];
+        const double* mp = move_part + threadIdx.x;
+        int sl = 0;
+        for (; sl + 8 <= slices; sl += 8) {  // eight loads in flight, added in slice order
+            double v[8];
+#pragma unroll
+            for (int u = 0; u < 8; u++) v[u] = mp[(size_t)(sl + u) * K];
+#pragma unroll
+            for (int u = 0; u < 8; u++) m2 += v[u];
+        }
+        for (; sl < slices; sl++) m2 += mp[(size_t)sl * K];
         pk = sqrt(m2);
     }
     s_p[threadIdx.x] = pk;
     __syncthreads();
-    if (threadIdx.x == 0) {
+    if (threadIdx.x < kWave) {
+        // the two largest movements: every lane ranks its four entries, then the wave's largest and, with that one
+        // taken out at the lane that holds it, the largest of the rest
         double t1 = 0.0, t2 = 0.0;
-        for (int k = 0; k < K; k++) {
-            const double v = s_p[k];
+#pragma unroll
+        for (int j = 0; j < kSelThreads / kWave; j++) {
+            const double v = s_p[threadIdx.x + j * kWave];
             if (v > t1) {
                 t2 = t1;
                 t1 = v;
@@ -330,8 +342,18 @@ __global__ __launch_bounds__(kSelThreads) void k_bound_select(const double* __re
                 t2 = v;
             }
         }
-        s_g = *g_prev + (t1 + t2) * (1.0 + 1e-9);
-        if (blockIdx.x == 0) *g_now = s_g;
+        double w1 = t1;
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) w1 = fmax(w1, __shfl_xor(w1, o, kWave));
+        const unsigned long long holders = __ballot(t1 == w1);
+        const bool mine = lane == (int)__builtin_ctzll(holders);
+        double w2 = mine ? t2 : t1;
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) w2 = fmax(w2, __shfl_xor(w2, o, kWave));
+        if (threadIdx.x == 0) {
+            s_g = *g_prev + (w1 + w2) * (1.0 + 1e-9);
+            if (blockIdx.x == 0) *g_now = s_g;
+        }
     }
     __syncthreads();
     const double G = s_g;

@@ -425,9 +425,10 @@ __device__ __forceinline__ void finish_tile(const TileParams& p, unsigned char* 
                                             uint32_t n_listed = 0, double gnow = 0.0, float2 carry = float2{0.f, 0.f}) {
     const int n = lane & 15, q = lane >> 4;
     const bool listed = BOUNDS && p.rows != nullptr;
-    const int64_t row0 = listed ? 0 : (int64_t)(p.reverse ? (int)p.ntiles - 1 - tile : tile) * kRows;
-    const int64_t myrow = listed ? (int64_t)row_in : row0 + n;
-    const bool valid = listed ? (uint32_t)(tile * kRows + n) < n_listed : myrow < p.N;
+    const int64_t row0 = BOUNDS ? 0 : (int64_t)(p.reverse ? (int)p.ntiles - 1 - tile : tile) * kRows;
+    const int64_t myrow = BOUNDS ? (int64_t)row_in : row0 + n;  // (BOUNDS: the clamped row the lane loaded)
+    const bool valid = listed ? (uint32_t)(tile * kRows + n) < n_listed
+                              : (BOUNDS ? (int64_t)(p.reverse ? (int)p.ntiles - 1 - tile : tile) * kRows + n < p.N : myrow < p.N);
     const float* s_cnorm = (const float*)(smem + p.off_cnorm);
     float xn2 = nrm;
     xn2 += __shfl_xor(xn2, 16, kWave);
@@ -672,33 +673,39 @@ __global__ __launch_bounds__(kMaxWaves * kWave) void k_tile(const TileParams p) 
     int tl = tile0, cl = 0;  // load cursor
     float cmax_out;
     ChunkRegs<BF16> b0, b1, b2;
-    // listed rows: the number of the row this lane loads in the tile at the load cursor, and in the tile after it
-    // (requested a whole tile ahead: waiting for it where it is needed would drain the chunks in flight)
+    // BOUNDS: the number of the row this lane loads in the tile at the load cursor, and in the tile after it: an
+    // entry of the list (requested a whole tile ahead: waiting for it where it is needed would drain the chunks in
+    // flight) or, without a list, the tile's own rows.  Either way the chunk loads themselves sit in no branch.
     int lrow = 0, lrow_nx = 0;
-    auto listed_row = [&](int tile) -> int {
-        uint32_t e = (uint32_t)tile * kRows + (uint32_t)(lane & 15);
-        e = e < n_listed ? e : n_listed - 1u;  // n_listed > 0 here (the workgroup has a tile)
-        return p.rows[e];
+    auto tile_row = [&](int tile) -> int {
+        if (listed) {
+            uint32_t e = (uint32_t)tile * kRows + (uint32_t)(lane & 15);
+            e = e < n_listed ? e : n_listed - 1u;  // n_listed > 0 here (the workgroup has a tile)
+            return p.rows[e];
+        }
+        const int64_t row0 = (int64_t)(p.reverse ? ntiles - 1 - tile : tile) * kRows;
+        const int nv = (p.N - row0) < kRows ? (int)(p.N - row0) : kRows;
+        return (int)row0 + ((lane & 15) < nv ? (lane & 15) : nv - 1);  // (N is below 2^31 in these passes)
     };
-    if (listed) {
-        lrow = listed_row(tile0 < ntiles ? tile0 : 0);
-        lrow_nx = listed_row(tile0 + tstride < ntiles ? tile0 + tstride : 0);
+    if (BOUNDS) {
+        lrow = tile_row(tile0 < ntiles ? tile0 : 0);
+        lrow_nx = tile_row(tile0 + tstride < ntiles ? tile0 + tstride : 0);
     }
     // A wave stops requesting rows once its cursor has passed its last tile.  (Requesting them
     // unconditionally, the last tile again, lets the compiler count on two chunks in flight at
     // every wait instead of draining to one; measured, that was 2-5 % slower, not faster.)
 #define CAT_ISSUE(buf)                                                                     \
     if (tl < ntiles) {                                                                     \
-        if (listed)                                                                        \
+        if (BOUNDS)                                                                        \
             load_chunk<BF16, 1, true>(buf, p, tl, cl, lane, lrow);                         \
         else                                                                               \
             load_chunk<BF16, MODE == MODE_ASSIGN ? (MULTI ? 2 : SPLIT ? 3 : 1) : 0>(buf, p, tl, cl, lane); \
         if (++cl == p.nchunks) {                                                           \
             cl = 0;                                                                        \
             tl += tstride;                                                                 \
-            if (listed) {                                                                  \
+            if (BOUNDS) {                                                                  \
                 lrow = lrow_nx;                                                            \
-                lrow_nx = listed_row(tl + tstride < ntiles ? tl + tstride : 0);            \
+                lrow_nx = tile_row(tl + tstride < ntiles ? tl + tstride : 0);              \
             }                                                                              \
         }                                                                                  \
     }
