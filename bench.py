@@ -54,17 +54,17 @@ HBM_PEAK_GBPS = 8000.0
 # one version of a kernel's source file: `traffic` is reported only while the hash of that file still matches, and the
 # line says that it comes from profiles/, not from this run.
 TRAFFIC_SOURCES = {
-    "k_tile": ("cat_tile_kernel.h", "c368204e0d3cb727b427eb617db98ee9711a7f8d82ac8120400e7d1b9dc3b32c"),
-    "k_infer": ("cat_infer_kernel.h", "3e0ddd9413898f44c15d9f8ddc35f7bc8085df908c46f96441599018b67b4c5f"),
+    "k_tile": ("cat_tile_kernel.h", "0f732d784bfed8b74f358ef562b497768225e66f55b3d667b2e2e619ce7805a6"),
+    "k_infer": ("cat_infer_kernel.h", "84d951b58971e51436fec82cd4288b211f4925980e492210e3468ba156edb414"),
 }
 TRAFFIC_COUNTERS = {
-    "cfg2": ("k_tile", (133759.4, 128011.7, 298.9, 256000.0)),
-    "cfg2_apply": ("k_infer", (129270.6, 128011.7, 266032.0, 256000.0)),
-    "cfg3": ("k_tile", (527767.7, 524299.7, 4721.1, 1048576.0)),
-    "cfg3_apply": ("k_infer", (524864.2, 524299.7, 1054739.0, 1048576.0)),
-    "cfg4": ("k_tile", (560461.8, 524299.7, 1191.4, 1048576.0)),
-    "cfg4_apply": ("k_tile", (1144058.5, 524299.7, 1049648.1, 1048576.0)),
-    "cfg5_apply": ("k_infer", (4197616.1, 4194318.0, 8413246.5, 8388608.0)),
+    "cfg2": ("k_tile", (133741.7, 128011.7, 298.7, 256000.0)),
+    "cfg2_apply": ("k_infer", (129264.8, 128011.7, 265353.6, 256000.0)),
+    "cfg3": ("k_tile", (527792.1, 524299.7, 4722.9, 1048576.0)),
+    "cfg3_apply": ("k_infer", (524882.1, 524299.7, 1054738.6, 1048576.0)),
+    "cfg4": ("k_tile", (560529.1, 524299.7, 1192.3, 1048576.0)),
+    "cfg4_apply": ("k_tile", (1140830.7, 524299.7, 1049646.2, 1048576.0)),
+    "cfg5_apply": ("k_infer", (4197553.8, 4194317.3, 8413228.9, 8388608.0)),
 }
 
 
@@ -174,6 +174,7 @@ def _run_workload(name, args, torch, np, cpu_budget_s, extras):
                     bytes_per_launch=alg_bytes, us_per_launch=1e3 * t_k, launches=len(ms))
         metric, unit = "cat_fit_lloyd_rows_per_s", "rows/s"
         value = N * iters / (ms_per_step * 1e-3)
+    if fit_kind and not args.hot_path_only:
         # the same fit with rows left out by distance bounds (same outputs; a separate figure, never the headline):
         # its average iteration against the same algorithmic bytes, and the share of the rows its passes evaluate
         ws_b = torch.empty(binding.load_library().cat_fit_bounds_workspace_bytes(N, D, K, iters, dtc), dtype=torch.uint8, device="cuda")
@@ -185,7 +186,7 @@ def _run_workload(name, args, torch, np, cpu_budget_s, extras):
                       lloyd_iter_frac_hbm_bounds=alg_bytes / t_iter_b / 1e6 / HBM_PEAK_GBPS,
                       bounds_rows_evaluated_frac=float(ev.mean()) / N)
         del ws_b
-    else:
+    if not fit_kind:
         apply_args = (cent, gamma, beta)
         roof = None
         metric, unit = "cat_apply_GBps", "GB/s"
@@ -208,7 +209,7 @@ def _run_workload(name, args, torch, np, cpu_budget_s, extras):
     if roof is None:
         roof = apply_roof
     # low-precision deployment of the same transformation: bfloat16 parameters, bfloat16 corrected rows (fp32 rows only)
-    if dt == "f32":
+    if dt == "f32" and not args.hot_path_only:
         from paper_2509_26277_amd import cat_apply_lp, cat_params_to_bf16
         cq, gq, bq = (cat_params_to_bf16(t) for t in apply_args)
         out16 = torch.empty((N, D), dtype=torch.bfloat16, device="cuda")
@@ -355,6 +356,10 @@ def main():
     ap.add_argument("--workload", default="all", choices=["all", "cfg1", "cfg2", "cfg3", "cfg4", "cfg5"])
     ap.add_argument("--rows", type=int, default=None, help="override N (debugging; the result is then not the named workload)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
+    ap.add_argument("--hot-path-only", action="store_true",
+                    help="only cat_fit and cat_apply: none of the rows beside them (bound-based fit, low-precision inference, "
+                         "PCA, sweeps, seeding, grid of cluster counts); the profile commands use it so that every launch of a "
+                         "kernel in the trace belongs to the two calls")
     ap.add_argument("--no-seeding", action="store_true",
                     help="skip the timing of the D^2-weighted seeding (detail.kmeanspp_*; cfg2 only)")
     ap.add_argument("--alpha-grid", type=int, default=10,
@@ -365,6 +370,8 @@ def main():
                     help="also time the PCA front-end (fit, projection, labelled affine map) with this many "
                          "components; reported under detail.pca_*; 0 skips it (cfg2, or the workload named with --workload)")
     args = ap.parse_args()
+    if args.hot_path_only:
+        args.no_seeding, args.pca_dim, args.alpha_grid = True, 0, 0
     if args.gpus != 1:
         sys.exit("bench.py: this library is single-GPU; run with --gpus 1 (rows shard trivially: one all-reduce of K x D sums per iteration)")
 
