@@ -292,14 +292,15 @@ def _run_workload(name, args, torch, np, cpu_budget_s, extras):
         pad = lambda t: torch.cat([t, t[:, :1]], dim=1).contiguous()
         lq_o, cent_o, g_o, b_o = pad(lq), pad(r["centroids"]), pad(r["gamma"]), pad(r["beta"])
         out_o = torch.empty_like(lq_o)
-        t_as = _events(lambda: cat_assign(lq_o, cent_o), 5, torch)
-        t_ap = _events(lambda: cat_apply(lq_o, cent_o, g_o, b_o, out=out_o), 5, torch)
-        t_as0 = _events(lambda: cat_assign(lq, r["centroids"]), 5, torch)
+        ws_o = torch.empty(binding.cat_fit_workspace_bytes(N, D + 1, K, dtc), dtype=torch.uint8, device="cuda")
+        t_as = _events(lambda: cat_assign(lq_o, cent_o, workspace=ws_o), 5, torch)
+        t_ap = _events(lambda: cat_apply(lq_o, cent_o, g_o, b_o, out=out_o, workspace=ws_o), 5, torch)
+        t_as0 = _events(lambda: cat_assign(lq, r["centroids"], workspace=ws_fit), 5, torch)
         detail.update(stream_shape=f"N={N} D={D + 1} K={K}", stream_assign_us=1e3 * t_as,
                       stream_assign_GBps=N * (D + 1) * esize / t_as / 1e6, stream_apply_us=1e3 * t_ap,
                       stream_apply_GBps=(2 * N * (D + 1) * esize + 4 * N) / t_ap / 1e6,
                       aligned_assign_us=1e3 * t_as0)
-        del lq_o, out_o
+        del lq_o, out_o, ws_o
 
     # context: plain device copy of the same matrix
     t_copy = _events(lambda: out.copy_(lq), 5, torch)
