@@ -109,9 +109,12 @@ struct ApplyWs {
     float* g_eff;
     float* b_eff;
     TileWs tile;
+    void* split;      // more than 128 clusters ranked by two launches: what the first hands to the second (N pairs), and
+    int32_t* labels;  //   the labels the map that follows goes by (N); both only with N given and where that applies
     size_t bytes;
 };
-static ApplyWs carve_apply(void* base, int64_t D, int32_t K, cat_dtype dt) {
+// N = 0: without the scratch of the split ranking (cat_apply_static: its array has a fixed size)
+static ApplyWs carve_apply(void* base, int64_t D, int32_t K, cat_dtype dt, int64_t N = 0) {
     Carver c(base);
     ApplyWs w;
     size_t KD = (size_t)K * (size_t)D;
@@ -120,6 +123,13 @@ static ApplyWs carve_apply(void* base, int64_t D, int32_t K, cat_dtype dt) {
     size_t tb = tile_workspace_bytes(D, K, dt);
     w.tile = tile_carve(base ? (void*)(c.base + c.off) : nullptr, D, K, dt);
     c.off += align256(tb);
+    w.split = nullptr;
+    w.labels = nullptr;
+    const size_t sb = N > 0 ? tile_split_scratch_bytes(N, D, K, dt) : 0;
+    if (sb) {
+        w.split = c.take<char>(sb);
+        w.labels = c.take<int32_t>((size_t)N);
+    }
     w.bytes = c.off;
     return w;
 }
@@ -163,7 +173,7 @@ static cat_status check_ws(const char* fn, const void* ws, size_t have, size_t n
 // device outputs, initialised here.
 static cat_status step_assign(const void* lq, cat_dtype dt, int64_t N, int64_t D, int32_t K, const float* cent,
                               int32_t* assign, int32_t* counts, double* inertia, unsigned long long* rep,
-                              const TileWs& tw, hipStream_t st) {
+                              const TileWs& tw, hipStream_t st, void* split_scratch = nullptr) {
     if (counts) CAT_TRY(launch_fill_zero(counts, (size_t)K * sizeof(int32_t), st));
     if (inertia) CAT_TRY(launch_fill_zero(inertia, sizeof(double), st));
     if (rep) CAT_TRY(launch_fill_u64(rep, K, ~0ull, st));
@@ -172,8 +182,11 @@ static cat_status step_assign(const void* lq, cat_dtype dt, int64_t N, int64_t D
     if (path == CAT_PATH_TILE && !tile_ok)
         return set_error(CAT_ERR_UNSUPPORTED, "tile path forced but D=%lld K=%d dt=%d does not fit it", (long long)D,
                          (int)K, (int)dt);
-    if (tile_ok && path != CAT_PATH_STREAM)
+    if (tile_ok && path != CAT_PATH_STREAM) {
+        if (split_scratch && tile_split_scratch_bytes(N, D, K, dt))  // more than 128 clusters: two launches of 8 tiles
+            return tile_assign_split(lq, dt, N, D, K, cent, assign, counts, inertia, rep, tw, split_scratch, st);
         return tile_assign(lq, dt, N, D, K, cent, assign, counts, inertia, rep, nullptr, nullptr, nullptr, tw, st);
+    }
     // shapes outside the matrix-core kernels: the LDS streaming kernel; the direct-form kernel only when asked for
     if (path != CAT_PATH_STREAM)
         return launch_assign_lds(lq, dt, N, D, K, cent, assign, counts, inertia, rep, nullptr, nullptr, nullptr, st);
@@ -304,7 +317,7 @@ size_t cat_fit_workspace_bytes(int64_t N, int64_t D, int32_t K, cat_dtype dt) {
 
 size_t cat_apply_workspace_bytes(int64_t N, int64_t D, int32_t K, cat_dtype dt) {
     if (!shape_ok(N, D, K, dt)) return 0;
-    return carve_apply(nullptr, D, K, dt).bytes;
+    return carve_apply(nullptr, D, K, dt, N).bytes;
 }
 
 cat_status cat_init_indices(int64_t N, int32_t K, uint64_t seed, int64_t* idx_out) {
@@ -339,7 +352,7 @@ cat_status cat_assign(const void* lq, int64_t N, int64_t D, int32_t K, cat_dtype
     FitWs w = carve_fit(workspace, N, D, K, dt);
     CAT_TRY(check_ws("cat_assign", workspace, workspace_bytes, w.bytes));
     hipStream_t st = (hipStream_t)hip_stream;
-    return step_assign(lq, dt, N, D, K, centroids, assignments, counts, inertia, nullptr, w.tile, st);
+    return step_assign(lq, dt, N, D, K, centroids, assignments, counts, inertia, nullptr, w.tile, st, w.lloyd.carry);
 }
 
 cat_status cat_update(const void* lq, const int32_t* assignments, int64_t N, int64_t D, int32_t K, cat_dtype dt,
@@ -744,7 +757,9 @@ static cat_status apply_impl(const char* who, const void* lq, int64_t N, int64_t
     CAT_TRY(check_ptr(who, "corrected", corrected, 16));
     if (corrected == lq) return set_error(CAT_ERR_INVALID_ARG, "%s: corrected may not alias lq", who);
     if (!std::isfinite(alpha)) return set_error(CAT_ERR_INVALID_ARG, "%s: alpha is not finite", who);
-    ApplyWs w = carve_apply(workspace, D, K, dt);
+    // (a workspace of the size without the scratch of the split ranking is accepted: cat_apply_static has no more)
+    ApplyWs w = carve_apply(workspace, D, K, dt, N);
+    if (w.split && workspace && workspace_bytes < w.bytes) w = carve_apply(workspace, D, K, dt);
     CAT_TRY(check_ws(who, workspace, workspace_bytes, w.bytes));
     const float* g = gamma;
     const float* b = beta;
@@ -767,6 +782,13 @@ static cat_status apply_impl(const char* who, const void* lq, int64_t N, int64_t
                          (long long)D, (int)K, (int)dt);
     if (rowtile_ok && path != CAT_PATH_STREAM && which != 1)
         return infer_apply(lq, dt, N, D, K, centroids, g, b, corrected, assignments, w.tile, st);
+    if (tile_ok && path != CAT_PATH_STREAM && w.split && which == 0) {
+        // more than 128 clusters: ranked by two launches of 8 cluster tiles, then mapped by the labels (the fused
+        // 16-tile kernel ranks with the one-part operand and re-ranks most rows: several times slower)
+        int32_t* labels = assignments ? assignments : w.labels;
+        CAT_TRY(tile_assign_split(lq, dt, N, D, K, centroids, labels, nullptr, nullptr, nullptr, w.tile, w.split, st));
+        return launch_affine_by_labels(lq, dt, labels, N, D, g, b, corrected, false, st);
+    }
     if (tile_ok && path != CAT_PATH_STREAM)
         return tile_assign(lq, dt, N, D, K, centroids, assignments, nullptr, nullptr, nullptr, g, b, corrected, w.tile,
                            st);
@@ -800,7 +822,7 @@ static ApplyLpWs carve_apply_lp(void* base, int64_t N, int64_t D, int32_t K, cat
     w.g = c.take<float>(KD);
     w.b = c.take<float>(KD);
     w.labels = c.take<int32_t>((size_t)N);
-    w.apply_bytes = carve_apply(nullptr, D, K, dt).bytes;
+    w.apply_bytes = carve_apply(nullptr, D, K, dt, N).bytes;
     w.apply = c.take<char>(w.apply_bytes);
     w.bytes = c.off;
     return w;
@@ -842,13 +864,13 @@ cat_status cat_apply_lp(const void* lq, int64_t N, int64_t D, int32_t K, cat_dty
         return apply_impl(who, lq, N, D, K, dt, w.cent, w.g, w.b, 1.0f, corrected, assignments, w.apply, w.apply_bytes, st);
     // fp32 rows, bfloat16 out: the row-tile kernel writes the narrower rows itself; shapes it has no instance for
     // assign first and map by the labels afterwards (a second read of the rows)
-    ApplyWs aw = carve_apply(w.apply, D, K, dt);
+    ApplyWs aw = carve_apply(w.apply, D, K, dt, N);
     const int path = g_path.load();
     if (infer_supported(N, D, K, dt) && path != CAT_PATH_STREAM && g_apply_kernel.load() != 1)
         return infer_apply(lq, dt, N, D, K, w.cent, w.g, w.b, corrected, assignments, aw.tile, st, true);
     int32_t* labels = assignments ? assignments : w.labels;
-    CAT_TRY(step_assign(lq, dt, N, D, K, w.cent, labels, nullptr, nullptr, nullptr, aw.tile, st));
-    return launch_affine_to_bf16((const float*)lq, labels, N, D, w.g, w.b, (uint16_t*)corrected, st);
+    CAT_TRY(step_assign(lq, dt, N, D, K, w.cent, labels, nullptr, nullptr, nullptr, aw.tile, st, aw.split));
+    return launch_affine_by_labels(lq, dt, labels, N, D, w.g, w.b, corrected, true, st);
 }
 
 // ---- cat_apply for callers that cannot allocate: the scratch memory is a device array of the library ----

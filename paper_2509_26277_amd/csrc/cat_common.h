@@ -134,12 +134,13 @@ cat_status launch_apply_pca_fused(const void* lq, int64_t N, int64_t D, int32_t 
 cat_status launch_keep_best(const double* cur, double* best, int32_t* state, int32_t run, double* finals, hipStream_t st);
 cat_status launch_copy_words_if(const int32_t* flag, const void* src, void* dst, int64_t nwords, hipStream_t st);
 // low-precision deployment (cat_lp.hip): fp32 -> bfloat16 (round to nearest even); stored parameters back to fp32 with
-// the blending coefficient folded into gamma / beta; fp32 rows with given labels -> bfloat16 corrected rows
+// the blending coefficient folded into gamma / beta; rows with given labels -> corrected rows (in the type of the rows, or
+// bfloat16 for fp32 rows)
 cat_status launch_to_bf16(const float* src, int64_t n, uint16_t* dst, hipStream_t st);
 cat_status launch_expand_params(const uint16_t* cent, const uint16_t* gamma, const uint16_t* beta, float alpha, int64_t n,
                                 float* c, float* g, float* b, hipStream_t st);
-cat_status launch_affine_to_bf16(const float* x, const int32_t* assign, int64_t N, int64_t D, const float* g, const float* b,
-                                 uint16_t* out, hipStream_t st);
+cat_status launch_affine_by_labels(const void* x, cat_dtype dt, const int32_t* assign, int64_t N, int64_t D, const float* g,
+                                   const float* b, void* out, bool out_bf16, hipStream_t st);
 // PCA scores (cat_pca.hip) with rows ldz >= p floats apart; the padding columns are written as zeros
 cat_status pca_project_ld(const void* lq, int64_t N, int64_t D, int32_t p, cat_dtype dt, const float* mean,
                           const float* components, float* z, int32_t ldz, hipStream_t st);

@@ -26,6 +26,13 @@ cat_status tile_assign(const void* lq, cat_dtype dt, int64_t N, int64_t D, int32
                        int32_t* assign, int32_t* counts, double* inertia, unsigned long long* rep,
                        const float* gamma, const float* beta, void* corrected, const TileWs& ws, hipStream_t st);
 
+// More than 128 clusters whose two-part operand does not fit LDS in one piece: the same assignment pass as two launches
+// over the halves of the clusters (assignment only: no inference).  tile_split_scratch_bytes is 0 where that does not apply.
+size_t tile_split_scratch_bytes(int64_t N, int64_t D, int32_t K, cat_dtype dt);
+cat_status tile_assign_split(const void* lq, cat_dtype dt, int64_t N, int64_t D, int32_t K, const float* cent, int32_t* assign,
+                             int32_t* counts, double* inertia, unsigned long long* rep, const TileWs& ws, void* scratch,
+                             hipStream_t st);
+
 // Extra device scratch of tile_lloyd: the list of rows that changed cluster in a pass (worst case
 // all N), the counters of the update kernel and the per-slice shares of the centroid norms.
 struct LloydWs {

@@ -513,10 +513,10 @@ LloydWs lloyd_carve(void* base, int64_t N, int64_t D, int32_t K) {
 
 // More than 128 clusters need 16 cluster tiles, whose two-part operand fits LDS only for short rows; otherwise the
 // clusters are ranked by two launches of 8 tiles each (k_tile<..., VAR_SPLIT>), the first handing its best on.
-static bool split_config(int64_t D, int32_t K, cat_dtype dt, TileCfg* out) {
+static bool split_config(int64_t D, int32_t K, cat_dtype dt, TileCfg* out, TileMode mode = TILE_LLOYD) {
     if (K <= kSplitTiles * 16 || K > 2 * kSplitTiles * 16) return false;
-    if (tile_config(TILE_LLOYD, D, K, dt, true).ok) return false;  // one launch ranks them all with two parts
-    TileCfg c = tile_config(TILE_LLOYD, D, kSplitTiles * 16, dt, true, K);
+    if (tile_config(mode, D, K, dt, true).ok) return false;  // one launch ranks them all with two parts
+    TileCfg c = tile_config(mode, D, kSplitTiles * 16, dt, true, K);
     if (!c.ok || c.KT != kSplitTiles) return false;
     if (out) *out = c;
     return true;
@@ -710,6 +710,67 @@ cat_status tile_assign(const void* lq, cat_dtype dt, int64_t N, int64_t D, int32
     return launch_tile(p, c, dt, st);
 }
 
+// The two launches of a pass whose clusters are split (p: the parameters of the pass as for one launch).
+static cat_status launch_split_pair(const TileParams& p, const TileCfg& c, cat_dtype dt, int32_t K, const TileWs& ws,
+                                    float2* carry, float* carry_cmax, hipStream_t st) {
+    // first launch: clusters 0 .. 127, no bookkeeping, leaves (best score, nearest centroid) per row
+    const int32_t K0 = kSplitTiles * 16;
+    TileParams a = p;
+    a.K = K0;
+    a.k_base = 0;
+    a.k_hist = K;
+    a.norm_stride = K;
+    a.carry_out = carry;
+    a.cmax_io = carry_cmax;
+    a.counts = nullptr;
+    a.inertia = nullptr;
+    a.rep = nullptr;
+    a.list = nullptr;
+    a.delta_mode = 0;
+    cat_status s = dt == CAT_BF16 ? launch_split_bf16(a, c, st) : launch_split_f32(a, c, st);
+    if (s != CAT_OK) return s;
+    // second launch: the other clusters beside that pair, and the bookkeeping of the pass
+    TileParams b = p;
+    b.K = K - K0;
+    b.k_base = K0;
+    b.k_hist = K;
+    b.norm_stride = K;
+    b.packA = ws.packA + (size_t)c.nchunks * 4 * kSplitTiles * c.P * 512;
+    b.cnorm = ws.cnorm + K0;
+    b.carry_in = carry;
+    b.cmax_io = carry_cmax;
+    return dt == CAT_BF16 ? launch_split_bf16(b, c, st) : launch_split_f32(b, c, st);
+}
+
+size_t tile_split_scratch_bytes(int64_t N, int64_t D, int32_t K, cat_dtype dt) {
+    return split_config(D, K, dt, nullptr, TILE_ASSIGN) ? a256((size_t)N * 8) + 256 : 0;
+}
+
+// tile_assign (assignment only) for more than 128 clusters, ranked by two launches; scratch: tile_split_scratch_bytes.
+cat_status tile_assign_split(const void* lq, cat_dtype dt, int64_t N, int64_t D, int32_t K, const float* cent, int32_t* assign,
+                             int32_t* counts, double* inertia, unsigned long long* rep, const TileWs& ws, void* scratch,
+                             hipStream_t st) {
+    TileCfg c;
+    if (!scratch || !split_config(D, K, dt, &c, TILE_ASSIGN))
+        return set_error(CAT_ERR_UNSUPPORTED, "split ranking does not apply to D=%lld K=%d", (long long)D, (int)K);
+    const float* cw = cent;
+    cat_status s = CAT_OK;
+    if (((uintptr_t)cent & 15u) != 0) {
+        s = launch_copy_words(cent, ws.cent, (int64_t)K * D, st);
+        if (s != CAT_OK) return s;
+        cw = ws.cent;
+    }
+    s = launch_prep(dt, const_cast<float*>(cw), nullptr, nullptr, nullptr, nullptr, D, K, c, ws, nullptr, nullptr, st, 1, 2);
+    if (s != CAT_OK) return s;
+    TileParams p = base_params(lq, N, D, K, c, ws, dt);
+    p.cent = cw;
+    p.assign = assign;
+    p.counts = counts;
+    p.inertia = inertia;
+    p.rep = rep;
+    return launch_split_pair(p, c, dt, K, ws, (float2*)scratch, (float*)((char*)scratch + a256((size_t)N * 8)), st);
+}
+
 cat_status tile_lloyd(const void* lq, cat_dtype dt, int64_t N, int64_t D, int32_t K, int32_t iters,
                       float* cent_io, double* sums, int32_t* assign, int32_t* counts, double* inertia,
                       unsigned long long* rep, int32_t* skipped, const TileWs& ws, const LloydWs& lw, hipStream_t st,
@@ -792,32 +853,7 @@ cat_status tile_lloyd(const void* lq, cat_dtype dt, int64_t N, int64_t D, int32_
         p.reverse = listed ? 0 : (t & 1);
         p.skip_when_zero = (skipped && t > kFullPasses && !last) ? lw.ctrl + ((t - 1) & 1) : nullptr;
         if (split) {
-            // first launch: clusters 0 .. 127, no bookkeeping, leaves (best score, nearest centroid) per row
-            const int32_t K0 = kSplitTiles * 16;
-            TileParams a = p;
-            a.K = K0;
-            a.k_base = 0;
-            a.k_hist = K;
-            a.norm_stride = K;
-            a.carry_out = lw.carry;
-            a.cmax_io = lw.carry_cmax;
-            a.counts = nullptr;
-            a.inertia = nullptr;
-            a.rep = nullptr;
-            a.list = nullptr;
-            a.delta_mode = 0;
-            CAT_T(dt == CAT_BF16 ? launch_split_bf16(a, c, st) : launch_split_f32(a, c, st));
-            // second launch: the other clusters beside that pair, and the bookkeeping of the pass
-            TileParams b = p;
-            b.K = K - K0;
-            b.k_base = K0;
-            b.k_hist = K;
-            b.norm_stride = K;
-            b.packA = ws.packA + (size_t)c.nchunks * 4 * kSplitTiles * c.P * 512;
-            b.cnorm = ws.cnorm + K0;
-            b.carry_in = lw.carry;
-            b.cmax_io = lw.carry_cmax;
-            CAT_T(dt == CAT_BF16 ? launch_split_bf16(b, c, st) : launch_split_f32(b, c, st));
+            CAT_T(launch_split_pair(p, c, dt, K, ws, lw.carry, lw.carry_cmax, st));
         } else if (keeps_bounds)
             CAT_T(dt == CAT_BF16 ? launch_bounds_bf16(p, c, st) : launch_bounds_f32(p, c, st));
         else

@@ -7,7 +7,7 @@ import pytest
 import torch
 
 import oracle
-from paper_2509_26277_amd import cat_apply, cat_fit, workloads
+from paper_2509_26277_amd import binding, cat_apply, cat_apply_lp, cat_assign, cat_fit, cat_params_to_bf16, workloads
 
 from parity_util import CENTROID_RTOL, RTOL, check_assignments_lazy, check_values, dev_matrix, host_matrix
 
@@ -81,3 +81,45 @@ def test_logit_workload_rows_with_256_clusters():
     exempt = check_assignments_lazy(a, o["assignments"], x, o["centroids"], "assignments")
     check_values(host_matrix(r["centroids"]), o["centroids"], CENTROID_RTOL if exempt == 0 else RTOL["f32"], "centroids")
     np.testing.assert_allclose(r["inertia"].cpu().numpy(), o["inertia"], rtol=1e-4)
+
+
+@pytest.mark.parametrize("N,D,K,dt", [(5000, 260, 200, "f32"), (4099, 1000, 256, "f32"), (3000, 2048, 150, "bf16"), (3000, 64, 200, "f32")])
+def test_assign_and_apply_match_the_oracle(N, D, K, dt):
+    """cat_assign and cat_apply with more than 128 clusters (two launches, then the map by the labels)."""
+    x, _ = _mixture(N + K, N, D, 40, dt, 1.0)
+    rng = np.random.default_rng(K)
+    cent = x[rng.choice(N, K, replace=False)].astype(np.float32)
+    cent[K - 1] = cent[3]          # an exact tie across the two halves: the lower index must win
+    gamma = rng.uniform(0.7, 1.3, (K, D)).astype(np.float32)
+    beta = (0.3 * rng.standard_normal((K, D))).astype(np.float32)
+    xd = dev_matrix(x, dt)
+    f = lambda a: torch.from_numpy(a).cuda()
+    o_a, d1, d2 = oracle.assign(x, cent.astype(np.float64), want_distances=True)
+    a, counts, inertia = cat_assign(xd, f(cent))
+    check_assignments_lazy(a.cpu().numpy(), o_a, x, cent.astype(np.float64), "cat_assign")
+    assert counts.cpu().numpy().tolist() == np.bincount(a.cpu().numpy(), minlength=K).tolist()
+    np.testing.assert_allclose(float(inertia), d1.sum(), rtol=1e-4)
+    assert not (a.cpu().numpy() == K - 1).any()
+    for alpha in (1.0, 0.6):
+        out, a2 = cat_apply(xd, f(cent), f(gamma), f(beta), alpha=alpha)
+        o_out, o_a2 = oracle.apply(x, cent, gamma, beta, alpha)
+        a2 = a2.cpu().numpy()
+        check_assignments_lazy(a2, o_a2, x, cent.astype(np.float64), "cat_apply")
+        same = a2 == o_a2
+        check_values(host_matrix(out)[same], o_out[same], RTOL[dt], "corrected")
+    # without the assignments output, and on the fused 16-tile kernel for comparison
+    out_b, _ = cat_apply(xd, f(cent), f(gamma), f(beta), alpha=0.6, want_assignments=False)
+    assert torch.equal(out_b, out)
+    binding.debug_apply_kernel(1)
+    try:
+        out_t, a_t = cat_apply(xd, f(cent), f(gamma), f(beta), alpha=0.6)
+    finally:
+        binding.debug_apply_kernel(0)
+    check_values(host_matrix(out_t)[a_t.cpu().numpy() == a2], host_matrix(out)[a_t.cpu().numpy() == a2], RTOL[dt], "fused kernel")
+    if dt == "f32":
+        cq, gq, bq = cat_params_to_bf16(f(cent)), cat_params_to_bf16(f(gamma)), cat_params_to_bf16(f(beta))
+        out16, a16 = cat_apply_lp(xd, cq, gq, bq, alpha=0.6, bf16_out=True)
+        o16, oa16, (ocq, _, _) = oracle.apply_lp(x, cent, gamma, beta, alpha=0.6)
+        a16 = a16.cpu().numpy()
+        check_assignments_lazy(a16, oa16, x, ocq, "cat_apply_lp")
+        check_values(host_matrix(out16)[a16 == oa16], o16[a16 == oa16], RTOL["bf16"], "corrected, low precision")
