@@ -366,8 +366,8 @@ cat_status cat_apply_lp(const void *lq, int64_t N, int64_t D, int32_t K, cat_dty
  * a list of cluster counts on the same calibration rows.  cat_fit_multi_k returns, for every K in the list, what
  * cat_fit(lq, fp, N, D, K, iters, seed, dt, NULL, ...) returns: the fits are independent and every one starts from
  * the rows cat_init_indices(N, K, seed) picks.  Where the shape fits the matrix-core kernels, consecutive entries of
- * the list whose clusters fill at most 128 slots together (each K rounded up to a multiple of 16) run their Lloyd
- * loops side by side, so that one read of lq per pass serves all of them; other entries run one after the other.
+ * the list whose clusters fill at most 64 slots together (128 for rows of at most 1 KB; each K rounded up to a multiple
+ * of 16) run their Lloyd loops side by side, so that one read of lq per pass serves all of them; other entries run one after the other.
  *
  * Ks           in, HOST array of nK cluster counts, 1 <= nK <= CAT_MAX_MULTI_K, each 1 <= K <= min(N, CAT_MAX_K)
  * centroids, gamma, beta
@@ -377,7 +377,8 @@ cat_status cat_apply_lp(const void *lq, int64_t N, int64_t D, int32_t K, cat_dty
  * inertia      out, device, nK x (iters + 1) doubles, nullable
  * workspace    cat_fit_multi_k_workspace_bytes(N, D, Ks, nK, iters, dt) bytes (0 for invalid arguments)
  * Other arguments and errors: as cat_fit.  Enqueues on the stream; no allocation, no synchronisation.
- * cat_debug_multi_group_tiles(t), t in {1, 2, 4, 8}: at most t 16-cluster tiles per group (default 8; 1 runs
+ * cat_debug_multi_group_tiles(t), t in {0, 1, 2, 4, 8}: at most t 16-cluster tiles per group (0, the default: 4, or 8 for
+ * rows of at most 1 KB; 1 runs
  * every entry on its own); process-wide, for measurements and tests; results do not depend on it. */
 #define CAT_MAX_MULTI_K 64
 size_t cat_fit_multi_k_workspace_bytes(int64_t N, int64_t D, const int32_t *Ks, int32_t nK, int32_t iters, cat_dtype dt);

@@ -556,10 +556,12 @@ cat_status cat_fit_restarts(const void* lq, const void* fp, int64_t N, int64_t D
 // Consecutive entries of Ks whose 16-cluster tiles fit one launch of the tile kernel together form a group and run
 // their Lloyd loops side by side (tile_lloyd_multi); an entry the tile kernels cannot take, or one left alone, runs
 // the ordinary loop.  The plan depends on the arguments only, so the workspace query and the call agree.
-// Tiles per group.  Measured on the paper's grid of eleven counts (1 .. 256): groups pay where a pass is bound by the
-// read of the rows (counts up to about 32: 0.6 of the time of separate fits); from 8 tiles on a pass is bound by the
-// contraction and sharing the read gains nothing, and the 16-tile instances of the kernel spill registers.
-static std::atomic<int> g_multi_tiles{8};  // cat_debug_multi_group_tiles
+// Tiles per group; 0: chosen from the shape.  Measured on the paper's grid of eleven counts (1 .. 256): groups pay where a
+// pass is bound by the read of the rows (counts up to about 32: 0.6 of the time of separate fits).  Rows of more than
+// 1 KB make a pass of more than 4 cluster tiles contraction-bound, where sharing the read gains nothing and the larger
+// kernel costs (65536 x 1000: the counts 48 and 64 together 6.7 ms, apart 5.6 ms), so groups stop at 4 tiles there and
+// at 8 for shorter rows (65536 x 52: the grid in 12.1 ms with 8, 12.9 ms with 4); 16-tile instances spill registers.
+static std::atomic<int> g_multi_tiles{0};  // cat_debug_multi_group_tiles
 
 struct MultiGroup {
     int first = 0, count = 0;
@@ -568,6 +570,7 @@ struct MultiGroup {
 static std::vector<MultiGroup> plan_multi(int64_t N, int64_t D, const int32_t* Ks, int32_t nK, cat_dtype dt) {
     std::vector<MultiGroup> groups;
     int cap = g_multi_tiles.load();
+    if (cap == 0) cap = D * (dt == CAT_BF16 ? 2 : 4) <= 1024 ? 8 : 4;
     const bool tiles_allowed = g_path.load() != CAT_PATH_STREAM;
     while (cap > 1 && !tile_multi_supports(N, D, 16 * cap, 1, dt)) cap /= 2;
     if (!tiles_allowed || !tile_multi_supports(N, D, 16 * cap, 1, dt)) cap = 0;
@@ -664,8 +667,8 @@ static void multi_extent(const std::vector<MultiGroup>& groups, const int32_t* K
 }
 
 cat_status cat_debug_multi_group_tiles(int tiles) {
-    if (tiles != 1 && tiles != 2 && tiles != 4 && tiles != 8)
-        return set_error(CAT_ERR_INVALID_ARG, "cat_debug_multi_group_tiles: %d is not 1, 2, 4 or 8", tiles);
+    if (tiles != 0 && tiles != 1 && tiles != 2 && tiles != 4 && tiles != 8)
+        return set_error(CAT_ERR_INVALID_ARG, "cat_debug_multi_group_tiles: %d is not 0, 1, 2, 4 or 8", tiles);
     g_multi_tiles.store(tiles);
     return CAT_OK;
 }

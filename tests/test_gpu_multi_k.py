@@ -22,7 +22,7 @@ PAPER_GRID = [1, 8, 16, 24, 32, 48, 64, 96, 128, 192, 256]  # the cluster counts
 @pytest.fixture(autouse=True)
 def _default_groups_after():
     yield
-    debug_multi_group_tiles(8)
+    debug_multi_group_tiles(0)
 
 
 def _mixture(seed, N, D, C, dt):
@@ -87,7 +87,7 @@ def test_paper_grid_small_rows():
         _same_as_oracle(r, o, x, "f32", f"K={K}")
 
 
-@pytest.mark.parametrize("tiles", [1, 2, 4])
+@pytest.mark.parametrize("tiles", [1, 2, 8])
 def test_results_do_not_depend_on_the_grouping(tiles):
     N, D, Ks, iters = 3000, 128, [3, 20, 16, 50, 9, 64], 6
     x, y = _mixture(5, N, D, 8, "f32")
