@@ -69,7 +69,7 @@ InferCfg infer_config(int64_t D, int32_t K, cat_dtype dt) {
         c.xstride = (uint32_t)(in.SPW * in.SC * 64 + 16);  // 32 channels of bf16 per step; + 16 bytes: rows 16 apart in banks
         c.xpart = (uint32_t)rows * c.xstride;
         c.off_s = up16((size_t)xp * c.xpart);
-        c.off_cnorm = up16(c.off_s + (size_t)rows * in.SC * KT * 16 * 4);
+        c.off_cnorm = up16(c.off_s + (size_t)rows * infer_dots_stride(in.SC * KT * 16) * 4);
         c.lds = c.off_cnorm + (size_t)KT * 16 * 4;
         if (c.lds > 160 * 1024) continue;
         c.ok = true;

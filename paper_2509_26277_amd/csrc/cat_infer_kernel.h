@@ -31,6 +31,8 @@ typedef __attribute__((ext_vector_type(4))) uint32_t iu32x4;
 typedef __attribute__((ext_vector_type(2))) uint32_t iu32x2;
 
 constexpr int kInferWaves = 8;
+// row stride (floats) of the partial dot products in LDS for a row of n floats: n rounded up to 16 mod 64
+constexpr int infer_dots_stride(int n) { return n + (16 - n % 64 + 64) % 64; }
 
 struct InferParams {
     const void* lq;
@@ -109,6 +111,12 @@ __global__ __launch_bounds__(kInferWaves * kWave) void k_infer(const InferParams
     constexpr int EPL = BF16 ? 8 : 4;              // channels per 16-byte vector
     constexpr int XP = (!BF16 && P == 2) ? 2 : 1;  // bf16 parts of a row in LDS
     constexpr int NSLOT = (K16 + kWave - 1) / kWave;  // clusters per lane in the ranking
+    // Floats between the rows of the partial dot products: SC * K16 plus a skew that leaves the row stride at 16 mod 64.
+    // Lane (n, g) writes four floats at 4 g of row n: with a stride that is a multiple of 64 floats all 16 rows would
+    // fall on the same 16 banks; at 16 mod 64 every bank is hit exactly four times, the least a 1 KB write can do
+    // (bank-conflict cycles per LDS instruction of the whole kernel 4.2 -> 3.1; the kernel's duration does not
+    // change, it is bound by the memory system).
+    constexpr int DS = infer_dots_stride(SC * K16);
     constexpr int DEPTH = VPR <= 2 ? 3 : 2;        // tiles requested ahead (a register buffer each)
     typedef typename std::conditional<BF16, bf16_t, float>::type T;
     typedef iu32x4 Rows[RPW][VPR];
@@ -117,7 +125,7 @@ __global__ __launch_bounds__(kInferWaves * kWave) void k_infer(const InferParams
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
     const int n = lane & 15, g = lane >> 4;
     const int ik = wave % SK, ic = wave / SK;
-    float* s_dots = (float*)(smem + p.off_s);       // [row][SC][K16]
+    float* s_dots = (float*)(smem + p.off_s);       // [row][SC][K16], rows DS floats apart
     float* s_cnorm = (float*)(smem + p.off_cnorm);
 
     // ---- prologue: zero the row tile (its padding channels stay zero for good), norms, operand share ----
@@ -237,7 +245,7 @@ __global__ __launch_bounds__(kInferWaves * kWave) void k_infer(const InferParams
             for (int rg = 0; rg < RGT; rg++) {
                 if32x4 c = acc[kw][rg][0];
                 if (NA == 2) c += acc[kw][rg][NA - 1];
-                *(if32x4*)(s_dots + ((size_t)(16 * rg + n) * SC + ic) * K16 + 16 * (ik * KW + kw) + 4 * g) = c;
+                *(if32x4*)(s_dots + (size_t)(16 * rg + n) * DS + ic * K16 + 16 * (ik * KW + kw) + 4 * g) = c;
             }
     };
 
@@ -263,7 +271,7 @@ __global__ __launch_bounds__(kInferWaves * kWave) void k_infer(const InferParams
                 const int k = lane + kWave * j;
                 sc[j] = 0x7fffffff;
                 if (K16 % kWave == 0 || k < K16) {
-                    const float* sp = s_dots + (size_t)trow * SC * K16 + k;
+                    const float* sp = s_dots + (size_t)trow * DS + k;
                     float dot = sp[0];
 #pragma unroll
                     for (int c = 1; c < SC; c++) dot += sp[c * K16];
