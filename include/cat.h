@@ -330,8 +330,9 @@ cat_status cat_top1(const void *x, int64_t N, int64_t D, cat_dtype dt, int32_t *
  * workspace       cat_fit_bounds_workspace_bytes(N, D, K, iters, dt) bytes
  * Other arguments and errors: as cat_fit.  N below 2^31.  Shapes the matrix-core kernels do not take, more than 128
  * clusters on rows of more than 128 channels (their passes rank in two launches, which keep no bounds), the streaming
- * path selected, or iters < 4: the plain loop runs and every pass reports N rows.  centroids, assignments, counts,
- * gamma and beta are those of cat_fit bit for bit. */
+ * path selected, or iters < 4: the plain loop runs and every pass reports N rows.  centroids, assignments and counts
+ * are those of cat_fit bit for bit, gamma and beta as from one call of cat_fit to the next (their sums are
+ * accumulated with atomics, whose order moves the last bits). */
 size_t cat_fit_bounds_workspace_bytes(int64_t N, int64_t D, int32_t K, int32_t iters, cat_dtype dt);
 cat_status cat_fit_bounds(const void *lq, const void *fp, int64_t N, int64_t D, int32_t K,
                           int32_t iters, uint64_t seed, cat_dtype dt,

@@ -37,8 +37,10 @@ def _mixture(seed, N, D, C, dt, spread=2.0):
 
 
 def _same_as_plain(b, p, iters):
-    for key in ("centroids", "gamma", "beta", "assignments", "counts"):
+    for key in ("centroids", "assignments", "counts"):
         assert torch.equal(b[key], p[key]), key
+    for key in ("gamma", "beta"):  # (the statistics are summed with atomics: two runs agree to the last bits, not bit for bit)
+        torch.testing.assert_close(b[key], p[key], rtol=1e-5, atol=1e-6)
     jb, jp = b["inertia"].cpu().numpy(), p["inertia"].cpu().numpy()
     full = [t for t in (0, 1, 2, iters) if t <= iters]
     np.testing.assert_allclose(jb[full], jp[full], rtol=5e-4)  # (the two may rank with different operand variants)
@@ -128,9 +130,7 @@ def test_the_streaming_path_runs_the_plain_loop():
     select_path(CAT_PATH_STREAM)
     b = cat_fit(xd, yd, 5, 6, seed=1, bounds=True)
     assert (b["rows_evaluated"].cpu().numpy() == 2000).all()
-    p = cat_fit(xd, yd, 5, 6, seed=1)
-    for key in ("centroids", "gamma", "beta", "assignments", "counts"):
-        assert torch.equal(b[key], p[key]), key
+    _same_as_plain(b, cat_fit(xd, yd, 5, 6, seed=1), 6)
 
 
 @pytest.mark.parametrize("name", ["cfg2", "cfg3", "cfg4"])

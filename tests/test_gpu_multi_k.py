@@ -2,8 +2,8 @@
 
 The oracle is a plain loop over its pinned ``fit`` (``oracle.fit_multi_k``).  The library runs the Lloyd loops of
 several cluster counts side by side where the shape allows it; every entry must equal the oracle's fit of that count
-to the usual tolerances, and the library's own single ``cat_fit`` of that count bit for bit (sharing the reads changes
-nothing that is computed)."""
+to the usual tolerances, and the library's own single ``cat_fit`` of that count: centroids, assignments and counts bit
+for bit, gamma and beta to rounding (sharing the reads changes nothing that is computed)."""
 import numpy as np
 import pytest
 import torch
@@ -37,8 +37,10 @@ def _mixture(seed, N, D, C, dt):
 
 
 def _same_as_single(r, s):
-    for key in ("centroids", "gamma", "beta", "assignments", "counts"):
+    for key in ("centroids", "assignments", "counts"):
         assert torch.equal(r[key], s[key]), key
+    for key in ("gamma", "beta"):  # (the statistics are summed with atomics: two runs agree to the last bits, not bit for bit)
+        torch.testing.assert_close(r[key], s[key], rtol=1e-5, atol=1e-6)
     # The objective is a diagnostic summed from the kernel's scores, and the two calls may run different variants of
     # the kernel: a group always ranks with the two-part operand, a single fit whose operand then fits LDS whole may
     # rank with one part (scores good to 2^-8 of |x||c|; the decision itself is re-ranked exactly either way).

@@ -27,6 +27,14 @@ def _mixture(seed, N, D, C, dt, spread=2.0):
     return x, y
 
 
+def _same(got, ref, key):
+    """integer outputs and centroids bit for bit; gamma / beta to rounding (their sums go through atomics)"""
+    if key in ("gamma", "beta"):
+        torch.testing.assert_close(got, ref, rtol=1e-5, atol=1e-6)
+    else:
+        assert torch.equal(got, ref), key
+
+
 def _capture(run):
     side = torch.cuda.Stream()
     side.wait_stream(torch.cuda.current_stream())
@@ -74,11 +82,14 @@ def test_new_calls_capture_into_a_hip_graph_and_replay():
         g.replay()
         torch.cuda.synchronize()
         for k in keys + ("rows_evaluated",):
-            assert torch.equal(b[k], ref_b[k]), k
+            _same(b[k], ref_b[k], k)
         for r, rr in zip(m, ref_m):
             for k in keys:
-                assert torch.equal(r[k], rr[k]), k
-        assert torch.equal(o, ref_o) and torch.equal(a, ref_a)
+                _same(r[k], rr[k], k)
+        # (the stored parameters are bfloat16 roundings of gamma / beta: a last-bit difference there moves an entry by a
+        # bfloat16 step at most)
+        assert torch.equal(a, ref_a)
+        torch.testing.assert_close(o.float(), ref_o.float(), rtol=2e-2, atol=1e-2)
 
 
 def _cases(n_cases=16, seed=20251128):
@@ -114,7 +125,7 @@ def test_random_shape_bounds_multi_k_low_precision(case, dt, N, D, K, iters):
     Ks = [max(1, K // 2), K, min(N, K + 5)]
     m = cat_fit_multi_k(xd, yd, Ks, iters, seed=case)
     for key in ("centroids", "assignments", "counts", "gamma", "beta"):
-        assert torch.equal(m[1][key], b[key]), key
+        _same(m[1][key], b[key], key)
     om = oracle.fit(x, y, Ks[2], iters, seed=case)
     check_assignments_lazy(m[2]["assignments"].cpu().numpy(), om["assignments"], x, om["centroids"], "third entry of the list")
     # low-precision inference with the fitted parameters
