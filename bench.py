@@ -297,11 +297,20 @@ def _run_workload(name, args, torch, np, cpu_budget_s, extras):
         t_as = _events(lambda: cat_assign(lq_o, cent_o, workspace=ws_o), 5, torch)
         t_ap = _events(lambda: cat_apply(lq_o, cent_o, g_o, b_o, out=out_o, workspace=ws_o), 5, torch)
         t_as0 = _events(lambda: cat_assign(lq, r["centroids"], workspace=ws_fit), 5, torch)
+        # the whole fit of those rows: its Lloyd loop runs on a zero-padded copy (the default), or on the LDS kernel
+        fp_o = pad(fp)
+        fit_o = lambda: cat_fit(lq_o, fp_o, K, iters, seed=w["seed"], workspace=ws_o)
+        t_fit_pad = _events(fit_o, 3, torch)
+        binding.debug_padded_fit(False)
+        try:
+            t_fit_lds = _events(fit_o, 3, torch)
+        finally:
+            binding.debug_padded_fit(True)
         detail.update(stream_shape=f"N={N} D={D + 1} K={K}", stream_assign_us=1e3 * t_as,
                       stream_assign_GBps=N * (D + 1) * esize / t_as / 1e6, stream_apply_us=1e3 * t_ap,
                       stream_apply_GBps=(2 * N * (D + 1) * esize + 4 * N) / t_ap / 1e6,
-                      aligned_assign_us=1e3 * t_as0)
-        del lq_o, out_o, ws_o
+                      aligned_assign_us=1e3 * t_as0, stream_shape_fit_ms=t_fit_pad, stream_shape_fit_lds_kernel_ms=t_fit_lds)
+        del lq_o, out_o, ws_o, fp_o
 
     # context: plain device copy of the same matrix
     t_copy = _events(lambda: out.copy_(lq), 5, torch)

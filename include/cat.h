@@ -76,8 +76,20 @@ cat_status cat_select_path(cat_path p);
 
 /* Bytes of device scratch cat_fit / cat_assign / cat_update / cat_stats need
  * (one size covers all four) and cat_apply needs.  Returns 0 for invalid
- * arguments. */
+ * arguments.
+ *
+ * Rows that are not a whole number of 16-byte groups (D not a multiple of 4, of 8
+ * for bf16) do not fit the MFMA tile kernels as they lie.  A fit reads lq once per
+ * Lloyd pass, so with CAT_PATH_AUTO and iters >= 2 the fits (cat_fit, cat_fit_early_stop,
+ * cat_fit_bounds, cat_fit_restarts, cat_fit_multi_k) copy lq once into rows padded
+ * with zero channels up to the next such multiple, which leave every distance as it
+ * is, and run their Lloyd loops on the copy wherever the tile kernels take the padded
+ * shape; the statistics read the original rows.  For those shapes the scratch sizes
+ * of the fits include the copy (N rows of the padded length).
+ * cat_debug_padded_fit(on): 0 keeps such fits on the streaming kernels; process-wide,
+ * default 1, for measurements and tests (results agree to rounding). */
 size_t cat_fit_workspace_bytes(int64_t N, int64_t D, int32_t K, cat_dtype dt);
+cat_status cat_debug_padded_fit(int on);
 size_t cat_apply_workspace_bytes(int64_t N, int64_t D, int32_t K, cat_dtype dt);
 
 /*
@@ -125,9 +137,9 @@ cat_status cat_fit(const void *lq, const void *fp, int64_t N, int64_t D, int32_t
  * passes_skipped  out, 1 int32: the number of assignment passes not run, between 0 and
  *                 iters - 3.  The library starts to look from pass 2 on: if pass t >= 1 is the
  *                 first whose assignments equal those of pass t - 1, this is
- *                 max(0, iters - 1 - max(t, 2)); 0 if there is none.  Shapes the tile kernels do
- *                 not take (D not a multiple of 4 (8 for bf16), K > 256, or the streaming path
- *                 selected) run every pass and report 0.
+ *                 max(0, iters - 1 - max(t, 2)); 0 if there is none.  Loops that run on the
+ *                 streaming kernels (K > 256, the streaming path selected, rows that are not
+ *                 whole 16-byte groups where no padded copy is made) run every pass and report 0.
  * Other arguments, workspace and errors: as cat_fit.
  *
  * cat_allow_early_stop(on != 0) lets every Lloyd loop the library runs stop in the same way

@@ -134,6 +134,44 @@ static ApplyWs carve_apply(void* base, int64_t D, int32_t K, cat_dtype dt, int64
     return w;
 }
 
+// Rows whose length is not a whole number of 16-byte groups do not fit the matrix-core kernels.  A fit reads the rows
+// once per Lloyd pass, so it pays to copy them once into rows padded with zero channels (distances are unchanged) and
+// to run the clustering on the copy: scratch for the copy, the padded centroids and a fit of the padded shape.
+struct PadWs {
+    void* lq = nullptr;      // N x Dp rows
+    float* cent = nullptr;   // K x Dp
+    float* init = nullptr;   // K x Dp
+    void* fit = nullptr;     // cat_fit scratch of the padded shape
+    void* bounds = nullptr;  // scratch of the bound-based loop on the padded shape (only where asked for)
+    int64_t Dp = 0;
+    size_t bytes = 0;
+};
+static int64_t padded_dim(int64_t D, cat_dtype dt) {
+    const int64_t step = dt == CAT_BF16 ? 8 : 4;
+    return (D + step - 1) / step * step;
+}
+static bool pad_applies(int64_t N, int64_t D, int32_t K, cat_dtype dt) {
+    const int64_t Dp = padded_dim(D, dt);
+    return Dp != D && !tile_supports(TILE_LLOYD, N, D, K, dt) && tile_supports(TILE_LLOYD, N, Dp, K, dt);
+}
+// (one pass or none: the copy would cost as much as it saves)
+static std::atomic<bool> g_padded_fit{true};  // cat_debug_padded_fit
+static bool fit_runs_padded(int64_t N, int64_t D, int32_t K, cat_dtype dt, int32_t iters) {
+    return g_padded_fit.load() && g_path.load() == CAT_PATH_AUTO && iters >= 2 && pad_applies(N, D, K, dt);
+}
+static PadWs carve_pad(void* base, int64_t N, int64_t D, int32_t K, cat_dtype dt, int32_t iters, bool with_bounds) {
+    PadWs w;
+    w.Dp = padded_dim(D, dt);
+    Carver c(base);
+    w.lq = c.take<char>((size_t)N * (size_t)w.Dp * (dt == CAT_BF16 ? 2 : 4));
+    w.cent = c.take<float>((size_t)K * (size_t)w.Dp);
+    w.init = c.take<float>((size_t)K * (size_t)w.Dp);
+    w.fit = c.take<char>(carve_fit(nullptr, N, w.Dp, K, dt).bytes);
+    if (with_bounds) w.bounds = c.take<char>(bounds_workspace_bytes(N, w.Dp, K, iters));
+    w.bytes = c.off;
+    return w;
+}
+
 // ---- argument checks ----------------------------------------------------------------
 static bool shape_ok(int64_t N, int64_t D, int32_t K, cat_dtype dt) {
     if (dt != CAT_F32 && dt != CAT_BF16) return false;
@@ -298,6 +336,11 @@ cat_status cat_debug_apply_kernel(int which) {
     return CAT_OK;
 }
 
+cat_status cat_debug_padded_fit(int on) {
+    g_padded_fit.store(on != 0);
+    return CAT_OK;
+}
+
 cat_status cat_allow_early_stop(int on) {
     g_early_stop.store(on != 0);
     return CAT_OK;
@@ -312,7 +355,9 @@ cat_status cat_select_path(cat_path p) {
 
 size_t cat_fit_workspace_bytes(int64_t N, int64_t D, int32_t K, cat_dtype dt) {
     if (!shape_ok(N, D, K, dt)) return 0;
-    return carve_fit(nullptr, N, D, K, dt).bytes;
+    size_t b = carve_fit(nullptr, N, D, K, dt).bytes;
+    if (pad_applies(N, D, K, dt)) b = align256(b) + carve_pad(nullptr, N, D, K, dt, 0, false).bytes;
+    return b;
 }
 
 size_t cat_apply_workspace_bytes(int64_t N, int64_t D, int32_t K, cat_dtype dt) {
@@ -418,10 +463,34 @@ static cat_status fit_impl(const char* who, const void* lq, const void* fp, int6
         bw.evaluated = evaluated;
         need = align256(w.bytes) + bw.bytes;
     }
+    // rows that are not whole 16-byte groups: the clustering runs on a zero-padded copy (the scratch sizes of the fits
+    // include it; the entry points that size their scratch from the pieces do not come through here)
+    const bool padded = fit_runs_padded(N, D, K, dt, iters);
+    PadWs pw;
+    if (padded) {
+        pw = carve_pad(workspace ? (char*)workspace + align256(need) : nullptr, N, D, K, dt, iters, with_bounds);
+        need = align256(need) + pw.bytes;
+    }
     CAT_TRY(check_ws(who, workspace, workspace_bytes, need));
     hipStream_t st = (hipStream_t)hip_stream;
-    CAT_TRY(run_lloyd(lq, dt, N, D, K, iters, seed, init_centroids, centroids, assignments, inertia, w, st, skipped,
-                      with_bounds ? &bw : nullptr));
+    if (padded) {
+        const int64_t Dp = pw.Dp;
+        FitWs wp = carve_fit(pw.fit, N, Dp, K, dt);
+        BoundsWs bp;
+        if (with_bounds) {
+            bp = bounds_carve(pw.bounds, N, Dp, K, iters);
+            bp.evaluated = evaluated;
+        }
+        CAT_TRY(launch_pad_rows(lq, dt, N, D, Dp, pw.lq, st));
+        if (init_centroids) CAT_TRY(launch_pad_rows(init_centroids, CAT_F32, K, D, Dp, pw.init, st));
+        CAT_TRY(run_lloyd(pw.lq, dt, N, Dp, K, iters, seed, init_centroids ? pw.init : nullptr, pw.cent, assignments, inertia,
+                          wp, st, skipped, with_bounds ? &bp : nullptr));
+        CAT_TRY(launch_pad_rows(pw.cent, CAT_F32, K, Dp, D, centroids, st));
+        w = wp;  // counts and first rows of the clusters are there; its arrays are at least as large
+    } else {
+        CAT_TRY(run_lloyd(lq, dt, N, D, K, iters, seed, init_centroids, centroids, assignments, inertia, w, st, skipped,
+                          with_bounds ? &bw : nullptr));
+    }
     // affine fit on that partition, shifted by the centroids
     CAT_TRY(step_stats(lq, fp, dt, assignments, N, D, K, w.counts, w.rep, centroids, w, gamma, beta, st));
     if (counts) CAT_TRY(launch_copy_words(w.counts, counts, K, st));
@@ -447,7 +516,9 @@ cat_status cat_fit_early_stop(const void* lq, const void* fp, int64_t N, int64_t
 
 size_t cat_fit_bounds_workspace_bytes(int64_t N, int64_t D, int32_t K, int32_t iters, cat_dtype dt) {
     if (!shape_ok(N, D, K, dt) || iters < 0) return 0;
-    return align256(carve_fit(nullptr, N, D, K, dt).bytes) + bounds_workspace_bytes(N, D, K, iters);
+    size_t b = align256(carve_fit(nullptr, N, D, K, dt).bytes) + bounds_workspace_bytes(N, D, K, iters);
+    if (pad_applies(N, D, K, dt)) b = align256(b) + carve_pad(nullptr, N, D, K, dt, iters, true).bytes;
+    return b;
 }
 
 cat_status cat_fit_bounds(const void* lq, const void* fp, int64_t N, int64_t D, int32_t K, int32_t iters, uint64_t seed,
@@ -457,7 +528,7 @@ cat_status cat_fit_bounds(const void* lq, const void* fp, int64_t N, int64_t D, 
     if (rows_evaluated) CAT_TRY(check_ptr("cat_fit_bounds", "rows_evaluated", rows_evaluated, 4));
     if (N >= ((int64_t)1 << 31))
         return set_error(CAT_ERR_UNSUPPORTED, "cat_fit_bounds: N = %lld does not fit the 32-bit row numbers of its lists", (long long)N);
-    const bool fused = tile_supports(TILE_LLOYD, N, D, K, dt) && g_path.load() != CAT_PATH_STREAM;
+    const bool fused = (tile_supports(TILE_LLOYD, N, D, K, dt) && g_path.load() != CAT_PATH_STREAM) || fit_runs_padded(N, D, K, dt, iters);
     cat_status s = fit_impl("cat_fit_bounds", lq, fp, N, D, K, iters, seed, dt, init_centroids, centroids, gamma, beta,
                             assignments, counts, inertia, nullptr, workspace, workspace_bytes, hip_stream, true, rows_evaluated);
     if (s != CAT_OK) return s;
@@ -476,6 +547,7 @@ struct RestartWs {
     double* inertia;     // iters + 1 objective values of the run
     double* best;        // lowest final objective so far
     int32_t* state;      // [0] the run just finished is the best so far, [1] its index
+    void* pad;           // scratch of the runs on a zero-padded copy of the rows (only for the shapes that use one)
     size_t fit_bytes, pp_bytes, bytes;
 };
 static RestartWs carve_restarts(void* base, int64_t N, int64_t D, int32_t K, int32_t iters, cat_dtype dt) {
@@ -497,6 +569,7 @@ static RestartWs carve_restarts(void* base, int64_t N, int64_t D, int32_t K, int
     w.inertia = (double*)take(((size_t)(iters < 0 ? 0 : iters) + 1) * sizeof(double));
     w.best = (double*)take(sizeof(double));
     w.state = (int32_t*)take(2 * sizeof(int32_t));
+    w.pad = pad_applies(N, D, K, dt) ? take(carve_pad(nullptr, N, D, K, dt, iters, false).bytes) : nullptr;
     w.bytes = off;
     return w;
 }
@@ -529,6 +602,15 @@ cat_status cat_fit_restarts(const void* lq, const void* fp, int64_t N, int64_t D
     hipStream_t st = (hipStream_t)hip_stream;
     FitWs fw = carve_fit(w.fit, N, D, K, dt);
     const size_t KD = (size_t)K * (size_t)D;
+    // as in cat_fit: rows that are not whole 16-byte groups are padded once, every run clusters the copy
+    const bool padded = fit_runs_padded(N, D, K, dt, iters);
+    PadWs pw;
+    FitWs wp;
+    if (padded) {
+        pw = carve_pad(w.pad, N, D, K, dt, iters, false);
+        wp = carve_fit(pw.fit, N, pw.Dp, K, dt);
+        CAT_TRY(launch_pad_rows(lq, dt, N, D, pw.Dp, pw.lq, st));
+    }
     for (int32_t r = 0; r < restarts; r++) {
         const uint64_t seed_r = seed + (uint64_t)r;
         const float* init = nullptr;
@@ -536,7 +618,13 @@ cat_status cat_fit_restarts(const void* lq, const void* fp, int64_t N, int64_t D
             CAT_TRY(cat_init_kmeanspp(lq, N, D, K, seed_r, dt, w.init, nullptr, w.pp, w.pp_bytes, hip_stream));
             init = w.init;
         }
-        CAT_TRY(run_lloyd(lq, dt, N, D, K, iters, seed_r, init, w.cent, w.assign, w.inertia, fw, st));
+        if (padded) {
+            if (init) CAT_TRY(launch_pad_rows(init, CAT_F32, K, D, pw.Dp, pw.init, st));
+            CAT_TRY(run_lloyd(pw.lq, dt, N, pw.Dp, K, iters, seed_r, init ? pw.init : nullptr, pw.cent, w.assign, w.inertia, wp, st));
+            CAT_TRY(launch_pad_rows(pw.cent, CAT_F32, K, pw.Dp, D, w.cent, st));
+        } else {
+            CAT_TRY(run_lloyd(lq, dt, N, D, K, iters, seed_r, init, w.cent, w.assign, w.inertia, fw, st));
+        }
         CAT_TRY(launch_keep_best(w.inertia + iters, w.best, w.state, r, final_inertia, st));
         CAT_TRY(launch_copy_words_if(w.state, w.cent, centroids, (int64_t)KD, st));
         CAT_TRY(launch_copy_words_if(w.state, w.assign, assignments, N, st));
@@ -614,20 +702,33 @@ struct MultiWs {
     unsigned long long* rep;  // slots
     double* inertia16;    // (iters + 1) x 16
     int32_t* column;      // N
+    void* lqpad;          // N x D rows padded with zero channels, and K x D centroids of a fit on them (only where
+    float* centpad;       //   the loops run on the padded copy)
     TileWs tile;
     LloydWs lloyd;
     size_t fit_bytes, bytes;
 };
+// D: the row length the Lloyd loops see; Dorig < D where they run on a zero-padded copy of the rows
 static MultiWs carve_multi(void* base, int64_t N, int64_t D, const int32_t* Ks, int32_t nK, int32_t slots, int32_t nsets,
-                           int32_t iters, cat_dtype dt) {
+                           int32_t iters, cat_dtype dt, int64_t Dorig) {
     MultiWs w = {};
     w.fit_bytes = 0;  // the scratch of one fit is not monotone in K (the tile kernels take some K and not others)
+    int32_t Kmax = 1;
     for (int i = 0; i < nK; i++) {
-        const size_t b = carve_fit(nullptr, N, D, Ks[i], dt).bytes;
+        size_t b = carve_fit(nullptr, N, D, Ks[i], dt).bytes;
+        if (Dorig != D) {
+            const size_t bo = carve_fit(nullptr, N, Dorig, Ks[i], dt).bytes;
+            b = bo > b ? bo : b;
+        }
         w.fit_bytes = b > w.fit_bytes ? b : w.fit_bytes;
+        Kmax = Ks[i] > Kmax ? Ks[i] : Kmax;
     }
     Carver c(base);
     w.fit = c.take<char>(w.fit_bytes);
+    if (Dorig != D) {
+        w.lqpad = c.take<char>((size_t)N * (size_t)D * (dt == CAT_BF16 ? 2 : 4));
+        w.centpad = c.take<float>((size_t)Kmax * (size_t)D);
+    }
     if (slots > 0) {
         const size_t SD = (size_t)slots * (size_t)D;
         w.cent = c.take<float>(SD);
@@ -666,6 +767,14 @@ static void multi_extent(const std::vector<MultiGroup>& groups, const int32_t* K
     }
 }
 
+// The same rule as for a single fit: rows that are not whole 16-byte groups are copied once, padded with zero channels,
+// and every cluster count the matrix-core kernels take at the padded length clusters on the copy.
+static bool multi_runs_padded(int64_t N, int64_t D, const int32_t* Ks, int32_t nK, cat_dtype dt, int32_t iters) {
+    for (int i = 0; i < nK; i++)
+        if (fit_runs_padded(N, D, Ks[i], dt, iters)) return true;
+    return false;
+}
+
 cat_status cat_debug_multi_group_tiles(int tiles) {
     if (tiles != 0 && tiles != 1 && tiles != 2 && tiles != 4 && tiles != 8)
         return set_error(CAT_ERR_INVALID_ARG, "cat_debug_multi_group_tiles: %d is not 0, 1, 2, 4 or 8", tiles);
@@ -678,8 +787,9 @@ size_t cat_fit_multi_k_workspace_bytes(int64_t N, int64_t D, const int32_t* Ks, 
     for (int i = 0; i < nK; i++)
         if (!shape_ok(N, D, Ks[i], dt)) return 0;
     int32_t Kmax, slots, nsets;
-    multi_extent(plan_multi(N, D, Ks, nK, dt), Ks, nK, Kmax, slots, nsets);
-    return carve_multi(nullptr, N, D, Ks, nK, slots, nsets, iters, dt).bytes;
+    const int64_t Dl = multi_runs_padded(N, D, Ks, nK, dt, iters) ? padded_dim(D, dt) : D;
+    multi_extent(plan_multi(N, Dl, Ks, nK, dt), Ks, nK, Kmax, slots, nsets);
+    return carve_multi(nullptr, N, Dl, Ks, nK, slots, nsets, iters, dt, D).bytes;
 }
 
 cat_status cat_fit_multi_k(const void* lq, const void* fp, int64_t N, int64_t D, const int32_t* Ks, int32_t nK, int32_t iters,
@@ -694,12 +804,16 @@ cat_status cat_fit_multi_k(const void* lq, const void* fp, int64_t N, int64_t D,
     CAT_TRY(check_ptr(who, "beta", beta, 16));
     CAT_TRY(check_ptr(who, "assignments", assignments, 4));
     if (inertia) CAT_TRY(check_ptr(who, "inertia", inertia, 8));
-    const std::vector<MultiGroup> groups = plan_multi(N, D, Ks, nK, dt);
+    const bool padded = multi_runs_padded(N, D, Ks, nK, dt, iters);
+    const int64_t Dl = padded ? padded_dim(D, dt) : D;  // the row length the Lloyd loops see
+    const std::vector<MultiGroup> groups = plan_multi(N, Dl, Ks, nK, dt);
     int32_t Kmax, slots, nsets;
     multi_extent(groups, Ks, nK, Kmax, slots, nsets);
-    MultiWs w = carve_multi(workspace, N, D, Ks, nK, slots, nsets, iters, dt);
+    MultiWs w = carve_multi(workspace, N, Dl, Ks, nK, slots, nsets, iters, dt, D);
     CAT_TRY(check_ws(who, workspace, workspace_bytes, w.bytes));
     hipStream_t st = (hipStream_t)hip_stream;
+    if (padded) CAT_TRY(launch_pad_rows(lq, dt, N, D, Dl, w.lqpad, st));
+    const void* lql = padded ? w.lqpad : lq;
     std::vector<int64_t> row0(nK + 1, 0);  // first row of set i in centroids / gamma / beta / counts
     for (int i = 0; i < nK; i++) row0[i + 1] = row0[i] + Ks[i];
     const int64_t nin = (int64_t)iters + 1;
@@ -707,10 +821,18 @@ cat_status cat_fit_multi_k(const void* lq, const void* fp, int64_t N, int64_t D,
         if (!g.ms.nsets) {  // the ordinary fit
             const int i = g.first;
             const int32_t K = Ks[i];
-            FitWs fw = carve_fit(w.fit, N, D, K, dt);
             float* cent_i = centroids + row0[i] * D;
             int32_t* asg_i = assignments + (int64_t)i * N;
-            CAT_TRY(run_lloyd(lq, dt, N, D, K, iters, seed, nullptr, cent_i, asg_i, inertia ? inertia + i * nin : nullptr, fw, st));
+            double* in_i = inertia ? inertia + i * nin : nullptr;
+            // (a count the matrix-core kernels do not take at the padded length either: the original rows, as cat_fit does)
+            const bool on_copy = padded && tile_supports(TILE_LLOYD, N, Dl, K, dt);
+            FitWs fw = carve_fit(w.fit, N, on_copy ? Dl : D, K, dt);
+            if (on_copy) {
+                CAT_TRY(run_lloyd(w.lqpad, dt, N, Dl, K, iters, seed, nullptr, w.centpad, asg_i, in_i, fw, st));
+                CAT_TRY(launch_pad_rows(w.centpad, CAT_F32, K, Dl, D, cent_i, st));
+            } else {
+                CAT_TRY(run_lloyd(lq, dt, N, D, K, iters, seed, nullptr, cent_i, asg_i, in_i, fw, st));
+            }
             CAT_TRY(step_stats(lq, fp, dt, asg_i, N, D, K, fw.counts, fw.rep, cent_i, fw, gamma + row0[i] * D,
                                beta + row0[i] * D, st));
             if (counts) CAT_TRY(launch_copy_words(fw.counts, counts + row0[i], K, st));
@@ -719,15 +841,15 @@ cat_status cat_fit_multi_k(const void* lq, const void* fp, int64_t N, int64_t D,
         const MultiSets& ms = g.ms;
         const int32_t gslots = 16 * ms.t0[ms.nsets];
         // seeded rows of every set into its slots; the other slots stay zero rows with zero counts
-        CAT_TRY(launch_fill_zero(w.cent, (size_t)gslots * D * sizeof(float), st));
-        FitWs fw = carve_fit(w.fit, N, D, Kmax, dt);
+        CAT_TRY(launch_fill_zero(w.cent, (size_t)gslots * Dl * sizeof(float), st));
+        FitWs fw = carve_fit(w.fit, N, Dl, Kmax, dt);
         for (int j = 0; j < ms.nsets; j++) {
             CAT_TRY(launch_init_indices(N, ms.k[j], seed, fw.idx, st));
-            CAT_TRY(launch_gather_rows(lq, dt, D, ms.k[j], fw.idx, w.cent + (size_t)16 * ms.t0[j] * D, st));
+            CAT_TRY(launch_gather_rows(lql, dt, Dl, ms.k[j], fw.idx, w.cent + (size_t)16 * ms.t0[j] * Dl, st));
         }
         LloydWs lw = w.lloyd;
         lw.sort_ws = fw.sort;
-        CAT_TRY(tile_lloyd_multi(lq, dt, N, D, ms, iters, w.cent, w.sums, w.assign16, w.counts, inertia ? w.inertia16 : nullptr,
+        CAT_TRY(tile_lloyd_multi(lql, dt, N, Dl, ms, iters, w.cent, w.sums, w.assign16, w.counts, inertia ? w.inertia16 : nullptr,
                                  w.rep, w.column, w.tile, lw, st));
         for (int j = 0; j < ms.nsets; j++) {
             const int i = g.first + j;
@@ -735,7 +857,10 @@ cat_status cat_fit_multi_k(const void* lq, const void* fp, int64_t N, int64_t D,
             float* cent_i = centroids + row0[i] * D;
             int32_t* asg_i = assignments + (int64_t)i * N;
             CAT_TRY(launch_multi_column(w.assign16, N, j, slot0, asg_i, st));
-            CAT_TRY(launch_copy_words(w.cent + (size_t)slot0 * D, cent_i, (int64_t)K * D, st));
+            if (padded)
+                CAT_TRY(launch_pad_rows(w.cent + (size_t)slot0 * Dl, CAT_F32, K, Dl, D, cent_i, st));
+            else
+                CAT_TRY(launch_copy_words(w.cent + (size_t)slot0 * D, cent_i, (int64_t)K * D, st));
             FitWs fk = carve_fit(w.fit, N, D, K, dt);
             CAT_TRY(step_stats(lq, fp, dt, asg_i, N, D, K, w.counts + slot0, w.rep + slot0, cent_i, fk, gamma + row0[i] * D,
                                beta + row0[i] * D, st));

@@ -73,6 +73,28 @@ cat_status launch_copy_cols(const float* src, int64_t rows, int32_t src_ld, floa
     return CAT_OK;
 }
 
+// dst (rows x dst_ld) <- the first dst_ld columns of src (rows x src_ld), zeros where src has none (fp32 or 16-bit elements)
+template <typename T>
+__global__ __launch_bounds__(256) void k_pad_rows(const T* __restrict__ src, int64_t rows, int64_t src_ld, int64_t dst_ld, T* __restrict__ dst) {
+    const int64_t n = rows * dst_ld;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) {
+        const int64_t r = i / dst_ld, c = i - r * dst_ld;
+        dst[i] = c < src_ld ? src[r * src_ld + c] : (T)0;
+    }
+}
+cat_status launch_pad_rows(const void* src, cat_dtype dt, int64_t rows, int64_t src_ld, int64_t dst_ld, void* dst, hipStream_t st) {
+    const int64_t n = rows * dst_ld;
+    if (n == 0) return CAT_OK;
+    int64_t blocks = (n + 255) / 256;
+    blocks = blocks > (1 << 20) ? (1 << 20) : blocks;
+    if (dt == CAT_F32)
+        hipLaunchKernelGGL(k_pad_rows<float>, dim3((unsigned)blocks), dim3(256), 0, st, (const float*)src, rows, src_ld, dst_ld, (float*)dst);
+    else
+        hipLaunchKernelGGL(k_pad_rows<bf16_t>, dim3((unsigned)blocks), dim3(256), 0, st, (const bf16_t*)src, rows, src_ld, dst_ld, (bf16_t*)dst);
+    CAT_LAUNCH_CHECK("k_pad_rows");
+    return CAT_OK;
+}
+
 __global__ void k_fill_u64(unsigned long long* p, int64_t n, unsigned long long v) {
     int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i < n) p[i] = v;

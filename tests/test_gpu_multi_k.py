@@ -62,7 +62,7 @@ def _same_as_oracle(r, o, x, dt, what):
     (3000, 64, [1, 5, 16, 17], 6, "f32"),                 # one group of five tiles
     (2500, 136, [9, 3, 40], 5, "bf16"),                   # a ragged last chunk of channels, bf16 rows
     (4099, 260, [2, 33, 7, 100, 64], 5, "f32"),           # rows not a multiple of 16; three groups
-    (1500, 37, [4, 6], 3, "f32"),                         # D not a multiple of 4: every entry on the streaming kernels
+    (1500, 37, [4, 6], 3, "f32"),                         # D not a multiple of 4: a group on a zero-padded copy of the rows
     (2000, 32, [300, 8, 12], 4, "f32"),                   # an entry the tile kernels cannot take, then a group
     (1200, 48, [7], 4, "f32"),                            # a list of one
     (900, 16, [3, 5], 0, "f32"),                          # no iterations

@@ -33,7 +33,7 @@ def _mixture(seed, N, D, K, dt):
     (3000, 64, 6, 5, 6, "f32", CAT_SEED_ROWS),
     (3000, 64, 6, 5, 6, "f32", CAT_SEED_KMEANSPP),
     (2500, 136, 9, 4, 5, "bf16", CAT_SEED_ROWS),
-    (1500, 37, 4, 3, 4, "f32", CAT_SEED_KMEANSPP),   # the streaming kernels (D not a multiple of 4)
+    (1500, 37, 4, 3, 4, "f32", CAT_SEED_KMEANSPP),   # D not a multiple of 4: every run on a zero-padded copy of the rows
     (800, 16, 3, 0, 3, "f32", CAT_SEED_ROWS),        # no iterations: the seeds themselves are compared
 ])
 def test_best_run_matches_the_oracle(N, D, K, iters, restarts, dt, seeding):
