@@ -483,16 +483,20 @@ __global__ __launch_bounds__(256) void k_sort_scatter(const int32_t* __restrict_
         if (a[u] >= 0) perm[s_cnt[a[u]] + rank[u]] = (uint32_t)(r0 + (int64_t)u * blockDim.x);
 }
 
-// One wave per (run of R positions of the ordered rows) x (64 V channels, V = channels per 16-byte
-// group).  The sums of the current cluster live in registers (doubles); when the run crosses into
-// the next cluster, and at its end, they are added to acc with atomics.
+// One wave per (run of R positions of the ordered rows) x (64 V channels).  The sums of the current
+// cluster live in registers (doubles); when the run crosses into the next cluster, and at its end, they
+// are added to acc with atomics.  V = 2 channels per lane (one 4-byte load of a bf16 row, one 8-byte load
+// of an fp32 row; a wave still reads whole cache lines): measured against 16-byte loads per lane (V = 8 / 4)
+// it is 1.3 - 1.5 x faster on bf16 rows and 1.1 x on fp32 rows, with a third of the registers and three
+// times the waves in flight; V = 1 gains nothing more.
 constexpr int kSortWaves = 4;
+constexpr int kSortV = 2;
 template <typename T, int NQ>
 __global__ __launch_bounds__(kSortWaves * kWave) void k_segsum_sorted(
     const T* __restrict__ lq, const T* __restrict__ fp, const uint32_t* __restrict__ perm,
     const uint32_t* __restrict__ offs, int64_t D, int32_t K, int32_t R, int32_t nsl, int64_t nitems,
     const float* __restrict__ pivx, const float* __restrict__ pivy, double* __restrict__ acc) {
-    constexpr int V = sizeof(T) == 2 ? 8 : 4;
+    constexpr int V = kSortV;
     constexpr int RB = 4;  // rows per round; two rounds are in flight
     __shared__ uint32_t s_offs[CAT_MAX_K + 1];
     for (int k = threadIdx.x; k <= K; k += blockDim.x) s_offs[k] = offs[k];
@@ -509,6 +513,11 @@ __global__ __launch_bounds__(kSortWaves * kWave) void k_segsum_sorted(
     const int64_t c0 = (int64_t)slice * (kWave * V) + (int64_t)lane * V;
     const bool on = c0 < D;  // D is a multiple of V: a lane's group is inside or outside as a whole
     const int64_t KD = (int64_t)K * D;
+    // Every load of the loop below is issued by every wave on every path (a lane outside the row reads channel 0, a
+    // round past the end reads the last row again; neither is used).  The compiler counts the loads still in flight
+    // at each use; a load it cannot prove was issued makes it wait for all of them, which would empty the pipeline
+    // once per row.
+    const int64_t cl = on ? c0 : 0;
 
     // cluster of position p0: the last k with offs[k] <= p0
     int k = 0;
@@ -557,7 +566,7 @@ __global__ __launch_bounds__(kSortWaves * kWave) void k_segsum_sorted(
     // Rounds of RB rows, two register buffers: the loads of round r + 1 are requested before round r
     // is added up (each round is a gather of RB rows from anywhere in the matrix, a full memory
     // round trip).  The row numbers come 64 at a time (one per lane), one batch ahead.
-    typedef __attribute__((ext_vector_type(4))) uint32_t u4;
+    typedef __attribute__((ext_vector_type(V * sizeof(T) / 4))) uint32_t u4;  // the V channels of a lane
     const uint32_t n = p1 - p0;
     const int nr = (int)((n + RB - 1) / RB);
     uint32_t cur = perm[p0 + ((uint32_t)lane < n ? lane : n - 1)];
@@ -576,10 +585,8 @@ __global__ __launch_bounds__(kSortWaves * kWave) void k_segsum_sorted(
             uint32_t i = (uint32_t)(r * RB + u);
             if (i >= n) i = n - 1;  // past the end: the last row again, unused
             const int64_t row = (int64_t)__builtin_amdgcn_readlane(src, (int)(i & (kWave - 1)));
-            if (on) {
-                xv[u] = *(const u4*)(lq + row * D + c0);
-                if (NQ == 4) yv[u] = *(const u4*)(fp + row * D + c0);
-            }
+            xv[u] = *(const u4*)(lq + row * D + cl);
+            if (NQ == 4) yv[u] = *(const u4*)(fp + row * D + cl);
         }
     };
     auto consume = [&](int r, const u4 (&xv)[RB], const u4 (&yv)[RB]) {
@@ -595,6 +602,10 @@ __global__ __launch_bounds__(kSortWaves * kWave) void k_segsum_sorted(
                     nextb = s_offs[k + 1];
                 } while (pos >= nextb);
                 load_piv();
+                // vmcnt(0): atomics count with the loads here and may complete out of order with them, so with any
+                // of them possibly in flight every later wait in the loop would be for everything; drained once per
+                // cluster boundary instead
+                __builtin_amdgcn_s_waitcnt(0x0F70);
             }
             if (on) {
 #pragma unroll
@@ -629,23 +640,25 @@ __global__ __launch_bounds__(kSortWaves * kWave) void k_segsum_sorted(
     issue(0, 0, xa, ya);
     for (int r = 0; r < nr; r += 2) {
         advance(r);
-        if (r + 1 < nr) issue(r + 1, r, xb, yb);
+        issue(r + 1, r, xb, yb);
         consume(r, xa, ya);
         if (r + 1 >= nr) break;
         advance(r + 1);
-        if (r + 2 < nr) issue(r + 2, r + 1, xa, ya);
+        issue(r + 2, r + 1, xa, ya);
         consume(r + 1, xb, yb);
     }
     flush();
 }
 
 bool segsum_sorted_supported(int nq, int64_t N, int64_t D, cat_dtype dt) {
-    if (N >= ((int64_t)1 << 31) || D % (dt == CAT_BF16 ? 8 : 4)) return false;
+    (void)nq;
+    if (N >= ((int64_t)1 << 31) || D % kSortV) return false;
     // Where it pays (measured): always for bf16 rows (the LDS-panel kernel reads them two bytes per
-    // lane); for fp32 rows only for the four-quantity statistics of a large matrix.  The plain sums of
-    // fp32 rows, and small matrices, are faster in launch_segsum, which reads the rows in order.
+    // lane); for fp32 rows from a few million elements on (65536 x 1000: 105 against 156 us for the
+    // statistics, 47 against 64 us for the plain sums; 65536 x 256: 32 against 62 us).  Below that the two
+    // launches of the ordering cost more than they save (16384 x 128: 38 against 34 us for the whole call).
     if (dt == CAT_BF16 || fast_paths_forced()) return true;
-    return nq == 4 && N * D >= ((int64_t)1 << 27);
+    return N * D >= ((int64_t)1 << 22);
 }
 size_t sort_workspace_words(int64_t N, int32_t K) { return (size_t)N + 2 * (size_t)K + 2; }
 
@@ -661,7 +674,7 @@ cat_status launch_segsum_sorted(int nq, const void* lq, const void* fp, cat_dtyp
     hipLaunchKernelGGL(k_sort_scatter, dim3((unsigned)((N + per_block - 1) / per_block)), dim3(256), 0, st, assign, N, K,
                        cursor, perm);
     CAT_LAUNCH_CHECK("k_sort_scatter");
-    const int V = dt == CAT_BF16 ? 8 : 4;
+    const int V = kSortV;
     const int nsl = (int)((D + kWave * V - 1) / (kWave * V));
     // One wave per run: as many runs as waves are resident at once (or a multiple of that), so
     // the launch has no ragged second round; a run is at least 64 rows (shorter runs only add
