@@ -225,7 +225,14 @@ static cat_status step_assign(const void* lq, cat_dtype dt, int64_t N, int64_t D
             return tile_assign_split(lq, dt, N, D, K, cent, assign, counts, inertia, rep, tw, split_scratch, st);
         return tile_assign(lq, dt, N, D, K, cent, assign, counts, inertia, rep, nullptr, nullptr, nullptr, tw, st);
     }
-    // shapes outside the matrix-core kernels: the LDS streaming kernel; the direct-form kernel only when asked for
+    // shapes outside the matrix-core tile kernels: the row-tile inference kernel without its map where it has an instance
+    // (rows that are not whole 16-byte groups), counts and first rows from the labels afterwards; else the LDS streaming
+    // kernel; the direct-form kernel only when asked for
+    if (path == CAT_PATH_AUTO && assign && tw.packA && infer_supported(N, D, K, dt) && g_apply_kernel.load() != 1) {
+        CAT_TRY(infer_apply(lq, dt, N, D, K, cent, nullptr, nullptr, nullptr, assign, tw, st, false, inertia));
+        if (counts || rep) CAT_TRY(launch_count_rep(assign, N, K, counts, rep, st));
+        return CAT_OK;
+    }
     if (path != CAT_PATH_STREAM)
         return launch_assign_lds(lq, dt, N, D, K, cent, assign, counts, inertia, rep, nullptr, nullptr, nullptr, st);
     return launch_assign_stream(lq, dt, N, D, K, cent, assign, counts, inertia, rep, nullptr, nullptr, nullptr, st);

@@ -36,8 +36,9 @@ constexpr int infer_dots_stride(int n) { return n + (16 - n % 64 + 64) % 64; }
 
 struct InferParams {
     const void* lq;
-    void* out;
+    void* out;        // nullable: nothing is written (assignment only; gamma / beta must still be readable K x D arrays)
     int32_t* assign;  // nullable
+    double* inertia;  // nullable: the sum of the squared distances to the assigned centroids is added here
     int64_t N, D, ntiles;
     int32_t K, KT;        // clusters; cluster tiles of 16 in packA
     int32_t psteps;       // steps present in packA (4 per 128-channel chunk)
@@ -101,7 +102,11 @@ __device__ __forceinline__ float wave_sum_all(float v) {
 // times SC channel shares).  SPW: MFMA steps per wave and tile.  P: parts of the centroid operand (2: hi + lo, 1: hi
 // only, wider re-rank bound).  RGT: 16-row groups per tile.  VPR: 16-byte vectors per lane and row
 // (ceil(D * b / 1024)).  DYN: tiles handed out in order by counters instead of a fixed stride.
-template <bool BF16, int KW, int SC, int SPW, int P, int RGT, int VPR, bool DYN>
+// UA: rows that are not whole 16-byte groups (D not a multiple of 4, of 8 for bf16).  Rows, parameters and outputs
+// then move in 4-byte words, and word e of vector v of a lane is word 256 v + 64 e + lane of the row instead of word
+// 256 v + 4 lane + e: every wave instruction still reads or writes 256 consecutive bytes, and no access is wider than
+// its alignment.  Only the addressing differs: on chip a word is a word, whichever channels it holds.
+template <bool BF16, int KW, int SC, int SPW, int P, int RGT, int VPR, bool DYN, bool UA = false>
 __global__ __launch_bounds__(kInferWaves * kWave) void k_infer(const InferParams p) {
     extern __shared__ __align__(16) unsigned char smem[];
     constexpr int SK = kInferWaves / SC;           // cluster shares
@@ -169,6 +174,47 @@ __global__ __launch_bounds__(kInferWaves * kWave) void k_infer(const InferParams
         ch[v] = (v * kWave + lane) * EPL;
         ch_ok[v] = ch[v] < p.D;
     }
+    // UA: the row words of this lane, clamped to the last word of the row (no load is conditional), and which exist
+    const int Wx = (int)(BF16 ? p.D / 2 : p.D);
+    uint32_t wo[UA ? VPR : 1][4];  // as byte offsets (unsigned 32 bits: base in scalar registers + offset per lane)
+    int okm[UA ? VPR : 1];
+    if (UA) {
+#pragma unroll
+        for (int v = 0; v < VPR; v++) {
+            okm[v] = 0;
+#pragma unroll
+            for (int e = 0; e < 4; e++) {
+                const int wi = v * 4 * kWave + e * kWave + lane;
+                wo[v][e] = 4u * (uint32_t)(wi < Wx ? wi : Wx - 1);
+                okm[v] |= (wi < Wx ? 1 : 0) << e;
+            }
+            ch_ok[v] = okm[v] != 0;
+        }
+    }
+    auto word_ok = [&](int v, int e) { return !UA || ((okm[UA ? v : 0] >> e) & 1) != 0; };
+    // the fp32 parameters under the words of vector v of a parameter row (centroids, gamma, beta)
+    auto load_params = [&](const float* row, int v, if32x4& lo4, if32x4& hi4) {
+        if (!UA) {
+            const int cc = ch_ok[v] ? ch[v] : 0;
+            lo4 = *(const if32x4*)(row + cc);
+            if (BF16) hi4 = *(const if32x4*)(row + cc + 4);
+        } else if (BF16) {  // two channels per word: D is even, so the pairs are 8-byte aligned
+#pragma unroll
+            for (int e = 0; e < 4; e++) {
+                const if32x2 t = *(const if32x2*)((const unsigned char*)row + 2u * wo[UA ? v : 0][e]);
+                if (e < 2) {
+                    lo4[2 * e] = t.x;
+                    lo4[2 * e + 1] = t.y;
+                } else {
+                    hi4[2 * e - 4] = t.x;
+                    hi4[2 * e - 3] = t.y;
+                }
+            }
+        } else {
+#pragma unroll
+            for (int e = 0; e < 4; e++) lo4[e] = *(const float*)((const unsigned char*)row + wo[UA ? v : 0][e]);
+        }
+    };
 
     // rows of tile number i of this workgroup as loaded (rows past N repeat the last row, vectors past D the first
     // one, a tile number past the last repeats the last: no load is conditional)
@@ -180,7 +226,14 @@ __global__ __launch_bounds__(kInferWaves * kWave) void k_infer(const InferParams
             row = row < p.N ? row : p.N - 1;
             const T* x = (const T*)p.lq + row * p.D;
 #pragma unroll
-            for (int v = 0; v < VPR; v++) G[r][v] = *(const iu32x4*)(x + (ch_ok[v] ? ch[v] : 0));
+            for (int v = 0; v < VPR; v++) {
+                if (UA) {
+#pragma unroll
+                    for (int e = 0; e < 4; e++) G[r][v][e] = *(const uint32_t*)((const unsigned char*)x + wo[UA ? v : 0][e]);
+                } else {
+                    G[r][v] = *(const iu32x4*)(x + (ch_ok[v] ? ch[v] : 0));
+                }
+            }
         }
     };
     // bf16 copy of the wave's rows into the LDS tile
@@ -190,7 +243,21 @@ __global__ __launch_bounds__(kInferWaves * kWave) void k_infer(const InferParams
             unsigned char* xr = smem + (size_t)(wave * RPW + r) * p.xstride;
 #pragma unroll
             for (int v = 0; v < VPR; v++) {
-                if (ch_ok[v]) {
+                if (UA) {
+#pragma unroll
+                    for (int e = 0; e < 4; e++) {
+                        if (!word_ok(v, e)) continue;
+                        const int wi = v * 4 * kWave + e * kWave + lane;
+                        if (BF16) {
+                            *(uint32_t*)(xr + 4 * wi) = G[r][v][e];
+                        } else {
+                            const float x0 = __uint_as_float(G[r][v][e]);
+                            const uint32_t h = ipack_bf16(x0, 0.f);
+                            *(uint16_t*)(xr + 2 * wi) = (uint16_t)h;
+                            if (XP == 2) *(uint16_t*)(xr + p.xpart + 2 * wi) = (uint16_t)ipack_bf16(x0 - ilo_half(h), 0.f);
+                        }
+                    }
+                } else if (ch_ok[v]) {
                     if (BF16) {
                         *(iu32x4*)(xr + ch[v] * 2) = G[r][v];
                     } else {
@@ -252,6 +319,8 @@ __global__ __launch_bounds__(kInferWaves * kWave) void k_infer(const InferParams
     // One step of the pipeline.  On entry: Xc holds this wave's rows of tile i, the partial dot products of tile i
     // are in LDS, the rows of tile i + 1 are on their way into Xn, Xf is free.
     float cmax = 0.f;
+    double in_acc = 0.0;  // wave-uniform: this wave's rows
+    const int64_t Nst = p.out ? p.N : 0;  // rows to store
     auto step = [&](Rows& Xc, Rows& Xn, Rows& Xf, int64_t i) {
         const int64_t t = tile_at(i);
         long long fetched = 0;
@@ -301,6 +370,7 @@ __global__ __launch_bounds__(kInferWaves * kWave) void k_infer(const InferParams
                 if (ch_ok[v]) {
 #pragma unroll
                     for (int e = 0; e < 4; e++) {
+                        if (!word_ok(v, e)) continue;
                         if (BF16) {
                             const float x0 = ilo_half(Xc[r][v][e]), x1 = ihi_half(Xc[r][v][e]);
                             xn2 = fmaf(x0, x0, fmaf(x1, x1, xn2));
@@ -331,11 +401,12 @@ __global__ __launch_bounds__(kInferWaves * kWave) void k_infer(const InferParams
 #pragma unroll
                         for (int v = 0; v < VPR; v++) {
                             if (ch_ok[v]) {
-                                const if32x4 c0 = *(const if32x4*)(cr + ch[v]);
+                                if32x4 c0, c1;
+                                load_params(cr, v, c0, c1);
                                 if (BF16) {
-                                    const if32x4 c1 = *(const if32x4*)(cr + ch[v] + 4);
 #pragma unroll
                                     for (int e = 0; e < 4; e++) {
+                                        if (!word_ok(v, e)) continue;
                                         const double d0 = (double)ilo_half(Xc[r][v][e]) - (double)(e < 2 ? c0[2 * e] : c1[2 * e - 4]);
                                         const double d1 = (double)ihi_half(Xc[r][v][e]) - (double)(e < 2 ? c0[2 * e + 1] : c1[2 * e - 3]);
                                         d = fma(d0, d0, d);
@@ -344,6 +415,7 @@ __global__ __launch_bounds__(kInferWaves * kWave) void k_infer(const InferParams
                                 } else {
 #pragma unroll
                                     for (int e = 0; e < 4; e++) {
+                                        if (!word_ok(v, e)) continue;
                                         const double d0 = (double)__uint_as_float(Xc[r][v][e]) - (double)c0[e];
                                         d = fma(d0, d0, d);
                                     }
@@ -357,8 +429,12 @@ __global__ __launch_bounds__(kInferWaves * kWave) void k_infer(const InferParams
                         }
                     }
                 }
-                if (kbest != 0x7fffffff) i1 = kbest;
+                if (kbest != 0x7fffffff) {
+                    i1 = kbest;
+                    if (row < p.N) in_acc += dbest - (double)fmaxf(xn2 + b1, 0.f);  // (the score's share is added below)
+                }
             }
+            if (row < p.N) in_acc += (double)fmaxf(xn2 + b1, 0.f);
             // (non-finite rows have no defined result; whatever they rank first, the index stays inside the tables)
             idx[r] = __builtin_amdgcn_readfirstlane(i1 < p.K ? i1 : p.K - 1);
             if (p.assign && lane == 0 && row < p.N) p.assign[row] = idx[r];
@@ -372,13 +448,8 @@ __global__ __launch_bounds__(kInferWaves * kWave) void k_infer(const InferParams
             const float* br = p.beta + (int64_t)idx[r] * p.D;
 #pragma unroll
             for (int v = 0; v < VPR; v++) {
-                const int cc = ch_ok[v] ? ch[v] : 0;
-                gv[r][v][0] = *(const if32x4*)(gr + cc);
-                bv[r][v][0] = *(const if32x4*)(br + cc);
-                if (BF16) {
-                    gv[r][v][BF16 ? 1 : 0] = *(const if32x4*)(gr + cc + 4);
-                    bv[r][v][BF16 ? 1 : 0] = *(const if32x4*)(br + cc + 4);
-                }
+                load_params(gr, v, gv[r][v][0], gv[r][v][BF16 ? 1 : 0]);
+                load_params(br, v, bv[r][v][0], bv[r][v][BF16 ? 1 : 0]);
             }
         }
         // ---- the rows of tile i + 2 are requested, those of tile i + 1 (in flight since the last step) go to LDS ----
@@ -411,8 +482,21 @@ __global__ __launch_bounds__(kInferWaves * kWave) void k_infer(const InferParams
                 if (!BF16 && p.out_bf16) {  // uniform over the launch
                     const iu32x2 o2 = {ipack_bf16(__uint_as_float(o.x), __uint_as_float(o.y)),
                                        ipack_bf16(__uint_as_float(o.z), __uint_as_float(o.w))};
-                    if (row < p.N && ch_ok[v]) __builtin_nontemporal_store(o2, (iu32x2*)((bf16_t*)p.out + row * p.D + ch[v]));
-                } else if (row < p.N && ch_ok[v]) {
+                    if (UA) {
+                        bf16_t* oh = (bf16_t*)p.out + row * p.D + (v * 4 * kWave + lane);
+#pragma unroll
+                        for (int e = 0; e < 4; e++)
+                            if (row < Nst && word_ok(v, e))
+                                __builtin_nontemporal_store((bf16_t)(o2[e >> 1] >> (16 * (e & 1))), oh + e * kWave);
+                    } else if (row < Nst && ch_ok[v]) {
+                        __builtin_nontemporal_store(o2, (iu32x2*)((bf16_t*)p.out + row * p.D + ch[v]));
+                    }
+                } else if (UA) {
+                    uint32_t* ow = (uint32_t*)orow + (v * 4 * kWave + lane);
+#pragma unroll
+                    for (int e = 0; e < 4; e++)
+                        if (row < Nst && word_ok(v, e)) __builtin_nontemporal_store(o[e], ow + e * kWave);
+                } else if (row < Nst && ch_ok[v]) {
                     __builtin_nontemporal_store(o, (iu32x4*)(orow + ch[v]));
                 }
             }
@@ -458,6 +542,7 @@ __global__ __launch_bounds__(kInferWaves * kWave) void k_infer(const InferParams
             if (tile_at(++i) >= p.ntiles) break;
         }
     }
+    if (p.inertia && lane == 0) atomicAdd(p.inertia, in_acc);
 }
 
 }  // namespace cat

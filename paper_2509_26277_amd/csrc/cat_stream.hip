@@ -296,8 +296,8 @@ __global__ __launch_bounds__(256) void k_count_rep(const int32_t* __restrict__ a
     }
     __syncthreads();
     for (int k = threadIdx.x; k < K; k += blockDim.x) {
-        if (s_cnt[k]) atomicAdd(&counts[k], s_cnt[k]);
-        if (s_rep[k] != ~0ull) atomicMin(&rep[k], s_rep[k]);
+        if (counts && s_cnt[k]) atomicAdd(&counts[k], s_cnt[k]);
+        if (rep && s_rep[k] != ~0ull) atomicMin(&rep[k], s_rep[k]);
     }
 }
 cat_status launch_count_rep(const int32_t* assign, int64_t N, int32_t K, int32_t* counts,

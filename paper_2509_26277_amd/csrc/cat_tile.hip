@@ -1,6 +1,7 @@
 // MFMA tile kernels of the CAT hot path: host side (variant selection, workspace, the Lloyd
 // driver) and the centroid preparation kernel.  The tile kernel itself is in cat_tile_kernel.h.
 #include "cat_tile_kernel.h"
+#include "cat_infer.h"
 
 namespace cat {
 
@@ -468,7 +469,8 @@ static size_t packA_bytes(int64_t D, int32_t K) {
 static inline size_t a256(size_t x) { return (x + 255) & ~(size_t)255; }
 
 size_t tile_workspace_bytes(int64_t D, int32_t K, cat_dtype dt) {
-    if (!tile_config(TILE_ASSIGN, D, K, dt).ok) return 0;
+    // (the row-tile inference kernel shares this scratch and also takes rows that are not whole 16-byte groups)
+    if (!tile_config(TILE_ASSIGN, D, K, dt).ok && !infer_supported(1, D, K, dt)) return 0;
     return a256(packA_bytes(D, K)) + a256(16 * 16 * 4 * sizeof(float)) + a256((size_t)K * D * sizeof(float));
 }
 TileWs tile_carve(void* base, int64_t D, int32_t K, cat_dtype dt) {

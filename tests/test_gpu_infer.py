@@ -97,7 +97,7 @@ def test_exact_ties_go_to_the_lowest_index():
 
 
 def test_forcing_it_on_a_shape_without_an_instance_is_an_error():
-    lq, cent, gamma, beta = _mixture(64, 7, 3, seed=1)  # rows of 28 bytes: not whole 16-byte groups
+    lq, cent, gamma, beta = _mixture(400, 8, 300, seed=1)  # more than 256 clusters
     with pytest.raises(binding.CatError) as e:
         _run(lq, cent, gamma, beta, "f32", 1.0, which=2)
     assert e.value.status == 2

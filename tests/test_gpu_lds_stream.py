@@ -47,9 +47,11 @@ def _data(N, D, K, dt, seed):
 def _auto_path():
     binding.select_path(binding.CAT_PATH_AUTO)
     binding.debug_padded_fit(False)  # the Lloyd loops here are this kernel's, not those on a zero-padded copy of the rows
+    binding.debug_apply_kernel(1)    # and the inference passes too, not the row-tile kernel's word-by-word instances
     yield
     binding.select_path(binding.CAT_PATH_AUTO)
     binding.debug_padded_fit(True)
+    binding.debug_apply_kernel(0)
 
 
 @pytest.mark.parametrize("N,D,K,dt", SHAPES)
