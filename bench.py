@@ -285,8 +285,9 @@ def _run_workload(name, args, torch, np, cpu_budget_s, extras):
                       multi_k_ratio=t_multi / sum(t_sep.values()), multi_k_upto32_ms=t_small,
                       multi_k_upto32_separate_ms=sum(t_sep[k] for k in small))
 
-    # ---- a shape outside the matrix-core kernels (one more channel: rows are no longer whole 16-byte groups), which
-    # takes the LDS streaming kernel; beside it the same calls on the workload's own, aligned shape ----
+    # ---- a shape outside the matrix-core tile kernels (one more channel: rows are no longer whole 16-byte groups): single
+    # passes take the row-tile kernel's word-by-word form, fits a zero-padded copy; beside them the same calls on the
+    # workload's own, aligned shape and on the LDS streaming kernel ----
     if extras and fit_kind and dt == "f32" and not args.no_seeding:
         from paper_2509_26277_amd import cat_assign
         r = state["fit"]
@@ -296,6 +297,12 @@ def _run_workload(name, args, torch, np, cpu_budget_s, extras):
         ws_o = torch.empty(binding.cat_fit_workspace_bytes(N, D + 1, K, dtc), dtype=torch.uint8, device="cuda")
         t_as = _events(lambda: cat_assign(lq_o, cent_o, workspace=ws_o), 5, torch)
         t_ap = _events(lambda: cat_apply(lq_o, cent_o, g_o, b_o, out=out_o, workspace=ws_o), 5, torch)
+        binding.debug_apply_kernel(1)  # the same calls on the LDS streaming kernel (the shapes without a row-tile instance)
+        try:
+            t_as_lds = _events(lambda: cat_assign(lq_o, cent_o, workspace=ws_o), 5, torch)
+            t_ap_lds = _events(lambda: cat_apply(lq_o, cent_o, g_o, b_o, out=out_o, workspace=ws_o), 5, torch)
+        finally:
+            binding.debug_apply_kernel(0)
         t_as0 = _events(lambda: cat_assign(lq, r["centroids"], workspace=ws_fit), 5, torch)
         # the whole fit of those rows: its Lloyd loop runs on a zero-padded copy (the default), or on the LDS kernel
         fp_o = pad(fp)
@@ -309,7 +316,8 @@ def _run_workload(name, args, torch, np, cpu_budget_s, extras):
         detail.update(stream_shape=f"N={N} D={D + 1} K={K}", stream_assign_us=1e3 * t_as,
                       stream_assign_GBps=N * (D + 1) * esize / t_as / 1e6, stream_apply_us=1e3 * t_ap,
                       stream_apply_GBps=(2 * N * (D + 1) * esize + 4 * N) / t_ap / 1e6,
-                      aligned_assign_us=1e3 * t_as0, stream_shape_fit_ms=t_fit_pad, stream_shape_fit_lds_kernel_ms=t_fit_lds)
+                      aligned_assign_us=1e3 * t_as0, stream_shape_fit_ms=t_fit_pad, stream_shape_fit_lds_kernel_ms=t_fit_lds,
+                      stream_assign_lds_kernel_us=1e3 * t_as_lds, stream_apply_lds_kernel_us=1e3 * t_ap_lds)
         del lq_o, out_o, ws_o, fp_o
 
     # context: plain device copy of the same matrix

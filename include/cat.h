@@ -87,7 +87,12 @@ cat_status cat_select_path(cat_path p);
  * shape; the statistics read the original rows.  For those shapes the scratch sizes
  * of the fits include the copy (N rows of the padded length).
  * cat_debug_padded_fit(on): 0 keeps such fits on the streaming kernels; process-wide,
- * default 1, for measurements and tests (results agree to rounding). */
+ * default 1, for measurements and tests (results agree to rounding).
+ * Single passes over such rows (cat_apply, cat_apply_lp, cat_apply_static, cat_assign,
+ * fits of fewer than two iterations) run the fused row-tile inference kernel in a form
+ * that moves rows, parameters and outputs in 4-byte words (K <= 128; rows of at most
+ * 4 KB for fp32, 2 KB for bf16; for 33 .. 64 clusters at most 2 KB), and the LDS
+ * streaming kernel beyond that. */
 size_t cat_fit_workspace_bytes(int64_t N, int64_t D, int32_t K, cat_dtype dt);
 cat_status cat_debug_padded_fit(int on);
 size_t cat_apply_workspace_bytes(int64_t N, int64_t D, int32_t K, cat_dtype dt);

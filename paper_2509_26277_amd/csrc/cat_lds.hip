@@ -106,9 +106,22 @@ __global__ __launch_bounds__(kLT, 2) void k_assign_lds(const T* __restrict__ lq,
                     xr[i] = ld_elem(base + (int64_t)(rr < last ? rr : last) * Dv);
                 }
             };
+            // the same chunk of the group's centroids, one chunk ahead like the rows (clusters past K repeat the last
+            // one, channels past D the last channel; zeroed on the way into LDS)
+            float cr[KG * kLC / kLT];
+            auto cfetch = [&](int c) {
+                const int64_t ch = (int64_t)c * kLC + ech;
+                const int64_t chc = ch < D ? ch : D - 1;
+#pragma unroll
+                for (int i = 0; i < KG * kLC / kLT; i++) {
+                    const int k = k0 + erow + 8 * i;
+                    cr[i] = cent[(int64_t)(k < K ? k : K - 1) * D + chc];
+                }
+            };
             fetch(0);
+            cfetch(0);
             for (int c = 0; c < nchunks; c++) {
-                // rows of chunk c: registers -> LDS; centroids of chunk c: global -> LDS
+                // chunk c of the rows and of the centroids: registers -> LDS
 #pragma unroll
                 for (int i = 0; i < kLPT; i++)
                     xs[(erow + 8 * i) * kLS + ech] = (row0 + erow + 8 * i < N && (int64_t)c * kLC + ech < D) ? xr[i] : 0.f;
@@ -117,11 +130,14 @@ __global__ __launch_bounds__(kLT, 2) void k_assign_lds(const T* __restrict__ lq,
 #pragma unroll
                     for (int i = 0; i < KG * kLC / kLT; i++) {
                         const int k = erow + 8 * i;
-                        cs[k * kLS + ech] = (k0 + k < K && ch < D) ? cent[(int64_t)(k0 + k) * D + ch] : 0.f;
+                        cs[k * kLS + ech] = (k0 + k < K && ch < D) ? cr[i] : 0.f;
                     }
                 }
                 __syncthreads();
-                if (c + 1 < nchunks) fetch(c + 1);
+                // chunk c + 1 is requested by every wave on every pass (after the last chunk: the last one again, unused),
+                // so that the compiler can count the loads in flight instead of waiting for all of them
+                fetch(c + 1 < nchunks ? c + 1 : c);
+                cfetch(c + 1 < nchunks ? c + 1 : c);
                 const float* xrow = xs + tid * kLS;
 #pragma unroll 1
                 for (int j = 0; j < kLC; j += 4) {
