@@ -55,16 +55,16 @@ HBM_PEAK_GBPS = 8000.0
 # line says that it comes from profiles/, not from this run.
 TRAFFIC_SOURCES = {
     "k_tile": ("cat_tile_kernel.h", "0f732d784bfed8b74f358ef562b497768225e66f55b3d667b2e2e619ce7805a6"),
-    "k_infer": ("cat_infer_kernel.h", "51a36cc34f1aa27276dfdf2a541bcd6ac8dec90f13d45532a9c66e593cd1a7ff"),
+    "k_infer": ("cat_infer_kernel.h", "d243d921fdcd31650ab229d15f5f562a3fb2bcae57aa0e239eb2055818ac6c93"),
 }
 TRAFFIC_COUNTERS = {
-    "cfg2": ("k_tile", (133761.8, 128011.7, 298.5, 256000.0)),
-    "cfg2_apply": ("k_infer", (129272.7, 128011.7, 265645.6, 256000.0)),
-    "cfg3": ("k_tile", (527777.6, 524299.7, 4721.8, 1048576.0)),
-    "cfg3_apply": ("k_infer", (524885.8, 524299.7, 1054740.7, 1048576.0)),
-    "cfg4": ("k_tile", (560508.0, 524299.7, 1191.2, 1048576.0)),
-    "cfg4_apply": ("k_tile", (1145757.6, 524299.7, 1049648.0, 1048576.0)),
-    "cfg5_apply": ("k_infer", (4197634.2, 4194317.2, 8413243.8, 8388608.0)),
+    "cfg2": ("k_tile", (133769.7, 128011.7, 299.2, 256000.0)),
+    "cfg2_apply": ("k_infer", (129303.0, 128011.7, 265720.2, 256000.0)),
+    "cfg3": ("k_tile", (527781.1, 524299.7, 4721.3, 1048576.0)),
+    "cfg3_apply": ("k_infer", (524886.2, 524299.7, 1054738.5, 1048576.0)),
+    "cfg4": ("k_tile", (560474.5, 524299.7, 1192.3, 1048576.0)),
+    "cfg4_apply": ("k_tile", (1145720.1, 524299.7, 1049647.4, 1048576.0)),
+    "cfg5_apply": ("k_infer", (4197668.8, 4194317.5, 8413242.2, 8388608.0)),
 }
 
 
