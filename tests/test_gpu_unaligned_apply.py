@@ -174,3 +174,34 @@ def test_assignment_step_without_the_map(N, D, K, dt):
         check_values(host_matrix(r["centroids"]), o["centroids"], 1e-6, "centroids")
         check_values(host_matrix(r["gamma"]), o["gamma"], RTOL[dt], "gamma")
     np.testing.assert_allclose(r["inertia"].cpu().numpy(), o["inertia"], rtol=1e-4)
+
+
+def test_captures_into_a_hip_graph_and_replays():
+    N, D, K = 5000, 1001, 16
+    x, cent, gamma, beta = _problem(3, N, D, K, "f32")
+    xd = dev_matrix(x, "f32")
+    c, g, b = (torch.from_numpy(a).cuda() for a in (cent, gamma, beta))
+    ws = torch.empty(binding.cat_apply_workspace_bytes(N, D, K), dtype=torch.uint8, device="cuda")
+    out = torch.empty_like(xd)
+
+    def run():
+        return cat_apply(xd, c, g, b, alpha=0.6, out=out, workspace=ws)
+
+    ref_out, ref_a = (t.clone() for t in run())
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        run()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        o, a = run()
+    for _ in range(3):
+        o.zero_()
+        a.zero_()
+        ws.zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(o, ref_out) and torch.equal(a, ref_a)

@@ -26,7 +26,8 @@ def _rows(N, cent, seed, dtype):
     return torch.from_numpy(x).cuda()
 
 
-@pytest.mark.parametrize("dtype,D,K", [("f32", 512, 128), ("f32", 1000, 16), ("bf16", 256, 48), ("f32", 37, 5)])
+@pytest.mark.parametrize("dtype,D,K", [("f32", 512, 128), ("f32", 1000, 16), ("bf16", 256, 48), ("f32", 37, 5),
+                                        ("f32", 1001, 16), ("bf16", 1002, 16)])
 def test_two_calls_in_a_row_match_cat_apply(dtype, D, K):
     """Two calls in a row on the one built-in scratch array, the second on a smaller input with other parameters
     (fewer rows, fewer clusters): each must equal cat_apply with a caller workspace bit for bit."""
