@@ -159,6 +159,13 @@ def _run_workload(name, args, torch, np, cpu_budget_s, extras):
         detail.update(fit_ms=t_fit, fit_iters0_ms=t_fit0, lloyd_iter_us=1e3 * t_iter,
                       lloyd_iters_per_s=1e3 / t_iter, lloyd_rows_per_s=N * 1e3 / t_iter,
                       lloyd_iter_frac_hbm=alg_bytes / t_iter / 1e6 / HBM_PEAK_GBPS)
+        # the two segmented-sum steps as calls of their own (the ordering of the rows, the zeroing and the finishing
+        # kernels included): the statistics read lq and fp once, the centroid update lq once
+        from paper_2509_26277_amd import cat_stats, cat_update
+        t_stats = _events(lambda: cat_stats(lq, fp, r["assignments"], K, centroids=r["centroids"], workspace=ws_fit), reps, torch)
+        t_upd = _events(lambda: cat_update(lq, r["assignments"], r["centroids"], workspace=ws_fit), reps, torch)
+        detail.update(stats_call_us=1e3 * t_stats, stats_call_frac_hbm=2 * alg_bytes / t_stats / 1e6 / HBM_PEAK_GBPS,
+                      update_call_us=1e3 * t_upd, update_call_frac_hbm=alg_bytes / t_upd / 1e6 / HBM_PEAK_GBPS)
         # the dominant kernel by itself: events around every k_tile launch of `reps` fits
         binding.profile_enable(True)
         for _ in range(reps):
