@@ -54,56 +54,79 @@ __global__ __launch_bounds__(kPpWaves* kWave) void k_pp_update(const T* __restri
     const T* c = x + idx[t - 1] * D;  // the row chosen last
     const int64_t row0 = (int64_t)blockIdx.x * kPpGroup + (int64_t)wave * kPpRowsPerWave;
     double run = 0.0;  // lane 0: the wave's rows, in row order
-    for (int r = 0; r < kPpRowsPerWave; r += RPI) {
+    // RU row groups at a time: all their loads are requested before the first sum, and the chosen row is read once for
+    // all of them.  Every load is unconditional (rows past the end repeat the last row, a second vector past the row
+    // repeats the first), so that they overlap; what a row adds up, and in which order, does not depend on RU.
+    constexpr int RU = 4;
+    for (int r = 0; r < kPpRowsPerWave; r += RPI * RU) {
         if (row0 + r >= N) break;  // wave-uniform
-        const bool row_ok = row0 + r + grp < N;
-        const int64_t row = row_ok ? row0 + r + grp : N - 1;
-        const T* xr = x + row * D;
-        // the row's distance so far, requested ahead of the row itself (its leader lane needs it at the end)
-        double old = 0.0;
-        if (t > 1 && sub == 0 && row_ok) old = d2[row];
-        double s = 0.0;
+        bool row_ok[RU];
+        int64_t row[RU];
+        const T* xr[RU];
+        double old[RU], s[RU];
+#pragma unroll
+        for (int u = 0; u < RU; u++) {
+            const int64_t rr = row0 + r + u * RPI + grp;
+            row_ok[u] = rr < N;
+            row[u] = row_ok[u] ? rr : N - 1;
+            xr[u] = x + row[u] * D;
+            // the row's distance so far, requested ahead of the row itself (its leader lane needs it at the end)
+            old[u] = d2[row[u]];
+            s[u] = 0.0;
+        }
         if (WIDE) {
             const int64_t step = (int64_t)GROUP * EPL;
             for (int64_t j0 = (int64_t)sub * EPL; j0 < D; j0 += 2 * step) {
                 const int64_t j1 = j0 + step;
                 const bool two = j1 < D;
-                float xa[8], ca[8], xb[8], cb[8];
-                ld16(xr + j0, xa);
+                float xa[RU][8], xb[RU][8], ca[8], cb[8];
                 ld16(c + j0, ca);
-                ld16(xr + (two ? j1 : j0), xb);
                 ld16(c + (two ? j1 : j0), cb);
 #pragma unroll
-                for (int e = 0; e < EPL; e++) {
-                    const double d = (double)xa[e] - (double)ca[e];
-                    s = fma(d, d, s);
+                for (int u = 0; u < RU; u++) {
+                    ld16(xr[u] + j0, xa[u]);
+                    ld16(xr[u] + (two ? j1 : j0), xb[u]);
                 }
-                if (two) {
+#pragma unroll
+                for (int u = 0; u < RU; u++) {
 #pragma unroll
                     for (int e = 0; e < EPL; e++) {
-                        const double d = (double)xb[e] - (double)cb[e];
-                        s = fma(d, d, s);
+                        const double d = (double)xa[u][e] - (double)ca[e];
+                        s[u] = fma(d, d, s[u]);
+                    }
+                    if (two) {
+#pragma unroll
+                        for (int e = 0; e < EPL; e++) {
+                            const double d = (double)xb[u][e] - (double)cb[e];
+                            s[u] = fma(d, d, s[u]);
+                        }
                     }
                 }
             }
         } else {
             for (int64_t j = sub; j < D; j += GROUP) {
-                const double d = (double)ld_elem(xr + j) - (double)ld_elem(c + j);
-                s = fma(d, d, s);
+                const double cj = (double)ld_elem(c + j);
+#pragma unroll
+                for (int u = 0; u < RU; u++) {
+                    const double d = (double)ld_elem(xr[u] + j) - cj;
+                    s[u] = fma(d, d, s[u]);
+                }
             }
         }
 #pragma unroll
-        for (int o = GROUP / 2; o > 0; o >>= 1) s += __shfl_xor(s, o, kWave);
-        double v = s;
-        if (sub == 0 && row_ok) {
-            if (t > 1) v = s < old ? s : old;
-            d2[row] = v;
-        }
-        if (!row_ok) v = 0.0;
+        for (int u = 0; u < RU; u++) {
+            double su = s[u];
 #pragma unroll
-        for (int g = 0; g < RPI; g++) {  // the group leaders' values reach lane 0 in row order
-            const double vg = __shfl(v, g * GROUP, kWave);
-            run += vg;
+            for (int o = GROUP / 2; o > 0; o >>= 1) su += __shfl_xor(su, o, kWave);
+            double v = su;
+            if (t > 1) v = su < old[u] ? su : old[u];
+            if (sub == 0 && row_ok[u]) d2[row[u]] = v;
+            if (!row_ok[u]) v = 0.0;
+#pragma unroll
+            for (int g = 0; g < RPI; g++) {  // the group leaders' values reach lane 0 in row order
+                const double vg = __shfl(v, g * GROUP, kWave);
+                run += vg;
+            }
         }
     }
     if (lane == 0) s_sum[wave] = run;
