@@ -327,9 +327,14 @@ def _run_workload(name, args, torch, np, cpu_budget_s, extras):
                       stream_assign_lds_kernel_us=1e3 * t_as_lds, stream_apply_lds_kernel_us=1e3 * t_ap_lds)
         del lq_o, out_o, ws_o, fp_o
 
-    # context: plain device copy of the same matrix
+    # context: plain device copy of the same matrix, and what a kernel that only streams it reaches (one read; a read and a write)
     t_copy = _events(lambda: out.copy_(lq), 5, torch)
     detail["device_copy_GBps"] = 2 * N * D * esize / t_copy / 1e6
+    if (N * D * esize) % 16 == 0:
+        t_rd = _events(lambda: binding.stream_probe(lq), 5, torch)
+        t_cp = _events(lambda: binding.stream_probe(lq, out), 5, torch)
+        detail.update(stream_read_GBps=N * D * esize / t_rd / 1e6, stream_read_frac_hbm=N * D * esize / t_rd / 1e6 / HBM_PEAK_GBPS,
+                      stream_copy_GBps=2 * N * D * esize / t_cp / 1e6, stream_copy_frac_hbm=2 * N * D * esize / t_cp / 1e6 / HBM_PEAK_GBPS)
 
     # ---- the oracle on the host cores, bounded sample ----
     cpu = None

@@ -467,6 +467,19 @@ cat_status cat_profile_enable(int on);
 int cat_profile_read(float *ms_out, int cap);
 
 /*
+ * What the memory system gives a kernel that does nothing else, for benchmarks: the yardstick beside the 8 TB/s
+ * peak for the passes above, which are bound by one read (assignment, sums) or by a read and a write (inference) of
+ * the rows.  One launch streams `bytes` bytes from src: dst == NULL reads them and keeps nothing, else copies them to
+ * dst.  Blocks of 256 lanes walk contiguous spans, 16 bytes per lane, four loads in flight per lane.
+ *
+ * src    in,  device, bytes (a multiple of 16), 16-byte aligned
+ * dst    out, device, bytes, 16-byte aligned, or NULL
+ * Enqueues on the stream; no allocation, no synchronisation.  CAT_ERR_INVALID_ARG for a null or misaligned
+ * pointer or a size that is zero or not a multiple of 16.
+ */
+cat_status cat_stream_probe(const void *src, void *dst, size_t bytes, void *hip_stream);
+
+/*
  * Test hook.  In the fused Lloyd loop (cat_fit on the tile path) every workgroup collects the rows
  * that changed cluster in a list in fast memory before appending them to the device-wide list; a
  * workgroup whose list is full appends tile by tile instead.  This call sets the capacity of that

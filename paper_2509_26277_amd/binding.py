@@ -28,7 +28,7 @@ EXPORTS = ("cat_select_path", "cat_fit_workspace_bytes", "cat_apply_workspace_by
            "cat_apply_static", "cat_apply_static_max_workspace_bytes", "cat_debug_apply_kernel",
            "cat_fit_multi_k_workspace_bytes", "cat_fit_multi_k", "cat_debug_multi_group_tiles",
            "cat_params_to_bf16", "cat_apply_lp_workspace_bytes", "cat_apply_lp",
-           "cat_fit_bounds_workspace_bytes", "cat_fit_bounds", "cat_debug_padded_fit")
+           "cat_fit_bounds_workspace_bytes", "cat_fit_bounds", "cat_debug_padded_fit", "cat_stream_probe")
 
 
 class CatError(RuntimeError):
@@ -131,6 +131,8 @@ def load_library():
     lib.cat_apply_lp.restype = c.c_int
     lib.cat_debug_multi_group_tiles.argtypes = [c.c_int]
     lib.cat_debug_multi_group_tiles.restype = c.c_int
+    lib.cat_stream_probe.argtypes = [vp, vp, sz, vp]
+    lib.cat_stream_probe.restype = c.c_int
     lib.cat_debug_padded_fit.argtypes = [c.c_int]
     lib.cat_debug_padded_fit.restype = c.c_int
     lib.cat_debug_apply_kernel.argtypes = [c.c_int]
@@ -472,6 +474,14 @@ def cat_fit_restarts(lq, fp, K, iters, seed=0, restarts=4, seeding=CAT_SEED_ROWS
                                 workspace.data_ptr(), workspace.numel(), _stream()))
     return dict(centroids=cent, gamma=gamma, beta=beta, assignments=a, counts=counts, inertia=inertia, best_run=best,
                 final_inertia=finals)
+
+
+def stream_probe(src, dst=None):
+    """One launch that only reads ``src`` (``dst`` None) or copies it to ``dst``: what the memory system gives (cat_stream_probe)."""
+    nbytes = src.numel() * src.element_size()
+    if dst is not None and dst.numel() * dst.element_size() != nbytes:
+        raise ValueError("dst must have the size of src")
+    _check(load_library().cat_stream_probe(src.data_ptr(), None if dst is None else dst.data_ptr(), nbytes, _stream()))
 
 
 def debug_padded_fit(on):

@@ -330,6 +330,13 @@ int cat_profile_read(float* ms_out, int cap) {
     return (int)pairs;
 }
 
+cat_status cat_stream_probe(const void* src, void* dst, size_t bytes, void* hip_stream) {
+    CAT_TRY(check_ptr("cat_stream_probe", "src", src, 16));
+    if (dst) CAT_TRY(check_ptr("cat_stream_probe", "dst", dst, 16));
+    if (bytes == 0 || bytes % 16) return set_error(CAT_ERR_INVALID_ARG, "cat_stream_probe: bytes = %zu is not a positive multiple of 16", bytes);
+    return launch_stream_probe(src, dst, bytes, (hipStream_t)hip_stream);
+}
+
 cat_status cat_debug_list_capacity(int entries) {
     if (entries < 0 || entries > 1024)
         return set_error(CAT_ERR_INVALID_ARG, "cat_debug_list_capacity: %d is outside 0 .. 1024", entries);

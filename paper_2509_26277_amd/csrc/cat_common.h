@@ -123,6 +123,8 @@ cat_status launch_fill_u64(unsigned long long* p, int64_t n, unsigned long long 
 // dst (rows x dst_ld) <- the first `cols` columns of src (rows x src_ld), zeros in the columns from `cols` on
 cat_status launch_copy_cols(const float* src, int64_t rows, int32_t src_ld, float* dst, int32_t dst_ld, int32_t cols,
                             hipStream_t st);
+// cat_stream_probe: a pure read of `bytes` bytes (dst == nullptr) or a pure copy
+cat_status launch_stream_probe(const void* src, void* dst, size_t bytes, hipStream_t st);
 // dst (rows x dst_ld) <- the first dst_ld columns of src (rows x src_ld), zeros where src has none; elements of dtype dt
 cat_status launch_pad_rows(const void* src, cat_dtype dt, int64_t rows, int64_t src_ld, int64_t dst_ld, void* dst, hipStream_t st);
 // inference with the PCA front-end in one kernel (cat_pca.hip), where the shape allows it
