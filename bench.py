@@ -335,6 +335,10 @@ def _run_workload(name, args, torch, np, cpu_budget_s, extras):
         t_cp = _events(lambda: binding.stream_probe(lq, out), 5, torch)
         detail.update(stream_read_GBps=N * D * esize / t_rd / 1e6, stream_read_frac_hbm=N * D * esize / t_rd / 1e6 / HBM_PEAK_GBPS,
                       stream_copy_GBps=2 * N * D * esize / t_cp / 1e6, stream_copy_frac_hbm=2 * N * D * esize / t_cp / 1e6 / HBM_PEAK_GBPS)
+        # beside each kernel's fraction of the peak: the fraction a kernel that only streams the same bytes reaches
+        if roof is not None and roof is not apply_roof:
+            roof["stream_probe_frac"] = detail["stream_read_frac_hbm"]
+        apply_roof["stream_probe_frac"] = detail["stream_copy_frac_hbm"]
 
     # ---- the oracle on the host cores, bounded sample ----
     cpu = None
