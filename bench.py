@@ -1,15 +1,17 @@
 #!/usr/bin/env python3
 """Benchmark of the CAT hot path on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload all|cfg1..cfg5] [--no-cpu]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload all|cfg1..cfg5|cfg2u] [--no-cpu]
 
 One step = one pass of the whole hot path over one synthetic batch that is
 already resident in HBM: cat_fit (seeded init, `iters` Lloyd iterations, final
 assignment, per-cluster affine fit) followed by cat_apply on the same rows
 (inference-only workload cfg5: cat_apply alone).  Prints ONE JSON line.
 
-With no --workload (or "all") the five workloads run one after the other in this
-process.  The top-level fields are those of cfg3, the largest fitting workload
+With no --workload (or "all") the five workloads, and cfg2u (cfg2 with one more
+channel: rows that are not whole 16-byte groups, so the fit's Lloyd loop runs on a
+zero-padded copy and the inference pass reads and writes word by word), run one
+after the other in this process.  The top-level fields are those of cfg3, the largest fitting workload
 (1 GiB of rows like cfg4, and the most rows: the metric counts rows); `configs`
 holds, for every workload, the same figures: value, ms_per_step, roofline (the
 assignment pass), apply_roofline (the fused inference pass), the whole Lloyd
@@ -388,7 +390,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=5)
     ap.add_argument("--warmup", type=int, default=2)
-    ap.add_argument("--workload", default="all", choices=["all", "cfg1", "cfg2", "cfg3", "cfg4", "cfg5"])
+    ap.add_argument("--workload", default="all", choices=["all", "cfg1", "cfg2", "cfg3", "cfg4", "cfg5", "cfg2u"])
     ap.add_argument("--rows", type=int, default=None, help="override N (debugging; the result is then not the named workload)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
     ap.add_argument("--hot-path-only", action="store_true",
@@ -425,7 +427,7 @@ def main():
     else:
         # the oracle's time is shared out: most of it to the headline workload, a few seconds to each of the others
         per = {}
-        for name in ("cfg1", "cfg2", "cfg3", "cfg4", "cfg5"):
+        for name in ("cfg1", "cfg2", "cfg3", "cfg4", "cfg5", "cfg2u"):
             per[name] = _run_workload(name, args, torch, np, 12.0 if name == HEADLINE else 4.0, extras=(name == "cfg2"))
             torch.cuda.empty_cache()
         top = per[HEADLINE]
