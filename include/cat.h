@@ -121,7 +121,13 @@ size_t cat_apply_workspace_bytes(int64_t N, int64_t D, int32_t K, cat_dtype dt);
  * counts          out, K int32, nullable: rows per cluster of `assignments`
  * inertia         out, iters + 1 doubles, nullable: k-means objective (sum of
  *                 squared distances to the assigned centroid) of each of the
- *                 iters + 1 assignment passes
+ *                 iters + 1 assignment passes.  On the tile kernels a row's term is
+ *                 |x|^2 plus its best score in single precision (exact only for the rows
+ *                 that go through the double-precision re-rank), so its error is the error
+ *                 bound of a score, about 1e-4 |x||c| (3e-5 for bfloat16 rows): far below
+ *                 1e-4 of the sum where the rows are as far from their centroid as from the
+ *                 origin, a larger share of it where the data sit far from the origin
+ *                 compared with their spread.  The assignments do not depend on it.
  */
 cat_status cat_fit(const void *lq, const void *fp, int64_t N, int64_t D, int32_t K,
                    int32_t iters, uint64_t seed, cat_dtype dt,
@@ -488,6 +494,18 @@ cat_status cat_stream_probe(const void *src, void *dst, size_t bytes, void *hip_
  * CAT_ERR_INVALID_ARG outside that range.  Not thread-safe.
  */
 cat_status cat_debug_list_capacity(int entries);
+
+/*
+ * Test hook.  In the assignment passes of the tile path (cat_assign, the passes of cat_fit without distance
+ * bounds), a row whose two best scores are within the error bound of the split arithmetic is measured exactly,
+ * in double precision.  A workgroup does not do that where it finds the row: it queues the row in fast memory
+ * and its waves share the queued rows out when the workgroup has no tiles left; a row that finds the queue
+ * full, or has more than 8 candidates, is measured on the spot.  This call sets the capacity of the queue for
+ * later calls of the process (1 .. 256 entries; 0 restores the default, 256; -1: no queue, every such row is
+ * measured on the spot), so that both ways can be reached on small inputs.  Results never depend on it.
+ * CAT_ERR_INVALID_ARG outside that range.  Not thread-safe.
+ */
+cat_status cat_debug_rerank_queue(int entries);
 
 /*
  * Test hook.  cat_apply (and cat_apply_static) on the fused path has two kernels: one that keeps a tile of rows

@@ -20,7 +20,7 @@ _STATUS = {0: "CAT_OK", 1: "CAT_ERR_INVALID_ARG", 2: "CAT_ERR_UNSUPPORTED", 3: "
 
 EXPORTS = ("cat_select_path", "cat_fit_workspace_bytes", "cat_apply_workspace_bytes", "cat_fit", "cat_apply",
            "cat_assign", "cat_update", "cat_stats", "cat_init_indices", "cat_last_error", "cat_profile_enable",
-           "cat_profile_read", "cat_debug_list_capacity", "cat_pca_workspace_bytes", "cat_pca_fit", "cat_pca_project",
+           "cat_profile_read", "cat_debug_list_capacity", "cat_debug_rerank_queue", "cat_pca_workspace_bytes", "cat_pca_fit", "cat_pca_project",
            "cat_apply_assigned", "cat_fit_pca_workspace_bytes", "cat_fit_pca", "cat_apply_pca_workspace_bytes", "cat_apply_pca",
            "cat_alpha_sweep_workspace_bytes", "cat_alpha_sweep", "cat_top1",
            "cat_init_kmeanspp_workspace_bytes", "cat_init_kmeanspp",
@@ -139,6 +139,8 @@ def load_library():
     lib.cat_debug_apply_kernel.restype = c.c_int
     lib.cat_debug_list_capacity.argtypes = [c.c_int]
     lib.cat_debug_list_capacity.restype = c.c_int
+    lib.cat_debug_rerank_queue.argtypes = [c.c_int]
+    lib.cat_debug_rerank_queue.restype = c.c_int
     lib.cat_last_error.argtypes = []
     lib.cat_last_error.restype = c.c_char_p
     _lib = lib
@@ -186,6 +188,11 @@ def allow_early_stop(on):
 def debug_list_capacity(entries):
     """Test hook: capacity of the per-workgroup changed-row list of the fused Lloyd loop (0 = default)."""
     _check(load_library().cat_debug_list_capacity(int(entries)))
+
+
+def debug_rerank_queue(entries):
+    """Test hook: capacity of the per-workgroup queue of rows whose exact re-rank is put off (0 = default, -1 = no queue)."""
+    _check(load_library().cat_debug_rerank_queue(int(entries)))
 
 
 def debug_apply_kernel(which):

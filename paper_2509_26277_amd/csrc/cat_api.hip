@@ -36,6 +36,8 @@ bool fast_paths_forced() { return g_path.load() == CAT_PATH_TILE; }
 static std::atomic<int> g_apply_kernel{0};  // cat_debug_apply_kernel
 static std::atomic<int> g_list_cap{1024};
 int lloyd_list_capacity() { return g_list_cap.load(); }
+static std::atomic<int> g_queue_cap{256};
+int rerank_queue_capacity() { return g_queue_cap.load(); }
 
 cat_status profile_mark(bool begin, hipStream_t st) {
     (void)begin;
@@ -341,6 +343,13 @@ cat_status cat_debug_list_capacity(int entries) {
     if (entries < 0 || entries > 1024)
         return set_error(CAT_ERR_INVALID_ARG, "cat_debug_list_capacity: %d is outside 0 .. 1024", entries);
     g_list_cap.store(entries == 0 ? 1024 : entries);
+    return CAT_OK;
+}
+
+cat_status cat_debug_rerank_queue(int entries) {
+    if (entries < -1 || entries > 256)
+        return set_error(CAT_ERR_INVALID_ARG, "cat_debug_rerank_queue: %d is outside -1 .. 256", entries);
+    g_queue_cap.store(entries == 0 ? 256 : (entries < 0 ? 0 : entries));
     return CAT_OK;
 }
 

@@ -100,6 +100,8 @@ cat_status launch_multi_column(const int32_t* assign16, int64_t N, int32_t s, in
 
 // Capacity of the per-workgroup changed-row list (cat_debug_list_capacity in cat.h).
 int lloyd_list_capacity();
+// Capacity of the per-workgroup queue of rows whose exact re-rank is put off (cat_debug_rerank_queue in cat.h).
+int rerank_queue_capacity();
 
 // Kernel timing hooks (see cat_profile_enable in cat.h): bracket one launch with events.
 bool profile_on();

@@ -498,6 +498,13 @@ static TileCfg tile_config(TileMode mode, int64_t D, int32_t K, cat_dtype dt, bo
             t.off_misc = up16(off);
             off = t.off_misc + 16 + 8 * kMaxWaves + 8 * 16;  // list count, objective per wave, objective per centroid set
             if (off > kLdsLimit) continue;
+            // assignment passes: the queue of rows whose exact re-rank waits for the end of the workgroup's tiles,
+            // where the layout leaves room for it
+            if (mode != TILE_APPLY && up16(off) + 16 + (size_t)kQueueCap * sizeof(DeferredRow) <= kLdsLimit) {
+                t.off_queue = up16(off);
+                t.queue_cap = kQueueCap;
+                off = t.off_queue + 16 + (size_t)kQueueCap * sizeof(DeferredRow);
+            }
             t.ok = true;
             t.KT = KT;
             t.P = P;
@@ -744,6 +751,8 @@ static TileParams base_params(const void* lq, int64_t N, int64_t D, int32_t K, c
     p.off_rep = c.off_rep;
     p.off_list = c.off_list;
     p.off_misc = c.off_misc;
+    p.off_queue = c.off_queue;
+    p.queue_cap = c.queue_cap < rerank_queue_capacity() ? c.queue_cap : rerank_queue_capacity();
     return p;
 }
 

@@ -34,6 +34,7 @@ typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 constexpr int kRows = 16;          // rows per wave tile (the N of the 16x16x32 MFMA)
 constexpr int kChunk = 128;        // channels per pipeline stage (4 MFMA steps of 32)
 constexpr int kMaxWaves = 8;
+constexpr int kQueueCap = 256;     // rows a workgroup queues in LDS for the exact re-rank at the end of its tiles
 constexpr int kListCap = 1024;     // changed rows a workgroup collects in LDS before they go to the global list
 constexpr size_t kLdsLimit = 160 * 1024;
 constexpr float kPadNorm = 3.0e38f;
@@ -66,6 +67,13 @@ struct TileParams {
     void* out;
     float tau, tau2;         // re-rank threshold T = tau |x| cmax + tau2 cmax^2
     uint32_t ldsA_bytes, off_cnorm, off_hist, off_rep, off_list, off_misc;
+    // Plain assignment passes: rows inside the error bound are not measured where they are found (the wave would
+    // leave the pipeline of row loads it has in flight, and in the chunked-operand loop hold up the other seven) but
+    // queued in LDS, queue_cap entries of DeferredRow after a 16-byte header at off_queue, and measured by all waves
+    // when the workgroup has run out of tiles.  A row that finds the queue full, or has more than kQueueCand
+    // candidates, is measured on the spot; queue_cap = 0: every row is.
+    uint32_t off_queue;
+    int32_t queue_cap;
     // Several independent centroid sets side by side (fits for a grid of cluster counts that share every read of
     // the rows; MULTI instantiations only).  Set s owns the cluster tiles set_t0[s] .. set_t0[s + 1] - 1, of whose
     // 16-cluster slots the first set_k[s] hold centroids.  Cluster numbers everywhere (assignments, counts, list
@@ -94,6 +102,16 @@ struct TileParams {
     float2* carry_out;
     float* cmax_io;  // the first launch leaves the largest centroid norm of its share, the second takes the larger of the two
 };
+
+// A row whose exact re-rank waits for the end of the workgroup's tiles: its number, the assignment it had before the
+// pass (-1: none), and the clusters whose scores are within the error bound of the best one.
+constexpr int kQueueCand = 8;
+struct DeferredRow {
+    long long row;
+    int prev, ncand;
+    short cand[kQueueCand];
+};
+static_assert(sizeof(DeferredRow) == 32, "queue entries are 32 bytes");
 
 // Which lane group g (0..3) and which of its 8 operand elements j hold channel r (0..31) of a
 // 32-channel MFMA step.  The contraction does not care how channels map to the k index as long as
@@ -292,12 +310,15 @@ __device__ __forceinline__ void contract_chunk(const ChunkRegs<BF16>& r, f32x4 (
 // myrow: the number of row n (lanes of q = 0 at least), valid: whether it exists.  first / second / reranked / bound
 // (optional outputs): the best score, the best among the other centroids, whether the row goes through the exact
 // re-rank, and the threshold of that decision.
-template <int KT, bool BF16>
+// DEFER (with queue, the LDS queue, and prev, lane n's previous assignment of row n): such a row is queued instead,
+// if the queue has room and the row at most kQueueCand candidates, and *deferred says so for row n.
+template <int KT, bool BF16, bool DEFER = false>
 __device__ __forceinline__ void rank_rows(const TileParams& p, const f32x4 (&acc)[KT], const float* s_cnorm,
                                           float xn2, float cmax, int64_t myrow, bool valid, int lane, int& idx, float& dmin,
                                           int t0 = 0, int t1 = KT, float* first = nullptr, float* second = nullptr,
                                           bool* reranked = nullptr, float* bound = nullptr, int k_base = 0,
-                                          bool has_carry = false, float carry_s = 0.f, int carry_i = 0) {
+                                          bool has_carry = false, float carry_s = 0.f, int carry_i = 0,
+                                          unsigned char* queue = nullptr, int prev = -1, bool* deferred = nullptr) {
     const int n = lane & 15, q = lane >> 4;
     float b1 = __builtin_inff(), b2 = __builtin_inff();
     int i1 = 16 * t0;
@@ -358,7 +379,9 @@ __device__ __forceinline__ void rank_rows(const TileParams& p, const f32x4 (&acc
         // the candidates (scores within the bound of the best) are listed first, one per lane, then
         // measured two at a time: the usual case is exactly two
         int cand = 0, cnt = 0;
+        bool measured = false;
         auto measure = [&]() {
+            measured = true;
             for (int c0 = 0; c0 < cnt; c0 += 2) {
                 const int k0 = __builtin_amdgcn_readlane(cand, c0);
                 if (c0 + 1 < cnt) {
@@ -406,6 +429,23 @@ __device__ __forceinline__ void rank_rows(const TileParams& p, const f32x4 (&acc
                 }
             }
         }
+        if (DEFER && p.queue_cap > 0 && !measured && cnt >= 1 && cnt <= kQueueCand) {
+            int pos = 0;
+            if (lane == 0) pos = atomicAdd((int*)queue, 1);
+            pos = __builtin_amdgcn_readfirstlane(pos);
+            if (pos < p.queue_cap) {
+                DeferredRow* e = (DeferredRow*)(queue + 16) + pos;
+                if (lane < cnt) e->cand[lane] = (short)cand;
+                const int pv = __builtin_amdgcn_readlane(prev, r);
+                if (lane == 0) {
+                    e->row = row;
+                    e->prev = pv;
+                    e->ncand = cnt;
+                }
+                if (n == r) *deferred = true;
+                continue;
+            }
+        }
         measure();
         if (n == r && kbest != 0x7fffffff) {
             i1 = kbest;
@@ -413,6 +453,58 @@ __device__ __forceinline__ void rank_rows(const TileParams& p, const f32x4 (&acc
         }
     }
     idx = i1;
+}
+
+// A queued row, measured by one wave: the exact nearest centroid among its candidates and the bookkeeping of the pass
+// for that row (what finish_tile does for the rows ranked on the spot), by lane 0.
+template <bool BF16>
+__device__ __forceinline__ void finish_deferred(const TileParams& p, unsigned char* smem, const DeferredRow& e, int lane,
+                                                double& in_acc) {
+    double dbest = __builtin_inf();
+    int kbest = 0x7fffffff;
+    const int nc = __builtin_amdgcn_readfirstlane(e.ncand);
+    const int64_t row = ((int64_t)__builtin_amdgcn_readfirstlane((int)(e.row >> 32)) << 32) |
+                        (int64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)e.row);
+    for (int c0 = 0; c0 < nc; c0 += 2) {
+        const int k0 = __builtin_amdgcn_readfirstlane((int)e.cand[c0]);
+        if (c0 + 1 < nc) {
+            const int kk[2] = {k0, __builtin_amdgcn_readfirstlane((int)e.cand[c0 + 1])};
+            double d[2];
+            exact_dists<BF16, 2>(p.lq, row, p.D, p.cent, kk, lane, d);
+#pragma unroll
+            for (int c = 0; c < 2; c++)
+                if (d[c] < dbest || (d[c] == dbest && kk[c] < kbest)) {
+                    dbest = d[c];
+                    kbest = kk[c];
+                }
+        } else {
+            const int kk[1] = {k0};
+            double d[1];
+            exact_dists<BF16, 1>(p.lq, row, p.D, p.cent, kk, lane, d);
+            if (d[0] < dbest || (d[0] == dbest && k0 < kbest)) {
+                dbest = d[0];
+                kbest = k0;
+            }
+        }
+    }
+    if (lane != 0) return;
+    if (kbest == 0x7fffffff) kbest = (int)e.cand[0];  // no distance compares (non-finite input): any listed cluster
+    int* s_hist = (int*)(smem + p.off_hist);
+    unsigned long long* s_rep = (unsigned long long*)(smem + p.off_rep);
+    int* s_misc = (int*)(smem + p.off_misc);
+    p.assign[row] = kbest;
+    if (p.counts) atomicAdd(&s_hist[kbest], 1);
+    if (p.rep) atomicMin(&s_rep[kbest], (unsigned long long)row);
+    in_acc += (double)(float)dbest;
+    if (p.list && e.prev != kbest) {
+        const unsigned long long entry =
+            ((unsigned long long)row << 24) | ((unsigned long long)(e.prev + 1) << 12) | (unsigned long long)kbest;
+        const int pos = atomicAdd(&s_misc[0], 1);
+        if (pos < p.list_cap)
+            ((unsigned long long*)(smem + p.off_list))[pos] = entry;
+        else
+            p.list[atomicAdd(p.list_count, 1u)] = entry;
+    }
 }
 
 // Per-tile finishing work of the streaming modes: rank, write, book-keep; resets acc / nrm.
@@ -435,8 +527,13 @@ __device__ __forceinline__ void finish_tile(const TileParams& p, unsigned char* 
     xn2 += __shfl_xor(xn2, 32, kWave);
     int idx;
     float dmin, first = 0.f, second = 0.f, bound = 0.f;
-    bool reranked = false;
-    if (SPLIT)
+    bool reranked = false, deferred = false;
+    constexpr bool DEFER = !BOUNDS && !SPLIT && MODE == MODE_ASSIGN;
+    const int prev = p.delta_mode ? prev_in : -1;
+    if (DEFER)
+        rank_rows<KT, BF16, true>(p, acc, s_cnorm, xn2, cmax, myrow, valid, lane, idx, dmin, 0, KT, nullptr, nullptr, nullptr,
+                                  nullptr, 0, false, 0.f, 0, smem + p.off_queue, prev, &deferred);
+    else if (SPLIT)
         rank_rows<KT, BF16>(p, acc, s_cnorm, xn2, cmax, myrow, valid, lane, idx, dmin, 0, KT, &first, nullptr, nullptr, nullptr,
                             p.k_base, p.carry_in != nullptr, carry.x, __float_as_int(carry.y));
     else
@@ -445,7 +542,7 @@ __device__ __forceinline__ void finish_tile(const TileParams& p, unsigned char* 
 #pragma unroll
     for (int t = 0; t < KT; t++) acc[t] = (f32x4){0.f, 0.f, 0.f, 0.f};
     nrm = 0.f;
-    const bool owner = q == 0 && valid;
+    const bool owner = q == 0 && valid && !deferred;
     if (SPLIT && p.carry_out) {  // the first of the two launches: hand the pair on, nothing else
         if (owner) p.carry_out[myrow] = float2{first, __int_as_float(idx)};
         return;
@@ -532,7 +629,6 @@ __device__ __forceinline__ void finish_tile(const TileParams& p, unsigned char* 
     int* s_hist = (int*)(smem + p.off_hist);
     unsigned long long* s_rep = (unsigned long long*)(smem + p.off_rep);
     int* s_misc = (int*)(smem + p.off_misc);
-    const int prev = p.delta_mode ? prev_in : -1;
     if (owner) {
         p.assign[myrow] = idx;
         if (p.counts) atomicAdd(&s_hist[idx], 1);
@@ -775,6 +871,7 @@ __global__ __launch_bounds__(kMaxWaves * kWave) void k_tile(const TileParams p) 
             s_rep[k] = ~0ull;
         }
         if (threadIdx.x == 0) s_misc[0] = 0;
+        if (VAR == VAR_PLAIN && MODE == MODE_ASSIGN && p.queue_cap > 0 && threadIdx.x == 0) *(int*)(smem + p.off_queue) = 0;
     }
     __syncthreads();
     {
@@ -907,6 +1004,15 @@ __global__ __launch_bounds__(kMaxWaves * kWave) void k_tile(const TileParams p) 
 
     if (MODE != MODE_ASSIGN) return;
 
+    if (VAR == VAR_PLAIN && p.queue_cap > 0) {
+        // the rows whose exact re-rank was put off: shared out over the waves, one row at a time
+        __syncthreads();
+        const int pushed = *(const int*)(smem + p.off_queue);
+        const int qn = pushed < p.queue_cap ? pushed : p.queue_cap;
+        const DeferredRow* qe = (const DeferredRow*)(smem + p.off_queue + 16);
+        for (int e = wave; e < qn; e += p.waves) finish_deferred<BF16>(p, smem, qe[e], lane, in_acc);
+    }
+
     // workgroup epilogue: counts, first rows, objective
     double* s_in = (double*)(s_misc + 2);
     in_acc = wave_sum(in_acc);
@@ -940,7 +1046,8 @@ struct TileCfg {
     bool ok = false;
     int KT = 0, P = 0, waves = 0, nchunks = 0, mode = MODE_ASSIGN;
     bool chunked = false;  // the centroid operand streams through LDS instead of living there
-    uint32_t ldsA = 0, off_cnorm = 0, off_hist = 0, off_rep = 0, off_list = 0, off_misc = 0;
+    uint32_t ldsA = 0, off_cnorm = 0, off_hist = 0, off_rep = 0, off_list = 0, off_misc = 0, off_queue = 0;
+    int queue_cap = 0;  // entries of the queue of rows whose exact re-rank is put off (0: the layout has no room for one)
     size_t lds_total = 0;
 };
 
