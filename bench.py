@@ -56,17 +56,17 @@ HBM_PEAK_GBPS = 8000.0
 # one version of a kernel's source file: `traffic` is reported only while the hash of that file still matches, and the
 # line says that it comes from profiles/, not from this run.
 TRAFFIC_SOURCES = {
-    "k_tile": ("cat_tile_kernel.h", "0f732d784bfed8b74f358ef562b497768225e66f55b3d667b2e2e619ce7805a6"),
+    "k_tile": ("cat_tile_kernel.h", "472f6a191f297087c5dde13eff6acb5362dc7edcf2edd990f39205d51f880eed"),
     "k_infer": ("cat_infer_kernel.h", "d243d921fdcd31650ab229d15f5f562a3fb2bcae57aa0e239eb2055818ac6c93"),
 }
 TRAFFIC_COUNTERS = {
-    "cfg2": ("k_tile", (133769.7, 128011.7, 299.2, 256000.0)),
-    "cfg2_apply": ("k_infer", (129303.0, 128011.7, 265720.2, 256000.0)),
-    "cfg3": ("k_tile", (527781.1, 524299.7, 4721.3, 1048576.0)),
-    "cfg3_apply": ("k_infer", (524886.2, 524299.7, 1054738.5, 1048576.0)),
-    "cfg4": ("k_tile", (560474.5, 524299.7, 1192.3, 1048576.0)),
-    "cfg4_apply": ("k_tile", (1145720.1, 524299.7, 1049647.4, 1048576.0)),
-    "cfg5_apply": ("k_infer", (4197668.8, 4194317.5, 8413242.2, 8388608.0)),
+    "cfg2": ("k_tile", (133598.9, 128011.7, 303.2, 256000.0)),
+    "cfg2_apply": ("k_infer", (129302.2, 128011.7, 265872.3, 256000.0)),
+    "cfg3": ("k_tile", (527575.5, 524299.7, 4735.2, 1048576.0)),
+    "cfg3_apply": ("k_infer", (524886.5, 524299.7, 1054738.4, 1048576.0)),
+    "cfg4": ("k_tile", (553051.7, 524299.7, 1281.2, 1048576.0)),
+    "cfg4_apply": ("k_tile", (1142554.3, 524299.7, 1049647.2, 1048576.0)),
+    "cfg5_apply": ("k_infer", (4197661.2, 4194317.8, 8413233.7, 8388608.0)),
 }
 
 
