@@ -318,7 +318,8 @@ __device__ __forceinline__ void rank_rows(const TileParams& p, const f32x4 (&acc
                                           int t0 = 0, int t1 = KT, float* first = nullptr, float* second = nullptr,
                                           bool* reranked = nullptr, float* bound = nullptr, int k_base = 0,
                                           bool has_carry = false, float carry_s = 0.f, int carry_i = 0,
-                                          unsigned char* queue = nullptr, int prev = -1, bool* deferred = nullptr) {
+                                          unsigned char* queue = nullptr, int prev = -1, bool* deferred = nullptr,
+                                          int k_last = -1) {
     const int n = lane & 15, q = lane >> 4;
     float b1 = __builtin_inff(), b2 = __builtin_inff();
     int i1 = 16 * t0;
@@ -347,6 +348,12 @@ __device__ __forceinline__ void rank_rows(const TileParams& p, const f32x4 (&acc
         b1 = take ? ob1 : b1;
         i1 = take ? oi1 : i1;
         b2 = fminf(fminf(b2, ob2), loser);
+    }
+    {
+        // A slot past the last cluster (k_last; p.K - 1 unless given) holds no centroid and a huge norm: it can only
+        // win when every real score is non-finite.  The label stays a cluster number whatever the input.
+        const int kl = k_last >= 0 ? k_last : p.K - 1;
+        i1 = i1 < kl ? i1 : kl;
     }
     i1 += k_base;
     if (has_carry) {
@@ -698,7 +705,9 @@ __device__ __forceinline__ void finish_tile_multi(const TileParams& p, unsigned 
     for (int s = 0; s < p.nsets; s++) {
         int idx;
         float dmin;
-        rank_rows<KT, BF16>(p, acc, s_cnorm, xn2, cmax, row0 + n, valid, lane, idx, dmin, (int)p.set_t0[s], (int)p.set_t0[s + 1]);
+        rank_rows<KT, BF16>(p, acc, s_cnorm, xn2, cmax, row0 + n, valid, lane, idx, dmin, (int)p.set_t0[s], (int)p.set_t0[s + 1],
+                            nullptr, nullptr, nullptr, nullptr, 0, false, 0.f, 0, nullptr, -1, nullptr,
+                            16 * (int)p.set_t0[s] + (int)p.set_k[s] - 1);
         const bool owner = valid && q == (s >> 2);
         const int e = s & 3;
         const int prev = p.delta_mode ? (int)(e == 0 ? prevv.x : e == 1 ? prevv.y : e == 2 ? prevv.z : prevv.w) : -1;
