@@ -56,17 +56,17 @@ HBM_PEAK_GBPS = 8000.0
 # one version of a kernel's source file: `traffic` is reported only while the hash of that file still matches, and the
 # line says that it comes from profiles/, not from this run.
 TRAFFIC_SOURCES = {
-    "k_tile": ("cat_tile_kernel.h", "cc032e0be87526811ddbc8cda1697e36833fc1e56af1a5f2782ab9f4a9cf7a92"),
+    "k_tile": ("cat_tile_kernel.h", "f7df3b216487c7955991ad77a448159b9bc0e66c1d4168af298b081d3a85d32d"),
     "k_infer": ("cat_infer_kernel.h", "d243d921fdcd31650ab229d15f5f562a3fb2bcae57aa0e239eb2055818ac6c93"),
 }
 TRAFFIC_COUNTERS = {
-    "cfg2": ("k_tile", (133589.1, 128011.7, 303.6, 256000.0)),
-    "cfg2_apply": ("k_infer", (129307.2, 128011.7, 265886.7, 256000.0)),
-    "cfg3": ("k_tile", (527575.4, 524299.7, 4732.6, 1048576.0)),
-    "cfg3_apply": ("k_infer", (524891.8, 524299.7, 1054738.4, 1048576.0)),
-    "cfg4": ("k_tile", (552961.0, 524299.7, 1280.2, 1048576.0)),
-    "cfg4_apply": ("k_tile", (1142846.6, 524299.7, 1049647.4, 1048576.0)),
-    "cfg5_apply": ("k_infer", (4197690.7, 4194317.3, 8413235.6, 8388608.0)),
+    "cfg2": ("k_tile", (133499.5, 128011.7, 302.6, 256000.0)),
+    "cfg2_apply": ("k_infer", (129304.7, 128011.7, 265969.1, 256000.0)),
+    "cfg3": ("k_tile", (526984.8, 524299.7, 4747.4, 1048576.0)),
+    "cfg3_apply": ("k_infer", (524886.7, 524299.7, 1054738.2, 1048576.0)),
+    "cfg4": ("k_tile", (551642.5, 524299.7, 1273.3, 1048576.0)),
+    "cfg4_apply": ("k_tile", (1141365.2, 524299.7, 1049665.2, 1048576.0)),
+    "cfg5_apply": ("k_infer", (4197668.4, 4194317.9, 8413243.7, 8388608.0)),
 }
 
 

@@ -14,8 +14,12 @@ import time
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _ROOT = os.path.dirname(_HERE)
 CSRC = os.path.join(_HERE, "csrc")
-SOURCES = ["cat_api.hip", "cat_stream.hip", "cat_tile.hip", "cat_pca.hip", "cat_sweep.hip", "cat_seed.hip", "cat_infer.hip", "cat_lds.hip", "cat_lp.hip", "cat_tile_multi_f32.hip", "cat_tile_multi_bf16.hip", "cat_tile_bounds_f32.hip", "cat_tile_bounds_bf16.hip", "cat_tile_split.hip"] + [
-    f"cat_tile_k{kt}_{dt}.hip" for kt in (16, 8, 4, 2, 1) for dt in ("f32", "bf16")]
+# (the files that take longest to compile come first: they start at once and the rest fills in beside them)
+SOURCES = ["cat_tile_k16_f32.hip", "cat_tile_k16_bf16.hip", "cat_tile_k16_f32_p1.hip", "cat_tile_k16_bf16_p1.hip",
+           "cat_tile_bounds_f32.hip", "cat_tile_bounds_bf16.hip", "cat_infer.hip", "cat_api.hip", "cat_stream.hip", "cat_tile.hip",
+           "cat_pca.hip", "cat_sweep.hip", "cat_seed.hip", "cat_lds.hip", "cat_lp.hip", "cat_tile_multi_f32.hip",
+           "cat_tile_multi_bf16.hip", "cat_tile_split.hip"] + [
+    f"cat_tile_k{kt}_{dt}.hip" for kt in (8, 4, 2, 1) for dt in ("f32", "bf16")]
 HEADERS = ["cat_common.h", "cat_tile.h", "cat_tile_kernel.h", "cat_infer.h", "cat_infer_kernel.h"]
 OUT = os.path.join(_HERE, "libcat_hip.so")
 OBJ_DIR = os.path.join(_HERE, "_build")

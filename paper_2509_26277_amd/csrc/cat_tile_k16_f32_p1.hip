@@ -1,0 +1,10 @@
+// Instantiations of the tile kernel: 256 padded clusters (KT = 16), f32 rows, the one-part operand.
+#include "cat_tile_kernel.h"
+
+namespace cat {
+
+cat_status launch_kt16_f32_one_part(const TileParams& p, const TileCfg& c, hipStream_t st) {
+    return launch_mode<16, 1, false>(p, c, st);
+}
+
+}  // namespace cat

@@ -383,16 +383,31 @@ __device__ __forceinline__ void rank_rows(const TileParams& p, const f32x4 (&acc
                             (int64_t)(uint32_t)__builtin_amdgcn_readlane((int)myrow, r);
         double dbest = __builtin_inf();
         int kbest = 0x7fffffff;
-        // the candidates (scores within the bound of the best) are listed first, one per lane, then
-        // measured two at a time: the usual case is exactly two
-        int cand = 0, cnt = 0;
-        bool measured = false;
+        // the candidates (scores within the bound of the best) are listed first, one per lane (entry c in lane
+        // c mod 64 of register c / 64: every cluster of the pass may be one), then measured two at a time: the
+        // usual case is exactly two
+        constexpr int NCR = (KT * 16 + kWave) / kWave;
+        int cand[NCR];
+#pragma unroll
+        for (int j = 0; j < NCR; j++) cand[j] = 0;
+        int cnt = 0;
+        auto add = [&](int k) {
+#pragma unroll
+            for (int j = 0; j < NCR; j++)
+                if ((cnt >> 6) == j && lane == (cnt & (kWave - 1))) cand[j] = k;
+            ++cnt;
+        };
+        auto get = [&](int c) -> int {  // c is wave-uniform
+            int v = cand[0];
+#pragma unroll
+            for (int j = 1; j < NCR; j++) v = (c >> 6) == j ? cand[j] : v;
+            return __builtin_amdgcn_readlane(v, c & (kWave - 1));
+        };
         auto measure = [&]() {
-            measured = true;
             for (int c0 = 0; c0 < cnt; c0 += 2) {
-                const int k0 = __builtin_amdgcn_readlane(cand, c0);
+                const int k0 = get(c0);
                 if (c0 + 1 < cnt) {
-                    const int kk[2] = {k0, __builtin_amdgcn_readlane(cand, c0 + 1)};
+                    const int kk[2] = {k0, get(c0 + 1)};
                     double d[2];
                     exact_dists<BF16, 2>(p.lq, row, p.D, p.cent, kk, lane, d);
 #pragma unroll
@@ -411,12 +426,9 @@ __device__ __forceinline__ void rank_rows(const TileParams& p, const f32x4 (&acc
                     }
                 }
             }
-            cnt = 0;
         };
         if (has_carry && readlane_f(carry_s, r) <= thr) {
-            const int ka = __builtin_amdgcn_readlane(carry_i, r);
-            if (lane == cnt) cand = ka;
-            ++cnt;
+            add(__builtin_amdgcn_readlane(carry_i, r));
         }
 #pragma unroll
         for (int t = 0; t < KT; t++) {
@@ -429,20 +441,17 @@ __device__ __forceinline__ void rank_rows(const TileParams& p, const f32x4 (&acc
                     const int l = __builtin_amdgcn_readfirstlane(__builtin_ctzll(m));
                     m &= m - 1;
                     const int k = 16 * t + 4 * (l >> 4) + i;
-                    if (k < p.K) {
-                        if (lane == cnt) cand = k + k_base;
-                        if (++cnt == kWave) measure();
-                    }
+                    if (k < p.K) add(k + k_base);
                 }
             }
         }
-        if (DEFER && p.queue_cap > 0 && !measured && cnt >= 1 && cnt <= kQueueCand) {
+        if (DEFER && p.queue_cap > 0 && cnt >= 1 && cnt <= kQueueCand) {
             int pos = 0;
             if (lane == 0) pos = atomicAdd((int*)queue, 1);
             pos = __builtin_amdgcn_readfirstlane(pos);
             if (pos < p.queue_cap) {
                 DeferredRow* e = (DeferredRow*)(queue + 16) + pos;
-                if (lane < cnt) e->cand[lane] = (short)cand;
+                if (lane < cnt) e->cand[lane] = (short)cand[0];
                 const int pv = __builtin_amdgcn_readlane(prev, r);
                 if (lane == 0) {
                     e->row = row;

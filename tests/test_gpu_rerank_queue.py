@@ -51,6 +51,8 @@ def _crowded(seed, N, D, K, dt, offset, dup=0):
     (3000, 2048, 64, "bf16", 24.0, 2),   # the chunked operand: eight waves in lockstep
     (2500, 1000, 16, "f32", 30.0, 0),
     (1500, 96, 20, "f32", 10.0, -12),    # rows of cluster 0 have 13 candidates: measured on the spot
+    (1200, 64, 150, "f32", 5.0, -149),   # every centroid the same: 150 candidates per row, sixteen cluster tiles
+    (1000, 1000, 150, "f32", 3.0, -149), # the same with the clusters split over two launches
 ])
 def test_single_pass_every_capacity(N, D, K, dt, offset, dup):
     x, _, cent = _crowded(N + D, N, D, K, dt, offset, dup)
